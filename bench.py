@@ -1,0 +1,160 @@
+"""Benchmark of the SGD matrix-factorization hot path on one MI355X.
+
+A step is one epoch of the paper's Algorithm 1 over the whole training set of the workload
+(rating fetch, gather, dot, update, scatter, stratum scheduling) in HOGWILD mode, followed by the
+held-out RMSE.  The rating matrix is partitioned and resident in HBM before the timed region.
+Prints one JSON line (see README for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def load_dataset(name, factor):
+    import numpy as np
+
+    import workloads
+
+    cfg = workloads.scaled(workloads.CONFIGS[name], factor)
+    cache = os.environ.get("MF_DATA_CACHE", os.path.join(ROOT, ".cache"))
+    path = os.path.join(cache, f"{name}_{factor:g}_seed{cfg.seed}.npz")
+    fields = ["rows", "cols", "vals", "test_rows", "test_cols", "test_vals", "max_row_degree",
+              "max_col_degree", "median_row_degree", "median_col_degree"]
+    if os.path.exists(path):
+        z = np.load(path)
+        return workloads.Dataset(cfg, *[z[f] if z[f].ndim else z[f].item() for f in fields])
+    ds = workloads.generate(cfg)
+    try:
+        os.makedirs(cache, exist_ok=True)
+        np.savez(path, **{f: getattr(ds, f) for f in fields})
+    except OSError:
+        pass
+    return ds
+
+
+def cpu_baseline(ds, gr, gc, k):
+    """The oracle as it stands, timed on the host cores: one epoch with the independent blocks
+    of every stratum on OpenMP threads (bit-identical to the serial order), and the serial
+    oracle on a prefix of the strata."""
+    import numpy as np
+
+    import oracle
+
+    cfg = ds.cfg
+    perm, bp, _, _ = oracle.partition(ds.rows, ds.cols, cfg.m, cfg.n, gr, gc, oracle.SPLIT_NNZ_BALANCED)
+    P = oracle.init_factors(cfg.m * k, 1, 0, 0.1).reshape(cfg.m, k)
+    Q = oracle.init_factors(cfg.n * k, 1, 1, 0.1).reshape(cfg.n, k)
+    t0 = time.perf_counter()
+    oracle.sgd_epoch_omp(P, Q, ds.rows, ds.cols, ds.vals, perm, bp, gr, gc, cfg.lr, cfg.lam)
+    t_omp = time.perf_counter() - t0
+    # serial: the first stratum only (a bounded sample of the same epoch)
+    bp1 = bp[: gr + 1].copy()
+    n1 = int(bp1[-1])
+    t0 = time.perf_counter()
+    oracle.sgd_epoch(P, Q, ds.rows, ds.cols, ds.vals, perm, bp1, gr, 1, cfg.lr, cfg.lam)
+    t_ser = time.perf_counter() - t0
+    threads = min(oracle.num_threads(), gr)
+    return {"value": ds.rows.size / t_omp, "unit": "updates/s", "cores": threads, "kind": "oracle",
+            "sample": f"one full epoch ({ds.rows.size} updates) of the same workload and grid, fp64 oracle, "
+                      f"independent blocks of each stratum on {threads} OpenMP threads",
+            "serial_value": n1 / t_ser, "serial_cores": 1,
+            "serial_sample": f"stratum 0 of the same epoch ({n1} updates) on one core",
+            "host_cores": len(os.sched_getaffinity(0))}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="medium")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (testing only)")
+    ap.add_argument("--mode", default="hogwild", choices=["hogwild", "det"])
+    ap.add_argument("--grid", default="8x8")
+    ap.add_argument("--chunk", type=int, default=128)
+    ap.add_argument("--affinity", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2006_15980_amd as mf
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
+        sys.exit(3)
+    ds = load_dataset(args.workload, args.scale)
+    cfg = ds.cfg
+    gr, gc = (int(x) for x in args.grid.split("x"))
+    mode = mf.MF_MODE_HOGWILD if args.mode == "hogwild" else mf.MF_MODE_DET
+    k = cfg.k
+    elt = 4 if cfg.storage == "f32" else 2
+    bytes_per_update = 12 + 4 * k * elt      # rating record + read and write of p_u and q_v
+
+    opts = {mf.MF_OPT_HOGWILD_CHUNK: args.chunk, mf.MF_OPT_XCD_AFFINITY: args.affinity,
+            mf.MF_OPT_PROFILE: 0 if args.no_kernel_events else 1}
+    model = mf.MatrixFactorization(cfg.m, cfg.n, k, cfg.storage, seed=1, scale=0.1, options=opts)
+    t0 = time.perf_counter()
+    model.load_blocks(ds.rows, ds.cols, ds.vals, gr, gc, mf.MF_SPLIT_NNZ_BALANCED)
+    t_load = time.perf_counter() - t0
+    tr, tc, tv = model.to_device(ds.test_rows, ds.test_cols, ds.test_vals)
+    nnz = ds.rows.size
+
+    rmse = float("nan")
+    for _ in range(args.warmup):
+        model.sgd_epoch(cfg.lr, cfg.lam, mode)
+        rmse = model.rmse(tr, tc, tv)
+    mf.binding.mf_profile_read(model.ctx)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        model.sgd_epoch(cfg.lr, cfg.lam, mode)
+        rmse = model.rmse(tr, tc, tv)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kernel_ms, launches = mf.binding.mf_profile_read(model.ctx)
+    model.close()
+
+    value = nnz * args.steps / elapsed
+    roofline = None
+    if launches > 0:
+        avg_s = kernel_ms * 1e-3 / launches
+        bytes_per_launch = bytes_per_update * nnz * args.steps / launches
+        achieved = bytes_per_launch / avg_s / 1e9
+        roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "sgd_chunks<float,128>",
+                    "avg_launch_us": avg_s * 1e6, "launches_per_step": launches / args.steps,
+                    "bytes_per_update": bytes_per_update}
+    out = {"metric": "SGD updates/s at k=128 (HOGWILD epoch + held-out RMSE per step)", "value": value,
+           "unit": "updates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": elapsed * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32" if cfg.storage == "f32" else "f16 storage / f32 math",
+           "data": "synthetic",
+           "config": {"workload": f"{cfg.name}: m={cfg.m} n={cfg.n} nnz_train={nnz} k={k} {cfg.storage}",
+                      "mode": args.mode, "grid": args.grid, "chunk": args.chunk, "xcd_affinity": args.affinity,
+                      "lr": cfg.lr, "lambda": cfg.lam},
+           "final_test_rmse": rmse, "load_blocks_s": t_load,
+           "algorithmic_gbs": value * bytes_per_update / 1e9,
+           "hbm_roofline_frac": value * bytes_per_update / 1e9 / HBM_PEAK_GBS,
+           "roofline": roofline}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(ds, gr, gc, k)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,161 @@
+/*
+ * mf_sgd.h -- C ABI of the MI355X (gfx950) SGD matrix-factorization library.
+ *
+ * The library runs the training phase of the paper's Algorithm 1 ("SGD") -- for every rating
+ * r_uv:  e = r_uv - p_u.q_v ;  p_u += lr*(e*q_v - lambda*p_u) ;  q_v += lr*(e*p_u - lambda*q_v),
+ * both right-hand sides using the values read before the step -- over a grid of blocks of the
+ * sparse rating matrix R (m x n), on dense factors P (m x k) and Q (k x n), one epoch (every
+ * rating exactly once) per call, on one GPU.  Blocks that share neither a row strip nor a column
+ * strip are independent (Section 3.1, Example 2) and are processed concurrently.
+ *
+ * Conventions
+ *   - No exception crosses this boundary; no call aborts or prints.  Every call returns an int:
+ *     MF_OK or a negative MF_E* code; mf_last_error() gives a message for the last failure.
+ *   - "host" / "device" is stated for every pointer.  Device pointers are plain HIP device
+ *     addresses (for instance torch tensors' data_ptr()).  The caller owns every buffer it
+ *     passes; the library owns its context, its host-side metadata and one small device
+ *     buffer for reduction partials (allocated in mf_create, freed in mf_destroy).
+ *   - Indices are 0-based.  Q is held transposed: Qt is n x k row-major and Qt[v] is the
+ *     paper's column q_v.  P is m x k row-major.
+ *   - A context is not thread-safe.  All device work is enqueued on the stream given to
+ *     mf_create; calls that return data to the host synchronise that stream.
+ */
+#ifndef MF_SGD_H
+#define MF_SGD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mf_ctx mf_ctx;
+
+enum {
+    MF_OK = 0,
+    MF_EINVAL = -1,   /* bad argument                                   */
+    MF_ESTATE = -2,   /* call out of order (e.g. epoch before load)     */
+    MF_ENOMEM = -3,   /* workspace too small / host allocation failed   */
+    MF_EDEVICE = -4,  /* a HIP call failed                              */
+    MF_ERANGE = -5    /* a row / column index outside [0,m) / [0,n)     */
+};
+
+enum { MF_F32 = 0, MF_F16 = 1 };               /* storage type of the factors; arithmetic is fp32 */
+enum { MF_MODE_DET = 0, MF_MODE_HOGWILD = 1 };
+enum { MF_SPLIT_EQUAL_WIDTH = 0, MF_SPLIT_NNZ_BALANCED = 1 };
+
+/* Tuning options for mf_set_option (all have working defaults). */
+enum {
+    MF_OPT_HOGWILD_CHUNK = 1,     /* target ratings per wavefront in HOGWILD mode (default 128)      */
+    MF_OPT_XCD_AFFINITY = 2,      /* 1 (default): all wavefronts working on one block are placed on  */
+                                  /* one XCD; 0: spread over all XCDs                                 */
+    MF_OPT_PROFILE = 3            /* 1: time every SGD kernel launch with HIP events (see below)     */
+};
+
+/* Create a context on HIP device `device`.  `hip_stream` is a hipStream_t of the caller (may be
+ * NULL for the default stream); all work of this context is enqueued on it. */
+int mf_create(mf_ctx** out, int device, void* hip_stream);
+int mf_destroy(mf_ctx* ctx);
+
+/* Message of the last failed call on ctx (owned by ctx, valid until the next call on ctx). */
+const char* mf_last_error(const mf_ctx* ctx);
+
+/* Set a tuning option.  Must be called before mf_load_blocks to affect the schedule. */
+int mf_set_option(mf_ctx* ctx, int32_t option, int64_t value);
+
+/* "init_model" of Algorithm 1.  Registers the factor buffers and optionally fills them.
+ *   m, n      : size of R;  k : number of latent factors, one of 32, 64, 128, 256.
+ *   dtype     : MF_F32 or MF_F16 -- element type of dP and dQt.
+ *   dP        : DEVICE, m*k elements, row-major, caller-owned, 16-byte aligned.
+ *   dQt       : DEVICE, n*k elements, row-major, caller-owned, 16-byte aligned.
+ *   scale >= 0: every element i of P becomes scale*U(seed,0,i), of Qt scale*U(seed,1,i), where
+ *               U is a counter-based uniform generator on the 24-bit grid in [0,1) (the paper
+ *               only says the factors start from random values); in MF_F16 the value is rounded
+ *               to binary16 (nearest even).
+ *   scale < 0 : the buffers keep their current contents (the caller initialised them).
+ * The buffers stay registered (and are updated in place by mf_sgd_epoch) until the next mf_init. */
+int mf_init(mf_ctx* ctx, int64_t m, int64_t n, int32_t k, int32_t dtype,
+            void* dP, void* dQt, uint64_t seed, float scale);
+
+/* Size in bytes of the device workspace mf_load_blocks needs for nnz ratings on this grid. */
+int mf_load_blocks_workspace(const mf_ctx* ctx, int64_t nnz, int32_t grid_r, int32_t grid_c,
+                             size_t* bytes_out);
+
+/* Partition R into a grid_r x grid_c grid of blocks (Section 3.1) and upload it.
+ *   rows, cols, vals : HOST arrays of nnz entries (COO triples, the paper's "triadic tuples"),
+ *                      read-only, not retained.  Duplicate (u,v) entries are legal.
+ *   grid_r <= grid_c, grid_r <= m, grid_c <= n.
+ *   split            : MF_SPLIT_EQUAL_WIDTH  -- strip a = [ceil(a*size/G), ceil((a+1)*size/G)) (the
+ *                                               uniform division);
+ *                      MF_SPLIT_NNZ_BALANCED -- strip bounds chosen so that every strip holds about
+ *                                               nnz/G ratings: bounds[a] = the smallest id whose
+ *                                               exclusive degree prefix is >= ceil(a*nnz/G).
+ *   d_workspace      : DEVICE, caller-owned, workspace_bytes >= mf_load_blocks_workspace(); must
+ *                      stay alive and untouched until the next mf_load_blocks / mf_destroy.
+ * Block (a,b) belongs to stratum s = (b-a) mod grid_c and has linear id L = s*grid_r + a; the
+ * grid_r blocks of one stratum are mutually independent.  Ratings are stored block after block in
+ * ascending L, inside a block in ascending (row, column, original position).
+ * Requires mf_init first (m and n come from there).  Synchronises the stream. */
+int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const float* vals,
+                   int64_t nnz, int32_t grid_r, int32_t grid_c, int32_t split,
+                   void* d_workspace, size_t workspace_bytes);
+
+/* Copy the partition to HOST arrays of the caller (any pointer may be NULL):
+ *   perm[nnz]                 original position of the rating stored at each packed position;
+ *   block_ptr[grid_r*grid_c+1] start of every block in the packed order;
+ *   row_bounds[grid_r+1], col_bounds[grid_c+1]. */
+int mf_get_partition(const mf_ctx* ctx, int64_t* perm, int64_t* block_ptr,
+                     int32_t* row_bounds, int32_t* col_bounds);
+
+/* One epoch of Algorithm 1's training phase: every loaded rating exactly once, stratum after
+ * stratum (one kernel launch per stratum on the context's stream).  Returns after enqueueing.
+ *   MF_MODE_DET     : one wavefront per block, ratings in stored order.  The result is the same
+ *                     on every run and equals the sequential order (strata ascending, blocks
+ *                     ascending, stored order) up to fp32 rounding.
+ *   MF_MODE_HOGWILD : every block is cut into chunks of whole rows that many wavefronts process
+ *                     concurrently without locks (lock-free updates in the sense of Hogwild,
+ *                     Section 3.1); rows of Qt are raced on, the result varies from run to run. */
+int mf_sgd_epoch(mf_ctx* ctx, float lr, float lambda, int32_t mode);
+
+/* RMSE = sqrt(mean (r - p_u.q_v)^2) of the current factors (the quality metric of Section 7).
+ *   d_rows, d_cols, d_vals : DEVICE arrays of `count` entries, caller-owned; if d_rows is NULL
+ *                            the loaded training ratings are used and count is ignored.
+ *   rmse_out               : HOST.  Products and sums are taken in double; the reduction order is
+ *                            fixed, so the value is reproducible.
+ * count == 0 gives MF_EINVAL.  Synchronises the stream. */
+int mf_rmse(mf_ctx* ctx, const int32_t* d_rows, const int32_t* d_cols, const float* d_vals,
+            int64_t count, double* rmse_out);
+
+/* Wait for all work enqueued by this context. */
+int mf_sync(mf_ctx* ctx);
+
+/* With MF_OPT_PROFILE = 1 every SGD kernel launch is bracketed by HIP events on the context's
+ * stream.  This call synchronises, then returns the summed kernel time in milliseconds and the
+ * number of launches since the previous call (HOST pointers, either may be NULL). */
+int mf_profile_read(mf_ctx* ctx, double* kernel_ms_out, int64_t* launches_out);
+
+/* Diagnostic: launch n_groups workgroups and report, for each, the id of the XCD (accelerator
+ * die) it ran on.  xcc_out: HOST array of n_groups int32.  Used to check the workgroup-to-XCD
+ * placement MF_OPT_XCD_AFFINITY relies on. */
+int mf_debug_xcc_ids(mf_ctx* ctx, int32_t n_groups, int32_t* xcc_out);
+
+/* Host-only planning (no device, no context): the partition mf_load_blocks would build for these
+ * arguments, and the per-wavefront work list of one epoch mode, for inspection and for checking
+ * the block rule of Section 3.1 without a GPU.  All pointers are HOST; any output may be NULL.
+ *   perm, block_ptr, row_bounds, col_bounds : as in mf_get_partition.
+ *   entry_begin[entry_cap], entry_len[entry_cap] : work-list entries (first packed position and
+ *       number of ratings; length 0 = padding); entry e of a stratum is run by workgroup e/4 of
+ *       that stratum's launch, and with xcd_affinity = 1 workgroup w serves die w mod 8.
+ *   stratum_entry[grid_c+1] : first entry of each stratum;  n_entries_out : entries in total.
+ * MF_ENOMEM if entry_cap is too small. */
+int mf_plan_host(const int32_t* rows, const int32_t* cols, int64_t nnz, int64_t m, int64_t n,
+                 int32_t grid_r, int32_t grid_c, int32_t split, int32_t mode, int32_t chunk,
+                 int32_t xcd_affinity, int64_t* perm, int64_t* block_ptr, int32_t* row_bounds,
+                 int32_t* col_bounds, int64_t* entry_begin, int32_t* entry_len, int64_t entry_cap,
+                 int64_t* stratum_entry, int64_t* n_entries_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MF_SGD_H */

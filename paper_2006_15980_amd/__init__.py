@@ -1,0 +1,88 @@
+"""MI355X-native SGD matrix factorization (hot path of arxiv 2006.15980's method).
+
+``binding`` mirrors the C ABI of include/mf_sgd.h one to one.  ``MatrixFactorization`` is a
+small convenience holder that keeps the torch tensors (device memory) alive next to the
+library context; every step of the method runs inside libmf_sgd.so.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import binding
+from .binding import *  # noqa: F401,F403
+from .binding import (MF_F16, MF_F32, MF_MODE_DET, MF_MODE_HOGWILD, MF_OPT_HOGWILD_CHUNK, MF_OPT_PROFILE,
+                      MF_OPT_XCD_AFFINITY, MF_SPLIT_EQUAL_WIDTH, MF_SPLIT_NNZ_BALANCED, MFError)
+
+
+class MatrixFactorization:
+    """Owns the device buffers (torch tensors) and a library context on the current stream."""
+
+    def __init__(self, m: int, n: int, k: int, storage: str = "f32", device: int = 0, seed: int = 1,
+                 scale: float = 0.1, options: dict | None = None):
+        import torch
+
+        if not torch.cuda.is_available():
+            raise RuntimeError("no HIP device: the library has no CPU path")
+        self.torch = torch
+        self.m, self.n, self.k = m, n, k
+        self.dtype = {"f32": MF_F32, "f16": MF_F16}[storage]
+        tdt = torch.float32 if self.dtype == MF_F32 else torch.float16
+        self.dev = torch.device("cuda", device)
+        with torch.cuda.device(self.dev):
+            self.stream = torch.cuda.current_stream().cuda_stream
+        self.ctx = binding.mf_create(device, self.stream)
+        for key, val in (options or {}).items():
+            binding.mf_set_option(self.ctx, key, val)
+        self.P = torch.empty((m, k), dtype=tdt, device=self.dev)
+        self.Qt = torch.empty((n, k), dtype=tdt, device=self.dev)
+        binding.mf_init(self.ctx, m, n, k, self.dtype, self.P.data_ptr(), self.Qt.data_ptr(), seed, scale)
+        self.workspace = None
+        self.nnz = 0
+        self.grid = (0, 0)
+
+    def set_factors(self, P: np.ndarray, Qt: np.ndarray):
+        t = self.torch
+        self.P.copy_(t.from_numpy(np.ascontiguousarray(P)).to(self.P.dtype))
+        self.Qt.copy_(t.from_numpy(np.ascontiguousarray(Qt)).to(self.Qt.dtype))
+
+    def get_factors(self):
+        return self.P.float().cpu().numpy().astype(np.float64), self.Qt.float().cpu().numpy().astype(np.float64)
+
+    def load_blocks(self, rows, cols, vals, grid_r: int, grid_c: int, split: int = MF_SPLIT_NNZ_BALANCED):
+        t = self.torch
+        nbytes = binding.mf_load_blocks_workspace(self.ctx, rows.size, grid_r, grid_c)
+        binding.mf_sync(self.ctx)
+        self.workspace = t.empty(nbytes + 256, dtype=t.uint8, device=self.dev)
+        base = (self.workspace.data_ptr() + 255) & ~255
+        binding.mf_load_blocks(self.ctx, rows, cols, vals, grid_r, grid_c, split, base, nbytes)
+        self.nnz = rows.size
+        self.grid = (grid_r, grid_c)
+
+    def partition(self):
+        return binding.mf_get_partition(self.ctx, self.nnz, *self.grid)
+
+    def sgd_epoch(self, lr: float, lam: float, mode: int):
+        binding.mf_sgd_epoch(self.ctx, lr, lam, mode)
+
+    def rmse(self, rows=None, cols=None, vals=None) -> float:
+        if rows is None:
+            return binding.mf_rmse(self.ctx, None, None, None, 0)
+        return binding.mf_rmse(self.ctx, rows.data_ptr(), cols.data_ptr(), vals.data_ptr(), rows.numel())
+
+    def to_device(self, rows, cols, vals):
+        t = self.torch
+        return (t.from_numpy(rows).to(self.dev), t.from_numpy(cols).to(self.dev), t.from_numpy(vals).to(self.dev))
+
+    def sync(self):
+        binding.mf_sync(self.ctx)
+
+    def close(self):
+        if self.ctx:
+            binding.mf_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

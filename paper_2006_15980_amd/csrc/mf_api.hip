@@ -1,0 +1,406 @@
+// C ABI of libmf_sgd (declared in include/mf_sgd.h): argument checks, state machine
+// (created -> initialised -> loaded), workspace layout and the stratum scheduler that turns one
+// epoch of Algorithm 1's training phase into one kernel launch per stratum.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/mf_sgd.h"
+#include "mf_internal.h"
+
+struct mf_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    std::string err;
+
+    // factors (caller-owned device buffers)
+    bool inited = false;
+    int64_t m = 0, n = 0;
+    int32_t k = 0, dtype = MF_F32;
+    void* dP = nullptr;
+    void* dQt = nullptr;
+
+    // partition and schedules
+    bool loaded = false;
+    mf::Partition part;
+    mf::Schedule sched[2];   // indexed by MF_MODE_*
+    int32_t* dU = nullptr;
+    int32_t* dV = nullptr;
+    float* dR = nullptr;
+
+    // options
+    int32_t hogwild_chunk = 128;
+    int32_t xcd_affinity = 1;
+    int32_t profile = 0;
+
+    // library-owned device buffer: RMSE partials followed by the final sum
+    double* d_partials = nullptr;
+
+    // profiling events (start, stop) of the launches since the last mf_profile_read
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> events;
+    size_t events_used = 0;
+};
+
+namespace {
+
+int fail(mf_ctx* ctx, int code, const std::string& msg)
+{
+    if (ctx) ctx->err = msg;
+    return code;
+}
+
+int fail_hip(mf_ctx* ctx, const char* what, hipError_t e)
+{
+    return fail(ctx, MF_EDEVICE, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+#define MF_HIP(ctx, call)                                      \
+    do {                                                       \
+        hipError_t e_ = (call);                                \
+        if (e_ != hipSuccess) return fail_hip(ctx, #call, e_); \
+    } while (0)
+
+size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+bool valid_k(int32_t k) { return k == 32 || k == 64 || k == 128 || k == 256; }
+
+struct Layout {
+    size_t off_u, off_v, off_r, off_begin[2], off_len[2], total;
+    int64_t cap[2];
+};
+
+Layout make_layout(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk)
+{
+    Layout l;
+    l.cap[MF_MODE_DET] = mf::det_entries_bound(gr, gc);
+    l.cap[MF_MODE_HOGWILD] = mf::hogwild_entries_bound(nnz, gr, gc, chunk);
+    size_t off = 0;
+    l.off_u = off; off += align_up((size_t)nnz * 4);
+    l.off_v = off; off += align_up((size_t)nnz * 4);
+    l.off_r = off; off += align_up((size_t)nnz * 4);
+    for (int mode = 0; mode < 2; ++mode) {
+        l.off_begin[mode] = off; off += align_up((size_t)l.cap[mode] * 8);
+        l.off_len[mode] = off; off += align_up((size_t)l.cap[mode] * 4);
+    }
+    l.total = off;
+    return l;
+}
+
+int check_grid(mf_ctx* ctx, int64_t nnz, int32_t gr, int32_t gc)
+{
+    if (nnz < 0 || nnz >= ((int64_t)1 << 31)) return fail(ctx, MF_EINVAL, "nnz must be in [0, 2^31)");
+    if (gr < 1 || gc < 1 || gr > gc) return fail(ctx, MF_EINVAL, "need 1 <= grid_r <= grid_c");
+    if ((int64_t)gr * gc >= ((int64_t)1 << 30)) return fail(ctx, MF_EINVAL, "grid too large");
+    return MF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mf_create(mf_ctx** out, int device, void* hip_stream)
+{
+    if (!out) return MF_EINVAL;
+    *out = nullptr;
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return MF_EDEVICE;
+    mf_ctx* ctx = new (std::nothrow) mf_ctx();
+    if (!ctx) return MF_ENOMEM;
+    ctx->device = device;
+    ctx->stream = (hipStream_t)hip_stream;
+    if (hipSetDevice(device) != hipSuccess ||
+        hipMalloc((void**)&ctx->d_partials, (mf::kRmsePartials + 1) * sizeof(double)) != hipSuccess) {
+        delete ctx;
+        return MF_EDEVICE;
+    }
+    *out = ctx;
+    return MF_OK;
+}
+
+int mf_destroy(mf_ctx* ctx)
+{
+    if (!ctx) return MF_EINVAL;
+    (void)hipSetDevice(ctx->device);
+    (void)hipStreamSynchronize(ctx->stream);
+    for (auto& ev : ctx->events) {
+        (void)hipEventDestroy(ev.first);
+        (void)hipEventDestroy(ev.second);
+    }
+    if (ctx->d_partials) (void)hipFree(ctx->d_partials);
+    delete ctx;
+    return MF_OK;
+}
+
+const char* mf_last_error(const mf_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+int mf_set_option(mf_ctx* ctx, int32_t option, int64_t value)
+{
+    if (!ctx) return MF_EINVAL;
+    switch (option) {
+        case MF_OPT_HOGWILD_CHUNK:
+            if (value < 1 || value > (1 << 20)) return fail(ctx, MF_EINVAL, "chunk must be in [1, 2^20]");
+            ctx->hogwild_chunk = (int32_t)value;
+            return MF_OK;
+        case MF_OPT_XCD_AFFINITY:
+            ctx->xcd_affinity = value ? 1 : 0;
+            return MF_OK;
+        case MF_OPT_PROFILE:
+            ctx->profile = value ? 1 : 0;
+            return MF_OK;
+    }
+    return fail(ctx, MF_EINVAL, "unknown option");
+}
+
+int mf_init(mf_ctx* ctx, int64_t m, int64_t n, int32_t k, int32_t dtype, void* dP, void* dQt,
+            uint64_t seed, float scale)
+{
+    if (!ctx) return MF_EINVAL;
+    if (m < 1 || n < 1 || m >= ((int64_t)1 << 31) || n >= ((int64_t)1 << 31))
+        return fail(ctx, MF_EINVAL, "m and n must be in [1, 2^31)");
+    if (!valid_k(k)) return fail(ctx, MF_EINVAL, "k must be 32, 64, 128 or 256");
+    if (dtype != MF_F32 && dtype != MF_F16) return fail(ctx, MF_EINVAL, "dtype must be MF_F32 or MF_F16");
+    if (!dP || !dQt) return fail(ctx, MF_EINVAL, "null factor buffer");
+    if (((uintptr_t)dP | (uintptr_t)dQt) & 15) return fail(ctx, MF_EINVAL, "factor buffers must be 16-byte aligned");
+    if (!(scale == scale)) return fail(ctx, MF_EINVAL, "scale is NaN");
+    MF_HIP(ctx, hipSetDevice(ctx->device));
+    ctx->inited = false;
+    ctx->loaded = false;   // a partition belongs to the matrix shape it was made for
+    if (scale >= 0.f) {
+        MF_HIP(ctx, mf::launch_init(dtype, dP, m * k, seed, 0, scale, ctx->stream));
+        MF_HIP(ctx, mf::launch_init(dtype, dQt, n * k, seed, 1, scale, ctx->stream));
+    }
+    ctx->m = m;
+    ctx->n = n;
+    ctx->k = k;
+    ctx->dtype = dtype;
+    ctx->dP = dP;
+    ctx->dQt = dQt;
+    ctx->inited = true;
+    return MF_OK;
+}
+
+int mf_load_blocks_workspace(const mf_ctx* ctx, int64_t nnz, int32_t grid_r, int32_t grid_c,
+                             size_t* bytes_out)
+{
+    if (!ctx || !bytes_out) return MF_EINVAL;
+    int rc = check_grid(const_cast<mf_ctx*>(ctx), nnz, grid_r, grid_c);
+    if (rc) return rc;
+    *bytes_out = make_layout(nnz, grid_r, grid_c, ctx->hogwild_chunk).total;
+    return MF_OK;
+}
+
+int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const float* vals,
+                   int64_t nnz, int32_t grid_r, int32_t grid_c, int32_t split, void* d_workspace,
+                   size_t workspace_bytes)
+{
+    if (!ctx) return MF_EINVAL;
+    if (!ctx->inited) return fail(ctx, MF_ESTATE, "mf_load_blocks before mf_init");
+    int rc = check_grid(ctx, nnz, grid_r, grid_c);
+    if (rc) return rc;
+    if (grid_r > ctx->m || grid_c > ctx->n) return fail(ctx, MF_EINVAL, "grid exceeds the matrix size");
+    if (split != MF_SPLIT_EQUAL_WIDTH && split != MF_SPLIT_NNZ_BALANCED) return fail(ctx, MF_EINVAL, "unknown split rule");
+    if (nnz > 0 && (!rows || !cols || !vals)) return fail(ctx, MF_EINVAL, "null rating array");
+    if (!d_workspace) return fail(ctx, MF_EINVAL, "null workspace");
+    if ((uintptr_t)d_workspace & 255) return fail(ctx, MF_EINVAL, "workspace must be 256-byte aligned");
+    const Layout lay = make_layout(nnz, grid_r, grid_c, ctx->hogwild_chunk);
+    if (workspace_bytes < lay.total) return fail(ctx, MF_ENOMEM, "workspace too small");
+    MF_HIP(ctx, hipSetDevice(ctx->device));
+    ctx->loaded = false;
+
+    std::vector<int32_t> pu, pv;
+    std::vector<float> pr;
+    try {
+        std::string err;
+        rc = mf::build_partition(rows, cols, vals, nnz, ctx->m, ctx->n, grid_r, grid_c, split, ctx->part,
+                                 pu, pv, pr, err);
+        if (rc) return fail(ctx, rc, err);
+        mf::build_det_schedule(ctx->part, ctx->xcd_affinity != 0, ctx->sched[MF_MODE_DET]);
+        mf::build_hogwild_schedule(ctx->part, pu, ctx->hogwild_chunk, ctx->xcd_affinity != 0,
+                                   ctx->sched[MF_MODE_HOGWILD]);
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, MF_ENOMEM, "host allocation failed while partitioning");
+    }
+
+    char* base = (char*)d_workspace;
+    ctx->dU = (int32_t*)(base + lay.off_u);
+    ctx->dV = (int32_t*)(base + lay.off_v);
+    ctx->dR = (float*)(base + lay.off_r);
+    // the stream may still be running an epoch that reads the old contents of the workspace
+    MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (nnz > 0) {
+        MF_HIP(ctx, hipMemcpy(ctx->dU, pu.data(), (size_t)nnz * 4, hipMemcpyHostToDevice));
+        MF_HIP(ctx, hipMemcpy(ctx->dV, pv.data(), (size_t)nnz * 4, hipMemcpyHostToDevice));
+        MF_HIP(ctx, hipMemcpy(ctx->dR, pr.data(), (size_t)nnz * 4, hipMemcpyHostToDevice));
+    }
+    for (int mode = 0; mode < 2; ++mode) {
+        mf::Schedule& s = ctx->sched[mode];
+        if ((int64_t)s.begin.size() > lay.cap[mode])
+            return fail(ctx, MF_ENOMEM, "schedule larger than its workspace bound");
+        s.d_begin = (int64_t*)(base + lay.off_begin[mode]);
+        s.d_len = (int32_t*)(base + lay.off_len[mode]);
+        if (!s.begin.empty()) {
+            MF_HIP(ctx, hipMemcpy(s.d_begin, s.begin.data(), s.begin.size() * 8, hipMemcpyHostToDevice));
+            MF_HIP(ctx, hipMemcpy(s.d_len, s.len.data(), s.len.size() * 4, hipMemcpyHostToDevice));
+        }
+    }
+    ctx->loaded = true;
+    return MF_OK;
+}
+
+int mf_get_partition(const mf_ctx* ctx, int64_t* perm, int64_t* block_ptr, int32_t* row_bounds,
+                     int32_t* col_bounds)
+{
+    if (!ctx) return MF_EINVAL;
+    if (!ctx->loaded) return fail(const_cast<mf_ctx*>(ctx), MF_ESTATE, "no partition loaded");
+    const mf::Partition& p = ctx->part;
+    if (perm && !p.perm.empty()) std::memcpy(perm, p.perm.data(), p.perm.size() * 8);
+    if (block_ptr) std::memcpy(block_ptr, p.block_ptr.data(), p.block_ptr.size() * 8);
+    if (row_bounds) std::memcpy(row_bounds, p.row_bounds.data(), p.row_bounds.size() * 4);
+    if (col_bounds) std::memcpy(col_bounds, p.col_bounds.data(), p.col_bounds.size() * 4);
+    return MF_OK;
+}
+
+int mf_sgd_epoch(mf_ctx* ctx, float lr, float lambda, int32_t mode)
+{
+    if (!ctx) return MF_EINVAL;
+    if (!ctx->loaded) return fail(ctx, MF_ESTATE, "mf_sgd_epoch before mf_load_blocks");
+    if (mode != MF_MODE_DET && mode != MF_MODE_HOGWILD) return fail(ctx, MF_EINVAL, "unknown mode");
+    if (!(lr == lr) || !(lambda == lambda)) return fail(ctx, MF_EINVAL, "lr or lambda is NaN");
+    MF_HIP(ctx, hipSetDevice(ctx->device));
+    const mf::Schedule& s = ctx->sched[mode];
+    for (int32_t st = 0; st < ctx->part.gc; ++st) {
+        const int64_t first = s.stratum_entry[st];
+        const int64_t count = s.stratum_entry[st + 1] - first;
+        if (count == 0) continue;
+        hipEvent_t ev0 = nullptr, ev1 = nullptr;
+        if (ctx->profile) {
+            if (ctx->events_used == ctx->events.size()) {
+                MF_HIP(ctx, hipEventCreate(&ev0));
+                MF_HIP(ctx, hipEventCreate(&ev1));
+                ctx->events.push_back({ev0, ev1});
+            }
+            ev0 = ctx->events[ctx->events_used].first;
+            ev1 = ctx->events[ctx->events_used].second;
+            ctx->events_used += 1;
+            MF_HIP(ctx, hipEventRecord(ev0, ctx->stream));
+        }
+        MF_HIP(ctx, mf::launch_sgd(ctx->dtype, ctx->k, ctx->dP, ctx->dQt, ctx->dU, ctx->dV, ctx->dR,
+                                   s.d_begin, s.d_len, first, count, lr, lambda, ctx->stream));
+        if (ctx->profile) MF_HIP(ctx, hipEventRecord(ev1, ctx->stream));
+    }
+    return MF_OK;
+}
+
+int mf_rmse(mf_ctx* ctx, const int32_t* d_rows, const int32_t* d_cols, const float* d_vals,
+            int64_t count, double* rmse_out)
+{
+    if (!ctx || !rmse_out) return MF_EINVAL;
+    if (!ctx->inited) return fail(ctx, MF_ESTATE, "mf_rmse before mf_init");
+    if (!d_rows) {
+        if (!ctx->loaded) return fail(ctx, MF_ESTATE, "no training ratings loaded");
+        d_rows = ctx->dU;
+        d_cols = ctx->dV;
+        d_vals = ctx->dR;
+        count = ctx->part.nnz;
+    } else if (!d_cols || !d_vals) {
+        return fail(ctx, MF_EINVAL, "null rating array");
+    }
+    if (count <= 0) return fail(ctx, MF_EINVAL, "RMSE over an empty set");
+    MF_HIP(ctx, hipSetDevice(ctx->device));
+    double* d_sum = ctx->d_partials + mf::kRmsePartials;
+    MF_HIP(ctx, mf::launch_rmse(ctx->dtype, ctx->k, ctx->dP, ctx->dQt, d_rows, d_cols, d_vals, count,
+                                ctx->d_partials, d_sum, ctx->stream));
+    double sum = 0.0;
+    MF_HIP(ctx, hipMemcpyAsync(&sum, d_sum, sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
+    MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    *rmse_out = std::sqrt(sum / (double)count);
+    return MF_OK;
+}
+
+int mf_sync(mf_ctx* ctx)
+{
+    if (!ctx) return MF_EINVAL;
+    MF_HIP(ctx, hipSetDevice(ctx->device));
+    MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    return MF_OK;
+}
+
+int mf_profile_read(mf_ctx* ctx, double* kernel_ms_out, int64_t* launches_out)
+{
+    if (!ctx) return MF_EINVAL;
+    MF_HIP(ctx, hipSetDevice(ctx->device));
+    MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    double total = 0.0;
+    for (size_t i = 0; i < ctx->events_used; ++i) {
+        float ms = 0.f;
+        MF_HIP(ctx, hipEventElapsedTime(&ms, ctx->events[i].first, ctx->events[i].second));
+        total += ms;
+    }
+    if (kernel_ms_out) *kernel_ms_out = total;
+    if (launches_out) *launches_out = (int64_t)ctx->events_used;
+    ctx->events_used = 0;
+    return MF_OK;
+}
+
+int mf_debug_xcc_ids(mf_ctx* ctx, int32_t n_groups, int32_t* xcc_out)
+{
+    if (!ctx || !xcc_out) return MF_EINVAL;
+    if (n_groups < 1 || n_groups > (1 << 20)) return fail(ctx, MF_EINVAL, "n_groups must be in [1, 2^20]");
+    MF_HIP(ctx, hipSetDevice(ctx->device));
+    int32_t* d = nullptr;
+    MF_HIP(ctx, hipMalloc((void**)&d, (size_t)n_groups * 4));
+    hipError_t e = mf::launch_xcc_probe(n_groups, d, ctx->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(xcc_out, d, (size_t)n_groups * 4, hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    (void)hipFree(d);
+    if (e != hipSuccess) return fail_hip(ctx, "xcc probe", e);
+    return MF_OK;
+}
+
+int mf_plan_host(const int32_t* rows, const int32_t* cols, int64_t nnz, int64_t m, int64_t n,
+                 int32_t grid_r, int32_t grid_c, int32_t split, int32_t mode, int32_t chunk,
+                 int32_t xcd_affinity, int64_t* perm, int64_t* block_ptr, int32_t* row_bounds,
+                 int32_t* col_bounds, int64_t* entry_begin, int32_t* entry_len, int64_t entry_cap,
+                 int64_t* stratum_entry, int64_t* n_entries_out)
+{
+    if (check_grid(nullptr, nnz, grid_r, grid_c)) return MF_EINVAL;
+    if (m < 1 || n < 1 || grid_r > m || grid_c > n) return MF_EINVAL;
+    if (split != MF_SPLIT_EQUAL_WIDTH && split != MF_SPLIT_NNZ_BALANCED) return MF_EINVAL;
+    if (mode != MF_MODE_DET && mode != MF_MODE_HOGWILD) return MF_EINVAL;
+    if (chunk < 1 || (nnz > 0 && (!rows || !cols))) return MF_EINVAL;
+    try {
+        mf::Partition part;
+        std::vector<int32_t> pu, pv;
+        std::vector<float> pr, vals((size_t)nnz, 0.f);
+        std::string err;
+        int rc = mf::build_partition(rows, cols, vals.data(), nnz, m, n, grid_r, grid_c, split, part, pu, pv, pr, err);
+        if (rc) return rc;
+        mf::Schedule s;
+        if (mode == MF_MODE_DET) mf::build_det_schedule(part, xcd_affinity != 0, s);
+        else mf::build_hogwild_schedule(part, pu, chunk, xcd_affinity != 0, s);
+        const int64_t bound = mode == MF_MODE_DET ? mf::det_entries_bound(grid_r, grid_c)
+                                                  : mf::hogwild_entries_bound(nnz, grid_r, grid_c, chunk);
+        if ((int64_t)s.begin.size() > bound) return MF_ENOMEM;
+        if (perm && nnz > 0) std::memcpy(perm, part.perm.data(), (size_t)nnz * 8);
+        if (block_ptr) std::memcpy(block_ptr, part.block_ptr.data(), part.block_ptr.size() * 8);
+        if (row_bounds) std::memcpy(row_bounds, part.row_bounds.data(), part.row_bounds.size() * 4);
+        if (col_bounds) std::memcpy(col_bounds, part.col_bounds.data(), part.col_bounds.size() * 4);
+        if (n_entries_out) *n_entries_out = (int64_t)s.begin.size();
+        if (entry_begin || entry_len) {
+            if ((int64_t)s.begin.size() > entry_cap) return MF_ENOMEM;
+            if (entry_begin && !s.begin.empty()) std::memcpy(entry_begin, s.begin.data(), s.begin.size() * 8);
+            if (entry_len && !s.len.empty()) std::memcpy(entry_len, s.len.data(), s.len.size() * 4);
+        }
+        if (stratum_entry) std::memcpy(stratum_entry, s.stratum_entry.data(), s.stratum_entry.size() * 8);
+    } catch (const std::bad_alloc&) {
+        return MF_ENOMEM;
+    }
+    return MF_OK;
+}
+
+}  // extern "C"

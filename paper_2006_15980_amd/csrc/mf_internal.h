@@ -1,0 +1,65 @@
+// Internal declarations shared by the translation units of libmf_sgd (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <string>
+#include <utility>
+#include <vector>
+
+namespace mf {
+
+constexpr int kWave = 64;            // gfx950 wavefront width
+constexpr int kWavesPerGroup = 4;    // 256 threads per workgroup
+constexpr int kGroupThreads = kWave * kWavesPerGroup;
+constexpr int kXcds = 8;             // accelerator dies of an MI355X; workgroup i is placed on die i mod 8
+constexpr int kRmseGroups = 2048;    // fixed launch shape of the RMSE partial kernel
+constexpr int kRmsePartials = kRmseGroups * kWavesPerGroup;
+
+// One unit of work of a wavefront: `len` consecutive ratings of the packed order from `begin`.
+struct Schedule {
+    std::vector<int64_t> begin;          // per entry
+    std::vector<int32_t> len;            // per entry (0 = padding, the wavefront exits at once)
+    std::vector<int64_t> stratum_entry;  // first entry of stratum s (size G_c + 1)
+    int64_t* d_begin = nullptr;          // device copies inside the caller's workspace
+    int32_t* d_len = nullptr;
+};
+
+// Host partition of R into the block grid.
+struct Partition {
+    int64_t nnz = 0;
+    int32_t gr = 0, gc = 0;
+    std::vector<int64_t> perm;        // packed position -> original position
+    std::vector<int64_t> block_ptr;   // gr*gc + 1
+    std::vector<int32_t> row_bounds;  // gr + 1
+    std::vector<int32_t> col_bounds;  // gc + 1
+};
+
+// partition.cpp ------------------------------------------------------------------------------
+// Returns 0 or an MF_E* code; fills `out` and the packed COO arrays (host).
+int build_partition(const int32_t* rows, const int32_t* cols, const float* vals, int64_t nnz,
+                    int64_t m, int64_t n, int32_t gr, int32_t gc, int32_t split, Partition& out,
+                    std::vector<int32_t>& pu, std::vector<int32_t>& pv, std::vector<float>& pr,
+                    std::string& err);
+// DET schedule: one entry per block.  HOGWILD schedule: blocks cut into chunks of whole rows.
+void build_det_schedule(const Partition& part, bool xcd_affinity, Schedule& out);
+void build_hogwild_schedule(const Partition& part, const std::vector<int32_t>& pu, int32_t chunk,
+                            bool xcd_affinity, Schedule& out);
+// Upper bounds on the number of schedule entries, usable before the partition is known.
+int64_t det_entries_bound(int32_t gr, int32_t gc);
+int64_t hogwild_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk);
+
+// kernels.hip ---------------------------------------------------------------------------------
+hipError_t launch_sgd(int dtype, int k, void* P, void* Qt, const int32_t* U, const int32_t* V,
+                      const float* R, const int64_t* entry_begin, const int32_t* entry_len,
+                      int64_t first_entry, int64_t n_entries, float lr, float lambda,
+                      hipStream_t stream);
+hipError_t launch_init(int dtype, void* X, int64_t count, uint64_t seed, uint64_t stream_id,
+                       float scale, hipStream_t stream);
+hipError_t launch_rmse(int dtype, int k, const void* P, const void* Qt, const int32_t* U,
+                       const int32_t* V, const float* R, int64_t count, double* partials,
+                       double* sum_out, hipStream_t stream);
+hipError_t launch_xcc_probe(int32_t n_groups, int32_t* d_out, hipStream_t stream);
+
+}  // namespace mf

@@ -1,0 +1,328 @@
+// Host side of mf_load_blocks: cut the rating matrix into a grid of blocks (Section 3.1 of the
+// paper: blocks that share neither a row strip nor a column strip are independent), order the
+// ratings block by block, and derive the per-wavefront work lists of the two epoch modes.
+//
+// Method: strip lookup tables -> block id per rating -> stable parallel counting sort by block
+// -> per-block sort by (row, column, original position) -> gather into packed arrays.
+#include "mf_internal.h"
+
+#include <algorithm>
+#include <atomic>
+#include <cstdlib>
+#include <thread>
+
+#include "../../include/mf_sgd.h"
+
+namespace mf {
+namespace {
+
+int host_threads()
+{
+    int t = (int)std::thread::hardware_concurrency();
+    if (const char* e = std::getenv("MF_HOST_THREADS")) t = std::atoi(e);
+    return std::max(1, std::min(t, 16));
+}
+
+// Run fn(thread_index, begin, end) over [0, total) split into contiguous ranges.
+template <class F>
+void parallel_ranges(int64_t total, int threads, F fn)
+{
+    if (total < (1 << 16)) threads = 1;
+    std::vector<std::thread> pool;
+    for (int i = 0; i < threads; ++i) {
+        int64_t b = total * i / threads, e = total * (i + 1) / threads;
+        pool.emplace_back([=] { fn(i, b, e); });
+    }
+    for (auto& th : pool) th.join();
+}
+
+// Run fn(item) for item in [0, total), items handed out dynamically.
+template <class F>
+void parallel_items(int64_t total, int threads, F fn)
+{
+    std::atomic<int64_t> next{0};
+    std::vector<std::thread> pool;
+    for (int i = 0; i < threads; ++i)
+        pool.emplace_back([&] {
+            for (;;) {
+                int64_t it = next.fetch_add(1);
+                if (it >= total) break;
+                fn(it);
+            }
+        });
+    for (auto& th : pool) th.join();
+}
+
+void equal_width_bounds(int64_t size, int32_t g, std::vector<int32_t>& b)
+{
+    b.resize((size_t)g + 1);
+    for (int32_t a = 0; a <= g; ++a) b[a] = (int32_t)(((int64_t)a * size + g - 1) / g);
+}
+
+void balanced_bounds(const int32_t* idx, int64_t nnz, int64_t size, int32_t g, int threads,
+                     std::vector<int32_t>& b)
+{
+    // degree histogram with one private histogram per thread
+    std::vector<std::vector<int64_t>> priv((size_t)threads);
+    parallel_ranges(nnz, threads, [&](int i, int64_t s, int64_t e) {
+        priv[i].assign((size_t)size, 0);
+        for (int64_t t = s; t < e; ++t) priv[i][idx[t]] += 1;
+    });
+    b.assign((size_t)g + 1, 0);
+    b[g] = (int32_t)size;
+    int64_t before = 0;   // ratings with id < x
+    int32_t a = 1;
+    for (int64_t x = 0; x < size && a < g; ++x) {
+        // strip boundary a sits at the first id whose exclusive prefix reaches ceil(a*nnz/g)
+        while (a < g && before >= ((int64_t)a * nnz + g - 1) / g) b[a++] = (int32_t)x;
+        for (int i = 0; i < threads; ++i)
+            if (!priv[i].empty()) before += priv[i][x];
+    }
+    while (a < g) b[a++] = (int32_t)size;
+}
+
+void strip_table(const std::vector<int32_t>& bounds, int64_t size, std::vector<int32_t>& table)
+{
+    table.resize((size_t)size);
+    int32_t g = (int32_t)bounds.size() - 1;
+    for (int32_t a = 0; a < g; ++a)
+        for (int64_t x = bounds[a]; x < bounds[a + 1]; ++x) table[x] = a;
+}
+
+struct KeyPos {
+    uint64_t key;   // row << 32 | column
+    int64_t t;      // original position
+};
+
+}  // namespace
+
+int build_partition(const int32_t* rows, const int32_t* cols, const float* vals, int64_t nnz,
+                    int64_t m, int64_t n, int32_t gr, int32_t gc, int32_t split, Partition& out,
+                    std::vector<int32_t>& pu, std::vector<int32_t>& pv, std::vector<float>& pr,
+                    std::string& err)
+{
+    const int threads = host_threads();
+    std::atomic<int> bad{0};
+    parallel_ranges(nnz, threads, [&](int, int64_t s, int64_t e) {
+        for (int64_t t = s; t < e; ++t)
+            if (rows[t] < 0 || rows[t] >= m || cols[t] < 0 || cols[t] >= n) { bad = 1; return; }
+    });
+    if (bad) { err = "a row or column index lies outside the matrix"; return MF_ERANGE; }
+
+    out.nnz = nnz;
+    out.gr = gr;
+    out.gc = gc;
+    if (split == MF_SPLIT_EQUAL_WIDTH) {
+        equal_width_bounds(m, gr, out.row_bounds);
+        equal_width_bounds(n, gc, out.col_bounds);
+    } else {
+        balanced_bounds(rows, nnz, m, gr, threads, out.row_bounds);
+        balanced_bounds(cols, nnz, n, gc, threads, out.col_bounds);
+    }
+    std::vector<int32_t> row_strip, col_strip;
+    strip_table(out.row_bounds, m, row_strip);
+    strip_table(out.col_bounds, n, col_strip);
+
+    const int64_t nblocks = (int64_t)gr * gc;
+    // stable counting sort by block id: thread i owns a contiguous range of original positions
+    int ct = threads;
+    while (ct > 1 && nblocks * ct > ((int64_t)1 << 27)) ct /= 2;
+    if (nnz < (1 << 16)) ct = 1;
+    std::vector<int32_t> blk((size_t)nnz);
+    std::vector<std::vector<int64_t>> hist((size_t)ct);
+    auto range_of = [&](int i, int64_t& s, int64_t& e) { s = nnz * i / ct; e = nnz * (i + 1) / ct; };
+    {
+        std::vector<std::thread> pool;
+        for (int i = 0; i < ct; ++i)
+            pool.emplace_back([&, i] {
+                int64_t s, e;
+                range_of(i, s, e);
+                hist[i].assign((size_t)nblocks, 0);
+                for (int64_t t = s; t < e; ++t) {
+                    int32_t a = row_strip[rows[t]], b = col_strip[cols[t]];
+                    int32_t st = b - a;
+                    if (st < 0) st += gc;
+                    int32_t L = st * gr + a;
+                    blk[t] = L;
+                    hist[i][L] += 1;
+                }
+            });
+        for (auto& th : pool) th.join();
+    }
+    out.block_ptr.assign((size_t)nblocks + 1, 0);
+    {
+        int64_t run = 0;
+        for (int64_t L = 0; L < nblocks; ++L) {
+            out.block_ptr[L] = run;
+            for (int i = 0; i < ct; ++i) {
+                int64_t c = hist[i][L];
+                hist[i][L] = run;      // becomes thread i's write cursor for block L
+                run += c;
+            }
+        }
+        out.block_ptr[nblocks] = run;
+    }
+    out.perm.resize((size_t)nnz);
+    {
+        std::vector<std::thread> pool;
+        for (int i = 0; i < ct; ++i)
+            pool.emplace_back([&, i] {
+                int64_t s, e;
+                range_of(i, s, e);
+                for (int64_t t = s; t < e; ++t) out.perm[hist[i][blk[t]]++] = t;
+            });
+        for (auto& th : pool) th.join();
+    }
+    hist.clear();
+    blk.clear();
+    blk.shrink_to_fit();
+
+    // inside every block: ascending (row, column, original position)
+    parallel_items(nblocks, threads, [&](int64_t L) {
+        int64_t b = out.block_ptr[L], e = out.block_ptr[L + 1];
+        if (e - b < 2) return;
+        std::vector<KeyPos> tmp((size_t)(e - b));
+        for (int64_t i = b; i < e; ++i) {
+            int64_t t = out.perm[i];
+            tmp[i - b] = {((uint64_t)(uint32_t)rows[t] << 32) | (uint32_t)cols[t], t};
+        }
+        std::sort(tmp.begin(), tmp.end(), [](const KeyPos& x, const KeyPos& y) {
+            return x.key != y.key ? x.key < y.key : x.t < y.t;
+        });
+        for (int64_t i = b; i < e; ++i) out.perm[i] = tmp[i - b].t;
+    });
+
+    pu.resize((size_t)nnz);
+    pv.resize((size_t)nnz);
+    pr.resize((size_t)nnz);
+    parallel_ranges(nnz, threads, [&](int, int64_t s, int64_t e) {
+        for (int64_t i = s; i < e; ++i) {
+            int64_t t = out.perm[i];
+            pu[i] = rows[t];
+            pv[i] = cols[t];
+            pr[i] = vals[t];
+        }
+    });
+    return MF_OK;
+}
+
+// Entries of one stratum are laid out for a launch of kWavesPerGroup wavefronts per workgroup:
+// entry e of the stratum is taken by workgroup e / kWavesPerGroup, wavefront e % kWavesPerGroup.
+// With XCD affinity workgroup w serves die (w mod kXcds) and block row a is bound to die
+// a mod kXcds, so every row of P and every row of Qt touched during one launch is touched from
+// one die only (each die has a private L2).  Lists shorter than the longest one are padded with
+// empty entries.
+static void lay_out_stratum(const std::vector<std::vector<std::pair<int64_t, int32_t>>>& per_die,
+                            bool xcd_affinity, Schedule& out)
+{
+    if (!xcd_affinity) {
+        int64_t count = 0;
+        for (auto& l : per_die)
+            for (auto& c : l) {
+                out.begin.push_back(c.first);
+                out.len.push_back(c.second);
+                ++count;
+            }
+        while (count % kWavesPerGroup) {
+            out.begin.push_back(0);
+            out.len.push_back(0);
+            ++count;
+        }
+        return;
+    }
+    size_t longest = 0;
+    for (auto& l : per_die) longest = std::max(longest, l.size());
+    size_t groups_per_die = (longest + kWavesPerGroup - 1) / kWavesPerGroup;
+    for (size_t g = 0; g < groups_per_die; ++g)
+        for (int die = 0; die < kXcds; ++die)
+            for (int w = 0; w < kWavesPerGroup; ++w) {
+                size_t i = g * kWavesPerGroup + w;
+                if (i < per_die[die].size()) {
+                    out.begin.push_back(per_die[die][i].first);
+                    out.len.push_back(per_die[die][i].second);
+                } else {
+                    out.begin.push_back(0);
+                    out.len.push_back(0);
+                }
+            }
+}
+
+void build_det_schedule(const Partition& part, bool xcd_affinity, Schedule& out)
+{
+    out.begin.clear();
+    out.len.clear();
+    out.stratum_entry.assign((size_t)part.gc + 1, 0);
+    std::vector<std::vector<std::pair<int64_t, int32_t>>> per_die((size_t)kXcds);
+    for (int32_t s = 0; s < part.gc; ++s) {
+        for (auto& l : per_die) l.clear();
+        for (int32_t a = 0; a < part.gr; ++a) {
+            int64_t L = (int64_t)s * part.gr + a;
+            int64_t b = part.block_ptr[L], e = part.block_ptr[L + 1];
+            if (e > b) per_die[a % kXcds].push_back({b, (int32_t)(e - b)});
+        }
+        lay_out_stratum(per_die, xcd_affinity, out);
+        out.stratum_entry[(size_t)s + 1] = (int64_t)out.begin.size();
+    }
+}
+
+void build_hogwild_schedule(const Partition& part, const std::vector<int32_t>& pu, int32_t chunk,
+                            bool xcd_affinity, Schedule& out)
+{
+    out.begin.clear();
+    out.len.clear();
+    out.stratum_entry.assign((size_t)part.gc + 1, 0);
+    const int32_t long_row = 2 * chunk;   // rows longer than this are cut into pieces of `chunk`
+    std::vector<std::vector<std::pair<int64_t, int32_t>>> per_die((size_t)kXcds);
+    int64_t spread = 0;
+    for (int32_t s = 0; s < part.gc; ++s) {
+        for (auto& l : per_die) l.clear();
+        for (int32_t a = 0; a < part.gr; ++a) {
+            int64_t L = (int64_t)s * part.gr + a;
+            int64_t pos = part.block_ptr[L];
+            const int64_t end = part.block_ptr[L + 1];
+            auto emit = [&](int64_t b, int64_t e) {
+                if (e <= b) return;
+                int die = xcd_affinity ? a % kXcds : (int)(spread++ % kXcds);
+                per_die[die].push_back({b, (int32_t)(e - b)});
+            };
+            int64_t cur = pos;   // start of the chunk being filled with whole rows
+            while (pos < end) {
+                int64_t row_end = pos + 1;
+                while (row_end < end && pu[row_end] == pu[pos]) ++row_end;
+                int64_t row_len = row_end - pos;
+                if (row_len > long_row) {
+                    emit(cur, pos);
+                    for (int64_t b = pos; b < row_end; b += chunk) emit(b, std::min<int64_t>(b + chunk, row_end));
+                    cur = row_end;
+                } else if (pos > cur && (row_end - cur) > chunk) {
+                    emit(cur, pos);
+                    cur = pos;
+                }
+                pos = row_end;
+            }
+            emit(cur, end);
+        }
+        lay_out_stratum(per_die, xcd_affinity, out);
+        out.stratum_entry[(size_t)s + 1] = (int64_t)out.begin.size();
+    }
+}
+
+int64_t det_entries_bound(int32_t gr, int32_t gc)
+{
+    // per stratum: kXcds lists of at most ceil(gr/kXcds) entries, padded to whole workgroups
+    int64_t per_die = (gr + kXcds - 1) / kXcds;
+    int64_t groups = (per_die + kWavesPerGroup - 1) / kWavesPerGroup;
+    return (int64_t)gc * groups * kXcds * kWavesPerGroup;
+}
+
+int64_t hogwild_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk)
+{
+    // Two consecutive chunks of whole rows of a block hold more than `chunk` ratings together
+    // (at most 2c/chunk + 1 of them for c ratings); a row longer than 2*chunk gives
+    // ceil(len/chunk) pieces and may close one short chunk before it (together at most
+    // 2*len/chunk).  Padding can multiply one die's list by kXcds in the worst case.
+    int64_t chunks = 4 * (nnz / chunk + 1) + 2 * (int64_t)gr * gc;
+    return chunks * kXcds + (int64_t)gc * kXcds * kWavesPerGroup;
+}
+
+}  // namespace mf

@@ -1,0 +1,304 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same
+seeded inputs.
+
+Bars (written out here):
+  * integer work (partition, permutation, block pointers, bounds, initial factors' bit patterns):
+    bit-exact;
+  * deterministic mode, fp32 storage: max |dP|, |dQ| <= 1e-4 against the fp64 oracle after one
+    epoch; final held-out RMSE within 1e-3 (absolute) after the configuration's epochs;
+  * deterministic mode, binary16 storage: the rounding to binary16 is a decision taken in fp32 on
+    both sides (oracle arithmetic F16); elements may still land on neighbouring binary16 values
+    when the two fp32 dot products differ in their last bits, so the bar is 4 binary16 ulps of
+    the element plus the RMSE bar;
+  * Hogwild mode: final held-out RMSE within 0.5 % (relative) of the oracle's;
+  * RMSE kernel: relative 1e-9 against the fp64 oracle.
+"""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from tests.util import dataset, oracle_init, oracle_train
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+FULL = os.environ.get("MF_FULL", "0") == "1"
+
+
+@pytest.fixture(scope="module")
+def mfmod():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2006_15980_amd as mf
+    mf.binding.lib()          # fails loudly when the HIP library is not built
+    return mf
+
+
+def _arith(storage):
+    return oracle.ARITH_F16 if storage == "f16" else oracle.ARITH_F64
+
+
+def _make(mf, ds, k, storage, gr, gc, split, seed=1, scale=0.1, options=None):
+    model = mf.MatrixFactorization(ds.cfg.m, ds.cfg.n, k, storage, seed=seed, scale=scale, options=options)
+    model.load_blocks(ds.rows, ds.cols, ds.vals, gr, gc, split)
+    return model
+
+
+# ------------------------------------------------------------------------------- integer work
+@pytest.mark.parametrize("storage", ["f32", "f16"])
+def test_init_factors_bit_exact(mfmod, storage):
+    m, n, k = 1000, 777, 64
+    model = mfmod.MatrixFactorization(m, n, k, storage, seed=99, scale=0.1)
+    P, Q = model.get_factors()
+    Po, Qo = oracle_init(m, n, k, 99, 0.1, oracle.ARITH_F16 if storage == "f16" else oracle.ARITH_F32)
+    assert np.array_equal(P, Po) and np.array_equal(Q, Qo)
+    model.close()
+
+
+@pytest.mark.parametrize("split", [0, 1])
+def test_partition_through_the_device_path_is_bit_exact(mfmod, split):
+    ds = dataset("tiny")
+    model = _make(mfmod, ds, 32, "f32", 7, 9, split)
+    perm, bp, rb, cb = model.partition()
+    o = oracle.partition(ds.rows, ds.cols, ds.cfg.m, ds.cfg.n, 7, 9, split)
+    for a, b in zip((perm, bp, rb, cb), o):
+        assert np.array_equal(a, b)
+    model.close()
+
+
+# ------------------------------------------------------------------------------- RMSE kernel
+@pytest.mark.parametrize("storage,k", [("f32", 32), ("f32", 128), ("f16", 128), ("f32", 256), ("f16", 64)])
+def test_rmse_kernel_matches_oracle(mfmod, storage, k):
+    ds = dataset("tiny")
+    model = _make(mfmod, ds, k, storage, 4, 4, 1, seed=5, scale=0.6)
+    P, Q = model.get_factors()              # exact: fp32 / binary16 values widen exactly
+    tr, tc, tv = model.to_device(ds.test_rows, ds.test_cols, ds.test_vals)
+    got = model.rmse(tr, tc, tv)
+    want = oracle.rmse(P, Q, ds.test_rows, ds.test_cols, ds.test_vals)
+    assert abs(got - want) <= 1e-9 * want
+    got_tr = model.rmse()                   # over the loaded training ratings
+    want_tr = oracle.rmse(P, Q, ds.rows, ds.cols, ds.vals)
+    assert abs(got_tr - want_tr) <= 1e-9 * want_tr
+    # ragged tail: 1, 63, 64, 65 entries
+    for cnt in (1, 63, 64, 65):
+        g = model.rmse(tr[:cnt], tc[:cnt], tv[:cnt])
+        w = oracle.rmse(P, Q, ds.test_rows[:cnt], ds.test_cols[:cnt], ds.test_vals[:cnt])
+        assert abs(g - w) <= 1e-9 * w
+    model.close()
+
+
+# ------------------------------------------------------------------------------- deterministic mode
+def _det_one_epoch(mfmod, ds, k, storage, gr, gc, split, lr=None, lam=None):
+    lr = ds.cfg.lr if lr is None else lr
+    lam = ds.cfg.lam if lam is None else lam
+    model = _make(mfmod, ds, k, storage, gr, gc, split)
+    model.sgd_epoch(lr, lam, mfmod.MF_MODE_DET)
+    P, Q = model.get_factors()
+    model.close()
+    arith = _arith(storage)
+    perm, bp, _, _ = oracle.partition(ds.rows, ds.cols, ds.cfg.m, ds.cfg.n, gr, gc, split)
+    Po, Qo = oracle_init(ds.cfg.m, ds.cfg.n, k, 1, 0.1, arith)
+    P0, Q0 = Po.copy(), Qo.copy()
+    oracle.sgd_epoch_omp(Po, Qo, ds.rows, ds.cols, ds.vals, perm, bp, gr, gc, lr, lam, arith)
+    assert not np.array_equal(Po, P0) and not np.array_equal(Qo, Q0)
+    return P, Q, Po, Qo
+
+
+@pytest.mark.parametrize("k", [32, 64, 128, 256])
+@pytest.mark.parametrize("grid,split", [((1, 1), 0), ((5, 7), 1), ((32, 32), 1), ((8, 64), 0)])
+def test_det_one_epoch_fp32_within_1e4(mfmod, k, grid, split):
+    ds = dataset("tiny")
+    P, Q, Po, Qo = _det_one_epoch(mfmod, ds, k, "f32", grid[0], grid[1], split)
+    assert np.abs(P - Po).max() <= 1e-4 and np.abs(Q - Qo).max() <= 1e-4, (np.abs(P - Po).max(), np.abs(Q - Qo).max())
+
+
+@pytest.mark.parametrize("k", [32, 128])
+def test_det_one_epoch_binary16_storage(mfmod, k):
+    ds = dataset("tiny")
+    P, Q, Po, Qo = _det_one_epoch(mfmod, ds, k, "f16", 6, 6, 1)
+    for X, Xo in ((P, Po), (Q, Qo)):
+        ulp = np.spacing(np.maximum(np.abs(X), np.abs(Xo)).astype(np.float16)).astype(np.float64)
+        assert (np.abs(X - Xo) <= 4 * ulp).all(), float((np.abs(X - Xo) / ulp).max())
+        assert np.mean(X == Xo) > 0.9
+
+
+def test_det_is_reproducible_and_order_is_respected(mfmod):
+    ds = dataset("tiny")
+    outs = []
+    for _ in range(2):
+        model = _make(mfmod, ds, 32, "f32", 16, 16, 1)
+        for _ in range(2):
+            model.sgd_epoch(ds.cfg.lr, ds.cfg.lam, mfmod.MF_MODE_DET)
+        outs.append(model.get_factors())
+        model.close()
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+
+
+def test_det_edge_cases(mfmod):
+    rng = np.random.default_rng(3)
+    # duplicates of one (u, v), a single long row, a single long column, and empty strata
+    m, n, k = 70, 90, 32
+    rows = np.concatenate([np.full(300, 5), rng.integers(0, m, 300), np.full(130, 9), np.full(40, 11)]).astype(np.int32)
+    cols = np.concatenate([rng.integers(0, n, 300), np.full(300, 17), np.full(130, 21), np.full(40, 21)]).astype(np.int32)
+    vals = rng.uniform(1, 5, rows.size).astype(np.float32)
+    for gr, gc in [(1, 1), (3, 3), (7, 30)]:
+        model = mfmod.MatrixFactorization(m, n, k, "f32", seed=4, scale=0.1)
+        model.load_blocks(rows, cols, vals, gr, gc, 0)
+        model.sgd_epoch(0.01, 0.05, mfmod.MF_MODE_DET)
+        P, Q = model.get_factors()
+        model.close()
+        perm, bp, _, _ = oracle.partition(rows, cols, m, n, gr, gc, 0)
+        Po, Qo = oracle_init(m, n, k, 4, 0.1)
+        oracle.sgd_epoch(Po, Qo, rows, cols, vals, perm, bp, gr, gc, 0.01, 0.05)
+        assert np.abs(P - Po).max() <= 1e-4 and np.abs(Q - Qo).max() <= 1e-4
+        untouched = np.setdiff1d(np.arange(m), rows)
+        P0, _ = oracle_init(m, n, k, 4, 0.1, oracle.ARITH_F32)
+        assert np.array_equal(P[untouched], P0[untouched])          # rows without ratings never change
+
+
+def test_empty_rating_set_is_a_valid_epoch(mfmod):
+    model = mfmod.MatrixFactorization(50, 40, 32, "f32", seed=2, scale=0.1)
+    z = np.zeros(0, np.int32)
+    model.load_blocks(z, z, np.zeros(0, np.float32), 4, 4, 1)
+    before = model.get_factors()
+    model.sgd_epoch(0.01, 0.05, mfmod.MF_MODE_DET)
+    model.sgd_epoch(0.01, 0.05, mfmod.MF_MODE_HOGWILD)
+    after = model.get_factors()
+    assert np.array_equal(before[0], after[0]) and np.array_equal(before[1], after[1])
+    with pytest.raises(mfmod.MFError) as e:
+        model.rmse()
+    assert e.value.code == mfmod.binding.MF_EINVAL
+    model.close()
+
+
+def test_zero_learning_rate_changes_nothing_in_either_mode(mfmod):
+    ds = dataset("tiny")
+    model = _make(mfmod, ds, 128, "f32", 8, 8, 1)
+    before = model.get_factors()
+    model.sgd_epoch(0.0, 0.05, mfmod.MF_MODE_DET)
+    model.sgd_epoch(0.0, 0.05, mfmod.MF_MODE_HOGWILD)
+    after = model.get_factors()
+    assert np.array_equal(before[0], after[0]) and np.array_equal(before[1], after[1])
+    model.close()
+
+
+# ------------------------------------------------------------------------------- full runs of configuration 1
+def _train_gpu(mfmod, ds, k, storage, gr, gc, split, mode, epochs, options=None):
+    model = _make(mfmod, ds, k, storage, gr, gc, split, options=options)
+    tr, tc, tv = model.to_device(ds.test_rows, ds.test_cols, ds.test_vals)
+    for _ in range(epochs):
+        model.sgd_epoch(ds.cfg.lr, ds.cfg.lam, mode)
+    out = model.rmse(tr, tc, tv)
+    model.close()
+    return out
+
+
+def test_tiny_config_det_final_rmse_within_1e3(mfmod):
+    ds = dataset("tiny")
+    gr, gc = 16, 16
+    Po, Qo, _ = oracle_train(ds, gr, gc, 1, ds.cfg.epochs)
+    want = oracle.rmse(Po, Qo, ds.test_rows, ds.test_cols, ds.test_vals)
+    got = _train_gpu(mfmod, ds, ds.cfg.k, "f32", gr, gc, 1, mfmod.MF_MODE_DET, ds.cfg.epochs)
+    assert abs(got - want) <= 1e-3, (got, want)
+
+
+@pytest.mark.parametrize("affinity", [1, 0])
+def test_tiny_config_hogwild_final_rmse_within_half_percent(mfmod, affinity):
+    ds = dataset("tiny")
+    Po, Qo, _ = oracle_train(ds, 8, 8, 1, ds.cfg.epochs)
+    want = oracle.rmse(Po, Qo, ds.test_rows, ds.test_cols, ds.test_vals)
+    got = _train_gpu(mfmod, ds, ds.cfg.k, "f32", 8, 8, 1, mfmod.MF_MODE_HOGWILD, ds.cfg.epochs,
+                     options={mfmod.MF_OPT_XCD_AFFINITY: affinity, mfmod.MF_OPT_HOGWILD_CHUNK: 32})
+    assert abs(got - want) <= 0.005 * want, (got, want)
+
+
+# ------------------------------------------------------------------------------- error paths (forced from the host)
+def test_error_codes(mfmod):
+    b = mfmod.binding
+    ctx = b.mf_create(0, torch.cuda.current_stream().cuda_stream)
+    P = torch.empty((10, 32), device="cuda")
+    Q = torch.empty((12, 32), device="cuda")
+    with pytest.raises(mfmod.MFError) as e:
+        b.mf_sgd_epoch(ctx, 0.1, 0.1, 0)                  # epoch before init/load
+    assert e.value.code == b.MF_ESTATE
+    with pytest.raises(mfmod.MFError) as e:
+        b.mf_init(ctx, 10, 12, 48, 0, P.data_ptr(), Q.data_ptr(), 1, 0.1)   # k not supported
+    assert e.value.code == b.MF_EINVAL
+    with pytest.raises(mfmod.MFError) as e:
+        b.mf_init(ctx, 10, 12, 32, 0, 0, Q.data_ptr(), 1, 0.1)              # null buffer
+    assert e.value.code == b.MF_EINVAL
+    b.mf_init(ctx, 10, 12, 32, 0, P.data_ptr(), Q.data_ptr(), 1, 0.1)
+    rows = np.array([0, 3, 9], np.int32)
+    cols = np.array([0, 5, 11], np.int32)
+    vals = np.ones(3, np.float32)
+    nbytes = b.mf_load_blocks_workspace(ctx, 3, 2, 2)
+    ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+    base = (ws.data_ptr() + 255) & ~255
+    with pytest.raises(mfmod.MFError) as e:
+        b.mf_load_blocks(ctx, rows, cols, vals, 2, 2, 0, base, nbytes - 1)  # workspace too small
+    assert e.value.code == b.MF_ENOMEM
+    with pytest.raises(mfmod.MFError) as e:
+        b.mf_load_blocks(ctx, rows, cols, vals, 3, 2, 0, base, nbytes)      # grid_r > grid_c
+    assert e.value.code == b.MF_EINVAL
+    bad = cols.copy()
+    bad[1] = 12
+    with pytest.raises(mfmod.MFError) as e:
+        b.mf_load_blocks(ctx, rows, bad, vals, 2, 2, 0, base, nbytes)       # column out of range
+    assert e.value.code == b.MF_ERANGE
+    with pytest.raises(mfmod.MFError) as e:
+        b.mf_sgd_epoch(ctx, 0.1, 0.1, 0)                  # still nothing loaded
+    assert e.value.code == b.MF_ESTATE
+    b.mf_load_blocks(ctx, rows, cols, vals, 2, 2, 0, base, nbytes)
+    with pytest.raises(mfmod.MFError) as e:
+        b.mf_sgd_epoch(ctx, 0.1, 0.1, 5)                  # unknown mode
+    assert e.value.code == b.MF_EINVAL
+    b.mf_sgd_epoch(ctx, 0.1, 0.1, 0)
+    b.mf_sync(ctx)
+    b.mf_destroy(ctx)
+
+
+def test_workgroups_are_dealt_round_robin_over_the_eight_dies(mfmod):
+    # the placement MF_OPT_XCD_AFFINITY relies on: workgroup i of a launch runs on die i mod 8
+    ctx = mfmod.binding.mf_create(0, torch.cuda.current_stream().cuda_stream)
+    ids = mfmod.binding.mf_debug_xcc_ids(ctx, 4096)
+    mfmod.binding.mf_destroy(ctx)
+    assert set(ids.tolist()) == set(range(8))
+    rel = (ids - ids[0]) % 8
+    assert np.array_equal(rel, np.arange(4096) % 8)
+
+
+# ------------------------------------------------------------------------------- configuration 2 (the benchmark workload)
+def test_medium_config_scaled_det_and_hogwild(mfmod):
+    ds = dataset("medium", 0.05)
+    k = 128
+    P, Q, Po, Qo = _det_one_epoch(mfmod, ds, k, "f32", 64, 64, 1)
+    assert np.abs(P - Po).max() <= 1e-4 and np.abs(Q - Qo).max() <= 1e-4
+    epochs = 5
+    Po, Qo, _ = oracle_train(ds, 8, 8, 1, epochs)
+    want = oracle.rmse(Po, Qo, ds.test_rows, ds.test_cols, ds.test_vals)
+    got = _train_gpu(mfmod, ds, k, "f32", 8, 8, 1, mfmod.MF_MODE_HOGWILD, epochs)
+    assert abs(got - want) <= 0.005 * want, (got, want)
+
+
+def test_medium_config_full_size(mfmod):
+    """Configuration 2 at its full size, in the launch configuration the benchmark times
+    (HOGWILD on an 8 x 8 grid) plus the deterministic mode on a fine grid."""
+    ds = dataset("medium")
+    k = ds.cfg.k
+    print("medium: max row/col degree", ds.max_row_degree, ds.max_col_degree, flush=True)
+    P, Q, Po, Qo = _det_one_epoch(mfmod, ds, k, "f32", 256, 256, 1)
+    dP, dQ = np.abs(P - Po).max(), np.abs(Q - Qo).max()
+    print("medium DET one epoch: max|dP| %.3g max|dQ| %.3g" % (dP, dQ), flush=True)
+    assert dP <= 1e-4 and dQ <= 1e-4
+    epochs = ds.cfg.epochs if FULL else 4
+    Po, Qo, _ = oracle_train(ds, 8, 8, 1, epochs)
+    want = oracle.rmse(Po, Qo, ds.test_rows, ds.test_cols, ds.test_vals)
+    got = _train_gpu(mfmod, ds, k, "f32", 8, 8, 1, mfmod.MF_MODE_HOGWILD, epochs)
+    print("medium HOGWILD %d epochs: rmse gpu %.6f oracle %.6f" % (epochs, got, want), flush=True)
+    assert abs(got - want) <= 0.005 * want, (got, want)
+    got_det = _train_gpu(mfmod, ds, k, "f32", 8, 8, 1, mfmod.MF_MODE_DET, 1)
+    Po, Qo, _ = oracle_train(ds, 8, 8, 1, 1)
+    want_det = oracle.rmse(Po, Qo, ds.test_rows, ds.test_cols, ds.test_vals)
+    assert abs(got_det - want_det) <= 1e-3, (got_det, want_det)

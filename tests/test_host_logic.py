@@ -1,0 +1,136 @@
+"""CPU-only checks of the library's host side: the C ABI loads and exports what the header
+declares, the host partitioner agrees bit for bit with the oracle's, and the per-wavefront
+work lists visit every rating exactly once inside the right stratum."""
+import ctypes
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from paper_2006_15980_amd import binding as B
+from tests.util import ROOT, declared_functions
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions(os.path.join(ROOT, "include", "mf_sgd.h"))
+    assert set(names) == set(B.EXPORTS)
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for nm in names:
+        assert hasattr(lib, nm), nm
+
+
+def test_no_product_module_reaches_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2006_15980_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".cpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f
+
+
+def _cases():
+    rng = np.random.default_rng(0)
+    out = []
+    m, n, nnz = 300, 200, 20000
+    out.append(("uniform", rng.integers(0, m, nnz).astype(np.int32), rng.integers(0, n, nnz).astype(np.int32), m, n))
+    w = 1.0 / np.arange(1, m + 1) ** 1.2
+    out.append(("skewed", rng.choice(m, nnz, p=w / w.sum()).astype(np.int32),
+                rng.integers(0, n, nnz).astype(np.int32), m, n))
+    r = rng.integers(0, 50, 3000).astype(np.int32)
+    c = rng.integers(0, 40, 3000).astype(np.int32)
+    r[100:400] = 7
+    c[100:400] = 3                     # many duplicates of one (u, v)
+    out.append(("dups", r, c, 50, 40))
+    out.append(("empty", np.zeros(0, np.int32), np.zeros(0, np.int32), 10, 10))
+    out.append(("one", np.array([4], np.int32), np.array([9], np.int32), 10, 10))
+    return out
+
+
+@pytest.mark.parametrize("split", [B.MF_SPLIT_EQUAL_WIDTH, B.MF_SPLIT_NNZ_BALANCED])
+@pytest.mark.parametrize("grid", [(1, 1), (2, 5), (8, 8), (9, 10), (10, 10)])
+def test_host_partition_is_bit_exact_with_the_oracle(split, grid):
+    gr, gc = grid
+    for name, rows, cols, m, n in _cases():
+        plan = B.mf_plan_host(rows, cols, m, n, gr, gc, split, B.MF_MODE_DET)
+        perm, bp, rb, cb = oracle.partition(rows, cols, m, n, gr, gc, split)
+        assert np.array_equal(plan["perm"], perm), name
+        assert np.array_equal(plan["block_ptr"], bp), name
+        assert np.array_equal(plan["row_bounds"], rb), name
+        assert np.array_equal(plan["col_bounds"], cb), name
+
+
+def test_host_partition_bit_exact_on_a_workload_shaped_case():
+    ds = workloads.generate(workloads.scaled(workloads.CONFIGS["large"], 0.003, k=32))
+    for (gr, gc, split) in [(8, 16, 1), (64, 64, 1), (32, 48, 0)]:
+        plan = B.mf_plan_host(ds.rows, ds.cols, ds.cfg.m, ds.cfg.n, gr, gc, split, B.MF_MODE_HOGWILD)
+        perm, bp, rb, cb = oracle.partition(ds.rows, ds.cols, ds.cfg.m, ds.cfg.n, gr, gc, split)
+        assert np.array_equal(plan["perm"], perm) and np.array_equal(plan["block_ptr"], bp)
+        assert np.array_equal(plan["row_bounds"], rb) and np.array_equal(plan["col_bounds"], cb)
+
+
+@pytest.mark.parametrize("mode", [B.MF_MODE_DET, B.MF_MODE_HOGWILD])
+@pytest.mark.parametrize("affinity", [0, 1])
+@pytest.mark.parametrize("grid", [(1, 1), (3, 4), (8, 8), (20, 24)])
+def test_work_lists_cover_every_rating_once_inside_its_stratum(mode, affinity, grid):
+    gr, gc = grid
+    chunk = 48
+    for name, rows, cols, m, n in _cases():
+        if gr > m or gc > n:
+            continue
+        plan = B.mf_plan_host(rows, cols, m, n, gr, gc, B.MF_SPLIT_NNZ_BALANCED, mode, chunk, affinity)
+        eb, el, se, bp, perm = (plan[k] for k in ("entry_begin", "entry_len", "stratum_entry", "block_ptr", "perm"))
+        nnz = rows.size
+        assert se[0] == 0 and se[-1] == eb.size and eb.size % 4 == 0
+        seen = np.zeros(nnz, np.int32)
+        pu = rows[perm]
+        for s in range(gc):
+            assert (se[s + 1] - se[s]) % 4 == 0
+            if affinity:
+                assert (se[s + 1] - se[s]) % 32 == 0
+            lo, hi = bp[s * gr], bp[(s + 1) * gr]
+            for e in range(se[s], se[s + 1]):
+                if el[e] == 0:
+                    continue
+                b, ln = eb[e], el[e]
+                assert lo <= b and b + ln <= hi                      # stays inside its stratum
+                L = np.searchsorted(bp, b, side="right") - 1
+                assert b + ln <= bp[L + 1]                           # and inside one block
+                seen[b:b + ln] += 1
+                a = L - s * gr
+                if affinity:
+                    group = (e - se[s]) // 4
+                    assert group % 8 == a % 8                        # block row a runs on die a mod 8
+                if mode == B.MF_MODE_DET:
+                    assert b == bp[L] and ln == bp[L + 1] - bp[L]    # one wavefront per block
+                else:
+                    # chunks are whole rows unless the row is longer than two chunks
+                    first_row, last_row = pu[b], pu[b + ln - 1]
+                    for edge_row, pos in ((first_row, b - 1), (last_row, b + ln)):
+                        if bp[L] <= pos < bp[L + 1] and pu[pos] == edge_row:
+                            row_len = np.count_nonzero(pu[bp[L]:bp[L + 1]] == edge_row)
+                            assert row_len > 2 * chunk, (name, row_len)
+                    assert ln <= 2 * chunk
+        assert (seen == 1).all(), name
+
+
+def test_plan_rejects_bad_arguments():
+    rows = np.array([0, 1, 2], np.int32)
+    cols = np.array([0, 1, 5], np.int32)
+    with pytest.raises(B.MFError) as e:
+        B.mf_plan_host(rows, cols, 3, 5, 1, 1, 0, 0)                 # column 5 out of range
+    assert e.value.code == B.MF_ERANGE
+    for args in [(3, 6, 2, 1, 0, 0), (3, 6, 0, 1, 0, 0), (3, 6, 4, 4, 0, 0), (3, 6, 1, 1, 7, 0), (3, 6, 1, 1, 0, 9)]:
+        with pytest.raises(B.MFError) as e:
+            B.mf_plan_host(rows, cols, *args)
+        assert e.value.code == B.MF_EINVAL, args
+
+
+def test_create_without_a_device_is_an_error_not_a_crash():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(B.MFError) as e:
+        B.mf_create(0, 0)
+    assert e.value.code == B.MF_EDEVICE
