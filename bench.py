@@ -78,7 +78,10 @@ def main():
     ap.add_argument("--workload", default="medium")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (testing only)")
     ap.add_argument("--mode", default="hogwild", choices=["hogwild", "det"])
-    ap.add_argument("--grid", default="8x8")
+    ap.add_argument("--grid", default="128x128")
+    ap.add_argument("--hogwild-kernel", default="auto", choices=["auto", "global_atomics", "lds"])
+    ap.add_argument("--lds-chunk", type=int, default=32)
+    ap.add_argument("--lds-waves", type=int, default=16)
     ap.add_argument("--chunk", type=int, default=128)
     ap.add_argument("--affinity", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -105,8 +108,11 @@ def main():
     elt = 4 if cfg.storage == "f32" else 2
     bytes_per_update = 12 + 4 * k * elt      # rating record + read and write of p_u and q_v
 
+    which = {"auto": mf.MF_HOGWILD_AUTO, "global_atomics": mf.MF_HOGWILD_GLOBAL_ATOMICS,
+             "lds": mf.MF_HOGWILD_LDS}[args.hogwild_kernel]
     opts = {mf.MF_OPT_HOGWILD_CHUNK: args.chunk, mf.MF_OPT_XCD_AFFINITY: args.affinity,
-            mf.MF_OPT_PROFILE: 0 if args.no_kernel_events else 1}
+            mf.MF_OPT_PROFILE: 0 if args.no_kernel_events else 1, mf.MF_OPT_HOGWILD_KERNEL: which,
+            mf.MF_OPT_LDS_CHUNK: args.lds_chunk, mf.MF_OPT_LDS_WAVES: args.lds_waves}
     model = mf.MatrixFactorization(cfg.m, cfg.n, k, cfg.storage, seed=1, scale=0.1, options=opts)
     t0 = time.perf_counter()
     model.load_blocks(ds.rows, ds.cols, ds.vals, gr, gc, mf.MF_SPLIT_NNZ_BALANCED)
@@ -136,7 +142,7 @@ def main():
         bytes_per_launch = bytes_per_update * nnz * args.steps / launches
         achieved = bytes_per_launch / avg_s / 1e9
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "sgd_chunks<float,128>",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "sgd_block_lds<float,128>" if (args.mode == "hogwild" and args.hogwild_kernel != "global_atomics") else "sgd_chunks<float,128>",
                     "avg_launch_us": avg_s * 1e6, "launches_per_step": launches / args.steps,
                     "bytes_per_update": bytes_per_update}
     out = {"metric": "SGD updates/s at k=128 (HOGWILD epoch + held-out RMSE per step)", "value": value,
@@ -145,7 +151,9 @@ def main():
            "vs_baseline": None, "dtype": "f32" if cfg.storage == "f32" else "f16 storage / f32 math",
            "data": "synthetic",
            "config": {"workload": f"{cfg.name}: m={cfg.m} n={cfg.n} nnz_train={nnz} k={k} {cfg.storage}",
-                      "mode": args.mode, "grid": args.grid, "chunk": args.chunk, "xcd_affinity": args.affinity,
+                      "mode": args.mode, "grid": args.grid, "hogwild_kernel": args.hogwild_kernel,
+                      "lds_chunk": args.lds_chunk, "lds_waves": args.lds_waves, "chunk": args.chunk,
+                      "xcd_affinity": args.affinity,
                       "lr": cfg.lr, "lambda": cfg.lam},
            "final_test_rmse": rmse, "load_blocks_s": t_load,
            "algorithmic_gbs": value * bytes_per_update / 1e9,

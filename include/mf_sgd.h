@@ -50,8 +50,14 @@ enum {
     MF_OPT_HOGWILD_CHUNK = 1,     /* target ratings per wavefront in HOGWILD mode (default 128)      */
     MF_OPT_XCD_AFFINITY = 2,      /* 1 (default): all wavefronts working on one block are placed on  */
                                   /* one XCD; 0: spread over all XCDs                                 */
-    MF_OPT_PROFILE = 3            /* 1: time every SGD kernel launch with HIP events (see below)     */
+    MF_OPT_PROFILE = 3,           /* 1: time every SGD kernel launch with HIP events (see below)     */
+    MF_OPT_HOGWILD_KERNEL = 4,    /* MF_HOGWILD_AUTO (default), _GLOBAL_ATOMICS or _LDS, see          */
+                                  /* mf_sgd_epoch                                                     */
+    MF_OPT_LDS_CHUNK = 5,         /* target ratings per work-list entry of the LDS kernel (default 32)*/
+    MF_OPT_LDS_WAVES = 6          /* wavefronts per workgroup of the LDS kernel, 1..16 (default 16)   */
 };
+enum { MF_HOGWILD_AUTO = 0, MF_HOGWILD_GLOBAL_ATOMICS = 1, MF_HOGWILD_LDS = 2 };
+enum { MF_PLAN_HOGWILD_LDS = 2 };  /* third value of `mode` accepted by mf_plan_host only */
 
 /* Create a context on HIP device `device`.  `hip_stream` is a hipStream_t of the caller (may be
  * NULL for the default stream); all work of this context is enqueued on it. */
@@ -115,7 +121,16 @@ int mf_get_partition(const mf_ctx* ctx, int64_t* perm, int64_t* block_ptr,
  *                     ascending, stored order) up to fp32 rounding.
  *   MF_MODE_HOGWILD : every block is cut into chunks of whole rows that many wavefronts process
  *                     concurrently without locks (lock-free updates in the sense of Hogwild,
- *                     Section 3.1); rows of Qt are raced on, the result varies from run to run. */
+ *                     Section 3.1).  A wavefront owns the rows of P of its chunk; rows of Qt are
+ *                     shared: each wavefront ADDS its change of q_v with a floating-point atomic,
+ *                     computed from a value that other wavefronts may have changed meanwhile, so
+ *                     no update is lost but the result varies from run to run.  Two kernels:
+ *                       MF_HOGWILD_LDS            one workgroup per block keeps the block's strip
+ *                                                 of Qt in LDS (fp32) and uses LDS atomics; needs
+ *                                                 (widest column strip) * k * 4 bytes <= 159 KiB;
+ *                       MF_HOGWILD_GLOBAL_ATOMICS wavefronts of a whole die share a block and use
+ *                                                 atomics in that die's L2 (any grid, slower).
+ *                     MF_HOGWILD_AUTO takes the LDS kernel whenever the grid allows it. */
 int mf_sgd_epoch(mf_ctx* ctx, float lr, float lambda, int32_t mode);
 
 /* RMSE = sqrt(mean (r - p_u.q_v)^2) of the current factors (the quality metric of Section 7).
@@ -145,9 +160,14 @@ int mf_debug_xcc_ids(mf_ctx* ctx, int32_t n_groups, int32_t* xcc_out);
  * the block rule of Section 3.1 without a GPU.  All pointers are HOST; any output may be NULL.
  *   perm, block_ptr, row_bounds, col_bounds : as in mf_get_partition.
  *   entry_begin[entry_cap], entry_len[entry_cap] : work-list entries (first packed position and
- *       number of ratings; length 0 = padding); entry e of a stratum is run by workgroup e/4 of
- *       that stratum's launch, and with xcd_affinity = 1 workgroup w serves die w mod 8.
+ *       number of ratings; length 0 = padding; in HOGWILD lists the sign bit of the length marks
+ *       a piece of a matrix row that was cut because it is longer than two chunks, the low 31
+ *       bits are the length); entry e of a stratum is run by workgroup e/4 of that stratum's
+ *       launch, and with xcd_affinity = 1 workgroup w serves die w mod 8.
  *   stratum_entry[grid_c+1] : first entry of each stratum;  n_entries_out : entries in total.
+ * mode = MF_PLAN_HOGWILD_LDS gives the work list of the LDS kernel: entries block after block
+ * without padding (chunk = MF_OPT_LDS_CHUNK's meaning); every block's entries are taken by the
+ * wavefronts of one workgroup.
  * MF_ENOMEM if entry_cap is too small. */
 int mf_plan_host(const int32_t* rows, const int32_t* cols, int64_t nnz, int64_t m, int64_t n,
                  int32_t grid_r, int32_t grid_c, int32_t split, int32_t mode, int32_t chunk,

@@ -21,12 +21,23 @@ namespace mf {
 namespace {
 
 // ---------------------------------------------------------------------------------- row access
-// A factor row of K elements is held by a wavefront as VEC consecutive elements per lane;
-// lanes >= K / VEC (only for K = 32) hold zeros and never touch memory.
+// A factor row of K elements is spread over the lanes of a wavefront, VEC values per lane:
+//   fp32     : value j of lane l is element l + 64*j, so every load / store / atomic instruction
+//              of the wavefront covers 256 contiguous bytes; lanes >= K are idle (K = 32);
+//   binary16 : values 2j, 2j+1 of lane l are the element pair 2*l + 128*j, +1 (one 32-bit word,
+//              which is what the packed binary16 atomic add needs); lanes >= K/2 are idle.
+// Idle lanes hold zeros and never touch memory.
+template <typename T, int K>
+struct RowShape;
 template <int K>
-struct RowShape {
+struct RowShape<float, K> {
     static constexpr int VEC = K >= 64 ? K / 64 : 1;
-    static constexpr int ACTIVE = K / VEC;
+    static constexpr int ACTIVE = K >= 64 ? 64 : K;
+};
+template <int K>
+struct RowShape<__half, K> {
+    static constexpr int VEC = K >= 128 ? K / 64 : 2;
+    static constexpr int ACTIVE = K >= 128 ? 64 : K / 2;
 };
 
 template <int VEC>
@@ -34,51 +45,53 @@ struct Row {
     float x[VEC];
 };
 
-template <int VEC>
+// 32-bit load; FRESH = read through to the die's L2 (agent-scope atomic load) instead of the
+// compute unit's private L1, which atomic updates made by other compute units do not refresh.
+template <bool FRESH>
+__device__ __forceinline__ unsigned load_word(const unsigned* p)
+{
+    if constexpr (FRESH) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return *p;
+}
+
+__device__ __forceinline__ float2 unpack_half2(unsigned w)
+{
+    __half2 h = *reinterpret_cast<__half2*>(&w);
+    return make_float2(__low2float(h), __high2float(h));
+}
+
+__device__ __forceinline__ unsigned pack_half2(float a, float b)
+{
+    __half2 h = __floats2half2_rn(a, b);
+    return *reinterpret_cast<unsigned*>(&h);
+}
+
+template <int VEC, bool FRESH>
 __device__ __forceinline__ Row<VEC> load_row(const float* row_ptr, int lane, bool active)
 {
     Row<VEC> r;
 #pragma unroll
     for (int j = 0; j < VEC; ++j) r.x[j] = 0.f;
     if (active) {
-        if constexpr (VEC == 1) {
-            r.x[0] = row_ptr[lane];
-        } else if constexpr (VEC == 2) {
-            float2 t = *reinterpret_cast<const float2*>(row_ptr + 2 * lane);
-            r.x[0] = t.x;
-            r.x[1] = t.y;
-        } else {
-            float4 t = *reinterpret_cast<const float4*>(row_ptr + 4 * lane);
-            r.x[0] = t.x;
-            r.x[1] = t.y;
-            r.x[2] = t.z;
-            r.x[3] = t.w;
-        }
+#pragma unroll
+        for (int j = 0; j < VEC; ++j)
+            r.x[j] = __uint_as_float(load_word<FRESH>(reinterpret_cast<const unsigned*>(row_ptr) + lane + kWave * j));
     }
     return r;
 }
 
-template <int VEC>
+template <int VEC, bool FRESH>
 __device__ __forceinline__ Row<VEC> load_row(const __half* row_ptr, int lane, bool active)
 {
     Row<VEC> r;
 #pragma unroll
     for (int j = 0; j < VEC; ++j) r.x[j] = 0.f;
     if (active) {
-        if constexpr (VEC == 1) {
-            r.x[0] = __half2float(row_ptr[lane]);
-        } else if constexpr (VEC == 2) {
-            __half2 t = *reinterpret_cast<const __half2*>(row_ptr + 2 * lane);
-            r.x[0] = __low2float(t);
-            r.x[1] = __high2float(t);
-        } else {
-            uint2 raw = *reinterpret_cast<const uint2*>(row_ptr + 4 * lane);
-            __half2 a = *reinterpret_cast<__half2*>(&raw.x);
-            __half2 b = *reinterpret_cast<__half2*>(&raw.y);
-            r.x[0] = __low2float(a);
-            r.x[1] = __high2float(a);
-            r.x[2] = __low2float(b);
-            r.x[3] = __high2float(b);
+#pragma unroll
+        for (int j = 0; j < VEC / 2; ++j) {
+            float2 t = unpack_half2(load_word<FRESH>(reinterpret_cast<const unsigned*>(row_ptr) + lane + kWave * j));
+            r.x[2 * j] = t.x;
+            r.x[2 * j + 1] = t.y;
         }
     }
     return r;
@@ -88,13 +101,8 @@ template <int VEC>
 __device__ __forceinline__ void store_row(float* row_ptr, int lane, bool active, const Row<VEC>& r)
 {
     if (!active) return;
-    if constexpr (VEC == 1) {
-        row_ptr[lane] = r.x[0];
-    } else if constexpr (VEC == 2) {
-        *reinterpret_cast<float2*>(row_ptr + 2 * lane) = make_float2(r.x[0], r.x[1]);
-    } else {
-        *reinterpret_cast<float4*>(row_ptr + 4 * lane) = make_float4(r.x[0], r.x[1], r.x[2], r.x[3]);
-    }
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) row_ptr[lane + kWave * j] = r.x[j];
 }
 
 // binary16 storage: the row kept in registers already holds values on the binary16 grid
@@ -103,26 +111,44 @@ template <int VEC>
 __device__ __forceinline__ void store_row(__half* row_ptr, int lane, bool active, const Row<VEC>& r)
 {
     if (!active) return;
-    if constexpr (VEC == 1) {
-        row_ptr[lane] = __float2half_rn(r.x[0]);
-    } else if constexpr (VEC == 2) {
-        *reinterpret_cast<__half2*>(row_ptr + 2 * lane) = __floats2half2_rn(r.x[0], r.x[1]);
-    } else {
-        __half2 a = __floats2half2_rn(r.x[0], r.x[1]);
-        __half2 b = __floats2half2_rn(r.x[2], r.x[3]);
-        uint2 raw;
-        raw.x = *reinterpret_cast<unsigned*>(&a);
-        raw.y = *reinterpret_cast<unsigned*>(&b);
-        *reinterpret_cast<uint2*>(row_ptr + 4 * lane) = raw;
-    }
+#pragma unroll
+    for (int j = 0; j < VEC / 2; ++j)
+        reinterpret_cast<unsigned*>(row_ptr)[lane + kWave * j] = pack_half2(r.x[2 * j], r.x[2 * j + 1]);
+}
+
+// row += d with hardware floating-point atomic adds executed in the L2 (no value returned).
+template <int VEC>
+__device__ __forceinline__ void atomic_add_row(float* row_ptr, int lane, bool active, const Row<VEC>& d)
+{
+    if (!active) return;
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) unsafeAtomicAdd(row_ptr + lane + kWave * j, d.x[j]);
+}
+
+template <int VEC>
+__device__ __forceinline__ void atomic_add_row(__half* row_ptr, int lane, bool active, const Row<VEC>& d)
+{
+    if (!active) return;
+#pragma unroll
+    for (int j = 0; j < VEC / 2; ++j)
+        unsafeAtomicAdd(reinterpret_cast<__half2*>(row_ptr) + lane + kWave * j,
+                        __floats2half2_rn(d.x[2 * j], d.x[2 * j + 1]));
 }
 
 // Values leave a step on the grid of the storage type: fp32 as they are, binary16 rounded to
 // nearest even after EVERY step, also while a row stays in registers across several ratings.
+// The conversion takes a finished fp32 value: the empty asm keeps the compiler from folding the
+// producing multiply-add into a mixed-precision instruction that would round only once.
+__device__ __forceinline__ __half round_to_half(float x)
+{
+    asm("" : "+v"(x));
+    return __float2half_rn(x);
+}
+
 template <typename T>
 __device__ __forceinline__ float quantise(float x)
 {
-    if constexpr (sizeof(T) == 2) return __half2float(__float2half_rn(x));
+    if constexpr (sizeof(T) == 2) return __half2float(round_to_half(x));
     return x;
 }
 
@@ -160,26 +186,52 @@ __device__ __forceinline__ int uniform_lane(int v, int lane)
 //      row index does not change, written back when it changes and at the end);
 //   q  holds row v_i of Qt likewise: it was requested while rating i-1 was being computed, and
 //      replaced by the freshly computed row when v_i == v_{i-1} (the request was issued before
-//      the store of rating i-1 and would be stale).
-template <typename T, int K>
+//      the write of rating i-1 and would be stale).
+// HOG = false (deterministic mode): the wavefront is the only one touching its rows during the
+//      launch; rows are written with plain stores.
+// HOG = true (Hogwild mode): other wavefronts of the same die update rows of Qt at the same
+//      time, so the change of q_v is ADDED to memory with a floating-point atomic (no update is
+//      lost; the value it was computed from may be slightly out of date), and rows are read
+//      past the L1.  Entries whose length has the sign bit set share their row of P with other
+//      entries (a very long row cut into pieces that run concurrently): they treat p_u like
+//      q_v -- re-read it for every rating and add every change atomically -- because pieces
+//      that each corrected a private copy of p_u over many ratings and then added those
+//      corrections up would overshoot.  All other entries own their rows of P, keep p_u in
+//      registers over the whole row and store it once.
+constexpr int32_t kSharedRowFlag = (int32_t)0x80000000;
+
+template <typename T, int K, bool HOG>
 __global__ __launch_bounds__(kGroupThreads) void sgd_chunks(
     T* __restrict__ P, T* __restrict__ Qt, const int32_t* __restrict__ U,
     const int32_t* __restrict__ V, const float* __restrict__ R,
     const int64_t* __restrict__ entry_begin, const int32_t* __restrict__ entry_len,
     int64_t first_entry, float lr, float lambda)
 {
-    constexpr int VEC = RowShape<K>::VEC;
+    constexpr int VEC = RowShape<T, K>::VEC;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t entry = first_entry + (int64_t)blockIdx.x * kWavesPerGroup + wave;
-    const int32_t len = entry_len[entry];
-    if (len == 0) return;
+    const int32_t raw_len = entry_len[entry];
+    if (raw_len == 0) return;
+    const bool shared_rows = HOG && raw_len < 0;
+    const int32_t len = raw_len & ~kSharedRowFlag;
     const int64_t begin = entry_begin[entry];
-    const bool active = lane < RowShape<K>::ACTIVE;
+    const bool active = lane < RowShape<T, K>::ACTIVE;
     const float shrink = lr * lambda;
 
-    Row<VEC> p, q;
+    Row<VEC> p, q, p_at_load;
     int cur_u = -1;
+    // write row `row` of P back: plain store, or the accumulated change as an atomic add
+    auto flush_p = [&](int row, const Row<VEC>& val) {
+        if (shared_rows) {
+            Row<VEC> d;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) d.x[j] = val.x[j] - p_at_load.x[j];
+            atomic_add_row<VEC>(P + (int64_t)row * K, lane, active, d);
+        } else {
+            store_row<VEC>(P + (int64_t)row * K, lane, active, val);
+        }
+    };
     for (int32_t off = 0; off < len; off += kWave) {
         const int cnt = min(kWave, len - off);
         int mu = 0, mv = 0;
@@ -192,11 +244,12 @@ __global__ __launch_bounds__(kGroupThreads) void sgd_chunks(
         int u = uniform_lane(mu, 0);
         int v = uniform_lane(mv, 0);
         if (u != cur_u) {
-            if (cur_u >= 0) store_row<VEC>(P + (int64_t)cur_u * K, lane, active, p);
-            p = load_row<VEC>(P + (int64_t)u * K, lane, active);
+            if (cur_u >= 0) flush_p(cur_u, p);
+            p = load_row<VEC, HOG>(P + (int64_t)u * K, lane, active);
+            p_at_load = p;
             cur_u = u;
         }
-        q = load_row<VEC>(Qt + (int64_t)v * K, lane, active);
+        q = load_row<VEC, HOG>(Qt + (int64_t)v * K, lane, active);
         for (int i = 0; i < cnt; ++i) {
             const float r = __int_as_float(uniform_lane(__float_as_int(mr), i));
             // request the rows of the next rating of this batch before computing this one
@@ -206,8 +259,8 @@ __global__ __launch_bounds__(kGroupThreads) void sgd_chunks(
             if (more) {
                 un = uniform_lane(mu, i + 1);
                 vn = uniform_lane(mv, i + 1);
-                qn = load_row<VEC>(Qt + (int64_t)vn * K, lane, active);
-                if (un != u) pn = load_row<VEC>(P + (int64_t)un * K, lane, active);
+                qn = load_row<VEC, HOG>(Qt + (int64_t)vn * K, lane, active);
+                if (un != u || shared_rows) pn = load_row<VEC, HOG>(P + (int64_t)un * K, lane, active);
             }
             float part = 0.f;
 #pragma unroll
@@ -220,14 +273,37 @@ __global__ __launch_bounds__(kGroupThreads) void sgd_chunks(
                 // p + lr*(e*q - lambda*p) regrouped as (p - (lr*lambda)*p) + (lr*e)*q: two
                 // fused operations, each rounded once at the magnitude of the element
                 p2.x[j] = quantise<T>(fmaf(step, q.x[j], fmaf(-shrink, p.x[j], p.x[j])));
-                q2.x[j] = quantise<T>(fmaf(step, p.x[j], fmaf(-shrink, q.x[j], q.x[j])));
             }
-            store_row<VEC>(Qt + (int64_t)v * K, lane, active, q2);
+            if constexpr (HOG) {
+                Row<VEC> dq;
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    dq.x[j] = fmaf(step, p.x[j], -shrink * q.x[j]);
+                    q2.x[j] = quantise<T>(q.x[j] + dq.x[j]);
+                }
+                atomic_add_row<VEC>(Qt + (int64_t)v * K, lane, active, dq);
+            } else {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j)
+                    q2.x[j] = quantise<T>(fmaf(step, p.x[j], fmaf(-shrink, q.x[j], q.x[j])));
+                store_row<VEC>(Qt + (int64_t)v * K, lane, active, q2);
+            }
             if (more) {
                 if (un != u) {
-                    store_row<VEC>(P + (int64_t)u * K, lane, active, p2);
+                    flush_p(u, p2);
                     p = pn;
+                    p_at_load = pn;
                     cur_u = un;
+                } else if (shared_rows) {
+                    // publish this rating's change, go on from the re-read row plus that change
+                    // (the re-read was requested before the change was added)
+                    Row<VEC> d;
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) d.x[j] = p2.x[j] - p_at_load.x[j];
+                    atomic_add_row<VEC>(P + (int64_t)u * K, lane, active, d);
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) p.x[j] = quantise<T>(pn.x[j] + d.x[j]);
+                    p_at_load = p;
                 } else {
                     p = p2;
                 }
@@ -239,7 +315,254 @@ __global__ __launch_bounds__(kGroupThreads) void sgd_chunks(
             }
         }
     }
-    store_row<VEC>(P + (int64_t)cur_u * K, lane, active, p);
+    flush_p(cur_u, p);
+}
+
+// ------------------------------------------------------------- Hogwild with the Qt strip in LDS
+// One workgroup per block of the grid.  The block's strip of Qt (its ncols columns, contiguous
+// rows of Qt) is copied into LDS, the wavefronts of the workgroup take the block's entries
+// (chunks of whole matrix rows) from a shared counter and run the step of Algorithm 1 on them
+// -- p_u in registers, q_v read from LDS and changed with LDS atomic adds, so no update of q_v
+// is lost although the wavefronts do not lock anything -- and the strip is written back at the
+// end.  Blocks of one launch are mutually independent, so no other workgroup touches these rows
+// of P or columns of Qt meanwhile.
+// The strip is held as 32-bit fixed point with kFixedBits fraction bits (range +-2^(31-bits),
+// step 2^-bits, i.e. the fp32 spacing of values in [0.5, 1)): the LDS executes integer atomic
+// adds at the rate of plain accesses, floating-point ones some twenty times slower (measured),
+// and integer sums do not depend on the order in which the wavefronts add.
+// The columns of a strip are reused once per rating of the block (tens of times each), which is
+// what makes the staging pay; rows of P are used by one wavefront and stream through registers.
+template <typename T>
+__device__ __forceinline__ int strip_elem(int lane, int j)
+{
+    if constexpr (sizeof(T) == 2) return 2 * lane + 2 * kWave * (j >> 1) + (j & 1);
+    return lane + kWave * j;
+}
+
+constexpr int kFixedBits = 24;
+constexpr float kToFixed = (float)(1 << kFixedBits);
+constexpr float kFromFixed = 1.0f / (float)(1 << kFixedBits);
+
+__device__ __forceinline__ int to_fixed(float x)
+{
+    // saturating: factors anywhere near +-128 mean the training has already diverged
+    return __float2int_rn(fminf(fmaxf(x * kToFixed, -2147483520.f), 2147483520.f));
+}
+
+__device__ __forceinline__ float from_fixed(int x) { return (float)x * kFromFixed; }
+
+template <typename T, int VEC>
+__device__ __forceinline__ Row<VEC> strip_read(const int* qrow, int lane, bool active)
+{
+    Row<VEC> q;
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) q.x[j] = active ? from_fixed(qrow[strip_elem<T>(lane, j)]) : 0.f;
+    return q;
+}
+
+// A chunk whose rows of P belong to this wavefront alone.  Rows of P are cold (each is visited by
+// one wavefront per launch), so their latency is hidden by requesting the row of the rating DEPTH
+// positions ahead; every rating issues the same memory operations (one row request, one row
+// store, whether or not the row changes) so that the wait counters are exact.  A rating whose row
+// equals the previous rating's takes the row from registers: the request for it was issued before
+// the previous ratings of that run were applied.  Positions past the end of the batch repeat the
+// last rating with a zero step, which changes nothing.
+template <typename T, int K, int DEPTH>
+__device__ __forceinline__ void lds_owned_chunk(T* __restrict__ P, int* strip, int col0,
+                                                const int32_t* __restrict__ U,
+                                                const int32_t* __restrict__ V,
+                                                const float* __restrict__ R, int64_t begin,
+                                                int32_t len, float lr, float shrink, int lane,
+                                                bool active)
+{
+    constexpr int VEC = RowShape<T, K>::VEC;
+    Row<VEC> p_prev;
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) p_prev.x[j] = 0.f;
+    int u_prev = -1;
+    for (int32_t off = 0; off < len; off += kWave) {
+        const int cnt = min(kWave, len - off);
+        int mu = 0, mv = 0;
+        float mr = 0.f;
+        if (lane < cnt) {
+            mu = U[begin + off + lane];
+            mv = V[begin + off + lane];
+            mr = R[begin + off + lane];
+        }
+        const int last = cnt - 1;
+        Row<VEC> ring[DEPTH];
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d)
+            ring[d] = load_row<VEC, false>(P + (int64_t)uniform_lane(mu, min(d, last)) * K, lane, active);
+        int v_next = uniform_lane(mv, 0);
+        Row<VEC> q_next = strip_read<T, VEC>(strip + (v_next - col0) * K, lane, active);
+        for (int base = 0; base < cnt; base += DEPTH) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                const int i = base + d;
+                const bool valid = i < cnt;
+                const int ic = min(i, last);
+                const int u = uniform_lane(mu, ic);
+                const int v = v_next;
+                const float r = __int_as_float(uniform_lane(__float_as_int(mr), ic));
+                Row<VEC> p;
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) p.x[j] = (u == u_prev) ? p_prev.x[j] : ring[d].x[j];
+                ring[d] = load_row<VEC, false>(P + (int64_t)uniform_lane(mu, min(i + DEPTH, last)) * K, lane, active);
+                const Row<VEC> q = q_next;
+                int* const qrow = strip + (v - col0) * K;
+                v_next = uniform_lane(mv, min(i + 1, last));
+                const Row<VEC> q_ahead = strip_read<T, VEC>(strip + (v_next - col0) * K, lane, active);
+                float part = 0.f;
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) part = fmaf(p.x[j], q.x[j], part);
+                const float e = r - wave_sum(part);
+                const float step = valid ? lr * e : 0.f;
+                const float sh = valid ? shrink : 0.f;
+                Row<VEC> p2;
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    p2.x[j] = quantise<T>(fmaf(step, q.x[j], fmaf(-sh, p.x[j], p.x[j])));
+                    const int dq = to_fixed(fmaf(step, p.x[j], -sh * q.x[j]));
+                    if (active) atomicAdd(&qrow[strip_elem<T>(lane, j)], dq);
+                    // the read-ahead of the next column was taken before this add
+                    q_next.x[j] = (v_next == v) ? q.x[j] + from_fixed(dq) : q_ahead.x[j];
+                }
+                store_row<VEC>(P + (int64_t)u * K, lane, active, p2);
+                p_prev = p2;
+                u_prev = u;
+            }
+        }
+    }
+}
+
+// A chunk that is a piece of a very long row cut into pieces which run concurrently: p_u is
+// treated like q_v -- re-read for every rating and changed with atomic adds (in the L2).
+template <typename T, int K>
+__device__ __forceinline__ void lds_shared_row_chunk(T* __restrict__ P, int* strip, int col0,
+                                                     const int32_t* __restrict__ U,
+                                                     const int32_t* __restrict__ V,
+                                                     const float* __restrict__ R, int64_t begin,
+                                                     int32_t len, float lr, float shrink, int lane,
+                                                     bool active)
+{
+    constexpr int VEC = RowShape<T, K>::VEC;
+    for (int32_t off = 0; off < len; off += kWave) {
+        const int cnt = min(kWave, len - off);
+        int mu = 0, mv = 0;
+        float mr = 0.f;
+        if (lane < cnt) {
+            mu = U[begin + off + lane];
+            mv = V[begin + off + lane];
+            mr = R[begin + off + lane];
+        }
+        Row<VEC> pn = load_row<VEC, true>(P + (int64_t)uniform_lane(mu, 0) * K, lane, active);
+        for (int i = 0; i < cnt; ++i) {
+            const int u = uniform_lane(mu, i);
+            const int v = uniform_lane(mv, i);
+            const float r = __int_as_float(uniform_lane(__float_as_int(mr), i));
+            const Row<VEC> p = pn;
+            pn = load_row<VEC, true>(P + (int64_t)uniform_lane(mu, min(i + 1, cnt - 1)) * K, lane, active);
+            int* const qrow = strip + (v - col0) * K;
+            const Row<VEC> q = strip_read<T, VEC>(qrow, lane, active);
+            float part = 0.f;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) part = fmaf(p.x[j], q.x[j], part);
+            const float e = r - wave_sum(part);
+            const float step = lr * e;
+            Row<VEC> dp;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                dp.x[j] = fmaf(step, q.x[j], -shrink * p.x[j]);
+                const int dq = to_fixed(fmaf(step, p.x[j], -shrink * q.x[j]));
+                if (active) atomicAdd(&qrow[strip_elem<T>(lane, j)], dq);
+            }
+            atomic_add_row<VEC>(P + (int64_t)u * K, lane, active, dp);
+            // the re-read of p_u was requested before this change was added
+            if (i + 1 < cnt && uniform_lane(mu, i + 1) == u) {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) pn.x[j] += dp.x[j];
+            }
+        }
+    }
+}
+
+constexpr int kLdsPrefetchDepth = 8;
+
+template <typename T, int K>
+__global__ __launch_bounds__(1024) void sgd_block_lds(
+    T* __restrict__ P, T* __restrict__ Qt, const int32_t* __restrict__ U,
+    const int32_t* __restrict__ V, const float* __restrict__ R,
+    const int64_t* __restrict__ entry_begin, const int32_t* __restrict__ entry_len,
+    const LdsBlock* __restrict__ blocks, float lr, float lambda)
+{
+    extern __shared__ int strip[];            // ncols * K fixed-point values
+    __shared__ unsigned next_entry;
+    const int lane = threadIdx.x & (kWave - 1);
+    const bool active = lane < RowShape<T, K>::ACTIVE;
+    const LdsBlock blk = blocks[blockIdx.x];
+    const int total = blk.ncols * K;          // multiple of 32
+    T* const strip_src = Qt + (int64_t)blk.col0 * K;
+    const int stride = 4 * (int)blockDim.x;
+
+    if (threadIdx.x == 0) next_entry = 0;
+    for (int i0 = 4 * (int)threadIdx.x; i0 < total; i0 += 4 * stride) {
+        float4 val[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int i = i0 + t * stride;
+            if (i < total) {
+                if constexpr (sizeof(T) == 2) {
+                    uint2 raw = *reinterpret_cast<const uint2*>(strip_src + i);
+                    float2 a = unpack_half2(raw.x), b = unpack_half2(raw.y);
+                    val[t] = make_float4(a.x, a.y, b.x, b.y);
+                } else {
+                    val[t] = *reinterpret_cast<const float4*>(strip_src + i);
+                }
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int i = i0 + t * stride;
+            if (i < total)
+                *reinterpret_cast<int4*>(strip + i) =
+                    make_int4(to_fixed(val[t].x), to_fixed(val[t].y), to_fixed(val[t].z), to_fixed(val[t].w));
+        }
+    }
+    __syncthreads();
+
+    const float shrink = lr * lambda;
+    for (;;) {
+        unsigned taken = 0;
+        if (lane == 0) taken = atomicAdd(&next_entry, 1u);
+        taken = __builtin_amdgcn_readfirstlane(taken);
+        if (taken >= (unsigned)blk.n_entries) break;
+        const int64_t entry = blk.first_entry + taken;
+        const int32_t raw_len = entry_len[entry];
+        const int32_t len = raw_len & ~kSharedRowFlag;
+        const int64_t begin = entry_begin[entry];
+        if (raw_len < 0)
+            lds_shared_row_chunk<T, K>(P, strip, blk.col0, U, V, R, begin, len, lr, shrink, lane, active);
+        else
+            lds_owned_chunk<T, K, kLdsPrefetchDepth>(P, strip, blk.col0, U, V, R, begin, len, lr, shrink, lane,
+                                                     active);
+    }
+    __syncthreads();
+
+    for (int i = 4 * (int)threadIdx.x; i < total; i += stride) {
+        const int4 raw4 = *reinterpret_cast<const int4*>(strip + i);
+        const float4 val = make_float4(from_fixed(raw4.x), from_fixed(raw4.y), from_fixed(raw4.z), from_fixed(raw4.w));
+        if constexpr (sizeof(T) == 2) {
+            __half2 a = __halves2half2(round_to_half(val.x), round_to_half(val.y));
+            __half2 b = __halves2half2(round_to_half(val.z), round_to_half(val.w));
+            uint2 raw;
+            raw.x = *reinterpret_cast<unsigned*>(&a);
+            raw.y = *reinterpret_cast<unsigned*>(&b);
+            *reinterpret_cast<uint2*>(strip_src + i) = raw;
+        } else {
+            *reinterpret_cast<float4*>(strip_src + i) = val;
+        }
+    }
 }
 
 // ------------------------------------------------------------------------------------- RMSE
@@ -258,12 +581,12 @@ __global__ __launch_bounds__(kGroupThreads) void rmse_partial(
     const int32_t* __restrict__ V, const float* __restrict__ R, int64_t count,
     double* __restrict__ partials)
 {
-    constexpr int VEC = RowShape<K>::VEC;
+    constexpr int VEC = RowShape<T, K>::VEC;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t wave_id = (int64_t)blockIdx.x * kWavesPerGroup + wave;
     const int64_t n_waves = (int64_t)gridDim.x * kWavesPerGroup;
-    const bool active = lane < RowShape<K>::ACTIVE;
+    const bool active = lane < RowShape<T, K>::ACTIVE;
     double acc = 0.0;
     for (int64_t base = wave_id * kWave; base < count; base += n_waves * kWave) {
         const int cnt = (int)min((int64_t)kWave, count - base);
@@ -278,8 +601,8 @@ __global__ __launch_bounds__(kGroupThreads) void rmse_partial(
             const int u = uniform_lane(mu, i);
             const int v = uniform_lane(mv, i);
             const float r = __int_as_float(uniform_lane(__float_as_int(mr), i));
-            Row<VEC> p = load_row<VEC>(P + (int64_t)u * K, lane, active);
-            Row<VEC> q = load_row<VEC>(Qt + (int64_t)v * K, lane, active);
+            Row<VEC> p = load_row<VEC, false>(P + (int64_t)u * K, lane, active);
+            Row<VEC> q = load_row<VEC, false>(Qt + (int64_t)v * K, lane, active);
             double part = 0.0;
 #pragma unroll
             for (int j = 0; j < VEC; ++j) part = fma((double)p.x[j], (double)q.x[j], part);
@@ -325,7 +648,7 @@ __global__ __launch_bounds__(kGroupThreads) void init_fill(T* __restrict__ X, in
         const uint64_t h = mix64(key + (uint64_t)i);
         const float u01 = (float)(uint32_t)(h >> 40) * (1.0f / 16777216.0f);
         const float val = u01 * scale;
-        if constexpr (sizeof(T) == 2) X[i] = __float2half_rn(val);
+        if constexpr (sizeof(T) == 2) X[i] = round_to_half(val);
         else X[i] = val;
     }
 }
@@ -338,13 +661,39 @@ __global__ void xcc_probe(int32_t* out)
 }
 
 template <typename T, int K>
-hipError_t launch_sgd_t(void* P, void* Qt, const int32_t* U, const int32_t* V, const float* R,
-                        const int64_t* eb, const int32_t* el, int64_t first, int64_t n_entries,
-                        float lr, float lambda, hipStream_t stream)
+hipError_t launch_sgd_t(bool hogwild, void* P, void* Qt, const int32_t* U, const int32_t* V,
+                        const float* R, const int64_t* eb, const int32_t* el, int64_t first,
+                        int64_t n_entries, float lr, float lambda, hipStream_t stream)
 {
     const unsigned groups = (unsigned)(n_entries / kWavesPerGroup);
-    hipLaunchKernelGGL((sgd_chunks<T, K>), dim3(groups), dim3(kGroupThreads), 0, stream, (T*)P, (T*)Qt, U,
-                       V, R, eb, el, first, lr, lambda);
+    if (hogwild)
+        hipLaunchKernelGGL((sgd_chunks<T, K, true>), dim3(groups), dim3(kGroupThreads), 0, stream, (T*)P,
+                           (T*)Qt, U, V, R, eb, el, first, lr, lambda);
+    else
+        hipLaunchKernelGGL((sgd_chunks<T, K, false>), dim3(groups), dim3(kGroupThreads), 0, stream, (T*)P,
+                           (T*)Qt, U, V, R, eb, el, first, lr, lambda);
+    return hipGetLastError();
+}
+
+template <typename T, int K>
+hipError_t launch_sgd_lds_t(int waves, void* P, void* Qt, const int32_t* U, const int32_t* V,
+                            const float* R, const int64_t* eb, const int32_t* el,
+                            const LdsBlock* blocks, int64_t n_blocks, size_t lds_bytes, float lr,
+                            float lambda, hipStream_t stream)
+{
+    // more than 64 KiB of dynamic LDS has to be allowed once per kernel and device
+    static bool raised[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64 && !raised[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sgd_block_lds<T, K>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
+        if (e != hipSuccess) return e;
+        raised[dev] = true;
+    }
+    hipLaunchKernelGGL((sgd_block_lds<T, K>), dim3((unsigned)n_blocks), dim3(waves * kWave), lds_bytes,
+                       stream, (T*)P, (T*)Qt, U, V, R, eb, el, blocks, lr, lambda);
     return hipGetLastError();
 }
 
@@ -384,15 +733,28 @@ hipError_t launch_rmse_t(const void* P, const void* Qt, const int32_t* U, const 
         return hipErrorInvalidValue;                                             \
     } while (0)
 
-hipError_t launch_sgd(int dtype, int k, void* P, void* Qt, const int32_t* U, const int32_t* V,
-                      const float* R, const int64_t* entry_begin, const int32_t* entry_len,
-                      int64_t first_entry, int64_t n_entries, float lr, float lambda,
-                      hipStream_t stream)
+hipError_t launch_sgd(int dtype, int k, bool hogwild, void* P, void* Qt, const int32_t* U,
+                      const int32_t* V, const float* R, const int64_t* entry_begin,
+                      const int32_t* entry_len, int64_t first_entry, int64_t n_entries, float lr,
+                      float lambda, hipStream_t stream)
 {
     if (n_entries <= 0) return hipSuccess;
     if (n_entries % kWavesPerGroup) return hipErrorInvalidValue;
-    MF_DISPATCH(launch_sgd_t, P, Qt, U, V, R, entry_begin, entry_len, first_entry, n_entries, lr,
+    MF_DISPATCH(launch_sgd_t, hogwild, P, Qt, U, V, R, entry_begin, entry_len, first_entry, n_entries, lr,
                 lambda, stream);
+}
+
+size_t lds_strip_bytes(int k, int32_t max_cols) { return (size_t)max_cols * k * sizeof(float); }
+
+hipError_t launch_sgd_lds(int dtype, int k, int waves, void* P, void* Qt, const int32_t* U,
+                          const int32_t* V, const float* R, const int64_t* entry_begin,
+                          const int32_t* entry_len, const LdsBlock* blocks, int64_t n_blocks,
+                          size_t lds_bytes, float lr, float lambda, hipStream_t stream)
+{
+    if (n_blocks <= 0) return hipSuccess;
+    if (waves < 1 || waves > 16 || lds_bytes > kLdsBudget) return hipErrorInvalidValue;
+    MF_DISPATCH(launch_sgd_lds_t, waves, P, Qt, U, V, R, entry_begin, entry_len, blocks, n_blocks,
+                lds_bytes, lr, lambda, stream);
 }
 
 hipError_t launch_rmse(int dtype, int k, const void* P, const void* Qt, const int32_t* U,

@@ -29,6 +29,7 @@ struct mf_ctx {
     bool loaded = false;
     mf::Partition part;
     mf::Schedule sched[2];   // indexed by MF_MODE_*
+    mf::LdsSchedule lds;     // Hogwild with the Qt strip in LDS
     int32_t* dU = nullptr;
     int32_t* dV = nullptr;
     float* dR = nullptr;
@@ -37,6 +38,9 @@ struct mf_ctx {
     int32_t hogwild_chunk = 128;
     int32_t xcd_affinity = 1;
     int32_t profile = 0;
+    int32_t hogwild_kernel = MF_HOGWILD_AUTO;
+    int32_t lds_chunk = 32;
+    int32_t lds_waves = 16;
 
     // library-owned device buffer: RMSE partials followed by the final sum
     double* d_partials = nullptr;
@@ -70,15 +74,17 @@ size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 bool valid_k(int32_t k) { return k == 32 || k == 64 || k == 128 || k == 256; }
 
 struct Layout {
-    size_t off_u, off_v, off_r, off_begin[2], off_len[2], total;
-    int64_t cap[2];
+    size_t off_u, off_v, off_r, off_begin[2], off_len[2], off_lds_begin, off_lds_len, off_lds_blocks, total;
+    int64_t cap[2], lds_cap, lds_blocks_cap;
 };
 
-Layout make_layout(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk)
+Layout make_layout(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t lds_chunk)
 {
     Layout l;
     l.cap[MF_MODE_DET] = mf::det_entries_bound(gr, gc);
     l.cap[MF_MODE_HOGWILD] = mf::hogwild_entries_bound(nnz, gr, gc, chunk);
+    l.lds_cap = mf::lds_entries_bound(nnz, gr, gc, lds_chunk);
+    l.lds_blocks_cap = (int64_t)gr * gc;
     size_t off = 0;
     l.off_u = off; off += align_up((size_t)nnz * 4);
     l.off_v = off; off += align_up((size_t)nnz * 4);
@@ -87,6 +93,9 @@ Layout make_layout(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk)
         l.off_begin[mode] = off; off += align_up((size_t)l.cap[mode] * 8);
         l.off_len[mode] = off; off += align_up((size_t)l.cap[mode] * 4);
     }
+    l.off_lds_begin = off; off += align_up((size_t)l.lds_cap * 8);
+    l.off_lds_len = off; off += align_up((size_t)l.lds_cap * 4);
+    l.off_lds_blocks = off; off += align_up((size_t)l.lds_blocks_cap * sizeof(mf::LdsBlock));
     l.total = off;
     return l;
 }
@@ -152,6 +161,18 @@ int mf_set_option(mf_ctx* ctx, int32_t option, int64_t value)
         case MF_OPT_PROFILE:
             ctx->profile = value ? 1 : 0;
             return MF_OK;
+        case MF_OPT_HOGWILD_KERNEL:
+            if (value < MF_HOGWILD_AUTO || value > MF_HOGWILD_LDS) return fail(ctx, MF_EINVAL, "unknown Hogwild kernel");
+            ctx->hogwild_kernel = (int32_t)value;
+            return MF_OK;
+        case MF_OPT_LDS_CHUNK:
+            if (value < 1 || value > (1 << 20)) return fail(ctx, MF_EINVAL, "chunk must be in [1, 2^20]");
+            ctx->lds_chunk = (int32_t)value;
+            return MF_OK;
+        case MF_OPT_LDS_WAVES:
+            if (value < 1 || value > 16) return fail(ctx, MF_EINVAL, "wavefronts per workgroup must be in [1, 16]");
+            ctx->lds_waves = (int32_t)value;
+            return MF_OK;
     }
     return fail(ctx, MF_EINVAL, "unknown option");
 }
@@ -190,7 +211,7 @@ int mf_load_blocks_workspace(const mf_ctx* ctx, int64_t nnz, int32_t grid_r, int
     if (!ctx || !bytes_out) return MF_EINVAL;
     int rc = check_grid(const_cast<mf_ctx*>(ctx), nnz, grid_r, grid_c);
     if (rc) return rc;
-    *bytes_out = make_layout(nnz, grid_r, grid_c, ctx->hogwild_chunk).total;
+    *bytes_out = make_layout(nnz, grid_r, grid_c, ctx->hogwild_chunk, ctx->lds_chunk).total;
     return MF_OK;
 }
 
@@ -207,7 +228,7 @@ int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const 
     if (nnz > 0 && (!rows || !cols || !vals)) return fail(ctx, MF_EINVAL, "null rating array");
     if (!d_workspace) return fail(ctx, MF_EINVAL, "null workspace");
     if ((uintptr_t)d_workspace & 255) return fail(ctx, MF_EINVAL, "workspace must be 256-byte aligned");
-    const Layout lay = make_layout(nnz, grid_r, grid_c, ctx->hogwild_chunk);
+    const Layout lay = make_layout(nnz, grid_r, grid_c, ctx->hogwild_chunk, ctx->lds_chunk);
     if (workspace_bytes < lay.total) return fail(ctx, MF_ENOMEM, "workspace too small");
     MF_HIP(ctx, hipSetDevice(ctx->device));
     ctx->loaded = false;
@@ -222,6 +243,7 @@ int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const 
         mf::build_det_schedule(ctx->part, ctx->xcd_affinity != 0, ctx->sched[MF_MODE_DET]);
         mf::build_hogwild_schedule(ctx->part, pu, ctx->hogwild_chunk, ctx->xcd_affinity != 0,
                                    ctx->sched[MF_MODE_HOGWILD]);
+        mf::build_lds_schedule(ctx->part, pu, ctx->lds_chunk, ctx->lds);
     } catch (const std::bad_alloc&) {
         return fail(ctx, MF_ENOMEM, "host allocation failed while partitioning");
     }
@@ -246,6 +268,20 @@ int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const 
         if (!s.begin.empty()) {
             MF_HIP(ctx, hipMemcpy(s.d_begin, s.begin.data(), s.begin.size() * 8, hipMemcpyHostToDevice));
             MF_HIP(ctx, hipMemcpy(s.d_len, s.len.data(), s.len.size() * 4, hipMemcpyHostToDevice));
+        }
+    }
+    {
+        mf::LdsSchedule& l = ctx->lds;
+        if ((int64_t)l.begin.size() > lay.lds_cap || (int64_t)l.blocks.size() > lay.lds_blocks_cap)
+            return fail(ctx, MF_ENOMEM, "schedule larger than its workspace bound");
+        l.d_begin = (int64_t*)(base + lay.off_lds_begin);
+        l.d_len = (int32_t*)(base + lay.off_lds_len);
+        l.d_blocks = (mf::LdsBlock*)(base + lay.off_lds_blocks);
+        if (!l.begin.empty()) {
+            MF_HIP(ctx, hipMemcpy(l.d_begin, l.begin.data(), l.begin.size() * 8, hipMemcpyHostToDevice));
+            MF_HIP(ctx, hipMemcpy(l.d_len, l.len.data(), l.len.size() * 4, hipMemcpyHostToDevice));
+            MF_HIP(ctx, hipMemcpy(l.d_blocks, l.blocks.data(), l.blocks.size() * sizeof(mf::LdsBlock),
+                                  hipMemcpyHostToDevice));
         }
     }
     ctx->loaded = true;
@@ -273,9 +309,23 @@ int mf_sgd_epoch(mf_ctx* ctx, float lr, float lambda, int32_t mode)
     if (!(lr == lr) || !(lambda == lambda)) return fail(ctx, MF_EINVAL, "lr or lambda is NaN");
     MF_HIP(ctx, hipSetDevice(ctx->device));
     const mf::Schedule& s = ctx->sched[mode];
+    // Hogwild: the kernel that keeps the block's strip of Qt in LDS whenever the widest strip fits
+    const size_t lds_bytes = mf::lds_strip_bytes(ctx->k, ctx->lds.max_cols);
+    bool use_lds = false;
+    if (mode == MF_MODE_HOGWILD && ctx->hogwild_kernel != MF_HOGWILD_GLOBAL_ATOMICS) {
+        use_lds = lds_bytes <= mf::kLdsBudget;
+        if (!use_lds && ctx->hogwild_kernel == MF_HOGWILD_LDS)
+            return fail(ctx, MF_EINVAL, "the widest column strip of this grid does not fit the LDS");
+    }
     for (int32_t st = 0; st < ctx->part.gc; ++st) {
-        const int64_t first = s.stratum_entry[st];
-        const int64_t count = s.stratum_entry[st + 1] - first;
+        int64_t first, count;
+        if (use_lds) {
+            first = ctx->lds.stratum_block[st];
+            count = ctx->lds.stratum_block[st + 1] - first;
+        } else {
+            first = s.stratum_entry[st];
+            count = s.stratum_entry[st + 1] - first;
+        }
         if (count == 0) continue;
         hipEvent_t ev0 = nullptr, ev1 = nullptr;
         if (ctx->profile) {
@@ -289,8 +339,15 @@ int mf_sgd_epoch(mf_ctx* ctx, float lr, float lambda, int32_t mode)
             ctx->events_used += 1;
             MF_HIP(ctx, hipEventRecord(ev0, ctx->stream));
         }
-        MF_HIP(ctx, mf::launch_sgd(ctx->dtype, ctx->k, ctx->dP, ctx->dQt, ctx->dU, ctx->dV, ctx->dR,
-                                   s.d_begin, s.d_len, first, count, lr, lambda, ctx->stream));
+        if (use_lds)
+            MF_HIP(ctx, mf::launch_sgd_lds(ctx->dtype, ctx->k, ctx->lds_waves, ctx->dP, ctx->dQt, ctx->dU,
+                                           ctx->dV, ctx->dR, ctx->lds.d_begin, ctx->lds.d_len,
+                                           ctx->lds.d_blocks + first, count, lds_bytes, lr, lambda,
+                                           ctx->stream));
+        else
+            MF_HIP(ctx, mf::launch_sgd(ctx->dtype, ctx->k, mode == MF_MODE_HOGWILD, ctx->dP, ctx->dQt, ctx->dU,
+                                       ctx->dV, ctx->dR, s.d_begin, s.d_len, first, count, lr, lambda,
+                                       ctx->stream));
         if (ctx->profile) MF_HIP(ctx, hipEventRecord(ev1, ctx->stream));
     }
     return MF_OK;
@@ -371,7 +428,7 @@ int mf_plan_host(const int32_t* rows, const int32_t* cols, int64_t nnz, int64_t 
     if (check_grid(nullptr, nnz, grid_r, grid_c)) return MF_EINVAL;
     if (m < 1 || n < 1 || grid_r > m || grid_c > n) return MF_EINVAL;
     if (split != MF_SPLIT_EQUAL_WIDTH && split != MF_SPLIT_NNZ_BALANCED) return MF_EINVAL;
-    if (mode != MF_MODE_DET && mode != MF_MODE_HOGWILD) return MF_EINVAL;
+    if (mode != MF_MODE_DET && mode != MF_MODE_HOGWILD && mode != MF_PLAN_HOGWILD_LDS) return MF_EINVAL;
     if (chunk < 1 || (nnz > 0 && (!rows || !cols))) return MF_EINVAL;
     try {
         mf::Partition part;
@@ -381,10 +438,24 @@ int mf_plan_host(const int32_t* rows, const int32_t* cols, int64_t nnz, int64_t 
         int rc = mf::build_partition(rows, cols, vals.data(), nnz, m, n, grid_r, grid_c, split, part, pu, pv, pr, err);
         if (rc) return rc;
         mf::Schedule s;
-        if (mode == MF_MODE_DET) mf::build_det_schedule(part, xcd_affinity != 0, s);
-        else mf::build_hogwild_schedule(part, pu, chunk, xcd_affinity != 0, s);
-        const int64_t bound = mode == MF_MODE_DET ? mf::det_entries_bound(grid_r, grid_c)
-                                                  : mf::hogwild_entries_bound(nnz, grid_r, grid_c, chunk);
+        int64_t bound;
+        if (mode == MF_MODE_DET) {
+            mf::build_det_schedule(part, xcd_affinity != 0, s);
+            bound = mf::det_entries_bound(grid_r, grid_c);
+        } else if (mode == MF_MODE_HOGWILD) {
+            mf::build_hogwild_schedule(part, pu, chunk, xcd_affinity != 0, s);
+            bound = mf::hogwild_entries_bound(nnz, grid_r, grid_c, chunk);
+        } else {
+            mf::LdsSchedule l;
+            mf::build_lds_schedule(part, pu, chunk, l);
+            bound = mf::lds_entries_bound(nnz, grid_r, grid_c, chunk);
+            s.begin = l.begin;
+            s.len = l.len;
+            s.stratum_entry.assign((size_t)grid_c + 1, (int64_t)l.begin.size());
+            for (int32_t st = 0; st < grid_c; ++st)   // first entry of the first block of the stratum
+                if (l.stratum_block[st] < (int64_t)l.blocks.size())
+                    s.stratum_entry[st] = l.blocks[(size_t)l.stratum_block[st]].first_entry;
+        }
         if ((int64_t)s.begin.size() > bound) return MF_ENOMEM;
         if (perm && nnz > 0) std::memcpy(perm, part.perm.data(), (size_t)nnz * 8);
         if (block_ptr) std::memcpy(block_ptr, part.block_ptr.data(), part.block_ptr.size() * 8);

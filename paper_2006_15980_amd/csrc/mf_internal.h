@@ -20,10 +20,33 @@ constexpr int kRmsePartials = kRmseGroups * kWavesPerGroup;
 // One unit of work of a wavefront: `len` consecutive ratings of the packed order from `begin`.
 struct Schedule {
     std::vector<int64_t> begin;          // per entry
-    std::vector<int32_t> len;            // per entry (0 = padding, the wavefront exits at once)
+    std::vector<int32_t> len;            // per entry (0 = padding, the wavefront exits at once);
+                                         // sign bit set = the entry shares a row of P with others
     std::vector<int64_t> stratum_entry;  // first entry of stratum s (size G_c + 1)
     int64_t* d_begin = nullptr;          // device copies inside the caller's workspace
     int32_t* d_len = nullptr;
+};
+
+// Work of one workgroup of the LDS-resident Hogwild kernel: one block of the grid.  The block's
+// strip of Qt (columns col0 .. col0+ncols) is held in LDS while the wavefronts of the workgroup
+// take the block's entries (chunks of whole rows) one after another.
+struct LdsBlock {
+    int64_t first_entry;
+    int32_t n_entries;
+    int32_t col0;
+    int32_t ncols;
+    int32_t reserved;
+};
+
+struct LdsSchedule {
+    std::vector<int64_t> begin;          // per entry, block after block (no padding)
+    std::vector<int32_t> len;            // per entry; sign bit = shares its row of P
+    std::vector<LdsBlock> blocks;        // non-empty blocks, stratum after stratum
+    std::vector<int64_t> stratum_block;  // first block of stratum s (size G_c + 1)
+    int32_t max_cols = 0;                // widest column strip of the grid
+    int64_t* d_begin = nullptr;
+    int32_t* d_len = nullptr;
+    LdsBlock* d_blocks = nullptr;
 };
 
 // Host partition of R into the block grid.
@@ -46,15 +69,25 @@ int build_partition(const int32_t* rows, const int32_t* cols, const float* vals,
 void build_det_schedule(const Partition& part, bool xcd_affinity, Schedule& out);
 void build_hogwild_schedule(const Partition& part, const std::vector<int32_t>& pu, int32_t chunk,
                             bool xcd_affinity, Schedule& out);
+void build_lds_schedule(const Partition& part, const std::vector<int32_t>& pu, int32_t chunk,
+                        LdsSchedule& out);
 // Upper bounds on the number of schedule entries, usable before the partition is known.
+int64_t lds_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk);
 int64_t det_entries_bound(int32_t gr, int32_t gc);
 int64_t hogwild_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk);
 
 // kernels.hip ---------------------------------------------------------------------------------
-hipError_t launch_sgd(int dtype, int k, void* P, void* Qt, const int32_t* U, const int32_t* V,
-                      const float* R, const int64_t* entry_begin, const int32_t* entry_len,
-                      int64_t first_entry, int64_t n_entries, float lr, float lambda,
-                      hipStream_t stream);
+hipError_t launch_sgd(int dtype, int k, bool hogwild, void* P, void* Qt, const int32_t* U,
+                      const int32_t* V, const float* R, const int64_t* entry_begin,
+                      const int32_t* entry_len, int64_t first_entry, int64_t n_entries, float lr,
+                      float lambda, hipStream_t stream);
+// LDS-resident Hogwild kernel: one workgroup of `waves` wavefronts per block descriptor.
+hipError_t launch_sgd_lds(int dtype, int k, int waves, void* P, void* Qt, const int32_t* U,
+                          const int32_t* V, const float* R, const int64_t* entry_begin,
+                          const int32_t* entry_len, const LdsBlock* blocks, int64_t n_blocks,
+                          size_t lds_bytes, float lr, float lambda, hipStream_t stream);
+size_t lds_strip_bytes(int k, int32_t max_cols);   // dynamic LDS the kernel needs for a grid
+constexpr size_t kLdsBudget = 160 * 1024 - 1024;   // LDS of one gfx950 compute unit, minus static use
 hipError_t launch_init(int dtype, void* X, int64_t count, uint64_t seed, uint64_t stream_id,
                        float scale, hipStream_t stream);
 hipError_t launch_rmse(int dtype, int k, const void* P, const void* Qt, const int32_t* U,

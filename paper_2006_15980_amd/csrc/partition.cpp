@@ -265,45 +265,86 @@ void build_det_schedule(const Partition& part, bool xcd_affinity, Schedule& out)
     }
 }
 
+// Cut the packed range [pos, end) of one block into chunks of whole matrix rows of about `chunk`
+// ratings; a row longer than 2*chunk is cut into pieces of `chunk`, each flagged (sign bit of
+// the length) as sharing its row of P with other entries.  emit(begin, length_with_flag).
+template <class Emit>
+static void chunk_block(const std::vector<int32_t>& pu, int64_t pos, int64_t end, int32_t chunk, Emit emit_raw)
+{
+    const int32_t long_row = 2 * chunk;
+    auto emit = [&](int64_t b, int64_t e, bool shares_row) {
+        if (e <= b) return;
+        int32_t len = (int32_t)(e - b);
+        if (shares_row) len |= (int32_t)0x80000000;
+        emit_raw(b, len);
+    };
+    int64_t cur = pos;   // start of the chunk being filled with whole rows
+    while (pos < end) {
+        int64_t row_end = pos + 1;
+        while (row_end < end && pu[row_end] == pu[pos]) ++row_end;
+        if (row_end - pos > long_row) {
+            emit(cur, pos, false);
+            for (int64_t b = pos; b < row_end; b += chunk) emit(b, std::min<int64_t>(b + chunk, row_end), true);
+            cur = row_end;
+        } else if (pos > cur && (row_end - cur) > chunk) {
+            emit(cur, pos, false);
+            cur = pos;
+        }
+        pos = row_end;
+    }
+    emit(cur, end, false);
+}
+
 void build_hogwild_schedule(const Partition& part, const std::vector<int32_t>& pu, int32_t chunk,
                             bool xcd_affinity, Schedule& out)
 {
     out.begin.clear();
     out.len.clear();
     out.stratum_entry.assign((size_t)part.gc + 1, 0);
-    const int32_t long_row = 2 * chunk;   // rows longer than this are cut into pieces of `chunk`
     std::vector<std::vector<std::pair<int64_t, int32_t>>> per_die((size_t)kXcds);
     int64_t spread = 0;
     for (int32_t s = 0; s < part.gc; ++s) {
         for (auto& l : per_die) l.clear();
         for (int32_t a = 0; a < part.gr; ++a) {
             int64_t L = (int64_t)s * part.gr + a;
-            int64_t pos = part.block_ptr[L];
-            const int64_t end = part.block_ptr[L + 1];
-            auto emit = [&](int64_t b, int64_t e) {
-                if (e <= b) return;
+            chunk_block(pu, part.block_ptr[L], part.block_ptr[L + 1], chunk, [&](int64_t b, int32_t len) {
                 int die = xcd_affinity ? a % kXcds : (int)(spread++ % kXcds);
-                per_die[die].push_back({b, (int32_t)(e - b)});
-            };
-            int64_t cur = pos;   // start of the chunk being filled with whole rows
-            while (pos < end) {
-                int64_t row_end = pos + 1;
-                while (row_end < end && pu[row_end] == pu[pos]) ++row_end;
-                int64_t row_len = row_end - pos;
-                if (row_len > long_row) {
-                    emit(cur, pos);
-                    for (int64_t b = pos; b < row_end; b += chunk) emit(b, std::min<int64_t>(b + chunk, row_end));
-                    cur = row_end;
-                } else if (pos > cur && (row_end - cur) > chunk) {
-                    emit(cur, pos);
-                    cur = pos;
-                }
-                pos = row_end;
-            }
-            emit(cur, end);
+                per_die[die].push_back({b, len});
+            });
         }
         lay_out_stratum(per_die, xcd_affinity, out);
         out.stratum_entry[(size_t)s + 1] = (int64_t)out.begin.size();
+    }
+}
+
+void build_lds_schedule(const Partition& part, const std::vector<int32_t>& pu, int32_t chunk,
+                        LdsSchedule& out)
+{
+    out.begin.clear();
+    out.len.clear();
+    out.blocks.clear();
+    out.stratum_block.assign((size_t)part.gc + 1, 0);
+    out.max_cols = 0;
+    for (int32_t b = 0; b < part.gc; ++b)
+        out.max_cols = std::max(out.max_cols, part.col_bounds[b + 1] - part.col_bounds[b]);
+    for (int32_t s = 0; s < part.gc; ++s) {
+        for (int32_t a = 0; a < part.gr; ++a) {
+            int64_t L = (int64_t)s * part.gr + a;
+            if (part.block_ptr[L + 1] == part.block_ptr[L]) continue;
+            int32_t b = (a + s) % part.gc;
+            LdsBlock blk;
+            blk.first_entry = (int64_t)out.begin.size();
+            blk.col0 = part.col_bounds[b];
+            blk.ncols = part.col_bounds[b + 1] - part.col_bounds[b];
+            blk.reserved = 0;
+            chunk_block(pu, part.block_ptr[L], part.block_ptr[L + 1], chunk, [&](int64_t pos, int32_t len) {
+                out.begin.push_back(pos);
+                out.len.push_back(len);
+            });
+            blk.n_entries = (int32_t)((int64_t)out.begin.size() - blk.first_entry);
+            out.blocks.push_back(blk);
+        }
+        out.stratum_block[(size_t)s + 1] = (int64_t)out.blocks.size();
     }
 }
 
@@ -323,6 +364,11 @@ int64_t hogwild_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk
     // 2*len/chunk).  Padding can multiply one die's list by kXcds in the worst case.
     int64_t chunks = 4 * (nnz / chunk + 1) + 2 * (int64_t)gr * gc;
     return chunks * kXcds + (int64_t)gc * kXcds * kWavesPerGroup;
+}
+
+int64_t lds_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk)
+{
+    return 4 * (nnz / chunk + 1) + 2 * (int64_t)gr * gc;   // as above, without padding
 }
 
 }  // namespace mf

@@ -204,14 +204,85 @@ def test_tiny_config_det_final_rmse_within_1e3(mfmod):
     assert abs(got - want) <= 1e-3, (got, want)
 
 
-@pytest.mark.parametrize("affinity", [1, 0])
-def test_tiny_config_hogwild_final_rmse_within_half_percent(mfmod, affinity):
+@pytest.mark.parametrize("kernel", ["lds", "global_atomics"])
+@pytest.mark.parametrize("storage", ["f32", "f16"])
+def test_tiny_config_hogwild_final_rmse_within_half_percent(mfmod, kernel, storage):
+    ds = dataset("tiny")
+    Po, Qo, _ = oracle_train(ds, 8, 8, 1, ds.cfg.epochs, arith=_arith(storage))
+    want = oracle.rmse(Po, Qo, ds.test_rows, ds.test_cols, ds.test_vals)
+    which = mfmod.MF_HOGWILD_LDS if kernel == "lds" else mfmod.MF_HOGWILD_GLOBAL_ATOMICS
+    got = _train_gpu(mfmod, ds, ds.cfg.k, storage, 8, 8, 1, mfmod.MF_MODE_HOGWILD, ds.cfg.epochs,
+                     options={mfmod.MF_OPT_HOGWILD_CHUNK: 32, mfmod.MF_OPT_LDS_CHUNK: 16,
+                              mfmod.MF_OPT_HOGWILD_KERNEL: which})
+    print("tiny HOGWILD %s %s: rmse gpu %.6f oracle %.6f" % (kernel, storage, got, want), flush=True)
+    assert abs(got - want) <= 0.005 * want, (got, want)
+
+
+@pytest.mark.parametrize("k,storage", [(32, "f32"), (64, "f16"), (256, "f32"), (256, "f16")])
+def test_hogwild_lds_kernel_other_shapes_and_long_rows(mfmod, k, storage):
+    """LDS kernel on a matrix with two very long rows (cut into pieces that share p_u) and a
+    ragged strip width; checked against the oracle's held-out RMSE once both have converged."""
+    rng = np.random.default_rng(17)
+    m, n, nnz = 600, 333, 60000
+    rows = rng.integers(0, m, nnz).astype(np.int32)
+    rows[:3000] = 5
+    rows[3000:5000] = 77
+    cols = rng.integers(0, n, nnz).astype(np.int32)
+    ps = rng.uniform(0.2, 1.0, (m, 4))
+    qs = rng.uniform(0.2, 1.0, (n, 4))
+    vals = (np.einsum("ij,ij->i", ps[rows], qs[cols]) + rng.normal(0, 0.05, nnz)).astype(np.float32)
+    hold = rng.random(nnz) < 0.1
+    tr_r, tr_c, tr_v = (np.ascontiguousarray(x[~hold]) for x in (rows, cols, vals))
+    te_r, te_c, te_v = (np.ascontiguousarray(x[hold]) for x in (rows, cols, vals))
+    gr, gc, epochs, lr, lam = 3, 5, 40, 0.01, 0.02
+    model = mfmod.MatrixFactorization(m, n, k, storage, seed=3, scale=0.1,
+                                      options={mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS,
+                                               mfmod.MF_OPT_LDS_CHUNK: 24, mfmod.MF_OPT_LDS_WAVES: 8})
+    model.load_blocks(tr_r, tr_c, tr_v, gr, gc, 1)
+    for _ in range(epochs):
+        model.sgd_epoch(lr, lam, mfmod.MF_MODE_HOGWILD)
+    a, b, c = model.to_device(te_r, te_c, te_v)
+    got = model.rmse(a, b, c)
+    model.close()
+    arith = _arith(storage)
+    perm, bp, _, _ = oracle.partition(tr_r, tr_c, m, n, gr, gc, 1)
+    Po, Qo = oracle_init(m, n, k, 3, 0.1, arith)
+    for _ in range(epochs):
+        oracle.sgd_epoch(Po, Qo, tr_r, tr_c, tr_v, perm, bp, gr, gc, lr, lam, arith)
+    want = oracle.rmse(Po, Qo, te_r, te_c, te_v)
+    print("long rows k=%d %s: rmse gpu %.6f oracle %.6f" % (k, storage, got, want), flush=True)
+    assert abs(got - want) <= 0.005 * want, (got, want)
+
+
+def test_lds_kernel_is_refused_when_the_strip_does_not_fit(mfmod):
+    ds = dataset("tiny")
+    model = _make(mfmod, ds, 256, "f32", 2, 2, 0, options={mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS})
+    with pytest.raises(mfmod.MFError) as e:        # 500 columns * 256 * 4 B = 500 KiB > LDS
+        model.sgd_epoch(0.01, 0.05, mfmod.MF_MODE_HOGWILD)
+    assert e.value.code == mfmod.binding.MF_EINVAL
+    model.close()
+    # AUTO falls back to the kernel with atomics in L2 and still trains
+    model = _make(mfmod, ds, 256, "f32", 2, 2, 0)
+    before = model.rmse()
+    model.sgd_epoch(0.01, 0.05, mfmod.MF_MODE_HOGWILD)
+    assert model.rmse() < before
+    model.close()
+
+
+def test_tiny_config_hogwild_without_die_affinity_still_trains(mfmod):
+    """Diagnostic mode MF_OPT_XCD_AFFINITY = 0: the chunks of one block run on all dies, whose
+    private L2 caches do not see each other's updates inside a launch, so updates are lost and
+    the 0.5 % band is not promised; the run must still be a valid, converging training."""
     ds = dataset("tiny")
     Po, Qo, _ = oracle_train(ds, 8, 8, 1, ds.cfg.epochs)
     want = oracle.rmse(Po, Qo, ds.test_rows, ds.test_cols, ds.test_vals)
+    P0, Q0 = oracle_init(ds.cfg.m, ds.cfg.n, ds.cfg.k, 1, 0.1)
+    start = oracle.rmse(P0, Q0, ds.test_rows, ds.test_cols, ds.test_vals)
     got = _train_gpu(mfmod, ds, ds.cfg.k, "f32", 8, 8, 1, mfmod.MF_MODE_HOGWILD, ds.cfg.epochs,
-                     options={mfmod.MF_OPT_XCD_AFFINITY: affinity, mfmod.MF_OPT_HOGWILD_CHUNK: 32})
-    assert abs(got - want) <= 0.005 * want, (got, want)
+                     options={mfmod.MF_OPT_XCD_AFFINITY: 0, mfmod.MF_OPT_HOGWILD_CHUNK: 32,
+                              mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_GLOBAL_ATOMICS})
+    print("tiny HOGWILD (die affinity off): rmse gpu %.6f oracle %.6f start %.6f" % (got, want, start), flush=True)
+    assert got < 0.25 * start and abs(got - want) <= 0.10 * want, (got, want, start)
 
 
 # ------------------------------------------------------------------------------- error paths (forced from the host)
@@ -276,15 +347,18 @@ def test_medium_config_scaled_det_and_hogwild(mfmod):
     P, Q, Po, Qo = _det_one_epoch(mfmod, ds, k, "f32", 64, 64, 1)
     assert np.abs(P - Po).max() <= 1e-4 and np.abs(Q - Qo).max() <= 1e-4
     epochs = 5
-    Po, Qo, _ = oracle_train(ds, 8, 8, 1, epochs)
-    want = oracle.rmse(Po, Qo, ds.test_rows, ds.test_cols, ds.test_vals)
-    got = _train_gpu(mfmod, ds, k, "f32", 8, 8, 1, mfmod.MF_MODE_HOGWILD, epochs)
-    assert abs(got - want) <= 0.005 * want, (got, want)
+    for gr, gc, which in [(8, 8, mfmod.MF_HOGWILD_GLOBAL_ATOMICS), (32, 32, mfmod.MF_HOGWILD_LDS)]:
+        Po, Qo, _ = oracle_train(ds, gr, gc, 1, epochs)
+        want = oracle.rmse(Po, Qo, ds.test_rows, ds.test_cols, ds.test_vals)
+        got = _train_gpu(mfmod, ds, k, "f32", gr, gc, 1, mfmod.MF_MODE_HOGWILD, epochs,
+                         options={mfmod.MF_OPT_HOGWILD_KERNEL: which})
+        print("medium@0.05 HOGWILD kernel %d: rmse gpu %.6f oracle %.6f" % (which, got, want), flush=True)
+        assert abs(got - want) <= 0.005 * want, (got, want)
 
 
 def test_medium_config_full_size(mfmod):
     """Configuration 2 at its full size, in the launch configuration the benchmark times
-    (HOGWILD on an 8 x 8 grid) plus the deterministic mode on a fine grid."""
+    (HOGWILD, 128 x 128 grid, LDS kernel) plus the deterministic mode on a fine grid."""
     ds = dataset("medium")
     k = ds.cfg.k
     print("medium: max row/col degree", ds.max_row_degree, ds.max_col_degree, flush=True)
@@ -292,10 +366,10 @@ def test_medium_config_full_size(mfmod):
     dP, dQ = np.abs(P - Po).max(), np.abs(Q - Qo).max()
     print("medium DET one epoch: max|dP| %.3g max|dQ| %.3g" % (dP, dQ), flush=True)
     assert dP <= 1e-4 and dQ <= 1e-4
-    epochs = ds.cfg.epochs if FULL else 4
-    Po, Qo, _ = oracle_train(ds, 8, 8, 1, epochs)
+    epochs = ds.cfg.epochs if FULL else 6
+    Po, Qo, _ = oracle_train(ds, 128, 128, 1, epochs)
     want = oracle.rmse(Po, Qo, ds.test_rows, ds.test_cols, ds.test_vals)
-    got = _train_gpu(mfmod, ds, k, "f32", 8, 8, 1, mfmod.MF_MODE_HOGWILD, epochs)
+    got = _train_gpu(mfmod, ds, k, "f32", 128, 128, 1, mfmod.MF_MODE_HOGWILD, epochs)
     print("medium HOGWILD %d epochs: rmse gpu %.6f oracle %.6f" % (epochs, got, want), flush=True)
     assert abs(got - want) <= 0.005 * want, (got, want)
     got_det = _train_gpu(mfmod, ds, k, "f32", 8, 8, 1, mfmod.MF_MODE_DET, 1)

@@ -80,7 +80,9 @@ def test_work_lists_cover_every_rating_once_inside_its_stratum(mode, affinity, g
         if gr > m or gc > n:
             continue
         plan = B.mf_plan_host(rows, cols, m, n, gr, gc, B.MF_SPLIT_NNZ_BALANCED, mode, chunk, affinity)
-        eb, el, se, bp, perm = (plan[k] for k in ("entry_begin", "entry_len", "stratum_entry", "block_ptr", "perm"))
+        eb, raw_len, se, bp, perm = (plan[k] for k in ("entry_begin", "entry_len", "stratum_entry", "block_ptr", "perm"))
+        el = raw_len & 0x7FFFFFFF                                    # sign bit = "shares its row of P"
+        shared = raw_len < 0
         nnz = rows.size
         assert se[0] == 0 and se[-1] == eb.size and eb.size % 4 == 0
         seen = np.zeros(nnz, np.int32)
@@ -104,6 +106,7 @@ def test_work_lists_cover_every_rating_once_inside_its_stratum(mode, affinity, g
                     assert group % 8 == a % 8                        # block row a runs on die a mod 8
                 if mode == B.MF_MODE_DET:
                     assert b == bp[L] and ln == bp[L + 1] - bp[L]    # one wavefront per block
+                    assert not shared[e]
                 else:
                     # chunks are whole rows unless the row is longer than two chunks
                     first_row, last_row = pu[b], pu[b + ln - 1]
@@ -111,8 +114,37 @@ def test_work_lists_cover_every_rating_once_inside_its_stratum(mode, affinity, g
                         if bp[L] <= pos < bp[L + 1] and pu[pos] == edge_row:
                             row_len = np.count_nonzero(pu[bp[L]:bp[L + 1]] == edge_row)
                             assert row_len > 2 * chunk, (name, row_len)
+                            assert shared[e]                         # pieces of a cut row are flagged
                     assert ln <= 2 * chunk
         assert (seen == 1).all(), name
+
+
+@pytest.mark.parametrize("grid", [(1, 1), (3, 4), (8, 8), (20, 24)])
+def test_lds_work_list_covers_every_rating_once_block_by_block(grid):
+    gr, gc = grid
+    chunk = 20
+    for name, rows, cols, m, n in _cases():
+        if gr > m or gc > n:
+            continue
+        plan = B.mf_plan_host(rows, cols, m, n, gr, gc, B.MF_SPLIT_NNZ_BALANCED, B.MF_PLAN_HOGWILD_LDS, chunk)
+        eb, raw_len, se, bp, perm = (plan[k] for k in ("entry_begin", "entry_len", "stratum_entry", "block_ptr", "perm"))
+        el = raw_len & 0x7FFFFFFF
+        nnz = rows.size
+        assert (el > 0).all() and el.sum() == nnz
+        # entries tile the packed order without gaps, in order, and never cross a block boundary
+        assert np.array_equal(eb, np.concatenate([[0], np.cumsum(el)[:-1]])) if eb.size else nnz == 0
+        for e in range(eb.size):
+            L = np.searchsorted(bp, eb[e], side="right") - 1
+            assert eb[e] + el[e] <= bp[L + 1]
+        for s in range(gc):
+            if se[s] < eb.size:
+                assert eb[se[s]] >= bp[s * gr]
+        pu = rows[perm]
+        for e in range(eb.size):
+            if raw_len[e] >= 0 and eb[e] > 0 and e > 0:
+                L = np.searchsorted(bp, eb[e], side="right") - 1
+                if eb[e] > bp[L]:                                    # not the first entry of its block
+                    assert pu[eb[e] - 1] != pu[eb[e]] or raw_len[e - 1] < 0
 
 
 def test_plan_rejects_bad_arguments():
