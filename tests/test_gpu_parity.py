@@ -175,12 +175,25 @@ def test_empty_rating_set_is_a_valid_epoch(mfmod):
 
 def test_zero_learning_rate_changes_nothing_in_either_mode(mfmod):
     ds = dataset("tiny")
-    model = _make(mfmod, ds, 128, "f32", 8, 8, 1)
+    model = _make(mfmod, ds, 128, "f32", 8, 8, 1,
+                  options={mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_GLOBAL_ATOMICS})
     before = model.get_factors()
     model.sgd_epoch(0.0, 0.05, mfmod.MF_MODE_DET)
     model.sgd_epoch(0.0, 0.05, mfmod.MF_MODE_HOGWILD)
     after = model.get_factors()
     assert np.array_equal(before[0], after[0]) and np.array_equal(before[1], after[1])
+    model.close()
+    # the LDS kernel holds the strip of Qt as fixed point with 24 fraction bits: a pass with a
+    # zero step puts Qt on that grid (at most half a step away) and a second pass changes nothing
+    model = _make(mfmod, ds, 128, "f32", 8, 8, 1, options={mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS})
+    before = model.get_factors()
+    model.sgd_epoch(0.0, 0.05, mfmod.MF_MODE_HOGWILD)
+    once = model.get_factors()
+    model.sgd_epoch(0.0, 0.05, mfmod.MF_MODE_HOGWILD)
+    twice = model.get_factors()
+    assert np.array_equal(before[0], once[0]) and np.abs(before[1] - once[1]).max() <= 2.0 ** -25
+    assert np.array_equal(once[1] * 2.0 ** 24, np.round(once[1] * 2.0 ** 24))
+    assert np.array_equal(once[0], twice[0]) and np.array_equal(once[1], twice[1])
     model.close()
 
 
