@@ -17,6 +17,14 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
+# Memory-side bytes per launch of the dominant kernel, from the rocprofv3 counter passes summarised
+# under profiles/ (FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter reads for a plain
+# device copy of known size).  Counters cannot be read from inside this process, so the figure is
+# reported only for the exact configuration that was profiled, otherwise null.
+PROFILED_TRAFFIC = {
+    ("medium", 1.0, "hogwild", "128x128", "lds"): 45.60e6,   # profiles/sgd_block_lds_f32_k128_medium.md
+}
+
 
 def load_dataset(name, factor):
     import numpy as np
@@ -80,12 +88,15 @@ def main():
     ap.add_argument("--mode", default="hogwild", choices=["hogwild", "det"])
     ap.add_argument("--grid", default="128x128")
     ap.add_argument("--hogwild-kernel", default="auto", choices=["auto", "global_atomics", "lds"])
-    ap.add_argument("--lds-chunk", type=int, default=32)
+    ap.add_argument("--lds-chunk", type=int, default=0)
     ap.add_argument("--lds-waves", type=int, default=16)
     ap.add_argument("--chunk", type=int, default=128)
     ap.add_argument("--affinity", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="only run a plain device copy of this many MiB five times (a kernel of known "
+                         "traffic, used to scale the profiler's FETCH_SIZE / WRITE_SIZE readings) and exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1",
@@ -100,6 +111,16 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
         sys.exit(3)
+    if args.copy_calibration > 0:
+        n = args.copy_calibration * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_mib": args.copy_calibration, "bytes_read": n * 4, "bytes_written": n * 4,
+                          "launches": 5}))
+        return
     ds = load_dataset(args.workload, args.scale)
     cfg = ds.cfg
     gr, gc = (int(x) for x in args.grid.split("x"))
@@ -111,7 +132,7 @@ def main():
     which = {"auto": mf.MF_HOGWILD_AUTO, "global_atomics": mf.MF_HOGWILD_GLOBAL_ATOMICS,
              "lds": mf.MF_HOGWILD_LDS}[args.hogwild_kernel]
     opts = {mf.MF_OPT_HOGWILD_CHUNK: args.chunk, mf.MF_OPT_XCD_AFFINITY: args.affinity,
-            mf.MF_OPT_PROFILE: 0 if args.no_kernel_events else 1, mf.MF_OPT_HOGWILD_KERNEL: which,
+            mf.MF_OPT_HOGWILD_KERNEL: which,
             mf.MF_OPT_LDS_CHUNK: args.lds_chunk, mf.MF_OPT_LDS_WAVES: args.lds_waves}
     model = mf.MatrixFactorization(cfg.m, cfg.n, k, cfg.storage, seed=1, scale=0.1, options=opts)
     t0 = time.perf_counter()
@@ -120,19 +141,33 @@ def main():
     tr, tc, tv = model.to_device(ds.test_rows, ds.test_cols, ds.test_vals)
     nnz = ds.rows.size
 
-    rmse = float("nan")
-    for _ in range(args.warmup):
-        model.sgd_epoch(cfg.lr, cfg.lam, mode)
-        rmse = model.rmse(tr, tc, tv)
-    mf.binding.mf_profile_read(model.ctx)
+    def run_steps(count):
+        last = float("nan")
+        for _ in range(count):
+            model.sgd_epoch(cfg.lr, cfg.lam, mode)
+            last = model.rmse(tr, tc, tv)
+        return last
+
+    # timed region: K steps, no per-launch instrumentation
+    mf.binding.mf_set_option(model.ctx, mf.MF_OPT_PROFILE, 0)
+    run_steps(args.warmup)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        model.sgd_epoch(cfg.lr, cfg.lam, mode)
-        rmse = model.rmse(tr, tc, tv)
+    rmse = run_steps(args.steps)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    kernel_ms, launches = mf.binding.mf_profile_read(model.ctx)
+    # the same K steps once more with every SGD kernel launch bracketed by HIP events on the
+    # library's stream (the brackets cost about as much as the launches they time, so they are
+    # kept out of the region above); gives the kernel's average duration for the roofline
+    kernel_ms, launches, elapsed_events = 0.0, 0, 0.0
+    if not args.no_kernel_events:
+        mf.binding.mf_set_option(model.ctx, mf.MF_OPT_PROFILE, 1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        rmse = run_steps(args.steps)
+        torch.cuda.synchronize()
+        elapsed_events = time.perf_counter() - t0
+        kernel_ms, launches = mf.binding.mf_profile_read(model.ctx)
     model.close()
 
     value = nnz * args.steps / elapsed
@@ -141,10 +176,15 @@ def main():
         avg_s = kernel_ms * 1e-3 / launches
         bytes_per_launch = bytes_per_update * nnz * args.steps / launches
         achieved = bytes_per_launch / avg_s / 1e9
+        kern = "lds" if (args.mode == "hogwild" and args.hogwild_kernel != "global_atomics") else "chunks"
+        traffic = PROFILED_TRAFFIC.get((args.workload, args.scale, args.mode, args.grid, kern))
+        if args.lds_waves != 16 or args.lds_chunk != 0:
+            traffic = None
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "sgd_block_lds<float,128>" if (args.mode == "hogwild" and args.hogwild_kernel != "global_atomics") else "sgd_chunks<float,128>",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": "sgd_block_lds<float,128>" if (args.mode == "hogwild" and args.hogwild_kernel != "global_atomics") else "sgd_chunks<float,128>",
                     "avg_launch_us": avg_s * 1e6, "launches_per_step": launches / args.steps,
-                    "bytes_per_update": bytes_per_update}
+                    "bytes_per_update": bytes_per_update,
+                    "ms_per_step_with_event_brackets": elapsed_events * 1e3 / args.steps}
     out = {"metric": "SGD updates/s at k=128 (HOGWILD epoch + held-out RMSE per step)", "value": value,
            "unit": "updates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": elapsed * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak",

@@ -53,7 +53,8 @@ enum {
     MF_OPT_PROFILE = 3,           /* 1: time every SGD kernel launch with HIP events (see below)     */
     MF_OPT_HOGWILD_KERNEL = 4,    /* MF_HOGWILD_AUTO (default), _GLOBAL_ATOMICS or _LDS, see          */
                                   /* mf_sgd_epoch                                                     */
-    MF_OPT_LDS_CHUNK = 5,         /* target ratings per work-list entry of the LDS kernel (default 32)*/
+    MF_OPT_LDS_CHUNK = 5,         /* target ratings per work-list entry of the LDS kernel; 0 (default)*/
+                                  /* = the block's ratings divided by MF_OPT_LDS_WAVES               */
     MF_OPT_LDS_WAVES = 6          /* wavefronts per workgroup of the LDS kernel, 1..16 (default 16)   */
 };
 enum { MF_HOGWILD_AUTO = 0, MF_HOGWILD_GLOBAL_ATOMICS = 1, MF_HOGWILD_LDS = 2 };
@@ -147,7 +148,9 @@ int mf_sync(mf_ctx* ctx);
 
 /* With MF_OPT_PROFILE = 1 every SGD kernel launch is bracketed by HIP events on the context's
  * stream.  This call synchronises, then returns the summed kernel time in milliseconds and the
- * number of launches since the previous call (HOST pointers, either may be NULL). */
+ * number of launches since the previous call (HOST pointers, either may be NULL).  Each bracket is
+ * reduced by the duration of an empty event pair measured during this call, so that the figure
+ * is the kernels' own time. */
 int mf_profile_read(mf_ctx* ctx, double* kernel_ms_out, int64_t* launches_out);
 
 /* Diagnostic: launch n_groups workgroups and report, for each, the id of the XCD (accelerator

@@ -320,8 +320,8 @@ __global__ __launch_bounds__(kGroupThreads) void sgd_chunks(
 
 // ------------------------------------------------------------- Hogwild with the Qt strip in LDS
 // One workgroup per block of the grid.  The block's strip of Qt (its ncols columns, contiguous
-// rows of Qt) is copied into LDS, the wavefronts of the workgroup take the block's entries
-// (chunks of whole matrix rows) from a shared counter and run the step of Algorithm 1 on them
+// rows of Qt) is copied into LDS, the wavefronts of the workgroup share out the block's entries
+// (chunks of whole matrix rows) round-robin and run the step of Algorithm 1 on them
 // -- p_u in registers, q_v read from LDS and changed with LDS atomic adds, so no update of q_v
 // is lost although the wavefronts do not lock anything -- and the strip is written back at the
 // end.  Blocks of one launch are mutually independent, so no other workgroup touches these rows
@@ -372,9 +372,10 @@ __device__ __forceinline__ void lds_owned_chunk(T* __restrict__ P, int* strip, i
                                                 const int32_t* __restrict__ U,
                                                 const int32_t* __restrict__ V,
                                                 const float* __restrict__ R, int64_t begin,
-                                                int32_t len, float lr, float shrink, int lane,
-                                                bool active)
+                                                int32_t len, int mu, int mv, float mr, float lr,
+                                                float shrink, int lane, bool active)
 {
+    // mu, mv, mr: the first batch of the chunk (rating `lane` of it), already loaded by the caller
     constexpr int VEC = RowShape<T, K>::VEC;
     Row<VEC> p_prev;
 #pragma unroll
@@ -382,9 +383,7 @@ __device__ __forceinline__ void lds_owned_chunk(T* __restrict__ P, int* strip, i
     int u_prev = -1;
     for (int32_t off = 0; off < len; off += kWave) {
         const int cnt = min(kWave, len - off);
-        int mu = 0, mv = 0;
-        float mr = 0.f;
-        if (lane < cnt) {
+        if (off > 0 && lane < cnt) {
             mu = U[begin + off + lane];
             mv = V[begin + off + lane];
             mr = R[begin + off + lane];
@@ -497,7 +496,6 @@ __global__ __launch_bounds__(1024) void sgd_block_lds(
     const LdsBlock* __restrict__ blocks, float lr, float lambda)
 {
     extern __shared__ int strip[];            // ncols * K fixed-point values
-    __shared__ unsigned next_entry;
     const int lane = threadIdx.x & (kWave - 1);
     const bool active = lane < RowShape<T, K>::ACTIVE;
     const LdsBlock blk = blocks[blockIdx.x];
@@ -505,7 +503,25 @@ __global__ __launch_bounds__(1024) void sgd_block_lds(
     T* const strip_src = Qt + (int64_t)blk.col0 * K;
     const int stride = 4 * (int)blockDim.x;
 
-    if (threadIdx.x == 0) next_entry = 0;
+    // Entries are dealt to the wavefronts round-robin.  The first entry's ratings are requested
+    // before the strip is copied so that the two latencies overlap.
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n_waves = (int)(blockDim.x >> 6);
+    int32_t raw_len = 0;
+    int64_t begin = 0;
+    int mu = 0, mv = 0;
+    float mr = 0.f;
+    auto fetch_entry = [&](int e) {
+        raw_len = entry_len[blk.first_entry + e];
+        begin = entry_begin[blk.first_entry + e];
+        if (lane < min(kWave, raw_len & ~kSharedRowFlag)) {
+            mu = U[begin + lane];
+            mv = V[begin + lane];
+            mr = R[begin + lane];
+        }
+    };
+    if (wave < blk.n_entries) fetch_entry(wave);
+
     for (int i0 = 4 * (int)threadIdx.x; i0 < total; i0 += 4 * stride) {
         float4 val[4];
 #pragma unroll
@@ -532,20 +548,14 @@ __global__ __launch_bounds__(1024) void sgd_block_lds(
     __syncthreads();
 
     const float shrink = lr * lambda;
-    for (;;) {
-        unsigned taken = 0;
-        if (lane == 0) taken = atomicAdd(&next_entry, 1u);
-        taken = __builtin_amdgcn_readfirstlane(taken);
-        if (taken >= (unsigned)blk.n_entries) break;
-        const int64_t entry = blk.first_entry + taken;
-        const int32_t raw_len = entry_len[entry];
+    for (int e = wave; e < blk.n_entries; e += n_waves) {
+        if (e != wave) fetch_entry(e);
         const int32_t len = raw_len & ~kSharedRowFlag;
-        const int64_t begin = entry_begin[entry];
         if (raw_len < 0)
             lds_shared_row_chunk<T, K>(P, strip, blk.col0, U, V, R, begin, len, lr, shrink, lane, active);
         else
-            lds_owned_chunk<T, K, kLdsPrefetchDepth>(P, strip, blk.col0, U, V, R, begin, len, lr, shrink, lane,
-                                                     active);
+            lds_owned_chunk<T, K, kLdsPrefetchDepth>(P, strip, blk.col0, U, V, R, begin, len, mu, mv, mr, lr,
+                                                     shrink, lane, active);
     }
     __syncthreads();
 

@@ -39,7 +39,7 @@ struct mf_ctx {
     int32_t xcd_affinity = 1;
     int32_t profile = 0;
     int32_t hogwild_kernel = MF_HOGWILD_AUTO;
-    int32_t lds_chunk = 32;
+    int32_t lds_chunk = 0;   // 0 = one chunk per wavefront
     int32_t lds_waves = 16;
 
     // library-owned device buffer: RMSE partials followed by the final sum
@@ -78,12 +78,12 @@ struct Layout {
     int64_t cap[2], lds_cap, lds_blocks_cap;
 };
 
-Layout make_layout(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t lds_chunk)
+Layout make_layout(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t lds_chunk, int32_t lds_waves)
 {
     Layout l;
     l.cap[MF_MODE_DET] = mf::det_entries_bound(gr, gc);
     l.cap[MF_MODE_HOGWILD] = mf::hogwild_entries_bound(nnz, gr, gc, chunk);
-    l.lds_cap = mf::lds_entries_bound(nnz, gr, gc, lds_chunk);
+    l.lds_cap = mf::lds_entries_bound(nnz, gr, gc, lds_chunk, lds_waves);
     l.lds_blocks_cap = (int64_t)gr * gc;
     size_t off = 0;
     l.off_u = off; off += align_up((size_t)nnz * 4);
@@ -166,7 +166,7 @@ int mf_set_option(mf_ctx* ctx, int32_t option, int64_t value)
             ctx->hogwild_kernel = (int32_t)value;
             return MF_OK;
         case MF_OPT_LDS_CHUNK:
-            if (value < 1 || value > (1 << 20)) return fail(ctx, MF_EINVAL, "chunk must be in [1, 2^20]");
+            if (value < 0 || value > (1 << 20)) return fail(ctx, MF_EINVAL, "chunk must be in [0, 2^20]");
             ctx->lds_chunk = (int32_t)value;
             return MF_OK;
         case MF_OPT_LDS_WAVES:
@@ -211,7 +211,7 @@ int mf_load_blocks_workspace(const mf_ctx* ctx, int64_t nnz, int32_t grid_r, int
     if (!ctx || !bytes_out) return MF_EINVAL;
     int rc = check_grid(const_cast<mf_ctx*>(ctx), nnz, grid_r, grid_c);
     if (rc) return rc;
-    *bytes_out = make_layout(nnz, grid_r, grid_c, ctx->hogwild_chunk, ctx->lds_chunk).total;
+    *bytes_out = make_layout(nnz, grid_r, grid_c, ctx->hogwild_chunk, ctx->lds_chunk, ctx->lds_waves).total;
     return MF_OK;
 }
 
@@ -228,7 +228,7 @@ int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const 
     if (nnz > 0 && (!rows || !cols || !vals)) return fail(ctx, MF_EINVAL, "null rating array");
     if (!d_workspace) return fail(ctx, MF_EINVAL, "null workspace");
     if ((uintptr_t)d_workspace & 255) return fail(ctx, MF_EINVAL, "workspace must be 256-byte aligned");
-    const Layout lay = make_layout(nnz, grid_r, grid_c, ctx->hogwild_chunk, ctx->lds_chunk);
+    const Layout lay = make_layout(nnz, grid_r, grid_c, ctx->hogwild_chunk, ctx->lds_chunk, ctx->lds_waves);
     if (workspace_bytes < lay.total) return fail(ctx, MF_ENOMEM, "workspace too small");
     MF_HIP(ctx, hipSetDevice(ctx->device));
     ctx->loaded = false;
@@ -243,7 +243,7 @@ int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const 
         mf::build_det_schedule(ctx->part, ctx->xcd_affinity != 0, ctx->sched[MF_MODE_DET]);
         mf::build_hogwild_schedule(ctx->part, pu, ctx->hogwild_chunk, ctx->xcd_affinity != 0,
                                    ctx->sched[MF_MODE_HOGWILD]);
-        mf::build_lds_schedule(ctx->part, pu, ctx->lds_chunk, ctx->lds);
+        mf::build_lds_schedule(ctx->part, pu, ctx->lds_chunk, ctx->lds_waves, ctx->lds);
     } catch (const std::bad_alloc&) {
         return fail(ctx, MF_ENOMEM, "host allocation failed while partitioning");
     }
@@ -392,11 +392,28 @@ int mf_profile_read(mf_ctx* ctx, double* kernel_ms_out, int64_t* launches_out)
     if (!ctx) return MF_EINVAL;
     MF_HIP(ctx, hipSetDevice(ctx->device));
     MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    // An event pair around nothing still measures the time between its two markers; take the
+    // smallest of a few such empty pairs now and remove it from every bracketed launch.
+    float empty_ms = 0.f;
+    if (ctx->events_used > 0) {
+        constexpr int kEmptyPairs = 16;
+        hipEvent_t ev[2 * kEmptyPairs];
+        for (auto& e : ev) MF_HIP(ctx, hipEventCreate(&e));
+        for (auto& e : ev) MF_HIP(ctx, hipEventRecord(e, ctx->stream));
+        MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        empty_ms = 1e30f;
+        for (int i = 0; i < kEmptyPairs; ++i) {
+            float ms = 0.f;
+            MF_HIP(ctx, hipEventElapsedTime(&ms, ev[2 * i], ev[2 * i + 1]));
+            empty_ms = ms < empty_ms ? ms : empty_ms;
+        }
+        for (auto& e : ev) (void)hipEventDestroy(e);
+    }
     double total = 0.0;
     for (size_t i = 0; i < ctx->events_used; ++i) {
         float ms = 0.f;
         MF_HIP(ctx, hipEventElapsedTime(&ms, ctx->events[i].first, ctx->events[i].second));
-        total += ms;
+        total += ms > empty_ms ? ms - empty_ms : 0.f;
     }
     if (kernel_ms_out) *kernel_ms_out = total;
     if (launches_out) *launches_out = (int64_t)ctx->events_used;
@@ -429,7 +446,7 @@ int mf_plan_host(const int32_t* rows, const int32_t* cols, int64_t nnz, int64_t 
     if (m < 1 || n < 1 || grid_r > m || grid_c > n) return MF_EINVAL;
     if (split != MF_SPLIT_EQUAL_WIDTH && split != MF_SPLIT_NNZ_BALANCED) return MF_EINVAL;
     if (mode != MF_MODE_DET && mode != MF_MODE_HOGWILD && mode != MF_PLAN_HOGWILD_LDS) return MF_EINVAL;
-    if (chunk < 1 || (nnz > 0 && (!rows || !cols))) return MF_EINVAL;
+    if (chunk < (mode == MF_PLAN_HOGWILD_LDS ? 0 : 1) || (nnz > 0 && (!rows || !cols))) return MF_EINVAL;
     try {
         mf::Partition part;
         std::vector<int32_t> pu, pv;
@@ -447,8 +464,8 @@ int mf_plan_host(const int32_t* rows, const int32_t* cols, int64_t nnz, int64_t 
             bound = mf::hogwild_entries_bound(nnz, grid_r, grid_c, chunk);
         } else {
             mf::LdsSchedule l;
-            mf::build_lds_schedule(part, pu, chunk, l);
-            bound = mf::lds_entries_bound(nnz, grid_r, grid_c, chunk);
+            mf::build_lds_schedule(part, pu, chunk, 16, l);
+            bound = mf::lds_entries_bound(nnz, grid_r, grid_c, chunk, 16);
             s.begin = l.begin;
             s.len = l.len;
             s.stratum_entry.assign((size_t)grid_c + 1, (int64_t)l.begin.size());

@@ -70,9 +70,9 @@ void build_det_schedule(const Partition& part, bool xcd_affinity, Schedule& out)
 void build_hogwild_schedule(const Partition& part, const std::vector<int32_t>& pu, int32_t chunk,
                             bool xcd_affinity, Schedule& out);
 void build_lds_schedule(const Partition& part, const std::vector<int32_t>& pu, int32_t chunk,
-                        LdsSchedule& out);
+                        int32_t waves, LdsSchedule& out);
 // Upper bounds on the number of schedule entries, usable before the partition is known.
-int64_t lds_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk);
+int64_t lds_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t waves);
 int64_t det_entries_bound(int32_t gr, int32_t gc);
 int64_t hogwild_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk);
 

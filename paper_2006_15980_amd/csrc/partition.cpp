@@ -318,8 +318,9 @@ void build_hogwild_schedule(const Partition& part, const std::vector<int32_t>& p
 }
 
 void build_lds_schedule(const Partition& part, const std::vector<int32_t>& pu, int32_t chunk,
-                        LdsSchedule& out)
+                        int32_t waves, LdsSchedule& out)
 {
+    // chunk == 0: cut every block into about one chunk per wavefront of its workgroup
     out.begin.clear();
     out.len.clear();
     out.blocks.clear();
@@ -337,7 +338,9 @@ void build_lds_schedule(const Partition& part, const std::vector<int32_t>& pu, i
             blk.col0 = part.col_bounds[b];
             blk.ncols = part.col_bounds[b + 1] - part.col_bounds[b];
             blk.reserved = 0;
-            chunk_block(pu, part.block_ptr[L], part.block_ptr[L + 1], chunk, [&](int64_t pos, int32_t len) {
+            int64_t size = part.block_ptr[L + 1] - part.block_ptr[L];
+            int32_t this_chunk = chunk > 0 ? chunk : (int32_t)std::max<int64_t>(8, (size + waves - 1) / waves);
+            chunk_block(pu, part.block_ptr[L], part.block_ptr[L + 1], this_chunk, [&](int64_t pos, int32_t len) {
                 out.begin.push_back(pos);
                 out.len.push_back(len);
             });
@@ -366,9 +369,12 @@ int64_t hogwild_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk
     return chunks * kXcds + (int64_t)gc * kXcds * kWavesPerGroup;
 }
 
-int64_t lds_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk)
+int64_t lds_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t waves)
 {
-    return 4 * (nnz / chunk + 1) + 2 * (int64_t)gr * gc;   // as above, without padding
+    // as above, without padding; with chunk == 0 a block of c ratings is cut with a chunk of
+    // max(8, ceil(c / waves)), which gives at most 4 * min(c / 8, waves) + 2 entries
+    if (chunk > 0) return 4 * (nnz / chunk + 1) + 2 * (int64_t)gr * gc;
+    return std::min<int64_t>(4 * (nnz / 8 + 1), 4 * (int64_t)waves * gr * gc) + 2 * (int64_t)gr * gc;
 }
 
 }  // namespace mf

@@ -247,7 +247,7 @@ def test_hogwild_lds_kernel_other_shapes_and_long_rows(mfmod, k, storage):
     hold = rng.random(nnz) < 0.1
     tr_r, tr_c, tr_v = (np.ascontiguousarray(x[~hold]) for x in (rows, cols, vals))
     te_r, te_c, te_v = (np.ascontiguousarray(x[hold]) for x in (rows, cols, vals))
-    gr, gc, epochs, lr, lam = 3, 5, 40, 0.01, 0.02
+    gr, gc, epochs, lr, lam = 3, 5, 60, 0.01, 0.05
     model = mfmod.MatrixFactorization(m, n, k, storage, seed=3, scale=0.1,
                                       options={mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS,
                                                mfmod.MF_OPT_LDS_CHUNK: 24, mfmod.MF_OPT_LDS_WAVES: 8})
