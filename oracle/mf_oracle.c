@@ -26,10 +26,15 @@
  * Arithmetic: `arith` selects the number system of the factor state.
  *   MFO_ARITH_F64 : state, dot product and step all in double.  This is the definition.
  *   MFO_ARITH_F32 : state on the fp32 grid; dot in double rounded once to fp32; the
- *                   element-wise step in fp32 with separately rounded operations.
+ *                   element-wise step in fp32, written as  x + ((g*e)*y - (g*lambda)*x)
+ *                   with the inner multiply-subtract fused (fmaf) and every other operation
+ *                   rounded separately.
  *   MFO_ARITH_F16 : as F32, then every stored value is rounded to IEEE binary16
  *                   (round-to-nearest-even) after every step ("stored fp16, updated in
- *                   fp32").
+ *                   fp32").  The rounding to binary16 is a decision taken from an fp32 value;
+ *                   the grouping above is Algorithm 1's line regrouped so that this value is
+ *                   defined operation by operation and does not depend on the order in which
+ *                   the dot product is summed (the dot is exact to double precision).
  * The state arrays are always `double` so one interface serves the three.
  *
  * Parity pins live in tests/test_oracle_pins.py (worked example of the paper, finite
@@ -233,10 +238,13 @@ static void step_f32(double* p, double* q, int32_t k, float r, float g, float la
     double dot = 0.0;
     for (int32_t f = 0; f < k; ++f) dot += p[f] * q[f];   /* state is on the fp32 grid   */
     float e = r - (float)dot;
+    float step = g * e;                                    /* gamma * e                   */
+    float shrink = g * lam;                                /* gamma * lambda              */
     for (int32_t f = 0; f < k; ++f) {
         float pf = (float)p[f], qf = (float)q[f];
-        float pn = pf + g * (e * qf - lam * pf);           /* -ffp-contract=off: each     */
-        float qn = qf + g * (e * pf - lam * qf);           /* operation rounds separately */
+        float sp = shrink * pf, sq = shrink * qf;          /* -ffp-contract=off: only the */
+        float pn = pf + fmaf(step, qf, -sp);               /* explicit fmaf is fused      */
+        float qn = qf + fmaf(step, pf, -sq);
         p[f] = to_f16 ? mfo_round_f16((double)pn) : (double)pn;
         q[f] = to_f16 ? mfo_round_f16((double)qn) : (double)qn;
     }

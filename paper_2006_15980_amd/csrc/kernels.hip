@@ -174,6 +174,31 @@ __device__ __forceinline__ float wave_sum(float x)
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
 }
 
+// The same reduction on doubles (each step moves the two 32-bit halves).  Used where the sum
+// must not depend on rounding order: the deterministic mode with binary16 storage.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_add_f64(double x)
+{
+    const long long bits = __double_as_longlong(x);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)bits, CTRL, ROW_MASK, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(bits >> 32), CTRL, ROW_MASK, 0xf, false);
+    return x + __longlong_as_double(((long long)hi << 32) | (unsigned)lo);
+}
+
+__device__ __forceinline__ double wave_sum_f64_dpp(double x)
+{
+    x = dpp_add_f64<0xB1, 0xf>(x);
+    x = dpp_add_f64<0x4E, 0xf>(x);
+    x = dpp_add_f64<0x141, 0xf>(x);
+    x = dpp_add_f64<0x140, 0xf>(x);
+    x = dpp_add_f64<0x142, 0xa>(x);
+    x = dpp_add_f64<0x143, 0xc>(x);
+    const long long bits = __double_as_longlong(x);
+    const int lo = __builtin_amdgcn_readlane((int)bits, 63);
+    const int hi = __builtin_amdgcn_readlane((int)(bits >> 32), 63);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned)lo);
+}
+
 __device__ __forceinline__ int uniform_lane(int v, int lane)
 {
     return __builtin_amdgcn_readlane(v, lane);
@@ -262,17 +287,29 @@ __global__ __launch_bounds__(kGroupThreads) void sgd_chunks(
                 qn = load_row<VEC, HOG>(Qt + (int64_t)vn * K, lane, active);
                 if (un != u || shared_rows) pn = load_row<VEC, HOG>(P + (int64_t)un * K, lane, active);
             }
-            float part = 0.f;
+            float e;
+            if constexpr (!HOG && sizeof(T) == 2) {
+                // deterministic mode on binary16 storage: the value that gets rounded to binary16
+                // must not depend on the summation order of the dot product, so it is summed in
+                // double and rounded once
+                double part = 0.0;
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) part = fmaf(p.x[j], q.x[j], part);
-            const float e = r - wave_sum(part);
+                for (int j = 0; j < VEC; ++j) part = fma((double)p.x[j], (double)q.x[j], part);
+                e = r - (float)wave_sum_f64_dpp(part);
+            } else {
+                float part = 0.f;
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) part = fmaf(p.x[j], q.x[j], part);
+                e = r - wave_sum(part);
+            }
             const float step = lr * e;
             Row<VEC> p2, q2;
 #pragma unroll
             for (int j = 0; j < VEC; ++j) {
-                // p + lr*(e*q - lambda*p) regrouped as (p - (lr*lambda)*p) + (lr*e)*q: two
-                // fused operations, each rounded once at the magnitude of the element
-                p2.x[j] = quantise<T>(fmaf(step, q.x[j], fmaf(-shrink, p.x[j], p.x[j])));
+                // p + lr*(e*q - lambda*p) as p + ((lr*e)*q - (lr*lambda)*p): the small change is
+                // formed first, so that only ONE rounding happens at the magnitude of the element
+                // (and none with a bias, as a precomputed factor 1 - lr*lambda would have)
+                p2.x[j] = quantise<T>(p.x[j] + fmaf(step, q.x[j], -shrink * p.x[j]));
             }
             if constexpr (HOG) {
                 Row<VEC> dq;
@@ -285,7 +322,7 @@ __global__ __launch_bounds__(kGroupThreads) void sgd_chunks(
             } else {
 #pragma unroll
                 for (int j = 0; j < VEC; ++j)
-                    q2.x[j] = quantise<T>(fmaf(step, p.x[j], fmaf(-shrink, q.x[j], q.x[j])));
+                    q2.x[j] = quantise<T>(q.x[j] + fmaf(step, p.x[j], -shrink * q.x[j]));
                 store_row<VEC>(Qt + (int64_t)v * K, lane, active, q2);
             }
             if (more) {
@@ -421,7 +458,7 @@ __device__ __forceinline__ void lds_owned_chunk(T* __restrict__ P, int* strip, i
                 Row<VEC> p2;
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) {
-                    p2.x[j] = quantise<T>(fmaf(step, q.x[j], fmaf(-sh, p.x[j], p.x[j])));
+                    p2.x[j] = quantise<T>(p.x[j] + fmaf(step, q.x[j], -sh * p.x[j]));
                     const int dq = to_fixed(fmaf(step, p.x[j], -sh * q.x[j]));
                     if (active) atomicAdd(&qrow[strip_elem<T>(lane, j)], dq);
                     // the read-ahead of the next column was taken before this add
