@@ -55,9 +55,11 @@ enum {
                                   /* mf_sgd_epoch                                                     */
     MF_OPT_LDS_CHUNK = 5,         /* target ratings per work-list entry of the LDS kernel; 0 (default)*/
                                   /* = the block's ratings divided by MF_OPT_LDS_WAVES               */
-    MF_OPT_LDS_WAVES = 6          /* wavefronts per workgroup of the LDS kernel, 1..16 (default 16)   */
+    MF_OPT_LDS_WAVES = 6,         /* wavefronts per workgroup of the LDS kernel, 1..16 (default 16)   */
+    MF_OPT_DET_KERNEL = 7         /* MF_KERNEL_AUTO (default), _GLOBAL or _LDS for MF_MODE_DET        */
 };
-enum { MF_HOGWILD_AUTO = 0, MF_HOGWILD_GLOBAL_ATOMICS = 1, MF_HOGWILD_LDS = 2 };
+enum { MF_KERNEL_AUTO = 0, MF_KERNEL_GLOBAL = 1, MF_KERNEL_LDS = 2 };
+enum { MF_HOGWILD_AUTO = MF_KERNEL_AUTO, MF_HOGWILD_GLOBAL_ATOMICS = MF_KERNEL_GLOBAL, MF_HOGWILD_LDS = MF_KERNEL_LDS };
 enum { MF_PLAN_HOGWILD_LDS = 2 };  /* third value of `mode` accepted by mf_plan_host only */
 
 /* Create a context on HIP device `device`.  `hip_stream` is a hipStream_t of the caller (may be
@@ -119,7 +121,10 @@ int mf_get_partition(const mf_ctx* ctx, int64_t* perm, int64_t* block_ptr,
  * stratum (one kernel launch per stratum on the context's stream).  Returns after enqueueing.
  *   MF_MODE_DET     : one wavefront per block, ratings in stored order.  The result is the same
  *                     on every run and equals the sequential order (strata ascending, blocks
- *                     ascending, stored order) up to fp32 rounding.
+ *                     ascending, stored order) up to fp32 rounding.  Two kernels with identical
+ *                     results: MF_KERNEL_LDS keeps the block's strip of Qt in LDS (fp32; taken by
+ *                     MF_KERNEL_AUTO when a strip needs at most 39 KiB, so that several blocks
+ *                     fit one compute unit), MF_KERNEL_GLOBAL works on Qt in memory (any grid).
  *   MF_MODE_HOGWILD : every block is cut into chunks of whole rows that many wavefronts process
  *                     concurrently without locks (lock-free updates in the sense of Hogwild,
  *                     Section 3.1).  A wavefront owns the rows of P of its chunk; rows of Qt are

@@ -388,12 +388,16 @@ __device__ __forceinline__ int to_fixed(float x)
 
 __device__ __forceinline__ float from_fixed(int x) { return (float)x * kFromFixed; }
 
-template <typename T, int VEC>
+// EXACT = the strip holds fp32 bit patterns (deterministic mode), else fixed point (Hogwild).
+template <typename T, int VEC, bool EXACT = false>
 __device__ __forceinline__ Row<VEC> strip_read(const int* qrow, int lane, bool active)
 {
     Row<VEC> q;
 #pragma unroll
-    for (int j = 0; j < VEC; ++j) q.x[j] = active ? from_fixed(qrow[strip_elem<T>(lane, j)]) : 0.f;
+    for (int j = 0; j < VEC; ++j) {
+        const int raw = active ? qrow[strip_elem<T>(lane, j)] : 0;
+        q.x[j] = EXACT ? __int_as_float(raw) : from_fixed(raw);
+    }
     return q;
 }
 
@@ -404,7 +408,9 @@ __device__ __forceinline__ Row<VEC> strip_read(const int* qrow, int lane, bool a
 // equals the previous rating's takes the row from registers: the request for it was issued before
 // the previous ratings of that run were applied.  Positions past the end of the batch repeat the
 // last rating with a zero step, which changes nothing.
-template <typename T, int K, int DEPTH>
+// EXACT (deterministic mode, the wavefront is alone in its workgroup): the strip holds fp32, q_v
+// is read and written in program order, every operation is the sequential order's.
+template <typename T, int K, int DEPTH, bool EXACT>
 __device__ __forceinline__ void lds_owned_chunk(T* __restrict__ P, int* strip, int col0,
                                                 const int32_t* __restrict__ U,
                                                 const int32_t* __restrict__ V,
@@ -418,12 +424,15 @@ __device__ __forceinline__ void lds_owned_chunk(T* __restrict__ P, int* strip, i
 #pragma unroll
     for (int j = 0; j < VEC; ++j) p_prev.x[j] = 0.f;
     int u_prev = -1;
+    int nu = 0, nv = 0;
+    float nr = 0.f;
     for (int32_t off = 0; off < len; off += kWave) {
         const int cnt = min(kWave, len - off);
-        if (off > 0 && lane < cnt) {
-            mu = U[begin + off + lane];
-            mv = V[begin + off + lane];
-            mr = R[begin + off + lane];
+        // the ratings of the batch after this one are requested now
+        if (lane < len - off - kWave) {
+            nu = U[begin + off + kWave + lane];
+            nv = V[begin + off + kWave + lane];
+            nr = R[begin + off + kWave + lane];
         }
         const int last = cnt - 1;
         Row<VEC> ring[DEPTH];
@@ -431,7 +440,7 @@ __device__ __forceinline__ void lds_owned_chunk(T* __restrict__ P, int* strip, i
         for (int d = 0; d < DEPTH; ++d)
             ring[d] = load_row<VEC, false>(P + (int64_t)uniform_lane(mu, min(d, last)) * K, lane, active);
         int v_next = uniform_lane(mv, 0);
-        Row<VEC> q_next = strip_read<T, VEC>(strip + (v_next - col0) * K, lane, active);
+        Row<VEC> q_next = strip_read<T, VEC, EXACT>(strip + (v_next - col0) * K, lane, active);
         for (int base = 0; base < cnt; base += DEPTH) {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
@@ -448,27 +457,145 @@ __device__ __forceinline__ void lds_owned_chunk(T* __restrict__ P, int* strip, i
                 const Row<VEC> q = q_next;
                 int* const qrow = strip + (v - col0) * K;
                 v_next = uniform_lane(mv, min(i + 1, last));
-                const Row<VEC> q_ahead = strip_read<T, VEC>(strip + (v_next - col0) * K, lane, active);
-                float part = 0.f;
+                const Row<VEC> q_ahead = strip_read<T, VEC, EXACT>(strip + (v_next - col0) * K, lane, active);
+                float e;
+                if constexpr (EXACT && sizeof(T) == 2) {
+                    double part = 0.0;   // see sgd_chunks: the binary16 result must not depend on summation order
 #pragma unroll
-                for (int j = 0; j < VEC; ++j) part = fmaf(p.x[j], q.x[j], part);
-                const float e = r - wave_sum(part);
+                    for (int j = 0; j < VEC; ++j) part = fma((double)p.x[j], (double)q.x[j], part);
+                    e = r - (float)wave_sum_f64_dpp(part);
+                } else {
+                    float part = 0.f;
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j) part = fmaf(p.x[j], q.x[j], part);
+                    e = r - wave_sum(part);
+                }
                 const float step = valid ? lr * e : 0.f;
                 const float sh = valid ? shrink : 0.f;
                 Row<VEC> p2;
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) {
                     p2.x[j] = quantise<T>(p.x[j] + fmaf(step, q.x[j], -sh * p.x[j]));
-                    const int dq = to_fixed(fmaf(step, p.x[j], -sh * q.x[j]));
-                    if (active) atomicAdd(&qrow[strip_elem<T>(lane, j)], dq);
-                    // the read-ahead of the next column was taken before this add
-                    q_next.x[j] = (v_next == v) ? q.x[j] + from_fixed(dq) : q_ahead.x[j];
+                    // the read-ahead of the next column was taken before this column is changed
+                    if constexpr (EXACT) {
+                        const float q2 = quantise<T>(q.x[j] + fmaf(step, p.x[j], -sh * q.x[j]));
+                        if (active) qrow[strip_elem<T>(lane, j)] = __float_as_int(q2);
+                        q_next.x[j] = (v_next == v) ? q2 : q_ahead.x[j];
+                    } else {
+                        const int dq = to_fixed(fmaf(step, p.x[j], -sh * q.x[j]));
+                        if (active) atomicAdd(&qrow[strip_elem<T>(lane, j)], dq);
+                        q_next.x[j] = (v_next == v) ? q.x[j] + from_fixed(dq) : q_ahead.x[j];
+                    }
                 }
                 store_row<VEC>(P + (int64_t)u * K, lane, active, p2);
                 p_prev = p2;
                 u_prev = u;
             }
         }
+        mu = nu;
+        mv = nv;
+        mr = nr;
+    }
+}
+
+// ---- Hogwild version of the loop above, trimmed for instruction count -------------------------
+// With 16 wavefronts per compute unit this loop is bound by VALU issue (measured: 0.245 us per
+// rating and wavefront = 37 cycles per rating and compute unit at ~50 VALU instructions), so:
+//  * q_v is kept in the scale of its fixed-point strip (float(q_fixed) = q * 2^24): reading it is
+//    one conversion, the change is one fused multiply-add and one conversion, and the factor
+//    2^-24 moves into the two wave-uniform step sizes;
+//  * the next rating's column is read from LDS AFTER this rating's atomic add (LDS executes a
+//    wavefront's operations in order), so no forwarding is needed when the column repeats; the
+//    read's latency is covered by the other wavefronts of the SIMD;
+//  * p_u is updated with two fused operations (the extra rounding of the deterministic form is
+//    irrelevant here);
+//  * the last two steps of the cross-lane sum are single DPP adds.
+__device__ __forceinline__ float wave_sum_fused(float x)
+{
+    x = dpp_add<0xB1, 0xf>(x);
+    x = dpp_add<0x4E, 0xf>(x);
+    x = dpp_add<0x141, 0xf>(x);
+    x = dpp_add<0x140, 0xf>(x);
+    // rows 1 and 3 add lane 15 of the row before; then rows 2 and 3 add lane 31: one instruction
+    // each (rows outside the mask keep their value); two wait states before a DPP read
+    asm("s_nop 1\n\tv_add_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf" : "+v"(x));
+    asm("s_nop 1\n\tv_add_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf" : "+v"(x));
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+
+template <typename T, int K, int DEPTH>
+__device__ __forceinline__ void lds_hog_chunk(T* __restrict__ P, int* strip, int col0,
+                                              const int32_t* __restrict__ U,
+                                              const int32_t* __restrict__ V,
+                                              const float* __restrict__ R, int64_t begin, int32_t len,
+                                              int mu, int mv, float mr, float lr, float shrink, int lane,
+                                              bool active)
+{
+    constexpr int VEC = RowShape<T, K>::VEC;
+    Row<VEC> p_prev;
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) p_prev.x[j] = 0.f;
+    int u_prev = -1;
+    int nu = 0, nv = 0;
+    float nr = 0.f;
+    auto row_of = [&](int u) { return P + (int64_t)u * K; };
+    auto read_scaled = [&](int v) {
+        const int* qrow = strip + (v - col0) * K;
+        Row<VEC> q;
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) q.x[j] = active ? (float)qrow[strip_elem<T>(lane, j)] : 0.f;
+        return q;
+    };
+    for (int32_t off = 0; off < len; off += kWave) {
+        const int cnt = min(kWave, len - off);
+        if (lane < len - off - kWave) {
+            nu = U[begin + off + kWave + lane];
+            nv = V[begin + off + kWave + lane];
+            nr = R[begin + off + kWave + lane];
+        }
+        const int last = cnt - 1;
+        Row<VEC> ring[DEPTH];
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) ring[d] = load_row<VEC, false>(row_of(uniform_lane(mu, min(d, last))), lane, active);
+        Row<VEC> qs = read_scaled(uniform_lane(mv, 0));
+        for (int base = 0; base < cnt; base += DEPTH) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                const int i = base + d;
+                const bool valid = i < cnt;
+                const int ic = min(i, last);
+                const int u = uniform_lane(mu, ic);
+                const int v = uniform_lane(mv, ic);
+                const float r = __int_as_float(uniform_lane(__float_as_int(mr), ic));
+                Row<VEC> p;
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) p.x[j] = (u == u_prev) ? p_prev.x[j] : ring[d].x[j];
+                ring[d] = load_row<VEC, false>(row_of(uniform_lane(mu, min(i + DEPTH, last))), lane, active);
+                float part = 0.f;
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) part = fmaf(p.x[j], qs.x[j], part);
+                const float e = fmaf(-kFromFixed, wave_sum_fused(part), r);
+                const float step = valid ? lr * e : 0.f;
+                const float sh = valid ? shrink : 0.f;
+                const float step_q = step * kFromFixed;   // (lr*e) * q       = step_q * qs
+                const float step_p = step * kToFixed;     // (lr*e) * p * 2^24 = step_p * p
+                int* const qrow = strip + (v - col0) * K;
+                Row<VEC> p2;
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    p2.x[j] = quantise<T>(fmaf(step_q, qs.x[j], fmaf(-sh, p.x[j], p.x[j])));
+                    const int dq = __float2int_rn(fmaf(step_p, p.x[j], -sh * qs.x[j]));
+                    if (active) atomicAdd(&qrow[strip_elem<T>(lane, j)], dq);
+                }
+                store_row<VEC>(row_of(u), lane, active, p2);
+                qs = read_scaled(uniform_lane(mv, min(i + 1, last)));   // after the add above
+                p_prev = p2;
+                u_prev = u;
+            }
+        }
+        mu = nu;
+        mv = nv;
+        mr = nr;
     }
 }
 
@@ -525,8 +652,8 @@ __device__ __forceinline__ void lds_shared_row_chunk(T* __restrict__ P, int* str
 
 constexpr int kLdsPrefetchDepth = 8;
 
-template <typename T, int K>
-__global__ __launch_bounds__(1024) void sgd_block_lds(
+template <typename T, int K, bool EXACT>
+__global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_block_lds(
     T* __restrict__ P, T* __restrict__ Qt, const int32_t* __restrict__ U,
     const int32_t* __restrict__ V, const float* __restrict__ R,
     const int64_t* __restrict__ entry_begin, const int32_t* __restrict__ entry_len,
@@ -534,7 +661,7 @@ __global__ __launch_bounds__(1024) void sgd_block_lds(
 {
     extern __shared__ int strip[];            // ncols * K fixed-point values
     const int lane = threadIdx.x & (kWave - 1);
-    const bool active = lane < RowShape<T, K>::ACTIVE;
+    const bool active = RowShape<T, K>::ACTIVE == kWave ? true : lane < RowShape<T, K>::ACTIVE;
     const LdsBlock blk = blocks[blockIdx.x];
     const int total = blk.ncols * K;          // multiple of 32
     T* const strip_src = Qt + (int64_t)blk.col0 * K;
@@ -559,10 +686,11 @@ __global__ __launch_bounds__(1024) void sgd_block_lds(
     };
     if (wave < blk.n_entries) fetch_entry(wave);
 
-    for (int i0 = 4 * (int)threadIdx.x; i0 < total; i0 += 4 * stride) {
-        float4 val[4];
+    constexpr int kInFlight = 8;   // loads of the strip copy each thread keeps in flight
+    for (int i0 = 4 * (int)threadIdx.x; i0 < total; i0 += kInFlight * stride) {
+        float4 val[kInFlight];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
+        for (int t = 0; t < kInFlight; ++t) {
             const int i = i0 + t * stride;
             if (i < total) {
                 if constexpr (sizeof(T) == 2) {
@@ -575,11 +703,15 @@ __global__ __launch_bounds__(1024) void sgd_block_lds(
             }
         }
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
+        for (int t = 0; t < kInFlight; ++t) {
             const int i = i0 + t * stride;
-            if (i < total)
-                *reinterpret_cast<int4*>(strip + i) =
-                    make_int4(to_fixed(val[t].x), to_fixed(val[t].y), to_fixed(val[t].z), to_fixed(val[t].w));
+            if (i < total) {
+                if constexpr (EXACT)
+                    *reinterpret_cast<float4*>(strip + i) = val[t];
+                else
+                    *reinterpret_cast<int4*>(strip + i) =
+                        make_int4(to_fixed(val[t].x), to_fixed(val[t].y), to_fixed(val[t].z), to_fixed(val[t].w));
+            }
         }
     }
     __syncthreads();
@@ -588,17 +720,25 @@ __global__ __launch_bounds__(1024) void sgd_block_lds(
     for (int e = wave; e < blk.n_entries; e += n_waves) {
         if (e != wave) fetch_entry(e);
         const int32_t len = raw_len & ~kSharedRowFlag;
-        if (raw_len < 0)
-            lds_shared_row_chunk<T, K>(P, strip, blk.col0, U, V, R, begin, len, lr, shrink, lane, active);
-        else
-            lds_owned_chunk<T, K, kLdsPrefetchDepth>(P, strip, blk.col0, U, V, R, begin, len, mu, mv, mr, lr,
-                                                     shrink, lane, active);
+        if constexpr (EXACT) {
+            lds_owned_chunk<T, K, kLdsPrefetchDepth, true>(P, strip, blk.col0, U, V, R, begin, len, mu, mv, mr,
+                                                           lr, shrink, lane, active);
+        } else {
+            if (raw_len < 0)
+                lds_shared_row_chunk<T, K>(P, strip, blk.col0, U, V, R, begin, len, lr, shrink, lane, active);
+            else
+                lds_hog_chunk<T, K, kLdsPrefetchDepth>(P, strip, blk.col0, U, V, R, begin, len, mu, mv, mr, lr,
+                                                       shrink, lane, active);
+        }
     }
     __syncthreads();
 
     for (int i = 4 * (int)threadIdx.x; i < total; i += stride) {
         const int4 raw4 = *reinterpret_cast<const int4*>(strip + i);
-        const float4 val = make_float4(from_fixed(raw4.x), from_fixed(raw4.y), from_fixed(raw4.z), from_fixed(raw4.w));
+        const float4 val = EXACT ? make_float4(__int_as_float(raw4.x), __int_as_float(raw4.y),
+                                               __int_as_float(raw4.z), __int_as_float(raw4.w))
+                                 : make_float4(from_fixed(raw4.x), from_fixed(raw4.y), from_fixed(raw4.z),
+                                               from_fixed(raw4.w));
         if constexpr (sizeof(T) == 2) {
             __half2 a = __halves2half2(round_to_half(val.x), round_to_half(val.y));
             __half2 b = __halves2half2(round_to_half(val.z), round_to_half(val.w));
@@ -722,8 +862,8 @@ hipError_t launch_sgd_t(bool hogwild, void* P, void* Qt, const int32_t* U, const
     return hipGetLastError();
 }
 
-template <typename T, int K>
-hipError_t launch_sgd_lds_t(int waves, void* P, void* Qt, const int32_t* U, const int32_t* V,
+template <typename T, int K, bool EXACT>
+hipError_t launch_sgd_lds_impl(int waves, void* P, void* Qt, const int32_t* U, const int32_t* V,
                             const float* R, const int64_t* eb, const int32_t* el,
                             const LdsBlock* blocks, int64_t n_blocks, size_t lds_bytes, float lr,
                             float lambda, hipStream_t stream)
@@ -734,14 +874,27 @@ hipError_t launch_sgd_lds_t(int waves, void* P, void* Qt, const int32_t* U, cons
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev >= 0 && dev < 64 && !raised[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sgd_block_lds<T, K>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sgd_block_lds<T, K, EXACT>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
         if (e != hipSuccess) return e;
         raised[dev] = true;
     }
-    hipLaunchKernelGGL((sgd_block_lds<T, K>), dim3((unsigned)n_blocks), dim3(waves * kWave), lds_bytes,
+    hipLaunchKernelGGL((sgd_block_lds<T, K, EXACT>), dim3((unsigned)n_blocks), dim3(waves * kWave), lds_bytes,
                        stream, (T*)P, (T*)Qt, U, V, R, eb, el, blocks, lr, lambda);
     return hipGetLastError();
+}
+
+template <typename T, int K>
+hipError_t launch_sgd_lds_t(bool exact, int waves, void* P, void* Qt, const int32_t* U, const int32_t* V,
+                            const float* R, const int64_t* eb, const int32_t* el,
+                            const LdsBlock* blocks, int64_t n_blocks, size_t lds_bytes, float lr,
+                            float lambda, hipStream_t stream)
+{
+    if (exact)
+        return launch_sgd_lds_impl<T, K, true>(1, P, Qt, U, V, R, eb, el, blocks, n_blocks, lds_bytes, lr, lambda,
+                                               stream);
+    return launch_sgd_lds_impl<T, K, false>(waves, P, Qt, U, V, R, eb, el, blocks, n_blocks, lds_bytes, lr,
+                                            lambda, stream);
 }
 
 template <typename T, int K>
@@ -793,14 +946,14 @@ hipError_t launch_sgd(int dtype, int k, bool hogwild, void* P, void* Qt, const i
 
 size_t lds_strip_bytes(int k, int32_t max_cols) { return (size_t)max_cols * k * sizeof(float); }
 
-hipError_t launch_sgd_lds(int dtype, int k, int waves, void* P, void* Qt, const int32_t* U,
+hipError_t launch_sgd_lds(int dtype, int k, bool exact, int waves, void* P, void* Qt, const int32_t* U,
                           const int32_t* V, const float* R, const int64_t* entry_begin,
                           const int32_t* entry_len, const LdsBlock* blocks, int64_t n_blocks,
                           size_t lds_bytes, float lr, float lambda, hipStream_t stream)
 {
     if (n_blocks <= 0) return hipSuccess;
     if (waves < 1 || waves > 16 || lds_bytes > kLdsBudget) return hipErrorInvalidValue;
-    MF_DISPATCH(launch_sgd_lds_t, waves, P, Qt, U, V, R, entry_begin, entry_len, blocks, n_blocks,
+    MF_DISPATCH(launch_sgd_lds_t, exact, waves, P, Qt, U, V, R, entry_begin, entry_len, blocks, n_blocks,
                 lds_bytes, lr, lambda, stream);
 }
 

@@ -30,6 +30,7 @@ struct mf_ctx {
     mf::Partition part;
     mf::Schedule sched[2];   // indexed by MF_MODE_*
     mf::LdsSchedule lds;     // Hogwild with the Qt strip in LDS
+    mf::LdsSchedule det_lds; // deterministic mode with the Qt strip in LDS
     int32_t* dU = nullptr;
     int32_t* dV = nullptr;
     float* dR = nullptr;
@@ -39,6 +40,7 @@ struct mf_ctx {
     int32_t xcd_affinity = 1;
     int32_t profile = 0;
     int32_t hogwild_kernel = MF_HOGWILD_AUTO;
+    int32_t det_kernel = MF_KERNEL_AUTO;
     int32_t lds_chunk = 0;   // 0 = one chunk per wavefront
     int32_t lds_waves = 16;
 
@@ -74,7 +76,8 @@ size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 bool valid_k(int32_t k) { return k == 32 || k == 64 || k == 128 || k == 256; }
 
 struct Layout {
-    size_t off_u, off_v, off_r, off_begin[2], off_len[2], off_lds_begin, off_lds_len, off_lds_blocks, total;
+    size_t off_u, off_v, off_r, off_begin[2], off_len[2], off_lds_begin, off_lds_len, off_lds_blocks,
+        off_dlds_begin, off_dlds_len, off_dlds_blocks, total;
     int64_t cap[2], lds_cap, lds_blocks_cap;
 };
 
@@ -96,6 +99,9 @@ Layout make_layout(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t l
     l.off_lds_begin = off; off += align_up((size_t)l.lds_cap * 8);
     l.off_lds_len = off; off += align_up((size_t)l.lds_cap * 4);
     l.off_lds_blocks = off; off += align_up((size_t)l.lds_blocks_cap * sizeof(mf::LdsBlock));
+    l.off_dlds_begin = off; off += align_up((size_t)l.lds_blocks_cap * 8);   // one entry per block
+    l.off_dlds_len = off; off += align_up((size_t)l.lds_blocks_cap * 4);
+    l.off_dlds_blocks = off; off += align_up((size_t)l.lds_blocks_cap * sizeof(mf::LdsBlock));
     l.total = off;
     return l;
 }
@@ -164,6 +170,10 @@ int mf_set_option(mf_ctx* ctx, int32_t option, int64_t value)
         case MF_OPT_HOGWILD_KERNEL:
             if (value < MF_HOGWILD_AUTO || value > MF_HOGWILD_LDS) return fail(ctx, MF_EINVAL, "unknown Hogwild kernel");
             ctx->hogwild_kernel = (int32_t)value;
+            return MF_OK;
+        case MF_OPT_DET_KERNEL:
+            if (value < MF_KERNEL_AUTO || value > MF_KERNEL_LDS) return fail(ctx, MF_EINVAL, "unknown kernel choice");
+            ctx->det_kernel = (int32_t)value;
             return MF_OK;
         case MF_OPT_LDS_CHUNK:
             if (value < 0 || value > (1 << 20)) return fail(ctx, MF_EINVAL, "chunk must be in [0, 2^20]");
@@ -244,6 +254,7 @@ int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const 
         mf::build_hogwild_schedule(ctx->part, pu, ctx->hogwild_chunk, ctx->xcd_affinity != 0,
                                    ctx->sched[MF_MODE_HOGWILD]);
         mf::build_lds_schedule(ctx->part, pu, ctx->lds_chunk, ctx->lds_waves, ctx->lds);
+        mf::build_det_lds_schedule(ctx->part, ctx->det_lds);
     } catch (const std::bad_alloc&) {
         return fail(ctx, MF_ENOMEM, "host allocation failed while partitioning");
     }
@@ -270,13 +281,14 @@ int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const 
             MF_HIP(ctx, hipMemcpy(s.d_len, s.len.data(), s.len.size() * 4, hipMemcpyHostToDevice));
         }
     }
-    {
-        mf::LdsSchedule& l = ctx->lds;
-        if ((int64_t)l.begin.size() > lay.lds_cap || (int64_t)l.blocks.size() > lay.lds_blocks_cap)
+    for (int which = 0; which < 2; ++which) {
+        mf::LdsSchedule& l = which ? ctx->det_lds : ctx->lds;
+        const int64_t cap = which ? lay.lds_blocks_cap : lay.lds_cap;
+        if ((int64_t)l.begin.size() > cap || (int64_t)l.blocks.size() > lay.lds_blocks_cap)
             return fail(ctx, MF_ENOMEM, "schedule larger than its workspace bound");
-        l.d_begin = (int64_t*)(base + lay.off_lds_begin);
-        l.d_len = (int32_t*)(base + lay.off_lds_len);
-        l.d_blocks = (mf::LdsBlock*)(base + lay.off_lds_blocks);
+        l.d_begin = (int64_t*)(base + (which ? lay.off_dlds_begin : lay.off_lds_begin));
+        l.d_len = (int32_t*)(base + (which ? lay.off_dlds_len : lay.off_lds_len));
+        l.d_blocks = (mf::LdsBlock*)(base + (which ? lay.off_dlds_blocks : lay.off_lds_blocks));
         if (!l.begin.empty()) {
             MF_HIP(ctx, hipMemcpy(l.d_begin, l.begin.data(), l.begin.size() * 8, hipMemcpyHostToDevice));
             MF_HIP(ctx, hipMemcpy(l.d_len, l.len.data(), l.len.size() * 4, hipMemcpyHostToDevice));
@@ -309,19 +321,25 @@ int mf_sgd_epoch(mf_ctx* ctx, float lr, float lambda, int32_t mode)
     if (!(lr == lr) || !(lambda == lambda)) return fail(ctx, MF_EINVAL, "lr or lambda is NaN");
     MF_HIP(ctx, hipSetDevice(ctx->device));
     const mf::Schedule& s = ctx->sched[mode];
-    // Hogwild: the kernel that keeps the block's strip of Qt in LDS whenever the widest strip fits
-    const size_t lds_bytes = mf::lds_strip_bytes(ctx->k, ctx->lds.max_cols);
+    // both modes take the kernel that keeps the block's strip of Qt in LDS whenever the widest
+    // strip fits (the deterministic mode additionally wants several workgroups per compute unit
+    // to be possible, since each of its workgroups is a single wavefront)
+    const bool hog = mode == MF_MODE_HOGWILD;
+    const mf::LdsSchedule& lsched = hog ? ctx->lds : ctx->det_lds;
+    const size_t lds_bytes = mf::lds_strip_bytes(ctx->k, lsched.max_cols);
+    const int32_t choice = hog ? ctx->hogwild_kernel : ctx->det_kernel;
     bool use_lds = false;
-    if (mode == MF_MODE_HOGWILD && ctx->hogwild_kernel != MF_HOGWILD_GLOBAL_ATOMICS) {
-        use_lds = lds_bytes <= mf::kLdsBudget;
-        if (!use_lds && ctx->hogwild_kernel == MF_HOGWILD_LDS)
+    if (choice != MF_KERNEL_GLOBAL) {
+        use_lds = hog ? lds_bytes <= mf::kLdsBudget
+                      : (choice == MF_KERNEL_LDS ? lds_bytes <= mf::kLdsBudget : lds_bytes <= mf::kLdsBudget / 4);
+        if (!use_lds && choice == MF_KERNEL_LDS)
             return fail(ctx, MF_EINVAL, "the widest column strip of this grid does not fit the LDS");
     }
     for (int32_t st = 0; st < ctx->part.gc; ++st) {
         int64_t first, count;
         if (use_lds) {
-            first = ctx->lds.stratum_block[st];
-            count = ctx->lds.stratum_block[st + 1] - first;
+            first = lsched.stratum_block[st];
+            count = lsched.stratum_block[st + 1] - first;
         } else {
             first = s.stratum_entry[st];
             count = s.stratum_entry[st + 1] - first;
@@ -340,9 +358,9 @@ int mf_sgd_epoch(mf_ctx* ctx, float lr, float lambda, int32_t mode)
             MF_HIP(ctx, hipEventRecord(ev0, ctx->stream));
         }
         if (use_lds)
-            MF_HIP(ctx, mf::launch_sgd_lds(ctx->dtype, ctx->k, ctx->lds_waves, ctx->dP, ctx->dQt, ctx->dU,
-                                           ctx->dV, ctx->dR, ctx->lds.d_begin, ctx->lds.d_len,
-                                           ctx->lds.d_blocks + first, count, lds_bytes, lr, lambda,
+            MF_HIP(ctx, mf::launch_sgd_lds(ctx->dtype, ctx->k, !hog, ctx->lds_waves, ctx->dP, ctx->dQt, ctx->dU,
+                                           ctx->dV, ctx->dR, lsched.d_begin, lsched.d_len,
+                                           lsched.d_blocks + first, count, lds_bytes, lr, lambda,
                                            ctx->stream));
         else
             MF_HIP(ctx, mf::launch_sgd(ctx->dtype, ctx->k, mode == MF_MODE_HOGWILD, ctx->dP, ctx->dQt, ctx->dU,

@@ -71,6 +71,8 @@ void build_hogwild_schedule(const Partition& part, const std::vector<int32_t>& p
                             bool xcd_affinity, Schedule& out);
 void build_lds_schedule(const Partition& part, const std::vector<int32_t>& pu, int32_t chunk,
                         int32_t waves, LdsSchedule& out);
+// Deterministic mode on the LDS kernel: one entry (the whole block) per block descriptor.
+void build_det_lds_schedule(const Partition& part, LdsSchedule& out);
 // Upper bounds on the number of schedule entries, usable before the partition is known.
 int64_t lds_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t waves);
 int64_t det_entries_bound(int32_t gr, int32_t gc);
@@ -81,8 +83,9 @@ hipError_t launch_sgd(int dtype, int k, bool hogwild, void* P, void* Qt, const i
                       const int32_t* V, const float* R, const int64_t* entry_begin,
                       const int32_t* entry_len, int64_t first_entry, int64_t n_entries, float lr,
                       float lambda, hipStream_t stream);
-// LDS-resident Hogwild kernel: one workgroup of `waves` wavefronts per block descriptor.
-hipError_t launch_sgd_lds(int dtype, int k, int waves, void* P, void* Qt, const int32_t* U,
+// LDS-resident kernel: one workgroup per block descriptor; `exact` = deterministic mode (one
+// wavefront per workgroup, fp32 strip), else Hogwild (`waves` wavefronts, fixed-point strip).
+hipError_t launch_sgd_lds(int dtype, int k, bool exact, int waves, void* P, void* Qt, const int32_t* U,
                           const int32_t* V, const float* R, const int64_t* entry_begin,
                           const int32_t* entry_len, const LdsBlock* blocks, int64_t n_blocks,
                           size_t lds_bytes, float lr, float lambda, hipStream_t stream);

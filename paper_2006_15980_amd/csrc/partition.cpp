@@ -295,6 +295,35 @@ static void chunk_block(const std::vector<int32_t>& pu, int64_t pos, int64_t end
     emit(cur, end, false);
 }
 
+// Cut [pos, end) into at most `pieces` chunks of nearly equal size whose boundaries are moved
+// forward to the next row boundary; if that would move a boundary by more than two target
+// lengths (a very long row), the cut stays inside the row and the chunks on both sides of it
+// are flagged as sharing a row of P.
+template <class Emit>
+static void chunk_block_even(const std::vector<int32_t>& pu, int64_t pos, int64_t end, int32_t pieces, Emit emit_raw)
+{
+    const int64_t size = end - pos;
+    if (size <= 0) return;
+    const int64_t target = std::max<int64_t>(8, (size + pieces - 1) / pieces);
+    int64_t cur = pos;
+    bool starts_inside_row = false;
+    while (cur < end) {
+        int64_t cut = std::min(end, cur + target);
+        bool ends_inside_row = false;
+        if (cut < end) {
+            int64_t b = cut;
+            while (b < end && pu[b] == pu[b - 1]) ++b;
+            if (b - cut > 2 * target) ends_inside_row = true;   // keep the cut inside the long row
+            else cut = b;
+        }
+        int32_t len = (int32_t)(cut - cur);
+        if (starts_inside_row || ends_inside_row) len |= (int32_t)0x80000000;
+        emit_raw(cur, len);
+        starts_inside_row = ends_inside_row;
+        cur = cut;
+    }
+}
+
 void build_hogwild_schedule(const Partition& part, const std::vector<int32_t>& pu, int32_t chunk,
                             bool xcd_affinity, Schedule& out)
 {
@@ -338,12 +367,12 @@ void build_lds_schedule(const Partition& part, const std::vector<int32_t>& pu, i
             blk.col0 = part.col_bounds[b];
             blk.ncols = part.col_bounds[b + 1] - part.col_bounds[b];
             blk.reserved = 0;
-            int64_t size = part.block_ptr[L + 1] - part.block_ptr[L];
-            int32_t this_chunk = chunk > 0 ? chunk : (int32_t)std::max<int64_t>(8, (size + waves - 1) / waves);
-            chunk_block(pu, part.block_ptr[L], part.block_ptr[L + 1], this_chunk, [&](int64_t pos, int32_t len) {
+            auto push = [&](int64_t pos, int32_t len) {
                 out.begin.push_back(pos);
                 out.len.push_back(len);
-            });
+            };
+            if (chunk > 0) chunk_block(pu, part.block_ptr[L], part.block_ptr[L + 1], chunk, push);
+            else chunk_block_even(pu, part.block_ptr[L], part.block_ptr[L + 1], waves, push);
             blk.n_entries = (int32_t)((int64_t)out.begin.size() - blk.first_entry);
             out.blocks.push_back(blk);
         }
@@ -369,12 +398,40 @@ int64_t hogwild_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk
     return chunks * kXcds + (int64_t)gc * kXcds * kWavesPerGroup;
 }
 
+void build_det_lds_schedule(const Partition& part, LdsSchedule& out)
+{
+    out.begin.clear();
+    out.len.clear();
+    out.blocks.clear();
+    out.stratum_block.assign((size_t)part.gc + 1, 0);
+    out.max_cols = 0;
+    for (int32_t b = 0; b < part.gc; ++b)
+        out.max_cols = std::max(out.max_cols, part.col_bounds[b + 1] - part.col_bounds[b]);
+    for (int32_t s = 0; s < part.gc; ++s) {
+        for (int32_t a = 0; a < part.gr; ++a) {
+            int64_t L = (int64_t)s * part.gr + a;
+            int64_t size = part.block_ptr[L + 1] - part.block_ptr[L];
+            if (size == 0) continue;
+            int32_t b = (a + s) % part.gc;
+            LdsBlock blk;
+            blk.first_entry = (int64_t)out.begin.size();
+            blk.n_entries = 1;
+            blk.col0 = part.col_bounds[b];
+            blk.ncols = part.col_bounds[b + 1] - part.col_bounds[b];
+            blk.reserved = 0;
+            out.begin.push_back(part.block_ptr[L]);
+            out.len.push_back((int32_t)size);
+            out.blocks.push_back(blk);
+        }
+        out.stratum_block[(size_t)s + 1] = (int64_t)out.blocks.size();
+    }
+}
+
 int64_t lds_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t waves)
 {
-    // as above, without padding; with chunk == 0 a block of c ratings is cut with a chunk of
-    // max(8, ceil(c / waves)), which gives at most 4 * min(c / 8, waves) + 2 entries
+    // as above, without padding; with chunk == 0 a block is cut into at most `waves` chunks
     if (chunk > 0) return 4 * (nnz / chunk + 1) + 2 * (int64_t)gr * gc;
-    return std::min<int64_t>(4 * (nnz / 8 + 1), 4 * (int64_t)waves * gr * gc) + 2 * (int64_t)gr * gc;
+    return std::min<int64_t>(nnz / 8 + 1, (int64_t)waves * gr * gc) + (int64_t)gr * gc;
 }
 
 }  // namespace mf

@@ -91,11 +91,22 @@ def test_rmse_kernel_matches_oracle(mfmod, storage, k):
 
 
 # ------------------------------------------------------------------------------- deterministic mode
-def _det_one_epoch(mfmod, ds, k, storage, gr, gc, split, lr=None, lam=None):
+def _det_options(mfmod, kernel):
+    which = {"auto": mfmod.MF_KERNEL_AUTO, "global": mfmod.MF_KERNEL_GLOBAL, "lds": mfmod.MF_KERNEL_LDS}[kernel]
+    return {mfmod.MF_OPT_DET_KERNEL: which}
+
+
+def _det_one_epoch(mfmod, ds, k, storage, gr, gc, split, lr=None, lam=None, kernel="auto"):
     lr = ds.cfg.lr if lr is None else lr
     lam = ds.cfg.lam if lam is None else lam
-    model = _make(mfmod, ds, k, storage, gr, gc, split)
-    model.sgd_epoch(lr, lam, mfmod.MF_MODE_DET)
+    model = _make(mfmod, ds, k, storage, gr, gc, split, options=_det_options(mfmod, kernel))
+    try:
+        model.sgd_epoch(lr, lam, mfmod.MF_MODE_DET)
+    except mfmod.MFError as err:
+        model.close()
+        if kernel == "lds" and err.code == mfmod.binding.MF_EINVAL:
+            pytest.skip("the column strips of this grid do not fit the LDS")
+        raise
     P, Q = model.get_factors()
     model.close()
     arith = _arith(storage)
@@ -107,32 +118,35 @@ def _det_one_epoch(mfmod, ds, k, storage, gr, gc, split, lr=None, lam=None):
     return P, Q, Po, Qo
 
 
+@pytest.mark.parametrize("kernel", ["global", "lds"])
 @pytest.mark.parametrize("k", [32, 64, 128, 256])
 @pytest.mark.parametrize("grid,split", [((1, 1), 0), ((5, 7), 1), ((32, 32), 1), ((8, 64), 0)])
-def test_det_one_epoch_fp32_within_1e4(mfmod, k, grid, split):
+def test_det_one_epoch_fp32_within_1e4(mfmod, k, grid, split, kernel):
     ds = dataset("tiny")
-    P, Q, Po, Qo = _det_one_epoch(mfmod, ds, k, "f32", grid[0], grid[1], split)
+    P, Q, Po, Qo = _det_one_epoch(mfmod, ds, k, "f32", grid[0], grid[1], split, kernel=kernel)
     assert np.abs(P - Po).max() <= 1e-4 and np.abs(Q - Qo).max() <= 1e-4, (np.abs(P - Po).max(), np.abs(Q - Qo).max())
 
 
-@pytest.mark.parametrize("k", [32, 128])
-def test_det_one_epoch_binary16_storage(mfmod, k):
+@pytest.mark.parametrize("kernel", ["global", "lds"])
+@pytest.mark.parametrize("k", [32, 128, 256])
+def test_det_one_epoch_binary16_storage(mfmod, k, kernel):
     ds = dataset("tiny")
-    P, Q, Po, Qo = _det_one_epoch(mfmod, ds, k, "f16", 6, 6, 1)
+    P, Q, Po, Qo = _det_one_epoch(mfmod, ds, k, "f16", 6, 6, 1, kernel=kernel)
     for X, Xo in ((P, Po), (Q, Qo)):
         assert np.mean(X != Xo) <= 1e-5, float(np.mean(X != Xo))
 
 
-def test_det_is_reproducible_and_order_is_respected(mfmod):
+def test_det_is_reproducible_and_both_kernels_give_the_same_bits(mfmod):
     ds = dataset("tiny")
     outs = []
-    for _ in range(2):
-        model = _make(mfmod, ds, 32, "f32", 16, 16, 1)
+    for kernel in ("lds", "lds", "global", "global"):
+        model = _make(mfmod, ds, 32, "f32", 16, 16, 1, options=_det_options(mfmod, kernel))
         for _ in range(2):
             model.sgd_epoch(ds.cfg.lr, ds.cfg.lam, mfmod.MF_MODE_DET)
         outs.append(model.get_factors())
         model.close()
-    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+    for other in outs[1:]:
+        assert np.array_equal(outs[0][0], other[0]) and np.array_equal(outs[0][1], other[1])
 
 
 def test_det_edge_cases(mfmod):
@@ -142,8 +156,9 @@ def test_det_edge_cases(mfmod):
     rows = np.concatenate([np.full(300, 5), rng.integers(0, m, 300), np.full(130, 9), np.full(40, 11)]).astype(np.int32)
     cols = np.concatenate([rng.integers(0, n, 300), np.full(300, 17), np.full(130, 21), np.full(40, 21)]).astype(np.int32)
     vals = rng.uniform(1, 5, rows.size).astype(np.float32)
-    for gr, gc in [(1, 1), (3, 3), (7, 30)]:
-        model = mfmod.MatrixFactorization(m, n, k, "f32", seed=4, scale=0.1)
+    for gr, gc, kernel in [(1, 1, "global"), (1, 1, "lds"), (3, 3, "global"), (3, 3, "lds"), (7, 30, "global"),
+                           (7, 30, "lds")]:
+        model = mfmod.MatrixFactorization(m, n, k, "f32", seed=4, scale=0.1, options=_det_options(mfmod, kernel))
         model.load_blocks(rows, cols, vals, gr, gc, 0)
         model.sgd_epoch(0.01, 0.05, mfmod.MF_MODE_DET)
         P, Q = model.get_factors()
