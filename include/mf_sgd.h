@@ -43,7 +43,7 @@ enum {
 
 enum { MF_F32 = 0, MF_F16 = 1 };               /* storage type of the factors; arithmetic is fp32 */
 enum { MF_MODE_DET = 0, MF_MODE_HOGWILD = 1 };
-enum { MF_SPLIT_EQUAL_WIDTH = 0, MF_SPLIT_NNZ_BALANCED = 1 };
+enum { MF_SPLIT_EQUAL_WIDTH = 0, MF_SPLIT_NNZ_BALANCED = 1, MF_SPLIT_NNZ_WIDTH_BALANCED = 2 };
 
 /* Tuning options for mf_set_option (all have working defaults). */
 enum {
@@ -100,6 +100,13 @@ int mf_load_blocks_workspace(const mf_ctx* ctx, int64_t nnz, int32_t grid_r, int
  *                      MF_SPLIT_NNZ_BALANCED -- strip bounds chosen so that every strip holds about
  *                                               nnz/G ratings: bounds[a] = the smallest id whose
  *                                               exclusive degree prefix is >= ceil(a*nnz/G).
+ *                      MF_SPLIT_NNZ_WIDTH_BALANCED -- every id x weighs deg(x)*size + nnz (its share
+ *                                               of the ratings plus its share of the axis); with the
+ *                                               exclusive prefix W[x] = S[x]*size + x*nnz, bounds[a]
+ *                                               = the smallest x with W[x] >= ceil(a*2*nnz*size/G).
+ *                                               No strip holds more than about 2*nnz/G ratings nor
+ *                                               spans more than about 2*size/G ids, which bounds
+ *                                               the LDS the Hogwild kernel needs per strip.
  *   d_workspace      : DEVICE, caller-owned, workspace_bytes >= mf_load_blocks_workspace(); must
  *                      stay alive and untouched until the next mf_load_blocks / mf_destroy.
  * Block (a,b) belongs to stratum s = (b-a) mod grid_c and has linear id L = s*grid_r + a; the

@@ -59,6 +59,7 @@
 
 #define MFO_SPLIT_EQUAL_WIDTH 0
 #define MFO_SPLIT_NNZ_BALANCED 1
+#define MFO_SPLIT_NNZ_WIDTH_BALANCED 2
 
 /* ------------------------------------------------------------------------------------ */
 /* binary16 rounding (round to nearest, ties to even), written from the IEEE-754 format: */
@@ -139,6 +140,31 @@ int mfo_bounds_nnz_balanced(const int32_t* idx, int64_t nnz, int64_t size, int32
     return 0;
 }
 
+/* Every id x carries the weight deg(x)*size + nnz (its share of the ratings plus its share of
+ * the axis, both scaled to the common denominator nnz*size); with the exclusive prefix
+ * W[x] = S[x]*size + x*nnz (W[size] = 2*nnz*size), bounds[a] = smallest x with
+ * W[x] >= ceil(a*W[size]/G).  A strip then holds at most about twice its fair share of the
+ * ratings AND spans at most about twice its fair share of the ids.  nnz = 0 counts as 1. */
+int mfo_bounds_nnz_width_balanced(const int32_t* idx, int64_t nnz, int64_t size, int32_t G, int32_t* bounds)
+{
+    int64_t* S = (int64_t*)calloc((size_t)size + 1, sizeof(int64_t));
+    if (!S) return -3;
+    for (int64_t t = 0; t < nnz; ++t) S[idx[t] + 1] += 1;
+    for (int64_t x = 0; x < size; ++x) S[x + 1] += S[x];
+    int64_t unit = nnz > 0 ? nnz : 1;
+    int64_t total = S[size] * size + size * unit;
+    bounds[0] = 0;
+    int64_t x = 0;
+    for (int32_t a = 1; a < G; ++a) {
+        int64_t target = (int64_t)(((__int128)a * total + G - 1) / G);
+        while (x < size && S[x] * size + x * unit < target) ++x;
+        bounds[a] = (int32_t)x;
+    }
+    bounds[G] = (int32_t)size;
+    free(S);
+    return 0;
+}
+
 static int32_t strip_of(const int32_t* bounds, int32_t G, int32_t id)
 {
     /* the strip a with bounds[a] <= id < bounds[a+1] = the largest a in [0,G) with
@@ -192,6 +218,9 @@ int mfo_partition(const int32_t* rows, const int32_t* cols, int64_t nnz, int64_t
     } else if (split == MFO_SPLIT_NNZ_BALANCED) {
         if (mfo_bounds_nnz_balanced(rows, nnz, m, G_r, row_bounds)) return -3;
         if (mfo_bounds_nnz_balanced(cols, nnz, n, G_c, col_bounds)) return -3;
+    } else if (split == MFO_SPLIT_NNZ_WIDTH_BALANCED) {
+        if (mfo_bounds_nnz_width_balanced(rows, nnz, m, G_r, row_bounds)) return -3;
+        if (mfo_bounds_nnz_width_balanced(cols, nnz, n, G_c, col_bounds)) return -3;
     } else return -1;
 
     sort_key* keys = (sort_key*)malloc((size_t)(nnz > 0 ? nnz : 1) * sizeof(sort_key));

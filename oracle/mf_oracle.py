@@ -13,9 +13,10 @@ import numpy as np
 from . import build as _build
 
 ARITH_F64, ARITH_F32, ARITH_F16 = 0, 1, 2
-SPLIT_EQUAL_WIDTH, SPLIT_NNZ_BALANCED = 0, 1
+SPLIT_EQUAL_WIDTH, SPLIT_NNZ_BALANCED, SPLIT_NNZ_WIDTH_BALANCED = 0, 1, 2
 
 __all__ = ["ARITH_F64", "ARITH_F32", "ARITH_F16", "SPLIT_EQUAL_WIDTH", "SPLIT_NNZ_BALANCED",
+           "SPLIT_NNZ_WIDTH_BALANCED", "bounds_nnz_width_balanced",
            "round_f16", "init_factors", "partition", "blocks_independent", "sgd_step",
            "sgd_epoch", "sgd_epoch_omp", "sgd_sweep", "predict", "rating_loss", "rmse",
            "num_threads", "bounds_equal_width", "bounds_nnz_balanced"]
@@ -62,6 +63,14 @@ def bounds_nnz_balanced(idx: np.ndarray, size: int, G: int) -> np.ndarray:
     b = np.empty(G + 1, dtype=np.int32)
     rc = _load().mfo_bounds_nnz_balanced(_p(idx, np.int32), C.c_int64(idx.size), C.c_int64(size),
                                          C.c_int32(G), _p(b, np.int32))
+    assert rc == 0
+    return b
+
+
+def bounds_nnz_width_balanced(idx: np.ndarray, size: int, G: int) -> np.ndarray:
+    b = np.empty(G + 1, dtype=np.int32)
+    rc = _load().mfo_bounds_nnz_width_balanced(_p(idx, np.int32), C.c_int64(idx.size), C.c_int64(size),
+                                               C.c_int32(G), _p(b, np.int32))
     assert rc == 0
     return b
 

@@ -16,7 +16,7 @@ import numpy as np
 MF_OK, MF_EINVAL, MF_ESTATE, MF_ENOMEM, MF_EDEVICE, MF_ERANGE = 0, -1, -2, -3, -4, -5
 MF_F32, MF_F16 = 0, 1
 MF_MODE_DET, MF_MODE_HOGWILD = 0, 1
-MF_SPLIT_EQUAL_WIDTH, MF_SPLIT_NNZ_BALANCED = 0, 1
+MF_SPLIT_EQUAL_WIDTH, MF_SPLIT_NNZ_BALANCED, MF_SPLIT_NNZ_WIDTH_BALANCED = 0, 1, 2
 MF_OPT_HOGWILD_CHUNK, MF_OPT_XCD_AFFINITY, MF_OPT_PROFILE = 1, 2, 3
 MF_OPT_HOGWILD_KERNEL, MF_OPT_LDS_CHUNK, MF_OPT_LDS_WAVES = 4, 5, 6
 MF_OPT_DET_KERNEL = 7

@@ -234,7 +234,7 @@ int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const 
     int rc = check_grid(ctx, nnz, grid_r, grid_c);
     if (rc) return rc;
     if (grid_r > ctx->m || grid_c > ctx->n) return fail(ctx, MF_EINVAL, "grid exceeds the matrix size");
-    if (split != MF_SPLIT_EQUAL_WIDTH && split != MF_SPLIT_NNZ_BALANCED) return fail(ctx, MF_EINVAL, "unknown split rule");
+    if (split < MF_SPLIT_EQUAL_WIDTH || split > MF_SPLIT_NNZ_WIDTH_BALANCED) return fail(ctx, MF_EINVAL, "unknown split rule");
     if (nnz > 0 && (!rows || !cols || !vals)) return fail(ctx, MF_EINVAL, "null rating array");
     if (!d_workspace) return fail(ctx, MF_EINVAL, "null workspace");
     if ((uintptr_t)d_workspace & 255) return fail(ctx, MF_EINVAL, "workspace must be 256-byte aligned");
@@ -462,7 +462,7 @@ int mf_plan_host(const int32_t* rows, const int32_t* cols, int64_t nnz, int64_t 
 {
     if (check_grid(nullptr, nnz, grid_r, grid_c)) return MF_EINVAL;
     if (m < 1 || n < 1 || grid_r > m || grid_c > n) return MF_EINVAL;
-    if (split != MF_SPLIT_EQUAL_WIDTH && split != MF_SPLIT_NNZ_BALANCED) return MF_EINVAL;
+    if (split < MF_SPLIT_EQUAL_WIDTH || split > MF_SPLIT_NNZ_WIDTH_BALANCED) return MF_EINVAL;
     if (mode != MF_MODE_DET && mode != MF_MODE_HOGWILD && mode != MF_PLAN_HOGWILD_LDS) return MF_EINVAL;
     if (chunk < (mode == MF_PLAN_HOGWILD_LDS ? 0 : 1) || (nnz > 0 && (!rows || !cols))) return MF_EINVAL;
     try {

@@ -59,8 +59,11 @@ void equal_width_bounds(int64_t size, int32_t g, std::vector<int32_t>& b)
     for (int32_t a = 0; a <= g; ++a) b[a] = (int32_t)(((int64_t)a * size + g - 1) / g);
 }
 
+// `width_weight` = false: every id weighs its number of ratings.  true: its number of ratings
+// times the axis length plus the number of ratings in total, i.e. its share of the ratings plus
+// its share of the axis, so that a strip is bounded in ratings and in width.
 void balanced_bounds(const int32_t* idx, int64_t nnz, int64_t size, int32_t g, int threads,
-                     std::vector<int32_t>& b)
+                     bool width_weight, std::vector<int32_t>& b)
 {
     // degree histogram with one private histogram per thread
     std::vector<std::vector<int64_t>> priv((size_t)threads);
@@ -70,11 +73,14 @@ void balanced_bounds(const int32_t* idx, int64_t nnz, int64_t size, int32_t g, i
     });
     b.assign((size_t)g + 1, 0);
     b[g] = (int32_t)size;
+    const int64_t unit = nnz > 0 ? nnz : 1;
+    const __int128 total = width_weight ? (__int128)nnz * size + (__int128)size * unit : (__int128)nnz;
     int64_t before = 0;   // ratings with id < x
     int32_t a = 1;
     for (int64_t x = 0; x < size && a < g; ++x) {
-        // strip boundary a sits at the first id whose exclusive prefix reaches ceil(a*nnz/g)
-        while (a < g && before >= ((int64_t)a * nnz + g - 1) / g) b[a++] = (int32_t)x;
+        // strip boundary a sits at the first id whose exclusive weight prefix reaches ceil(a*total/g)
+        const __int128 prefix = width_weight ? (__int128)before * size + (__int128)x * unit : (__int128)before;
+        while (a < g && prefix >= ((__int128)a * total + g - 1) / g) b[a++] = (int32_t)x;
         for (int i = 0; i < threads; ++i)
             if (!priv[i].empty()) before += priv[i][x];
     }
@@ -116,8 +122,9 @@ int build_partition(const int32_t* rows, const int32_t* cols, const float* vals,
         equal_width_bounds(m, gr, out.row_bounds);
         equal_width_bounds(n, gc, out.col_bounds);
     } else {
-        balanced_bounds(rows, nnz, m, gr, threads, out.row_bounds);
-        balanced_bounds(cols, nnz, n, gc, threads, out.col_bounds);
+        const bool width_weight = split == MF_SPLIT_NNZ_WIDTH_BALANCED;
+        balanced_bounds(rows, nnz, m, gr, threads, width_weight, out.row_bounds);
+        balanced_bounds(cols, nnz, n, gc, threads, width_weight, out.col_bounds);
     }
     std::vector<int32_t> row_strip, col_strip;
     strip_table(out.row_bounds, m, row_strip);

@@ -408,13 +408,16 @@ def test_medium_config_full_size(mfmod):
 # ------------------------------------------------------------------------------- configurations 3, 4, 5 (scaled, and full size on request)
 OTHER = {
     # name: (scale for the default run, DET grid, HOGWILD grid, epochs for the default run)
+    # The HOGWILD grids use the split that bounds a strip's width as well as its ratings, fine
+    # enough for the widest column strip to fit the LDS (the LDS kernel is forced, so a strip that
+    # does not fit is an error and not a silent change of kernel).
     "large": (0.02, (64, 64), (32, 32), 8),
-    "xlarge": (0.01, (128, 128), (256, 256), 8),
-    "stress": (0.005, (128, 128), (256, 256), 6),
+    "xlarge": (0.01, (128, 128), (128, 512), 8),
+    "stress": (0.005, (128, 128), (128, 512), 6),
 }
 
 
-def _config_case(mfmod, name, scale, det_grid, hog_grid, epochs):
+def _config_case(mfmod, name, scale, det_grid, hog_grid, epochs, hog_split=2):
     ds = dataset(name, scale)
     cfg = ds.cfg
     print("%s: m=%d n=%d nnz=%d %s, max row/col degree %d/%d" % (cfg.name, cfg.m, cfg.n, ds.rows.size, cfg.storage,
@@ -434,9 +437,10 @@ def _config_case(mfmod, name, scale, det_grid, hog_grid, epochs):
             print("%s binary16: fraction of differing elements %.3g" % (cfg.name, np.mean(X != Xo)), flush=True)
             assert np.mean(X != Xo) <= 1e-5, float(np.mean(X != Xo))
     arith = _arith(cfg.storage)
-    Po, Qo, _ = oracle_train(ds, hog_grid[0], hog_grid[1], 1, epochs, arith=arith)
+    Po, Qo, _ = oracle_train(ds, hog_grid[0], hog_grid[1], hog_split, epochs, arith=arith)
     want = oracle.rmse(Po, Qo, ds.test_rows, ds.test_cols, ds.test_vals)
-    got = _train_gpu(mfmod, ds, cfg.k, cfg.storage, hog_grid[0], hog_grid[1], 1, mfmod.MF_MODE_HOGWILD, epochs)
+    got = _train_gpu(mfmod, ds, cfg.k, cfg.storage, hog_grid[0], hog_grid[1], hog_split, mfmod.MF_MODE_HOGWILD,
+                     epochs, options={mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS})
     print("%s HOGWILD %d epochs: rmse gpu %.6f oracle %.6f" % (cfg.name, epochs, got, want), flush=True)
     assert abs(got - want) <= 0.005 * want, (got, want)
     got_det = _train_gpu(mfmod, ds, cfg.k, cfg.storage, det_grid[0], det_grid[1], 1, mfmod.MF_MODE_DET, epochs)
@@ -450,3 +454,17 @@ def _config_case(mfmod, name, scale, det_grid, hog_grid, epochs):
 def test_other_configs_scaled(mfmod, name):
     scale, det_grid, hog_grid, epochs = OTHER[name]
     _config_case(mfmod, name, scale, det_grid, hog_grid, epochs)
+
+
+FULL_SIZE = {
+    # name: (DET grid, HOGWILD grid, epochs)
+    "large": ((512, 512), (128, 128), 20),
+}
+
+
+@pytest.mark.slow
+@pytest.mark.skipif(not FULL, reason="full-size run: set MF_FULL=1 (takes several minutes, mostly CPU oracle)")
+@pytest.mark.parametrize("name", sorted(FULL_SIZE))
+def test_other_configs_full_size(mfmod, name):
+    det_grid, hog_grid, epochs = FULL_SIZE[name]
+    _config_case(mfmod, name, 1.0, det_grid, hog_grid, epochs)

@@ -48,7 +48,7 @@ def _cases():
     return out
 
 
-@pytest.mark.parametrize("split", [B.MF_SPLIT_EQUAL_WIDTH, B.MF_SPLIT_NNZ_BALANCED])
+@pytest.mark.parametrize("split", [B.MF_SPLIT_EQUAL_WIDTH, B.MF_SPLIT_NNZ_BALANCED, B.MF_SPLIT_NNZ_WIDTH_BALANCED])
 @pytest.mark.parametrize("grid", [(1, 1), (2, 5), (8, 8), (9, 10), (10, 10)])
 def test_host_partition_is_bit_exact_with_the_oracle(split, grid):
     gr, gc = grid
@@ -63,7 +63,7 @@ def test_host_partition_is_bit_exact_with_the_oracle(split, grid):
 
 def test_host_partition_bit_exact_on_a_workload_shaped_case():
     ds = workloads.generate(workloads.scaled(workloads.CONFIGS["large"], 0.003, k=32))
-    for (gr, gc, split) in [(8, 16, 1), (64, 64, 1), (32, 48, 0)]:
+    for (gr, gc, split) in [(8, 16, 1), (64, 64, 1), (32, 48, 0), (16, 96, 2)]:
         plan = B.mf_plan_host(ds.rows, ds.cols, ds.cfg.m, ds.cfg.n, gr, gc, split, B.MF_MODE_HOGWILD)
         perm, bp, rb, cb = oracle.partition(ds.rows, ds.cols, ds.cfg.m, ds.cfg.n, gr, gc, split)
         assert np.array_equal(plan["perm"], perm) and np.array_equal(plan["block_ptr"], bp)
@@ -153,7 +153,8 @@ def test_plan_rejects_bad_arguments():
     with pytest.raises(B.MFError) as e:
         B.mf_plan_host(rows, cols, 3, 5, 1, 1, 0, 0)                 # column 5 out of range
     assert e.value.code == B.MF_ERANGE
-    for args in [(3, 6, 2, 1, 0, 0), (3, 6, 0, 1, 0, 0), (3, 6, 4, 4, 0, 0), (3, 6, 1, 1, 7, 0), (3, 6, 1, 1, 0, 9)]:
+    for args in [(3, 6, 2, 1, 0, 0), (3, 6, 0, 1, 0, 0), (3, 6, 4, 4, 0, 0), (3, 6, 1, 1, 7, 0), (3, 6, 1, 1, 0, 9),
+                 (3, 6, 1, 1, 3, 0)]:
         with pytest.raises(B.MFError) as e:
             B.mf_plan_host(rows, cols, *args)
         assert e.value.code == B.MF_EINVAL, args

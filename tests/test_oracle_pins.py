@@ -264,6 +264,35 @@ def test_partition_nnz_balanced_bounds_and_brute_force():
     assert np.array_equal(perm, perm2) and np.array_equal(bp, bp2)
 
 
+def test_partition_nnz_width_balanced_bounds_and_brute_force():
+    rng = np.random.default_rng(78)
+    m, n, nnz = 64, 50, 3000
+    w = 1.0 / np.arange(1, n + 1) ** 1.3
+    rows = rng.integers(0, m, nnz).astype(np.int32)
+    cols = rng.choice(n, nnz, p=w / w.sum()).astype(np.int32)
+    gr, gc = 4, 10
+    perm, bp, rb, cb = oracle.partition(rows, cols, m, n, gr, gc, oracle.SPLIT_NNZ_WIDTH_BALANCED)
+    for idx, size, G, bounds in ((rows, m, gr, rb), (cols, n, gc, cb)):
+        deg = np.bincount(idx, minlength=size)
+        S = np.concatenate([[0], np.cumsum(deg)])
+        W = [int(S[x]) * size + x * nnz for x in range(size + 1)]        # python integers: exact
+        assert W[size] == 2 * nnz * size
+        for a in range(1, G):
+            target = -(-a * W[size] // G)
+            assert W[bounds[a]] >= target and (bounds[a] == 0 or W[bounds[a] - 1] < target)
+        assert bounds[0] == 0 and bounds[G] == size and (np.diff(bounds) >= 0).all()
+        # a strip is bounded in width and in ratings: twice the fair share plus one id
+        widths = np.diff(bounds)
+        per = np.array([deg[bounds[a]:bounds[a + 1]].sum() for a in range(G)])
+        assert widths.max() <= 2 * size / G + 1
+        assert per.max() <= 2 * nnz / G + deg.max()
+    perm2, bp2 = _py_partition(rows, cols, m, n, gr, gc, rb, cb)
+    assert np.array_equal(perm, perm2) and np.array_equal(bp, bp2)
+    # without ratings the rule degenerates to the uniform division of the axis
+    z = np.zeros(0, np.int32)
+    assert np.array_equal(oracle.bounds_nnz_width_balanced(z, 20, 4), [0, 5, 10, 15, 20])
+
+
 def test_partition_rejects_bad_arguments():
     rows = np.array([0, 1], np.int32)
     cols = np.array([0, 5], np.int32)

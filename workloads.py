@@ -15,11 +15,21 @@ from __future__ import annotations
 
 import dataclasses
 import math
+import os
+import sys
+import time
 from typing import Optional
 
 import numpy as np
 
 BASE_SEED = 20061598
+_T0 = time.time()
+
+
+def _progress(msg: str) -> None:
+    """Stage messages for the large configurations (MF_VERBOSE=1): generation takes minutes."""
+    if os.environ.get("MF_VERBOSE", "0") == "1":
+        print(f"[workloads +{time.time() - _T0:6.1f}s] {msg}", file=sys.stderr, flush=True)
 
 
 @dataclasses.dataclass(frozen=True)
@@ -143,8 +153,9 @@ def _pairs(cfg: Config, total: int, rng: np.random.Generator):
         dcol = _zipf_degrees(n, cfg.alpha_col, total, 0.9 * m, rng)
         keys = np.empty(0, dtype=np.int64)
         want = total
-        for _ in range(64):
+        for rnd in range(64):
             draw = int(want * 1.05) + 1024
+            _progress(f"{cfg.name}: pair round {rnd}, drawing {draw}")
             u = _sample_axis(drow, draw, rng)
             v = _sample_axis(dcol, draw, rng)
             keys = np.unique(np.concatenate([keys, u * n + v]))
@@ -194,7 +205,9 @@ def generate(cfg: Config) -> Dataset:
     rng = np.random.Generator(np.random.Philox(cfg.seed))
     total = cfg.nnz_train + cfg.nnz_test
     u, v = _pairs(cfg, total, rng)
+    _progress(f"{cfg.name}: pairs done, rating values")
     r = _ratings(cfg, u, v, rng)
+    _progress(f"{cfg.name}: values done, holdout split")
     hold = np.zeros(total, dtype=bool)
     hold[rng.choice(total, size=cfg.nnz_test, replace=False)] = True
     tr = ~hold
