@@ -22,7 +22,8 @@ HBM_PEAK_GBS = 8000.0
 # device copy of known size).  Counters cannot be read from inside this process, so the figure is
 # reported only for the exact configuration that was profiled, otherwise null.
 PROFILED_TRAFFIC = {
-    ("medium", 1.0, "hogwild", "128x128", "lds"): 45.60e6,   # profiles/sgd_block_lds_f32_k128_medium.md
+    # (workload, scale, mode, grid, kernel, ring): bytes per launch
+    ("medium", 1.0, "hogwild", "128x128", "lds", 0): 45.60e6,   # profiles/sgd_block_lds_f32_k128_medium.md
 }
 
 
@@ -86,12 +87,13 @@ def main():
     ap.add_argument("--workload", default="medium")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (testing only)")
     ap.add_argument("--mode", default="hogwild", choices=["hogwild", "det"])
-    ap.add_argument("--grid", default="128x128")
+    ap.add_argument("--grid", default="224x224")
     ap.add_argument("--hogwild-kernel", default="auto", choices=["auto", "global_atomics", "lds"])
     ap.add_argument("--lds-chunk", type=int, default=0)
     ap.add_argument("--lds-waves", type=int, default=16)
     ap.add_argument("--chunk", type=int, default=128)
     ap.add_argument("--affinity", type=int, default=1)
+    ap.add_argument("--ring", type=int, default=1, help="1: one launch per epoch (workgroups hand the strips round)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -133,7 +135,7 @@ def main():
              "lds": mf.MF_HOGWILD_LDS}[args.hogwild_kernel]
     opts = {mf.MF_OPT_HOGWILD_CHUNK: args.chunk, mf.MF_OPT_XCD_AFFINITY: args.affinity,
             mf.MF_OPT_HOGWILD_KERNEL: which,
-            mf.MF_OPT_LDS_CHUNK: args.lds_chunk, mf.MF_OPT_LDS_WAVES: args.lds_waves}
+            mf.MF_OPT_LDS_CHUNK: args.lds_chunk, mf.MF_OPT_LDS_WAVES: args.lds_waves, mf.MF_OPT_RING: args.ring}
     model = mf.MatrixFactorization(cfg.m, cfg.n, k, cfg.storage, seed=1, scale=0.1, options=opts)
     t0 = time.perf_counter()
     model.load_blocks(ds.rows, ds.cols, ds.vals, gr, gc, mf.MF_SPLIT_NNZ_BALANCED)
@@ -177,11 +179,11 @@ def main():
         bytes_per_launch = bytes_per_update * nnz * args.steps / launches
         achieved = bytes_per_launch / avg_s / 1e9
         kern = "lds" if (args.mode == "hogwild" and args.hogwild_kernel != "global_atomics") else "chunks"
-        traffic = PROFILED_TRAFFIC.get((args.workload, args.scale, args.mode, args.grid, kern))
+        traffic = PROFILED_TRAFFIC.get((args.workload, args.scale, args.mode, args.grid, kern, args.ring))
         if args.lds_waves != 16 or args.lds_chunk != 0:
             traffic = None
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": "sgd_block_lds<float,128>" if (args.mode == "hogwild" and args.hogwild_kernel != "global_atomics") else "sgd_chunks<float,128>",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": ("sgd_ring_lds<float,128>" if args.ring else "sgd_block_lds<float,128>") if (args.mode == "hogwild" and args.hogwild_kernel != "global_atomics") else "sgd_chunks<float,128>",
                     "avg_launch_us": avg_s * 1e6, "launches_per_step": launches / args.steps,
                     "bytes_per_update": bytes_per_update,
                     "ms_per_step_with_event_brackets": elapsed_events * 1e3 / args.steps}
@@ -192,7 +194,8 @@ def main():
            "data": "synthetic",
            "config": {"workload": f"{cfg.name}: m={cfg.m} n={cfg.n} nnz_train={nnz} k={k} {cfg.storage}",
                       "mode": args.mode, "grid": args.grid, "hogwild_kernel": args.hogwild_kernel,
-                      "lds_chunk": args.lds_chunk, "lds_waves": args.lds_waves, "chunk": args.chunk,
+                      "lds_chunk": args.lds_chunk, "lds_waves": args.lds_waves, "ring": args.ring,
+                      "chunk": args.chunk,
                       "xcd_affinity": args.affinity,
                       "lr": cfg.lr, "lambda": cfg.lam},
            "final_test_rmse": rmse, "load_blocks_s": t_load,

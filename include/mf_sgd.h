@@ -56,7 +56,12 @@ enum {
     MF_OPT_LDS_CHUNK = 5,         /* target ratings per work-list entry of the LDS kernel; 0 (default)*/
                                   /* = the block's ratings divided by MF_OPT_LDS_WAVES               */
     MF_OPT_LDS_WAVES = 6,         /* wavefronts per workgroup of the LDS kernel, 1..16 (default 16)   */
-    MF_OPT_DET_KERNEL = 7         /* MF_KERNEL_AUTO (default), _GLOBAL or _LDS for MF_MODE_DET        */
+    MF_OPT_DET_KERNEL = 7,        /* MF_KERNEL_AUTO (default), _GLOBAL or _LDS for MF_MODE_DET        */
+    MF_OPT_RING = 8,              /* 1 (default): with the LDS kernels, run an epoch as ONE launch in */
+                                  /* which the workgroups hand the column strips round (see           */
+                                  /* mf_sgd_epoch) when all grid_r workgroups fit the device at once; */
+                                  /* 0: always one launch per stratum                                 */
+    MF_OPT_RING_SPIN_LIMIT = 9    /* polls after which a waiting workgroup gives up (default 2^22)    */
 };
 enum { MF_KERNEL_AUTO = 0, MF_KERNEL_GLOBAL = 1, MF_KERNEL_LDS = 2 };
 enum { MF_HOGWILD_AUTO = MF_KERNEL_AUTO, MF_HOGWILD_GLOBAL_ATOMICS = MF_KERNEL_GLOBAL, MF_HOGWILD_LDS = MF_KERNEL_LDS };
@@ -143,7 +148,12 @@ int mf_get_partition(const mf_ctx* ctx, int64_t* perm, int64_t* block_ptr,
  *                                                 (widest column strip) * k * 4 bytes <= 159 KiB;
  *                       MF_HOGWILD_GLOBAL_ATOMICS wavefronts of a whole die share a block and use
  *                                                 atomics in that die's L2 (any grid, slower).
- *                     MF_HOGWILD_AUTO takes the LDS kernel whenever the grid allows it. */
+ *                     MF_HOGWILD_AUTO takes the LDS kernel whenever the grid allows it.
+ * With the LDS kernels and MF_OPT_RING = 1 the epoch is a single launch: workgroup a keeps block
+ * row a, walks the strata in order and waits (bounded) for the workgroup that used its next column
+ * strip last.  The order of the steps, and in MF_MODE_DET every bit of the result, is the same as
+ * with one launch per stratum.  If a wait exceeds its limit all workgroups leave the kernel and
+ * the next mf_sync / mf_rmse returns MF_EDEVICE. */
 int mf_sgd_epoch(mf_ctx* ctx, float lr, float lambda, int32_t mode);
 
 /* RMSE = sqrt(mean (r - p_u.q_v)^2) of the current factors (the quality metric of Section 7).

@@ -652,17 +652,20 @@ __device__ __forceinline__ void lds_shared_row_chunk(T* __restrict__ P, int* str
 
 constexpr int kLdsPrefetchDepth = 8;
 
-template <typename T, int K, bool EXACT>
-__global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_block_lds(
-    T* __restrict__ P, T* __restrict__ Qt, const int32_t* __restrict__ U,
-    const int32_t* __restrict__ V, const float* __restrict__ R,
-    const int64_t* __restrict__ entry_begin, const int32_t* __restrict__ entry_len,
-    const LdsBlock* __restrict__ blocks, float lr, float lambda)
+// Work of one workgroup on one block: copy the strip in, run the block's entries, copy it back.
+// COHERENT: the strip is handed from workgroup to workgroup INSIDE one launch (ring kernel
+// below), possibly across dies whose L2s do not see each other's plain stores; it is then read
+// and written with agent-scope accesses (sc1: past the L2s' non-coherent lines), one dword each.
+template <typename T, int K, bool EXACT, bool COHERENT>
+__device__ __forceinline__ void lds_block_body(int* strip, T* __restrict__ P, T* __restrict__ Qt,
+                                               const int32_t* __restrict__ U, const int32_t* __restrict__ V,
+                                               const float* __restrict__ R,
+                                               const int64_t* __restrict__ entry_begin,
+                                               const int32_t* __restrict__ entry_len, const LdsBlock blk,
+                                               float lr, float lambda)
 {
-    extern __shared__ int strip[];            // ncols * K fixed-point values
     const int lane = threadIdx.x & (kWave - 1);
     const bool active = RowShape<T, K>::ACTIVE == kWave ? true : lane < RowShape<T, K>::ACTIVE;
-    const LdsBlock blk = blocks[blockIdx.x];
     const int total = blk.ncols * K;          // multiple of 32
     T* const strip_src = Qt + (int64_t)blk.col0 * K;
     const int stride = 4 * (int)blockDim.x;
@@ -686,31 +689,58 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_block_lds(
     };
     if (wave < blk.n_entries) fetch_entry(wave);
 
-    constexpr int kInFlight = 8;   // loads of the strip copy each thread keeps in flight
-    for (int i0 = 4 * (int)threadIdx.x; i0 < total; i0 += kInFlight * stride) {
-        float4 val[kInFlight];
+    auto to_strip = [](float x) { return EXACT ? __float_as_int(x) : to_fixed(x); };
+    auto from_strip = [](int x) { return EXACT ? __int_as_float(x) : from_fixed(x); };
+    if constexpr (COHERENT) {
+        // words of the storage type: one fp32 value or one pair of binary16 values each
+        constexpr int kPerWord = sizeof(T) == 2 ? 2 : 1;
+        const unsigned* src = reinterpret_cast<const unsigned*>(strip_src);
+        const int words = total / kPerWord;
+        constexpr int kInFlight = 8;
+        for (int w0 = (int)threadIdx.x; w0 < words; w0 += kInFlight * (int)blockDim.x) {
+            unsigned raw[kInFlight];
 #pragma unroll
-        for (int t = 0; t < kInFlight; ++t) {
-            const int i = i0 + t * stride;
-            if (i < total) {
-                if constexpr (sizeof(T) == 2) {
-                    uint2 raw = *reinterpret_cast<const uint2*>(strip_src + i);
-                    float2 a = unpack_half2(raw.x), b = unpack_half2(raw.y);
-                    val[t] = make_float4(a.x, a.y, b.x, b.y);
-                } else {
-                    val[t] = *reinterpret_cast<const float4*>(strip_src + i);
+            for (int t = 0; t < kInFlight; ++t) {
+                const int w = w0 + t * (int)blockDim.x;
+                if (w < words) raw[t] = load_word<true>(src + w);
+            }
+#pragma unroll
+            for (int t = 0; t < kInFlight; ++t) {
+                const int w = w0 + t * (int)blockDim.x;
+                if (w < words) {
+                    if constexpr (sizeof(T) == 2) {
+                        const float2 f = unpack_half2(raw[t]);
+                        strip[2 * w] = to_strip(f.x);
+                        strip[2 * w + 1] = to_strip(f.y);
+                    } else {
+                        strip[w] = to_strip(__uint_as_float(raw[t]));
+                    }
                 }
             }
         }
+    } else {
+        constexpr int kInFlight = 8;   // loads of the strip copy each thread keeps in flight
+        for (int i0 = 4 * (int)threadIdx.x; i0 < total; i0 += kInFlight * stride) {
+            float4 val[kInFlight];
 #pragma unroll
-        for (int t = 0; t < kInFlight; ++t) {
-            const int i = i0 + t * stride;
-            if (i < total) {
-                if constexpr (EXACT)
-                    *reinterpret_cast<float4*>(strip + i) = val[t];
-                else
+            for (int t = 0; t < kInFlight; ++t) {
+                const int i = i0 + t * stride;
+                if (i < total) {
+                    if constexpr (sizeof(T) == 2) {
+                        uint2 raw = *reinterpret_cast<const uint2*>(strip_src + i);
+                        float2 a = unpack_half2(raw.x), b = unpack_half2(raw.y);
+                        val[t] = make_float4(a.x, a.y, b.x, b.y);
+                    } else {
+                        val[t] = *reinterpret_cast<const float4*>(strip_src + i);
+                    }
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < kInFlight; ++t) {
+                const int i = i0 + t * stride;
+                if (i < total)
                     *reinterpret_cast<int4*>(strip + i) =
-                        make_int4(to_fixed(val[t].x), to_fixed(val[t].y), to_fixed(val[t].z), to_fixed(val[t].w));
+                        make_int4(to_strip(val[t].x), to_strip(val[t].y), to_strip(val[t].z), to_strip(val[t].w));
             }
         }
     }
@@ -733,22 +763,110 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_block_lds(
     }
     __syncthreads();
 
-    for (int i = 4 * (int)threadIdx.x; i < total; i += stride) {
-        const int4 raw4 = *reinterpret_cast<const int4*>(strip + i);
-        const float4 val = EXACT ? make_float4(__int_as_float(raw4.x), __int_as_float(raw4.y),
-                                               __int_as_float(raw4.z), __int_as_float(raw4.w))
-                                 : make_float4(from_fixed(raw4.x), from_fixed(raw4.y), from_fixed(raw4.z),
-                                               from_fixed(raw4.w));
-        if constexpr (sizeof(T) == 2) {
-            __half2 a = __halves2half2(round_to_half(val.x), round_to_half(val.y));
-            __half2 b = __halves2half2(round_to_half(val.z), round_to_half(val.w));
-            uint2 raw;
-            raw.x = *reinterpret_cast<unsigned*>(&a);
-            raw.y = *reinterpret_cast<unsigned*>(&b);
-            *reinterpret_cast<uint2*>(strip_src + i) = raw;
-        } else {
-            *reinterpret_cast<float4*>(strip_src + i) = val;
+    if constexpr (COHERENT) {
+        constexpr int kPerWord = sizeof(T) == 2 ? 2 : 1;
+        unsigned* dst = reinterpret_cast<unsigned*>(strip_src);
+        const int words = total / kPerWord;
+        for (int w = (int)threadIdx.x; w < words; w += (int)blockDim.x) {
+            unsigned raw;
+            if constexpr (sizeof(T) == 2) {
+                __half2 h = __halves2half2(round_to_half(from_strip(strip[2 * w])),
+                                           round_to_half(from_strip(strip[2 * w + 1])));
+                raw = *reinterpret_cast<unsigned*>(&h);
+            } else {
+                raw = __float_as_uint(from_strip(strip[w]));
+            }
+            __hip_atomic_store(dst + w, raw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
+    } else {
+        for (int i = 4 * (int)threadIdx.x; i < total; i += stride) {
+            const int4 raw4 = *reinterpret_cast<const int4*>(strip + i);
+            const float4 val = make_float4(from_strip(raw4.x), from_strip(raw4.y), from_strip(raw4.z),
+                                           from_strip(raw4.w));
+            if constexpr (sizeof(T) == 2) {
+                __half2 a = __halves2half2(round_to_half(val.x), round_to_half(val.y));
+                __half2 b = __halves2half2(round_to_half(val.z), round_to_half(val.w));
+                uint2 raw;
+                raw.x = *reinterpret_cast<unsigned*>(&a);
+                raw.y = *reinterpret_cast<unsigned*>(&b);
+                *reinterpret_cast<uint2*>(strip_src + i) = raw;
+            } else {
+                *reinterpret_cast<float4*>(strip_src + i) = val;
+            }
+        }
+    }
+}
+
+// One launch per stratum: workgroup i works on the i-th non-empty block of the stratum.
+template <typename T, int K, bool EXACT>
+__global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_block_lds(
+    T* __restrict__ P, T* __restrict__ Qt, const int32_t* __restrict__ U,
+    const int32_t* __restrict__ V, const float* __restrict__ R,
+    const int64_t* __restrict__ entry_begin, const int32_t* __restrict__ entry_len,
+    const LdsBlock* __restrict__ blocks, float lr, float lambda)
+{
+    extern __shared__ int strip[];            // ncols * K values (fixed point, or fp32 bits if EXACT)
+    lds_block_body<T, K, EXACT, false>(strip, P, Qt, U, V, R, entry_begin, entry_len, blocks[blockIdx.x], lr,
+                                       lambda);
+}
+
+// One launch per EPOCH: workgroup a keeps block row a for the whole epoch (its rows of P are
+// never touched by anyone else) and walks the strata s = 0 .. grid_c-1 on blocks
+// (a, (a+s) mod grid_c); the column strips of Qt rotate through the workgroups (the rotation of
+// distributed SGD, here between compute units instead of machines).  The only other user of
+// column strip (a+s) mod grid_c is the workgroup of the next block row one stratum earlier, so
+// before stratum s workgroup a waits until done[a+1] >= first + s (the last block row waits
+// for block row 0 having finished stratum s - (grid_c - grid_r) - 1); every workgroup waits
+// also when its own block is empty, which keeps the chain of guarantees unbroken.  `done`
+// counts strata finished since mf_load_blocks (`first` = its value before this epoch).
+// All grid_r workgroups must be resident at once (checked by the host before launching).
+// Every wait is bounded: after spin_limit polls a workgroup raises *abort_flag and leaves, and
+// every waiting workgroup leaves as soon as it sees the flag, so the grid always drains.
+template <typename T, int K, bool EXACT>
+__global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_ring_lds(
+    T* __restrict__ P, T* __restrict__ Qt, const int32_t* __restrict__ U,
+    const int32_t* __restrict__ V, const float* __restrict__ R,
+    const int64_t* __restrict__ entry_begin, const int32_t* __restrict__ entry_len,
+    const LdsBlock* __restrict__ ring_blocks, int grid_r, int grid_c, float lr, float lambda,
+    int* done, int first, int* abort_flag, long long spin_limit)
+{
+    extern __shared__ int strip[];
+    __shared__ int go;
+    const int a = (int)blockIdx.x;
+    const int waits_on = a + 1 < grid_r ? a + 1 : 0;
+    const int lag = a + 1 < grid_r ? 0 : grid_c - grid_r;
+    for (int s = 0; s < grid_c; ++s) {
+        if (threadIdx.x == 0) {
+            int ok = 1;
+            const int need = first + s - lag;
+            if (s - lag > 0) {
+                long long polls = 0;
+                while (__hip_atomic_load(done + waits_on, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < need) {
+                    if (__hip_atomic_load(abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                        ok = 0;
+                        break;
+                    }
+                    if (++polls > spin_limit) {
+                        __hip_atomic_store(abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        ok = 0;
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(4);
+                }
+            }
+            go = ok;
+        }
+        __syncthreads();
+        if (go == 0) return;                       // the whole workgroup leaves together
+        const LdsBlock blk = ring_blocks[(int64_t)s * grid_r + a];
+        if (blk.n_entries > 0)
+            lds_block_body<T, K, EXACT, true>(strip, P, Qt, U, V, R, entry_begin, entry_len, blk, lr, lambda);
+        // every thread's stores of the strip have been acknowledged before the stratum is
+        // reported finished
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (threadIdx.x == 0)
+            __hip_atomic_store(done + a, first + s + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -884,6 +1002,55 @@ hipError_t launch_sgd_lds_impl(int waves, void* P, void* Qt, const int32_t* U, c
     return hipGetLastError();
 }
 
+template <typename T, int K, bool EXACT>
+hipError_t launch_sgd_ring_impl(int waves, bool query_only, int* max_resident, void* P, void* Qt,
+                                const int32_t* U, const int32_t* V, const float* R, const int64_t* eb,
+                                const int32_t* el, const LdsBlock* ring_blocks, int grid_r, int grid_c,
+                                size_t lds_bytes, float lr, float lambda, int* done, int first,
+                                int* abort_flag, long long spin_limit, hipStream_t stream)
+{
+    static bool raised[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64 && !raised[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sgd_ring_lds<T, K, EXACT>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
+        if (e != hipSuccess) return e;
+        raised[dev] = true;
+    }
+    if (query_only) {
+        int per_cu = 0, cus = 0;
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, sgd_ring_lds<T, K, EXACT>, waves * kWave,
+                                                         lds_bytes);
+        if (e != hipSuccess) return e;
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        *max_resident = per_cu * cus;
+        return hipSuccess;
+    }
+    hipLaunchKernelGGL((sgd_ring_lds<T, K, EXACT>), dim3((unsigned)grid_r), dim3(waves * kWave), lds_bytes,
+                       stream, (T*)P, (T*)Qt, U, V, R, eb, el, ring_blocks, grid_r, grid_c, lr, lambda, done,
+                       first, abort_flag, spin_limit);
+    return hipGetLastError();
+}
+
+template <typename T, int K>
+hipError_t launch_sgd_ring_t(bool exact, int waves, bool query_only, int* max_resident, void* P, void* Qt,
+                             const int32_t* U, const int32_t* V, const float* R, const int64_t* eb,
+                             const int32_t* el, const LdsBlock* ring_blocks, int grid_r, int grid_c,
+                             size_t lds_bytes, float lr, float lambda, int* done, int first, int* abort_flag,
+                             long long spin_limit, hipStream_t stream)
+{
+    if (exact)
+        return launch_sgd_ring_impl<T, K, true>(1, query_only, max_resident, P, Qt, U, V, R, eb, el, ring_blocks,
+                                                grid_r, grid_c, lds_bytes, lr, lambda, done, first, abort_flag,
+                                                spin_limit, stream);
+    return launch_sgd_ring_impl<T, K, false>(waves, query_only, max_resident, P, Qt, U, V, R, eb, el, ring_blocks,
+                                             grid_r, grid_c, lds_bytes, lr, lambda, done, first, abort_flag,
+                                             spin_limit, stream);
+}
+
 template <typename T, int K>
 hipError_t launch_sgd_lds_t(bool exact, int waves, void* P, void* Qt, const int32_t* U, const int32_t* V,
                             const float* R, const int64_t* eb, const int32_t* el,
@@ -955,6 +1122,18 @@ hipError_t launch_sgd_lds(int dtype, int k, bool exact, int waves, void* P, void
     if (waves < 1 || waves > 16 || lds_bytes > kLdsBudget) return hipErrorInvalidValue;
     MF_DISPATCH(launch_sgd_lds_t, exact, waves, P, Qt, U, V, R, entry_begin, entry_len, blocks, n_blocks,
                 lds_bytes, lr, lambda, stream);
+}
+
+hipError_t launch_sgd_ring(int dtype, int k, bool exact, int waves, bool query_only, int* max_resident,
+                           void* P, void* Qt, const int32_t* U, const int32_t* V, const float* R,
+                           const int64_t* entry_begin, const int32_t* entry_len, const LdsBlock* ring_blocks,
+                           int grid_r, int grid_c, size_t lds_bytes, float lr, float lambda, int* done,
+                           int first, int* abort_flag, long long spin_limit, hipStream_t stream)
+{
+    if (waves < 1 || waves > 16 || lds_bytes > kLdsBudget || grid_r < 1) return hipErrorInvalidValue;
+    MF_DISPATCH(launch_sgd_ring_t, exact, waves, query_only, max_resident, P, Qt, U, V, R, entry_begin,
+                entry_len, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done, first, abort_flag,
+                spin_limit, stream);
 }
 
 hipError_t launch_rmse(int dtype, int k, const void* P, const void* Qt, const int32_t* U,

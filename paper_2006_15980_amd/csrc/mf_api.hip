@@ -41,6 +41,11 @@ struct mf_ctx {
     int32_t profile = 0;
     int32_t hogwild_kernel = MF_HOGWILD_AUTO;
     int32_t det_kernel = MF_KERNEL_AUTO;
+    int32_t use_ring = 1;                 // one launch per epoch when the grid allows it
+    int64_t spin_limit = (int64_t)1 << 22;
+    int32_t ring_resident[2] = {-1, -1};  // workgroups of the ring kernel the device holds at once, per mode
+    int32_t ring_epochs = 0;              // epochs run by the ring kernel since mf_load_blocks
+    int32_t* d_ring_done = nullptr;       // grid_r counters + 1 abort flag, inside the workspace
     int32_t lds_chunk = 0;   // 0 = one chunk per wavefront
     int32_t lds_waves = 16;
 
@@ -77,7 +82,7 @@ bool valid_k(int32_t k) { return k == 32 || k == 64 || k == 128 || k == 256; }
 
 struct Layout {
     size_t off_u, off_v, off_r, off_begin[2], off_len[2], off_lds_begin, off_lds_len, off_lds_blocks,
-        off_dlds_begin, off_dlds_len, off_dlds_blocks, total;
+        off_dlds_begin, off_dlds_len, off_dlds_blocks, off_ring[2], off_ring_done, total;
     int64_t cap[2], lds_cap, lds_blocks_cap;
 };
 
@@ -102,8 +107,25 @@ Layout make_layout(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t l
     l.off_dlds_begin = off; off += align_up((size_t)l.lds_blocks_cap * 8);   // one entry per block
     l.off_dlds_len = off; off += align_up((size_t)l.lds_blocks_cap * 4);
     l.off_dlds_blocks = off; off += align_up((size_t)l.lds_blocks_cap * sizeof(mf::LdsBlock));
+    for (int which = 0; which < 2; ++which) {
+        l.off_ring[which] = off; off += align_up((size_t)l.lds_blocks_cap * sizeof(mf::LdsBlock));
+    }
+    l.off_ring_done = off; off += align_up(((size_t)gr + 1) * 4);
     l.total = off;
     return l;
+}
+
+// After a synchronisation: did a workgroup of the ring kernel give up waiting?
+int check_ring_abort(mf_ctx* ctx)
+{
+    if (!ctx->loaded || !ctx->d_ring_done || ctx->ring_epochs == 0) return MF_OK;
+    int32_t flag = 0;
+    hipError_t e = hipMemcpy(&flag, ctx->d_ring_done + ctx->part.gr, 4, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail_hip(ctx, "reading the ring kernel's abort flag", e);
+    if (flag != 0)
+        return fail(ctx, MF_EDEVICE, "a workgroup of the one-launch-per-epoch kernel exceeded its wait limit; "
+                                     "the factors are in an undefined state (MF_OPT_RING = 0 avoids this kernel)");
+    return MF_OK;
 }
 
 int check_grid(mf_ctx* ctx, int64_t nnz, int32_t gr, int32_t gc)
@@ -174,6 +196,13 @@ int mf_set_option(mf_ctx* ctx, int32_t option, int64_t value)
         case MF_OPT_DET_KERNEL:
             if (value < MF_KERNEL_AUTO || value > MF_KERNEL_LDS) return fail(ctx, MF_EINVAL, "unknown kernel choice");
             ctx->det_kernel = (int32_t)value;
+            return MF_OK;
+        case MF_OPT_RING:
+            ctx->use_ring = value ? 1 : 0;
+            return MF_OK;
+        case MF_OPT_RING_SPIN_LIMIT:
+            if (value < 1) return fail(ctx, MF_EINVAL, "spin limit must be positive");
+            ctx->spin_limit = value;
             return MF_OK;
         case MF_OPT_LDS_CHUNK:
             if (value < 0 || value > (1 << 20)) return fail(ctx, MF_EINVAL, "chunk must be in [0, 2^20]");
@@ -289,6 +318,8 @@ int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const 
         l.d_begin = (int64_t*)(base + (which ? lay.off_dlds_begin : lay.off_lds_begin));
         l.d_len = (int32_t*)(base + (which ? lay.off_dlds_len : lay.off_lds_len));
         l.d_blocks = (mf::LdsBlock*)(base + (which ? lay.off_dlds_blocks : lay.off_lds_blocks));
+        l.d_ring = (mf::LdsBlock*)(base + lay.off_ring[which]);
+        MF_HIP(ctx, hipMemcpy(l.d_ring, l.ring.data(), l.ring.size() * sizeof(mf::LdsBlock), hipMemcpyHostToDevice));
         if (!l.begin.empty()) {
             MF_HIP(ctx, hipMemcpy(l.d_begin, l.begin.data(), l.begin.size() * 8, hipMemcpyHostToDevice));
             MF_HIP(ctx, hipMemcpy(l.d_len, l.len.data(), l.len.size() * 4, hipMemcpyHostToDevice));
@@ -296,6 +327,10 @@ int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const 
                                   hipMemcpyHostToDevice));
         }
     }
+    ctx->d_ring_done = (int32_t*)(base + lay.off_ring_done);
+    MF_HIP(ctx, hipMemset(ctx->d_ring_done, 0, ((size_t)grid_r + 1) * 4));
+    ctx->ring_epochs = 0;
+    ctx->ring_resident[0] = ctx->ring_resident[1] = -1;
     ctx->loaded = true;
     return MF_OK;
 }
@@ -334,6 +369,44 @@ int mf_sgd_epoch(mf_ctx* ctx, float lr, float lambda, int32_t mode)
                       : (choice == MF_KERNEL_LDS ? lds_bytes <= mf::kLdsBudget : lds_bytes <= mf::kLdsBudget / 4);
         if (!use_lds && choice == MF_KERNEL_LDS)
             return fail(ctx, MF_EINVAL, "the widest column strip of this grid does not fit the LDS");
+    }
+    if (use_lds && ctx->use_ring && ctx->part.nnz > 0) {
+        // one launch for the whole epoch if every block row's workgroup can be resident at once
+        const int m_idx = hog ? 1 : 0;
+        if (ctx->ring_resident[m_idx] < 0) {
+            int resident = 0;
+            MF_HIP(ctx, mf::launch_sgd_ring(ctx->dtype, ctx->k, !hog, ctx->lds_waves, true, &resident, nullptr, nullptr,
+                                            nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, ctx->part.gr,
+                                            ctx->part.gc, lds_bytes, 0.f, 0.f, nullptr, 0, nullptr, 0, ctx->stream));
+            ctx->ring_resident[m_idx] = resident;
+        }
+        if (ctx->part.gr <= ctx->ring_resident[m_idx]) {
+            if ((int64_t)(ctx->ring_epochs + 1) * ctx->part.gc > ((int64_t)1 << 30)) {
+                // the strata counters are about to run out of range: start them again from zero
+                MF_HIP(ctx, hipMemsetAsync(ctx->d_ring_done, 0, (size_t)ctx->part.gr * 4, ctx->stream));
+                ctx->ring_epochs = 0;
+            }
+            hipEvent_t ev0 = nullptr, ev1 = nullptr;
+            if (ctx->profile) {
+                if (ctx->events_used == ctx->events.size()) {
+                    MF_HIP(ctx, hipEventCreate(&ev0));
+                    MF_HIP(ctx, hipEventCreate(&ev1));
+                    ctx->events.push_back({ev0, ev1});
+                }
+                ev0 = ctx->events[ctx->events_used].first;
+                ev1 = ctx->events[ctx->events_used].second;
+                ctx->events_used += 1;
+                MF_HIP(ctx, hipEventRecord(ev0, ctx->stream));
+            }
+            MF_HIP(ctx, mf::launch_sgd_ring(ctx->dtype, ctx->k, !hog, ctx->lds_waves, false, nullptr, ctx->dP, ctx->dQt,
+                                            ctx->dU, ctx->dV, ctx->dR, lsched.d_begin, lsched.d_len, lsched.d_ring,
+                                            ctx->part.gr, ctx->part.gc, lds_bytes, lr, lambda, ctx->d_ring_done,
+                                            ctx->ring_epochs * ctx->part.gc, ctx->d_ring_done + ctx->part.gr,
+                                            (long long)ctx->spin_limit, ctx->stream));
+            if (ctx->profile) MF_HIP(ctx, hipEventRecord(ev1, ctx->stream));
+            ctx->ring_epochs += 1;
+            return MF_OK;
+        }
     }
     for (int32_t st = 0; st < ctx->part.gc; ++st) {
         int64_t first, count;
@@ -394,7 +467,7 @@ int mf_rmse(mf_ctx* ctx, const int32_t* d_rows, const int32_t* d_cols, const flo
     MF_HIP(ctx, hipMemcpyAsync(&sum, d_sum, sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
     MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
     *rmse_out = std::sqrt(sum / (double)count);
-    return MF_OK;
+    return check_ring_abort(ctx);
 }
 
 int mf_sync(mf_ctx* ctx)
@@ -402,7 +475,7 @@ int mf_sync(mf_ctx* ctx)
     if (!ctx) return MF_EINVAL;
     MF_HIP(ctx, hipSetDevice(ctx->device));
     MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    return MF_OK;
+    return check_ring_abort(ctx);
 }
 
 int mf_profile_read(mf_ctx* ctx, double* kernel_ms_out, int64_t* launches_out)

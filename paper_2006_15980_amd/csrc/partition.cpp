@@ -364,6 +364,7 @@ void build_lds_schedule(const Partition& part, const std::vector<int32_t>& pu, i
     out.max_cols = 0;
     for (int32_t b = 0; b < part.gc; ++b)
         out.max_cols = std::max(out.max_cols, part.col_bounds[b + 1] - part.col_bounds[b]);
+    out.ring.assign((size_t)part.gr * part.gc, LdsBlock{0, 0, 0, 0, 0});
     for (int32_t s = 0; s < part.gc; ++s) {
         for (int32_t a = 0; a < part.gr; ++a) {
             int64_t L = (int64_t)s * part.gr + a;
@@ -382,6 +383,7 @@ void build_lds_schedule(const Partition& part, const std::vector<int32_t>& pu, i
             else chunk_block_even(pu, part.block_ptr[L], part.block_ptr[L + 1], waves, push);
             blk.n_entries = (int32_t)((int64_t)out.begin.size() - blk.first_entry);
             out.blocks.push_back(blk);
+            out.ring[(size_t)L] = blk;
         }
         out.stratum_block[(size_t)s + 1] = (int64_t)out.blocks.size();
     }
@@ -414,6 +416,7 @@ void build_det_lds_schedule(const Partition& part, LdsSchedule& out)
     out.max_cols = 0;
     for (int32_t b = 0; b < part.gc; ++b)
         out.max_cols = std::max(out.max_cols, part.col_bounds[b + 1] - part.col_bounds[b]);
+    out.ring.assign((size_t)part.gr * part.gc, LdsBlock{0, 0, 0, 0, 0});
     for (int32_t s = 0; s < part.gc; ++s) {
         for (int32_t a = 0; a < part.gr; ++a) {
             int64_t L = (int64_t)s * part.gr + a;
@@ -429,6 +432,7 @@ void build_det_lds_schedule(const Partition& part, LdsSchedule& out)
             out.begin.push_back(part.block_ptr[L]);
             out.len.push_back((int32_t)size);
             out.blocks.push_back(blk);
+            out.ring[(size_t)L] = blk;
         }
         out.stratum_block[(size_t)s + 1] = (int64_t)out.blocks.size();
     }

@@ -149,6 +149,40 @@ def test_det_is_reproducible_and_both_kernels_give_the_same_bits(mfmod):
         assert np.array_equal(outs[0][0], other[0]) and np.array_equal(outs[0][1], other[1])
 
 
+@pytest.mark.parametrize("storage", ["f32", "f16"])
+@pytest.mark.parametrize("grid", [(5, 7), (16, 16), (8, 64), (33, 40)])
+def test_one_launch_per_epoch_gives_the_same_bits_as_one_launch_per_stratum(mfmod, grid, storage):
+    """Deterministic mode: the ring kernel (MF_OPT_RING = 1) hands the column strips from workgroup
+    to workgroup inside one launch; any strip read too early or from a stale cache line would
+    change bits."""
+    ds = dataset("tiny")
+    outs = []
+    for ring in (0, 1):
+        opts = {mfmod.MF_OPT_DET_KERNEL: mfmod.MF_KERNEL_LDS, mfmod.MF_OPT_RING: ring}
+        model = _make(mfmod, ds, 64, storage, grid[0], grid[1], 2, options=opts)
+        for _ in range(3):
+            model.sgd_epoch(ds.cfg.lr, ds.cfg.lam, mfmod.MF_MODE_DET)
+        model.sync()
+        outs.append(model.get_factors())
+        model.close()
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+
+
+def test_ring_kernel_gives_up_cleanly_when_its_wait_limit_is_tiny(mfmod):
+    """Failure handling forced from the host: with a wait limit of one poll some workgroup finds
+    its neighbour not ready, raises the abort flag, every workgroup leaves, and the next
+    synchronising call reports MF_EDEVICE (the kernel itself ends normally)."""
+    ds = dataset("tiny")
+    opts = {mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS, mfmod.MF_OPT_RING: 1,
+            mfmod.MF_OPT_RING_SPIN_LIMIT: 1}
+    model = _make(mfmod, ds, 128, "f32", 64, 64, 1, options=opts)
+    model.sgd_epoch(ds.cfg.lr, ds.cfg.lam, mfmod.MF_MODE_HOGWILD)
+    with pytest.raises(mfmod.MFError) as e:
+        model.sync()
+    assert e.value.code == mfmod.binding.MF_EDEVICE
+    model.close()
+
+
 def test_det_edge_cases(mfmod):
     rng = np.random.default_rng(3)
     # duplicates of one (u, v), a single long row, a single long column, and empty strata
@@ -231,16 +265,17 @@ def test_tiny_config_det_final_rmse_within_1e3(mfmod):
     assert abs(got - want) <= 1e-3, (got, want)
 
 
-@pytest.mark.parametrize("kernel", ["lds", "global_atomics"])
+@pytest.mark.parametrize("kernel", ["lds", "lds_per_stratum", "global_atomics"])
 @pytest.mark.parametrize("storage", ["f32", "f16"])
 def test_tiny_config_hogwild_final_rmse_within_half_percent(mfmod, kernel, storage):
     ds = dataset("tiny")
     Po, Qo, _ = oracle_train(ds, 8, 8, 1, ds.cfg.epochs, arith=_arith(storage))
     want = oracle.rmse(Po, Qo, ds.test_rows, ds.test_cols, ds.test_vals)
-    which = mfmod.MF_HOGWILD_LDS if kernel == "lds" else mfmod.MF_HOGWILD_GLOBAL_ATOMICS
+    which = mfmod.MF_HOGWILD_GLOBAL_ATOMICS if kernel == "global_atomics" else mfmod.MF_HOGWILD_LDS
     got = _train_gpu(mfmod, ds, ds.cfg.k, storage, 8, 8, 1, mfmod.MF_MODE_HOGWILD, ds.cfg.epochs,
                      options={mfmod.MF_OPT_HOGWILD_CHUNK: 32, mfmod.MF_OPT_LDS_CHUNK: 16,
-                              mfmod.MF_OPT_HOGWILD_KERNEL: which})
+                              mfmod.MF_OPT_HOGWILD_KERNEL: which,
+                              mfmod.MF_OPT_RING: 0 if kernel == "lds_per_stratum" else 1})
     print("tiny HOGWILD %s %s: rmse gpu %.6f oracle %.6f" % (kernel, storage, got, want), flush=True)
     assert abs(got - want) <= 0.005 * want, (got, want)
 
@@ -385,7 +420,8 @@ def test_medium_config_scaled_det_and_hogwild(mfmod):
 
 def test_medium_config_full_size(mfmod):
     """Configuration 2 at its full size, in the launch configuration the benchmark times
-    (HOGWILD, 128 x 128 grid, LDS kernel) plus the deterministic mode on a fine grid."""
+    (HOGWILD, 224 x 224 grid, LDS kernel, one launch per epoch) plus the deterministic mode on a
+    fine grid."""
     ds = dataset("medium")
     k = ds.cfg.k
     print("medium: max row/col degree", ds.max_row_degree, ds.max_col_degree, flush=True)
@@ -394,9 +430,10 @@ def test_medium_config_full_size(mfmod):
     print("medium DET one epoch: max|dP| %.3g max|dQ| %.3g" % (dP, dQ), flush=True)
     assert dP <= 1e-4 and dQ <= 1e-4
     epochs = ds.cfg.epochs if FULL else 6
-    Po, Qo, _ = oracle_train(ds, 128, 128, 1, epochs)
+    Po, Qo, _ = oracle_train(ds, 224, 224, 1, epochs)
     want = oracle.rmse(Po, Qo, ds.test_rows, ds.test_cols, ds.test_vals)
-    got = _train_gpu(mfmod, ds, k, "f32", 128, 128, 1, mfmod.MF_MODE_HOGWILD, epochs)
+    got = _train_gpu(mfmod, ds, k, "f32", 224, 224, 1, mfmod.MF_MODE_HOGWILD, epochs,
+                     options={mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS})
     print("medium HOGWILD %d epochs: rmse gpu %.6f oracle %.6f" % (epochs, got, want), flush=True)
     assert abs(got - want) <= 0.005 * want, (got, want)
     got_det = _train_gpu(mfmod, ds, k, "f32", 8, 8, 1, mfmod.MF_MODE_DET, 1)
