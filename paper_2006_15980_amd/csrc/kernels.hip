@@ -401,6 +401,24 @@ __device__ __forceinline__ Row<VEC> strip_read(const int* qrow, int lane, bool a
     return q;
 }
 
+// The rows of P of the first DEPTH ratings of a batch, requested ahead of their use.
+template <int VEC, int DEPTH>
+struct RowRing {
+    Row<VEC> r[DEPTH];
+};
+
+template <typename T, int K, int DEPTH>
+__device__ __forceinline__ RowRing<RowShape<T, K>::VEC, DEPTH> request_first_rows(const T* __restrict__ P, int mu,
+                                                                                  int cnt, int lane, bool active)
+{
+    constexpr int VEC = RowShape<T, K>::VEC;
+    RowRing<VEC, DEPTH> ring;
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d)
+        ring.r[d] = load_row<VEC, false>(P + (int64_t)uniform_lane(mu, min(d, cnt - 1)) * K, lane, active);
+    return ring;
+}
+
 // A chunk whose rows of P belong to this wavefront alone.  Rows of P are cold (each is visited by
 // one wavefront per launch), so their latency is hidden by requesting the row of the rating DEPTH
 // positions ahead; every rating issues the same memory operations (one row request, one row
@@ -415,10 +433,12 @@ __device__ __forceinline__ void lds_owned_chunk(T* __restrict__ P, int* strip, i
                                                 const int32_t* __restrict__ U,
                                                 const int32_t* __restrict__ V,
                                                 const float* __restrict__ R, int64_t begin,
-                                                int32_t len, int mu, int mv, float mr, float lr,
+                                                int32_t len, int mu, int mv, float mr,
+                                                RowRing<RowShape<T, K>::VEC, DEPTH> first_rows, float lr,
                                                 float shrink, int lane, bool active)
 {
-    // mu, mv, mr: the first batch of the chunk (rating `lane` of it), already loaded by the caller
+    // mu, mv, mr: the first batch of the chunk (rating `lane` of it), already loaded by the caller;
+    // first_rows: the rows of P of its first DEPTH ratings, already requested by the caller
     constexpr int VEC = RowShape<T, K>::VEC;
     Row<VEC> p_prev;
 #pragma unroll
@@ -436,9 +456,14 @@ __device__ __forceinline__ void lds_owned_chunk(T* __restrict__ P, int* strip, i
         }
         const int last = cnt - 1;
         Row<VEC> ring[DEPTH];
+        if (off == 0) {
 #pragma unroll
-        for (int d = 0; d < DEPTH; ++d)
-            ring[d] = load_row<VEC, false>(P + (int64_t)uniform_lane(mu, min(d, last)) * K, lane, active);
+            for (int d = 0; d < DEPTH; ++d) ring[d] = first_rows.r[d];
+        } else {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d)
+                ring[d] = load_row<VEC, false>(P + (int64_t)uniform_lane(mu, min(d, last)) * K, lane, active);
+        }
         int v_next = uniform_lane(mv, 0);
         Row<VEC> q_next = strip_read<T, VEC, EXACT>(strip + (v_next - col0) * K, lane, active);
         for (int base = 0; base < cnt; base += DEPTH) {
@@ -528,8 +553,9 @@ __device__ __forceinline__ void lds_hog_chunk(T* __restrict__ P, int* strip, int
                                               const int32_t* __restrict__ U,
                                               const int32_t* __restrict__ V,
                                               const float* __restrict__ R, int64_t begin, int32_t len,
-                                              int mu, int mv, float mr, float lr, float shrink, int lane,
-                                              bool active)
+                                              int mu, int mv, float mr,
+                                              RowRing<RowShape<T, K>::VEC, DEPTH> first_rows, float lr,
+                                              float shrink, int lane, bool active)
 {
     constexpr int VEC = RowShape<T, K>::VEC;
     Row<VEC> p_prev;
@@ -555,8 +581,14 @@ __device__ __forceinline__ void lds_hog_chunk(T* __restrict__ P, int* strip, int
         }
         const int last = cnt - 1;
         Row<VEC> ring[DEPTH];
+        if (off == 0) {
 #pragma unroll
-        for (int d = 0; d < DEPTH; ++d) ring[d] = load_row<VEC, false>(row_of(uniform_lane(mu, min(d, last))), lane, active);
+            for (int d = 0; d < DEPTH; ++d) ring[d] = first_rows.r[d];
+        } else {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d)
+                ring[d] = load_row<VEC, false>(row_of(uniform_lane(mu, min(d, last))), lane, active);
+        }
         Row<VEC> qs = read_scaled(uniform_lane(mv, 0));
         for (int base = 0; base < cnt; base += DEPTH) {
 #pragma unroll
@@ -656,13 +688,17 @@ constexpr int kLdsPrefetchDepth = 8;
 // COHERENT: the strip is handed from workgroup to workgroup INSIDE one launch (ring kernel
 // below), possibly across dies whose L2s do not see each other's plain stores; it is then read
 // and written with agent-scope accesses (sc1: past the L2s' non-coherent lines), one dword each.
-template <typename T, int K, bool EXACT, bool COHERENT>
-__device__ __forceinline__ void lds_block_body(int* strip, T* __restrict__ P, T* __restrict__ Qt,
+// `before_strip()` is called after the block's first ratings and rows of P have been requested
+// and before the strip is read: the ring kernel waits there for the strip's previous user
+// (returning false means "give up": the workgroup leaves); everything requested before it is
+// independent of the strip.
+template <typename T, int K, bool EXACT, bool COHERENT, class BeforeStrip>
+__device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T* __restrict__ Qt,
                                                const int32_t* __restrict__ U, const int32_t* __restrict__ V,
                                                const float* __restrict__ R,
                                                const int64_t* __restrict__ entry_begin,
                                                const int32_t* __restrict__ entry_len, const LdsBlock blk,
-                                               float lr, float lambda)
+                                               float lr, float lambda, BeforeStrip before_strip)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const bool active = RowShape<T, K>::ACTIVE == kWave ? true : lane < RowShape<T, K>::ACTIVE;
@@ -687,7 +723,19 @@ __device__ __forceinline__ void lds_block_body(int* strip, T* __restrict__ P, T*
             mr = R[begin + lane];
         }
     };
-    if (wave < blk.n_entries) fetch_entry(wave);
+    constexpr int VEC = RowShape<T, K>::VEC;
+    RowRing<VEC, kLdsPrefetchDepth> first_rows;
+#pragma unroll
+    for (int d = 0; d < kLdsPrefetchDepth; ++d)
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) first_rows.r[d].x[j] = 0.f;
+    if (wave < blk.n_entries) {
+        fetch_entry(wave);
+        if (EXACT || raw_len > 0)
+            first_rows = request_first_rows<T, K, kLdsPrefetchDepth>(P, mu, min(kWave, raw_len & ~kSharedRowFlag), lane,
+                                                                     active);
+    }
+    if (!before_strip()) return false;
 
     auto to_strip = [](float x) { return EXACT ? __float_as_int(x) : to_fixed(x); };
     auto from_strip = [](int x) { return EXACT ? __int_as_float(x) : from_fixed(x); };
@@ -696,7 +744,7 @@ __device__ __forceinline__ void lds_block_body(int* strip, T* __restrict__ P, T*
         constexpr int kPerWord = sizeof(T) == 2 ? 2 : 1;
         const unsigned* src = reinterpret_cast<const unsigned*>(strip_src);
         const int words = total / kPerWord;
-        constexpr int kInFlight = 8;
+        constexpr int kInFlight = EXACT ? 16 : 8;   // a deterministic workgroup is a single wavefront
         for (int w0 = (int)threadIdx.x; w0 < words; w0 += kInFlight * (int)blockDim.x) {
             unsigned raw[kInFlight];
 #pragma unroll
@@ -748,17 +796,22 @@ __device__ __forceinline__ void lds_block_body(int* strip, T* __restrict__ P, T*
 
     const float shrink = lr * lambda;
     for (int e = wave; e < blk.n_entries; e += n_waves) {
-        if (e != wave) fetch_entry(e);
+        if (e != wave) {
+            fetch_entry(e);
+            if (EXACT || raw_len > 0)
+                first_rows = request_first_rows<T, K, kLdsPrefetchDepth>(P, mu, min(kWave, raw_len & ~kSharedRowFlag),
+                                                                         lane, active);
+        }
         const int32_t len = raw_len & ~kSharedRowFlag;
         if constexpr (EXACT) {
             lds_owned_chunk<T, K, kLdsPrefetchDepth, true>(P, strip, blk.col0, U, V, R, begin, len, mu, mv, mr,
-                                                           lr, shrink, lane, active);
+                                                           first_rows, lr, shrink, lane, active);
         } else {
             if (raw_len < 0)
                 lds_shared_row_chunk<T, K>(P, strip, blk.col0, U, V, R, begin, len, lr, shrink, lane, active);
             else
-                lds_hog_chunk<T, K, kLdsPrefetchDepth>(P, strip, blk.col0, U, V, R, begin, len, mu, mv, mr, lr,
-                                                       shrink, lane, active);
+                lds_hog_chunk<T, K, kLdsPrefetchDepth>(P, strip, blk.col0, U, V, R, begin, len, mu, mv, mr,
+                                                       first_rows, lr, shrink, lane, active);
         }
     }
     __syncthreads();
@@ -795,6 +848,7 @@ __device__ __forceinline__ void lds_block_body(int* strip, T* __restrict__ P, T*
             }
         }
     }
+    return true;
 }
 
 // One launch per stratum: workgroup i works on the i-th non-empty block of the stratum.
@@ -807,7 +861,7 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_block_lds(
 {
     extern __shared__ int strip[];            // ncols * K values (fixed point, or fp32 bits if EXACT)
     lds_block_body<T, K, EXACT, false>(strip, P, Qt, U, V, R, entry_begin, entry_len, blocks[blockIdx.x], lr,
-                                       lambda);
+                                       lambda, [] { return true; });
 }
 
 // One launch per EPOCH: workgroup a keeps block row a for the whole epoch (its rows of P are
@@ -836,31 +890,40 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_ring_lds(
     const int waits_on = a + 1 < grid_r ? a + 1 : 0;
     const int lag = a + 1 < grid_r ? 0 : grid_c - grid_r;
     for (int s = 0; s < grid_c; ++s) {
-        if (threadIdx.x == 0) {
-            int ok = 1;
-            const int need = first + s - lag;
-            if (s - lag > 0) {
-                long long polls = 0;
-                while (__hip_atomic_load(done + waits_on, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < need) {
-                    if (__hip_atomic_load(abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
-                        ok = 0;
-                        break;
+        // wait (bounded) until the previous user of this stratum's column strip has reported it
+        // finished; returns false when the workgroup has to leave
+        auto wait_for_strip = [&]() -> bool {
+            if (threadIdx.x == 0) {
+                int ok = 1;
+                const int need = first + s - lag;
+                if (s - lag > 0) {
+                    long long polls = 0;
+                    while (__hip_atomic_load(done + waits_on, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < need) {
+                        if (__hip_atomic_load(abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                            ok = 0;
+                            break;
+                        }
+                        if (++polls > spin_limit) {
+                            __hip_atomic_store(abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            ok = 0;
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(2);
                     }
-                    if (++polls > spin_limit) {
-                        __hip_atomic_store(abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        ok = 0;
-                        break;
-                    }
-                    __builtin_amdgcn_s_sleep(4);
                 }
+                go = ok;
             }
-            go = ok;
-        }
-        __syncthreads();
-        if (go == 0) return;                       // the whole workgroup leaves together
+            __syncthreads();
+            return go != 0;                        // the same answer in every thread of the workgroup
+        };
         const LdsBlock blk = ring_blocks[(int64_t)s * grid_r + a];
+        bool ok;
         if (blk.n_entries > 0)
-            lds_block_body<T, K, EXACT, true>(strip, P, Qt, U, V, R, entry_begin, entry_len, blk, lr, lambda);
+            ok = lds_block_body<T, K, EXACT, true>(strip, P, Qt, U, V, R, entry_begin, entry_len, blk, lr, lambda,
+                                                   wait_for_strip);
+        else
+            ok = wait_for_strip();   // an empty block still waits: it passes the guarantee on
+        if (!ok) return;
         // every thread's stores of the strip have been acknowledged before the stratum is
         // reported finished
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
