@@ -49,7 +49,7 @@ def load_dataset(name, factor):
     return ds
 
 
-def cpu_baseline(ds, gr, gc, k):
+def cpu_baseline(ds, gr, gc, k, split):
     """The oracle as it stands, timed on the host cores: one epoch with the independent blocks
     of every stratum on OpenMP threads (bit-identical to the serial order), and the serial
     oracle on a prefix of the strata."""
@@ -58,7 +58,7 @@ def cpu_baseline(ds, gr, gc, k):
     import oracle
 
     cfg = ds.cfg
-    perm, bp, _, _ = oracle.partition(ds.rows, ds.cols, cfg.m, cfg.n, gr, gc, oracle.SPLIT_NNZ_BALANCED)
+    perm, bp, _, _ = oracle.partition(ds.rows, ds.cols, cfg.m, cfg.n, gr, gc, split)
     P = oracle.init_factors(cfg.m * k, 1, 0, 0.1).reshape(cfg.m, k)
     Q = oracle.init_factors(cfg.n * k, 1, 1, 0.1).reshape(cfg.n, k)
     t0 = time.perf_counter()
@@ -91,8 +91,9 @@ def main():
     ap.add_argument("--hogwild-kernel", default="auto", choices=["auto", "global_atomics", "lds"])
     ap.add_argument("--lds-chunk", type=int, default=0)
     ap.add_argument("--lds-waves", type=int, default=16)
-    ap.add_argument("--chunk", type=int, default=128)
+    ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--affinity", type=int, default=1)
+    ap.add_argument("--split", type=int, default=1, help="0 equal width, 1 ratings balanced, 2 ratings and width balanced")
     ap.add_argument("--ring", type=int, default=1, help="1: one launch per epoch (workgroups hand the strips round)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
@@ -138,7 +139,7 @@ def main():
             mf.MF_OPT_LDS_CHUNK: args.lds_chunk, mf.MF_OPT_LDS_WAVES: args.lds_waves, mf.MF_OPT_RING: args.ring}
     model = mf.MatrixFactorization(cfg.m, cfg.n, k, cfg.storage, seed=1, scale=0.1, options=opts)
     t0 = time.perf_counter()
-    model.load_blocks(ds.rows, ds.cols, ds.vals, gr, gc, mf.MF_SPLIT_NNZ_BALANCED)
+    model.load_blocks(ds.rows, ds.cols, ds.vals, gr, gc, args.split)
     t_load = time.perf_counter() - t0
     tr, tc, tv = model.to_device(ds.test_rows, ds.test_cols, ds.test_vals)
     nnz = ds.rows.size
@@ -180,7 +181,7 @@ def main():
         achieved = bytes_per_launch / avg_s / 1e9
         kern = "lds" if (args.mode == "hogwild" and args.hogwild_kernel != "global_atomics") else "chunks"
         traffic = PROFILED_TRAFFIC.get((args.workload, args.scale, args.mode, args.grid, kern, args.ring))
-        if args.lds_waves != 16 or args.lds_chunk != 0:
+        if args.lds_waves != 16 or args.lds_chunk != 0 or args.split != 1:
             traffic = None
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": ("sgd_ring_lds<float,128>" if args.ring else "sgd_block_lds<float,128>") if (args.mode == "hogwild" and args.hogwild_kernel != "global_atomics") else "sgd_chunks<float,128>",
@@ -193,7 +194,7 @@ def main():
            "vs_baseline": None, "dtype": "f32" if cfg.storage == "f32" else "f16 storage / f32 math",
            "data": "synthetic",
            "config": {"workload": f"{cfg.name}: m={cfg.m} n={cfg.n} nnz_train={nnz} k={k} {cfg.storage}",
-                      "mode": args.mode, "grid": args.grid, "hogwild_kernel": args.hogwild_kernel,
+                      "mode": args.mode, "grid": args.grid, "split": args.split, "hogwild_kernel": args.hogwild_kernel,
                       "lds_chunk": args.lds_chunk, "lds_waves": args.lds_waves, "ring": args.ring,
                       "chunk": args.chunk,
                       "xcd_affinity": args.affinity,
@@ -203,7 +204,7 @@ def main():
            "hbm_roofline_frac": value * bytes_per_update / 1e9 / HBM_PEAK_GBS,
            "roofline": roofline}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(ds, gr, gc, k)
+        out["cpu_baseline"] = cpu_baseline(ds, gr, gc, k, args.split)
     print(json.dumps(out))
 
 

@@ -47,7 +47,9 @@ enum { MF_SPLIT_EQUAL_WIDTH = 0, MF_SPLIT_NNZ_BALANCED = 1, MF_SPLIT_NNZ_WIDTH_B
 
 /* Tuning options for mf_set_option (all have working defaults). */
 enum {
-    MF_OPT_HOGWILD_CHUNK = 1,     /* target ratings per wavefront in HOGWILD mode (default 128)      */
+    MF_OPT_HOGWILD_CHUNK = 1,     /* target ratings per wavefront of the L2-atomics Hogwild kernel;   */
+                                  /* 0 (default) = the block's ratings divided by MF_OPT_LDS_WAVES,   */
+                                  /* which bounds how many wavefronts change one column concurrently */
     MF_OPT_XCD_AFFINITY = 2,      /* 1 (default): all wavefronts working on one block are placed on  */
                                   /* one XCD; 0: spread over all XCDs                                 */
     MF_OPT_PROFILE = 3,           /* 1: time every SGD kernel launch with HIP events (see below)     */

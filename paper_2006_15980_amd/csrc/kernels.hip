@@ -684,10 +684,14 @@ __device__ __forceinline__ void lds_shared_row_chunk(T* __restrict__ P, int* str
 
 constexpr int kLdsPrefetchDepth = 8;
 
+typedef unsigned int uint4_t __attribute__((ext_vector_type(4)));
+constexpr int kRawBufferFlags = 0x00020000;   // word 3 of a raw (untyped, unswizzled) buffer descriptor on gfx9
+constexpr int kCachePolicySc1 = 16;           // auxiliary operand of the buffer intrinsics: bit 4 = sc1
+
 // Work of one workgroup on one block: copy the strip in, run the block's entries, copy it back.
 // COHERENT: the strip is handed from workgroup to workgroup INSIDE one launch (ring kernel
 // below), possibly across dies whose L2s do not see each other's plain stores; it is then read
-// and written with agent-scope accesses (sc1: past the L2s' non-coherent lines), one dword each.
+// and written with agent-scope accesses (sc1: past the L2s' non-coherent lines).
 // `before_strip()` is called after the block's first ratings and rows of P have been requested
 // and before the strip is read: the ring kernel waits there for the strip's previous user
 // (returning false means "give up": the workgroup leaves); everything requested before it is
@@ -739,12 +743,14 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
 
     auto to_strip = [](float x) { return EXACT ? __float_as_int(x) : to_fixed(x); };
     auto from_strip = [](int x) { return EXACT ? __int_as_float(x) : from_fixed(x); };
-    if constexpr (COHERENT) {
-        // words of the storage type: one fp32 value or one pair of binary16 values each
+    if constexpr (COHERENT && !EXACT) {
+        // 1024 threads: one 32-bit word each (one fp32 value or one pair of binary16 values); wider
+        // pieces were measured 5 % slower per epoch here, and faster for the 64-thread workgroups
+        // of the deterministic mode below
         constexpr int kPerWord = sizeof(T) == 2 ? 2 : 1;
         const unsigned* src = reinterpret_cast<const unsigned*>(strip_src);
         const int words = total / kPerWord;
-        constexpr int kInFlight = EXACT ? 16 : 8;   // a deterministic workgroup is a single wavefront
+        constexpr int kInFlight = 8;
         for (int w0 = (int)threadIdx.x; w0 < words; w0 += kInFlight * (int)blockDim.x) {
             unsigned raw[kInFlight];
 #pragma unroll
@@ -762,6 +768,40 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
                         strip[2 * w + 1] = to_strip(f.y);
                     } else {
                         strip[w] = to_strip(__uint_as_float(raw[t]));
+                    }
+                }
+            }
+        }
+    } else if constexpr (COHERENT) {
+        // 16-byte pieces (4 fp32 values or 8 binary16 values) through a raw buffer descriptor of
+        // the strip with the agent-scope cache policy (sc1)
+        constexpr int kPerPiece = 16 / (int)sizeof(T);
+        const int pieces = total / kPerPiece;
+        const __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc((void*)strip_src, 0, total * (int)sizeof(T), kRawBufferFlags);
+        constexpr int kInFlight = 8;
+        for (int p0 = (int)threadIdx.x; p0 < pieces; p0 += kInFlight * (int)blockDim.x) {
+            uint4_t raw[kInFlight];
+#pragma unroll
+            for (int t = 0; t < kInFlight; ++t) {
+                const int pc = p0 + t * (int)blockDim.x;
+                if (pc < pieces) raw[t] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, pc * 16, 0, kCachePolicySc1);
+            }
+#pragma unroll
+            for (int t = 0; t < kInFlight; ++t) {
+                const int pc = p0 + t * (int)blockDim.x;
+                if (pc < pieces) {
+                    if constexpr (sizeof(T) == 2) {
+#pragma unroll
+                        for (int h = 0; h < 4; ++h) {
+                            const float2 f = unpack_half2(raw[t][h]);
+                            strip[pc * 8 + 2 * h] = to_strip(f.x);
+                            strip[pc * 8 + 2 * h + 1] = to_strip(f.y);
+                        }
+                    } else {
+                        *reinterpret_cast<int4*>(strip + pc * 4) =
+                            make_int4(to_strip(__uint_as_float(raw[t][0])), to_strip(__uint_as_float(raw[t][1])),
+                                      to_strip(__uint_as_float(raw[t][2])), to_strip(__uint_as_float(raw[t][3])));
                     }
                 }
             }
@@ -816,7 +856,7 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
     }
     __syncthreads();
 
-    if constexpr (COHERENT) {
+    if constexpr (COHERENT && !EXACT) {
         constexpr int kPerWord = sizeof(T) == 2 ? 2 : 1;
         unsigned* dst = reinterpret_cast<unsigned*>(strip_src);
         const int words = total / kPerWord;
@@ -830,6 +870,29 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
                 raw = __float_as_uint(from_strip(strip[w]));
             }
             __hip_atomic_store(dst + w, raw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    } else if constexpr (COHERENT) {
+        constexpr int kPerPiece = 16 / (int)sizeof(T);
+        const int pieces = total / kPerPiece;
+        const __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc((void*)strip_src, 0, total * (int)sizeof(T), kRawBufferFlags);
+        for (int pc = (int)threadIdx.x; pc < pieces; pc += (int)blockDim.x) {
+            uint4_t raw;
+            if constexpr (sizeof(T) == 2) {
+#pragma unroll
+                for (int h = 0; h < 4; ++h) {
+                    __half2 hh = __halves2half2(round_to_half(from_strip(strip[pc * 8 + 2 * h])),
+                                                round_to_half(from_strip(strip[pc * 8 + 2 * h + 1])));
+                    raw[h] = *reinterpret_cast<unsigned*>(&hh);
+                }
+            } else {
+                const int4 v = *reinterpret_cast<const int4*>(strip + pc * 4);
+                raw[0] = __float_as_uint(from_strip(v.x));
+                raw[1] = __float_as_uint(from_strip(v.y));
+                raw[2] = __float_as_uint(from_strip(v.z));
+                raw[3] = __float_as_uint(from_strip(v.w));
+            }
+            __builtin_amdgcn_raw_buffer_store_b128(raw, rsrc, pc * 16, 0, kCachePolicySc1);
         }
     } else {
         for (int i = 4 * (int)threadIdx.x; i < total; i += stride) {

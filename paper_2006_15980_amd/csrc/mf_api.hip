@@ -36,7 +36,7 @@ struct mf_ctx {
     float* dR = nullptr;
 
     // options
-    int32_t hogwild_chunk = 128;
+    int32_t hogwild_chunk = 0;   // 0 = at most lds_waves chunks per block
     int32_t xcd_affinity = 1;
     int32_t profile = 0;
     int32_t hogwild_kernel = MF_HOGWILD_AUTO;
@@ -90,7 +90,7 @@ Layout make_layout(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t l
 {
     Layout l;
     l.cap[MF_MODE_DET] = mf::det_entries_bound(gr, gc);
-    l.cap[MF_MODE_HOGWILD] = mf::hogwild_entries_bound(nnz, gr, gc, chunk);
+    l.cap[MF_MODE_HOGWILD] = mf::hogwild_entries_bound(nnz, gr, gc, chunk, lds_waves);
     l.lds_cap = mf::lds_entries_bound(nnz, gr, gc, lds_chunk, lds_waves);
     l.lds_blocks_cap = (int64_t)gr * gc;
     size_t off = 0;
@@ -180,7 +180,7 @@ int mf_set_option(mf_ctx* ctx, int32_t option, int64_t value)
     if (!ctx) return MF_EINVAL;
     switch (option) {
         case MF_OPT_HOGWILD_CHUNK:
-            if (value < 1 || value > (1 << 20)) return fail(ctx, MF_EINVAL, "chunk must be in [1, 2^20]");
+            if (value < 0 || value > (1 << 20)) return fail(ctx, MF_EINVAL, "chunk must be in [0, 2^20]");
             ctx->hogwild_chunk = (int32_t)value;
             return MF_OK;
         case MF_OPT_XCD_AFFINITY:
@@ -280,7 +280,7 @@ int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const 
                                  pu, pv, pr, err);
         if (rc) return fail(ctx, rc, err);
         mf::build_det_schedule(ctx->part, ctx->xcd_affinity != 0, ctx->sched[MF_MODE_DET]);
-        mf::build_hogwild_schedule(ctx->part, pu, ctx->hogwild_chunk, ctx->xcd_affinity != 0,
+        mf::build_hogwild_schedule(ctx->part, pu, ctx->hogwild_chunk, ctx->lds_waves, ctx->xcd_affinity != 0,
                                    ctx->sched[MF_MODE_HOGWILD]);
         mf::build_lds_schedule(ctx->part, pu, ctx->lds_chunk, ctx->lds_waves, ctx->lds);
         mf::build_det_lds_schedule(ctx->part, ctx->det_lds);
@@ -537,7 +537,7 @@ int mf_plan_host(const int32_t* rows, const int32_t* cols, int64_t nnz, int64_t 
     if (m < 1 || n < 1 || grid_r > m || grid_c > n) return MF_EINVAL;
     if (split < MF_SPLIT_EQUAL_WIDTH || split > MF_SPLIT_NNZ_WIDTH_BALANCED) return MF_EINVAL;
     if (mode != MF_MODE_DET && mode != MF_MODE_HOGWILD && mode != MF_PLAN_HOGWILD_LDS) return MF_EINVAL;
-    if (chunk < (mode == MF_PLAN_HOGWILD_LDS ? 0 : 1) || (nnz > 0 && (!rows || !cols))) return MF_EINVAL;
+    if (chunk < 0 || (nnz > 0 && (!rows || !cols))) return MF_EINVAL;
     try {
         mf::Partition part;
         std::vector<int32_t> pu, pv;
@@ -551,8 +551,8 @@ int mf_plan_host(const int32_t* rows, const int32_t* cols, int64_t nnz, int64_t 
             mf::build_det_schedule(part, xcd_affinity != 0, s);
             bound = mf::det_entries_bound(grid_r, grid_c);
         } else if (mode == MF_MODE_HOGWILD) {
-            mf::build_hogwild_schedule(part, pu, chunk, xcd_affinity != 0, s);
-            bound = mf::hogwild_entries_bound(nnz, grid_r, grid_c, chunk);
+            mf::build_hogwild_schedule(part, pu, chunk, 16, xcd_affinity != 0, s);
+            bound = mf::hogwild_entries_bound(nnz, grid_r, grid_c, chunk, 16);
         } else {
             mf::LdsSchedule l;
             mf::build_lds_schedule(part, pu, chunk, 16, l);

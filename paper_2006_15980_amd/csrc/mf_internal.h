@@ -70,7 +70,7 @@ int build_partition(const int32_t* rows, const int32_t* cols, const float* vals,
 // DET schedule: one entry per block.  HOGWILD schedule: blocks cut into chunks of whole rows.
 void build_det_schedule(const Partition& part, bool xcd_affinity, Schedule& out);
 void build_hogwild_schedule(const Partition& part, const std::vector<int32_t>& pu, int32_t chunk,
-                            bool xcd_affinity, Schedule& out);
+                            int32_t waves, bool xcd_affinity, Schedule& out);
 void build_lds_schedule(const Partition& part, const std::vector<int32_t>& pu, int32_t chunk,
                         int32_t waves, LdsSchedule& out);
 // Deterministic mode on the LDS kernel: one entry (the whole block) per block descriptor.
@@ -78,7 +78,7 @@ void build_det_lds_schedule(const Partition& part, LdsSchedule& out);
 // Upper bounds on the number of schedule entries, usable before the partition is known.
 int64_t lds_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t waves);
 int64_t det_entries_bound(int32_t gr, int32_t gc);
-int64_t hogwild_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk);
+int64_t hogwild_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t waves);
 
 // kernels.hip ---------------------------------------------------------------------------------
 hipError_t launch_sgd(int dtype, int k, bool hogwild, void* P, void* Qt, const int32_t* U,

@@ -332,8 +332,11 @@ static void chunk_block_even(const std::vector<int32_t>& pu, int64_t pos, int64_
 }
 
 void build_hogwild_schedule(const Partition& part, const std::vector<int32_t>& pu, int32_t chunk,
-                            bool xcd_affinity, Schedule& out)
+                            int32_t waves, bool xcd_affinity, Schedule& out)
 {
+    // chunk == 0: at most `waves` chunks per block, which bounds the number of wavefronts that
+    // change one column of Qt at the same time (each adds a change computed from a value the
+    // others may have changed meanwhile: with hundreds of them the sum overshoots)
     out.begin.clear();
     out.len.clear();
     out.stratum_entry.assign((size_t)part.gc + 1, 0);
@@ -343,10 +346,12 @@ void build_hogwild_schedule(const Partition& part, const std::vector<int32_t>& p
         for (auto& l : per_die) l.clear();
         for (int32_t a = 0; a < part.gr; ++a) {
             int64_t L = (int64_t)s * part.gr + a;
-            chunk_block(pu, part.block_ptr[L], part.block_ptr[L + 1], chunk, [&](int64_t b, int32_t len) {
+            auto push = [&](int64_t b, int32_t len) {
                 int die = xcd_affinity ? a % kXcds : (int)(spread++ % kXcds);
                 per_die[die].push_back({b, len});
-            });
+            };
+            if (chunk > 0) chunk_block(pu, part.block_ptr[L], part.block_ptr[L + 1], chunk, push);
+            else chunk_block_even(pu, part.block_ptr[L], part.block_ptr[L + 1], waves, push);
         }
         lay_out_stratum(per_die, xcd_affinity, out);
         out.stratum_entry[(size_t)s + 1] = (int64_t)out.begin.size();
@@ -397,8 +402,12 @@ int64_t det_entries_bound(int32_t gr, int32_t gc)
     return (int64_t)gc * groups * kXcds * kWavesPerGroup;
 }
 
-int64_t hogwild_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk)
+int64_t hogwild_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t waves)
 {
+    if (chunk == 0) {
+        int64_t chunks = std::min<int64_t>(nnz / 8 + 1, (int64_t)waves * gr * gc) + (int64_t)gr * gc;
+        return chunks * kXcds + (int64_t)gc * kXcds * kWavesPerGroup;
+    }
     // Two consecutive chunks of whole rows of a block hold more than `chunk` ratings together
     // (at most 2c/chunk + 1 of them for c ratings); a row longer than 2*chunk gives
     // ceil(len/chunk) pieces and may close one short chunk before it (together at most
