@@ -182,6 +182,17 @@ int mf_profile_read(mf_ctx* ctx, double* kernel_ms_out, int64_t* launches_out);
  * placement MF_OPT_XCD_AFFINITY relies on. */
 int mf_debug_xcc_ids(mf_ctx* ctx, int32_t n_groups, int32_t* xcc_out);
 
+/* Host-only: a grid and split rule for mf_load_blocks that suit the kernels of `mode` on an MI355X,
+ * from the measured trade-off between the fixed cost of a stratum and the number of workgroups
+ * that work at a time (the role the paper gives its kernel cost model, Section 5.3: block sizes
+ * that are too small leave the GPU idle).  Rules: MF_MODE_HOGWILD wants about 224 x 224 blocks (all
+ * block rows resident for the one-launch ring kernel), at least ~64 ratings per block, and column
+ * strips that fit the LDS under MF_SPLIT_NNZ_WIDTH_BALANCED (at most 2*n/grid_c columns of k fp32
+ * values in 159 KiB), which raises grid_c for wide matrices; MF_MODE_DET wants strips of at most a
+ * quarter of that and about 40 ratings per block, capped at 512.  All outputs are HOST pointers. */
+int mf_suggest_grid(int64_t m, int64_t n, int64_t nnz, int32_t k, int32_t mode,
+                    int32_t* grid_r_out, int32_t* grid_c_out, int32_t* split_out);
+
 /* Host-only planning (no device, no context): the partition mf_load_blocks would build for these
  * arguments, and the per-wavefront work list of one epoch mode, for inspection and for checking
  * the block rule of Section 3.1 without a GPU.  All pointers are HOST; any output may be NULL.

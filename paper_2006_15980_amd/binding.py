@@ -29,7 +29,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmf_sgd.s
 
 EXPORTS = ["mf_create", "mf_destroy", "mf_last_error", "mf_set_option", "mf_init",
            "mf_load_blocks_workspace", "mf_load_blocks", "mf_get_partition", "mf_sgd_epoch",
-           "mf_rmse", "mf_sync", "mf_profile_read", "mf_debug_xcc_ids", "mf_plan_host"]
+           "mf_rmse", "mf_sync", "mf_profile_read", "mf_debug_xcc_ids", "mf_plan_host", "mf_suggest_grid"]
 
 
 class MFError(RuntimeError):
@@ -63,6 +63,7 @@ def lib() -> C.CDLL:
         l.mf_sync.argtypes = [vp]
         l.mf_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
         l.mf_debug_xcc_ids.argtypes = [vp, i32, vp]
+        l.mf_suggest_grid.argtypes = [i64, i64, i64, i32, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
         l.mf_plan_host.argtypes = [vp, vp, i64, i64, i64, i32, i32, i32, i32, i32, i32,
                                    vp, vp, vp, vp, vp, vp, i64, vp, C.POINTER(i64)]
         for name in EXPORTS:
@@ -159,6 +160,15 @@ def mf_debug_xcc_ids(ctx: int, n_groups: int) -> np.ndarray:
     out = np.empty(n_groups, np.int32)
     _check(ctx, lib().mf_debug_xcc_ids(ctx, n_groups, out.ctypes.data))
     return out
+
+
+def mf_suggest_grid(m: int, n: int, nnz: int, k: int, mode: int):
+    """-> (grid_r, grid_c, split)"""
+    gr, gc, sp = C.c_int32(), C.c_int32(), C.c_int32()
+    rc = lib().mf_suggest_grid(m, n, nnz, k, mode, C.byref(gr), C.byref(gc), C.byref(sp))
+    if rc != MF_OK:
+        raise MFError(rc, "mf_suggest_grid failed")
+    return gr.value, gc.value, sp.value
 
 
 def mf_plan_host(rows: np.ndarray, cols: np.ndarray, m: int, n: int, grid_r: int, grid_c: int, split: int,

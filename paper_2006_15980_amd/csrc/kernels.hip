@@ -750,7 +750,7 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
         constexpr int kPerWord = sizeof(T) == 2 ? 2 : 1;
         const unsigned* src = reinterpret_cast<const unsigned*>(strip_src);
         const int words = total / kPerWord;
-        constexpr int kInFlight = 8;
+        constexpr int kInFlight = 16;
         for (int w0 = (int)threadIdx.x; w0 < words; w0 += kInFlight * (int)blockDim.x) {
             unsigned raw[kInFlight];
 #pragma unroll
@@ -779,7 +779,7 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
         const int pieces = total / kPerPiece;
         const __amdgpu_buffer_rsrc_t rsrc =
             __builtin_amdgcn_make_buffer_rsrc((void*)strip_src, 0, total * (int)sizeof(T), kRawBufferFlags);
-        constexpr int kInFlight = 8;
+        constexpr int kInFlight = 16;
         for (int p0 = (int)threadIdx.x; p0 < pieces; p0 += kInFlight * (int)blockDim.x) {
             uint4_t raw[kInFlight];
 #pragma unroll

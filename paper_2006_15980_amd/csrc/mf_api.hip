@@ -527,6 +527,30 @@ int mf_debug_xcc_ids(mf_ctx* ctx, int32_t n_groups, int32_t* xcc_out)
     return MF_OK;
 }
 
+int mf_suggest_grid(int64_t m, int64_t n, int64_t nnz, int32_t k, int32_t mode, int32_t* grid_r_out,
+                    int32_t* grid_c_out, int32_t* split_out)
+{
+    if (m < 1 || n < 1 || nnz < 0 || !valid_k(k) || !grid_r_out || !grid_c_out || !split_out) return MF_EINVAL;
+    if (mode != MF_MODE_DET && mode != MF_MODE_HOGWILD) return MF_EINVAL;
+    const bool hog = mode == MF_MODE_HOGWILD;
+    const int64_t lds = hog ? (int64_t)mf::kLdsBudget : (int64_t)mf::kLdsBudget / 4;
+    const int64_t strip_cols = std::max<int64_t>(1, lds / ((int64_t)k * 4));   // columns one strip may hold
+    // enough column strips for the widest one (at most about 2*n/grid_c columns) to fit
+    const int64_t gc_for_lds = (2 * n + strip_cols - 1) / strip_cols;
+    // few enough blocks for ~64 (Hogwild) / ~40 (deterministic) ratings in each
+    const double per_block = hog ? 64.0 : 40.0;
+    int64_t g = (int64_t)std::floor(std::sqrt((double)std::max<int64_t>(nnz, 1) / per_block));
+    g = std::min<int64_t>(g, hog ? 224 : 512);
+    g = std::max<int64_t>(g, 1);
+    int64_t gr = std::min<int64_t>(g, m);
+    int64_t gc = std::min<int64_t>(std::max<int64_t>(g, gc_for_lds), n);
+    gr = std::min(gr, gc);
+    *grid_r_out = (int32_t)gr;
+    *grid_c_out = (int32_t)gc;
+    *split_out = MF_SPLIT_NNZ_WIDTH_BALANCED;
+    return MF_OK;
+}
+
 int mf_plan_host(const int32_t* rows, const int32_t* cols, int64_t nnz, int64_t m, int64_t n,
                  int32_t grid_r, int32_t grid_c, int32_t split, int32_t mode, int32_t chunk,
                  int32_t xcd_affinity, int64_t* perm, int64_t* block_ptr, int32_t* row_bounds,

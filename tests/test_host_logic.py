@@ -160,6 +160,26 @@ def test_plan_rejects_bad_arguments():
         assert e.value.code == B.MF_EINVAL, args
 
 
+def test_suggested_grids_fit_the_lds_and_keep_blocks_reasonable():
+    import workloads
+    for name, cfg in workloads.CONFIGS.items():
+        total = cfg.nnz_train
+        for mode in (B.MF_MODE_DET, B.MF_MODE_HOGWILD):
+            gr, gc, split = B.mf_suggest_grid(cfg.m, cfg.n, total, cfg.k, mode)
+            assert 1 <= gr <= gc <= cfg.n and gr <= cfg.m and split == B.MF_SPLIT_NNZ_WIDTH_BALANCED
+            budget = 159 * 1024 if mode == B.MF_MODE_HOGWILD else 159 * 1024 // 4
+            assert (2 * cfg.n / gc) * cfg.k * 4 <= budget * 1.01, (name, gr, gc)
+            if mode == B.MF_MODE_HOGWILD:
+                assert gr <= 256                                  # every block row resident in the ring kernel
+    # the bound on the widest strip really holds for a generated matrix
+    ds = workloads.generate(workloads.scaled(workloads.CONFIGS["xlarge"], 0.004))
+    gr, gc, split = B.mf_suggest_grid(ds.cfg.m, ds.cfg.n, ds.rows.size, ds.cfg.k, B.MF_MODE_HOGWILD)
+    plan = B.mf_plan_host(ds.rows, ds.cols, ds.cfg.m, ds.cfg.n, gr, gc, split, B.MF_PLAN_HOGWILD_LDS, 0)
+    assert np.diff(plan["col_bounds"]).max() * ds.cfg.k * 4 <= 159 * 1024
+    with pytest.raises(B.MFError):
+        B.mf_suggest_grid(10, 10, 5, 48, B.MF_MODE_DET)
+
+
 def test_create_without_a_device_is_an_error_not_a_crash():
     import torch
     if torch.cuda.is_available():
