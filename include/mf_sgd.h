@@ -124,6 +124,18 @@ int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const 
                    int64_t nnz, int32_t grid_r, int32_t grid_c, int32_t split,
                    void* d_workspace, size_t workspace_bytes);
 
+/* mf_load_blocks for COO arrays that already live in device memory ("partition R" and
+ * "preprocess data" of the paper's Algorithm 2, done on the GPU): the same partition, packed order
+ * and work lists as mf_load_blocks, bit for bit, with the block ids, the sort and the gather
+ * computed by kernels on the context's stream.  d_rows, d_cols, d_vals: DEVICE pointers, nnz entries
+ * each, read only, not needed after the call returns.  d_workspace as for mf_load_blocks.  The call
+ * allocates about 24 bytes per rating of temporary device memory (hipMalloc) and frees it before it
+ * returns; it synchronises the stream.  Errors as mf_load_blocks, plus MF_EINVAL if block id, row
+ * offset and column offset of the grid do not fit 64 key bits together (then use mf_load_blocks). */
+int mf_load_blocks_device(mf_ctx* ctx, const int32_t* d_rows, const int32_t* d_cols, const float* d_vals,
+                          int64_t nnz, int32_t grid_r, int32_t grid_c, int32_t split, void* d_workspace,
+                          size_t workspace_bytes);
+
 /* Copy the partition to HOST arrays of the caller (any pointer may be NULL):
  *   perm[nnz]                 original position of the rating stored at each packed position;
  *   block_ptr[grid_r*grid_c+1] start of every block in the packed order;

@@ -60,6 +60,21 @@ class MatrixFactorization:
         self.nnz = rows.size
         self.grid = (grid_r, grid_c)
 
+    def load_blocks_device(self, rows, cols, vals, grid_r: int, grid_c: int, split: int = MF_SPLIT_NNZ_BALANCED):
+        """rows, cols (int32) and vals (float32): torch tensors on this model's device."""
+        t = self.torch
+        for x, dt in ((rows, t.int32), (cols, t.int32), (vals, t.float32)):
+            if x.dtype != dt or x.device != self.P.device or not x.is_contiguous() or x.numel() != rows.numel():
+                raise ValueError("need contiguous int32 / int32 / float32 tensors of one length on the model's device")
+        nbytes = binding.mf_load_blocks_workspace(self.ctx, rows.numel(), grid_r, grid_c)
+        binding.mf_sync(self.ctx)
+        self.workspace = t.empty(nbytes + 256, dtype=t.uint8, device=self.dev)
+        base = (self.workspace.data_ptr() + 255) & ~255
+        binding.mf_load_blocks_device(self.ctx, rows.data_ptr(), cols.data_ptr(), vals.data_ptr(), rows.numel(),
+                                      grid_r, grid_c, split, base, nbytes)
+        self.nnz = rows.numel()
+        self.grid = (grid_r, grid_c)
+
     def partition(self):
         return binding.mf_get_partition(self.ctx, self.nnz, *self.grid)
 

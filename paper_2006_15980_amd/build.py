@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmf_sgd.so")
-SOURCES = ["mf_api.hip", "kernels.hip", "partition.cpp"]
+SOURCES = ["mf_api.hip", "kernels.hip", "partition.cpp", "partition_device.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 

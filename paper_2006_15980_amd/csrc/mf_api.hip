@@ -254,11 +254,11 @@ int mf_load_blocks_workspace(const mf_ctx* ctx, int64_t nnz, int32_t grid_r, int
     return MF_OK;
 }
 
-int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const float* vals,
-                   int64_t nnz, int32_t grid_r, int32_t grid_c, int32_t split, void* d_workspace,
-                   size_t workspace_bytes)
+namespace {
+
+int check_load(mf_ctx* ctx, const void* rows, const void* cols, const void* vals, int64_t nnz, int32_t grid_r,
+               int32_t grid_c, int32_t split, void* d_workspace, size_t workspace_bytes, Layout& lay)
 {
-    if (!ctx) return MF_EINVAL;
     if (!ctx->inited) return fail(ctx, MF_ESTATE, "mf_load_blocks before mf_init");
     int rc = check_grid(ctx, nnz, grid_r, grid_c);
     if (rc) return rc;
@@ -267,37 +267,23 @@ int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const 
     if (nnz > 0 && (!rows || !cols || !vals)) return fail(ctx, MF_EINVAL, "null rating array");
     if (!d_workspace) return fail(ctx, MF_EINVAL, "null workspace");
     if ((uintptr_t)d_workspace & 255) return fail(ctx, MF_EINVAL, "workspace must be 256-byte aligned");
-    const Layout lay = make_layout(nnz, grid_r, grid_c, ctx->hogwild_chunk, ctx->lds_chunk, ctx->lds_waves);
+    lay = make_layout(nnz, grid_r, grid_c, ctx->hogwild_chunk, ctx->lds_chunk, ctx->lds_waves);
     if (workspace_bytes < lay.total) return fail(ctx, MF_ENOMEM, "workspace too small");
-    MF_HIP(ctx, hipSetDevice(ctx->device));
-    ctx->loaded = false;
+    return MF_OK;
+}
 
-    std::vector<int32_t> pu, pv;
-    std::vector<float> pr;
+// The partition and the packed arrays exist (ctx->part; `pu` = packed row indices on the host):
+// derive the work lists and put them into the workspace.
+int finish_load(mf_ctx* ctx, const Layout& lay, char* base, const std::vector<int32_t>& pu)
+{
     try {
-        std::string err;
-        rc = mf::build_partition(rows, cols, vals, nnz, ctx->m, ctx->n, grid_r, grid_c, split, ctx->part,
-                                 pu, pv, pr, err);
-        if (rc) return fail(ctx, rc, err);
         mf::build_det_schedule(ctx->part, ctx->xcd_affinity != 0, ctx->sched[MF_MODE_DET]);
         mf::build_hogwild_schedule(ctx->part, pu, ctx->hogwild_chunk, ctx->lds_waves, ctx->xcd_affinity != 0,
                                    ctx->sched[MF_MODE_HOGWILD]);
         mf::build_lds_schedule(ctx->part, pu, ctx->lds_chunk, ctx->lds_waves, ctx->lds);
         mf::build_det_lds_schedule(ctx->part, ctx->det_lds);
     } catch (const std::bad_alloc&) {
-        return fail(ctx, MF_ENOMEM, "host allocation failed while partitioning");
-    }
-
-    char* base = (char*)d_workspace;
-    ctx->dU = (int32_t*)(base + lay.off_u);
-    ctx->dV = (int32_t*)(base + lay.off_v);
-    ctx->dR = (float*)(base + lay.off_r);
-    // the stream may still be running an epoch that reads the old contents of the workspace
-    MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    if (nnz > 0) {
-        MF_HIP(ctx, hipMemcpy(ctx->dU, pu.data(), (size_t)nnz * 4, hipMemcpyHostToDevice));
-        MF_HIP(ctx, hipMemcpy(ctx->dV, pv.data(), (size_t)nnz * 4, hipMemcpyHostToDevice));
-        MF_HIP(ctx, hipMemcpy(ctx->dR, pr.data(), (size_t)nnz * 4, hipMemcpyHostToDevice));
+        return fail(ctx, MF_ENOMEM, "host allocation failed while building the work lists");
     }
     for (int mode = 0; mode < 2; ++mode) {
         mf::Schedule& s = ctx->sched[mode];
@@ -328,11 +314,76 @@ int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const 
         }
     }
     ctx->d_ring_done = (int32_t*)(base + lay.off_ring_done);
-    MF_HIP(ctx, hipMemset(ctx->d_ring_done, 0, ((size_t)grid_r + 1) * 4));
+    MF_HIP(ctx, hipMemset(ctx->d_ring_done, 0, ((size_t)ctx->part.gr + 1) * 4));
     ctx->ring_epochs = 0;
     ctx->ring_resident[0] = ctx->ring_resident[1] = -1;
     ctx->loaded = true;
     return MF_OK;
+}
+
+}  // namespace
+
+int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const float* vals,
+                   int64_t nnz, int32_t grid_r, int32_t grid_c, int32_t split, void* d_workspace,
+                   size_t workspace_bytes)
+{
+    if (!ctx) return MF_EINVAL;
+    Layout lay;
+    int rc = check_load(ctx, rows, cols, vals, nnz, grid_r, grid_c, split, d_workspace, workspace_bytes, lay);
+    if (rc) return rc;
+    MF_HIP(ctx, hipSetDevice(ctx->device));
+    ctx->loaded = false;
+
+    std::vector<int32_t> pu, pv;
+    std::vector<float> pr;
+    try {
+        std::string err;
+        rc = mf::build_partition(rows, cols, vals, nnz, ctx->m, ctx->n, grid_r, grid_c, split, ctx->part,
+                                 pu, pv, pr, err);
+        if (rc) return fail(ctx, rc, err);
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, MF_ENOMEM, "host allocation failed while partitioning");
+    }
+
+    char* base = (char*)d_workspace;
+    ctx->dU = (int32_t*)(base + lay.off_u);
+    ctx->dV = (int32_t*)(base + lay.off_v);
+    ctx->dR = (float*)(base + lay.off_r);
+    // the stream may still be running an epoch that reads the old contents of the workspace
+    MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (nnz > 0) {
+        MF_HIP(ctx, hipMemcpy(ctx->dU, pu.data(), (size_t)nnz * 4, hipMemcpyHostToDevice));
+        MF_HIP(ctx, hipMemcpy(ctx->dV, pv.data(), (size_t)nnz * 4, hipMemcpyHostToDevice));
+        MF_HIP(ctx, hipMemcpy(ctx->dR, pr.data(), (size_t)nnz * 4, hipMemcpyHostToDevice));
+    }
+    return finish_load(ctx, lay, base, pu);
+}
+
+int mf_load_blocks_device(mf_ctx* ctx, const int32_t* d_rows, const int32_t* d_cols, const float* d_vals,
+                          int64_t nnz, int32_t grid_r, int32_t grid_c, int32_t split, void* d_workspace,
+                          size_t workspace_bytes)
+{
+    if (!ctx) return MF_EINVAL;
+    Layout lay;
+    int rc = check_load(ctx, d_rows, d_cols, d_vals, nnz, grid_r, grid_c, split, d_workspace, workspace_bytes, lay);
+    if (rc) return rc;
+    MF_HIP(ctx, hipSetDevice(ctx->device));
+    ctx->loaded = false;
+    char* base = (char*)d_workspace;
+    ctx->dU = (int32_t*)(base + lay.off_u);
+    ctx->dV = (int32_t*)(base + lay.off_v);
+    ctx->dR = (float*)(base + lay.off_r);
+    MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    std::vector<int32_t> pu;
+    try {
+        std::string err;
+        rc = mf::build_partition_device(d_rows, d_cols, d_vals, nnz, ctx->m, ctx->n, grid_r, grid_c, split,
+                                        ctx->dU, ctx->dV, ctx->dR, ctx->part, pu, ctx->stream, err);
+        if (rc) return fail(ctx, rc, err);
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, MF_ENOMEM, "host allocation failed while partitioning");
+    }
+    return finish_load(ctx, lay, base, pu);
 }
 
 int mf_get_partition(const mf_ctx* ctx, int64_t* perm, int64_t* block_ptr, int32_t* row_bounds,

@@ -67,6 +67,12 @@ int build_partition(const int32_t* rows, const int32_t* cols, const float* vals,
                     int64_t m, int64_t n, int32_t gr, int32_t gc, int32_t split, Partition& out,
                     std::vector<int32_t>& pu, std::vector<int32_t>& pv, std::vector<float>& pr,
                     std::string& err);
+// Strip boundaries (size g + 1) of one axis: uniform division, or balanced by the per-id rating
+// counts `degree` (see mf_sgd.h for the two balanced rules); strip index of every id.
+void equal_width_bounds(int64_t size, int32_t g, std::vector<int32_t>& b);
+void bounds_from_degrees(const int32_t* degree, int64_t nnz, int64_t size, int32_t g, bool width_weight,
+                         std::vector<int32_t>& b);
+void strip_table(const std::vector<int32_t>& bounds, int64_t size, std::vector<int32_t>& table);
 // DET schedule: one entry per block.  HOGWILD schedule: blocks cut into chunks of whole rows.
 void build_det_schedule(const Partition& part, bool xcd_affinity, Schedule& out);
 void build_hogwild_schedule(const Partition& part, const std::vector<int32_t>& pu, int32_t chunk,
@@ -79,6 +85,16 @@ void build_det_lds_schedule(const Partition& part, LdsSchedule& out);
 int64_t lds_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t waves);
 int64_t det_entries_bound(int32_t gr, int32_t gc);
 int64_t hogwild_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t waves);
+
+// partition_device.hip ------------------------------------------------------------------------
+// The same partition computed on the device from COO arrays that already live in HBM: fills
+// dU, dV, dR (packed order) and `out`, and copies the packed row indices to `pu` (the schedule
+// builders read them).  Temporary device memory (about 24 bytes per rating) is allocated and
+// freed inside.  Bit-identical to build_partition.
+int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const float* d_vals, int64_t nnz,
+                           int64_t m, int64_t n, int32_t gr, int32_t gc, int32_t split, int32_t* dU,
+                           int32_t* dV, float* dR, Partition& out, std::vector<int32_t>& pu,
+                           hipStream_t stream, std::string& err);
 
 // kernels.hip ---------------------------------------------------------------------------------
 hipError_t launch_sgd(int dtype, int k, bool hogwild, void* P, void* Qt, const int32_t* U,

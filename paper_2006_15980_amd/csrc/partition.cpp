@@ -53,24 +53,14 @@ void parallel_items(int64_t total, int threads, F fn)
     for (auto& th : pool) th.join();
 }
 
-void equal_width_bounds(int64_t size, int32_t g, std::vector<int32_t>& b)
-{
-    b.resize((size_t)g + 1);
-    for (int32_t a = 0; a <= g; ++a) b[a] = (int32_t)(((int64_t)a * size + g - 1) / g);
-}
+}  // namespace
 
 // `width_weight` = false: every id weighs its number of ratings.  true: its number of ratings
 // times the axis length plus the number of ratings in total, i.e. its share of the ratings plus
 // its share of the axis, so that a strip is bounded in ratings and in width.
-void balanced_bounds(const int32_t* idx, int64_t nnz, int64_t size, int32_t g, int threads,
-                     bool width_weight, std::vector<int32_t>& b)
+void bounds_from_degrees(const int32_t* degree, int64_t nnz, int64_t size, int32_t g, bool width_weight,
+                         std::vector<int32_t>& b)
 {
-    // degree histogram with one private histogram per thread
-    std::vector<std::vector<int64_t>> priv((size_t)threads);
-    parallel_ranges(nnz, threads, [&](int i, int64_t s, int64_t e) {
-        priv[i].assign((size_t)size, 0);
-        for (int64_t t = s; t < e; ++t) priv[i][idx[t]] += 1;
-    });
     b.assign((size_t)g + 1, 0);
     b[g] = (int32_t)size;
     const int64_t unit = nnz > 0 ? nnz : 1;
@@ -81,11 +71,36 @@ void balanced_bounds(const int32_t* idx, int64_t nnz, int64_t size, int32_t g, i
         // strip boundary a sits at the first id whose exclusive weight prefix reaches ceil(a*total/g)
         const __int128 prefix = width_weight ? (__int128)before * size + (__int128)x * unit : (__int128)before;
         while (a < g && prefix >= ((__int128)a * total + g - 1) / g) b[a++] = (int32_t)x;
-        for (int i = 0; i < threads; ++i)
-            if (!priv[i].empty()) before += priv[i][x];
+        before += degree[x];
     }
     while (a < g) b[a++] = (int32_t)size;
 }
+
+void equal_width_bounds(int64_t size, int32_t g, std::vector<int32_t>& b)
+{
+    b.resize((size_t)g + 1);
+    for (int32_t a = 0; a <= g; ++a) b[a] = (int32_t)(((int64_t)a * size + g - 1) / g);
+}
+
+namespace {
+
+void balanced_bounds(const int32_t* idx, int64_t nnz, int64_t size, int32_t g, int threads,
+                     bool width_weight, std::vector<int32_t>& b)
+{
+    // degree histogram with one private histogram per thread
+    std::vector<std::vector<int32_t>> priv((size_t)threads);
+    parallel_ranges(nnz, threads, [&](int i, int64_t s, int64_t e) {
+        priv[i].assign((size_t)size, 0);
+        for (int64_t t = s; t < e; ++t) priv[i][idx[t]] += 1;
+    });
+    std::vector<int32_t> degree((size_t)size, 0);
+    for (auto& h : priv)
+        if (!h.empty())
+            for (int64_t x = 0; x < size; ++x) degree[x] += h[x];
+    bounds_from_degrees(degree.data(), nnz, size, g, width_weight, b);
+}
+
+}  // namespace
 
 void strip_table(const std::vector<int32_t>& bounds, int64_t size, std::vector<int32_t>& table)
 {
@@ -94,6 +109,8 @@ void strip_table(const std::vector<int32_t>& bounds, int64_t size, std::vector<i
     for (int32_t a = 0; a < g; ++a)
         for (int64_t x = bounds[a]; x < bounds[a + 1]; ++x) table[x] = a;
 }
+
+namespace {
 
 struct KeyPos {
     uint64_t key;   // row << 32 | column

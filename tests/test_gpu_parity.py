@@ -69,6 +69,69 @@ def test_partition_through_the_device_path_is_bit_exact(mfmod, split):
     model.close()
 
 
+def _device_load_matches(mfmod, rows, cols, vals, m, n, gr, gc, split, k=32):
+    """mf_load_blocks_device against the oracle's partition (bit-exact) and against a model loaded
+    through the host path (same bits after one deterministic epoch: the packed values too)."""
+    dev = mfmod.MatrixFactorization(m, n, k, "f32", seed=3, scale=0.1)
+    t = torch
+    d = dev.P.device
+    dev.load_blocks_device(t.from_numpy(rows).to(d), t.from_numpy(cols).to(d), t.from_numpy(vals).to(d), gr, gc, split)
+    got = dev.partition()
+    want = oracle.partition(rows, cols, m, n, gr, gc, split)
+    for name, a, b in zip(("perm", "block_ptr", "row_bounds", "col_bounds"), got, want):
+        assert np.array_equal(a, b), (name, gr, gc, split, rows.size)
+    host = mfmod.MatrixFactorization(m, n, k, "f32", seed=3, scale=0.1)
+    host.load_blocks(rows, cols, vals, gr, gc, split)
+    for mode in (mfmod.MF_MODE_DET, mfmod.MF_MODE_DET):
+        dev.sgd_epoch(0.01, 0.05, mode)
+        host.sgd_epoch(0.01, 0.05, mode)
+    for a, b in zip(dev.get_factors(), host.get_factors()):
+        assert np.array_equal(a, b)
+    dev.close()
+    host.close()
+
+
+@pytest.mark.parametrize("split", [0, 1, 2])
+@pytest.mark.parametrize("grid", [(1, 1), (7, 9), (16, 16), (40, 333)])
+def test_device_partitioner_is_bit_exact(mfmod, grid, split):
+    ds = dataset("tiny")
+    _device_load_matches(mfmod, ds.rows, ds.cols, ds.vals, ds.cfg.m, ds.cfg.n, grid[0], grid[1], split)
+
+
+@pytest.mark.parametrize("count", [1, 63, 4095, 4096, 4097, 8193])
+def test_device_partitioner_ragged_sizes_and_duplicates(mfmod, count):
+    ds = dataset("tiny")
+    rows, cols, vals = ds.rows[:count].copy(), ds.cols[:count].copy(), ds.vals[:count].copy()
+    if count > 10:      # the same (row, column) several times: original order must be kept
+        rows[count // 2:count // 2 + 5] = rows[0]
+        cols[count // 2:count // 2 + 5] = cols[0]
+        rows[-1], cols[-1] = rows[1], cols[1]
+    _device_load_matches(mfmod, rows, cols, vals, ds.cfg.m, ds.cfg.n, 5, 6, 1)
+
+
+def test_device_partitioner_skewed_matrix_many_tiles(mfmod):
+    ds = dataset("medium", 0.2)     # 1.98 M ratings = 484 tiles, Zipf degrees
+    _device_load_matches(mfmod, ds.rows, ds.cols, ds.vals, ds.cfg.m, ds.cfg.n, 64, 96, 2, k=32)
+    _device_load_matches(mfmod, ds.rows, ds.cols, ds.vals, ds.cfg.m, ds.cfg.n, 224, 224, 1, k=32)
+
+
+def test_device_partitioner_rejects_indices_outside_the_matrix_and_accepts_no_ratings(mfmod):
+    m, n = 100, 50
+    model = mfmod.MatrixFactorization(m, n, 32, "f32")
+    d = model.P.device
+    rows = torch.tensor([1, 2, 100], dtype=torch.int32, device=d)
+    cols = torch.tensor([1, 2, 3], dtype=torch.int32, device=d)
+    vals = torch.ones(3, dtype=torch.float32, device=d)
+    with pytest.raises(mfmod.MFError) as err:
+        model.load_blocks_device(rows, cols, vals, 2, 2, 1)
+    assert err.value.code == mfmod.binding.MF_ERANGE
+    model.load_blocks_device(rows[:0], cols[:0], vals[:0], 2, 2, 1)
+    P0 = model.get_factors()[0]
+    model.sgd_epoch(0.01, 0.05, mfmod.MF_MODE_DET)
+    assert np.array_equal(model.get_factors()[0], P0)
+    model.close()
+
+
 # ------------------------------------------------------------------------------- RMSE kernel
 @pytest.mark.parametrize("storage,k", [("f32", 32), ("f32", 128), ("f16", 128), ("f32", 256), ("f16", 64)])
 def test_rmse_kernel_matches_oracle(mfmod, storage, k):
