@@ -45,6 +45,7 @@ struct mf_ctx {
     int64_t spin_limit = (int64_t)1 << 22;
     int32_t ring_resident[2] = {-1, -1};  // workgroups of the ring kernel the device holds at once, per mode
     int32_t ring_epochs = 0;              // epochs run by the ring kernel since mf_load_blocks
+    uint32_t* d_perm = nullptr;           // packed -> original position when the partition was made on the device
     int32_t* d_ring_done = nullptr;       // grid_r counters + 1 abort flag, inside the workspace
     int32_t lds_chunk = 0;   // 0 = one chunk per wavefront
     int32_t lds_waves = 16;
@@ -81,7 +82,7 @@ size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 bool valid_k(int32_t k) { return k == 32 || k == 64 || k == 128 || k == 256; }
 
 struct Layout {
-    size_t off_u, off_v, off_r, off_begin[2], off_len[2], off_lds_begin, off_lds_len, off_lds_blocks,
+    size_t off_u, off_v, off_r, off_perm, off_begin[2], off_len[2], off_lds_begin, off_lds_len, off_lds_blocks,
         off_dlds_begin, off_dlds_len, off_dlds_blocks, off_ring[2], off_ring_done, total;
     int64_t cap[2], lds_cap, lds_blocks_cap;
 };
@@ -97,6 +98,7 @@ Layout make_layout(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t l
     l.off_u = off; off += align_up((size_t)nnz * 4);
     l.off_v = off; off += align_up((size_t)nnz * 4);
     l.off_r = off; off += align_up((size_t)nnz * 4);
+    l.off_perm = off; off += align_up((size_t)nnz * 4);   // written by mf_load_blocks_device only
     for (int mode = 0; mode < 2; ++mode) {
         l.off_begin[mode] = off; off += align_up((size_t)l.cap[mode] * 8);
         l.off_len[mode] = off; off += align_up((size_t)l.cap[mode] * 4);
@@ -272,15 +274,15 @@ int check_load(mf_ctx* ctx, const void* rows, const void* cols, const void* vals
     return MF_OK;
 }
 
-// The partition and the packed arrays exist (ctx->part; `pu` = packed row indices on the host):
+// The partition and the packed arrays exist (ctx->part; `rs` = where the row runs begin):
 // derive the work lists and put them into the workspace.
-int finish_load(mf_ctx* ctx, const Layout& lay, char* base, const std::vector<int32_t>& pu)
+int finish_load(mf_ctx* ctx, const Layout& lay, char* base, const mf::RowStarts& rs)
 {
     try {
         mf::build_det_schedule(ctx->part, ctx->xcd_affinity != 0, ctx->sched[MF_MODE_DET]);
-        mf::build_hogwild_schedule(ctx->part, pu, ctx->hogwild_chunk, ctx->lds_waves, ctx->xcd_affinity != 0,
+        mf::build_hogwild_schedule(ctx->part, rs, ctx->hogwild_chunk, ctx->lds_waves, ctx->xcd_affinity != 0,
                                    ctx->sched[MF_MODE_HOGWILD]);
-        mf::build_lds_schedule(ctx->part, pu, ctx->lds_chunk, ctx->lds_waves, ctx->lds);
+        mf::build_lds_schedule(ctx->part, rs, ctx->lds_chunk, ctx->lds_waves, ctx->lds);
         mf::build_det_lds_schedule(ctx->part, ctx->det_lds);
     } catch (const std::bad_alloc&) {
         return fail(ctx, MF_ENOMEM, "host allocation failed while building the work lists");
@@ -356,7 +358,10 @@ int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const 
         MF_HIP(ctx, hipMemcpy(ctx->dV, pv.data(), (size_t)nnz * 4, hipMemcpyHostToDevice));
         MF_HIP(ctx, hipMemcpy(ctx->dR, pr.data(), (size_t)nnz * 4, hipMemcpyHostToDevice));
     }
-    return finish_load(ctx, lay, base, pu);
+    ctx->d_perm = nullptr;
+    mf::RowStarts rs;
+    mf::row_starts_from_rows(pu.data(), nnz, rs);
+    return finish_load(ctx, lay, base, rs);
 }
 
 int mf_load_blocks_device(mf_ctx* ctx, const int32_t* d_rows, const int32_t* d_cols, const float* d_vals,
@@ -374,16 +379,17 @@ int mf_load_blocks_device(mf_ctx* ctx, const int32_t* d_rows, const int32_t* d_c
     ctx->dV = (int32_t*)(base + lay.off_v);
     ctx->dR = (float*)(base + lay.off_r);
     MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    std::vector<int32_t> pu;
+    mf::RowStarts rs;
+    ctx->d_perm = (uint32_t*)(base + lay.off_perm);
     try {
         std::string err;
         rc = mf::build_partition_device(d_rows, d_cols, d_vals, nnz, ctx->m, ctx->n, grid_r, grid_c, split,
-                                        ctx->dU, ctx->dV, ctx->dR, ctx->part, pu, ctx->stream, err);
+                                        ctx->dU, ctx->dV, ctx->dR, ctx->d_perm, ctx->part, rs, ctx->stream, err);
         if (rc) return fail(ctx, rc, err);
     } catch (const std::bad_alloc&) {
         return fail(ctx, MF_ENOMEM, "host allocation failed while partitioning");
     }
-    return finish_load(ctx, lay, base, pu);
+    return finish_load(ctx, lay, base, rs);
 }
 
 int mf_get_partition(const mf_ctx* ctx, int64_t* perm, int64_t* block_ptr, int32_t* row_bounds,
@@ -393,6 +399,15 @@ int mf_get_partition(const mf_ctx* ctx, int64_t* perm, int64_t* block_ptr, int32
     if (!ctx->loaded) return fail(const_cast<mf_ctx*>(ctx), MF_ESTATE, "no partition loaded");
     const mf::Partition& p = ctx->part;
     if (perm && !p.perm.empty()) std::memcpy(perm, p.perm.data(), p.perm.size() * 8);
+    if (perm && p.perm.empty() && ctx->d_perm && p.nnz > 0) {
+        // partition made on the device: the permutation lives in the workspace as 32-bit numbers
+        std::vector<uint32_t> narrow((size_t)p.nnz);
+        hipError_t e = hipSetDevice(ctx->device);
+        if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+        if (e == hipSuccess) e = hipMemcpy(narrow.data(), ctx->d_perm, (size_t)p.nnz * 4, hipMemcpyDeviceToHost);
+        if (e != hipSuccess) return fail_hip(const_cast<mf_ctx*>(ctx), "reading the permutation", e);
+        for (int64_t i = 0; i < p.nnz; ++i) perm[i] = (int64_t)narrow[(size_t)i];
+    }
     if (block_ptr) std::memcpy(block_ptr, p.block_ptr.data(), p.block_ptr.size() * 8);
     if (row_bounds) std::memcpy(row_bounds, p.row_bounds.data(), p.row_bounds.size() * 4);
     if (col_bounds) std::memcpy(col_bounds, p.col_bounds.data(), p.col_bounds.size() * 4);
@@ -620,17 +635,19 @@ int mf_plan_host(const int32_t* rows, const int32_t* cols, int64_t nnz, int64_t 
         std::string err;
         int rc = mf::build_partition(rows, cols, vals.data(), nnz, m, n, grid_r, grid_c, split, part, pu, pv, pr, err);
         if (rc) return rc;
+        mf::RowStarts rs;
+        mf::row_starts_from_rows(pu.data(), nnz, rs);
         mf::Schedule s;
         int64_t bound;
         if (mode == MF_MODE_DET) {
             mf::build_det_schedule(part, xcd_affinity != 0, s);
             bound = mf::det_entries_bound(grid_r, grid_c);
         } else if (mode == MF_MODE_HOGWILD) {
-            mf::build_hogwild_schedule(part, pu, chunk, 16, xcd_affinity != 0, s);
+            mf::build_hogwild_schedule(part, rs, chunk, 16, xcd_affinity != 0, s);
             bound = mf::hogwild_entries_bound(nnz, grid_r, grid_c, chunk, 16);
         } else {
             mf::LdsSchedule l;
-            mf::build_lds_schedule(part, pu, chunk, 16, l);
+            mf::build_lds_schedule(part, rs, chunk, 16, l);
             bound = mf::lds_entries_bound(nnz, grid_r, grid_c, chunk, 16);
             s.begin = l.begin;
             s.len = l.len;

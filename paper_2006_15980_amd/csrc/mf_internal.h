@@ -51,11 +51,19 @@ struct LdsSchedule {
     LdsBlock* d_ring = nullptr;
 };
 
+// Where the runs of one matrix row begin in the packed order: bit i is set when rating i has
+// another row index than rating i-1 (bit 0 always).  The schedule builders cut blocks there.
+struct RowStarts {
+    std::vector<uint64_t> bits;
+    bool starts(int64_t i) const { return (bits[(size_t)(i >> 6)] >> (i & 63)) & 1; }
+};
+void row_starts_from_rows(const int32_t* pu, int64_t nnz, RowStarts& out);
+
 // Host partition of R into the block grid.
 struct Partition {
     int64_t nnz = 0;
     int32_t gr = 0, gc = 0;
-    std::vector<int64_t> perm;        // packed position -> original position
+    std::vector<int64_t> perm;        // packed position -> original position (empty if kept on the device)
     std::vector<int64_t> block_ptr;   // gr*gc + 1
     std::vector<int32_t> row_bounds;  // gr + 1
     std::vector<int32_t> col_bounds;  // gc + 1
@@ -75,9 +83,9 @@ void bounds_from_degrees(const int32_t* degree, int64_t nnz, int64_t size, int32
 void strip_table(const std::vector<int32_t>& bounds, int64_t size, std::vector<int32_t>& table);
 // DET schedule: one entry per block.  HOGWILD schedule: blocks cut into chunks of whole rows.
 void build_det_schedule(const Partition& part, bool xcd_affinity, Schedule& out);
-void build_hogwild_schedule(const Partition& part, const std::vector<int32_t>& pu, int32_t chunk,
+void build_hogwild_schedule(const Partition& part, const RowStarts& rs, int32_t chunk,
                             int32_t waves, bool xcd_affinity, Schedule& out);
-void build_lds_schedule(const Partition& part, const std::vector<int32_t>& pu, int32_t chunk,
+void build_lds_schedule(const Partition& part, const RowStarts& rs, int32_t chunk,
                         int32_t waves, LdsSchedule& out);
 // Deterministic mode on the LDS kernel: one entry (the whole block) per block descriptor.
 void build_det_lds_schedule(const Partition& part, LdsSchedule& out);
@@ -88,12 +96,12 @@ int64_t hogwild_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk
 
 // partition_device.hip ------------------------------------------------------------------------
 // The same partition computed on the device from COO arrays that already live in HBM: fills
-// dU, dV, dR (packed order) and `out`, and copies the packed row indices to `pu` (the schedule
-// builders read them).  Temporary device memory (about 24 bytes per rating) is allocated and
-// freed inside.  Bit-identical to build_partition.
+// dU, dV, dR (packed order), d_perm (packed position -> original position; out.perm stays
+// empty), the rest of `out`, and `rs` for the schedule builders.  Temporary device memory (about
+// 24 bytes per rating) is allocated and freed inside.  Bit-identical to build_partition.
 int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const float* d_vals, int64_t nnz,
                            int64_t m, int64_t n, int32_t gr, int32_t gc, int32_t split, int32_t* dU,
-                           int32_t* dV, float* dR, Partition& out, std::vector<int32_t>& pu,
+                           int32_t* dV, float* dR, uint32_t* d_perm, Partition& out, RowStarts& rs,
                            hipStream_t stream, std::string& err);
 
 // kernels.hip ---------------------------------------------------------------------------------

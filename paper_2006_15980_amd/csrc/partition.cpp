@@ -230,6 +230,20 @@ int build_partition(const int32_t* rows, const int32_t* cols, const float* vals,
     return MF_OK;
 }
 
+void row_starts_from_rows(const int32_t* pu, int64_t nnz, RowStarts& out)
+{
+    out.bits.assign((size_t)((nnz + 63) / 64), 0);
+    parallel_ranges((nnz + 63) / 64, host_threads(), [&](int, int64_t s, int64_t e) {
+        for (int64_t w = s; w < e; ++w) {
+            uint64_t word = 0;
+            const int64_t last = std::min<int64_t>(nnz, (w + 1) * 64);
+            for (int64_t i = w * 64; i < last; ++i)
+                if (i == 0 || pu[i] != pu[i - 1]) word |= 1ull << (i & 63);
+            out.bits[(size_t)w] = word;
+        }
+    });
+}
+
 // Entries of one stratum are laid out for a launch of kWavesPerGroup wavefronts per workgroup:
 // entry e of the stratum is taken by workgroup e / kWavesPerGroup, wavefront e % kWavesPerGroup.
 // With XCD affinity workgroup w serves die (w mod kXcds) and block row a is bound to die
@@ -293,7 +307,7 @@ void build_det_schedule(const Partition& part, bool xcd_affinity, Schedule& out)
 // ratings; a row longer than 2*chunk is cut into pieces of `chunk`, each flagged (sign bit of
 // the length) as sharing its row of P with other entries.  emit(begin, length_with_flag).
 template <class Emit>
-static void chunk_block(const std::vector<int32_t>& pu, int64_t pos, int64_t end, int32_t chunk, Emit emit_raw)
+static void chunk_block(const RowStarts& rs, int64_t pos, int64_t end, int32_t chunk, Emit emit_raw)
 {
     const int32_t long_row = 2 * chunk;
     auto emit = [&](int64_t b, int64_t e, bool shares_row) {
@@ -305,7 +319,7 @@ static void chunk_block(const std::vector<int32_t>& pu, int64_t pos, int64_t end
     int64_t cur = pos;   // start of the chunk being filled with whole rows
     while (pos < end) {
         int64_t row_end = pos + 1;
-        while (row_end < end && pu[row_end] == pu[pos]) ++row_end;
+        while (row_end < end && !rs.starts(row_end)) ++row_end;
         if (row_end - pos > long_row) {
             emit(cur, pos, false);
             for (int64_t b = pos; b < row_end; b += chunk) emit(b, std::min<int64_t>(b + chunk, row_end), true);
@@ -324,7 +338,7 @@ static void chunk_block(const std::vector<int32_t>& pu, int64_t pos, int64_t end
 // lengths (a very long row), the cut stays inside the row and the chunks on both sides of it
 // are flagged as sharing a row of P.
 template <class Emit>
-static void chunk_block_even(const std::vector<int32_t>& pu, int64_t pos, int64_t end, int32_t pieces, Emit emit_raw)
+static void chunk_block_even(const RowStarts& rs, int64_t pos, int64_t end, int32_t pieces, Emit emit_raw)
 {
     const int64_t size = end - pos;
     if (size <= 0) return;
@@ -336,7 +350,7 @@ static void chunk_block_even(const std::vector<int32_t>& pu, int64_t pos, int64_
         bool ends_inside_row = false;
         if (cut < end) {
             int64_t b = cut;
-            while (b < end && pu[b] == pu[b - 1]) ++b;
+            while (b < end && !rs.starts(b)) ++b;
             if (b - cut > 2 * target) ends_inside_row = true;   // keep the cut inside the long row
             else cut = b;
         }
@@ -348,7 +362,7 @@ static void chunk_block_even(const std::vector<int32_t>& pu, int64_t pos, int64_
     }
 }
 
-void build_hogwild_schedule(const Partition& part, const std::vector<int32_t>& pu, int32_t chunk,
+void build_hogwild_schedule(const Partition& part, const RowStarts& rs, int32_t chunk,
                             int32_t waves, bool xcd_affinity, Schedule& out)
 {
     // chunk == 0: at most `waves` chunks per block, which bounds the number of wavefronts that
@@ -367,15 +381,15 @@ void build_hogwild_schedule(const Partition& part, const std::vector<int32_t>& p
                 int die = xcd_affinity ? a % kXcds : (int)(spread++ % kXcds);
                 per_die[die].push_back({b, len});
             };
-            if (chunk > 0) chunk_block(pu, part.block_ptr[L], part.block_ptr[L + 1], chunk, push);
-            else chunk_block_even(pu, part.block_ptr[L], part.block_ptr[L + 1], waves, push);
+            if (chunk > 0) chunk_block(rs, part.block_ptr[L], part.block_ptr[L + 1], chunk, push);
+            else chunk_block_even(rs, part.block_ptr[L], part.block_ptr[L + 1], waves, push);
         }
         lay_out_stratum(per_die, xcd_affinity, out);
         out.stratum_entry[(size_t)s + 1] = (int64_t)out.begin.size();
     }
 }
 
-void build_lds_schedule(const Partition& part, const std::vector<int32_t>& pu, int32_t chunk,
+void build_lds_schedule(const Partition& part, const RowStarts& rs, int32_t chunk,
                         int32_t waves, LdsSchedule& out)
 {
     // chunk == 0: cut every block into about one chunk per wavefront of its workgroup
@@ -401,8 +415,8 @@ void build_lds_schedule(const Partition& part, const std::vector<int32_t>& pu, i
                 out.begin.push_back(pos);
                 out.len.push_back(len);
             };
-            if (chunk > 0) chunk_block(pu, part.block_ptr[L], part.block_ptr[L + 1], chunk, push);
-            else chunk_block_even(pu, part.block_ptr[L], part.block_ptr[L + 1], waves, push);
+            if (chunk > 0) chunk_block(rs, part.block_ptr[L], part.block_ptr[L + 1], chunk, push);
+            else chunk_block_even(rs, part.block_ptr[L], part.block_ptr[L + 1], waves, push);
             blk.n_entries = (int32_t)((int64_t)out.begin.size() - blk.first_entry);
             out.blocks.push_back(blk);
             out.ring[(size_t)L] = blk;

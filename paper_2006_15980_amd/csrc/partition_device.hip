@@ -7,12 +7,15 @@
 // rating, (block id L, row inside its strip, column inside its strip) from the most to the
 // least significant bits, payload = original position -> stable least-significant-digit radix
 // sort over the used bits, 8 bits per pass -> keys decoded into the packed row / column
-// arrays, values gathered through the payload.  The payload starts in ascending original
+// arrays, values gathered through the payload (which stays on the device as the permutation).  The payload starts in ascending original
 // position and every pass is stable, so equal (L, row, column) stay in original order: the
 // result is the order (L, row, column, original position) the host partitioner produces.
 #include "mf_internal.h"
 
 #include <algorithm>
+#include <chrono>
+#include <cstdio>
+#include <cstdlib>
 
 #include "../../include/mf_sgd.h"
 
@@ -263,7 +266,7 @@ __global__ __launch_bounds__(kSortThreads) void unpack_keys(
     const uint64_t* __restrict__ keys, const uint32_t* __restrict__ payload, int64_t nnz,
     const int32_t* __restrict__ row_bounds, const int32_t* __restrict__ col_bounds, int32_t gr, int32_t gc,
     int ubits, int vbits, const float* __restrict__ vals, int32_t* __restrict__ U, int32_t* __restrict__ V,
-    float* __restrict__ R)
+    float* __restrict__ R, uint32_t* __restrict__ perm)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nnz; i += stride) {
@@ -274,9 +277,41 @@ __global__ __launch_bounds__(kSortThreads) void unpack_keys(
         if (b >= gc) b -= gc;
         U[i] = row_bounds[a] + (int32_t)((k >> vbits) & ((1ull << ubits) - 1ull));
         V[i] = col_bounds[b] + (int32_t)(k & ((1ull << vbits) - 1ull));
-        R[i] = vals[payload[i]];
+        const uint32_t t = payload[i];
+        R[i] = vals[t];
+        perm[i] = t;
     }
 }
+
+// Word w of `words`: bit j set when packed rating 64*w + j has another row index than the
+// rating before it (rating 0 always).  One wavefront per word.
+__global__ __launch_bounds__(kSortThreads) void row_start_words(const int32_t* __restrict__ U, int64_t nnz,
+                                                              uint64_t* __restrict__ words, int64_t nwords)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t waves = (int64_t)gridDim.x * kSortWaves;
+    for (int64_t w = (int64_t)blockIdx.x * kSortWaves + (threadIdx.x >> 6); w < nwords; w += waves) {
+        const int64_t i = w * kWave + lane;
+        const bool start = i < nnz && (i == 0 || U[i] != U[i - 1]);
+        const uint64_t word = __ballot(start);
+        if (lane == 0) words[w] = word;
+    }
+}
+
+// MF_LOAD_TIMING=1 in the environment: stage times of the device partitioner on stderr.
+struct StageTimer {
+    bool on = std::getenv("MF_LOAD_TIMING") != nullptr;
+    std::chrono::steady_clock::time_point t0 = std::chrono::steady_clock::now();
+    void mark(const char* what, hipStream_t stream)
+    {
+        if (!on) return;
+        (void)hipStreamSynchronize(stream);
+        auto t1 = std::chrono::steady_clock::now();
+        std::fprintf(stderr, "[mf_load_blocks_device] %-28s %8.3f ms\n", what,
+                     std::chrono::duration<double, std::milli>(t1 - t0).count());
+        t0 = t1;
+    }
+};
 
 int bits_for(int64_t values)   // bits needed to tell `values` different numbers apart
 {
@@ -300,11 +335,12 @@ int streaming_groups(int64_t items) { return (int)std::max<int64_t>(1, std::min<
 
 int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const float* d_vals, int64_t nnz,
                            int64_t m, int64_t n, int32_t gr, int32_t gc, int32_t split, int32_t* dU,
-                           int32_t* dV, float* dR, Partition& out, std::vector<int32_t>& pu,
+                           int32_t* dV, float* dR, uint32_t* d_perm, Partition& out, RowStarts& rs,
                            hipStream_t stream, std::string& err)
 {
     const int64_t nblocks = (int64_t)gr * gc;
     const bool balanced = split != MF_SPLIT_EQUAL_WIDTH;
+    StageTimer timer;
     out.nnz = nnz;
     out.gr = gr;
     out.gc = gc;
@@ -343,9 +379,10 @@ int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const f
         equal_width_bounds(m, gr, out.row_bounds);
         equal_width_bounds(n, gc, out.col_bounds);
     }
+    timer.mark("degrees and bounds", stream);
     out.block_ptr.assign((size_t)nblocks + 1, 0);
     out.perm.clear();
-    pu.clear();
+    rs.bits.clear();
     if (nnz == 0) return MF_OK;
 
     // ---- key layout
@@ -375,6 +412,7 @@ int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const f
     PD_HIP(hipMemcpy(d_col_bounds.p, out.col_bounds.data(), ((size_t)gc + 1) * 4, hipMemcpyHostToDevice));
     PD_HIP(hipMemsetAsync(block_count.p, 0, (size_t)nblocks * 4, stream));
 
+    timer.mark("strip tables", stream);
     // ---- keys, payload, block sizes
     const int64_t ntiles = (nnz + kSortTile - 1) / kSortTile;
     const int64_t hist_len = (int64_t)kRadix * ntiles;
@@ -391,6 +429,7 @@ int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const f
                        d_col_bounds.as<int32_t>(), gr, gc, ubits, vbits, keys[0].as<uint64_t>(),
                        payload[0].as<uint32_t>(), block_count.as<int32_t>());
     PD_HIP(hipGetLastError());
+    timer.mark("allocations and keys", stream);
 
     // ---- stable radix passes over the used bits
     int cur = 0;
@@ -409,14 +448,22 @@ int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const f
         cur ^= 1;
     }
 
+    timer.mark("radix passes", stream);
     // ---- packed arrays
     hipLaunchKernelGGL(unpack_keys, dim3(streaming_groups(nnz)), dim3(kSortThreads), 0, stream,
                        keys[cur].as<uint64_t>(), payload[cur].as<uint32_t>(), nnz, d_row_bounds.as<int32_t>(),
-                       d_col_bounds.as<int32_t>(), gr, gc, ubits, vbits, d_vals, dU, dV, dR);
+                       d_col_bounds.as<int32_t>(), gr, gc, ubits, vbits, d_vals, dU, dV, dR, d_perm);
+    PD_HIP(hipGetLastError());
+    const int64_t nwords = (nnz + kWave - 1) / kWave;
+    DeviceBuffer words;
+    PD_HIP(words.alloc((size_t)nwords * 8));
+    hipLaunchKernelGGL(row_start_words, dim3(streaming_groups(nwords * kWave / kSortWaves)), dim3(kSortThreads), 0, stream,
+                       dU, nnz, words.as<uint64_t>(), nwords);
     PD_HIP(hipGetLastError());
     PD_HIP(hipStreamSynchronize(stream));
 
-    // ---- what the host keeps: block boundaries, the permutation, the packed row indices
+    timer.mark("unpack", stream);
+    // ---- what the host needs for the work lists: block boundaries and where the row runs begin
     {
         std::vector<int32_t> counts((size_t)nblocks);
         PD_HIP(hipMemcpy(counts.data(), block_count.p, (size_t)nblocks * 4, hipMemcpyDeviceToHost));
@@ -427,14 +474,9 @@ int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const f
         }
         out.block_ptr[(size_t)nblocks] = run;
     }
-    {
-        std::vector<uint32_t> narrow((size_t)nnz);
-        PD_HIP(hipMemcpy(narrow.data(), payload[cur].p, (size_t)nnz * 4, hipMemcpyDeviceToHost));
-        out.perm.resize((size_t)nnz);
-        for (int64_t i = 0; i < nnz; ++i) out.perm[(size_t)i] = (int64_t)narrow[(size_t)i];
-    }
-    pu.resize((size_t)nnz);
-    PD_HIP(hipMemcpy(pu.data(), dU, (size_t)nnz * 4, hipMemcpyDeviceToHost));
+    rs.bits.resize((size_t)nwords);
+    PD_HIP(hipMemcpy(rs.bits.data(), words.p, (size_t)nwords * 8, hipMemcpyDeviceToHost));
+    timer.mark("block sizes and row starts", stream);
     return MF_OK;
 }
 
