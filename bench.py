@@ -95,6 +95,8 @@ def main():
     ap.add_argument("--affinity", type=int, default=1)
     ap.add_argument("--split", type=int, default=1, help="0 equal width, 1 ratings balanced, 2 ratings and width balanced")
     ap.add_argument("--ring", type=int, default=1, help="1: one launch per epoch (workgroups hand the strips round)")
+    ap.add_argument("--load", default="device", choices=["host", "device"],
+                    help="partition on the host (mf_load_blocks) or on the GPU (mf_load_blocks_device); outside the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -138,9 +140,20 @@ def main():
             mf.MF_OPT_HOGWILD_KERNEL: which,
             mf.MF_OPT_LDS_CHUNK: args.lds_chunk, mf.MF_OPT_LDS_WAVES: args.lds_waves, mf.MF_OPT_RING: args.ring}
     model = mf.MatrixFactorization(cfg.m, cfg.n, k, cfg.storage, seed=1, scale=0.1, options=opts)
-    t0 = time.perf_counter()
-    model.load_blocks(ds.rows, ds.cols, ds.vals, gr, gc, args.split)
-    t_load = time.perf_counter() - t0
+    if args.load == "device":
+        import torch
+        coo = [torch.from_numpy(x).to(model.P.device) for x in (ds.rows, ds.cols, ds.vals)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        model.load_blocks_device(coo[0], coo[1], coo[2], gr, gc, args.split)
+        model.sync()
+        t_load = time.perf_counter() - t0
+        del coo
+    else:
+        t0 = time.perf_counter()
+        model.load_blocks(ds.rows, ds.cols, ds.vals, gr, gc, args.split)
+        model.sync()
+        t_load = time.perf_counter() - t0
     tr, tc, tv = model.to_device(ds.test_rows, ds.test_cols, ds.test_vals)
     nnz = ds.rows.size
 
@@ -199,7 +212,7 @@ def main():
                       "chunk": args.chunk,
                       "xcd_affinity": args.affinity,
                       "lr": cfg.lr, "lambda": cfg.lam},
-           "final_test_rmse": rmse, "load_blocks_s": t_load,
+           "final_test_rmse": rmse, "load_blocks_s": t_load, "load_path": args.load,
            "algorithmic_gbs": value * bytes_per_update / 1e9,
            "hbm_roofline_frac": value * bytes_per_update / 1e9 / HBM_PEAK_GBS,
            "roofline": roofline}
