@@ -333,6 +333,59 @@ int mfo_sgd_epoch_omp(double* P, double* Qt, int32_t k, const int32_t* rows, con
     return 0;
 }
 
+/* Randomised visiting order (the paper's scheduler hands out blocks "randomly", Section 3.1
+ * and Example 3; it fixes no generator).  Convention of this build: per epoch a permutation
+ * of the strata, still exactly once per epoch and still deterministic -- stratum s gets the key
+ * mix64(mix64(seed ^ epoch * 0xD1B54A32D192ED03) + s) and the strata are visited in ascending
+ * (key, s).  order[t] = stratum visited at step t. */
+uint64_t mfo_mix64(uint64_t z) { return mix64(z); }
+
+void mfo_stratum_order(uint64_t seed, uint64_t epoch, int32_t G_c, int32_t* order)
+{
+    uint64_t base = mix64(seed ^ (epoch * 0xD1B54A32D192ED03ULL));
+    uint64_t* key = (uint64_t*)malloc((size_t)G_c * sizeof(uint64_t));
+    for (int32_t s = 0; s < G_c; ++s) key[s] = mix64(base + (uint64_t)s);
+    /* selection by repeated minimum: quadratic, obviously a sort by (key, s) */
+    char* used = (char*)calloc((size_t)G_c, 1);
+    for (int32_t t = 0; t < G_c; ++t) {
+        int32_t best = -1;
+        for (int32_t s = 0; s < G_c; ++s)
+            if (!used[s] && (best < 0 || key[s] < key[best])) best = s;   /* ties: the smaller s stays */
+        used[best] = 1;
+        order[t] = best;
+    }
+    free(used);
+    free(key);
+}
+
+/* One epoch with the strata visited in the given order (a permutation of 0..G_c-1); inside a
+ * stratum and inside a block as mfo_sgd_epoch.  parallel != 0 runs the independent blocks of a
+ * stratum on OpenMP threads (bit-identical, as for mfo_sgd_epoch_omp). */
+int mfo_sgd_epoch_ordered(double* P, double* Qt, int32_t k, const int32_t* rows, const int32_t* cols,
+                          const float* vals, const int64_t* perm, const int64_t* block_ptr,
+                          int32_t G_r, int32_t G_c, float lr, float lambda, int arith,
+                          const int32_t* stratum_order, int parallel, int32_t* visits)
+{
+    if (arith < 0 || arith > 2 || k < 1 || !stratum_order) return -1;
+    for (int32_t t = 0; t < G_c; ++t) {
+        int32_t s = stratum_order[t];
+        if (s < 0 || s >= G_c) return -2;
+        if (parallel && !visits) {
+#pragma omp parallel for schedule(dynamic, 1)
+            for (int32_t a = 0; a < G_r; ++a) {
+                int64_t L = (int64_t)s * G_r + a;
+                run_block(P, Qt, k, rows, cols, vals, perm, block_ptr[L], block_ptr[L + 1], lr, lambda, arith, 0);
+            }
+        } else {
+            for (int32_t a = 0; a < G_r; ++a) {
+                int64_t L = (int64_t)s * G_r + a;
+                run_block(P, Qt, k, rows, cols, vals, perm, block_ptr[L], block_ptr[L + 1], lr, lambda, arith, visits);
+            }
+        }
+    }
+    return 0;
+}
+
 /* Plain Algorithm 1 over the ratings in the order given (no grid): used by pins. */
 void mfo_sgd_sweep(double* P, double* Qt, int32_t k, const int32_t* rows, const int32_t* cols,
                    const float* vals, int64_t nnz, float lr, float lambda, int arith)

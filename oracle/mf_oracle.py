@@ -19,7 +19,8 @@ __all__ = ["ARITH_F64", "ARITH_F32", "ARITH_F16", "SPLIT_EQUAL_WIDTH", "SPLIT_NN
            "SPLIT_NNZ_WIDTH_BALANCED", "bounds_nnz_width_balanced",
            "round_f16", "init_factors", "partition", "blocks_independent", "sgd_step",
            "sgd_epoch", "sgd_epoch_omp", "sgd_sweep", "predict", "rating_loss", "rmse",
-           "num_threads", "bounds_equal_width", "bounds_nnz_balanced"]
+           "num_threads", "bounds_equal_width", "bounds_nnz_balanced", "mix64", "stratum_order",
+           "sgd_epoch_ordered"]
 
 _lib = None
 
@@ -118,6 +119,33 @@ def sgd_epoch_omp(P, Qt, rows, cols, vals, perm, block_ptr, G_r, G_c, lr, lam, a
                                    _p(cols, np.int32), _p(vals, np.float32), _p(perm, np.int64),
                                    _p(block_ptr, np.int64), C.c_int32(G_r), C.c_int32(G_c), C.c_float(lr),
                                    C.c_float(lam), C.c_int(arith))
+    assert rc == 0
+
+
+def mix64(z: int) -> int:
+    f = _load().mfo_mix64
+    f.restype = C.c_uint64
+    return int(f(C.c_uint64(z & 0xFFFFFFFFFFFFFFFF)))
+
+
+def stratum_order(seed: int, epoch: int, G_c: int) -> np.ndarray:
+    """Per-epoch permutation of the strata (order[t] = stratum visited at step t)."""
+    out = np.empty(G_c, np.int32)
+    _load().mfo_stratum_order(C.c_uint64(seed), C.c_uint64(epoch), C.c_int32(G_c), _p(out, np.int32))
+    return out
+
+
+def sgd_epoch_ordered(P, Qt, rows, cols, vals, perm, block_ptr, G_r, G_c, lr, lam, order, arith=ARITH_F64,
+                      parallel=True, visits=None):
+    k = P.shape[1]
+    order = np.ascontiguousarray(order, np.int32)
+    assert order.size == G_c
+    rc = _load().mfo_sgd_epoch_ordered(_p(P, np.float64), _p(Qt, np.float64), C.c_int32(k), _p(rows, np.int32),
+                                       _p(cols, np.int32), _p(vals, np.float32), _p(perm, np.int64),
+                                       _p(block_ptr, np.int64), C.c_int32(G_r), C.c_int32(G_c), C.c_float(lr),
+                                       C.c_float(lam), C.c_int(arith), _p(order, np.int32),
+                                       C.c_int(1 if parallel else 0),
+                                       _p(visits, np.int32) if visits is not None else None)
     assert rc == 0
 
 

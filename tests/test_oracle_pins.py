@@ -324,6 +324,68 @@ def test_block_order_inside_strata_and_openmp_are_bit_identical():
         assert not np.array_equal(A[0], P0)
 
 
+# --------------------------------------------------------------------------- randomised stratum order
+def test_mixer_reproduces_the_published_splitmix64_stream(golden_dir):
+    """The oracle's mixer is the SplitMix64 output function: fed with seed + i * increment it must
+    give that generator's published first outputs for seed 1234567 (fixture with its source)."""
+    g = _read_golden(os.path.join(golden_dir, "splitmix64_seed1234567.txt"))
+    want = [int(g[f"x{i}"][0]) for i in range(5)]
+    golden_ratio = 0x9E3779B97F4A7C15
+    got = [oracle.mix64(1234567 + i * golden_ratio) for i in range(len(want))]
+    assert got == want
+
+
+def test_stratum_order_is_a_reproducible_permutation_sorted_by_its_keys():
+    for gc in (1, 2, 7, 64, 333):
+        o = oracle.stratum_order(5, 3, gc)
+        assert sorted(o.tolist()) == list(range(gc))
+        assert np.array_equal(o, oracle.stratum_order(5, 3, gc))
+        # independent restatement: argsort of the keys, ties by index (keys via the pinned mixer)
+        base = oracle.mix64(5 ^ ((3 * 0xD1B54A32D192ED03) & 0xFFFFFFFFFFFFFFFF))
+        keys = [oracle.mix64((base + s) & 0xFFFFFFFFFFFFFFFF) for s in range(gc)]
+        assert o.tolist() == sorted(range(gc), key=lambda s: (keys[s], s))
+    a, b, c = oracle.stratum_order(5, 0, 64), oracle.stratum_order(5, 1, 64), oracle.stratum_order(6, 0, 64)
+    assert not np.array_equal(a, b) and not np.array_equal(a, c)
+    # no position is favoured: over many epochs stratum 0 lands everywhere about equally often
+    gc = 8
+    hits = np.zeros(gc)
+    for e in range(4000):
+        hits[oracle.stratum_order(11, e, gc).tolist().index(0)] += 1
+    assert hits.min() > 400 and hits.max() < 600          # mean 500, sd 21
+
+
+def test_ordered_epoch_is_the_blocks_swept_in_that_order_exactly_once():
+    ds = workloads.generate(workloads.scaled(workloads.CONFIGS["medium"], 0.003, k=16))
+    m, n, k = ds.cfg.m, ds.cfg.n, 16
+    gr, gc = 5, 9
+    perm, bp, _, _ = oracle.partition(ds.rows, ds.cols, m, n, gr, gc, oracle.SPLIT_NNZ_BALANCED)
+    P0 = oracle.init_factors(m * k, 1, 0, 0.1).reshape(m, k)
+    Q0 = oracle.init_factors(n * k, 1, 1, 0.1).reshape(n, k)
+    order = oracle.stratum_order(9, 2, gc)
+    assert not np.array_equal(order, np.arange(gc))
+    for arith in (oracle.ARITH_F64, oracle.ARITH_F16):
+        ident = (P0.copy(), Q0.copy())
+        plain = (P0.copy(), Q0.copy())
+        oracle.sgd_epoch_ordered(*ident, ds.rows, ds.cols, ds.vals, perm, bp, gr, gc, 0.01, 0.05, np.arange(gc), arith)
+        oracle.sgd_epoch(*plain, ds.rows, ds.cols, ds.vals, perm, bp, gr, gc, 0.01, 0.05, arith)
+        assert np.array_equal(ident[0], plain[0]) and np.array_equal(ident[1], plain[1])
+        # the given order = plain sweeps (another entry point) over the blocks' ratings, stratum after stratum
+        A = (P0.copy(), Q0.copy())
+        B = (P0.copy(), Q0.copy())
+        Cc = (P0.copy(), Q0.copy())
+        visits = np.zeros(ds.rows.size, np.int32)
+        oracle.sgd_epoch_ordered(*A, ds.rows, ds.cols, ds.vals, perm, bp, gr, gc, 0.01, 0.05, order, arith, parallel=False,
+                                 visits=visits)
+        oracle.sgd_epoch_ordered(*Cc, ds.rows, ds.cols, ds.vals, perm, bp, gr, gc, 0.01, 0.05, order, arith, parallel=True)
+        for s in order:
+            sel = perm[bp[s * gr]:bp[(s + 1) * gr]]
+            oracle.sgd_sweep(*B, ds.rows[sel], ds.cols[sel], ds.vals[sel], 0.01, 0.05, arith)
+        assert np.array_equal(visits, np.ones_like(visits))
+        assert np.array_equal(A[0], B[0]) and np.array_equal(A[1], B[1])
+        assert np.array_equal(A[0], Cc[0]) and np.array_equal(A[1], Cc[1])
+        assert not np.array_equal(A[1], plain[1])          # the order does matter across strata
+
+
 # --------------------------------------------------------------------------- convergence on noiseless planted data
 def test_noiseless_planted_low_rank_reaches_near_zero_rmse():
     m, n, rank = 150, 120, 3
