@@ -170,6 +170,21 @@ int mf_get_partition(const mf_ctx* ctx, int64_t* perm, int64_t* block_ptr,
  * the next mf_sync / mf_rmse returns MF_EDEVICE. */
 int mf_sgd_epoch(mf_ctx* ctx, float lr, float lambda, int32_t mode);
 
+/* One epoch with the strata visited in a given order (the paper's scheduler hands blocks out
+ * "randomly", Section 3.1; Example 3 argues for balanced, random visiting): stratum_order is a HOST
+ * array of grid_c numbers, a permutation of 0 .. grid_c-1, stratum_order[t] = stratum of step t;
+ * NULL = natural order (then the call is mf_sgd_epoch).  Every rating is still visited exactly
+ * once, blocks of a stratum and ratings of a block as in mf_sgd_epoch; MF_MODE_DET stays
+ * deterministic.  With an order given, the call waits for the stream's earlier work before it
+ * uploads the order.  MF_EINVAL if stratum_order is not a permutation. */
+int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, const int32_t* stratum_order);
+
+/* Host-only: the per-epoch stratum permutation this library proposes (a convention, the paper
+ * names no generator): stratum s gets the key mix(mix(seed ^ epoch * 0xD1B54A32D192ED03) + s) with
+ * mix = the SplitMix64 output function, strata in ascending (key, s).  order_out: HOST, grid_c
+ * numbers. */
+int mf_stratum_order(uint64_t seed, uint64_t epoch, int32_t grid_c, int32_t* order_out);
+
 /* RMSE = sqrt(mean (r - p_u.q_v)^2) of the current factors (the quality metric of Section 7).
  *   d_rows, d_cols, d_vals : DEVICE arrays of `count` entries, caller-owned; if d_rows is NULL
  *                            the loaded training ratings are used and count is ignored.

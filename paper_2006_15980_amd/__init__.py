@@ -78,8 +78,13 @@ class MatrixFactorization:
     def partition(self):
         return binding.mf_get_partition(self.ctx, self.nnz, *self.grid)
 
-    def sgd_epoch(self, lr: float, lam: float, mode: int):
-        binding.mf_sgd_epoch(self.ctx, lr, lam, mode)
+    def sgd_epoch(self, lr: float, lam: float, mode: int, stratum_order=None):
+        if stratum_order is None:
+            binding.mf_sgd_epoch(self.ctx, lr, lam, mode)
+        else:
+            if len(stratum_order) != self.grid[1]:
+                raise ValueError("stratum_order needs grid_c entries")
+            binding.mf_sgd_epoch_ordered(self.ctx, lr, lam, mode, np.ascontiguousarray(stratum_order, np.int32))
 
     def rmse(self, rows=None, cols=None, vals=None) -> float:
         if rows is None:

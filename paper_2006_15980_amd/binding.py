@@ -29,6 +29,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmf_sgd.s
 
 EXPORTS = ["mf_create", "mf_destroy", "mf_last_error", "mf_set_option", "mf_init",
            "mf_load_blocks_workspace", "mf_load_blocks", "mf_load_blocks_device", "mf_get_partition", "mf_sgd_epoch",
+           "mf_sgd_epoch_ordered", "mf_stratum_order",
            "mf_rmse", "mf_sync", "mf_profile_read", "mf_debug_xcc_ids", "mf_plan_host", "mf_suggest_grid"]
 
 
@@ -60,6 +61,8 @@ def lib() -> C.CDLL:
         l.mf_load_blocks_device.argtypes = [vp, vp, vp, vp, i64, i32, i32, i32, vp, C.c_size_t]
         l.mf_get_partition.argtypes = [vp, vp, vp, vp, vp]
         l.mf_sgd_epoch.argtypes = [vp, f32, f32, i32]
+        l.mf_sgd_epoch_ordered.argtypes = [vp, f32, f32, i32, vp]
+        l.mf_stratum_order.argtypes = [C.c_uint64, C.c_uint64, i32, vp]
         l.mf_rmse.argtypes = [vp, vp, vp, vp, i64, C.POINTER(C.c_double)]
         l.mf_sync.argtypes = [vp]
         l.mf_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -145,6 +148,19 @@ def mf_get_partition(ctx: int, nnz: int, grid_r: int, grid_c: int):
 
 def mf_sgd_epoch(ctx: int, lr: float, lam: float, mode: int) -> None:
     _check(ctx, lib().mf_sgd_epoch(ctx, lr, lam, mode))
+
+
+def mf_sgd_epoch_ordered(ctx: int, lr: float, lam: float, mode: int, stratum_order: Optional[np.ndarray]) -> None:
+    order = None if stratum_order is None else _host(stratum_order, np.int32)
+    _check(ctx, lib().mf_sgd_epoch_ordered(ctx, lr, lam, mode, order))
+
+
+def mf_stratum_order(seed: int, epoch: int, grid_c: int) -> np.ndarray:
+    out = np.empty(grid_c, np.int32)
+    rc = lib().mf_stratum_order(seed, epoch, grid_c, out.ctypes.data)
+    if rc != MF_OK:
+        raise MFError(rc, "mf_stratum_order failed")
+    return out
 
 
 def mf_rmse(ctx: int, d_rows: Optional[int], d_cols: Optional[int], d_vals: Optional[int], count: int) -> float:

@@ -928,14 +928,19 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_block_lds(
 }
 
 // One launch per EPOCH: workgroup a keeps block row a for the whole epoch (its rows of P are
-// never touched by anyone else) and walks the strata s = 0 .. grid_c-1 on blocks
-// (a, (a+s) mod grid_c); the column strips of Qt rotate through the workgroups (the rotation of
-// distributed SGD, here between compute units instead of machines).  The only other user of
-// column strip (a+s) mod grid_c is the workgroup of the next block row one stratum earlier, so
-// before stratum s workgroup a waits until done[a+1] >= first + s (the last block row waits
-// for block row 0 having finished stratum s - (grid_c - grid_r) - 1); every workgroup waits
-// also when its own block is empty, which keeps the chain of guarantees unbroken.  `done`
-// counts strata finished since mf_load_blocks (`first` = its value before this epoch).
+// never touched by anyone else) and walks the strata on blocks (a, (a+s) mod grid_c); the column
+// strips of Qt rotate through the workgroups (the rotation of distributed SGD, here between
+// compute units instead of machines).  `done[a]` counts the steps block row a has finished since
+// mf_load_blocks (`first` = its value before this epoch).  Before step t a workgroup waits for
+// the most recent earlier user of its column strip; that one waited for its own predecessor
+// (every workgroup waits also when its block is empty), so the chain of guarantees is unbroken.
+//   Strata in natural order (order == nullptr): the only other user of strip (a+s) mod grid_c
+//   is the next block row one stratum earlier, so workgroup a waits for done[a+1] >= first + s
+//   (the last block row waits for block row 0 having finished stratum s - (grid_c - grid_r) - 1).
+//   Strata in a given order (order[t] = stratum of step t, pos = its inverse): the earlier users
+//   of strip c are the block rows a' != a at the steps pos[(c - a') mod grid_c] that lie before
+//   t; the first wavefront takes the latest of them (one look-up per block row, a wave-wide
+//   maximum) and waits for that block row to have finished that step.
 // All grid_r workgroups must be resident at once (checked by the host before launching).
 // Every wait is bounded: after spin_limit polls a workgroup raises *abort_flag and leaves, and
 // every waiting workgroup leaves as soon as it sees the flag, so the grid always drains.
@@ -945,36 +950,61 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_ring_lds(
     const int32_t* __restrict__ V, const float* __restrict__ R,
     const int64_t* __restrict__ entry_begin, const int32_t* __restrict__ entry_len,
     const LdsBlock* __restrict__ ring_blocks, int grid_r, int grid_c, float lr, float lambda,
-    int* done, int first, int* abort_flag, long long spin_limit)
+    int* done, int first, int* abort_flag, long long spin_limit, const int32_t* __restrict__ order,
+    const int32_t* __restrict__ pos)
 {
     extern __shared__ int strip[];
     __shared__ int go;
     const int a = (int)blockIdx.x;
-    const int waits_on = a + 1 < grid_r ? a + 1 : 0;
+    const int next_row = a + 1 < grid_r ? a + 1 : 0;
     const int lag = a + 1 < grid_r ? 0 : grid_c - grid_r;
-    for (int s = 0; s < grid_c; ++s) {
-        // wait (bounded) until the previous user of this stratum's column strip has reported it
+    for (int t = 0; t < grid_c; ++t) {
+        const int s = order ? order[t] : t;
+        // wait (bounded) until the previous user of this step's column strip has reported it
         // finished; returns false when the workgroup has to leave
         auto wait_for_strip = [&]() -> bool {
-            if (threadIdx.x == 0) {
-                int ok = 1;
-                const int need = first + s - lag;
-                if (s - lag > 0) {
-                    long long polls = 0;
-                    while (__hip_atomic_load(done + waits_on, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < need) {
-                        if (__hip_atomic_load(abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
-                            ok = 0;
-                            break;
-                        }
-                        if (++polls > spin_limit) {
-                            __hip_atomic_store(abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            ok = 0;
-                            break;
-                        }
-                        __builtin_amdgcn_s_sleep(2);
+            if (threadIdx.x < kWave) {
+                int waits_on = next_row;
+                int need = first + t - lag;          // value of done[waits_on] to wait for
+                bool must_wait = t - lag > 0;
+                if (order) {
+                    int c = a + s;
+                    if (c >= grid_c) c -= grid_c;
+                    int latest = -1;                 // latest earlier step at which another block row used strip c
+                    for (int other = (int)threadIdx.x; other < grid_r; other += kWave) {
+                        int s_other = c - other;
+                        if (s_other < 0) s_other += grid_c;
+                        const int t_other = pos[s_other];
+                        if (other != a && t_other < t) latest = max(latest, t_other);
+                    }
+#pragma unroll
+                    for (int d = 32; d >= 1; d >>= 1) latest = max(latest, __shfl_xor(latest, d, kWave));
+                    must_wait = latest >= 0;
+                    if (must_wait) {
+                        waits_on = c - order[latest];
+                        if (waits_on < 0) waits_on += grid_c;
+                        need = first + latest + 1;
                     }
                 }
-                go = ok;
+                if (threadIdx.x == 0) {
+                    int ok = 1;
+                    if (must_wait) {
+                        long long polls = 0;
+                        while (__hip_atomic_load(done + waits_on, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < need) {
+                            if (__hip_atomic_load(abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                                ok = 0;
+                                break;
+                            }
+                            if (++polls > spin_limit) {
+                                __hip_atomic_store(abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                ok = 0;
+                                break;
+                            }
+                            __builtin_amdgcn_s_sleep(2);
+                        }
+                    }
+                    go = ok;
+                }
             }
             __syncthreads();
             return go != 0;                        // the same answer in every thread of the workgroup
@@ -987,12 +1017,12 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_ring_lds(
         else
             ok = wait_for_strip();   // an empty block still waits: it passes the guarantee on
         if (!ok) return;
-        // every thread's stores of the strip have been acknowledged before the stratum is
+        // every thread's stores of the strip have been acknowledged before the step is
         // reported finished
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         if (threadIdx.x == 0)
-            __hip_atomic_store(done + a, first + s + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(done + a, first + t + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -1133,7 +1163,8 @@ hipError_t launch_sgd_ring_impl(int waves, bool query_only, int* max_resident, v
                                 const int32_t* U, const int32_t* V, const float* R, const int64_t* eb,
                                 const int32_t* el, const LdsBlock* ring_blocks, int grid_r, int grid_c,
                                 size_t lds_bytes, float lr, float lambda, int* done, int first,
-                                int* abort_flag, long long spin_limit, hipStream_t stream)
+                                int* abort_flag, long long spin_limit, const int32_t* order, const int32_t* pos,
+                                hipStream_t stream)
 {
     static bool raised[64] = {};
     int dev = 0;
@@ -1157,7 +1188,7 @@ hipError_t launch_sgd_ring_impl(int waves, bool query_only, int* max_resident, v
     }
     hipLaunchKernelGGL((sgd_ring_lds<T, K, EXACT>), dim3((unsigned)grid_r), dim3(waves * kWave), lds_bytes,
                        stream, (T*)P, (T*)Qt, U, V, R, eb, el, ring_blocks, grid_r, grid_c, lr, lambda, done,
-                       first, abort_flag, spin_limit);
+                       first, abort_flag, spin_limit, order, pos);
     return hipGetLastError();
 }
 
@@ -1166,15 +1197,15 @@ hipError_t launch_sgd_ring_t(bool exact, int waves, bool query_only, int* max_re
                              const int32_t* U, const int32_t* V, const float* R, const int64_t* eb,
                              const int32_t* el, const LdsBlock* ring_blocks, int grid_r, int grid_c,
                              size_t lds_bytes, float lr, float lambda, int* done, int first, int* abort_flag,
-                             long long spin_limit, hipStream_t stream)
+                             long long spin_limit, const int32_t* order, const int32_t* pos, hipStream_t stream)
 {
     if (exact)
         return launch_sgd_ring_impl<T, K, true>(1, query_only, max_resident, P, Qt, U, V, R, eb, el, ring_blocks,
                                                 grid_r, grid_c, lds_bytes, lr, lambda, done, first, abort_flag,
-                                                spin_limit, stream);
+                                                spin_limit, order, pos, stream);
     return launch_sgd_ring_impl<T, K, false>(waves, query_only, max_resident, P, Qt, U, V, R, eb, el, ring_blocks,
                                              grid_r, grid_c, lds_bytes, lr, lambda, done, first, abort_flag,
-                                             spin_limit, stream);
+                                             spin_limit, order, pos, stream);
 }
 
 template <typename T, int K>
@@ -1254,12 +1285,14 @@ hipError_t launch_sgd_ring(int dtype, int k, bool exact, int waves, bool query_o
                            void* P, void* Qt, const int32_t* U, const int32_t* V, const float* R,
                            const int64_t* entry_begin, const int32_t* entry_len, const LdsBlock* ring_blocks,
                            int grid_r, int grid_c, size_t lds_bytes, float lr, float lambda, int* done,
-                           int first, int* abort_flag, long long spin_limit, hipStream_t stream)
+                           int first, int* abort_flag, long long spin_limit, const int32_t* order,
+                           const int32_t* pos, hipStream_t stream)
 {
     if (waves < 1 || waves > 16 || lds_bytes > kLdsBudget || grid_r < 1) return hipErrorInvalidValue;
+    if ((order == nullptr) != (pos == nullptr)) return hipErrorInvalidValue;
     MF_DISPATCH(launch_sgd_ring_t, exact, waves, query_only, max_resident, P, Qt, U, V, R, entry_begin,
                 entry_len, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done, first, abort_flag,
-                spin_limit, stream);
+                spin_limit, order, pos, stream);
 }
 
 hipError_t launch_rmse(int dtype, int k, const void* P, const void* Qt, const int32_t* U,

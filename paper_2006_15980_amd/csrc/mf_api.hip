@@ -3,6 +3,7 @@
 // epoch of Algorithm 1's training phase into one kernel launch per stratum.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -46,6 +47,7 @@ struct mf_ctx {
     int32_t ring_resident[2] = {-1, -1};  // workgroups of the ring kernel the device holds at once, per mode
     int32_t ring_epochs = 0;              // epochs run by the ring kernel since mf_load_blocks
     uint32_t* d_perm = nullptr;           // packed -> original position when the partition was made on the device
+    int32_t* d_order = nullptr;           // 2 * grid_c numbers inside the workspace: order, inverse
     int32_t* d_ring_done = nullptr;       // grid_r counters + 1 abort flag, inside the workspace
     int32_t lds_chunk = 0;   // 0 = one chunk per wavefront
     int32_t lds_waves = 16;
@@ -83,7 +85,7 @@ bool valid_k(int32_t k) { return k == 32 || k == 64 || k == 128 || k == 256; }
 
 struct Layout {
     size_t off_u, off_v, off_r, off_perm, off_begin[2], off_len[2], off_lds_begin, off_lds_len, off_lds_blocks,
-        off_dlds_begin, off_dlds_len, off_dlds_blocks, off_ring[2], off_ring_done, total;
+        off_dlds_begin, off_dlds_len, off_dlds_blocks, off_ring[2], off_ring_done, off_order, total;
     int64_t cap[2], lds_cap, lds_blocks_cap;
 };
 
@@ -113,6 +115,7 @@ Layout make_layout(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t l
         l.off_ring[which] = off; off += align_up((size_t)l.lds_blocks_cap * sizeof(mf::LdsBlock));
     }
     l.off_ring_done = off; off += align_up(((size_t)gr + 1) * 4);
+    l.off_order = off; off += align_up((size_t)gc * 2 * 4);   // stratum order of an epoch and its inverse
     l.total = off;
     return l;
 }
@@ -316,6 +319,7 @@ int finish_load(mf_ctx* ctx, const Layout& lay, char* base, const mf::RowStarts&
         }
     }
     ctx->d_ring_done = (int32_t*)(base + lay.off_ring_done);
+    ctx->d_order = (int32_t*)(base + lay.off_order);
     MF_HIP(ctx, hipMemset(ctx->d_ring_done, 0, ((size_t)ctx->part.gr + 1) * 4));
     ctx->ring_epochs = 0;
     ctx->ring_resident[0] = ctx->ring_resident[1] = -1;
@@ -414,12 +418,46 @@ int mf_get_partition(const mf_ctx* ctx, int64_t* perm, int64_t* block_ptr, int32
     return MF_OK;
 }
 
+int mf_stratum_order(uint64_t seed, uint64_t epoch, int32_t grid_c, int32_t* order_out)
+{
+    if (grid_c < 1 || !order_out) return MF_EINVAL;
+    // SplitMix64 output function (published algorithm) as a counter-based source of sort keys
+    auto mix = [](uint64_t z) {
+        z += 0x9E3779B97F4A7C15ULL;
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+        return z ^ (z >> 31);
+    };
+    const uint64_t base = mix(seed ^ (epoch * 0xD1B54A32D192ED03ULL));
+    std::vector<std::pair<uint64_t, int32_t>> keyed((size_t)grid_c);
+    for (int32_t s = 0; s < grid_c; ++s) keyed[(size_t)s] = {mix(base + (uint64_t)s), s};
+    std::sort(keyed.begin(), keyed.end());
+    for (int32_t t = 0; t < grid_c; ++t) order_out[t] = keyed[(size_t)t].second;
+    return MF_OK;
+}
+
 int mf_sgd_epoch(mf_ctx* ctx, float lr, float lambda, int32_t mode)
+{
+    return mf_sgd_epoch_ordered(ctx, lr, lambda, mode, nullptr);
+}
+
+int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, const int32_t* stratum_order)
 {
     if (!ctx) return MF_EINVAL;
     if (!ctx->loaded) return fail(ctx, MF_ESTATE, "mf_sgd_epoch before mf_load_blocks");
     if (mode != MF_MODE_DET && mode != MF_MODE_HOGWILD) return fail(ctx, MF_EINVAL, "unknown mode");
     if (!(lr == lr) || !(lambda == lambda)) return fail(ctx, MF_EINVAL, "lr or lambda is NaN");
+    const int32_t gc = ctx->part.gc;
+    std::vector<int32_t> inverse;
+    if (stratum_order) {
+        inverse.assign((size_t)gc, -1);
+        for (int32_t t = 0; t < gc; ++t) {
+            const int32_t st = stratum_order[t];
+            if (st < 0 || st >= gc || inverse[(size_t)st] >= 0)
+                return fail(ctx, MF_EINVAL, "stratum_order is not a permutation of 0 .. grid_c-1");
+            inverse[(size_t)st] = t;
+        }
+    }
     MF_HIP(ctx, hipSetDevice(ctx->device));
     const mf::Schedule& s = ctx->sched[mode];
     // both modes take the kernel that keeps the block's strip of Qt in LDS whenever the widest
@@ -443,7 +481,8 @@ int mf_sgd_epoch(mf_ctx* ctx, float lr, float lambda, int32_t mode)
             int resident = 0;
             MF_HIP(ctx, mf::launch_sgd_ring(ctx->dtype, ctx->k, !hog, ctx->lds_waves, true, &resident, nullptr, nullptr,
                                             nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, ctx->part.gr,
-                                            ctx->part.gc, lds_bytes, 0.f, 0.f, nullptr, 0, nullptr, 0, ctx->stream));
+                                            ctx->part.gc, lds_bytes, 0.f, 0.f, nullptr, 0, nullptr, 0, nullptr, nullptr,
+                                            ctx->stream));
             ctx->ring_resident[m_idx] = resident;
         }
         if (ctx->part.gr <= ctx->ring_resident[m_idx]) {
@@ -451,6 +490,13 @@ int mf_sgd_epoch(mf_ctx* ctx, float lr, float lambda, int32_t mode)
                 // the strata counters are about to run out of range: start them again from zero
                 MF_HIP(ctx, hipMemsetAsync(ctx->d_ring_done, 0, (size_t)ctx->part.gr * 4, ctx->stream));
                 ctx->ring_epochs = 0;
+            }
+            if (stratum_order) {
+                // the order and its inverse go to the workspace; an epoch that may still be reading
+                // the previous order has to finish first
+                MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
+                MF_HIP(ctx, hipMemcpy(ctx->d_order, stratum_order, (size_t)gc * 4, hipMemcpyHostToDevice));
+                MF_HIP(ctx, hipMemcpy(ctx->d_order + gc, inverse.data(), (size_t)gc * 4, hipMemcpyHostToDevice));
             }
             hipEvent_t ev0 = nullptr, ev1 = nullptr;
             if (ctx->profile) {
@@ -468,13 +514,15 @@ int mf_sgd_epoch(mf_ctx* ctx, float lr, float lambda, int32_t mode)
                                             ctx->dU, ctx->dV, ctx->dR, lsched.d_begin, lsched.d_len, lsched.d_ring,
                                             ctx->part.gr, ctx->part.gc, lds_bytes, lr, lambda, ctx->d_ring_done,
                                             ctx->ring_epochs * ctx->part.gc, ctx->d_ring_done + ctx->part.gr,
-                                            (long long)ctx->spin_limit, ctx->stream));
+                                            (long long)ctx->spin_limit, stratum_order ? ctx->d_order : nullptr,
+                                            stratum_order ? ctx->d_order + gc : nullptr, ctx->stream));
             if (ctx->profile) MF_HIP(ctx, hipEventRecord(ev1, ctx->stream));
             ctx->ring_epochs += 1;
             return MF_OK;
         }
     }
-    for (int32_t st = 0; st < ctx->part.gc; ++st) {
+    for (int32_t step = 0; step < gc; ++step) {
+        const int32_t st = stratum_order ? stratum_order[step] : step;
         int64_t first, count;
         if (use_lds) {
             first = lsched.stratum_block[st];

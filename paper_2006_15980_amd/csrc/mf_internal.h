@@ -116,13 +116,15 @@ hipError_t launch_sgd_lds(int dtype, int k, bool exact, int waves, void* P, void
                           const int32_t* entry_len, const LdsBlock* blocks, int64_t n_blocks,
                           size_t lds_bytes, float lr, float lambda, hipStream_t stream);
 // One launch per epoch (ring of workgroups, see kernels.hip).  ring_blocks: grid_c * grid_r
-// descriptors indexed [stratum][block row], empty blocks included.  query_only: do not launch,
+// descriptors indexed [stratum][block row], empty blocks included.  order / pos (device, grid_c
+// entries each, both or neither): the stratum of every step and its inverse.  query_only: do not launch,
 // return in *max_resident how many workgroups of this shape the device can hold at once.
 hipError_t launch_sgd_ring(int dtype, int k, bool exact, int waves, bool query_only, int* max_resident,
                            void* P, void* Qt, const int32_t* U, const int32_t* V, const float* R,
                            const int64_t* entry_begin, const int32_t* entry_len, const LdsBlock* ring_blocks,
                            int grid_r, int grid_c, size_t lds_bytes, float lr, float lambda, int* done,
-                           int first, int* abort_flag, long long spin_limit, hipStream_t stream);
+                           int first, int* abort_flag, long long spin_limit, const int32_t* order,
+                           const int32_t* pos, hipStream_t stream);
 size_t lds_strip_bytes(int k, int32_t max_cols);   // dynamic LDS the kernel needs for a grid
 constexpr size_t kLdsBudget = 160 * 1024 - 1024;   // LDS of one gfx950 compute unit, minus static use
 hipError_t launch_init(int dtype, void* X, int64_t count, uint64_t seed, uint64_t stream_id,

@@ -246,6 +246,82 @@ def test_ring_kernel_gives_up_cleanly_when_its_wait_limit_is_tiny(mfmod):
     model.close()
 
 
+# ------------------------------------------------------------------------------- randomised stratum order
+@pytest.mark.parametrize("grid", [(5, 7), (16, 16), (8, 64), (33, 40)])
+def test_shuffled_strata_deterministic_mode_matches_oracle_on_every_kernel(mfmod, grid):
+    """Two epochs with two different stratum permutations: every launch scheme (ring kernel with
+    its generalised waits, one launch per stratum, global kernel) gives the same bits, and they
+    agree with the oracle run in the same orders."""
+    ds = dataset("tiny")
+    gr, gc = grid
+    cfg = ds.cfg
+    orders = [mfmod.binding.mf_stratum_order(77, e, gc) for e in range(2)]
+    assert all(np.array_equal(o, oracle.stratum_order(77, e, gc)) for e, o in enumerate(orders))
+    outs = []
+    for kernel, ring in (("lds", 1), ("lds", 0), ("global", 0)):
+        opts = dict(_det_options(mfmod, kernel))
+        opts[mfmod.MF_OPT_RING] = ring
+        model = _make(mfmod, ds, 32, "f32", gr, gc, 1, options=opts)
+        for o in orders:
+            model.sgd_epoch(cfg.lr, cfg.lam, mfmod.MF_MODE_DET, stratum_order=o)
+        outs.append(model.get_factors())
+        model.close()
+    for other in outs[1:]:
+        assert np.array_equal(outs[0][0], other[0]) and np.array_equal(outs[0][1], other[1])
+    perm, bp, _, _ = oracle.partition(ds.rows, ds.cols, cfg.m, cfg.n, gr, gc, 1)
+    Po, Qo = oracle_init(cfg.m, cfg.n, 32, 1, 0.1)
+    for o in orders:
+        oracle.sgd_epoch_ordered(Po, Qo, ds.rows, ds.cols, ds.vals, perm, bp, gr, gc, cfg.lr, cfg.lam, o)
+    assert np.abs(outs[0][0] - Po).max() <= 1e-4 and np.abs(outs[0][1] - Qo).max() <= 1e-4
+    # and the order does change the result (natural order differs by far more than the tolerance)
+    Pn, Qn = oracle_init(cfg.m, cfg.n, 32, 1, 0.1)
+    for _ in orders:
+        oracle.sgd_epoch_omp(Pn, Qn, ds.rows, ds.cols, ds.vals, perm, bp, gr, gc, cfg.lr, cfg.lam)
+    assert np.abs(Qn - Qo).max() > 1e-3
+
+
+@pytest.mark.parametrize("ring", [1, 0])
+def test_shuffled_strata_hogwild_final_rmse(mfmod, ring):
+    ds = dataset("tiny")
+    cfg = ds.cfg
+    gr = gc = 32
+    opts = {mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS, mfmod.MF_OPT_RING: ring}
+    model = _make(mfmod, ds, cfg.k, "f32", gr, gc, 1, options=opts)
+    perm, bp, _, _ = oracle.partition(ds.rows, ds.cols, cfg.m, cfg.n, gr, gc, 1)
+    Po, Qo = oracle_init(cfg.m, cfg.n, cfg.k, 1, 0.1)
+    for e in range(cfg.epochs):
+        o = oracle.stratum_order(3, e, gc)
+        model.sgd_epoch(cfg.lr, cfg.lam, mfmod.MF_MODE_HOGWILD, stratum_order=o)
+        oracle.sgd_epoch_ordered(Po, Qo, ds.rows, ds.cols, ds.vals, perm, bp, gr, gc, cfg.lr, cfg.lam, o)
+    tr, tc, tv = model.to_device(ds.test_rows, ds.test_cols, ds.test_vals)
+    got = model.rmse(tr, tc, tv)
+    want = oracle.rmse(Po, Qo, ds.test_rows, ds.test_cols, ds.test_vals)
+    model.close()
+    assert abs(got - want) <= 5e-3 * want, (got, want)
+
+
+def test_stratum_order_must_be_a_permutation(mfmod):
+    ds = dataset("tiny")
+    model = _make(mfmod, ds, 32, "f32", 4, 6, 1)
+    for bad in ([0, 1, 2, 3, 4, 4], [0, 1, 2, 3, 4, 6], [-1, 1, 2, 3, 4, 5]):
+        with pytest.raises(mfmod.MFError) as e:
+            model.sgd_epoch(0.01, 0.05, mfmod.MF_MODE_DET, stratum_order=np.array(bad, np.int32))
+        assert e.value.code == mfmod.binding.MF_EINVAL
+    model.close()
+
+
+def test_ring_kernel_with_an_order_gives_up_cleanly_when_its_wait_limit_is_tiny(mfmod):
+    ds = dataset("tiny")
+    opts = {mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS, mfmod.MF_OPT_RING: 1,
+            mfmod.MF_OPT_RING_SPIN_LIMIT: 1}
+    model = _make(mfmod, ds, 128, "f32", 64, 64, 1, options=opts)
+    model.sgd_epoch(ds.cfg.lr, ds.cfg.lam, mfmod.MF_MODE_HOGWILD, stratum_order=oracle.stratum_order(1, 0, 64))
+    with pytest.raises(mfmod.MFError) as e:
+        model.sync()
+    assert e.value.code == mfmod.binding.MF_EDEVICE
+    model.close()
+
+
 def test_det_edge_cases(mfmod):
     rng = np.random.default_rng(3)
     # duplicates of one (u, v), a single long row, a single long column, and empty strata

@@ -180,6 +180,13 @@ def test_suggested_grids_fit_the_lds_and_keep_blocks_reasonable():
         B.mf_suggest_grid(10, 10, 5, 48, B.MF_MODE_DET)
 
 
+def test_stratum_order_equals_the_oracles():
+    for seed, epoch, gc in [(0, 0, 1), (1, 0, 2), (5, 3, 7), (5, 4, 64), (2**63 + 5, 2**40, 333), (9, 1, 4096)]:
+        assert np.array_equal(B.mf_stratum_order(seed, epoch, gc), oracle.stratum_order(seed, epoch, gc))
+    with pytest.raises(B.MFError):
+        B.mf_stratum_order(1, 1, 0)
+
+
 def test_create_without_a_device_is_an_error_not_a_crash():
     import torch
     if torch.cuda.is_available():
