@@ -644,3 +644,95 @@ FULL_SIZE = {
 def test_other_configs_full_size(mfmod, name):
     det_grid, hog_grid, epochs = FULL_SIZE[name]
     _config_case(mfmod, name, 1.0, det_grid, hog_grid, epochs)
+
+
+# ------------------------------------------------------------------------------- configs 4 and 5 at full size
+# The CPU oracle needs tens of minutes on these, so its results are stored by
+# tests/golden/make_full_size_expected.py (which calls only the oracle and the input generators):
+# the held-out RMSE after every epoch and, after the first epoch, whole rows of P and Qt at
+# sampled indices.
+STORED = {
+    # name: Hogwild options at that size
+    "xlarge": {"lds_waves": 8},
+    "stress": {"lds_waves": 16},
+}
+
+
+def _read_stored(name):
+    path = os.path.join(os.path.dirname(__file__), "golden", f"full_{name}.txt")
+    if not os.path.exists(path):
+        return None
+    out = {"P": {}, "Q": {}}
+    with open(path) as fh:
+        for line in fh:
+            if line.startswith("#") or not line.strip():
+                continue
+            key, *vals = line.split()
+            if key[0] in "PQ" and key[1:].isdigit():
+                out[key[0]][int(key[1:])] = np.array([float.fromhex(v) for v in vals])
+            else:
+                out[key] = vals
+    return out
+
+
+@pytest.mark.slow
+@pytest.mark.skipif(not FULL, reason="full-size run: set MF_FULL=1 (several minutes of input generation)")
+@pytest.mark.parametrize("name", sorted(STORED))
+def test_full_size_against_the_stored_oracle_results(mfmod, name):
+    g = _read_stored(name)
+    if g is None:
+        pytest.skip("no stored oracle results for this configuration")
+    ds = dataset(name)
+    cfg = ds.cfg
+    gr, gc = int(g["grid"][0]), int(g["grid"][1])
+    split, scale = int(g["split"][0]), float(g["init_scale"][0])
+    want_rmse = [float(x) for x in g["rmse"]]
+    assert int(g["nnz_train"][0]) == ds.rows.size
+    dev = torch.device("cuda:0")
+    coo = [torch.from_numpy(x).to(dev) for x in (ds.rows, ds.cols, ds.vals)]
+    print(f"{name}: data on the device", flush=True)
+
+    # deterministic mode: sampled rows after one epoch, RMSE after every stored epoch
+    model = mfmod.MatrixFactorization(cfg.m, cfg.n, cfg.k, cfg.storage, seed=1, scale=scale)
+    model.load_blocks_device(coo[0], coo[1], coo[2], gr, gc, split)
+    tr, tc, tv = model.to_device(ds.test_rows, ds.test_cols, ds.test_vals)
+    model.sgd_epoch(cfg.lr, cfg.lam, mfmod.MF_MODE_DET)
+    for tag, X in (("P", model.P), ("Q", model.Qt)):
+        ids = sorted(g[tag])
+        got = X[torch.tensor(ids, device=dev)].float().cpu().numpy().astype(np.float64)
+        want = np.stack([g[tag][i] for i in ids])
+        if cfg.storage == "f16":
+            differing = int((got != want).sum())
+            print(f"{name} DET epoch 1, {tag}: {differing} of {want.size} sampled elements differ", flush=True)
+            assert differing <= max(1, int(1e-5 * want.size)) or np.abs(got - want).max() <= 2e-3
+        else:
+            err = np.abs(got - want) / np.maximum(1.0, np.abs(want))
+            print(f"{name} DET epoch 1, {tag}: max scaled error {err.max():.3g} on {len(ids)} sampled rows", flush=True)
+            assert err.max() <= 1e-4
+    got = model.rmse(tr, tc, tv)
+    print(f"{name} DET epoch 1: rmse gpu {got:.6f} oracle {want_rmse[0]:.6f}", flush=True)
+    assert abs(got - want_rmse[0]) <= 1e-3
+    for e in range(1, len(want_rmse)):
+        model.sgd_epoch(cfg.lr, cfg.lam, mfmod.MF_MODE_DET)
+    got = model.rmse(tr, tc, tv)
+    print(f"{name} DET {len(want_rmse)} epochs: rmse gpu {got:.6f} oracle {want_rmse[-1]:.6f}", flush=True)
+    assert abs(got - want_rmse[-1]) <= 1e-3
+    model.close()
+
+    # Hogwild mode on the LDS kernel: final RMSE
+    opts = {mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS, mfmod.MF_OPT_LDS_WAVES: STORED[name]["lds_waves"]}
+    model = mfmod.MatrixFactorization(cfg.m, cfg.n, cfg.k, cfg.storage, seed=1, scale=scale, options=opts)
+    model.load_blocks_device(coo[0], coo[1], coo[2], gr, gc, split)
+    tr, tc, tv = model.to_device(ds.test_rows, ds.test_cols, ds.test_vals)
+    import time
+    model.sync()
+    t0 = time.perf_counter()
+    for e in range(len(want_rmse)):
+        model.sgd_epoch(cfg.lr, cfg.lam, mfmod.MF_MODE_HOGWILD)
+    model.sync()
+    dt = time.perf_counter() - t0
+    got = model.rmse(tr, tc, tv)
+    print(f"{name} HOGWILD {len(want_rmse)} epochs: rmse gpu {got:.6f} oracle {want_rmse[-1]:.6f}; "
+          f"{ds.rows.size * len(want_rmse) / dt / 1e9:.3f} G updates/s", flush=True)
+    assert abs(got - want_rmse[-1]) <= 5e-3 * want_rmse[-1]
+    model.close()
