@@ -593,8 +593,11 @@ OTHER = {
 }
 
 
-def _config_case(mfmod, name, scale, det_grid, hog_grid, epochs, hog_split=2):
+def _config_case(mfmod, name, scale, det_grid, hog_grid, epochs, hog_split=2, storage=None):
     ds = dataset(name, scale)
+    if storage is not None:
+        import dataclasses
+        ds.cfg = dataclasses.replace(ds.cfg, storage=storage)
     cfg = ds.cfg
     print("%s: m=%d n=%d nnz=%d %s, max row/col degree %d/%d" % (cfg.name, cfg.m, cfg.n, ds.rows.size, cfg.storage,
                                                                   ds.max_row_degree, ds.max_col_degree), flush=True)
@@ -630,6 +633,13 @@ def _config_case(mfmod, name, scale, det_grid, hog_grid, epochs, hog_split=2):
 def test_other_configs_scaled(mfmod, name):
     scale, det_grid, hog_grid, epochs = OTHER[name]
     _config_case(mfmod, name, scale, det_grid, hog_grid, epochs)
+
+
+@pytest.mark.parametrize("name", ["large", "xlarge"])
+def test_binary16_storage_on_the_fp32_configs(mfmod, name):
+    """Half-precision storage is an option for every configuration, not only the one that names it."""
+    scale, det_grid, hog_grid, epochs = OTHER[name]
+    _config_case(mfmod, name, scale, det_grid, hog_grid, epochs, storage="f16")
 
 
 FULL_SIZE = {
