@@ -22,8 +22,8 @@ HBM_PEAK_GBS = 8000.0
 # device copy of known size).  Counters cannot be read from inside this process, so the figure is
 # reported only for the exact configuration that was profiled, otherwise null.
 PROFILED_TRAFFIC = {
-    # (workload, scale, mode, grid, kernel, ring): bytes per launch
-    ("medium", 1.0, "hogwild", "224x224", "lds", 1): 5290.3e6,   # profiles/sgd_ring_lds_f32_k128_medium.md
+    # (workload, scale, mode, grid, kernel, ring, lds_waves): bytes per launch
+    ("medium", 1.0, "hogwild", "256x256", "lds", 1, 12): 5727.9e6,   # profiles/sgd_ring_lds_f32_k128_medium.md
 }
 
 
@@ -87,10 +87,10 @@ def main():
     ap.add_argument("--workload", default="medium")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (testing only)")
     ap.add_argument("--mode", default="hogwild", choices=["hogwild", "det"])
-    ap.add_argument("--grid", default="224x224")
+    ap.add_argument("--grid", default="256x256")
     ap.add_argument("--hogwild-kernel", default="auto", choices=["auto", "global_atomics", "lds"])
     ap.add_argument("--lds-chunk", type=int, default=0)
-    ap.add_argument("--lds-waves", type=int, default=16)
+    ap.add_argument("--lds-waves", type=int, default=12)
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--affinity", type=int, default=1)
     ap.add_argument("--split", type=int, default=1, help="0 equal width, 1 ratings balanced, 2 ratings and width balanced")
@@ -193,8 +193,8 @@ def main():
         bytes_per_launch = bytes_per_update * nnz * args.steps / launches
         achieved = bytes_per_launch / avg_s / 1e9
         kern = "lds" if (args.mode == "hogwild" and args.hogwild_kernel != "global_atomics") else "chunks"
-        traffic = PROFILED_TRAFFIC.get((args.workload, args.scale, args.mode, args.grid, kern, args.ring))
-        if args.lds_waves != 16 or args.lds_chunk != 0 or args.split != 1:
+        traffic = PROFILED_TRAFFIC.get((args.workload, args.scale, args.mode, args.grid, kern, args.ring, args.lds_waves))
+        if args.lds_chunk != 0 or args.split != 1:
             traffic = None
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": ("sgd_ring_lds<float,128>" if args.ring else "sgd_block_lds<float,128>") if (args.mode == "hogwild" and args.hogwild_kernel != "global_atomics") else "sgd_chunks<float,128>",

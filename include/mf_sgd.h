@@ -63,7 +63,9 @@ enum {
                                   /* which the workgroups hand the column strips round (see           */
                                   /* mf_sgd_epoch) when all grid_r workgroups fit the device at once; */
                                   /* 0: always one launch per stratum                                 */
-    MF_OPT_RING_SPIN_LIMIT = 9    /* polls after which a waiting workgroup gives up (default 2^22)    */
+    MF_OPT_RING_SPIN_LIMIT = 9,   /* polls after which a waiting workgroup gives up (default 2^22)    */
+    MF_OPT_LDS_PREFETCH = 10      /* MF_MODE_HOGWILD, LDS kernels: rows of P requested 4 or 8 ratings */
+                                  /* ahead; 0 (default): 4 if P takes at most 64 MiB, else 8          */
 };
 enum { MF_KERNEL_AUTO = 0, MF_KERNEL_GLOBAL = 1, MF_KERNEL_LDS = 2 };
 enum { MF_HOGWILD_AUTO = MF_KERNEL_AUTO, MF_HOGWILD_GLOBAL_ATOMICS = MF_KERNEL_GLOBAL, MF_HOGWILD_LDS = MF_KERNEL_LDS };

@@ -682,7 +682,8 @@ __device__ __forceinline__ void lds_shared_row_chunk(T* __restrict__ P, int* str
     }
 }
 
-constexpr int kLdsPrefetchDepth = 8;
+constexpr int kLdsPrefetchDepth = 8;   // rows of P requested ahead (deterministic mode; Hogwild: 8 or kShortPrefetchDepth)
+constexpr int kShortPrefetchDepth = 4;
 
 typedef unsigned int uint4_t __attribute__((ext_vector_type(4)));
 constexpr int kRawBufferFlags = 0x00020000;   // word 3 of a raw (untyped, unswizzled) buffer descriptor on gfx9
@@ -696,7 +697,7 @@ constexpr int kCachePolicySc1 = 16;           // auxiliary operand of the buffer
 // and before the strip is read: the ring kernel waits there for the strip's previous user
 // (returning false means "give up": the workgroup leaves); everything requested before it is
 // independent of the strip.
-template <typename T, int K, bool EXACT, bool COHERENT, class BeforeStrip>
+template <typename T, int K, bool EXACT, bool COHERENT, int DEPTH, class BeforeStrip>
 __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T* __restrict__ Qt,
                                                const int32_t* __restrict__ U, const int32_t* __restrict__ V,
                                                const float* __restrict__ R,
@@ -728,15 +729,15 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
         }
     };
     constexpr int VEC = RowShape<T, K>::VEC;
-    RowRing<VEC, kLdsPrefetchDepth> first_rows;
+    RowRing<VEC, DEPTH> first_rows;
 #pragma unroll
-    for (int d = 0; d < kLdsPrefetchDepth; ++d)
+    for (int d = 0; d < DEPTH; ++d)
 #pragma unroll
         for (int j = 0; j < VEC; ++j) first_rows.r[d].x[j] = 0.f;
     if (wave < blk.n_entries) {
         fetch_entry(wave);
         if (EXACT || raw_len > 0)
-            first_rows = request_first_rows<T, K, kLdsPrefetchDepth>(P, mu, min(kWave, raw_len & ~kSharedRowFlag), lane,
+            first_rows = request_first_rows<T, K, DEPTH>(P, mu, min(kWave, raw_len & ~kSharedRowFlag), lane,
                                                                      active);
     }
     if (!before_strip()) return false;
@@ -839,18 +840,18 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
         if (e != wave) {
             fetch_entry(e);
             if (EXACT || raw_len > 0)
-                first_rows = request_first_rows<T, K, kLdsPrefetchDepth>(P, mu, min(kWave, raw_len & ~kSharedRowFlag),
+                first_rows = request_first_rows<T, K, DEPTH>(P, mu, min(kWave, raw_len & ~kSharedRowFlag),
                                                                          lane, active);
         }
         const int32_t len = raw_len & ~kSharedRowFlag;
         if constexpr (EXACT) {
-            lds_owned_chunk<T, K, kLdsPrefetchDepth, true>(P, strip, blk.col0, U, V, R, begin, len, mu, mv, mr,
+            lds_owned_chunk<T, K, DEPTH, true>(P, strip, blk.col0, U, V, R, begin, len, mu, mv, mr,
                                                            first_rows, lr, shrink, lane, active);
         } else {
             if (raw_len < 0)
                 lds_shared_row_chunk<T, K>(P, strip, blk.col0, U, V, R, begin, len, lr, shrink, lane, active);
             else
-                lds_hog_chunk<T, K, kLdsPrefetchDepth>(P, strip, blk.col0, U, V, R, begin, len, mu, mv, mr,
+                lds_hog_chunk<T, K, DEPTH>(P, strip, blk.col0, U, V, R, begin, len, mu, mv, mr,
                                                        first_rows, lr, shrink, lane, active);
         }
     }
@@ -915,7 +916,7 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
 }
 
 // One launch per stratum: workgroup i works on the i-th non-empty block of the stratum.
-template <typename T, int K, bool EXACT>
+template <typename T, int K, bool EXACT, int DEPTH>
 __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_block_lds(
     T* __restrict__ P, T* __restrict__ Qt, const int32_t* __restrict__ U,
     const int32_t* __restrict__ V, const float* __restrict__ R,
@@ -923,7 +924,7 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_block_lds(
     const LdsBlock* __restrict__ blocks, float lr, float lambda)
 {
     extern __shared__ int strip[];            // ncols * K values (fixed point, or fp32 bits if EXACT)
-    lds_block_body<T, K, EXACT, false>(strip, P, Qt, U, V, R, entry_begin, entry_len, blocks[blockIdx.x], lr,
+    lds_block_body<T, K, EXACT, false, DEPTH>(strip, P, Qt, U, V, R, entry_begin, entry_len, blocks[blockIdx.x], lr,
                                        lambda, [] { return true; });
 }
 
@@ -944,7 +945,7 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_block_lds(
 // All grid_r workgroups must be resident at once (checked by the host before launching).
 // Every wait is bounded: after spin_limit polls a workgroup raises *abort_flag and leaves, and
 // every waiting workgroup leaves as soon as it sees the flag, so the grid always drains.
-template <typename T, int K, bool EXACT>
+template <typename T, int K, bool EXACT, int DEPTH>
 __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_ring_lds(
     T* __restrict__ P, T* __restrict__ Qt, const int32_t* __restrict__ U,
     const int32_t* __restrict__ V, const float* __restrict__ R,
@@ -1012,7 +1013,7 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_ring_lds(
         const LdsBlock blk = ring_blocks[(int64_t)s * grid_r + a];
         bool ok;
         if (blk.n_entries > 0)
-            ok = lds_block_body<T, K, EXACT, true>(strip, P, Qt, U, V, R, entry_begin, entry_len, blk, lr, lambda,
+            ok = lds_block_body<T, K, EXACT, true, DEPTH>(strip, P, Qt, U, V, R, entry_begin, entry_len, blk, lr, lambda,
                                                    wait_for_strip);
         else
             ok = wait_for_strip();   // an empty block still waits: it passes the guarantee on
@@ -1136,7 +1137,7 @@ hipError_t launch_sgd_t(bool hogwild, void* P, void* Qt, const int32_t* U, const
     return hipGetLastError();
 }
 
-template <typename T, int K, bool EXACT>
+template <typename T, int K, bool EXACT, int DEPTH>
 hipError_t launch_sgd_lds_impl(int waves, void* P, void* Qt, const int32_t* U, const int32_t* V,
                             const float* R, const int64_t* eb, const int32_t* el,
                             const LdsBlock* blocks, int64_t n_blocks, size_t lds_bytes, float lr,
@@ -1148,17 +1149,17 @@ hipError_t launch_sgd_lds_impl(int waves, void* P, void* Qt, const int32_t* U, c
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev >= 0 && dev < 64 && !raised[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sgd_block_lds<T, K, EXACT>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sgd_block_lds<T, K, EXACT, DEPTH>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
         if (e != hipSuccess) return e;
         raised[dev] = true;
     }
-    hipLaunchKernelGGL((sgd_block_lds<T, K, EXACT>), dim3((unsigned)n_blocks), dim3(waves * kWave), lds_bytes,
+    hipLaunchKernelGGL((sgd_block_lds<T, K, EXACT, DEPTH>), dim3((unsigned)n_blocks), dim3(waves * kWave), lds_bytes,
                        stream, (T*)P, (T*)Qt, U, V, R, eb, el, blocks, lr, lambda);
     return hipGetLastError();
 }
 
-template <typename T, int K, bool EXACT>
+template <typename T, int K, bool EXACT, int DEPTH>
 hipError_t launch_sgd_ring_impl(int waves, bool query_only, int* max_resident, void* P, void* Qt,
                                 const int32_t* U, const int32_t* V, const float* R, const int64_t* eb,
                                 const int32_t* el, const LdsBlock* ring_blocks, int grid_r, int grid_c,
@@ -1171,14 +1172,14 @@ hipError_t launch_sgd_ring_impl(int waves, bool query_only, int* max_resident, v
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev >= 0 && dev < 64 && !raised[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sgd_ring_lds<T, K, EXACT>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sgd_ring_lds<T, K, EXACT, DEPTH>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
         if (e != hipSuccess) return e;
         raised[dev] = true;
     }
     if (query_only) {
         int per_cu = 0, cus = 0;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, sgd_ring_lds<T, K, EXACT>, waves * kWave,
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, sgd_ring_lds<T, K, EXACT, DEPTH>, waves * kWave,
                                                          lds_bytes);
         if (e != hipSuccess) return e;
         e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
@@ -1186,39 +1187,48 @@ hipError_t launch_sgd_ring_impl(int waves, bool query_only, int* max_resident, v
         *max_resident = per_cu * cus;
         return hipSuccess;
     }
-    hipLaunchKernelGGL((sgd_ring_lds<T, K, EXACT>), dim3((unsigned)grid_r), dim3(waves * kWave), lds_bytes,
+    hipLaunchKernelGGL((sgd_ring_lds<T, K, EXACT, DEPTH>), dim3((unsigned)grid_r), dim3(waves * kWave), lds_bytes,
                        stream, (T*)P, (T*)Qt, U, V, R, eb, el, ring_blocks, grid_r, grid_c, lr, lambda, done,
                        first, abort_flag, spin_limit, order, pos);
     return hipGetLastError();
 }
 
 template <typename T, int K>
-hipError_t launch_sgd_ring_t(bool exact, int waves, bool query_only, int* max_resident, void* P, void* Qt,
+hipError_t launch_sgd_ring_t(bool exact, bool short_prefetch, int waves, bool query_only, int* max_resident, void* P, void* Qt,
                              const int32_t* U, const int32_t* V, const float* R, const int64_t* eb,
                              const int32_t* el, const LdsBlock* ring_blocks, int grid_r, int grid_c,
                              size_t lds_bytes, float lr, float lambda, int* done, int first, int* abort_flag,
                              long long spin_limit, const int32_t* order, const int32_t* pos, hipStream_t stream)
 {
     if (exact)
-        return launch_sgd_ring_impl<T, K, true>(1, query_only, max_resident, P, Qt, U, V, R, eb, el, ring_blocks,
-                                                grid_r, grid_c, lds_bytes, lr, lambda, done, first, abort_flag,
-                                                spin_limit, order, pos, stream);
-    return launch_sgd_ring_impl<T, K, false>(waves, query_only, max_resident, P, Qt, U, V, R, eb, el, ring_blocks,
-                                             grid_r, grid_c, lds_bytes, lr, lambda, done, first, abort_flag,
-                                             spin_limit, order, pos, stream);
+        return launch_sgd_ring_impl<T, K, true, kLdsPrefetchDepth>(1, query_only, max_resident, P, Qt, U, V, R, eb, el,
+                                                                   ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda,
+                                                                   done, first, abort_flag, spin_limit, order, pos,
+                                                                   stream);
+    if (short_prefetch)
+        return launch_sgd_ring_impl<T, K, false, kShortPrefetchDepth>(waves, query_only, max_resident, P, Qt, U, V, R, eb,
+                                                                      el, ring_blocks, grid_r, grid_c, lds_bytes, lr,
+                                                                      lambda, done, first, abort_flag, spin_limit, order,
+                                                                      pos, stream);
+    return launch_sgd_ring_impl<T, K, false, kLdsPrefetchDepth>(waves, query_only, max_resident, P, Qt, U, V, R, eb, el,
+                                                                ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done,
+                                                                first, abort_flag, spin_limit, order, pos, stream);
 }
 
 template <typename T, int K>
-hipError_t launch_sgd_lds_t(bool exact, int waves, void* P, void* Qt, const int32_t* U, const int32_t* V,
+hipError_t launch_sgd_lds_t(bool exact, bool short_prefetch, int waves, void* P, void* Qt, const int32_t* U, const int32_t* V,
                             const float* R, const int64_t* eb, const int32_t* el,
                             const LdsBlock* blocks, int64_t n_blocks, size_t lds_bytes, float lr,
                             float lambda, hipStream_t stream)
 {
     if (exact)
-        return launch_sgd_lds_impl<T, K, true>(1, P, Qt, U, V, R, eb, el, blocks, n_blocks, lds_bytes, lr, lambda,
-                                               stream);
-    return launch_sgd_lds_impl<T, K, false>(waves, P, Qt, U, V, R, eb, el, blocks, n_blocks, lds_bytes, lr,
-                                            lambda, stream);
+        return launch_sgd_lds_impl<T, K, true, kLdsPrefetchDepth>(1, P, Qt, U, V, R, eb, el, blocks, n_blocks, lds_bytes,
+                                                                  lr, lambda, stream);
+    if (short_prefetch)
+        return launch_sgd_lds_impl<T, K, false, kShortPrefetchDepth>(waves, P, Qt, U, V, R, eb, el, blocks, n_blocks,
+                                                                     lds_bytes, lr, lambda, stream);
+    return launch_sgd_lds_impl<T, K, false, kLdsPrefetchDepth>(waves, P, Qt, U, V, R, eb, el, blocks, n_blocks, lds_bytes,
+                                                               lr, lambda, stream);
 }
 
 template <typename T, int K>
@@ -1270,18 +1280,18 @@ hipError_t launch_sgd(int dtype, int k, bool hogwild, void* P, void* Qt, const i
 
 size_t lds_strip_bytes(int k, int32_t max_cols) { return (size_t)max_cols * k * sizeof(float); }
 
-hipError_t launch_sgd_lds(int dtype, int k, bool exact, int waves, void* P, void* Qt, const int32_t* U,
+hipError_t launch_sgd_lds(int dtype, int k, bool exact, bool short_prefetch, int waves, void* P, void* Qt, const int32_t* U,
                           const int32_t* V, const float* R, const int64_t* entry_begin,
                           const int32_t* entry_len, const LdsBlock* blocks, int64_t n_blocks,
                           size_t lds_bytes, float lr, float lambda, hipStream_t stream)
 {
     if (n_blocks <= 0) return hipSuccess;
     if (waves < 1 || waves > 16 || lds_bytes > kLdsBudget) return hipErrorInvalidValue;
-    MF_DISPATCH(launch_sgd_lds_t, exact, waves, P, Qt, U, V, R, entry_begin, entry_len, blocks, n_blocks,
+    MF_DISPATCH(launch_sgd_lds_t, exact, short_prefetch, waves, P, Qt, U, V, R, entry_begin, entry_len, blocks, n_blocks,
                 lds_bytes, lr, lambda, stream);
 }
 
-hipError_t launch_sgd_ring(int dtype, int k, bool exact, int waves, bool query_only, int* max_resident,
+hipError_t launch_sgd_ring(int dtype, int k, bool exact, bool short_prefetch, int waves, bool query_only, int* max_resident,
                            void* P, void* Qt, const int32_t* U, const int32_t* V, const float* R,
                            const int64_t* entry_begin, const int32_t* entry_len, const LdsBlock* ring_blocks,
                            int grid_r, int grid_c, size_t lds_bytes, float lr, float lambda, int* done,
@@ -1290,7 +1300,7 @@ hipError_t launch_sgd_ring(int dtype, int k, bool exact, int waves, bool query_o
 {
     if (waves < 1 || waves > 16 || lds_bytes > kLdsBudget || grid_r < 1) return hipErrorInvalidValue;
     if ((order == nullptr) != (pos == nullptr)) return hipErrorInvalidValue;
-    MF_DISPATCH(launch_sgd_ring_t, exact, waves, query_only, max_resident, P, Qt, U, V, R, entry_begin,
+    MF_DISPATCH(launch_sgd_ring_t, exact, short_prefetch, waves, query_only, max_resident, P, Qt, U, V, R, entry_begin,
                 entry_len, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done, first, abort_flag,
                 spin_limit, order, pos, stream);
 }

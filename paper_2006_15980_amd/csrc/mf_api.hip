@@ -51,6 +51,7 @@ struct mf_ctx {
     int32_t* d_ring_done = nullptr;       // grid_r counters + 1 abort flag, inside the workspace
     int32_t lds_chunk = 0;   // 0 = one chunk per wavefront
     int32_t lds_waves = 16;
+    int32_t lds_prefetch = 0;  // 0 = by the size of P, else 4 or 8
 
     // library-owned device buffer: RMSE partials followed by the final sum
     double* d_partials = nullptr;
@@ -216,6 +217,10 @@ int mf_set_option(mf_ctx* ctx, int32_t option, int64_t value)
         case MF_OPT_LDS_WAVES:
             if (value < 1 || value > 16) return fail(ctx, MF_EINVAL, "wavefronts per workgroup must be in [1, 16]");
             ctx->lds_waves = (int32_t)value;
+            return MF_OK;
+        case MF_OPT_LDS_PREFETCH:
+            if (value != 0 && value != 4 && value != 8) return fail(ctx, MF_EINVAL, "MF_OPT_LDS_PREFETCH is 0, 4 or 8");
+            ctx->lds_prefetch = (int32_t)value;
             return MF_OK;
     }
     return fail(ctx, MF_EINVAL, "unknown option");
@@ -464,6 +469,10 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
     // strip fits (the deterministic mode additionally wants several workgroups per compute unit
     // to be possible, since each of its workgroups is a single wavefront)
     const bool hog = mode == MF_MODE_HOGWILD;
+    // rows of P are requested 8 ratings ahead when they come from HBM, 4 when P is small enough to
+    // be served from the L2s and the memory-side cache (fewer padded positions per batch)
+    const size_t p_bytes = (size_t)ctx->m * ctx->k * (ctx->dtype == MF_F16 ? 2 : 4);
+    const bool short_prefetch = ctx->lds_prefetch == 4 || (ctx->lds_prefetch == 0 && p_bytes <= ((size_t)64 << 20));
     const mf::LdsSchedule& lsched = hog ? ctx->lds : ctx->det_lds;
     const size_t lds_bytes = mf::lds_strip_bytes(ctx->k, lsched.max_cols);
     const int32_t choice = hog ? ctx->hogwild_kernel : ctx->det_kernel;
@@ -479,7 +488,7 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
         const int m_idx = hog ? 1 : 0;
         if (ctx->ring_resident[m_idx] < 0) {
             int resident = 0;
-            MF_HIP(ctx, mf::launch_sgd_ring(ctx->dtype, ctx->k, !hog, ctx->lds_waves, true, &resident, nullptr, nullptr,
+            MF_HIP(ctx, mf::launch_sgd_ring(ctx->dtype, ctx->k, !hog, short_prefetch, ctx->lds_waves, true, &resident, nullptr, nullptr,
                                             nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, ctx->part.gr,
                                             ctx->part.gc, lds_bytes, 0.f, 0.f, nullptr, 0, nullptr, 0, nullptr, nullptr,
                                             ctx->stream));
@@ -510,7 +519,7 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
                 ctx->events_used += 1;
                 MF_HIP(ctx, hipEventRecord(ev0, ctx->stream));
             }
-            MF_HIP(ctx, mf::launch_sgd_ring(ctx->dtype, ctx->k, !hog, ctx->lds_waves, false, nullptr, ctx->dP, ctx->dQt,
+            MF_HIP(ctx, mf::launch_sgd_ring(ctx->dtype, ctx->k, !hog, short_prefetch, ctx->lds_waves, false, nullptr, ctx->dP, ctx->dQt,
                                             ctx->dU, ctx->dV, ctx->dR, lsched.d_begin, lsched.d_len, lsched.d_ring,
                                             ctx->part.gr, ctx->part.gc, lds_bytes, lr, lambda, ctx->d_ring_done,
                                             ctx->ring_epochs * ctx->part.gc, ctx->d_ring_done + ctx->part.gr,
@@ -545,7 +554,7 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
             MF_HIP(ctx, hipEventRecord(ev0, ctx->stream));
         }
         if (use_lds)
-            MF_HIP(ctx, mf::launch_sgd_lds(ctx->dtype, ctx->k, !hog, ctx->lds_waves, ctx->dP, ctx->dQt, ctx->dU,
+            MF_HIP(ctx, mf::launch_sgd_lds(ctx->dtype, ctx->k, !hog, short_prefetch, ctx->lds_waves, ctx->dP, ctx->dQt, ctx->dU,
                                            ctx->dV, ctx->dR, lsched.d_begin, lsched.d_len,
                                            lsched.d_blocks + first, count, lds_bytes, lr, lambda,
                                            ctx->stream));

@@ -110,8 +110,10 @@ hipError_t launch_sgd(int dtype, int k, bool hogwild, void* P, void* Qt, const i
                       const int32_t* entry_len, int64_t first_entry, int64_t n_entries, float lr,
                       float lambda, hipStream_t stream);
 // LDS-resident kernel: one workgroup per block descriptor; `exact` = deterministic mode (one
-// wavefront per workgroup, fp32 strip), else Hogwild (`waves` wavefronts, fixed-point strip).
-hipError_t launch_sgd_lds(int dtype, int k, bool exact, int waves, void* P, void* Qt, const int32_t* U,
+// wavefront per workgroup, fp32 strip), else Hogwild (`waves` wavefronts, fixed-point strip;
+// short_prefetch: rows of P are requested 4 instead of 8 ratings ahead, which pays when P is
+// served from the caches).
+hipError_t launch_sgd_lds(int dtype, int k, bool exact, bool short_prefetch, int waves, void* P, void* Qt, const int32_t* U,
                           const int32_t* V, const float* R, const int64_t* entry_begin,
                           const int32_t* entry_len, const LdsBlock* blocks, int64_t n_blocks,
                           size_t lds_bytes, float lr, float lambda, hipStream_t stream);
@@ -119,7 +121,7 @@ hipError_t launch_sgd_lds(int dtype, int k, bool exact, int waves, void* P, void
 // descriptors indexed [stratum][block row], empty blocks included.  order / pos (device, grid_c
 // entries each, both or neither): the stratum of every step and its inverse.  query_only: do not launch,
 // return in *max_resident how many workgroups of this shape the device can hold at once.
-hipError_t launch_sgd_ring(int dtype, int k, bool exact, int waves, bool query_only, int* max_resident,
+hipError_t launch_sgd_ring(int dtype, int k, bool exact, bool short_prefetch, int waves, bool query_only, int* max_resident,
                            void* P, void* Qt, const int32_t* U, const int32_t* V, const float* R,
                            const int64_t* entry_begin, const int32_t* entry_len, const LdsBlock* ring_blocks,
                            int grid_r, int grid_c, size_t lds_bytes, float lr, float lambda, int* done,
