@@ -3,7 +3,10 @@
 A step is one epoch of the paper's Algorithm 1 over the whole training set of the workload
 (rating fetch, gather, dot, update, scatter, stratum scheduling) in HOGWILD mode, followed by the
 held-out RMSE.  The rating matrix is partitioned and resident in HBM before the timed region.
-Prints one JSON line (see README for the fields).
+Prints one JSON line: metric, value (updates per second over the timed steps), ms_per_step, config,
+`roofline` (algorithmic bytes per launch of the dominant kernel over its measured duration, against
+the 8 TB/s HBM peak; `traffic` = memory-side bytes per launch from the rocprofv3 counter passes) and
+`cpu_baseline` (the CPU oracle timed on the same workload).
 """
 import argparse
 import json
