@@ -56,13 +56,31 @@ __global__ __launch_bounds__(kSortThreads) void count_degrees(
     }
 }
 
+// Rating counts of an axis short enough for a private histogram per workgroup in LDS (the ids of
+// a skewed axis repeat often: LDS atomics instead of contended ones in the L2); the private counts
+// are added to the global ones at the end.  Dynamic LDS: size * 4 bytes.
+__global__ __launch_bounds__(1024) void count_ids_lds(const int32_t* __restrict__ ids, int64_t nnz, int32_t size,
+                                                     int32_t* __restrict__ degree)
+{
+    extern __shared__ int32_t priv[];
+    for (int i = threadIdx.x; i < size; i += blockDim.x) priv[i] = 0;
+    __syncthreads();
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < nnz; t += stride) {
+        const int32_t x = ids[t];
+        if (x >= 0 && x < size) atomicAdd(&priv[x], 1);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < size; i += blockDim.x)
+        if (priv[i] != 0) atomicAdd(&degree[i], priv[i]);
+}
+
 // key = L << (ubits + vbits) | (u - first row of its strip) << vbits | (v - first column of its strip)
 __global__ __launch_bounds__(kSortThreads) void make_keys(
     const int32_t* __restrict__ rows, const int32_t* __restrict__ cols, int64_t nnz,
     const int32_t* __restrict__ row_strip, const int32_t* __restrict__ col_strip,
     const int32_t* __restrict__ row_bounds, const int32_t* __restrict__ col_bounds, int32_t gr, int32_t gc,
-    int ubits, int vbits, uint64_t* __restrict__ keys, uint32_t* __restrict__ payload,
-    int32_t* __restrict__ block_count)
+    int ubits, int vbits, uint64_t* __restrict__ keys, uint32_t* __restrict__ payload)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < nnz; t += stride) {
@@ -74,7 +92,21 @@ __global__ __launch_bounds__(kSortThreads) void make_keys(
         const uint64_t ur = (uint64_t)(u - row_bounds[a]), vr = (uint64_t)(v - col_bounds[b]);
         keys[t] = ((uint64_t)L << (ubits + vbits)) | (ur << vbits) | vr;
         payload[t] = (uint32_t)t;
-        atomicAdd(&block_count[L], 1);
+    }
+}
+
+// First packed position of every block, read off the sorted keys: position i starts block L_i and
+// every empty block between L_(i-1) and L_i; the last thread closes the table.
+__global__ __launch_bounds__(kSortThreads) void block_starts(const uint64_t* __restrict__ keys, int64_t nnz, int shift,
+                                                           int64_t nblocks, uint32_t* __restrict__ block_ptr)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nnz; i += stride) {
+        const int64_t L = (int64_t)(keys[i] >> shift);
+        const int64_t before = i > 0 ? (int64_t)(keys[i - 1] >> shift) : -1;
+        for (int64_t x = before + 1; x <= L; ++x) block_ptr[x] = (uint32_t)i;
+        if (i == nnz - 1)
+            for (int64_t x = L + 1; x <= nblocks; ++x) block_ptr[x] = (uint32_t)nnz;
     }
 }
 
@@ -356,10 +388,33 @@ int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const f
         PD_HIP(hipMemsetAsync(col_degree.p, 0, (size_t)n * 4, stream));
     }
     if (nnz > 0) {
+        // an axis whose counters fit the LDS is counted there, the other one (and the range check) with
+        // global atomics
+        constexpr int64_t kLdsCounters = 36 * 1024;
+        const bool rows_in_lds = balanced && m <= kLdsCounters, cols_in_lds = balanced && n <= kLdsCounters;
         hipLaunchKernelGGL(count_degrees, dim3(streaming_groups(nnz)), dim3(kSortThreads), 0, stream, d_rows, d_cols,
-                           nnz, (int32_t)m, (int32_t)n, row_degree.as<int32_t>(), col_degree.as<int32_t>(),
-                           flag.as<int32_t>());
+                           nnz, (int32_t)m, (int32_t)n, rows_in_lds ? nullptr : row_degree.as<int32_t>(),
+                           cols_in_lds ? nullptr : col_degree.as<int32_t>(), flag.as<int32_t>());
         PD_HIP(hipGetLastError());
+        static bool raised[64] = {};
+        int dev = 0;
+        PD_HIP(hipGetDevice(&dev));
+        if ((rows_in_lds || cols_in_lds) && dev >= 0 && dev < 64 && !raised[dev]) {
+            PD_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&count_ids_lds),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kLdsCounters * 4)));
+            raised[dev] = true;
+        }
+        const int groups = (int)std::max<int64_t>(1, std::min<int64_t>((nnz + 16383) / 16384, 512));
+        if (rows_in_lds) {
+            hipLaunchKernelGGL(count_ids_lds, dim3(groups), dim3(1024), (size_t)m * 4, stream, d_rows, nnz, (int32_t)m,
+                               row_degree.as<int32_t>());
+            PD_HIP(hipGetLastError());
+        }
+        if (cols_in_lds) {
+            hipLaunchKernelGGL(count_ids_lds, dim3(groups), dim3(1024), (size_t)n * 4, stream, d_cols, nnz, (int32_t)n,
+                               col_degree.as<int32_t>());
+            PD_HIP(hipGetLastError());
+        }
     }
     int32_t bad = 0;
     PD_HIP(hipMemcpyAsync(&bad, flag.p, 4, hipMemcpyDeviceToHost, stream));
@@ -403,14 +458,13 @@ int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const f
     PD_HIP(col_strip.alloc((size_t)n * 4));
     PD_HIP(d_row_bounds.alloc(((size_t)gr + 1) * 4));
     PD_HIP(d_col_bounds.alloc(((size_t)gc + 1) * 4));
-    PD_HIP(block_count.alloc((size_t)nblocks * 4));
+    PD_HIP(block_count.alloc(((size_t)nblocks + 1) * 4));   // first packed position of every block
     strip_table(out.row_bounds, m, table);
     PD_HIP(hipMemcpy(row_strip.p, table.data(), (size_t)m * 4, hipMemcpyHostToDevice));
     strip_table(out.col_bounds, n, table);
     PD_HIP(hipMemcpy(col_strip.p, table.data(), (size_t)n * 4, hipMemcpyHostToDevice));
     PD_HIP(hipMemcpy(d_row_bounds.p, out.row_bounds.data(), ((size_t)gr + 1) * 4, hipMemcpyHostToDevice));
     PD_HIP(hipMemcpy(d_col_bounds.p, out.col_bounds.data(), ((size_t)gc + 1) * 4, hipMemcpyHostToDevice));
-    PD_HIP(hipMemsetAsync(block_count.p, 0, (size_t)nblocks * 4, stream));
 
     timer.mark("strip tables", stream);
     // ---- keys, payload, block sizes
@@ -427,7 +481,7 @@ int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const f
     hipLaunchKernelGGL(make_keys, dim3(streaming_groups(nnz)), dim3(kSortThreads), 0, stream, d_rows, d_cols, nnz,
                        row_strip.as<int32_t>(), col_strip.as<int32_t>(), d_row_bounds.as<int32_t>(),
                        d_col_bounds.as<int32_t>(), gr, gc, ubits, vbits, keys[0].as<uint64_t>(),
-                       payload[0].as<uint32_t>(), block_count.as<int32_t>());
+                       payload[0].as<uint32_t>());
     PD_HIP(hipGetLastError());
     timer.mark("allocations and keys", stream);
 
@@ -454,6 +508,9 @@ int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const f
                        keys[cur].as<uint64_t>(), payload[cur].as<uint32_t>(), nnz, d_row_bounds.as<int32_t>(),
                        d_col_bounds.as<int32_t>(), gr, gc, ubits, vbits, d_vals, dU, dV, dR, d_perm);
     PD_HIP(hipGetLastError());
+    hipLaunchKernelGGL(block_starts, dim3(streaming_groups(nnz)), dim3(kSortThreads), 0, stream,
+                       keys[cur].as<uint64_t>(), nnz, ubits + vbits, nblocks, block_count.as<uint32_t>());
+    PD_HIP(hipGetLastError());
     const int64_t nwords = (nnz + kWave - 1) / kWave;
     DeviceBuffer words;
     PD_HIP(words.alloc((size_t)nwords * 8));
@@ -465,14 +522,9 @@ int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const f
     timer.mark("unpack", stream);
     // ---- what the host needs for the work lists: block boundaries and where the row runs begin
     {
-        std::vector<int32_t> counts((size_t)nblocks);
-        PD_HIP(hipMemcpy(counts.data(), block_count.p, (size_t)nblocks * 4, hipMemcpyDeviceToHost));
-        int64_t run = 0;
-        for (int64_t L = 0; L < nblocks; ++L) {
-            out.block_ptr[(size_t)L] = run;
-            run += counts[(size_t)L];
-        }
-        out.block_ptr[(size_t)nblocks] = run;
+        std::vector<uint32_t> starts((size_t)nblocks + 1);
+        PD_HIP(hipMemcpy(starts.data(), block_count.p, ((size_t)nblocks + 1) * 4, hipMemcpyDeviceToHost));
+        for (int64_t L = 0; L <= nblocks; ++L) out.block_ptr[(size_t)L] = (int64_t)starts[(size_t)L];
     }
     rs.bits.resize((size_t)nwords);
     PD_HIP(hipMemcpy(rs.bits.data(), words.p, (size_t)nwords * 8, hipMemcpyDeviceToHost));
