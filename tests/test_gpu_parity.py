@@ -559,8 +559,8 @@ def test_medium_config_scaled_det_and_hogwild(mfmod):
 
 def test_medium_config_full_size(mfmod):
     """Configuration 2 at its full size, in the launch configuration the benchmark times
-    (HOGWILD, 224 x 224 grid, LDS kernel, one launch per epoch) plus the deterministic mode on a
-    fine grid."""
+    (HOGWILD, 256 x 256 grid, LDS kernel with 12 wavefronts per workgroup, one launch per epoch,
+    partitioned on the device) plus the deterministic mode on a fine grid."""
     ds = dataset("medium")
     k = ds.cfg.k
     print("medium: max row/col degree", ds.max_row_degree, ds.max_col_degree, flush=True)
@@ -569,10 +569,18 @@ def test_medium_config_full_size(mfmod):
     print("medium DET one epoch: max|dP| %.3g max|dQ| %.3g" % (dP, dQ), flush=True)
     assert dP <= 1e-4 and dQ <= 1e-4
     epochs = ds.cfg.epochs if FULL else 6
-    Po, Qo, _ = oracle_train(ds, 224, 224, 1, epochs)
+    Po, Qo, _ = oracle_train(ds, 256, 256, 1, epochs)
     want = oracle.rmse(Po, Qo, ds.test_rows, ds.test_cols, ds.test_vals)
-    got = _train_gpu(mfmod, ds, k, "f32", 224, 224, 1, mfmod.MF_MODE_HOGWILD, epochs,
-                     options={mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS})
+    model = mfmod.MatrixFactorization(ds.cfg.m, ds.cfg.n, k, "f32", seed=1, scale=0.1,
+                                      options={mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS,
+                                               mfmod.MF_OPT_LDS_WAVES: 12})
+    dev = model.P.device
+    model.load_blocks_device(*(torch.from_numpy(x).to(dev) for x in (ds.rows, ds.cols, ds.vals)), 256, 256, 1)
+    tr, tc, tv = model.to_device(ds.test_rows, ds.test_cols, ds.test_vals)
+    for _ in range(epochs):
+        model.sgd_epoch(ds.cfg.lr, ds.cfg.lam, mfmod.MF_MODE_HOGWILD)
+    got = model.rmse(tr, tc, tv)
+    model.close()
     print("medium HOGWILD %d epochs: rmse gpu %.6f oracle %.6f" % (epochs, got, want), flush=True)
     assert abs(got - want) <= 0.005 * want, (got, want)
     got_det = _train_gpu(mfmod, ds, k, "f32", 8, 8, 1, mfmod.MF_MODE_DET, 1)
