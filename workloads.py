@@ -132,7 +132,7 @@ def _zipf_degrees(size: int, alpha: float, total: int, cap: float, rng: np.rando
     return out
 
 
-def _sample_axis(deg: np.ndarray, count: int, rng: np.random.Generator) -> np.ndarray:
+def _sample_axis(deg: np.ndarray, count: int, rng: np.random.Generator, what: str = "") -> np.ndarray:
     cdf = np.cumsum(deg)
     cdf /= cdf[-1]
     out = np.empty(count, dtype=np.int64)
@@ -140,6 +140,8 @@ def _sample_axis(deg: np.ndarray, count: int, rng: np.random.Generator) -> np.nd
     for s in range(0, count, chunk):
         e = min(count, s + chunk)
         out[s:e] = np.searchsorted(cdf, rng.random(e - s), side="right")
+        if what and (s // chunk) % 8 == 7:
+            _progress(f"{what}: {e} of {count} drawn")
     np.minimum(out, deg.size - 1, out=out)
     return out
 
@@ -156,8 +158,9 @@ def _pairs(cfg: Config, total: int, rng: np.random.Generator):
         for rnd in range(64):
             draw = int(want * 1.05) + 1024
             _progress(f"{cfg.name}: pair round {rnd}, drawing {draw}")
-            u = _sample_axis(drow, draw, rng)
-            v = _sample_axis(dcol, draw, rng)
+            u = _sample_axis(drow, draw, rng, f"{cfg.name} rows")
+            v = _sample_axis(dcol, draw, rng, f"{cfg.name} columns")
+            _progress(f"{cfg.name}: removing duplicate pairs")
             keys = np.unique(np.concatenate([keys, u * n + v]))
             if keys.size >= total:
                 break
