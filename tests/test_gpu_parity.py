@@ -352,6 +352,19 @@ def test_hogwild_visits_every_rating_exactly_once(mfmod, kernel, ring, grid):
     assert np.abs(P - Po).max() <= 6e-7 and np.abs(Q - Qo).max() <= 1.2e-6, (np.abs(P - Po).max(), np.abs(Q - Qo).max())
 
 
+def test_suggested_grids_train_to_the_oracle_result(mfmod):
+    """mf_suggest_grid's answer for both modes is a grid the kernels accept and train on."""
+    ds = dataset("tiny")
+    cfg = ds.cfg
+    for mode in (mfmod.MF_MODE_HOGWILD, mfmod.MF_MODE_DET):
+        gr, gc, split = mfmod.binding.mf_suggest_grid(cfg.m, cfg.n, ds.rows.size, cfg.k, mode)
+        Po, Qo, _ = oracle_train(ds, gr, gc, split, cfg.epochs)
+        want = oracle.rmse(Po, Qo, ds.test_rows, ds.test_cols, ds.test_vals)
+        got = _train_gpu(mfmod, ds, cfg.k, "f32", gr, gc, split, mode, cfg.epochs)
+        tol = 5e-3 * want if mode == mfmod.MF_MODE_HOGWILD else 1e-3
+        assert abs(got - want) <= tol, (mode, gr, gc, got, want)
+
+
 def test_det_edge_cases(mfmod):
     rng = np.random.default_rng(3)
     # duplicates of one (u, v), a single long row, a single long column, and empty strata
