@@ -186,7 +186,8 @@ int mfo_blocks_independent(int32_t a1, int32_t b1, int32_t a2, int32_t b2)
 
 typedef struct {
     int64_t L;       /* linear block id = stratum * G_r + a */
-    int32_t u, v;
+    int64_t rank;    /* place of the row inside its strip (the row index itself for row_seed 0) */
+    int32_t v;
     int64_t t;       /* original position: total order even for duplicate (u,v) */
 } sort_key;
 
@@ -195,19 +196,46 @@ static int cmp_key(const void* pa, const void* pb)
     const sort_key* x = (const sort_key*)pa;
     const sort_key* y = (const sort_key*)pb;
     if (x->L != y->L) return x->L < y->L ? -1 : 1;
-    if (x->u != y->u) return x->u < y->u ? -1 : 1;
+    if (x->rank != y->rank) return x->rank < y->rank ? -1 : 1;
     if (x->v != y->v) return x->v < y->v ? -1 : 1;
     if (x->t != y->t) return x->t < y->t ? -1 : 1;
     return 0;
+}
+
+static uint64_t mix64(uint64_t z);
+
+/* Randomised order of the rows inside a block (the paper's scheduler visits "randomly"; it fixes
+ * no generator).  Convention of this build: the rows of row strip a (first row `first`, `width`
+ * rows) are visited in the order of ((u - first) * 2147483647 + offset_a) mod width with
+ * offset_a = mix64(row_seed + a) mod width -- an affine map with a prime multiplier larger than
+ * any width, hence a permutation of the strip's rows.  row_seed = 0 keeps ascending row order.
+ * All ratings of one row stay together, ordered by column and original position. */
+int64_t mfo_row_rank(int32_t u, int32_t first, int32_t width, uint64_t row_seed, int32_t a)
+{
+    if (row_seed == 0) return (int64_t)u;
+    uint64_t offset = mix64(row_seed + (uint64_t)a) % (uint64_t)width;
+    return (int64_t)((((uint64_t)(u - first)) * 2147483647ULL + offset) % (uint64_t)width);
 }
 
 /* Stratum of block (a,b): s = (b - a) mod G_c.  For fixed s the G_r blocks (a, (a+s) mod G_c)
  * have pairwise different a and (because G_r <= G_c) pairwise different b: they are mutually
  * independent.  Linear id L = s*G_r + a.  perm lists the original positions in ascending
  * (L, u, v, t); block_ptr[L] is where block L starts in perm. */
+int mfo_partition_seeded(const int32_t* rows, const int32_t* cols, int64_t nnz, int64_t m, int64_t n,
+                         int32_t G_r, int32_t G_c, int32_t split, uint64_t row_seed,
+                         int64_t* perm, int64_t* block_ptr, int32_t* row_bounds, int32_t* col_bounds);
+
 int mfo_partition(const int32_t* rows, const int32_t* cols, int64_t nnz, int64_t m, int64_t n,
                   int32_t G_r, int32_t G_c, int32_t split,
                   int64_t* perm, int64_t* block_ptr, int32_t* row_bounds, int32_t* col_bounds)
+{
+    return mfo_partition_seeded(rows, cols, nnz, m, n, G_r, G_c, split, 0, perm, block_ptr, row_bounds, col_bounds);
+}
+
+/* The same with the rows of every block in the order of mfo_row_rank (row_seed 0: ascending). */
+int mfo_partition_seeded(const int32_t* rows, const int32_t* cols, int64_t nnz, int64_t m, int64_t n,
+                         int32_t G_r, int32_t G_c, int32_t split, uint64_t row_seed,
+                         int64_t* perm, int64_t* block_ptr, int32_t* row_bounds, int32_t* col_bounds)
 {
     if (G_r < 1 || G_c < G_r || G_r > m || G_c > n) return -1;
     for (int64_t t = 0; t < nnz; ++t)
@@ -231,7 +259,7 @@ int mfo_partition(const int32_t* rows, const int32_t* cols, int64_t nnz, int64_t
         int32_t s = (b - a) % G_c;
         if (s < 0) s += G_c;
         keys[t].L = (int64_t)s * G_r + a;
-        keys[t].u = rows[t];
+        keys[t].rank = mfo_row_rank(rows[t], row_bounds[a], row_bounds[a + 1] - row_bounds[a], row_seed, a);
         keys[t].v = cols[t];
         keys[t].t = t;
     }

@@ -20,7 +20,7 @@ __all__ = ["ARITH_F64", "ARITH_F32", "ARITH_F16", "SPLIT_EQUAL_WIDTH", "SPLIT_NN
            "round_f16", "init_factors", "partition", "blocks_independent", "sgd_step",
            "sgd_epoch", "sgd_epoch_omp", "sgd_sweep", "predict", "rating_loss", "rmse",
            "num_threads", "bounds_equal_width", "bounds_nnz_balanced", "mix64", "stratum_order",
-           "sgd_epoch_ordered"]
+           "sgd_epoch_ordered", "row_rank"]
 
 _lib = None
 
@@ -76,19 +76,27 @@ def bounds_nnz_width_balanced(idx: np.ndarray, size: int, G: int) -> np.ndarray:
     return b
 
 
-def partition(rows, cols, m, n, G_r, G_c, split=SPLIT_EQUAL_WIDTH):
-    """-> (perm int64[nnz], block_ptr int64[G_r*G_c+1], row_bounds, col_bounds)."""
+def partition(rows, cols, m, n, G_r, G_c, split=SPLIT_EQUAL_WIDTH, row_seed=0):
+    """-> (perm int64[nnz], block_ptr int64[G_r*G_c+1], row_bounds, col_bounds).
+    row_seed != 0: the rows of every block in the seeded order of row_rank instead of ascending."""
     nnz = rows.size
     perm = np.empty(nnz, dtype=np.int64)
     bp = np.empty(G_r * G_c + 1, dtype=np.int64)
     rb = np.empty(G_r + 1, dtype=np.int32)
     cb = np.empty(G_c + 1, dtype=np.int32)
-    rc = _load().mfo_partition(_p(rows, np.int32), _p(cols, np.int32), C.c_int64(nnz), C.c_int64(m),
-                               C.c_int64(n), C.c_int32(G_r), C.c_int32(G_c), C.c_int32(split),
-                               _p(perm, np.int64), _p(bp, np.int64), _p(rb, np.int32), _p(cb, np.int32))
+    rc = _load().mfo_partition_seeded(_p(rows, np.int32), _p(cols, np.int32), C.c_int64(nnz), C.c_int64(m),
+                                      C.c_int64(n), C.c_int32(G_r), C.c_int32(G_c), C.c_int32(split),
+                                      C.c_uint64(row_seed),
+                                      _p(perm, np.int64), _p(bp, np.int64), _p(rb, np.int32), _p(cb, np.int32))
     if rc != 0:
         raise ValueError(f"mfo_partition failed with {rc}")
     return perm, bp, rb, cb
+
+
+def row_rank(u: int, first: int, width: int, row_seed: int, a: int) -> int:
+    f = _load().mfo_row_rank
+    f.restype = C.c_int64
+    return int(f(C.c_int32(u), C.c_int32(first), C.c_int32(width), C.c_uint64(row_seed), C.c_int32(a)))
 
 
 def blocks_independent(a1, b1, a2, b2) -> bool:

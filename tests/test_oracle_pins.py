@@ -386,6 +386,40 @@ def test_ordered_epoch_is_the_blocks_swept_in_that_order_exactly_once():
         assert not np.array_equal(A[1], plain[1])          # the order does matter across strata
 
 
+def test_seeded_row_order_is_a_permutation_of_every_strip_and_matches_brute_force():
+    m, n, gr, gc, seed = 211, 97, 4, 6, 12345
+    rng = np.random.default_rng(5)
+    rows = rng.integers(0, m, 3000).astype(np.int32)
+    cols = rng.integers(0, n, 3000).astype(np.int32)
+    perm, bp, rb, cb = oracle.partition(rows, cols, m, n, gr, gc, oracle.SPLIT_NNZ_BALANCED, row_seed=seed)
+    plain = oracle.partition(rows, cols, m, n, gr, gc, oracle.SPLIT_NNZ_BALANCED)
+    assert np.array_equal(bp, plain[1]) and np.array_equal(rb, plain[2]) and np.array_equal(cb, plain[3])
+    assert not np.array_equal(perm, plain[0])
+    assert np.array_equal(oracle.partition(rows, cols, m, n, gr, gc, oracle.SPLIT_NNZ_BALANCED, row_seed=0)[0], plain[0])
+    # the rank is the stated affine map (restated with Python integers and the pinned mixer) and a bijection
+    rank = {}
+    for a in range(gr):
+        first, width = int(rb[a]), int(rb[a + 1] - rb[a])
+        offset = oracle.mix64(seed + a) % width
+        got = [oracle.row_rank(u, first, width, seed, a) for u in range(first, first + width)]
+        assert got == [((u - first) * 2147483647 + offset) % width for u in range(first, first + width)]
+        assert sorted(got) == list(range(width))
+        for u, r in zip(range(first, first + width), got):
+            rank[u] = r
+    # brute force: block id, then rank of the row, column, original position
+    strip = lambda bounds, x: int(np.searchsorted(bounds, x, side="right") - 1)
+    def key(t):
+        a, b = strip(rb, rows[t]), strip(cb, cols[t])
+        return (((b - a) % gc) * gr + a, rank[int(rows[t])], int(cols[t]), t)
+    assert perm.tolist() == sorted(range(rows.size), key=key)
+    # all ratings of a row of a block stay together
+    for L in range(gr * gc):
+        blk_rows = rows[perm[bp[L]:bp[L + 1]]]
+        changes = np.flatnonzero(np.diff(blk_rows)) + 1
+        runs = np.split(blk_rows, changes)
+        assert len({int(r[0]) for r in runs}) == len(runs)
+
+
 # --------------------------------------------------------------------------- convergence on noiseless planted data
 def test_noiseless_planted_low_rank_reaches_near_zero_rmse():
     m, n, rank = 150, 120, 3
