@@ -64,8 +64,14 @@ enum {
                                   /* mf_sgd_epoch) when all grid_r workgroups fit the device at once; */
                                   /* 0: always one launch per stratum                                 */
     MF_OPT_RING_SPIN_LIMIT = 9,   /* polls after which a waiting workgroup gives up (default 2^22)    */
-    MF_OPT_LDS_PREFETCH = 10      /* MF_MODE_HOGWILD, LDS kernels: rows of P requested 4 or 8 ratings */
+    MF_OPT_LDS_PREFETCH = 10,     /* MF_MODE_HOGWILD, LDS kernels: rows of P requested 4 or 8 ratings */
                                   /* ahead; 0 (default): 4 if P takes at most 64 MiB, else 8          */
+    MF_OPT_ROW_ORDER_SEED = 11    /* read by mf_load_blocks(_device): 0 (default) = the rows of a     */
+                                  /* block in ascending order; else they are visited in a seeded      */
+                                  /* order (the paper's scheduler visits "randomly", Section 3.1):    */
+                                  /* rows of row strip a by ((u - first) * 2147483647 + shift_a) mod  */
+                                  /* width, shift_a = mix(seed + a) mod width, mix = the SplitMix64   */
+                                  /* output function.  The ratings of a row stay together.            */
 };
 enum { MF_KERNEL_AUTO = 0, MF_KERNEL_GLOBAL = 1, MF_KERNEL_LDS = 2 };
 enum { MF_HOGWILD_AUTO = MF_KERNEL_AUTO, MF_HOGWILD_GLOBAL_ATOMICS = MF_KERNEL_GLOBAL, MF_HOGWILD_LDS = MF_KERNEL_LDS };

@@ -52,6 +52,7 @@ struct mf_ctx {
     int32_t lds_chunk = 0;   // 0 = one chunk per wavefront
     int32_t lds_waves = 16;
     int32_t lds_prefetch = 0;  // 0 = by the size of P, else 4 or 8
+    uint64_t row_seed = 0;     // 0 = rows of a block in ascending order
 
     // library-owned device buffer: RMSE partials followed by the final sum
     double* d_partials = nullptr;
@@ -218,6 +219,10 @@ int mf_set_option(mf_ctx* ctx, int32_t option, int64_t value)
             if (value < 1 || value > 16) return fail(ctx, MF_EINVAL, "wavefronts per workgroup must be in [1, 16]");
             ctx->lds_waves = (int32_t)value;
             return MF_OK;
+        case MF_OPT_ROW_ORDER_SEED:
+            if (value < 0) return fail(ctx, MF_EINVAL, "the seed must not be negative");
+            ctx->row_seed = (uint64_t)value;
+            return MF_OK;
         case MF_OPT_LDS_PREFETCH:
             if (value != 0 && value != 4 && value != 8) return fail(ctx, MF_EINVAL, "MF_OPT_LDS_PREFETCH is 0, 4 or 8");
             ctx->lds_prefetch = (int32_t)value;
@@ -349,7 +354,7 @@ int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const 
     std::vector<float> pr;
     try {
         std::string err;
-        rc = mf::build_partition(rows, cols, vals, nnz, ctx->m, ctx->n, grid_r, grid_c, split, ctx->part,
+        rc = mf::build_partition(rows, cols, vals, nnz, ctx->m, ctx->n, grid_r, grid_c, split, ctx->row_seed, ctx->part,
                                  pu, pv, pr, err);
         if (rc) return fail(ctx, rc, err);
     } catch (const std::bad_alloc&) {
@@ -393,7 +398,7 @@ int mf_load_blocks_device(mf_ctx* ctx, const int32_t* d_rows, const int32_t* d_c
     try {
         std::string err;
         rc = mf::build_partition_device(d_rows, d_cols, d_vals, nnz, ctx->m, ctx->n, grid_r, grid_c, split,
-                                        ctx->dU, ctx->dV, ctx->dR, ctx->d_perm, ctx->part, rs, ctx->stream, err);
+                                        ctx->row_seed, ctx->dU, ctx->dV, ctx->dR, ctx->d_perm, ctx->part, rs, ctx->stream, err);
         if (rc) return fail(ctx, rc, err);
     } catch (const std::bad_alloc&) {
         return fail(ctx, MF_ENOMEM, "host allocation failed while partitioning");
@@ -426,13 +431,7 @@ int mf_get_partition(const mf_ctx* ctx, int64_t* perm, int64_t* block_ptr, int32
 int mf_stratum_order(uint64_t seed, uint64_t epoch, int32_t grid_c, int32_t* order_out)
 {
     if (grid_c < 1 || !order_out) return MF_EINVAL;
-    // SplitMix64 output function (published algorithm) as a counter-based source of sort keys
-    auto mix = [](uint64_t z) {
-        z += 0x9E3779B97F4A7C15ULL;
-        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
-        z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
-        return z ^ (z >> 31);
-    };
+    auto mix = [](uint64_t z) { return mf::mix64(z); };
     const uint64_t base = mix(seed ^ (epoch * 0xD1B54A32D192ED03ULL));
     std::vector<std::pair<uint64_t, int32_t>> keyed((size_t)grid_c);
     for (int32_t s = 0; s < grid_c; ++s) keyed[(size_t)s] = {mix(base + (uint64_t)s), s};
@@ -690,7 +689,7 @@ int mf_plan_host(const int32_t* rows, const int32_t* cols, int64_t nnz, int64_t 
         std::vector<int32_t> pu, pv;
         std::vector<float> pr, vals((size_t)nnz, 0.f);
         std::string err;
-        int rc = mf::build_partition(rows, cols, vals.data(), nnz, m, n, grid_r, grid_c, split, part, pu, pv, pr, err);
+        int rc = mf::build_partition(rows, cols, vals.data(), nnz, m, n, grid_r, grid_c, split, 0, part, pu, pv, pr, err);
         if (rc) return rc;
         mf::RowStarts rs;
         mf::row_starts_from_rows(pu.data(), nnz, rs);

@@ -59,6 +59,29 @@ struct RowStarts {
 };
 void row_starts_from_rows(const int32_t* pu, int64_t nnz, RowStarts& out);
 
+// SplitMix64 output function (published algorithm): the counter-based source of every seeded
+// choice of the library.
+__host__ __device__ inline uint64_t mix64(uint64_t z)
+{
+    z += 0x9E3779B97F4A7C15ULL;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+
+// Seeded order of the rows inside a block (MF_OPT_ROW_ORDER_SEED): the rows of a row strip of
+// `width` rows are visited in the order of (offset_in_strip * kRowOrderPrime + shift) mod width, an
+// affine map with a prime multiplier above any width, hence a permutation of the strip's rows.
+constexpr uint64_t kRowOrderPrime = 2147483647ULL;
+__host__ __device__ inline uint32_t row_order_shift(uint64_t row_seed, int32_t a, int32_t width)
+{
+    return (uint32_t)(mix64(row_seed + (uint64_t)a) % (uint64_t)width);
+}
+__host__ __device__ inline uint32_t row_order_rank(uint32_t offset_in_strip, uint32_t shift, uint32_t width)
+{
+    return (uint32_t)(((uint64_t)offset_in_strip * kRowOrderPrime + shift) % width);
+}
+
 // Host partition of R into the block grid.
 struct Partition {
     int64_t nnz = 0;
@@ -71,8 +94,9 @@ struct Partition {
 
 // partition.cpp ------------------------------------------------------------------------------
 // Returns 0 or an MF_E* code; fills `out` and the packed COO arrays (host).
+// row_seed != 0: rows of a block in the seeded order above instead of ascending.
 int build_partition(const int32_t* rows, const int32_t* cols, const float* vals, int64_t nnz,
-                    int64_t m, int64_t n, int32_t gr, int32_t gc, int32_t split, Partition& out,
+                    int64_t m, int64_t n, int32_t gr, int32_t gc, int32_t split, uint64_t row_seed, Partition& out,
                     std::vector<int32_t>& pu, std::vector<int32_t>& pv, std::vector<float>& pr,
                     std::string& err);
 // Strip boundaries (size g + 1) of one axis: uniform division, or balanced by the per-id rating
@@ -100,8 +124,8 @@ int64_t hogwild_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk
 // empty), the rest of `out`, and `rs` for the schedule builders.  Temporary device memory (about
 // 24 bytes per rating) is allocated and freed inside.  Bit-identical to build_partition.
 int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const float* d_vals, int64_t nnz,
-                           int64_t m, int64_t n, int32_t gr, int32_t gc, int32_t split, int32_t* dU,
-                           int32_t* dV, float* dR, uint32_t* d_perm, Partition& out, RowStarts& rs,
+                           int64_t m, int64_t n, int32_t gr, int32_t gc, int32_t split, uint64_t row_seed,
+                           int32_t* dU, int32_t* dV, float* dR, uint32_t* d_perm, Partition& out, RowStarts& rs,
                            hipStream_t stream, std::string& err);
 
 // kernels.hip ---------------------------------------------------------------------------------

@@ -120,7 +120,7 @@ struct KeyPos {
 }  // namespace
 
 int build_partition(const int32_t* rows, const int32_t* cols, const float* vals, int64_t nnz,
-                    int64_t m, int64_t n, int32_t gr, int32_t gc, int32_t split, Partition& out,
+                    int64_t m, int64_t n, int32_t gr, int32_t gc, int32_t split, uint64_t row_seed, Partition& out,
                     std::vector<int32_t>& pu, std::vector<int32_t>& pv, std::vector<float>& pr,
                     std::string& err)
 {
@@ -201,14 +201,20 @@ int build_partition(const int32_t* rows, const int32_t* cols, const float* vals,
     blk.clear();
     blk.shrink_to_fit();
 
-    // inside every block: ascending (row, column, original position)
+    // inside every block: ascending (row, column, original position), the rows in their seeded
+    // order if one is asked for
     parallel_items(nblocks, threads, [&](int64_t L) {
         int64_t b = out.block_ptr[L], e = out.block_ptr[L + 1];
         if (e - b < 2) return;
+        const int32_t a = (int32_t)(L % gr);
+        const int32_t first = out.row_bounds[a], width = out.row_bounds[a + 1] - first;
+        const uint32_t shift = row_seed ? row_order_shift(row_seed, a, width) : 0;
         std::vector<KeyPos> tmp((size_t)(e - b));
         for (int64_t i = b; i < e; ++i) {
             int64_t t = out.perm[i];
-            tmp[i - b] = {((uint64_t)(uint32_t)rows[t] << 32) | (uint32_t)cols[t], t};
+            const uint32_t place = row_seed ? row_order_rank((uint32_t)(rows[t] - first), shift, (uint32_t)width)
+                                            : (uint32_t)rows[t];
+            tmp[i - b] = {((uint64_t)place << 32) | (uint32_t)cols[t], t};
         }
         std::sort(tmp.begin(), tmp.end(), [](const KeyPos& x, const KeyPos& y) {
             return x.key != y.key ? x.key < y.key : x.t < y.t;

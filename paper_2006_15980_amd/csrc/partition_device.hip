@@ -80,7 +80,8 @@ __global__ __launch_bounds__(kSortThreads) void make_keys(
     const int32_t* __restrict__ rows, const int32_t* __restrict__ cols, int64_t nnz,
     const int32_t* __restrict__ row_strip, const int32_t* __restrict__ col_strip,
     const int32_t* __restrict__ row_bounds, const int32_t* __restrict__ col_bounds, int32_t gr, int32_t gc,
-    int ubits, int vbits, uint64_t* __restrict__ keys, uint32_t* __restrict__ payload)
+    int ubits, int vbits, const uint32_t* __restrict__ row_shift, uint64_t* __restrict__ keys,
+    uint32_t* __restrict__ payload)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < nnz; t += stride) {
@@ -89,7 +90,10 @@ __global__ __launch_bounds__(kSortThreads) void make_keys(
         int32_t s = b - a;
         if (s < 0) s += gc;
         const int64_t L = (int64_t)s * gr + a;
-        const uint64_t ur = (uint64_t)(u - row_bounds[a]), vr = (uint64_t)(v - col_bounds[b]);
+        uint64_t ur = (uint64_t)(u - row_bounds[a]);
+        // seeded row order: the key holds the row's place in its strip instead of its offset
+        if (row_shift) ur = row_order_rank((uint32_t)ur, row_shift[a], (uint32_t)(row_bounds[a + 1] - row_bounds[a]));
+        const uint64_t vr = (uint64_t)(v - col_bounds[b]);
         keys[t] = ((uint64_t)L << (ubits + vbits)) | (ur << vbits) | vr;
         payload[t] = (uint32_t)t;
     }
@@ -297,8 +301,9 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter(
 __global__ __launch_bounds__(kSortThreads) void unpack_keys(
     const uint64_t* __restrict__ keys, const uint32_t* __restrict__ payload, int64_t nnz,
     const int32_t* __restrict__ row_bounds, const int32_t* __restrict__ col_bounds, int32_t gr, int32_t gc,
-    int ubits, int vbits, const float* __restrict__ vals, int32_t* __restrict__ U, int32_t* __restrict__ V,
-    float* __restrict__ R, uint32_t* __restrict__ perm)
+    int ubits, int vbits, const uint32_t* __restrict__ row_shift, const uint32_t* __restrict__ row_inverse,
+    const float* __restrict__ vals, int32_t* __restrict__ U, int32_t* __restrict__ V, float* __restrict__ R,
+    uint32_t* __restrict__ perm)
 {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nnz; i += stride) {
@@ -307,7 +312,13 @@ __global__ __launch_bounds__(kSortThreads) void unpack_keys(
         const int32_t a = (int32_t)(L % gr), s = (int32_t)(L / gr);
         int32_t b = a + s;
         if (b >= gc) b -= gc;
-        U[i] = row_bounds[a] + (int32_t)((k >> vbits) & ((1ull << ubits) - 1ull));
+        uint64_t ur = (k >> vbits) & ((1ull << ubits) - 1ull);
+        if (row_shift) {
+            // undo the affine map: offset = (place - shift) * prime^-1 mod width
+            const uint64_t width = (uint64_t)(row_bounds[a + 1] - row_bounds[a]);
+            ur = ((ur + width - row_shift[a]) % width) * row_inverse[a] % width;
+        }
+        U[i] = row_bounds[a] + (int32_t)ur;
         V[i] = col_bounds[b] + (int32_t)(k & ((1ull << vbits) - 1ull));
         const uint32_t t = payload[i];
         R[i] = vals[t];
@@ -366,8 +377,8 @@ int streaming_groups(int64_t items) { return (int)std::max<int64_t>(1, std::min<
     } while (0)
 
 int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const float* d_vals, int64_t nnz,
-                           int64_t m, int64_t n, int32_t gr, int32_t gc, int32_t split, int32_t* dU,
-                           int32_t* dV, float* dR, uint32_t* d_perm, Partition& out, RowStarts& rs,
+                           int64_t m, int64_t n, int32_t gr, int32_t gc, int32_t split, uint64_t row_seed,
+                           int32_t* dU, int32_t* dV, float* dR, uint32_t* d_perm, Partition& out, RowStarts& rs,
                            hipStream_t stream, std::string& err)
 {
     const int64_t nblocks = (int64_t)gr * gc;
@@ -465,6 +476,27 @@ int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const f
     PD_HIP(hipMemcpy(col_strip.p, table.data(), (size_t)n * 4, hipMemcpyHostToDevice));
     PD_HIP(hipMemcpy(d_row_bounds.p, out.row_bounds.data(), ((size_t)gr + 1) * 4, hipMemcpyHostToDevice));
     PD_HIP(hipMemcpy(d_col_bounds.p, out.col_bounds.data(), ((size_t)gc + 1) * 4, hipMemcpyHostToDevice));
+    // seeded row order: per row strip the shift of the affine map and the inverse of its multiplier
+    DeviceBuffer d_row_shift, d_row_inverse;
+    if (row_seed) {
+        std::vector<uint32_t> shift((size_t)gr), inverse((size_t)gr);
+        for (int32_t a = 0; a < gr; ++a) {
+            const int64_t width = std::max(1, out.row_bounds[a + 1] - out.row_bounds[a]);
+            shift[(size_t)a] = row_order_shift(row_seed, a, (int32_t)width);
+            // inverse of the prime modulo width by the extended Euclidean algorithm
+            int64_t r0 = width, r1 = (int64_t)(kRowOrderPrime % (uint64_t)width), t0 = 0, t1 = 1;
+            while (r1 != 0) {
+                const int64_t q = r0 / r1;
+                const int64_t r2 = r0 - q * r1, t2 = t0 - q * t1;
+                r0 = r1; r1 = r2; t0 = t1; t1 = t2;
+            }
+            inverse[(size_t)a] = (uint32_t)(((t0 % width) + width) % width);   // width 1: 0, the only offset
+        }
+        PD_HIP(d_row_shift.alloc((size_t)gr * 4));
+        PD_HIP(d_row_inverse.alloc((size_t)gr * 4));
+        PD_HIP(hipMemcpy(d_row_shift.p, shift.data(), (size_t)gr * 4, hipMemcpyHostToDevice));
+        PD_HIP(hipMemcpy(d_row_inverse.p, inverse.data(), (size_t)gr * 4, hipMemcpyHostToDevice));
+    }
 
     timer.mark("strip tables", stream);
     // ---- keys, payload, block sizes
@@ -480,8 +512,8 @@ int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const f
     PD_HIP(chunk_sums.alloc((size_t)nchunks * 4));
     hipLaunchKernelGGL(make_keys, dim3(streaming_groups(nnz)), dim3(kSortThreads), 0, stream, d_rows, d_cols, nnz,
                        row_strip.as<int32_t>(), col_strip.as<int32_t>(), d_row_bounds.as<int32_t>(),
-                       d_col_bounds.as<int32_t>(), gr, gc, ubits, vbits, keys[0].as<uint64_t>(),
-                       payload[0].as<uint32_t>());
+                       d_col_bounds.as<int32_t>(), gr, gc, ubits, vbits, row_seed ? d_row_shift.as<uint32_t>() : nullptr,
+                       keys[0].as<uint64_t>(), payload[0].as<uint32_t>());
     PD_HIP(hipGetLastError());
     timer.mark("allocations and keys", stream);
 
@@ -506,7 +538,9 @@ int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const f
     // ---- packed arrays
     hipLaunchKernelGGL(unpack_keys, dim3(streaming_groups(nnz)), dim3(kSortThreads), 0, stream,
                        keys[cur].as<uint64_t>(), payload[cur].as<uint32_t>(), nnz, d_row_bounds.as<int32_t>(),
-                       d_col_bounds.as<int32_t>(), gr, gc, ubits, vbits, d_vals, dU, dV, dR, d_perm);
+                       d_col_bounds.as<int32_t>(), gr, gc, ubits, vbits,
+                       row_seed ? d_row_shift.as<uint32_t>() : nullptr,
+                       row_seed ? d_row_inverse.as<uint32_t>() : nullptr, d_vals, dU, dV, dR, d_perm);
     PD_HIP(hipGetLastError());
     hipLaunchKernelGGL(block_starts, dim3(streaming_groups(nnz)), dim3(kSortThreads), 0, stream,
                        keys[cur].as<uint64_t>(), nnz, ubits + vbits, nblocks, block_count.as<uint32_t>());

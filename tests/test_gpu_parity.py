@@ -132,6 +132,39 @@ def test_device_partitioner_rejects_indices_outside_the_matrix_and_accepts_no_ra
     model.close()
 
 
+@pytest.mark.parametrize("grid,split", [((7, 9), 1), ((16, 16), 0), ((40, 333), 2), ((1, 1), 1)])
+def test_seeded_row_order_host_and_device_partitioners_match_the_oracle(mfmod, grid, split):
+    """MF_OPT_ROW_ORDER_SEED: both partitioners give the oracle's seeded permutation bit for bit, and
+    a deterministic epoch on it matches the oracle run on that permutation."""
+    ds = dataset("tiny")
+    cfg = ds.cfg
+    gr, gc = grid
+    seed = 987654321
+    want = oracle.partition(ds.rows, ds.cols, cfg.m, cfg.n, gr, gc, split, row_seed=seed)
+    plain = oracle.partition(ds.rows, ds.cols, cfg.m, cfg.n, gr, gc, split)
+    if gr * gc < cfg.m:
+        assert not np.array_equal(want[0], plain[0])
+    Po, Qo = oracle_init(cfg.m, cfg.n, 32, 1, 0.1)
+    oracle.sgd_epoch_omp(Po, Qo, ds.rows, ds.cols, ds.vals, want[0], want[1], gr, gc, cfg.lr, cfg.lam)
+    for path in ("host", "device"):
+        model = mfmod.MatrixFactorization(cfg.m, cfg.n, 32, "f32", seed=1, scale=0.1,
+                                          options={mfmod.MF_OPT_ROW_ORDER_SEED: seed})
+        if path == "host":
+            model.load_blocks(ds.rows, ds.cols, ds.vals, gr, gc, split)
+        else:
+            d = model.P.device
+            model.load_blocks_device(*(torch.from_numpy(x).to(d) for x in (ds.rows, ds.cols, ds.vals)), gr, gc, split)
+        for name, a, b in zip(("perm", "block_ptr", "row_bounds", "col_bounds"), model.partition(), want):
+            assert np.array_equal(a, b), (path, name)
+        model.sgd_epoch(cfg.lr, cfg.lam, mfmod.MF_MODE_DET)
+        P, Q = model.get_factors()
+        assert np.abs(P - Po).max() <= 1e-4 and np.abs(Q - Qo).max() <= 1e-4, path
+        for _ in range(3):
+            model.sgd_epoch(cfg.lr, cfg.lam, mfmod.MF_MODE_HOGWILD)       # the work lists follow the new order
+        assert np.isfinite(model.rmse())
+        model.close()
+
+
 # ------------------------------------------------------------------------------- RMSE kernel
 @pytest.mark.parametrize("storage,k", [("f32", 32), ("f32", 128), ("f16", 128), ("f32", 256), ("f16", 64)])
 def test_rmse_kernel_matches_oracle(mfmod, storage, k):
