@@ -132,6 +132,22 @@ int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const 
                    int64_t nnz, int32_t grid_r, int32_t grid_c, int32_t split,
                    void* d_workspace, size_t workspace_bytes);
 
+/* mf_load_blocks for rating matrices that should NOT be kept in device memory: the packed ratings stay
+ * in pinned host memory owned by the library (12 bytes per rating) and every epoch streams them to the
+ * device stratum by stratum -- a stratum is one contiguous piece of the packed order -- into two
+ * library-owned device buffers of the largest stratum's size, on a second stream of default priority,
+ * while the stratum before is being computed (the overlap of transfer and kernel that the paper's
+ * Section 5.3 describes for its GPU workers).  The workspace (query its size with
+ * mf_load_blocks_streamed_workspace) holds the work lists only.  Epochs run one launch per stratum;
+ * their results are those of mf_load_blocks with MF_OPT_RING = 0 (bit for bit in MF_MODE_DET).
+ * mf_rmse over the training ratings (NULL arrays) is not available in this mode (MF_ESTATE).
+ * rows, cols, vals: HOST pointers as for mf_load_blocks.  Errors as mf_load_blocks. */
+int mf_load_blocks_streamed_workspace(const mf_ctx* ctx, int64_t nnz, int32_t grid_r, int32_t grid_c,
+                                      size_t* bytes_out);
+int mf_load_blocks_streamed(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const float* vals,
+                            int64_t nnz, int32_t grid_r, int32_t grid_c, int32_t split, void* d_workspace,
+                            size_t workspace_bytes);
+
 /* mf_load_blocks for COO arrays that already live in device memory ("partition R" and
  * "preprocess data" of the paper's Algorithm 2, done on the GPU): the same partition, packed order
  * and work lists as mf_load_blocks, bit for bit, with the block ids, the sort and the gather

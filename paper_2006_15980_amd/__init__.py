@@ -60,6 +60,17 @@ class MatrixFactorization:
         self.nnz = rows.size
         self.grid = (grid_r, grid_c)
 
+    def load_blocks_streamed(self, rows, cols, vals, grid_r: int, grid_c: int, split: int = MF_SPLIT_NNZ_BALANCED):
+        """The ratings stay in pinned host memory and are streamed to the device every epoch."""
+        t = self.torch
+        nbytes = binding.mf_load_blocks_streamed_workspace(self.ctx, rows.size, grid_r, grid_c)
+        binding.mf_sync(self.ctx)
+        self.workspace = t.empty(nbytes + 256, dtype=t.uint8, device=self.dev)
+        base = (self.workspace.data_ptr() + 255) & ~255
+        binding.mf_load_blocks_streamed(self.ctx, rows, cols, vals, grid_r, grid_c, split, base, nbytes)
+        self.nnz = rows.size
+        self.grid = (grid_r, grid_c)
+
     def load_blocks_device(self, rows, cols, vals, grid_r: int, grid_c: int, split: int = MF_SPLIT_NNZ_BALANCED):
         """rows, cols (int32) and vals (float32): torch tensors on this model's device."""
         t = self.torch

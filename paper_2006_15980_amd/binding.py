@@ -28,7 +28,8 @@ MF_PLAN_HOGWILD_LDS = 2
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmf_sgd.so")
 
 EXPORTS = ["mf_create", "mf_destroy", "mf_last_error", "mf_set_option", "mf_init",
-           "mf_load_blocks_workspace", "mf_load_blocks", "mf_load_blocks_device", "mf_get_partition", "mf_sgd_epoch",
+           "mf_load_blocks_workspace", "mf_load_blocks", "mf_load_blocks_device",
+           "mf_load_blocks_streamed_workspace", "mf_load_blocks_streamed", "mf_get_partition", "mf_sgd_epoch",
            "mf_sgd_epoch_ordered", "mf_stratum_order",
            "mf_rmse", "mf_sync", "mf_profile_read", "mf_debug_xcc_ids", "mf_plan_host", "mf_suggest_grid"]
 
@@ -59,6 +60,8 @@ def lib() -> C.CDLL:
         l.mf_load_blocks_workspace.argtypes = [vp, i64, i32, i32, C.POINTER(C.c_size_t)]
         l.mf_load_blocks.argtypes = [vp, vp, vp, vp, i64, i32, i32, i32, vp, C.c_size_t]
         l.mf_load_blocks_device.argtypes = [vp, vp, vp, vp, i64, i32, i32, i32, vp, C.c_size_t]
+        l.mf_load_blocks_streamed_workspace.argtypes = [vp, i64, i32, i32, C.POINTER(C.c_size_t)]
+        l.mf_load_blocks_streamed.argtypes = [vp, vp, vp, vp, i64, i32, i32, i32, vp, C.c_size_t]
         l.mf_get_partition.argtypes = [vp, vp, vp, vp, vp]
         l.mf_sgd_epoch.argtypes = [vp, f32, f32, i32]
         l.mf_sgd_epoch_ordered.argtypes = [vp, f32, f32, i32, vp]
@@ -128,6 +131,22 @@ def mf_load_blocks(ctx: int, rows: np.ndarray, cols: np.ndarray, vals: np.ndarra
         raise ValueError("rows, cols and vals must have the same length")
     _check(ctx, lib().mf_load_blocks(ctx, _host(rows, np.int32), _host(cols, np.int32), _host(vals, np.float32),
                                      nnz, grid_r, grid_c, split, d_workspace, workspace_bytes))
+
+
+def mf_load_blocks_streamed_workspace(ctx: int, nnz: int, grid_r: int, grid_c: int) -> int:
+    out = C.c_size_t()
+    _check(ctx, lib().mf_load_blocks_streamed_workspace(ctx, nnz, grid_r, grid_c, C.byref(out)))
+    return out.value
+
+
+def mf_load_blocks_streamed(ctx: int, rows: np.ndarray, cols: np.ndarray, vals: np.ndarray, grid_r: int, grid_c: int,
+                            split: int, d_workspace: int, workspace_bytes: int) -> None:
+    nnz = rows.size
+    if cols.size != nnz or vals.size != nnz:
+        raise ValueError("rows, cols and vals must have the same length")
+    _check(ctx, lib().mf_load_blocks_streamed(ctx, _host(rows, np.int32), _host(cols, np.int32),
+                                              _host(vals, np.float32), nnz, grid_r, grid_c, split, d_workspace,
+                                              workspace_bytes))
 
 
 def mf_load_blocks_device(ctx: int, d_rows: int, d_cols: int, d_vals: int, nnz: int, grid_r: int, grid_c: int,

@@ -57,6 +57,17 @@ struct mf_ctx {
     // library-owned device buffer: RMSE partials followed by the final sum
     double* d_partials = nullptr;
 
+    // streamed mode (mf_load_blocks_streamed): the packed ratings stay in pinned host memory and
+    // travel stratum by stratum into two device buffers while the stratum before is computed
+    bool streamed = false;
+    char* h_packed = nullptr;             // pinned, library-owned: stratum after stratum, each as its row
+                                          // indices, then its column indices, then its values
+    char* d_stream_buf[2] = {nullptr, nullptr};   // library-owned, 12 bytes x the largest stratum each
+    int64_t stratum_cap = 0;                      // ratings one buffer holds
+    hipStream_t copy_stream = nullptr;            // default priority
+    hipEvent_t copied[2] = {nullptr, nullptr}, consumed[2] = {nullptr, nullptr};
+    bool consumed_recorded[2] = {false, false};
+
     // profiling events (start, stop) of the launches since the last mf_profile_read
     std::vector<std::pair<hipEvent_t, hipEvent_t>> events;
     size_t events_used = 0;
@@ -83,6 +94,19 @@ int fail_hip(mf_ctx* ctx, const char* what, hipError_t e)
 
 size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
+void release_streaming(mf_ctx* ctx)
+{
+    if (ctx->copy_stream) (void)hipStreamSynchronize(ctx->copy_stream);
+    for (int i = 0; i < 2; ++i) {
+        if (ctx->d_stream_buf[i]) (void)hipFree(ctx->d_stream_buf[i]);
+        ctx->d_stream_buf[i] = nullptr;
+        ctx->consumed_recorded[i] = false;
+    }
+    if (ctx->h_packed) (void)hipHostFree(ctx->h_packed);
+    ctx->h_packed = nullptr;
+    ctx->streamed = false;
+}
+
 bool valid_k(int32_t k) { return k == 32 || k == 64 || k == 128 || k == 256; }
 
 struct Layout {
@@ -91,18 +115,20 @@ struct Layout {
     int64_t cap[2], lds_cap, lds_blocks_cap;
 };
 
-Layout make_layout(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t lds_chunk, int32_t lds_waves)
+Layout make_layout(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t lds_chunk, int32_t lds_waves,
+                   bool resident = true)
 {
+    const size_t packed = resident ? (size_t)nnz * 4 : 0;   // streamed mode keeps the ratings on the host
     Layout l;
     l.cap[MF_MODE_DET] = mf::det_entries_bound(gr, gc);
     l.cap[MF_MODE_HOGWILD] = mf::hogwild_entries_bound(nnz, gr, gc, chunk, lds_waves);
     l.lds_cap = mf::lds_entries_bound(nnz, gr, gc, lds_chunk, lds_waves);
     l.lds_blocks_cap = (int64_t)gr * gc;
     size_t off = 0;
-    l.off_u = off; off += align_up((size_t)nnz * 4);
-    l.off_v = off; off += align_up((size_t)nnz * 4);
-    l.off_r = off; off += align_up((size_t)nnz * 4);
-    l.off_perm = off; off += align_up((size_t)nnz * 4);   // written by mf_load_blocks_device only
+    l.off_u = off; off += align_up(packed);
+    l.off_v = off; off += align_up(packed);
+    l.off_r = off; off += align_up(packed);
+    l.off_perm = off; off += align_up(packed);   // written by mf_load_blocks_device only
     for (int mode = 0; mode < 2; ++mode) {
         l.off_begin[mode] = off; off += align_up((size_t)l.cap[mode] * 8);
         l.off_len[mode] = off; off += align_up((size_t)l.cap[mode] * 4);
@@ -176,6 +202,12 @@ int mf_destroy(mf_ctx* ctx)
         (void)hipEventDestroy(ev.second);
     }
     if (ctx->d_partials) (void)hipFree(ctx->d_partials);
+    release_streaming(ctx);
+    for (int i = 0; i < 2; ++i) {
+        if (ctx->copied[i]) (void)hipEventDestroy(ctx->copied[i]);
+        if (ctx->consumed[i]) (void)hipEventDestroy(ctx->consumed[i]);
+    }
+    if (ctx->copy_stream) (void)hipStreamDestroy(ctx->copy_stream);
     delete ctx;
     return MF_OK;
 }
@@ -272,7 +304,8 @@ int mf_load_blocks_workspace(const mf_ctx* ctx, int64_t nnz, int32_t grid_r, int
 namespace {
 
 int check_load(mf_ctx* ctx, const void* rows, const void* cols, const void* vals, int64_t nnz, int32_t grid_r,
-               int32_t grid_c, int32_t split, void* d_workspace, size_t workspace_bytes, Layout& lay)
+               int32_t grid_c, int32_t split, void* d_workspace, size_t workspace_bytes, Layout& lay,
+               bool resident = true)
 {
     if (!ctx->inited) return fail(ctx, MF_ESTATE, "mf_load_blocks before mf_init");
     int rc = check_grid(ctx, nnz, grid_r, grid_c);
@@ -282,7 +315,7 @@ int check_load(mf_ctx* ctx, const void* rows, const void* cols, const void* vals
     if (nnz > 0 && (!rows || !cols || !vals)) return fail(ctx, MF_EINVAL, "null rating array");
     if (!d_workspace) return fail(ctx, MF_EINVAL, "null workspace");
     if ((uintptr_t)d_workspace & 255) return fail(ctx, MF_EINVAL, "workspace must be 256-byte aligned");
-    lay = make_layout(nnz, grid_r, grid_c, ctx->hogwild_chunk, ctx->lds_chunk, ctx->lds_waves);
+    lay = make_layout(nnz, grid_r, grid_c, ctx->hogwild_chunk, ctx->lds_chunk, ctx->lds_waves, resident);
     if (workspace_bytes < lay.total) return fail(ctx, MF_ENOMEM, "workspace too small");
     return MF_OK;
 }
@@ -349,6 +382,8 @@ int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const 
     if (rc) return rc;
     MF_HIP(ctx, hipSetDevice(ctx->device));
     ctx->loaded = false;
+    MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    release_streaming(ctx);
 
     std::vector<int32_t> pu, pv;
     std::vector<float> pr;
@@ -388,6 +423,8 @@ int mf_load_blocks_device(mf_ctx* ctx, const int32_t* d_rows, const int32_t* d_c
     if (rc) return rc;
     MF_HIP(ctx, hipSetDevice(ctx->device));
     ctx->loaded = false;
+    MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    release_streaming(ctx);
     char* base = (char*)d_workspace;
     ctx->dU = (int32_t*)(base + lay.off_u);
     ctx->dV = (int32_t*)(base + lay.off_v);
@@ -404,6 +441,71 @@ int mf_load_blocks_device(mf_ctx* ctx, const int32_t* d_rows, const int32_t* d_c
         return fail(ctx, MF_ENOMEM, "host allocation failed while partitioning");
     }
     return finish_load(ctx, lay, base, rs);
+}
+
+int mf_load_blocks_streamed_workspace(const mf_ctx* ctx, int64_t nnz, int32_t grid_r, int32_t grid_c,
+                                      size_t* bytes_out)
+{
+    if (!ctx || !bytes_out) return MF_EINVAL;
+    int rc = check_grid(const_cast<mf_ctx*>(ctx), nnz, grid_r, grid_c);
+    if (rc) return rc;
+    *bytes_out = make_layout(nnz, grid_r, grid_c, ctx->hogwild_chunk, ctx->lds_chunk, ctx->lds_waves, false).total;
+    return MF_OK;
+}
+
+int mf_load_blocks_streamed(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const float* vals,
+                            int64_t nnz, int32_t grid_r, int32_t grid_c, int32_t split, void* d_workspace,
+                            size_t workspace_bytes)
+{
+    if (!ctx) return MF_EINVAL;
+    Layout lay;
+    int rc = check_load(ctx, rows, cols, vals, nnz, grid_r, grid_c, split, d_workspace, workspace_bytes, lay, false);
+    if (rc) return rc;
+    MF_HIP(ctx, hipSetDevice(ctx->device));
+    ctx->loaded = false;
+    MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    release_streaming(ctx);
+
+    std::vector<int32_t> pu, pv;
+    std::vector<float> pr;
+    try {
+        std::string err;
+        rc = mf::build_partition(rows, cols, vals, nnz, ctx->m, ctx->n, grid_r, grid_c, split, ctx->row_seed, ctx->part,
+                                 pu, pv, pr, err);
+        if (rc) return fail(ctx, rc, err);
+    } catch (const std::bad_alloc&) {
+        return fail(ctx, MF_ENOMEM, "host allocation failed while partitioning");
+    }
+    // the packed arrays go to pinned host memory; the device gets two buffers of the largest stratum
+    int64_t largest = 1;
+    for (int32_t st = 0; st < grid_c; ++st)
+        largest = std::max(largest, ctx->part.block_ptr[(size_t)(st + 1) * grid_r] - ctx->part.block_ptr[(size_t)st * grid_r]);
+    MF_HIP(ctx, hipHostMalloc((void**)&ctx->h_packed, std::max<size_t>((size_t)nnz * 12, 256), hipHostMallocDefault));
+    for (int32_t st = 0; st < grid_c; ++st) {
+        // one transfer per stratum: its three arrays lie one after the other
+        const int64_t begin = ctx->part.block_ptr[(size_t)st * grid_r];
+        const int64_t size = ctx->part.block_ptr[(size_t)(st + 1) * grid_r] - begin;
+        char* dst = ctx->h_packed + (size_t)begin * 12;
+        std::memcpy(dst, pu.data() + begin, (size_t)size * 4);
+        std::memcpy(dst + (size_t)size * 4, pv.data() + begin, (size_t)size * 4);
+        std::memcpy(dst + (size_t)size * 8, pr.data() + begin, (size_t)size * 4);
+    }
+    ctx->stratum_cap = (largest + 63) & ~(int64_t)63;
+    for (int i = 0; i < 2; ++i) MF_HIP(ctx, hipMalloc((void**)&ctx->d_stream_buf[i], (size_t)ctx->stratum_cap * 12));
+    if (!ctx->copy_stream) {
+        MF_HIP(ctx, hipStreamCreateWithFlags(&ctx->copy_stream, hipStreamNonBlocking));
+        for (int i = 0; i < 2; ++i) {
+            MF_HIP(ctx, hipEventCreateWithFlags(&ctx->copied[i], hipEventDisableTiming));
+            MF_HIP(ctx, hipEventCreateWithFlags(&ctx->consumed[i], hipEventDisableTiming));
+        }
+    }
+    ctx->streamed = true;
+    ctx->dU = ctx->dV = nullptr;
+    ctx->dR = nullptr;
+    ctx->d_perm = nullptr;
+    mf::RowStarts rs;
+    mf::row_starts_from_rows(pu.data(), nnz, rs);
+    return finish_load(ctx, lay, (char*)d_workspace, rs);
 }
 
 int mf_get_partition(const mf_ctx* ctx, int64_t* perm, int64_t* block_ptr, int32_t* row_bounds,
@@ -482,7 +584,7 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
         if (!use_lds && choice == MF_KERNEL_LDS)
             return fail(ctx, MF_EINVAL, "the widest column strip of this grid does not fit the LDS");
     }
-    if (use_lds && ctx->use_ring && ctx->part.nnz > 0) {
+    if (use_lds && ctx->use_ring && ctx->part.nnz > 0 && !ctx->streamed) {
         // one launch for the whole epoch if every block row's workgroup can be resident at once
         const int m_idx = hog ? 1 : 0;
         if (ctx->ring_resident[m_idx] < 0) {
@@ -529,8 +631,44 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
             return MF_OK;
         }
     }
+    // Streamed mode: the ratings of a stratum are one contiguous piece of the packed arrays; it is
+    // copied from pinned host memory into one of two device buffers on a second stream while the
+    // stratum before it is computed (the overlap of transfer and kernel of the paper's Section 5.3).
+    const int32_t gr_ = ctx->part.gr;
+    auto stratum_range = [&](int32_t st, int64_t& begin, int64_t& size) {
+        begin = ctx->part.block_ptr[(size_t)st * gr_];
+        size = ctx->part.block_ptr[(size_t)(st + 1) * gr_] - begin;
+    };
+    auto enqueue_copy = [&](int32_t st, int buf) -> hipError_t {
+        int64_t begin, size;
+        stratum_range(st, begin, size);
+        hipError_t e = hipSuccess;
+        // the buffer's previous contents must have been used up by their kernel
+        if (ctx->consumed_recorded[buf]) e = hipStreamWaitEvent(ctx->copy_stream, ctx->consumed[buf], 0);
+        if (e == hipSuccess && size > 0)
+            e = hipMemcpyAsync(ctx->d_stream_buf[buf], ctx->h_packed + (size_t)begin * 12, (size_t)size * 12,
+                               hipMemcpyHostToDevice, ctx->copy_stream);
+        if (e == hipSuccess) e = hipEventRecord(ctx->copied[buf], ctx->copy_stream);
+        return e;
+    };
+    if (ctx->streamed && gc > 0) MF_HIP(ctx, enqueue_copy(stratum_order ? stratum_order[0] : 0, 0));
     for (int32_t step = 0; step < gc; ++step) {
         const int32_t st = stratum_order ? stratum_order[step] : step;
+        const int32_t* U = ctx->dU;
+        const int32_t* V = ctx->dV;
+        const float* R = ctx->dR;
+        const int buf = step & 1;
+        if (ctx->streamed) {
+            if (step + 1 < gc) MF_HIP(ctx, enqueue_copy(stratum_order ? stratum_order[step + 1] : step + 1, buf ^ 1));
+            MF_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->copied[buf], 0));
+            // the work lists hold positions in the packed order: shift the buffer's base so that
+            // position `begin` of the packed order is its first element
+            int64_t begin, size;
+            stratum_range(st, begin, size);
+            U = (const int32_t*)(ctx->d_stream_buf[buf]) - begin;
+            V = (const int32_t*)(ctx->d_stream_buf[buf] + (size_t)size * 4) - begin;
+            R = (const float*)(ctx->d_stream_buf[buf] + (size_t)size * 8) - begin;
+        }
         int64_t first, count;
         if (use_lds) {
             first = lsched.stratum_block[st];
@@ -539,9 +677,8 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
             first = s.stratum_entry[st];
             count = s.stratum_entry[st + 1] - first;
         }
-        if (count == 0) continue;
         hipEvent_t ev0 = nullptr, ev1 = nullptr;
-        if (ctx->profile) {
+        if (count > 0 && ctx->profile) {
             if (ctx->events_used == ctx->events.size()) {
                 MF_HIP(ctx, hipEventCreate(&ev0));
                 MF_HIP(ctx, hipEventCreate(&ev1));
@@ -552,16 +689,18 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
             ctx->events_used += 1;
             MF_HIP(ctx, hipEventRecord(ev0, ctx->stream));
         }
-        if (use_lds)
-            MF_HIP(ctx, mf::launch_sgd_lds(ctx->dtype, ctx->k, !hog, short_prefetch, ctx->lds_waves, ctx->dP, ctx->dQt, ctx->dU,
-                                           ctx->dV, ctx->dR, lsched.d_begin, lsched.d_len,
-                                           lsched.d_blocks + first, count, lds_bytes, lr, lambda,
-                                           ctx->stream));
-        else
-            MF_HIP(ctx, mf::launch_sgd(ctx->dtype, ctx->k, mode == MF_MODE_HOGWILD, ctx->dP, ctx->dQt, ctx->dU,
-                                       ctx->dV, ctx->dR, s.d_begin, s.d_len, first, count, lr, lambda,
-                                       ctx->stream));
-        if (ctx->profile) MF_HIP(ctx, hipEventRecord(ev1, ctx->stream));
+        if (count > 0 && use_lds)
+            MF_HIP(ctx, mf::launch_sgd_lds(ctx->dtype, ctx->k, !hog, short_prefetch, ctx->lds_waves, ctx->dP, ctx->dQt, U, V,
+                                           R, lsched.d_begin, lsched.d_len, lsched.d_blocks + first, count, lds_bytes,
+                                           lr, lambda, ctx->stream));
+        else if (count > 0)
+            MF_HIP(ctx, mf::launch_sgd(ctx->dtype, ctx->k, mode == MF_MODE_HOGWILD, ctx->dP, ctx->dQt, U, V, R,
+                                       s.d_begin, s.d_len, first, count, lr, lambda, ctx->stream));
+        if (count > 0 && ctx->profile) MF_HIP(ctx, hipEventRecord(ev1, ctx->stream));
+        if (ctx->streamed) {
+            MF_HIP(ctx, hipEventRecord(ctx->consumed[buf], ctx->stream));
+            ctx->consumed_recorded[buf] = true;
+        }
     }
     return MF_OK;
 }
@@ -573,6 +712,7 @@ int mf_rmse(mf_ctx* ctx, const int32_t* d_rows, const int32_t* d_cols, const flo
     if (!ctx->inited) return fail(ctx, MF_ESTATE, "mf_rmse before mf_init");
     if (!d_rows) {
         if (!ctx->loaded) return fail(ctx, MF_ESTATE, "no training ratings loaded");
+        if (ctx->streamed) return fail(ctx, MF_ESTATE, "the training ratings are not resident on the device (streamed mode)");
         d_rows = ctx->dU;
         d_cols = ctx->dV;
         d_vals = ctx->dR;

@@ -398,6 +398,59 @@ def test_suggested_grids_train_to_the_oracle_result(mfmod):
         assert abs(got - want) <= tol, (mode, gr, gc, got, want)
 
 
+# ------------------------------------------------------------------------------- ratings streamed from the host
+@pytest.mark.parametrize("kernel", ["lds", "global"])
+@pytest.mark.parametrize("grid", [(5, 7), (16, 16), (1, 1)])
+def test_streamed_ratings_deterministic_mode_is_bit_identical_to_resident(mfmod, grid, kernel):
+    """mf_load_blocks_streamed keeps the ratings in pinned host memory and copies every stratum in
+    while the one before is computed: over several epochs (the two device buffers are reused) and
+    with a shuffled stratum order the deterministic result must equal the resident path's bits."""
+    ds = dataset("tiny")
+    cfg = ds.cfg
+    gr, gc = grid
+    opts = dict(_det_options(mfmod, kernel))
+    opts[mfmod.MF_OPT_RING] = 0
+    outs = []
+    for streamed in (False, True):
+        model = mfmod.MatrixFactorization(cfg.m, cfg.n, 32, "f32", seed=1, scale=0.1, options=opts)
+        (model.load_blocks_streamed if streamed else model.load_blocks)(ds.rows, ds.cols, ds.vals, gr, gc, 1)
+        for e in range(3):
+            model.sgd_epoch(cfg.lr, cfg.lam, mfmod.MF_MODE_DET)
+        model.sgd_epoch(cfg.lr, cfg.lam, mfmod.MF_MODE_DET, stratum_order=oracle.stratum_order(5, 0, gc))
+        outs.append(model.get_factors())
+        if streamed:
+            with pytest.raises(mfmod.MFError):
+                model.rmse()                      # the training ratings are not on the device
+            model.load_blocks(ds.rows, ds.cols, ds.vals, gr, gc, 1)       # back to the resident path
+            assert np.isfinite(model.rmse())
+        model.close()
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+    perm, bp, _, _ = oracle.partition(ds.rows, ds.cols, cfg.m, cfg.n, gr, gc, 1)
+    Po, Qo = oracle_init(cfg.m, cfg.n, 32, 1, 0.1)
+    for e in range(3):
+        oracle.sgd_epoch_omp(Po, Qo, ds.rows, ds.cols, ds.vals, perm, bp, gr, gc, cfg.lr, cfg.lam)
+    oracle.sgd_epoch_ordered(Po, Qo, ds.rows, ds.cols, ds.vals, perm, bp, gr, gc, cfg.lr, cfg.lam, oracle.stratum_order(5, 0, gc))
+    assert np.abs(outs[1][0] - Po).max() <= 1e-4 and np.abs(outs[1][1] - Qo).max() <= 1e-4
+
+
+def test_streamed_ratings_hogwild_final_rmse(mfmod):
+    ds = dataset("medium", 0.05)
+    cfg = ds.cfg
+    gr = gc = 48
+    epochs = 6
+    Po, Qo, _ = oracle_train(ds, gr, gc, 1, epochs)
+    want = oracle.rmse(Po, Qo, ds.test_rows, ds.test_cols, ds.test_vals)
+    model = mfmod.MatrixFactorization(cfg.m, cfg.n, cfg.k, "f32", seed=1, scale=0.1,
+                                      options={mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS})
+    model.load_blocks_streamed(ds.rows, ds.cols, ds.vals, gr, gc, 1)
+    tr, tc, tv = model.to_device(ds.test_rows, ds.test_cols, ds.test_vals)
+    for _ in range(epochs):
+        model.sgd_epoch(cfg.lr, cfg.lam, mfmod.MF_MODE_HOGWILD)
+    got = model.rmse(tr, tc, tv)
+    model.close()
+    assert abs(got - want) <= 5e-3 * want, (got, want)
+
+
 def test_det_edge_cases(mfmod):
     rng = np.random.default_rng(3)
     # duplicates of one (u, v), a single long row, a single long column, and empty strata
