@@ -207,6 +207,9 @@ def main():
                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": ("sgd_ring_lds<float,128>" if args.ring else "sgd_block_lds<float,128>") if (args.mode == "hogwild" and args.hogwild_kernel != "global_atomics") else "sgd_chunks<float,128>",
                     "avg_launch_us": avg_s * 1e6, "launches_per_step": launches / args.steps,
                     "bytes_per_update": bytes_per_update,
+                    # what the memory side really moved per second (counters), next to the algorithmic figure:
+                    # the strip of Qt lives in LDS and P mostly in the L2s, so it is far below `achieved`
+                    "traffic_gbs": None if traffic is None else traffic / avg_s / 1e9,
                     "ms_per_step_with_event_brackets": elapsed_events * 1e3 / args.steps}
     out = {"metric": "SGD updates/s at k=128 (HOGWILD epoch + held-out RMSE per step)", "value": value,
            "unit": "updates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
