@@ -134,9 +134,9 @@ int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const 
 
 /* mf_load_blocks for rating matrices that should NOT be kept in device memory: the packed ratings stay
  * in pinned host memory owned by the library (12 bytes per rating) and every epoch streams them to the
- * device stratum by stratum -- a stratum is one contiguous piece of the packed order -- into two
- * library-owned device buffers of the largest stratum's size, on a second stream of default priority,
- * while the stratum before is being computed (the overlap of transfer and kernel that the paper's
+ * device stratum by stratum -- a stratum is one contiguous piece of the packed order; small strata
+ * travel several at a time, about 4 MiB per transfer -- into two library-owned device buffers, on a
+ * second stream of default priority, while the strata before are being computed (the overlap of transfer and kernel that the paper's
  * Section 5.3 describes for its GPU workers).  The workspace (query its size with
  * mf_load_blocks_streamed_workspace) holds the work lists only.  Epochs run one launch per stratum;
  * their results are those of mf_load_blocks with MF_OPT_RING = 0 (bit for bit in MF_MODE_DET).

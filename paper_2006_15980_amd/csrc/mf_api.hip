@@ -64,6 +64,7 @@ struct mf_ctx {
                                           // indices, then its column indices, then its values
     char* d_stream_buf[2] = {nullptr, nullptr};   // library-owned, 12 bytes x the largest stratum each
     int64_t stratum_cap = 0;                      // ratings one buffer holds
+    int32_t stream_group = 1;                     // strata per transfer
     hipStream_t copy_stream = nullptr;            // default priority
     hipEvent_t copied[2] = {nullptr, nullptr}, consumed[2] = {nullptr, nullptr};
     bool consumed_recorded[2] = {false, false};
@@ -490,7 +491,10 @@ int mf_load_blocks_streamed(mf_ctx* ctx, const int32_t* rows, const int32_t* col
         std::memcpy(dst + (size_t)size * 4, pv.data() + begin, (size_t)size * 4);
         std::memcpy(dst + (size_t)size * 8, pr.data() + begin, (size_t)size * 4);
     }
-    ctx->stratum_cap = (largest + 63) & ~(int64_t)63;
+    // strata per transfer: enough for about 4 MiB; a buffer holds that many of the largest stratum
+    const int64_t average = std::max<int64_t>(1, nnz / grid_c);
+    ctx->stream_group = (int32_t)std::max<int64_t>(1, std::min<int64_t>(grid_c, ((int64_t)(4 << 20) / 12 + average - 1) / average));
+    ctx->stratum_cap = ((largest * ctx->stream_group) + 63) & ~(int64_t)63;
     for (int i = 0; i < 2; ++i) MF_HIP(ctx, hipMalloc((void**)&ctx->d_stream_buf[i], (size_t)ctx->stratum_cap * 12));
     if (!ctx->copy_stream) {
         MF_HIP(ctx, hipStreamCreateWithFlags(&ctx->copy_stream, hipStreamNonBlocking));
@@ -631,43 +635,69 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
             return MF_OK;
         }
     }
-    // Streamed mode: the ratings of a stratum are one contiguous piece of the packed arrays; it is
-    // copied from pinned host memory into one of two device buffers on a second stream while the
-    // stratum before it is computed (the overlap of transfer and kernel of the paper's Section 5.3).
+    // Streamed mode: the ratings of a stratum are one contiguous piece of the packed arrays.  The
+    // strata of `group` consecutive steps are copied from pinned host memory into one of two device
+    // buffers on a second stream while the group before is computed (the overlap of transfer and
+    // kernel of the paper's Section 5.3); groups keep a transfer above a few MiB, below which the
+    // hand-off between the two streams costs more than the transfer.
     const int32_t gr_ = ctx->part.gr;
+    const int32_t group = ctx->streamed ? ctx->stream_group : 1;
     auto stratum_range = [&](int32_t st, int64_t& begin, int64_t& size) {
         begin = ctx->part.block_ptr[(size_t)st * gr_];
         size = ctx->part.block_ptr[(size_t)(st + 1) * gr_] - begin;
     };
-    auto enqueue_copy = [&](int32_t st, int buf) -> hipError_t {
-        int64_t begin, size;
-        stratum_range(st, begin, size);
+    auto stratum_of = [&](int32_t step) { return stratum_order ? stratum_order[step] : step; };
+    auto enqueue_copy = [&](int32_t first_step, int buf) -> hipError_t {
         hipError_t e = hipSuccess;
-        // the buffer's previous contents must have been used up by their kernel
+        // the buffer's previous contents must have been used up by their kernels
         if (ctx->consumed_recorded[buf]) e = hipStreamWaitEvent(ctx->copy_stream, ctx->consumed[buf], 0);
-        if (e == hipSuccess && size > 0)
-            e = hipMemcpyAsync(ctx->d_stream_buf[buf], ctx->h_packed + (size_t)begin * 12, (size_t)size * 12,
-                               hipMemcpyHostToDevice, ctx->copy_stream);
+        const int32_t last_step = std::min(gc, first_step + group);
+        if (!stratum_order) {
+            // natural order: the strata of the group are one piece of the host array
+            int64_t begin, size, end_begin, end_size;
+            stratum_range(first_step, begin, size);
+            stratum_range(last_step - 1, end_begin, end_size);
+            const int64_t total = end_begin + end_size - begin;
+            if (e == hipSuccess && total > 0)
+                e = hipMemcpyAsync(ctx->d_stream_buf[buf], ctx->h_packed + (size_t)begin * 12, (size_t)total * 12,
+                                   hipMemcpyHostToDevice, ctx->copy_stream);
+        } else {
+            int64_t offset = 0;
+            for (int32_t step = first_step; step < last_step && e == hipSuccess; ++step) {
+                int64_t begin, size;
+                stratum_range(stratum_of(step), begin, size);
+                if (size > 0)
+                    e = hipMemcpyAsync(ctx->d_stream_buf[buf] + (size_t)offset * 12, ctx->h_packed + (size_t)begin * 12,
+                                       (size_t)size * 12, hipMemcpyHostToDevice, ctx->copy_stream);
+                offset += size;
+            }
+        }
         if (e == hipSuccess) e = hipEventRecord(ctx->copied[buf], ctx->copy_stream);
         return e;
     };
-    if (ctx->streamed && gc > 0) MF_HIP(ctx, enqueue_copy(stratum_order ? stratum_order[0] : 0, 0));
+    if (ctx->streamed && gc > 0) MF_HIP(ctx, enqueue_copy(0, 0));
+    int64_t offset_in_buffer = 0;        // ratings of the group's earlier strata
     for (int32_t step = 0; step < gc; ++step) {
-        const int32_t st = stratum_order ? stratum_order[step] : step;
+        const int32_t st = stratum_of(step);
         const int32_t* U = ctx->dU;
         const int32_t* V = ctx->dV;
         const float* R = ctx->dR;
-        const int buf = step & 1;
+        const int buf = (step / group) & 1;
         if (ctx->streamed) {
-            if (step + 1 < gc) MF_HIP(ctx, enqueue_copy(stratum_order ? stratum_order[step + 1] : step + 1, buf ^ 1));
-            MF_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->copied[buf], 0));
-            // the work lists hold positions in the packed order: shift the buffer's base so that
-            // position `begin` of the packed order is its first element
+            if (step % group == 0) {
+                if (step + group < gc) MF_HIP(ctx, enqueue_copy(step + group, buf ^ 1));
+                MF_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->copied[buf], 0));
+                offset_in_buffer = 0;
+            }
+            // the work lists hold positions in the packed order: shift the base so that position
+            // `begin` of the packed order is the first element of this stratum's piece
             int64_t begin, size;
             stratum_range(st, begin, size);
-            U = (const int32_t*)(ctx->d_stream_buf[buf]) - begin;
-            V = (const int32_t*)(ctx->d_stream_buf[buf] + (size_t)size * 4) - begin;
-            R = (const float*)(ctx->d_stream_buf[buf] + (size_t)size * 8) - begin;
+            const char* piece = ctx->d_stream_buf[buf] + (size_t)offset_in_buffer * 12;
+            U = (const int32_t*)piece - begin;
+            V = (const int32_t*)(piece + (size_t)size * 4) - begin;
+            R = (const float*)(piece + (size_t)size * 8) - begin;
+            offset_in_buffer += size;
         }
         int64_t first, count;
         if (use_lds) {
@@ -697,7 +727,7 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
             MF_HIP(ctx, mf::launch_sgd(ctx->dtype, ctx->k, mode == MF_MODE_HOGWILD, ctx->dP, ctx->dQt, U, V, R,
                                        s.d_begin, s.d_len, first, count, lr, lambda, ctx->stream));
         if (count > 0 && ctx->profile) MF_HIP(ctx, hipEventRecord(ev1, ctx->stream));
-        if (ctx->streamed) {
+        if (ctx->streamed && ((step + 1) % group == 0 || step + 1 == gc)) {
             MF_HIP(ctx, hipEventRecord(ctx->consumed[buf], ctx->stream));
             ctx->consumed_recorded[buf] = true;
         }
