@@ -149,6 +149,25 @@ Layout make_layout(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t l
     return l;
 }
 
+// MF_OPT_PROFILE: an event before a launch (begin_launch_timing) and one after it (its return
+// value, to be recorded by the caller); the pairs are read by mf_profile_read.
+hipError_t begin_launch_timing(mf_ctx* ctx, hipEvent_t* after)
+{
+    *after = nullptr;
+    if (!ctx->profile) return hipSuccess;
+    if (ctx->events_used == ctx->events.size()) {
+        hipEvent_t ev0 = nullptr, ev1 = nullptr;
+        hipError_t e = hipEventCreate(&ev0);
+        if (e == hipSuccess) e = hipEventCreate(&ev1);
+        if (e != hipSuccess) return e;
+        ctx->events.push_back({ev0, ev1});
+    }
+    *after = ctx->events[ctx->events_used].second;
+    const hipEvent_t before = ctx->events[ctx->events_used].first;
+    ctx->events_used += 1;
+    return hipEventRecord(before, ctx->stream);
+}
+
 // After a synchronisation: did a workgroup of the ring kernel give up waiting?
 int check_ring_abort(mf_ctx* ctx)
 {
@@ -612,25 +631,15 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
                 MF_HIP(ctx, hipMemcpy(ctx->d_order, stratum_order, (size_t)gc * 4, hipMemcpyHostToDevice));
                 MF_HIP(ctx, hipMemcpy(ctx->d_order + gc, inverse.data(), (size_t)gc * 4, hipMemcpyHostToDevice));
             }
-            hipEvent_t ev0 = nullptr, ev1 = nullptr;
-            if (ctx->profile) {
-                if (ctx->events_used == ctx->events.size()) {
-                    MF_HIP(ctx, hipEventCreate(&ev0));
-                    MF_HIP(ctx, hipEventCreate(&ev1));
-                    ctx->events.push_back({ev0, ev1});
-                }
-                ev0 = ctx->events[ctx->events_used].first;
-                ev1 = ctx->events[ctx->events_used].second;
-                ctx->events_used += 1;
-                MF_HIP(ctx, hipEventRecord(ev0, ctx->stream));
-            }
+            hipEvent_t ev1 = nullptr;
+            MF_HIP(ctx, begin_launch_timing(ctx, &ev1));
             MF_HIP(ctx, mf::launch_sgd_ring(ctx->dtype, ctx->k, !hog, short_prefetch, ctx->lds_waves, false, nullptr, ctx->dP, ctx->dQt,
                                             ctx->dU, ctx->dV, ctx->dR, lsched.d_begin, lsched.d_len, lsched.d_ring,
                                             ctx->part.gr, ctx->part.gc, lds_bytes, lr, lambda, ctx->d_ring_done,
                                             ctx->ring_epochs * ctx->part.gc, ctx->d_ring_done + ctx->part.gr,
                                             (long long)ctx->spin_limit, stratum_order ? ctx->d_order : nullptr,
                                             stratum_order ? ctx->d_order + gc : nullptr, ctx->stream));
-            if (ctx->profile) MF_HIP(ctx, hipEventRecord(ev1, ctx->stream));
+            if (ev1) MF_HIP(ctx, hipEventRecord(ev1, ctx->stream));
             ctx->ring_epochs += 1;
             return MF_OK;
         }
@@ -707,18 +716,8 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
             first = s.stratum_entry[st];
             count = s.stratum_entry[st + 1] - first;
         }
-        hipEvent_t ev0 = nullptr, ev1 = nullptr;
-        if (count > 0 && ctx->profile) {
-            if (ctx->events_used == ctx->events.size()) {
-                MF_HIP(ctx, hipEventCreate(&ev0));
-                MF_HIP(ctx, hipEventCreate(&ev1));
-                ctx->events.push_back({ev0, ev1});
-            }
-            ev0 = ctx->events[ctx->events_used].first;
-            ev1 = ctx->events[ctx->events_used].second;
-            ctx->events_used += 1;
-            MF_HIP(ctx, hipEventRecord(ev0, ctx->stream));
-        }
+        hipEvent_t ev1 = nullptr;
+        if (count > 0) MF_HIP(ctx, begin_launch_timing(ctx, &ev1));
         if (count > 0 && use_lds)
             MF_HIP(ctx, mf::launch_sgd_lds(ctx->dtype, ctx->k, !hog, short_prefetch, ctx->lds_waves, ctx->dP, ctx->dQt, U, V,
                                            R, lsched.d_begin, lsched.d_len, lsched.d_blocks + first, count, lds_bytes,
@@ -726,7 +725,7 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
         else if (count > 0)
             MF_HIP(ctx, mf::launch_sgd(ctx->dtype, ctx->k, mode == MF_MODE_HOGWILD, ctx->dP, ctx->dQt, U, V, R,
                                        s.d_begin, s.d_len, first, count, lr, lambda, ctx->stream));
-        if (count > 0 && ctx->profile) MF_HIP(ctx, hipEventRecord(ev1, ctx->stream));
+        if (ev1) MF_HIP(ctx, hipEventRecord(ev1, ctx->stream));
         if (ctx->streamed && ((step + 1) % group == 0 || step + 1 == gc)) {
             MF_HIP(ctx, hipEventRecord(ctx->consumed[buf], ctx->stream));
             ctx->consumed_recorded[buf] = true;
