@@ -13,8 +13,11 @@
  *     MF_OK or a negative MF_E* code; mf_last_error() gives a message for the last failure.
  *   - "host" / "device" is stated for every pointer.  Device pointers are plain HIP device
  *     addresses (for instance torch tensors' data_ptr()).  The caller owns every buffer it
- *     passes; the library owns its context, its host-side metadata and one small device
- *     buffer for reduction partials (allocated in mf_create, freed in mf_destroy).
+ *     passes; the library owns its context, its host-side metadata, one small device buffer
+ *     for reduction partials (allocated in mf_create, freed in mf_destroy), the temporary device
+ *     memory of mf_load_blocks_device (freed before it returns) and, in streamed mode only, the
+ *     pinned host copy of the ratings and two device buffers (freed by the next load or by
+ *     mf_destroy).
  *   - Indices are 0-based.  Q is held transposed: Qt is n x k row-major and Qt[v] is the
  *     paper's column q_v.  P is m x k row-major.
  *   - A context is not thread-safe.  All device work is enqueued on the stream given to
@@ -136,9 +139,9 @@ int mf_load_blocks(mf_ctx* ctx, const int32_t* rows, const int32_t* cols, const 
  * in pinned host memory owned by the library (12 bytes per rating) and every epoch streams them to the
  * device stratum by stratum -- a stratum is one contiguous piece of the packed order; small strata
  * travel several at a time, about 4 MiB per transfer -- into two library-owned device buffers, on a
- * second stream of default priority, while the strata before are being computed (the overlap of transfer and kernel that the paper's
- * Section 5.3 describes for its GPU workers).  The workspace (query its size with
- * mf_load_blocks_streamed_workspace) holds the work lists only.  Epochs run one launch per stratum;
+ * second stream of default priority, while the strata before are being computed (the overlap of
+ * transfer and kernel that the paper's Section 5.3 describes for its GPU workers).  The workspace
+ * (query its size with mf_load_blocks_streamed_workspace) holds the work lists only.  Epochs run one launch per stratum;
  * their results are those of mf_load_blocks with MF_OPT_RING = 0 (bit for bit in MF_MODE_DET).
  * mf_rmse over the training ratings (NULL arrays) is not available in this mode (MF_ESTATE).
  * rows, cols, vals: HOST pointers as for mf_load_blocks.  Errors as mf_load_blocks. */
@@ -168,7 +171,8 @@ int mf_get_partition(const mf_ctx* ctx, int64_t* perm, int64_t* block_ptr,
                      int32_t* row_bounds, int32_t* col_bounds);
 
 /* One epoch of Algorithm 1's training phase: every loaded rating exactly once, stratum after
- * stratum (one kernel launch per stratum on the context's stream).  Returns after enqueueing.
+ * stratum, on the context's stream (one kernel launch per stratum, or one per epoch, see
+ * MF_OPT_RING below).  Returns after enqueueing.
  *   MF_MODE_DET     : one wavefront per block, ratings in stored order.  The result is the same
  *                     on every run and equals the sequential order (strata ascending, blocks
  *                     ascending, stored order) up to fp32 rounding.  Two kernels with identical
@@ -178,14 +182,21 @@ int mf_get_partition(const mf_ctx* ctx, int64_t* perm, int64_t* block_ptr,
  *   MF_MODE_HOGWILD : every block is cut into chunks of whole rows that many wavefronts process
  *                     concurrently without locks (lock-free updates in the sense of Hogwild,
  *                     Section 3.1).  A wavefront owns the rows of P of its chunk; rows of Qt are
- *                     shared: each wavefront ADDS its change of q_v with a floating-point atomic,
+ *                     shared: each wavefront ADDS its change of q_v with an atomic operation,
  *                     computed from a value that other wavefronts may have changed meanwhile, so
  *                     no update is lost but the result varies from run to run.  Two kernels:
  *                       MF_HOGWILD_LDS            one workgroup per block keeps the block's strip
- *                                                 of Qt in LDS (fp32) and uses LDS atomics; needs
- *                                                 (widest column strip) * k * 4 bytes <= 159 KiB;
+ *                                                 of Qt in LDS as 32-bit fixed point with 24
+ *                                                 fraction bits and changes it with integer LDS
+ *                                                 atomics (floating-point ones are some twenty
+ *                                                 times slower on this chip).  While this kernel
+ *                                                 is used the values of Qt are multiples of 2^-24
+ *                                                 (the fp32 spacing in [0.5, 1)) and saturate at
+ *                                                 +-128.  Needs (widest column strip) * k * 4
+ *                                                 bytes <= 159 KiB of LDS;
  *                       MF_HOGWILD_GLOBAL_ATOMICS wavefronts of a whole die share a block and use
- *                                                 atomics in that die's L2 (any grid, slower).
+ *                                                 floating-point atomics in that die's L2 (any
+ *                                                 grid, slower).
  *                     MF_HOGWILD_AUTO takes the LDS kernel whenever the grid allows it.
  * With the LDS kernels and MF_OPT_RING = 1 the epoch is a single launch: workgroup a keeps block
  * row a, walks the strata in order and waits (bounded) for the workgroup that used its next column
