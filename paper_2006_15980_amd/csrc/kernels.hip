@@ -1,16 +1,23 @@
 // Device code of libmf_sgd for gfx950 (CDNA4, 64-wide wavefronts).
 //
-// sgd_chunks   : the training step of the paper's Algorithm 1 -- e = r - p.q, then
-//                p += lr*(e*q - lambda*p), q += lr*(e*p - lambda*q) with the old p on the right --
-//                one wavefront per work-list entry, one rating at a time, the k factors of a
-//                row spread over the lanes, the dot product reduced with DPP cross-lane adds.
-// rmse_partial : sum of squared prediction errors (Eq. 1 against the rating), double precision.
-// init_fill    : counter-based uniform initial factors.
+// All SGD kernels run the training step of the paper's Algorithm 1 -- e = r - p.q, then
+// p += lr*(e*q - lambda*p), q += lr*(e*p - lambda*q) with the old p on the right -- one rating at
+// a time per wavefront, the k factors of a row spread over the lanes, the dot product reduced with
+// DPP cross-lane adds.
+//   sgd_chunks    : one wavefront per work-list entry, rows of P and Qt in global memory
+//                   (deterministic mode on any grid; Hogwild fallback with L2 atomics).
+//   sgd_block_lds : one workgroup per block of a stratum; the block's strip of Qt lives in LDS
+//                   (fp32 for the deterministic mode, 32-bit fixed point + integer atomics for
+//                   Hogwild), rows of P stream through registers.
+//   sgd_ring_lds  : the same block body, one launch per epoch: workgroup a keeps block row a and
+//                   the column strips are handed from workgroup to workgroup with bounded waits.
+//   rmse_partial / rmse_final : sum of squared prediction errors (Eq. 1 against the rating),
+//                   double precision, fixed reduction order.
+//   init_fill     : counter-based uniform initial factors.
 //
-// This is a gather / dot / scatter over rows of 128..1024 bytes: it is bound by memory traffic
-// and latency, so there is no MFMA here; the lanes hold rows in registers, consecutive ratings
-// of one matrix row reuse p_u from registers, and the next rating's rows are requested before
-// the current rating is computed.
+// This is a gather / dot / scatter over rows of 128..1024 bytes with about half a flop per byte:
+// there is no MFMA here; the lanes hold rows in registers, consecutive ratings of one matrix row
+// reuse p_u from registers, and the rows of later ratings are requested ahead of their use.
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
