@@ -50,7 +50,9 @@ struct mf_ctx {
     int32_t* d_order = nullptr;           // 2 * grid_c numbers inside the workspace: order, inverse
     int32_t* d_ring_done = nullptr;       // grid_r counters + 1 abort flag, inside the workspace
     int32_t lds_chunk = 0;   // 0 = one chunk per wavefront
-    int32_t lds_waves = 16;
+    int32_t lds_waves = 16;    // option value (upper bound of the workspace estimates)
+    bool lds_waves_set = false;  // the caller chose it
+    int32_t lds_waves_used = 16; // what the loaded LDS work list was built for
     int32_t lds_prefetch = 0;  // 0 = by the size of P, else 4 or 8
     uint64_t row_seed = 0;     // 0 = rows of a block in ascending order
 
@@ -270,6 +272,7 @@ int mf_set_option(mf_ctx* ctx, int32_t option, int64_t value)
         case MF_OPT_LDS_WAVES:
             if (value < 1 || value > 16) return fail(ctx, MF_EINVAL, "wavefronts per workgroup must be in [1, 16]");
             ctx->lds_waves = (int32_t)value;
+            ctx->lds_waves_set = true;
             return MF_OK;
         case MF_OPT_ROW_ORDER_SEED:
             if (value < 0) return fail(ctx, MF_EINVAL, "the seed must not be negative");
@@ -349,6 +352,21 @@ int finish_load(mf_ctx* ctx, const Layout& lay, char* base, const mf::RowStarts&
         mf::build_hogwild_schedule(ctx->part, rs, ctx->hogwild_chunk, ctx->lds_waves, ctx->xcd_affinity != 0,
                                    ctx->sched[MF_MODE_HOGWILD]);
         mf::build_lds_schedule(ctx->part, rs, ctx->lds_chunk, ctx->lds_waves, ctx->lds);
+        ctx->lds_waves_used = ctx->lds_waves;
+        if (!ctx->lds_waves_set && ctx->lds_chunk == 0 && ctx->part.nnz > 0) {
+            // Rows that are long compared with a block's share per wavefront get cut into pieces,
+            // and pieces of one row fall back to per-rating atomics on p_u.  If more than 1/32 of the
+            // ratings sit in such pieces, half as many wavefronts (twice the share each) are faster
+            // (measured on the Yahoo!Music-shaped configuration, 5.3 % in pieces: 2.33 against 1.80 G
+            // updates/s; the MovieLens-shaped one has 1.1 % in pieces and keeps its wavefronts).
+            int64_t in_pieces = 0;
+            for (int32_t len : ctx->lds.len)
+                if (len < 0) in_pieces += len & 0x7fffffff;
+            if (in_pieces * 32 > ctx->part.nnz) {
+                ctx->lds_waves_used = std::max(1, ctx->lds_waves / 2);
+                mf::build_lds_schedule(ctx->part, rs, ctx->lds_chunk, ctx->lds_waves_used, ctx->lds);
+            }
+        }
         mf::build_det_lds_schedule(ctx->part, ctx->det_lds);
     } catch (const std::bad_alloc&) {
         return fail(ctx, MF_ENOMEM, "host allocation failed while building the work lists");
@@ -612,7 +630,7 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
         const int m_idx = hog ? 1 : 0;
         if (ctx->ring_resident[m_idx] < 0) {
             int resident = 0;
-            MF_HIP(ctx, mf::launch_sgd_ring(ctx->dtype, ctx->k, !hog, short_prefetch, ctx->lds_waves, true, &resident, nullptr, nullptr,
+            MF_HIP(ctx, mf::launch_sgd_ring(ctx->dtype, ctx->k, !hog, short_prefetch, ctx->lds_waves_used, true, &resident, nullptr, nullptr,
                                             nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, ctx->part.gr,
                                             ctx->part.gc, lds_bytes, 0.f, 0.f, nullptr, 0, nullptr, 0, nullptr, nullptr,
                                             ctx->stream));
@@ -633,7 +651,7 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
             }
             hipEvent_t ev1 = nullptr;
             MF_HIP(ctx, begin_launch_timing(ctx, &ev1));
-            MF_HIP(ctx, mf::launch_sgd_ring(ctx->dtype, ctx->k, !hog, short_prefetch, ctx->lds_waves, false, nullptr, ctx->dP, ctx->dQt,
+            MF_HIP(ctx, mf::launch_sgd_ring(ctx->dtype, ctx->k, !hog, short_prefetch, ctx->lds_waves_used, false, nullptr, ctx->dP, ctx->dQt,
                                             ctx->dU, ctx->dV, ctx->dR, lsched.d_begin, lsched.d_len, lsched.d_ring,
                                             ctx->part.gr, ctx->part.gc, lds_bytes, lr, lambda, ctx->d_ring_done,
                                             ctx->ring_epochs * ctx->part.gc, ctx->d_ring_done + ctx->part.gr,
@@ -719,7 +737,7 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
         hipEvent_t ev1 = nullptr;
         if (count > 0) MF_HIP(ctx, begin_launch_timing(ctx, &ev1));
         if (count > 0 && use_lds)
-            MF_HIP(ctx, mf::launch_sgd_lds(ctx->dtype, ctx->k, !hog, short_prefetch, ctx->lds_waves, ctx->dP, ctx->dQt, U, V,
+            MF_HIP(ctx, mf::launch_sgd_lds(ctx->dtype, ctx->k, !hog, short_prefetch, ctx->lds_waves_used, ctx->dP, ctx->dQt, U, V,
                                            R, lsched.d_begin, lsched.d_len, lsched.d_blocks + first, count, lds_bytes,
                                            lr, lambda, ctx->stream));
         else if (count > 0)
