@@ -798,11 +798,7 @@ def test_other_configs_full_size(mfmod, name):
 # tests/golden/make_full_size_expected.py (which calls only the oracle and the input generators):
 # the held-out RMSE after every epoch and, after the first epoch, whole rows of P and Qt at
 # sampled indices.
-STORED = {
-    # name: Hogwild options at that size
-    "xlarge": {"lds_waves": 8},
-    "stress": {"lds_waves": 16},
-}
+STORED = ("xlarge", "stress")
 
 
 def _read_stored(name):
@@ -824,7 +820,7 @@ def _read_stored(name):
 
 @pytest.mark.slow
 @pytest.mark.skipif(not FULL, reason="full-size run: set MF_FULL=1 (several minutes of input generation)")
-@pytest.mark.parametrize("name", sorted(STORED))
+@pytest.mark.parametrize("name", STORED)
 def test_full_size_against_the_stored_oracle_results(mfmod, name):
     g = _read_stored(name)
     if g is None:
@@ -867,7 +863,7 @@ def test_full_size_against_the_stored_oracle_results(mfmod, name):
     model.close()
 
     # Hogwild mode on the LDS kernel: final RMSE
-    opts = {mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS, mfmod.MF_OPT_LDS_WAVES: STORED[name]["lds_waves"]}
+    opts = {mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS}      # wavefronts per workgroup: the library's choice
     model = mfmod.MatrixFactorization(cfg.m, cfg.n, cfg.k, cfg.storage, seed=1, scale=scale, options=opts)
     model.load_blocks_device(coo[0], coo[1], coo[2], gr, gc, split)
     tr, tc, tv = model.to_device(ds.test_rows, ds.test_cols, ds.test_vals)
