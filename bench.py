@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 # reported only for the exact configuration that was profiled, otherwise null.
 PROFILED_TRAFFIC = {
     # (workload, scale, mode, grid, kernel, ring, lds_waves): bytes per launch
-    ("medium", 1.0, "hogwild", "256x256", "lds", 1, 12): 5727.9e6,   # profiles/sgd_ring_lds_f32_k128_medium.md
+    ("medium", 1.0, "hogwild", "256x256", "lds", 1, 0): 5727.9e6,   # profiles/sgd_ring_lds_f32_k128_medium.md
 }
 
 
@@ -97,7 +97,7 @@ def main():
     ap.add_argument("--grid", default="256x256")
     ap.add_argument("--hogwild-kernel", default="auto", choices=["auto", "global_atomics", "lds"])
     ap.add_argument("--lds-chunk", type=int, default=0)
-    ap.add_argument("--lds-waves", type=int, default=12)
+    ap.add_argument("--lds-waves", type=int, default=0, help="0: the library's choice")
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--affinity", type=int, default=1)
     ap.add_argument("--split", type=int, default=1, help="0 equal width, 1 ratings balanced, 2 ratings and width balanced")
@@ -145,7 +145,9 @@ def main():
              "lds": mf.MF_HOGWILD_LDS}[args.hogwild_kernel]
     opts = {mf.MF_OPT_HOGWILD_CHUNK: args.chunk, mf.MF_OPT_XCD_AFFINITY: args.affinity,
             mf.MF_OPT_HOGWILD_KERNEL: which,
-            mf.MF_OPT_LDS_CHUNK: args.lds_chunk, mf.MF_OPT_LDS_WAVES: args.lds_waves, mf.MF_OPT_RING: args.ring}
+            mf.MF_OPT_LDS_CHUNK: args.lds_chunk, mf.MF_OPT_RING: args.ring}
+    if args.lds_waves:
+        opts[mf.MF_OPT_LDS_WAVES] = args.lds_waves
     model = mf.MatrixFactorization(cfg.m, cfg.n, k, cfg.storage, seed=1, scale=0.1, options=opts)
     if args.load == "device":
         import torch

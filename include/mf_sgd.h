@@ -60,9 +60,10 @@ enum {
                                   /* mf_sgd_epoch                                                     */
     MF_OPT_LDS_CHUNK = 5,         /* target ratings per work-list entry of the LDS kernel; 0 (default)*/
                                   /* = the block's ratings divided by MF_OPT_LDS_WAVES               */
-    MF_OPT_LDS_WAVES = 6,         /* wavefronts per workgroup of the LDS kernel, 1..16.  Default: 16, */
-                                  /* or 8 when more than 1/32 of the ratings lie in pieces of rows    */
-                                  /* that had to be cut (rows long compared with a block)             */
+    MF_OPT_LDS_WAVES = 6,         /* wavefronts per workgroup of the LDS kernel, 1..16.  Default:     */
+                                  /* chosen by mf_load_blocks -- one per dozen ratings of an average  */
+                                  /* block, between 4 and 16, halved when more than 1/32 of the       */
+                                  /* ratings lie in pieces of rows that had to be cut                 */
     MF_OPT_DET_KERNEL = 7,        /* MF_KERNEL_AUTO (default), _GLOBAL or _LDS for MF_MODE_DET        */
     MF_OPT_RING = 8,              /* 1 (default): with the LDS kernels, run an epoch as ONE launch in */
                                   /* which the workgroups hand the column strips round (see           */

@@ -351,8 +351,17 @@ int finish_load(mf_ctx* ctx, const Layout& lay, char* base, const mf::RowStarts&
         mf::build_det_schedule(ctx->part, ctx->xcd_affinity != 0, ctx->sched[MF_MODE_DET]);
         mf::build_hogwild_schedule(ctx->part, rs, ctx->hogwild_chunk, ctx->lds_waves, ctx->xcd_affinity != 0,
                                    ctx->sched[MF_MODE_HOGWILD]);
-        mf::build_lds_schedule(ctx->part, rs, ctx->lds_chunk, ctx->lds_waves, ctx->lds);
         ctx->lds_waves_used = ctx->lds_waves;
+        if (!ctx->lds_waves_set && ctx->lds_chunk == 0 && ctx->part.nnz > 0) {
+            // about a dozen ratings per wavefront and block at least (measured on the MovieLens-shaped
+            // configuration: 16 wavefronts are best for blocks of 197 ratings, 12 for blocks of 151)
+            int64_t blocks = 0;
+            for (size_t L = 0; L + 1 < ctx->part.block_ptr.size(); ++L)
+                blocks += ctx->part.block_ptr[L + 1] > ctx->part.block_ptr[L];
+            const int64_t per_block = ctx->part.nnz / std::max<int64_t>(1, blocks);
+            ctx->lds_waves_used = (int32_t)std::min<int64_t>(ctx->lds_waves, std::max<int64_t>(4, (per_block + 6) / 12));
+        }
+        mf::build_lds_schedule(ctx->part, rs, ctx->lds_chunk, ctx->lds_waves_used, ctx->lds);
         if (!ctx->lds_waves_set && ctx->lds_chunk == 0 && ctx->part.nnz > 0) {
             // Rows that are long compared with a block's share per wavefront get cut into pieces,
             // and pieces of one row fall back to per-rating atomics on p_u.  If more than 1/32 of the
@@ -363,7 +372,7 @@ int finish_load(mf_ctx* ctx, const Layout& lay, char* base, const mf::RowStarts&
             for (int32_t len : ctx->lds.len)
                 if (len < 0) in_pieces += len & 0x7fffffff;
             if (in_pieces * 32 > ctx->part.nnz) {
-                ctx->lds_waves_used = std::max(1, ctx->lds_waves / 2);
+                ctx->lds_waves_used = std::max(1, ctx->lds_waves_used / 2);
                 mf::build_lds_schedule(ctx->part, rs, ctx->lds_chunk, ctx->lds_waves_used, ctx->lds);
             }
         }
