@@ -584,6 +584,40 @@ def test_hogwild_lds_kernel_other_shapes_and_long_rows(mfmod, k, storage):
     assert abs(got - want) <= 0.005 * want, (got, want)
 
 
+@pytest.mark.parametrize("ring", [1, 0])
+@pytest.mark.parametrize("k", [32, 128, 256])
+def test_hogwild_pieces_of_long_rows_in_one_wavefront_follow_the_sequential_order(mfmod, k, ring):
+    """With ONE wavefront per workgroup the pieces of a cut row run one after the other in stored
+    order, so the Hogwild LDS kernel (pieces of long rows included: rows requested ahead and
+    corrected by the wavefront's own changes) must reproduce the oracle's sequential epoch up to
+    the 2^-24 grid of its Qt strip.  A row value that missed changes still in flight would be off
+    by lr*e*q per missed rating, about 1e-2 here."""
+    rng = np.random.default_rng(23)
+    m, n, nnz = 300, 200, 30000
+    rows = rng.integers(0, m, nnz).astype(np.int32)
+    rows[:4000] = 9            # two long rows: ~800 and ~500 ratings in every block of their block row
+    rows[4000:6500] = 150
+    rows[6500:6600] = 151      # and a row of moderate length right after a long one
+    cols = rng.integers(0, n, nnz).astype(np.int32)
+    vals = rng.uniform(1.0, 5.0, nnz).astype(np.float32)
+    gr, gc, lr, lam = 2, 5, 0.02, 0.05
+    model = mfmod.MatrixFactorization(m, n, k, "f32", seed=5, scale=0.3,
+                                      options={mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS,
+                                               mfmod.MF_OPT_LDS_CHUNK: 24, mfmod.MF_OPT_LDS_WAVES: 1,
+                                               mfmod.MF_OPT_RING: ring})
+    model.load_blocks(rows, cols, vals, gr, gc, 1)
+    model.sgd_epoch(lr, lam, mfmod.MF_MODE_HOGWILD)
+    P, Qt = model.get_factors()
+    model.close()
+    perm, bp, _, _ = oracle.partition(rows, cols, m, n, gr, gc, 1)
+    Po, Qo = oracle_init(m, n, k, 5, 0.3, oracle.ARITH_F32)
+    oracle.sgd_epoch(Po, Qo, rows, cols, vals, perm, bp, gr, gc, lr, lam, oracle.ARITH_F32)
+    dp = float(np.abs(P - Po).max())
+    dq = float(np.abs(Qt - Qo).max())
+    print("long rows, one wavefront, k=%d ring=%d: max|dP| %.2e max|dQ| %.2e" % (k, ring, dp, dq), flush=True)
+    assert dp <= 2e-4 and dq <= 2e-4, (dp, dq)
+
+
 def test_lds_kernel_is_refused_when_the_strip_does_not_fit(mfmod):
     ds = dataset("tiny")
     model = _make(mfmod, ds, 256, "f32", 2, 2, 0, options={mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS})
