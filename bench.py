@@ -93,6 +93,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="medium")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (testing only)")
+    ap.add_argument("--init-scale", type=float, default=0.1, help="initial factors are uniform in [0, this)")
     ap.add_argument("--mode", default="hogwild", choices=["hogwild", "det"])
     ap.add_argument("--grid", default="256x256")
     ap.add_argument("--hogwild-kernel", default="auto", choices=["auto", "global_atomics", "lds"])
@@ -148,7 +149,7 @@ def main():
             mf.MF_OPT_LDS_CHUNK: args.lds_chunk, mf.MF_OPT_RING: args.ring}
     if args.lds_waves:
         opts[mf.MF_OPT_LDS_WAVES] = args.lds_waves
-    model = mf.MatrixFactorization(cfg.m, cfg.n, k, cfg.storage, seed=1, scale=0.1, options=opts)
+    model = mf.MatrixFactorization(cfg.m, cfg.n, k, cfg.storage, seed=1, scale=args.init_scale, options=opts)
     if args.load == "device":
         import torch
         coo = [torch.from_numpy(x).to(model.P.device) for x in (ds.rows, ds.cols, ds.vals)]
@@ -206,7 +207,8 @@ def main():
         if args.lds_chunk != 0 or args.split != 1:
             traffic = None
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": ("sgd_ring_lds<float,128>" if args.ring else "sgd_block_lds<float,128>") if (args.mode == "hogwild" and args.hogwild_kernel != "global_atomics") else "sgd_chunks<float,128>",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": (("sgd_ring_lds" if args.ring else "sgd_block_lds") if kern == "lds" else "sgd_chunks")
+                    + "<%s,%d>" % ("float" if cfg.storage == "f32" else "__half", k),
                     "avg_launch_us": avg_s * 1e6, "launches_per_step": launches / args.steps,
                     "bytes_per_update": bytes_per_update,
                     # what the memory side really moved per second (counters), next to the algorithmic figure:

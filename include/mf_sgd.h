@@ -61,9 +61,8 @@ enum {
     MF_OPT_LDS_CHUNK = 5,         /* target ratings per work-list entry of the LDS kernel; 0 (default)*/
                                   /* = the block's ratings divided by MF_OPT_LDS_WAVES               */
     MF_OPT_LDS_WAVES = 6,         /* wavefronts per workgroup of the LDS kernel, 1..16.  Default:     */
-                                  /* chosen by mf_load_blocks -- one per dozen ratings of an average  */
-                                  /* block, between 4 and 16, halved when more than 1/32 of the       */
-                                  /* ratings lie in pieces of rows that had to be cut                 */
+                                  /* chosen by mf_load_blocks -- one per eight ratings of an average  */
+                                  /* block, between 4 and 16                                          */
     MF_OPT_DET_KERNEL = 7,        /* MF_KERNEL_AUTO (default), _GLOBAL or _LDS for MF_MODE_DET        */
     MF_OPT_RING = 8,              /* 1 (default): with the LDS kernels, run an epoch as ONE launch in */
                                   /* which the workgroups hand the column strips round (see           */
@@ -81,7 +80,7 @@ enum {
 };
 enum { MF_KERNEL_AUTO = 0, MF_KERNEL_GLOBAL = 1, MF_KERNEL_LDS = 2 };
 enum { MF_HOGWILD_AUTO = MF_KERNEL_AUTO, MF_HOGWILD_GLOBAL_ATOMICS = MF_KERNEL_GLOBAL, MF_HOGWILD_LDS = MF_KERNEL_LDS };
-enum { MF_PLAN_HOGWILD_LDS = 2 };  /* third value of `mode` accepted by mf_plan_host only */
+enum { MF_PLAN_HOGWILD_LDS = 2, MF_PLAN_LDS_CUT_ROWS = 3 };  /* values of `mode` accepted by mf_plan_host only */
 
 /* Create a context on HIP device `device`.  `hip_stream` is a hipStream_t of the caller (may be
  * NULL for the default stream); all work of this context is enqueued on it. */
@@ -196,7 +195,13 @@ int mf_get_partition(const mf_ctx* ctx, int64_t* perm, int64_t* block_ptr,
  *                                                 is used the values of Qt are multiples of 2^-24
  *                                                 (the fp32 spacing in [0.5, 1)) and saturate at
  *                                                 +-128.  Needs (widest column strip) * k * 4
- *                                                 bytes <= 159 KiB of LDS;
+ *                                                 bytes <= 159 KiB of LDS.  A matrix row so long
+ *                                                 that a block's share of it is dealt to several
+ *                                                 wavefronts has its p_u kept in LDS in the same
+ *                                                 format while that block runs (up to 8 such
+ *                                                 rows per block, as room beside the strip
+ *                                                 allows; else p_u is changed with atomics in the
+ *                                                 L2);
  *                       MF_HOGWILD_GLOBAL_ATOMICS wavefronts of a whole die share a block and use
  *                                                 floating-point atomics in that die's L2 (any
  *                                                 grid, slower).
@@ -271,6 +276,11 @@ int mf_suggest_grid(int64_t m, int64_t n, int64_t nnz, int32_t k, int32_t mode,
  * mode = MF_PLAN_HOGWILD_LDS gives the work list of the LDS kernel: entries block after block
  * without padding (chunk = MF_OPT_LDS_CHUNK's meaning); every block's entries are taken by the
  * wavefronts of one workgroup.
+ * mode = MF_PLAN_LDS_CUT_ROWS lists, for the same work list, the matrix rows that a boundary
+ * between two entries of a block cuts (the LDS kernel keeps their p_u in LDS while the block runs,
+ * at most 8 per block; a block with more keeps none and is absent here): entry_begin[i] = packed
+ * position of one rating of the row, entry_len[i] = stratum * grid_r + block row of the block;
+ * stratum_entry is zero-filled.
  * MF_ENOMEM if entry_cap is too small. */
 int mf_plan_host(const int32_t* rows, const int32_t* cols, int64_t nnz, int64_t m, int64_t n,
                  int32_t grid_r, int32_t grid_c, int32_t split, int32_t mode, int32_t chunk,

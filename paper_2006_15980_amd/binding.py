@@ -24,6 +24,7 @@ MF_OPT_RING, MF_OPT_RING_SPIN_LIMIT, MF_OPT_LDS_PREFETCH, MF_OPT_ROW_ORDER_SEED 
 MF_KERNEL_AUTO, MF_KERNEL_GLOBAL, MF_KERNEL_LDS = 0, 1, 2
 MF_HOGWILD_AUTO, MF_HOGWILD_GLOBAL_ATOMICS, MF_HOGWILD_LDS = 0, 1, 2
 MF_PLAN_HOGWILD_LDS = 2
+MF_PLAN_LDS_CUT_ROWS = 3
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmf_sgd.so")
 

@@ -708,6 +708,74 @@ __device__ __forceinline__ void lds_shared_row_chunk(T* __restrict__ P, int* str
 }
 
 
+// ---- rows of P cut by entry boundaries, held in LDS while their block runs ----------------------
+// A very long row is shared out over several wavefronts of the workgroup.  Its p_u then lives in
+// LDS beside the strip, in the strip's fixed-point format, for as long as the block runs, and is
+// read and changed exactly like q_v (LDS atomic adds: no change is lost, every wavefront sees the
+// others' changes at once).  `prow`: the row's LDS slot.  All ratings of the piece have this row.
+template <typename T, int K>
+__device__ __forceinline__ void lds_hot_row_piece(int* prow, int* strip, int col0,
+                                                  const int32_t* __restrict__ V,
+                                                  const float* __restrict__ R, int64_t begin, int32_t len,
+                                                  float lr, float shrink, int lane, bool active)
+{
+    constexpr int VEC = RowShape<T, K>::VEC;
+    int mv = 0, nv = 0;
+    float mr = 0.f, nr = 0.f;
+    if (lane < min(kWave, len)) {
+        mv = V[begin + lane];
+        mr = R[begin + lane];
+    }
+    for (int32_t off = 0; off < len; off += kWave) {
+        const int cnt = min(kWave, len - off);
+        if (lane < len - off - kWave) {
+            nv = V[begin + off + kWave + lane];
+            nr = R[begin + off + kWave + lane];
+        }
+        for (int i = 0; i < cnt; ++i) {
+            const int v = uniform_lane(mv, i);
+            const float r = __int_as_float(uniform_lane(__float_as_int(mr), i));
+            int* const qrow = strip + (v - col0) * K;
+            const Row<VEC> q = strip_read<T, VEC>(qrow, lane, active);
+            const Row<VEC> p = strip_read<T, VEC>(prow, lane, active);
+            float part = 0.f;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) part = fmaf(p.x[j], q.x[j], part);
+            const float step = lr * (r - wave_sum(part));
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                const int dq = to_fixed(fmaf(step, p.x[j], -shrink * q.x[j]));
+                const int dp = to_fixed(fmaf(step, q.x[j], -shrink * p.x[j]));
+                if (active) {
+                    atomicAdd(&qrow[strip_elem<T>(lane, j)], dq);
+                    atomicAdd(&prow[strip_elem<T>(lane, j)], dp);
+                }
+            }
+        }
+        mv = nv;
+        mr = nr;
+    }
+}
+
+// Number of ratings at the front (FROM_END: at the back) of the packed range [begin, begin+len)
+// whose row index is `u`; wave-uniform.
+template <bool FROM_END>
+__device__ __forceinline__ int32_t run_of_row(const int32_t* __restrict__ U, int64_t begin, int32_t len, int u,
+                                              int lane)
+{
+    int32_t run = 0;
+    for (int32_t off = 0; off < len; off += kWave) {
+        const int cnt = min(kWave, len - off);
+        const int64_t at = FROM_END ? begin + len - 1 - off - lane : begin + off + lane;
+        const bool same = lane < cnt && U[at] == u;
+        const unsigned long long others = ~__ballot(same);   // lanes past cnt count as "another row"
+        const int first_other = others ? __builtin_ctzll(others) : kWave;
+        run += min(first_other, cnt);
+        if (first_other < cnt) break;
+    }
+    return run;
+}
+
 typedef unsigned int uint4_t __attribute__((ext_vector_type(4)));
 constexpr int kRawBufferFlags = 0x00020000;   // word 3 of a raw (untyped, unswizzled) buffer descriptor on gfx9
 constexpr int kCachePolicySc1 = 16;           // auxiliary operand of the buffer intrinsics: bit 4 = sc1
@@ -725,7 +793,8 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
                                                const int32_t* __restrict__ U, const int32_t* __restrict__ V,
                                                const float* __restrict__ R,
                                                const int64_t* __restrict__ entry_begin,
-                                               const int32_t* __restrict__ entry_len, const LdsBlock blk,
+                                               const int32_t* __restrict__ entry_len,
+                                               const int64_t* __restrict__ hot_pos, const LdsBlock blk,
                                                float lr, float lambda, BeforeStrip before_strip)
 {
     const int lane = threadIdx.x & (kWave - 1);
@@ -752,6 +821,12 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
         }
     };
     constexpr int VEC = RowShape<T, K>::VEC;
+    // rows of P cut by the entry boundaries of this block: lane s of every wavefront knows the
+    // row index of slot s; the slots follow the strip in LDS
+    const int n_hot = EXACT ? 0 : (blk.hot & 15);
+    int* const hot_rows = strip + total;
+    int hot_u = -1;
+    if (!EXACT && lane < n_hot) hot_u = U[hot_pos[(blk.hot >> 4) + lane]];
     RowRing<VEC, DEPTH> first_rows;
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d)
@@ -767,6 +842,15 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
 
     auto to_strip = [](float x) { return EXACT ? __float_as_int(x) : to_fixed(x); };
     auto from_strip = [](int x) { return EXACT ? __int_as_float(x) : from_fixed(x); };
+    if constexpr (!EXACT) {
+        // read past the L1: another block may have changed the row with atomics executed in the L2
+        for (int slot = wave; slot < n_hot; slot += n_waves) {
+            const Row<VEC> p = load_row<VEC, true>(P + (int64_t)uniform_lane(hot_u, slot) * K, lane, active);
+#pragma unroll
+            for (int j = 0; j < VEC; ++j)
+                if (active) hot_rows[slot * K + strip_elem<T>(lane, j)] = to_fixed(p.x[j]);
+        }
+    }
     if constexpr (COHERENT && !EXACT) {
         // 1024 threads: one 32-bit word each (one fp32 value or one pair of binary16 values); wider
         // pieces were measured 5 % slower per epoch here, and faster for the 64-thread workgroups
@@ -871,7 +955,38 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
             lds_owned_chunk<T, K, DEPTH, true>(P, strip, blk.col0, U, V, R, begin, len, mu, mv, mr,
                                                            first_rows, lr, shrink, lane, active);
         } else {
-            if (raw_len < 0)
+            if (raw_len < 0 && n_hot > 0) {
+                // a piece of a cut row at the front and / or at the back, whole rows between them
+                auto slot_of = [&](int u) {
+                    const unsigned long long hit = __ballot(hot_u == u);
+                    return hit ? (int)__builtin_ctzll(hit) : -1;
+                };
+                const int u_front = uniform_lane(mu, 0);
+                const int u_back = len <= kWave ? uniform_lane(mu, len - 1) : (int)U[begin + len - 1];
+                const int front_slot = slot_of(u_front), back_slot = slot_of(u_back);
+                const int32_t front = front_slot >= 0 ? run_of_row<false>(U, begin, len, u_front, lane) : 0;
+                const int32_t back = back_slot >= 0 && front < len
+                                         ? run_of_row<true>(U, begin + front, len - front, u_back, lane) : 0;
+                const int32_t between = len - front - back;
+                if (between > 0) {
+                    // requested now, used after the two pieces
+                    if (front > 0 && lane < min(kWave, between)) {
+                        mu = U[begin + front + lane];
+                        mv = V[begin + front + lane];
+                        mr = R[begin + front + lane];
+                    }
+                    first_rows = request_first_rows<T, K, DEPTH>(P, mu, min(kWave, between), lane, active);
+                }
+                if (front > 0)
+                    lds_hot_row_piece<T, K>(hot_rows + front_slot * K, strip, blk.col0, V, R, begin, front, lr, shrink,
+                                            lane, active);
+                if (back > 0)
+                    lds_hot_row_piece<T, K>(hot_rows + back_slot * K, strip, blk.col0, V, R, begin + len - back, back,
+                                            lr, shrink, lane, active);
+                if (between > 0)
+                    lds_hog_chunk<T, K, DEPTH>(P, strip, blk.col0, U, V, R, begin + front, between, mu, mv, mr,
+                                               first_rows, lr, shrink, lane, active);
+            } else if (raw_len < 0)
                 lds_shared_row_chunk<T, K>(P, strip, blk.col0, U, V, R, begin, len, lr, shrink, lane, active);
             else
                 lds_hog_chunk<T, K, DEPTH>(P, strip, blk.col0, U, V, R, begin, len, mu, mv, mr,
@@ -880,6 +995,15 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
     }
     __syncthreads();
 
+    if constexpr (!EXACT) {
+        for (int slot = wave; slot < n_hot; slot += n_waves) {
+            Row<VEC> p;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j)
+                p.x[j] = active ? quantise<T>(from_fixed(hot_rows[slot * K + strip_elem<T>(lane, j)])) : 0.f;
+            store_row<VEC>(P + (int64_t)uniform_lane(hot_u, slot) * K, lane, active, p);
+        }
+    }
     if constexpr (COHERENT && !EXACT) {
         constexpr int kPerWord = sizeof(T) == 2 ? 2 : 1;
         unsigned* dst = reinterpret_cast<unsigned*>(strip_src);
@@ -943,11 +1067,11 @@ template <typename T, int K, bool EXACT, int DEPTH>
 __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_block_lds(
     T* __restrict__ P, T* __restrict__ Qt, const int32_t* __restrict__ U,
     const int32_t* __restrict__ V, const float* __restrict__ R,
-    const int64_t* __restrict__ entry_begin, const int32_t* __restrict__ entry_len,
+    const int64_t* __restrict__ entry_begin, const int32_t* __restrict__ entry_len, const int64_t* __restrict__ hot_pos,
     const LdsBlock* __restrict__ blocks, float lr, float lambda)
 {
     extern __shared__ int strip[];            // ncols * K values (fixed point, or fp32 bits if EXACT)
-    lds_block_body<T, K, EXACT, false, DEPTH>(strip, P, Qt, U, V, R, entry_begin, entry_len, blocks[blockIdx.x], lr,
+    lds_block_body<T, K, EXACT, false, DEPTH>(strip, P, Qt, U, V, R, entry_begin, entry_len, hot_pos, blocks[blockIdx.x], lr,
                                        lambda, [] { return true; });
 }
 
@@ -972,7 +1096,7 @@ template <typename T, int K, bool EXACT, int DEPTH>
 __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_ring_lds(
     T* __restrict__ P, T* __restrict__ Qt, const int32_t* __restrict__ U,
     const int32_t* __restrict__ V, const float* __restrict__ R,
-    const int64_t* __restrict__ entry_begin, const int32_t* __restrict__ entry_len,
+    const int64_t* __restrict__ entry_begin, const int32_t* __restrict__ entry_len, const int64_t* __restrict__ hot_pos,
     const LdsBlock* __restrict__ ring_blocks, int grid_r, int grid_c, float lr, float lambda,
     int* done, int first, int* abort_flag, long long spin_limit, const int32_t* __restrict__ order,
     const int32_t* __restrict__ pos)
@@ -1036,7 +1160,7 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_ring_lds(
         const LdsBlock blk = ring_blocks[(int64_t)s * grid_r + a];
         bool ok;
         if (blk.n_entries > 0)
-            ok = lds_block_body<T, K, EXACT, true, DEPTH>(strip, P, Qt, U, V, R, entry_begin, entry_len, blk, lr, lambda,
+            ok = lds_block_body<T, K, EXACT, true, DEPTH>(strip, P, Qt, U, V, R, entry_begin, entry_len, hot_pos, blk, lr, lambda,
                                                    wait_for_strip);
         else
             ok = wait_for_strip();   // an empty block still waits: it passes the guarantee on
@@ -1162,7 +1286,7 @@ hipError_t launch_sgd_t(bool hogwild, void* P, void* Qt, const int32_t* U, const
 
 template <typename T, int K, bool EXACT, int DEPTH>
 hipError_t launch_sgd_lds_impl(int waves, void* P, void* Qt, const int32_t* U, const int32_t* V,
-                            const float* R, const int64_t* eb, const int32_t* el,
+                            const float* R, const int64_t* eb, const int32_t* el, const int64_t* hot,
                             const LdsBlock* blocks, int64_t n_blocks, size_t lds_bytes, float lr,
                             float lambda, hipStream_t stream)
 {
@@ -1178,14 +1302,14 @@ hipError_t launch_sgd_lds_impl(int waves, void* P, void* Qt, const int32_t* U, c
         raised[dev] = true;
     }
     hipLaunchKernelGGL((sgd_block_lds<T, K, EXACT, DEPTH>), dim3((unsigned)n_blocks), dim3(waves * kWave), lds_bytes,
-                       stream, (T*)P, (T*)Qt, U, V, R, eb, el, blocks, lr, lambda);
+                       stream, (T*)P, (T*)Qt, U, V, R, eb, el, hot, blocks, lr, lambda);
     return hipGetLastError();
 }
 
 template <typename T, int K, bool EXACT, int DEPTH>
 hipError_t launch_sgd_ring_impl(int waves, bool query_only, int* max_resident, void* P, void* Qt,
                                 const int32_t* U, const int32_t* V, const float* R, const int64_t* eb,
-                                const int32_t* el, const LdsBlock* ring_blocks, int grid_r, int grid_c,
+                                const int32_t* el, const int64_t* hot, const LdsBlock* ring_blocks, int grid_r, int grid_c,
                                 size_t lds_bytes, float lr, float lambda, int* done, int first,
                                 int* abort_flag, long long spin_limit, const int32_t* order, const int32_t* pos,
                                 hipStream_t stream)
@@ -1211,7 +1335,7 @@ hipError_t launch_sgd_ring_impl(int waves, bool query_only, int* max_resident, v
         return hipSuccess;
     }
     hipLaunchKernelGGL((sgd_ring_lds<T, K, EXACT, DEPTH>), dim3((unsigned)grid_r), dim3(waves * kWave), lds_bytes,
-                       stream, (T*)P, (T*)Qt, U, V, R, eb, el, ring_blocks, grid_r, grid_c, lr, lambda, done,
+                       stream, (T*)P, (T*)Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lr, lambda, done,
                        first, abort_flag, spin_limit, order, pos);
     return hipGetLastError();
 }
@@ -1219,38 +1343,38 @@ hipError_t launch_sgd_ring_impl(int waves, bool query_only, int* max_resident, v
 template <typename T, int K>
 hipError_t launch_sgd_ring_t(bool exact, bool short_prefetch, int waves, bool query_only, int* max_resident, void* P, void* Qt,
                              const int32_t* U, const int32_t* V, const float* R, const int64_t* eb,
-                             const int32_t* el, const LdsBlock* ring_blocks, int grid_r, int grid_c,
+                             const int32_t* el, const int64_t* hot, const LdsBlock* ring_blocks, int grid_r, int grid_c,
                              size_t lds_bytes, float lr, float lambda, int* done, int first, int* abort_flag,
                              long long spin_limit, const int32_t* order, const int32_t* pos, hipStream_t stream)
 {
     if (exact)
-        return launch_sgd_ring_impl<T, K, true, kLdsPrefetchDepth>(1, query_only, max_resident, P, Qt, U, V, R, eb, el,
+        return launch_sgd_ring_impl<T, K, true, kLdsPrefetchDepth>(1, query_only, max_resident, P, Qt, U, V, R, eb, el, hot,
                                                                    ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda,
                                                                    done, first, abort_flag, spin_limit, order, pos,
                                                                    stream);
     if (short_prefetch)
         return launch_sgd_ring_impl<T, K, false, kShortPrefetchDepth>(waves, query_only, max_resident, P, Qt, U, V, R, eb,
-                                                                      el, ring_blocks, grid_r, grid_c, lds_bytes, lr,
+                                                                      el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr,
                                                                       lambda, done, first, abort_flag, spin_limit, order,
                                                                       pos, stream);
-    return launch_sgd_ring_impl<T, K, false, kLdsPrefetchDepth>(waves, query_only, max_resident, P, Qt, U, V, R, eb, el,
+    return launch_sgd_ring_impl<T, K, false, kLdsPrefetchDepth>(waves, query_only, max_resident, P, Qt, U, V, R, eb, el, hot,
                                                                 ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done,
                                                                 first, abort_flag, spin_limit, order, pos, stream);
 }
 
 template <typename T, int K>
 hipError_t launch_sgd_lds_t(bool exact, bool short_prefetch, int waves, void* P, void* Qt, const int32_t* U, const int32_t* V,
-                            const float* R, const int64_t* eb, const int32_t* el,
+                            const float* R, const int64_t* eb, const int32_t* el, const int64_t* hot,
                             const LdsBlock* blocks, int64_t n_blocks, size_t lds_bytes, float lr,
                             float lambda, hipStream_t stream)
 {
     if (exact)
-        return launch_sgd_lds_impl<T, K, true, kLdsPrefetchDepth>(1, P, Qt, U, V, R, eb, el, blocks, n_blocks, lds_bytes,
+        return launch_sgd_lds_impl<T, K, true, kLdsPrefetchDepth>(1, P, Qt, U, V, R, eb, el, hot, blocks, n_blocks, lds_bytes,
                                                                   lr, lambda, stream);
     if (short_prefetch)
-        return launch_sgd_lds_impl<T, K, false, kShortPrefetchDepth>(waves, P, Qt, U, V, R, eb, el, blocks, n_blocks,
+        return launch_sgd_lds_impl<T, K, false, kShortPrefetchDepth>(waves, P, Qt, U, V, R, eb, el, hot, blocks, n_blocks,
                                                                      lds_bytes, lr, lambda, stream);
-    return launch_sgd_lds_impl<T, K, false, kLdsPrefetchDepth>(waves, P, Qt, U, V, R, eb, el, blocks, n_blocks, lds_bytes,
+    return launch_sgd_lds_impl<T, K, false, kLdsPrefetchDepth>(waves, P, Qt, U, V, R, eb, el, hot, blocks, n_blocks, lds_bytes,
                                                                lr, lambda, stream);
 }
 
@@ -1305,18 +1429,18 @@ size_t lds_strip_bytes(int k, int32_t max_cols) { return (size_t)max_cols * k * 
 
 hipError_t launch_sgd_lds(int dtype, int k, bool exact, bool short_prefetch, int waves, void* P, void* Qt, const int32_t* U,
                           const int32_t* V, const float* R, const int64_t* entry_begin,
-                          const int32_t* entry_len, const LdsBlock* blocks, int64_t n_blocks,
+                          const int32_t* entry_len, const int64_t* hot_pos, const LdsBlock* blocks, int64_t n_blocks,
                           size_t lds_bytes, float lr, float lambda, hipStream_t stream)
 {
     if (n_blocks <= 0) return hipSuccess;
     if (waves < 1 || waves > 16 || lds_bytes > kLdsBudget) return hipErrorInvalidValue;
-    MF_DISPATCH(launch_sgd_lds_t, exact, short_prefetch, waves, P, Qt, U, V, R, entry_begin, entry_len, blocks, n_blocks,
+    MF_DISPATCH(launch_sgd_lds_t, exact, short_prefetch, waves, P, Qt, U, V, R, entry_begin, entry_len, hot_pos, blocks, n_blocks,
                 lds_bytes, lr, lambda, stream);
 }
 
 hipError_t launch_sgd_ring(int dtype, int k, bool exact, bool short_prefetch, int waves, bool query_only, int* max_resident,
                            void* P, void* Qt, const int32_t* U, const int32_t* V, const float* R,
-                           const int64_t* entry_begin, const int32_t* entry_len, const LdsBlock* ring_blocks,
+                           const int64_t* entry_begin, const int32_t* entry_len, const int64_t* hot_pos, const LdsBlock* ring_blocks,
                            int grid_r, int grid_c, size_t lds_bytes, float lr, float lambda, int* done,
                            int first, int* abort_flag, long long spin_limit, const int32_t* order,
                            const int32_t* pos, hipStream_t stream)
@@ -1324,7 +1448,7 @@ hipError_t launch_sgd_ring(int dtype, int k, bool exact, bool short_prefetch, in
     if (waves < 1 || waves > 16 || lds_bytes > kLdsBudget || grid_r < 1) return hipErrorInvalidValue;
     if ((order == nullptr) != (pos == nullptr)) return hipErrorInvalidValue;
     MF_DISPATCH(launch_sgd_ring_t, exact, short_prefetch, waves, query_only, max_resident, P, Qt, U, V, R, entry_begin,
-                entry_len, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done, first, abort_flag,
+                entry_len, hot_pos, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done, first, abort_flag,
                 spin_limit, order, pos, stream);
 }
 

@@ -114,8 +114,8 @@ bool valid_k(int32_t k) { return k == 32 || k == 64 || k == 128 || k == 256; }
 
 struct Layout {
     size_t off_u, off_v, off_r, off_perm, off_begin[2], off_len[2], off_lds_begin, off_lds_len, off_lds_blocks,
-        off_dlds_begin, off_dlds_len, off_dlds_blocks, off_ring[2], off_ring_done, off_order, total;
-    int64_t cap[2], lds_cap, lds_blocks_cap;
+        off_dlds_begin, off_dlds_len, off_dlds_blocks, off_ring[2], off_ring_done, off_order, off_hot, total;
+    int64_t cap[2], lds_cap, lds_blocks_cap, hot_cap;
 };
 
 Layout make_layout(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t lds_chunk, int32_t lds_waves,
@@ -127,6 +127,7 @@ Layout make_layout(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t l
     l.cap[MF_MODE_HOGWILD] = mf::hogwild_entries_bound(nnz, gr, gc, chunk, lds_waves);
     l.lds_cap = mf::lds_entries_bound(nnz, gr, gc, lds_chunk, lds_waves);
     l.lds_blocks_cap = (int64_t)gr * gc;
+    l.hot_cap = mf::lds_hot_bound(nnz, gr, gc);
     size_t off = 0;
     l.off_u = off; off += align_up(packed);
     l.off_v = off; off += align_up(packed);
@@ -147,6 +148,7 @@ Layout make_layout(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t l
     }
     l.off_ring_done = off; off += align_up(((size_t)gr + 1) * 4);
     l.off_order = off; off += align_up((size_t)gc * 2 * 4);   // stratum order of an epoch and its inverse
+    l.off_hot = off; off += align_up((size_t)l.hot_cap * 8);   // cut rows of the Hogwild LDS work list
     l.total = off;
     return l;
 }
@@ -353,29 +355,19 @@ int finish_load(mf_ctx* ctx, const Layout& lay, char* base, const mf::RowStarts&
                                    ctx->sched[MF_MODE_HOGWILD]);
         ctx->lds_waves_used = ctx->lds_waves;
         if (!ctx->lds_waves_set && ctx->lds_chunk == 0 && ctx->part.nnz > 0) {
-            // about a dozen ratings per wavefront and block at least (measured on the MovieLens-shaped
-            // configuration: 16 wavefronts are best for blocks of 197 ratings, 12 for blocks of 151)
+            // eight ratings per wavefront and block at least (measured on the MovieLens-shaped
+            // configuration: 16 wavefronts are best for blocks of 197 and of 151 ratings)
             int64_t blocks = 0;
             for (size_t L = 0; L + 1 < ctx->part.block_ptr.size(); ++L)
                 blocks += ctx->part.block_ptr[L + 1] > ctx->part.block_ptr[L];
             const int64_t per_block = ctx->part.nnz / std::max<int64_t>(1, blocks);
-            ctx->lds_waves_used = (int32_t)std::min<int64_t>(ctx->lds_waves, std::max<int64_t>(4, (per_block + 6) / 12));
+            ctx->lds_waves_used = (int32_t)std::min<int64_t>(ctx->lds_waves, std::max<int64_t>(4, (per_block + 4) / 8));
         }
-        mf::build_lds_schedule(ctx->part, rs, ctx->lds_chunk, ctx->lds_waves_used, ctx->lds);
-        if (!ctx->lds_waves_set && ctx->lds_chunk == 0 && ctx->part.nnz > 0) {
-            // Rows that are long compared with a block's share per wavefront get cut into pieces,
-            // and pieces of one row fall back to per-rating atomics on p_u.  If more than 1/32 of the
-            // ratings sit in such pieces, half as many wavefronts (twice the share each) are faster
-            // (measured on the Yahoo!Music-shaped configuration, 5.3 % in pieces: 2.33 against 1.80 G
-            // updates/s; the MovieLens-shaped one has 1.1 % in pieces and keeps its wavefronts).
-            int64_t in_pieces = 0;
-            for (int32_t len : ctx->lds.len)
-                if (len < 0) in_pieces += len & 0x7fffffff;
-            if (in_pieces * 32 > ctx->part.nnz) {
-                ctx->lds_waves_used = std::max(1, ctx->lds_waves_used / 2);
-                mf::build_lds_schedule(ctx->part, rs, ctx->lds_chunk, ctx->lds_waves_used, ctx->lds);
-            }
-        }
+        // cut rows stay in LDS beside the strip, as many per block as the widest strip leaves room for
+        const int64_t widest = (int64_t)mf::lds_strip_bytes(ctx->k, mf::widest_strip(ctx->part));
+        const int32_t hot_slots = (int32_t)std::max<int64_t>(
+            0, std::min<int64_t>(mf::kMaxHotRows, ((int64_t)mf::kLdsBudget - widest) / ((int64_t)ctx->k * 4)));
+        mf::build_lds_schedule(ctx->part, rs, ctx->lds_chunk, ctx->lds_waves_used, hot_slots, ctx->lds);
         mf::build_det_lds_schedule(ctx->part, ctx->det_lds);
     } catch (const std::bad_alloc&) {
         return fail(ctx, MF_ENOMEM, "host allocation failed while building the work lists");
@@ -400,6 +392,10 @@ int finish_load(mf_ctx* ctx, const Layout& lay, char* base, const mf::RowStarts&
         l.d_len = (int32_t*)(base + (which ? lay.off_dlds_len : lay.off_lds_len));
         l.d_blocks = (mf::LdsBlock*)(base + (which ? lay.off_dlds_blocks : lay.off_lds_blocks));
         l.d_ring = (mf::LdsBlock*)(base + lay.off_ring[which]);
+        l.d_hot = (int64_t*)(base + lay.off_hot);
+        if ((int64_t)l.hot_pos.size() > lay.hot_cap) return fail(ctx, MF_ENOMEM, "schedule larger than its workspace bound");
+        if (!which && !l.hot_pos.empty())
+            MF_HIP(ctx, hipMemcpy(l.d_hot, l.hot_pos.data(), l.hot_pos.size() * 8, hipMemcpyHostToDevice));
         MF_HIP(ctx, hipMemcpy(l.d_ring, l.ring.data(), l.ring.size() * sizeof(mf::LdsBlock), hipMemcpyHostToDevice));
         if (!l.begin.empty()) {
             MF_HIP(ctx, hipMemcpy(l.d_begin, l.begin.data(), l.begin.size() * 8, hipMemcpyHostToDevice));
@@ -625,7 +621,7 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
     const size_t p_bytes = (size_t)ctx->m * ctx->k * (ctx->dtype == MF_F16 ? 2 : 4);
     const bool short_prefetch = ctx->lds_prefetch == 4 || (ctx->lds_prefetch == 0 && p_bytes <= ((size_t)64 << 20));
     const mf::LdsSchedule& lsched = hog ? ctx->lds : ctx->det_lds;
-    const size_t lds_bytes = mf::lds_strip_bytes(ctx->k, lsched.max_cols);
+    const size_t lds_bytes = mf::lds_strip_bytes(ctx->k, lsched.max_cols) + (size_t)lsched.max_hot * ctx->k * 4;
     const int32_t choice = hog ? ctx->hogwild_kernel : ctx->det_kernel;
     bool use_lds = false;
     if (choice != MF_KERNEL_GLOBAL) {
@@ -640,7 +636,7 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
         if (ctx->ring_resident[m_idx] < 0) {
             int resident = 0;
             MF_HIP(ctx, mf::launch_sgd_ring(ctx->dtype, ctx->k, !hog, short_prefetch, ctx->lds_waves_used, true, &resident, nullptr, nullptr,
-                                            nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, ctx->part.gr,
+                                            nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, ctx->part.gr,
                                             ctx->part.gc, lds_bytes, 0.f, 0.f, nullptr, 0, nullptr, 0, nullptr, nullptr,
                                             ctx->stream));
             ctx->ring_resident[m_idx] = resident;
@@ -661,7 +657,7 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
             hipEvent_t ev1 = nullptr;
             MF_HIP(ctx, begin_launch_timing(ctx, &ev1));
             MF_HIP(ctx, mf::launch_sgd_ring(ctx->dtype, ctx->k, !hog, short_prefetch, ctx->lds_waves_used, false, nullptr, ctx->dP, ctx->dQt,
-                                            ctx->dU, ctx->dV, ctx->dR, lsched.d_begin, lsched.d_len, lsched.d_ring,
+                                            ctx->dU, ctx->dV, ctx->dR, lsched.d_begin, lsched.d_len, lsched.d_hot, lsched.d_ring,
                                             ctx->part.gr, ctx->part.gc, lds_bytes, lr, lambda, ctx->d_ring_done,
                                             ctx->ring_epochs * ctx->part.gc, ctx->d_ring_done + ctx->part.gr,
                                             (long long)ctx->spin_limit, stratum_order ? ctx->d_order : nullptr,
@@ -747,7 +743,7 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
         if (count > 0) MF_HIP(ctx, begin_launch_timing(ctx, &ev1));
         if (count > 0 && use_lds)
             MF_HIP(ctx, mf::launch_sgd_lds(ctx->dtype, ctx->k, !hog, short_prefetch, ctx->lds_waves_used, ctx->dP, ctx->dQt, U, V,
-                                           R, lsched.d_begin, lsched.d_len, lsched.d_blocks + first, count, lds_bytes,
+                                           R, lsched.d_begin, lsched.d_len, lsched.d_hot, lsched.d_blocks + first, count, lds_bytes,
                                            lr, lambda, ctx->stream));
         else if (count > 0)
             MF_HIP(ctx, mf::launch_sgd(ctx->dtype, ctx->k, mode == MF_MODE_HOGWILD, ctx->dP, ctx->dQt, U, V, R,
@@ -878,7 +874,8 @@ int mf_plan_host(const int32_t* rows, const int32_t* cols, int64_t nnz, int64_t 
     if (check_grid(nullptr, nnz, grid_r, grid_c)) return MF_EINVAL;
     if (m < 1 || n < 1 || grid_r > m || grid_c > n) return MF_EINVAL;
     if (split < MF_SPLIT_EQUAL_WIDTH || split > MF_SPLIT_NNZ_WIDTH_BALANCED) return MF_EINVAL;
-    if (mode != MF_MODE_DET && mode != MF_MODE_HOGWILD && mode != MF_PLAN_HOGWILD_LDS) return MF_EINVAL;
+    if (mode != MF_MODE_DET && mode != MF_MODE_HOGWILD && mode != MF_PLAN_HOGWILD_LDS && mode != MF_PLAN_LDS_CUT_ROWS)
+        return MF_EINVAL;
     if (chunk < 0 || (nnz > 0 && (!rows || !cols))) return MF_EINVAL;
     try {
         mf::Partition part;
@@ -899,14 +896,23 @@ int mf_plan_host(const int32_t* rows, const int32_t* cols, int64_t nnz, int64_t 
             bound = mf::hogwild_entries_bound(nnz, grid_r, grid_c, chunk, 16);
         } else {
             mf::LdsSchedule l;
-            mf::build_lds_schedule(part, rs, chunk, 16, l);
-            bound = mf::lds_entries_bound(nnz, grid_r, grid_c, chunk, 16);
-            s.begin = l.begin;
-            s.len = l.len;
-            s.stratum_entry.assign((size_t)grid_c + 1, (int64_t)l.begin.size());
-            for (int32_t st = 0; st < grid_c; ++st)   // first entry of the first block of the stratum
-                if (l.stratum_block[st] < (int64_t)l.blocks.size())
-                    s.stratum_entry[st] = l.blocks[(size_t)l.stratum_block[st]].first_entry;
+            mf::build_lds_schedule(part, rs, chunk, 16, mode == MF_PLAN_LDS_CUT_ROWS ? mf::kMaxHotRows : 0, l);
+            if (mode == MF_PLAN_LDS_CUT_ROWS) {
+                bound = mf::lds_hot_bound(nnz, grid_r, grid_c);
+                s.begin = l.hot_pos;
+                s.len.assign(l.hot_pos.size(), 0);
+                s.stratum_entry.assign((size_t)grid_c + 1, 0);
+                for (size_t L = 0; L < l.ring.size(); ++L)
+                    for (int32_t j = 0; j < (l.ring[L].hot & 15); ++j) s.len[(size_t)(l.ring[L].hot >> 4) + j] = (int32_t)L;
+            } else {
+                bound = mf::lds_entries_bound(nnz, grid_r, grid_c, chunk, 16);
+                s.begin = l.begin;
+                s.len = l.len;
+                s.stratum_entry.assign((size_t)grid_c + 1, (int64_t)l.begin.size());
+                for (int32_t st = 0; st < grid_c; ++st)   // first entry of the first block of the stratum
+                    if (l.stratum_block[st] < (int64_t)l.blocks.size())
+                        s.stratum_entry[st] = l.blocks[(size_t)l.stratum_block[st]].first_entry;
+            }
         }
         if ((int64_t)s.begin.size() > bound) return MF_ENOMEM;
         if (perm && nnz > 0) std::memcpy(perm, part.perm.data(), (size_t)nnz * 8);

@@ -30,12 +30,17 @@ struct Schedule {
 // Work of one workgroup of the LDS-resident Hogwild kernel: one block of the grid.  The block's
 // strip of Qt (columns col0 .. col0+ncols) is held in LDS while the wavefronts of the workgroup
 // take the block's entries (chunks of whole rows) one after another.
+// Rows of P that the boundaries between the block's entries cut (very long rows shared out over
+// several wavefronts) are held in LDS beside the strip while the block runs: `hot` = number of
+// such rows (low 4 bits, at most kMaxHotRows) and the index of the first of them in the
+// schedule's hot_pos list (the bits above).
+constexpr int32_t kMaxHotRows = 8;
 struct LdsBlock {
     int64_t first_entry;
     int32_t n_entries;
     int32_t col0;
     int32_t ncols;
-    int32_t reserved;
+    int32_t hot;
 };
 
 struct LdsSchedule {
@@ -44,11 +49,14 @@ struct LdsSchedule {
     std::vector<LdsBlock> blocks;        // non-empty blocks, stratum after stratum
     std::vector<LdsBlock> ring;          // all G_c * G_r blocks, [stratum][block row], for the ring kernel
     std::vector<int64_t> stratum_block;  // first block of stratum s (size G_c + 1)
+    std::vector<int64_t> hot_pos;        // per cut row of a block: the packed position of one of its ratings
     int32_t max_cols = 0;                // widest column strip of the grid
+    int32_t max_hot = 0;                 // most cut rows any block keeps in LDS
     int64_t* d_begin = nullptr;
     int32_t* d_len = nullptr;
     LdsBlock* d_blocks = nullptr;
     LdsBlock* d_ring = nullptr;
+    int64_t* d_hot = nullptr;
 };
 
 // Where the runs of one matrix row begin in the packed order: bit i is set when rating i has
@@ -109,12 +117,15 @@ void strip_table(const std::vector<int32_t>& bounds, int64_t size, std::vector<i
 void build_det_schedule(const Partition& part, bool xcd_affinity, Schedule& out);
 void build_hogwild_schedule(const Partition& part, const RowStarts& rs, int32_t chunk,
                             int32_t waves, bool xcd_affinity, Schedule& out);
+// hot_slots: how many cut rows a block may keep in LDS (0: none, they are updated in the L2).
 void build_lds_schedule(const Partition& part, const RowStarts& rs, int32_t chunk,
-                        int32_t waves, LdsSchedule& out);
+                        int32_t waves, int32_t hot_slots, LdsSchedule& out);
 // Deterministic mode on the LDS kernel: one entry (the whole block) per block descriptor.
 void build_det_lds_schedule(const Partition& part, LdsSchedule& out);
 // Upper bounds on the number of schedule entries, usable before the partition is known.
 int64_t lds_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t waves);
+int64_t lds_hot_bound(int64_t nnz, int32_t gr, int32_t gc);
+int32_t widest_strip(const Partition& part);   // columns of the widest column strip
 int64_t det_entries_bound(int32_t gr, int32_t gc);
 int64_t hogwild_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t waves);
 
@@ -136,10 +147,11 @@ hipError_t launch_sgd(int dtype, int k, bool hogwild, void* P, void* Qt, const i
 // LDS-resident kernel: one workgroup per block descriptor; `exact` = deterministic mode (one
 // wavefront per workgroup, fp32 strip), else Hogwild (`waves` wavefronts, fixed-point strip;
 // short_prefetch: rows of P are requested 4 instead of 8 ratings ahead, which pays when P is
-// served from the caches).
+// served from the caches).  hot_pos: the schedule's list of cut rows (see LdsBlock); lds_bytes
+// covers the widest strip plus the most cut rows of any block.
 hipError_t launch_sgd_lds(int dtype, int k, bool exact, bool short_prefetch, int waves, void* P, void* Qt, const int32_t* U,
                           const int32_t* V, const float* R, const int64_t* entry_begin,
-                          const int32_t* entry_len, const LdsBlock* blocks, int64_t n_blocks,
+                          const int32_t* entry_len, const int64_t* hot_pos, const LdsBlock* blocks, int64_t n_blocks,
                           size_t lds_bytes, float lr, float lambda, hipStream_t stream);
 // One launch per epoch (ring of workgroups, see kernels.hip).  ring_blocks: grid_c * grid_r
 // descriptors indexed [stratum][block row], empty blocks included.  order / pos (device, grid_c
@@ -147,7 +159,7 @@ hipError_t launch_sgd_lds(int dtype, int k, bool exact, bool short_prefetch, int
 // return in *max_resident how many workgroups of this shape the device can hold at once.
 hipError_t launch_sgd_ring(int dtype, int k, bool exact, bool short_prefetch, int waves, bool query_only, int* max_resident,
                            void* P, void* Qt, const int32_t* U, const int32_t* V, const float* R,
-                           const int64_t* entry_begin, const int32_t* entry_len, const LdsBlock* ring_blocks,
+                           const int64_t* entry_begin, const int32_t* entry_len, const int64_t* hot_pos, const LdsBlock* ring_blocks,
                            int grid_r, int grid_c, size_t lds_bytes, float lr, float lambda, int* done,
                            int first, int* abort_flag, long long spin_limit, const int32_t* order,
                            const int32_t* pos, hipStream_t stream);

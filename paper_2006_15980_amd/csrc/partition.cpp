@@ -396,17 +396,20 @@ void build_hogwild_schedule(const Partition& part, const RowStarts& rs, int32_t 
 }
 
 void build_lds_schedule(const Partition& part, const RowStarts& rs, int32_t chunk,
-                        int32_t waves, LdsSchedule& out)
+                        int32_t waves, int32_t hot_slots, LdsSchedule& out)
 {
     // chunk == 0: cut every block into about one chunk per wavefront of its workgroup
     out.begin.clear();
     out.len.clear();
     out.blocks.clear();
+    out.hot_pos.clear();
+    out.max_hot = 0;
     out.stratum_block.assign((size_t)part.gc + 1, 0);
     out.max_cols = 0;
     for (int32_t b = 0; b < part.gc; ++b)
         out.max_cols = std::max(out.max_cols, part.col_bounds[b + 1] - part.col_bounds[b]);
     out.ring.assign((size_t)part.gr * part.gc, LdsBlock{0, 0, 0, 0, 0});
+    hot_slots = std::min(hot_slots, kMaxHotRows);
     for (int32_t s = 0; s < part.gc; ++s) {
         for (int32_t a = 0; a < part.gr; ++a) {
             int64_t L = (int64_t)s * part.gr + a;
@@ -416,7 +419,7 @@ void build_lds_schedule(const Partition& part, const RowStarts& rs, int32_t chun
             blk.first_entry = (int64_t)out.begin.size();
             blk.col0 = part.col_bounds[b];
             blk.ncols = part.col_bounds[b + 1] - part.col_bounds[b];
-            blk.reserved = 0;
+            blk.hot = 0;
             auto push = [&](int64_t pos, int32_t len) {
                 out.begin.push_back(pos);
                 out.len.push_back(len);
@@ -424,11 +427,52 @@ void build_lds_schedule(const Partition& part, const RowStarts& rs, int32_t chun
             if (chunk > 0) chunk_block(rs, part.block_ptr[L], part.block_ptr[L + 1], chunk, push);
             else chunk_block_even(rs, part.block_ptr[L], part.block_ptr[L + 1], waves, push);
             blk.n_entries = (int32_t)((int64_t)out.begin.size() - blk.first_entry);
+            // The rows of this block that an entry boundary cuts (each is named by the position of
+            // one of its ratings): a boundary lies inside a row when the entry after it does not
+            // begin a row; it continues the row of the boundary before it when that one lay inside
+            // a row too and no row begins between the two.
+            const int64_t hot_first = (int64_t)out.hot_pos.size();
+            int32_t n_hot = 0;
+            bool previous_cut_inside_row = false;
+            for (int64_t e = blk.first_entry + 1; e < (int64_t)out.begin.size() && hot_slots > 0; ++e) {
+                const int64_t at = out.begin[(size_t)e];
+                const bool inside_row = !rs.starts(at);
+                bool same_row = false;
+                if (inside_row && previous_cut_inside_row) {
+                    same_row = true;
+                    for (int64_t i = out.begin[(size_t)e - 1] + 1; i < at && same_row; ++i) same_row = !rs.starts(i);
+                }
+                if (inside_row && !same_row) {
+                    n_hot += 1;
+                    if (n_hot <= hot_slots) out.hot_pos.push_back(at);
+                }
+                previous_cut_inside_row = inside_row;
+            }
+            if (n_hot > hot_slots || hot_first + n_hot >= ((int64_t)1 << 27)) {
+                // more cut rows than slots (or than `hot` can index): this block keeps none in LDS
+                out.hot_pos.resize((size_t)hot_first);
+                n_hot = 0;
+            }
+            blk.hot = (int32_t)((hot_first << 4) | n_hot);
+            out.max_hot = std::max(out.max_hot, n_hot);
             out.blocks.push_back(blk);
             out.ring[(size_t)L] = blk;
         }
         out.stratum_block[(size_t)s + 1] = (int64_t)out.blocks.size();
     }
+}
+
+int32_t widest_strip(const Partition& part)
+{
+    int32_t widest = 0;
+    for (int32_t b = 0; b < part.gc; ++b) widest = std::max(widest, part.col_bounds[b + 1] - part.col_bounds[b]);
+    return widest;
+}
+
+int64_t lds_hot_bound(int64_t nnz, int32_t gr, int32_t gc)
+{
+    // at most kMaxHotRows per block, and a cut row has a rating on either side of the cut
+    return std::min<int64_t>((int64_t)kMaxHotRows * gr * gc, nnz / 2 + 1);
 }
 
 int64_t det_entries_bound(int32_t gr, int32_t gc)
@@ -474,7 +518,7 @@ void build_det_lds_schedule(const Partition& part, LdsSchedule& out)
             blk.n_entries = 1;
             blk.col0 = part.col_bounds[b];
             blk.ncols = part.col_bounds[b + 1] - part.col_bounds[b];
-            blk.reserved = 0;
+            blk.hot = 0;
             out.begin.push_back(part.block_ptr[L]);
             out.len.push_back((int32_t)size);
             out.blocks.push_back(blk);

@@ -357,6 +357,7 @@ def test_ring_kernel_with_an_order_gives_up_cleanly_when_its_wait_limit_is_tiny(
 
 # ------------------------------------------------------------------------------- every rating exactly once, in every Hogwild kernel
 @pytest.mark.parametrize("kernel,ring,grid", [("lds", 1, (16, 16)), ("lds", 1, (8, 40)), ("lds", 1, (33, 40)),
+                                              ("lds", 1, (8, 37)), ("lds", 1, (3, 40)),
                                               ("lds", 0, (16, 16)), ("lds", 0, (8, 40)),
                                               ("global_atomics", 0, (8, 8))])
 def test_hogwild_visits_every_rating_exactly_once(mfmod, kernel, ring, grid):
@@ -383,6 +384,42 @@ def test_hogwild_visits_every_rating_exactly_once(mfmod, kernel, ring, grid):
     oracle.sgd_epoch_omp(Po, Qo, ds.rows, ds.cols, ds.vals, perm, bp, gr, gc, lr, lam)
     assert np.abs(Po - P0).max() > 5e-5                      # the epoch does move the factors
     assert np.abs(P - Po).max() <= 6e-7 and np.abs(Q - Qo).max() <= 1.2e-6, (np.abs(P - Po).max(), np.abs(Q - Qo).max())
+
+
+@pytest.mark.parametrize("ring,waves,gc", [(1, 0, 6), (0, 0, 6), (1, 5, 6), (1, 0, 13)])
+def test_hogwild_visits_the_pieces_of_cut_rows_exactly_once(mfmod, ring, waves, gc):
+    """The same first-order argument for rows so long that the LDS kernel shares them out over
+    several wavefronts and keeps their p_u in LDS while the block runs: two rows with 20 000 and
+    12 000 ratings move by about 3e-3 at lr = 1e-6; the order of their ratings matters to about
+    6e-6 and the 2^-24 grid of the LDS copy to about 4e-6, while a piece that is skipped or applied
+    twice (a fourteenth of the row or more) moves the row by 2e-4."""
+    ds = dataset("tiny")
+    cfg = ds.cfg
+    rows = ds.rows.copy()
+    rows[:20000] = 7
+    rows[20000:32000] = 1500
+    gr, lr, lam = 4, 1e-6, 0.0
+    options = {mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS, mfmod.MF_OPT_RING: ring}
+    if waves:
+        options[mfmod.MF_OPT_LDS_WAVES] = waves
+    model = mfmod.MatrixFactorization(cfg.m, cfg.n, 32, "f32", seed=1, scale=0.1, options=options)
+    model.load_blocks(rows, ds.cols, ds.vals, gr, gc, 1)
+    model.sgd_epoch(lr, lam, mfmod.MF_MODE_HOGWILD)
+    P, Q = model.get_factors()
+    model.close()
+    perm, bp, _, _ = oracle.partition(rows, ds.cols, cfg.m, cfg.n, gr, gc, 1)
+    P0, Q0 = oracle_init(cfg.m, cfg.n, 32, 1, 0.1)
+    Po, Qo = P0.copy(), Q0.copy()
+    oracle.sgd_epoch_omp(Po, Qo, rows, ds.cols, ds.vals, perm, bp, gr, gc, lr, lam)
+    long_rows = np.array([7, 1500])
+    others = np.setdiff1d(np.arange(cfg.m), long_rows)
+    assert np.abs(Po[long_rows] - P0[long_rows]).max() > 1e-3
+    d_long = float(np.abs(P[long_rows] - Po[long_rows]).max())
+    d_rest = float(np.abs(P[others] - Po[others]).max())
+    d_q = float(np.abs(Q - Qo).max())
+    print("cut rows exactly once, ring=%d waves=%d: long rows %.2e, other rows %.2e, Qt %.2e" % (ring, waves, d_long, d_rest, d_q),
+          flush=True)
+    assert d_long <= 3e-5 and d_rest <= 6e-7 and d_q <= 2e-6, (d_long, d_rest, d_q)
 
 
 def test_suggested_grids_train_to_the_oracle_result(mfmod):

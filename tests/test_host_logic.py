@@ -147,6 +147,38 @@ def test_lds_work_list_covers_every_rating_once_block_by_block(grid):
                     assert pu[eb[e] - 1] != pu[eb[e]] or raw_len[e - 1] < 0
 
 
+@pytest.mark.parametrize("chunk", [0, 6, 48])
+@pytest.mark.parametrize("grid", [(1, 1), (3, 4), (8, 8)])
+def test_cut_rows_of_the_lds_work_list(grid, chunk):
+    """The rows whose p_u the LDS kernel keeps in LDS are exactly the rows that a boundary between
+    two entries of a block falls into, each listed once per block; a block with more than 8 of
+    them lists none."""
+    gr, gc = grid
+    found_some = False
+    for name, rows, cols, m, n in _cases():
+        if gr > m or gc > n:
+            continue
+        plan = B.mf_plan_host(rows, cols, m, n, gr, gc, B.MF_SPLIT_NNZ_BALANCED, B.MF_PLAN_HOGWILD_LDS, chunk)
+        cut = B.mf_plan_host(rows, cols, m, n, gr, gc, B.MF_SPLIT_NNZ_BALANCED, B.MF_PLAN_LDS_CUT_ROWS, chunk)
+        eb, bp, perm = plan["entry_begin"], plan["block_ptr"], plan["perm"]
+        pu = rows[perm]
+        want = {}
+        for e in range(1, eb.size):
+            b = eb[e]
+            L = int(np.searchsorted(bp, b, side="right") - 1)
+            if b > bp[L] and pu[b - 1] == pu[b]:          # the boundary before entry e lies inside a row
+                want.setdefault(L, set()).add(int(pu[b]))
+        want = {L: r for L, r in want.items() if len(r) <= 8}
+        got = {}
+        for pos, L in zip(cut["entry_begin"], cut["entry_len"]):
+            assert bp[L] <= pos < bp[L + 1], name
+            assert int(pu[pos]) not in got.setdefault(int(L), set()), name     # once per block
+            got[int(L)].add(int(pu[pos]))
+        assert got == want, (name, grid, chunk)
+        found_some = found_some or bool(want)
+    assert found_some or (grid, chunk) == ((1, 1), 6)     # there the one block has more than 8 cut rows
+
+
 def test_plan_rejects_bad_arguments():
     rows = np.array([0, 1, 2], np.int32)
     cols = np.array([0, 1, 5], np.int32)
