@@ -759,7 +759,7 @@ def test_medium_config_scaled_det_and_hogwild(mfmod):
 
 def test_medium_config_full_size(mfmod):
     """Configuration 2 at its full size, in the launch configuration the benchmark times
-    (HOGWILD, 256 x 256 grid, LDS kernel with 12 wavefronts per workgroup, one launch per epoch,
+    (HOGWILD, 256 x 256 grid, LDS kernel with the library's choice of wavefronts per workgroup, one launch per epoch,
     partitioned on the device) plus the deterministic mode on a fine grid."""
     ds = dataset("medium")
     k = ds.cfg.k
@@ -772,8 +772,7 @@ def test_medium_config_full_size(mfmod):
     Po, Qo, _ = oracle_train(ds, 256, 256, 1, epochs)
     want = oracle.rmse(Po, Qo, ds.test_rows, ds.test_cols, ds.test_vals)
     model = mfmod.MatrixFactorization(ds.cfg.m, ds.cfg.n, k, "f32", seed=1, scale=0.1,
-                                      options={mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS,
-                                               mfmod.MF_OPT_LDS_WAVES: 12})
+                                      options={mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS})
     dev = model.P.device
     model.load_blocks_device(*(torch.from_numpy(x).to(dev) for x in (ds.rows, ds.cols, ds.vals)), 256, 256, 1)
     tr, tc, tv = model.to_device(ds.test_rows, ds.test_cols, ds.test_vals)
