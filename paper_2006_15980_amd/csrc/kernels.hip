@@ -8,7 +8,8 @@
 //                   (deterministic mode on any grid; Hogwild fallback with L2 atomics).
 //   sgd_block_lds : one workgroup per block of a stratum; the block's strip of Qt lives in LDS
 //                   (fp32 for the deterministic mode, 32-bit fixed point + integer atomics for
-//                   Hogwild), rows of P stream through registers.
+//                   Hogwild), rows of P stream through registers; in Hogwild mode the few rows
+//                   of P that are shared out over several wavefronts sit in LDS beside the strip.
 //   sgd_ring_lds  : the same block body, one launch per epoch: workgroup a keeps block row a and
 //                   the column strips are handed from workgroup to workgroup with bounded waits.
 //   rmse_partial / rmse_final : sum of squared prediction errors (Eq. 1 against the rating),
