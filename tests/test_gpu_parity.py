@@ -386,8 +386,9 @@ def test_hogwild_visits_every_rating_exactly_once(mfmod, kernel, ring, grid):
     assert np.abs(P - Po).max() <= 6e-7 and np.abs(Q - Qo).max() <= 1.2e-6, (np.abs(P - Po).max(), np.abs(Q - Qo).max())
 
 
-@pytest.mark.parametrize("ring,waves,gc", [(1, 0, 6), (0, 0, 6), (1, 5, 6), (1, 0, 13)])
-def test_hogwild_visits_the_pieces_of_cut_rows_exactly_once(mfmod, ring, waves, gc):
+@pytest.mark.parametrize("ring,waves,gc,load", [(1, 0, 6, "host"), (0, 0, 6, "host"), (1, 5, 6, "device"),
+                                                (1, 0, 13, "host"), (0, 0, 6, "streamed")])
+def test_hogwild_visits_the_pieces_of_cut_rows_exactly_once(mfmod, ring, waves, gc, load):
     """The same first-order argument for rows so long that the LDS kernel shares them out over
     several wavefronts and keeps their p_u in LDS while the block runs: two rows with 20 000 and
     12 000 ratings move by about 3e-3 at lr = 1e-6; the order of their ratings matters to about
@@ -403,7 +404,13 @@ def test_hogwild_visits_the_pieces_of_cut_rows_exactly_once(mfmod, ring, waves, 
     if waves:
         options[mfmod.MF_OPT_LDS_WAVES] = waves
     model = mfmod.MatrixFactorization(cfg.m, cfg.n, 32, "f32", seed=1, scale=0.1, options=options)
-    model.load_blocks(rows, ds.cols, ds.vals, gr, gc, 1)
+    if load == "device":
+        d = model.P.device
+        model.load_blocks_device(*(torch.from_numpy(x).to(d) for x in (rows, ds.cols, ds.vals)), gr, gc, 1)
+    elif load == "streamed":
+        model.load_blocks_streamed(rows, ds.cols, ds.vals, gr, gc, 1)
+    else:
+        model.load_blocks(rows, ds.cols, ds.vals, gr, gc, 1)
     model.sgd_epoch(lr, lam, mfmod.MF_MODE_HOGWILD)
     P, Q = model.get_factors()
     model.close()
