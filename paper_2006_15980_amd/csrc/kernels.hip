@@ -1140,7 +1140,10 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_ring_lds(
                     if (must_wait) {
                         long long polls = 0;
                         while (__hip_atomic_load(done + waits_on, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < need) {
-                            if (__hip_atomic_load(abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                            // every poll is a round trip to memory: the abort flag is looked at on
+                            // every 16th only, so that the counter is read twice as often
+                            if ((polls & 15) == 15 &&
+                                __hip_atomic_load(abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
                                 ok = 0;
                                 break;
                             }
