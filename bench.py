@@ -20,69 +20,85 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
-# Memory-side bytes per launch of the dominant kernel, from the rocprofv3 counter passes summarised
-# under profiles/ (FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter reads for a plain
-# device copy of known size).  Counters cannot be read from inside this process, so the figure is
-# reported only for the exact configuration that was profiled, otherwise null.
-PROFILED_TRAFFIC = {
-    # (workload, scale, mode, grid, kernel, ring, lds_waves): bytes per launch
-    ("medium", 1.0, "hogwild", "256x256", "lds", 1, 0): 5732.6e6,   # profiles/sgd_ring_lds_f32_k128_medium.md
+# Launch configuration per workload: grid, split rule, scale of the initial factors.  The default
+# workload is the largest fp32 one (the Yahoo!Music shape of the paper's Table 1), where the
+# factors (833 MB) exceed every cache and the HBM roofline binds.
+WORKLOAD_DEFAULTS = {
+    "tiny": ("16x16", 1, 0.1),
+    "medium": ("256x256", 1, 0.1),
+    "large": ("224x224", 1, 0.1),
+    "xlarge": ("256x4096", 2, 1.25),
+    "stress": ("256x6400", 2, 0.1),
 }
+CPU_SAMPLE = 16_000_000     # ratings of the workload the CPU oracle is timed on
+
+
+def profiled_traffic(key):
+    """Memory-side bytes per launch of the dominant kernel for this exact configuration, from the
+    rocprofv3 counter passes summarised under profiles/ (FETCH_SIZE and WRITE_SIZE, each scaled by
+    what the same counter reads for a plain device copy of known size).  Counters cannot be read
+    from inside this process; a summary carries a line `bench-key: <key> traffic_bytes_per_launch=<n>`.
+    Returns (bytes, file name) or (None, None)."""
+    folder = os.path.join(ROOT, "profiles")
+    try:
+        names = sorted(os.listdir(folder))
+    except OSError:
+        return None, None
+    for name in names:
+        if not name.endswith(".md"):
+            continue
+        with open(os.path.join(folder, name)) as fh:
+            for line in fh:
+                if line.startswith("bench-key:") and f" {key} " in line + " ":
+                    for word in line.split():
+                        if word.startswith("traffic_bytes_per_launch="):
+                            return float(word.split("=", 1)[1]), name
+    return None, None
 
 
 def load_dataset(name, factor):
-    import numpy as np
-
     import workloads
 
-    cfg = workloads.scaled(workloads.CONFIGS[name], factor)
-    cache = os.environ.get("MF_DATA_CACHE", os.path.join(ROOT, ".cache"))
-    path = os.path.join(cache, f"{name}_{factor:g}_seed{cfg.seed}.npz")
-    fields = ["rows", "cols", "vals", "test_rows", "test_cols", "test_vals", "max_row_degree",
-              "max_col_degree", "median_row_degree", "median_col_degree"]
-    if os.path.exists(path):
-        z = np.load(path)
-        return workloads.Dataset(cfg, *[z[f] if z[f].ndim else z[f].item() for f in fields])
-    ds = workloads.generate(cfg)
-    try:
-        os.makedirs(cache, exist_ok=True)
-        np.savez(path, **{f: getattr(ds, f) for f in fields})
-    except OSError:
-        pass
-    return ds
+    return workloads.load(name, factor, keep=False)
 
 
-def cpu_baseline(ds, gr, gc, k, split):
-    """The oracle as it stands, timed on the host cores: one epoch with the independent blocks
-    of every stratum on OpenMP threads (bit-identical to the serial order), and the serial
-    oracle on a prefix of the strata."""
-    import numpy as np
-
+def cpu_baseline(ds, gr, gc, k, split, scale):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the workload: the
+    first CPU_SAMPLE training ratings in the data's own (seeded, unsorted) order, partitioned by
+    the oracle on the same grid and split rule, whole epochs with the independent blocks of every
+    stratum on OpenMP threads (bit-identical to the serial order), and the serial oracle on the
+    sample's first stratum."""
     import oracle
 
     cfg = ds.cfg
-    perm, bp, _, _ = oracle.partition(ds.rows, ds.cols, cfg.m, cfg.n, gr, gc, split)
-    P = oracle.init_factors(cfg.m * k, 1, 0, 0.1).reshape(cfg.m, k)
-    Q = oracle.init_factors(cfg.n * k, 1, 1, 0.1).reshape(cfg.n, k)
-    # whole epochs until about ten seconds of wall-clock have passed (at least one, at most 64)
+    take = min(CPU_SAMPLE, ds.rows.size)
+    rows, cols, vals = ds.rows[:take], ds.cols[:take], ds.vals[:take]
+    perm, bp, _, _ = oracle.partition(rows, cols, cfg.m, cfg.n, gr, gc, split)
+    P = oracle.init_factors(cfg.m * k, 1, 0, scale).reshape(cfg.m, k)
+    Q = oracle.init_factors(cfg.n * k, 1, 1, scale).reshape(cfg.n, k)
+    # whole epochs over the sample until about ten seconds have passed (at least one, at most 64)
     epochs = 0
     t0 = time.perf_counter()
     while epochs < 64 and (epochs == 0 or time.perf_counter() - t0 < 10.0):
-        oracle.sgd_epoch_omp(P, Q, ds.rows, ds.cols, ds.vals, perm, bp, gr, gc, cfg.lr, cfg.lam)
+        oracle.sgd_epoch_omp(P, Q, rows, cols, vals, perm, bp, gr, gc, cfg.lr, cfg.lam)
         epochs += 1
     t_omp = (time.perf_counter() - t0) / epochs
-    # serial: the first stratum only (a bounded sample of the same epoch)
-    bp1 = bp[: gr + 1].copy()
+    # serial: the sample's first strata, about a million ratings
+    strata = 1
+    while strata < gc and bp[strata * gr] < 1_000_000:
+        strata += 1
+    bp1 = bp[: strata * gr + 1].copy()
     n1 = int(bp1[-1])
     t0 = time.perf_counter()
-    oracle.sgd_epoch(P, Q, ds.rows, ds.cols, ds.vals, perm, bp1, gr, 1, cfg.lr, cfg.lam)
+    oracle.sgd_epoch(P, Q, rows, cols, vals, perm, bp1, gr, strata, cfg.lr, cfg.lam)
     t_ser = time.perf_counter() - t0
     threads = min(oracle.num_threads(), gr)
-    return {"value": ds.rows.size / t_omp, "unit": "updates/s", "cores": threads, "kind": "oracle",
-            "sample": f"{epochs} full epochs ({ds.rows.size} updates each) of the same workload and grid, fp64 oracle, "
+    what = "the whole training set" if take == ds.rows.size else f"the first {take} of {ds.rows.size} training ratings (seeded order)"
+    return {"value": take / t_omp, "unit": "updates/s", "cores": threads, "kind": "oracle",
+            "sample": f"{epochs} epochs over {what}, grid {gr}x{gc}, split {split}, fp64 oracle, "
                       f"independent blocks of each stratum on {threads} OpenMP threads",
-            "serial_value": n1 / t_ser, "serial_cores": 1,
-            "serial_sample": f"stratum 0 of the same epoch ({n1} updates) on one core",
+            "serial_value": n1 / max(t_ser, 1e-9), "serial_cores": 1,
+            "serial_sample": f"the first {strata} strata of the same sample ({n1} updates) on one core",
             "host_cores": len(os.sched_getaffinity(0))}
 
 
@@ -91,17 +107,19 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="medium")
+    ap.add_argument("--workload", default="xlarge", choices=sorted(WORKLOAD_DEFAULTS))
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (testing only)")
-    ap.add_argument("--init-scale", type=float, default=0.1, help="initial factors are uniform in [0, this)")
+    ap.add_argument("--init-scale", type=float, default=None,
+                    help="initial factors are uniform in [0, this); default: the workload's (WORKLOAD_DEFAULTS)")
     ap.add_argument("--mode", default="hogwild", choices=["hogwild", "det"])
-    ap.add_argument("--grid", default="256x256")
+    ap.add_argument("--grid", default=None, help="GRxGC; default: the workload's (WORKLOAD_DEFAULTS)")
     ap.add_argument("--hogwild-kernel", default="auto", choices=["auto", "global_atomics", "lds"])
     ap.add_argument("--lds-chunk", type=int, default=0)
     ap.add_argument("--lds-waves", type=int, default=0, help="0: the library's choice")
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--affinity", type=int, default=1)
-    ap.add_argument("--split", type=int, default=1, help="0 equal width, 1 ratings balanced, 2 ratings and width balanced")
+    ap.add_argument("--split", type=int, default=None,
+                    help="0 equal width, 1 ratings balanced, 2 ratings and width balanced; default: the workload's")
     ap.add_argument("--ring", type=int, default=1, help="1: one launch per epoch (workgroups hand the strips round)")
     ap.add_argument("--load", default="device", choices=["host", "device"],
                     help="partition on the host (mf_load_blocks) or on the GPU (mf_load_blocks_device); outside the timed region")
@@ -134,7 +152,13 @@ def main():
         print(json.dumps({"copy_calibration_mib": args.copy_calibration, "bytes_read": n * 4, "bytes_written": n * 4,
                           "launches": 5}))
         return
+    d_grid, d_split, d_scale = WORKLOAD_DEFAULTS[args.workload]
+    args.grid = args.grid or d_grid
+    args.split = d_split if args.split is None else args.split
+    args.init_scale = d_scale if args.init_scale is None else args.init_scale
+    t0 = time.perf_counter()
     ds = load_dataset(args.workload, args.scale)
+    t_generate = time.perf_counter() - t0
     cfg = ds.cfg
     gr, gc = (int(x) for x in args.grid.split("x"))
     mode = mf.MF_MODE_HOGWILD if args.mode == "hogwild" else mf.MF_MODE_DET
@@ -166,6 +190,9 @@ def main():
         t_load = time.perf_counter() - t0
     tr, tc, tv = model.to_device(ds.test_rows, ds.test_cols, ds.test_vals)
     nnz = ds.rows.size
+    plan = model.epoch_plan(mode)     # the kernel the library launches for this mode and grid
+    print(f"bench: {cfg.name} generated in {t_generate:.1f} s, loaded in {t_load:.2f} s; {plan['note']}",
+          file=sys.stderr, flush=True)
 
     def run_steps(count):
         last = float("nan")
@@ -202,18 +229,26 @@ def main():
         avg_s = kernel_ms * 1e-3 / launches
         bytes_per_launch = bytes_per_update * nnz * args.steps / launches
         achieved = bytes_per_launch / avg_s / 1e9
-        kern = "lds" if (args.mode == "hogwild" and args.hogwild_kernel != "global_atomics") else "chunks"
-        traffic = PROFILED_TRAFFIC.get((args.workload, args.scale, args.mode, args.grid, kern, args.ring, args.lds_waves))
-        if args.lds_chunk != 0 or args.split != 1:
-            traffic = None
+        # `achieved` counts ALGORITHMIC bytes (12 + 4*k*sizeof(storage) per update): what the path
+        # would move without any reuse.  The kernel keeps column strips in LDS and rows in the
+        # L2s, so it can exceed what the memory really carried; `traffic` is that real figure,
+        # taken from the counter passes summarised in `traffic_source`, not measured in this run.
+        key = (f"workload={args.workload} scale={args.scale:g} mode={args.mode} grid={args.grid} split={args.split} "
+               f"kernel={plan['kernel']} waves={plan['waves']}")
+        traffic, source = profiled_traffic(key)
+        if args.lds_chunk != 0 or args.chunk != 0 or not args.affinity:
+            traffic, source = None, None
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": (("sgd_ring_lds" if args.ring else "sgd_block_lds") if kern == "lds" else "sgd_chunks")
-                    + "<%s,%d>" % ("float" if cfg.storage == "f32" else "__half", k),
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                    "traffic_source": None if source is None else "profiles/" + source,
+                    "kernel": "%s<%s,%d>" % (plan["kernel"], "float" if cfg.storage == "f32" else "__half", k),
+                    "waves_per_workgroup": plan["waves"],
                     "avg_launch_us": avg_s * 1e6, "launches_per_step": launches / args.steps,
+                    "updates_per_launch": nnz * args.steps / launches,
                     "bytes_per_update": bytes_per_update,
-                    # what the memory side really moved per second (counters), next to the algorithmic figure:
-                    # the strip of Qt lives in LDS and P mostly in the L2s, so it is far below `achieved`
                     "traffic_gbs": None if traffic is None else traffic / avg_s / 1e9,
+                    "traffic_frac_of_peak": None if traffic is None else traffic / avg_s / 1e9 / HBM_PEAK_GBS,
+                    "profile_key": key,
                     "ms_per_step_with_event_brackets": elapsed_events * 1e3 / args.steps}
     out = {"metric": "SGD updates/s at k=128 (HOGWILD epoch + held-out RMSE per step)", "value": value,
            "unit": "updates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -221,17 +256,18 @@ def main():
            "vs_baseline": None, "dtype": "f32" if cfg.storage == "f32" else "f16 storage / f32 math",
            "data": "synthetic",
            "config": {"workload": f"{cfg.name}: m={cfg.m} n={cfg.n} nnz_train={nnz} k={k} {cfg.storage}",
-                      "mode": args.mode, "grid": args.grid, "split": args.split, "hogwild_kernel": args.hogwild_kernel,
+                      "mode": args.mode, "grid": args.grid, "split": args.split, "init_scale": args.init_scale,
+                      "hogwild_kernel": args.hogwild_kernel,
                       "lds_chunk": args.lds_chunk, "lds_waves": args.lds_waves, "ring": args.ring,
                       "chunk": args.chunk,
                       "xcd_affinity": args.affinity,
                       "lr": cfg.lr, "lambda": cfg.lam},
-           "final_test_rmse": rmse, "load_blocks_s": t_load, "load_path": args.load,
+           "final_test_rmse": rmse, "generate_s": t_generate, "load_blocks_s": t_load, "load_path": args.load,
            "algorithmic_gbs": value * bytes_per_update / 1e9,
            "hbm_roofline_frac": value * bytes_per_update / 1e9 / HBM_PEAK_GBS,
            "roofline": roofline}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(ds, gr, gc, k, args.split)
+        out["cpu_baseline"] = cpu_baseline(ds, gr, gc, k, args.split, args.init_scale)
     print(json.dumps(out))
 
 

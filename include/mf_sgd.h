@@ -40,8 +40,9 @@ enum {
     MF_EINVAL = -1,   /* bad argument                                   */
     MF_ESTATE = -2,   /* call out of order (e.g. epoch before load)     */
     MF_ENOMEM = -3,   /* workspace too small / host allocation failed   */
-    MF_EDEVICE = -4,  /* a HIP call failed                              */
-    MF_ERANGE = -5    /* a row / column index outside [0,m) / [0,n)     */
+    MF_EDEVICE = -4,  /* a HIP call failed, or the one-launch kernel gave up a wait */
+    MF_ERANGE = -5    /* a row / column index outside [0,m) / [0,n); or a factor  */
+                      /* left the range of the Hogwild kernel's fixed-point strip */
 };
 
 enum { MF_F32 = 0, MF_F16 = 1 };               /* storage type of the factors; arithmetic is fp32 */
@@ -81,6 +82,7 @@ enum {
 enum { MF_KERNEL_AUTO = 0, MF_KERNEL_GLOBAL = 1, MF_KERNEL_LDS = 2 };
 enum { MF_HOGWILD_AUTO = MF_KERNEL_AUTO, MF_HOGWILD_GLOBAL_ATOMICS = MF_KERNEL_GLOBAL, MF_HOGWILD_LDS = MF_KERNEL_LDS };
 enum { MF_PLAN_HOGWILD_LDS = 2, MF_PLAN_LDS_CUT_ROWS = 3 };  /* values of `mode` accepted by mf_plan_host only */
+enum { MF_KERNEL_ID_CHUNKS = 1, MF_KERNEL_ID_BLOCK_LDS = 2, MF_KERNEL_ID_RING_LDS = 3 };  /* see mf_epoch_plan */
 
 /* Create a context on HIP device `device`.  `hip_stream` is a hipStream_t of the caller (may be
  * NULL for the default stream); all work of this context is enqueued on it. */
@@ -209,9 +211,30 @@ int mf_get_partition(const mf_ctx* ctx, int64_t* perm, int64_t* block_ptr,
  * With the LDS kernels and MF_OPT_RING = 1 the epoch is a single launch: workgroup a keeps block
  * row a, walks the strata in order and waits (bounded) for the workgroup that used its next column
  * strip last.  The order of the steps, and in MF_MODE_DET every bit of the result, is the same as
- * with one launch per stratum.  If a wait exceeds its limit all workgroups leave the kernel and
- * the next mf_sync / mf_rmse returns MF_EDEVICE. */
+ * with one launch per stratum.  That kernel needs all grid_r workgroups on the device at the same
+ * time: it is taken only when an otherwise idle device holds them, and the device should not be
+ * shared while it runs.  If a wait exceeds its limit (MF_OPT_RING_SPIN_LIMIT) all workgroups leave
+ * the kernel, the epoch is abandoned half-applied, the next mf_sync / mf_rmse returns MF_EDEVICE
+ * once, and later epochs on this load run one launch per stratum, which needs no co-residency.
+ * Divergence: MF_HOGWILD_LDS watches its fixed-point strip; when it reads a value of magnitude >= 64
+ * or makes a single change of magnitude >= 4 (both far outside honest training; beyond +-128 a
+ * strip word would wrap round) the next mf_sync / mf_rmse returns MF_ERANGE once; the factors are
+ * then meaningless. */
 int mf_sgd_epoch(mf_ctx* ctx, float lr, float lambda, int32_t mode);
+
+/* What mf_sgd_epoch(mode) launches for the loaded grid, decided exactly as the epoch call decides it
+ * (the choice depends on the grid: strips that do not fit the LDS, or more block rows than the device
+ * holds workgroups at once, fall back to slower kernels, and a grid made for MF_MODE_HOGWILD is
+ * usually a poor one for MF_MODE_DET).  Outputs are HOST pointers, any may be NULL:
+ *   kernel_out   MF_KERNEL_ID_CHUNKS    one wavefront per work-list entry, Qt in memory, one launch per
+ *                                       non-empty stratum;
+ *                MF_KERNEL_ID_BLOCK_LDS one workgroup per block, the strip of Qt in LDS, one launch per
+ *                                       non-empty stratum;
+ *                MF_KERNEL_ID_RING_LDS  the same, one launch per epoch;
+ *   launches_out kernel launches per epoch;   waves_out wavefronts per workgroup.
+ * On success mf_last_error() returns a one-line description of the choice and, when a faster kernel
+ * was not taken, the reason.  MF_ESTATE before mf_load_blocks. */
+int mf_epoch_plan(mf_ctx* ctx, int32_t mode, int32_t* kernel_out, int64_t* launches_out, int32_t* waves_out);
 
 /* One epoch with the strata visited in a given order (the paper's scheduler hands blocks out
  * "randomly", Section 3.1; Example 3 argues for balanced, random visiting): stratum_order is a HOST

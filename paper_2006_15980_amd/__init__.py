@@ -97,6 +97,11 @@ class MatrixFactorization:
                 raise ValueError("stratum_order needs grid_c entries")
             binding.mf_sgd_epoch_ordered(self.ctx, lr, lam, mode, np.ascontiguousarray(stratum_order, np.int32))
 
+    def epoch_plan(self, mode: int) -> dict:
+        """What sgd_epoch(mode) launches on the loaded grid (mf_epoch_plan)."""
+        kernel, launches, waves, note = binding.mf_epoch_plan(self.ctx, mode)
+        return {"kernel": binding.KERNEL_NAMES[kernel], "launches": launches, "waves": waves, "note": note}
+
     def rmse(self, rows=None, cols=None, vals=None) -> float:
         if rows is None:
             return binding.mf_rmse(self.ctx, None, None, None, 0)

@@ -25,13 +25,16 @@ MF_KERNEL_AUTO, MF_KERNEL_GLOBAL, MF_KERNEL_LDS = 0, 1, 2
 MF_HOGWILD_AUTO, MF_HOGWILD_GLOBAL_ATOMICS, MF_HOGWILD_LDS = 0, 1, 2
 MF_PLAN_HOGWILD_LDS = 2
 MF_PLAN_LDS_CUT_ROWS = 3
+MF_KERNEL_ID_CHUNKS, MF_KERNEL_ID_BLOCK_LDS, MF_KERNEL_ID_RING_LDS = 1, 2, 3
+KERNEL_NAMES = {MF_KERNEL_ID_CHUNKS: "sgd_chunks", MF_KERNEL_ID_BLOCK_LDS: "sgd_block_lds",
+                MF_KERNEL_ID_RING_LDS: "sgd_ring_lds"}
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmf_sgd.so")
 
 EXPORTS = ["mf_create", "mf_destroy", "mf_last_error", "mf_set_option", "mf_init",
            "mf_load_blocks_workspace", "mf_load_blocks", "mf_load_blocks_device",
            "mf_load_blocks_streamed_workspace", "mf_load_blocks_streamed", "mf_get_partition", "mf_sgd_epoch",
-           "mf_sgd_epoch_ordered", "mf_stratum_order",
+           "mf_sgd_epoch_ordered", "mf_stratum_order", "mf_epoch_plan",
            "mf_rmse", "mf_sync", "mf_profile_read", "mf_debug_xcc_ids", "mf_plan_host", "mf_suggest_grid"]
 
 
@@ -66,6 +69,7 @@ def lib() -> C.CDLL:
         l.mf_get_partition.argtypes = [vp, vp, vp, vp, vp]
         l.mf_sgd_epoch.argtypes = [vp, f32, f32, i32]
         l.mf_sgd_epoch_ordered.argtypes = [vp, f32, f32, i32, vp]
+        l.mf_epoch_plan.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i64), C.POINTER(i32)]
         l.mf_stratum_order.argtypes = [C.c_uint64, C.c_uint64, i32, vp]
         l.mf_rmse.argtypes = [vp, vp, vp, vp, i64, C.POINTER(C.c_double)]
         l.mf_sync.argtypes = [vp]
@@ -173,6 +177,13 @@ def mf_sgd_epoch(ctx: int, lr: float, lam: float, mode: int) -> None:
 def mf_sgd_epoch_ordered(ctx: int, lr: float, lam: float, mode: int, stratum_order: Optional[np.ndarray]) -> None:
     order = None if stratum_order is None else _host(stratum_order, np.int32)
     _check(ctx, lib().mf_sgd_epoch_ordered(ctx, lr, lam, mode, order))
+
+
+def mf_epoch_plan(ctx: int, mode: int):
+    """-> (kernel id, launches per epoch, wavefronts per workgroup, the library's description)"""
+    kernel, launches, waves = C.c_int32(), C.c_int64(), C.c_int32()
+    _check(ctx, lib().mf_epoch_plan(ctx, mode, C.byref(kernel), C.byref(launches), C.byref(waves)))
+    return kernel.value, launches.value, waves.value, lib().mf_last_error(ctx).decode()
 
 
 def mf_stratum_order(seed: int, epoch: int, grid_c: int) -> np.ndarray:

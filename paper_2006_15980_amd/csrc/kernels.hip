@@ -399,6 +399,36 @@ __device__ __forceinline__ int to_fixed(float x)
 
 __device__ __forceinline__ float from_fixed(int x) { return (float)x * kFromFixed; }
 
+// Range watch of the fixed-point strip.  A strip word wraps round at +-2^31 (+-128.0).  Every add
+// of a wavefront follows its own read of the same word, and at most 16 wavefronts add to a strip
+// at a time, so no word can reach +-2^31 as long as every value READ stays below kWatchValue and
+// every single change below kWatchChange (2^30 + 16 * 2^26 = 2^31); the value a block leaves behind
+// is checked when the strip is written back.  Values and changes of honest training are orders of
+// magnitude smaller, so a hit means the training has diverged; it raises a flag that the host
+// reports as MF_ERANGE.  Both limits in the strip's scale (value * 2^24).
+constexpr float kWatchValue = 1073741824.f;   // 2^30 = 64.0
+constexpr float kWatchChange = 67108864.f;    // 2^26 =  4.0
+constexpr float kWatchPlain = 64.f;           // the same value limit for numbers not yet scaled
+
+struct RangeWatch {
+    float value = 0.f, change = 0.f;           // per lane: largest magnitudes seen
+    bool out = false;                          // per lane: a value met outside the strip's range
+    template <int VEC>
+    __device__ __forceinline__ void see(const Row<VEC>& scaled_q, const Row<VEC>& scaled_dq)
+    {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+            value = fmaxf(value, fabsf(scaled_q.x[j]));
+            change = fmaxf(change, fabsf(scaled_dq.x[j]));
+        }
+    }
+    __device__ __forceinline__ void see_plain(float x) { out |= !(fabsf(x) < kWatchPlain); }
+    __device__ __forceinline__ bool hit() const
+    {
+        return out || !(value < kWatchValue) || !(change < kWatchChange);
+    }
+};
+
 // EXACT = the strip holds fp32 bit patterns (deterministic mode), else fixed point (Hogwild).
 template <typename T, int VEC, bool EXACT = false>
 __device__ __forceinline__ Row<VEC> strip_read(const int* qrow, int lane, bool active)
@@ -566,7 +596,7 @@ __device__ __forceinline__ void lds_hog_chunk(T* __restrict__ P, int* strip, int
                                               const float* __restrict__ R, int64_t begin, int32_t len,
                                               int mu, int mv, float mr,
                                               RowRing<RowShape<T, K>::VEC, DEPTH> first_rows, float lr,
-                                              float shrink, int lane, bool active)
+                                              float shrink, int lane, bool active, RangeWatch& watch)
 {
     constexpr int VEC = RowShape<T, K>::VEC;
     Row<VEC> p_prev;
@@ -637,13 +667,15 @@ __device__ __forceinline__ void lds_hog_chunk(T* __restrict__ P, int* strip, int
                 const float step_q = step * kFromFixed;   // (lr*e) * q       = step_q * qs
                 const float step_p = step * kToFixed;     // (lr*e) * p * 2^24 = step_p * p
                 int* const qrow = strip + (v - col0) * K;
-                Row<VEC> p2;
+                Row<VEC> p2, dqs;
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) {
                     p2.x[j] = quantise<T>(fmaf(step_q, qs.x[j], fmaf(-sh, p.x[j], p.x[j])));
-                    const int dq = __float2int_rn(fmaf(step_p, p.x[j], -sh * qs.x[j]));
+                    dqs.x[j] = fmaf(step_p, p.x[j], -sh * qs.x[j]);
+                    const int dq = __float2int_rn(dqs.x[j]);
                     if (active) atomicAdd(&qrow[strip_elem<T>(lane, j)], dq);
                 }
+                watch.see<VEC>(qs, dqs);
                 store_row<VEC>(row_of(u), lane, active, p2);
                 qs = read_scaled(uniform_lane(mv, min(i + 1, last)));   // after the add above
                 p_prev = p2;
@@ -665,7 +697,7 @@ __device__ __forceinline__ void lds_shared_row_chunk(T* __restrict__ P, int* str
                                                      const int32_t* __restrict__ V,
                                                      const float* __restrict__ R, int64_t begin,
                                                      int32_t len, float lr, float shrink, int lane,
-                                                     bool active)
+                                                     bool active, RangeWatch& watch)
 {
     constexpr int VEC = RowShape<T, K>::VEC;
     for (int32_t off = 0; off < len; off += kWave) {
@@ -695,7 +727,10 @@ __device__ __forceinline__ void lds_shared_row_chunk(T* __restrict__ P, int* str
 #pragma unroll
             for (int j = 0; j < VEC; ++j) {
                 dp.x[j] = fmaf(step, q.x[j], -shrink * p.x[j]);
-                const int dq = to_fixed(fmaf(step, p.x[j], -shrink * q.x[j]));
+                const float change = fmaf(step, p.x[j], -shrink * q.x[j]);
+                watch.see_plain(q.x[j]);
+                watch.see_plain(16.f * change);
+                const int dq = to_fixed(change);
                 if (active) atomicAdd(&qrow[strip_elem<T>(lane, j)], dq);
             }
             atomic_add_row<VEC>(P + (int64_t)u * K, lane, active, dp);
@@ -718,7 +753,7 @@ template <typename T, int K>
 __device__ __forceinline__ void lds_hot_row_piece(int* prow, int* strip, int col0,
                                                   const int32_t* __restrict__ V,
                                                   const float* __restrict__ R, int64_t begin, int32_t len,
-                                                  float lr, float shrink, int lane, bool active)
+                                                  float lr, float shrink, int lane, bool active, RangeWatch& watch)
 {
     constexpr int VEC = RowShape<T, K>::VEC;
     int mv = 0, nv = 0;
@@ -745,8 +780,14 @@ __device__ __forceinline__ void lds_hot_row_piece(int* prow, int* strip, int col
             const float step = lr * (r - wave_sum(part));
 #pragma unroll
             for (int j = 0; j < VEC; ++j) {
-                const int dq = to_fixed(fmaf(step, p.x[j], -shrink * q.x[j]));
-                const int dp = to_fixed(fmaf(step, q.x[j], -shrink * p.x[j]));
+                const float change_q = fmaf(step, p.x[j], -shrink * q.x[j]);
+                const float change_p = fmaf(step, q.x[j], -shrink * p.x[j]);
+                watch.see_plain(q.x[j]);
+                watch.see_plain(p.x[j]);
+                watch.see_plain(16.f * change_q);
+                watch.see_plain(16.f * change_p);
+                const int dq = to_fixed(change_q);
+                const int dp = to_fixed(change_p);
                 if (active) {
                     atomicAdd(&qrow[strip_elem<T>(lane, j)], dq);
                     atomicAdd(&prow[strip_elem<T>(lane, j)], dp);
@@ -796,8 +837,9 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
                                                const int64_t* __restrict__ entry_begin,
                                                const int32_t* __restrict__ entry_len,
                                                const int64_t* __restrict__ hot_pos, const LdsBlock blk,
-                                               float lr, float lambda, BeforeStrip before_strip)
+                                               float lr, float lambda, int* range_flag, BeforeStrip before_strip)
 {
+    RangeWatch watch;   // Hogwild only: see RangeWatch
     const int lane = threadIdx.x & (kWave - 1);
     const bool active = RowShape<T, K>::ACTIVE == kWave ? true : lane < RowShape<T, K>::ACTIVE;
     const int total = blk.ncols * K;          // multiple of 32
@@ -841,15 +883,26 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
     }
     if (!before_strip()) return false;
 
-    auto to_strip = [](float x) { return EXACT ? __float_as_int(x) : to_fixed(x); };
-    auto from_strip = [](int x) { return EXACT ? __int_as_float(x) : from_fixed(x); };
+    // values entering and leaving the fixed-point strip are watched (a value of magnitude >= 128
+    // saturates on entry)
+    auto to_strip = [&](float x) {
+        if constexpr (EXACT) return __float_as_int(x);
+        watch.see_plain(x);
+        return to_fixed(x);
+    };
+    auto from_strip = [&](int x) {
+        if constexpr (EXACT) return __int_as_float(x);
+        const float f = from_fixed(x);
+        watch.see_plain(f);
+        return f;
+    };
     if constexpr (!EXACT) {
         // read past the L1: another block may have changed the row with atomics executed in the L2
         for (int slot = wave; slot < n_hot; slot += n_waves) {
             const Row<VEC> p = load_row<VEC, true>(P + (int64_t)uniform_lane(hot_u, slot) * K, lane, active);
 #pragma unroll
             for (int j = 0; j < VEC; ++j)
-                if (active) hot_rows[slot * K + strip_elem<T>(lane, j)] = to_fixed(p.x[j]);
+                if (active) hot_rows[slot * K + strip_elem<T>(lane, j)] = to_strip(p.x[j]);
         }
     }
     if constexpr (COHERENT && !EXACT) {
@@ -980,18 +1033,18 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
                 }
                 if (front > 0)
                     lds_hot_row_piece<T, K>(hot_rows + front_slot * K, strip, blk.col0, V, R, begin, front, lr, shrink,
-                                            lane, active);
+                                            lane, active, watch);
                 if (back > 0)
                     lds_hot_row_piece<T, K>(hot_rows + back_slot * K, strip, blk.col0, V, R, begin + len - back, back,
-                                            lr, shrink, lane, active);
+                                            lr, shrink, lane, active, watch);
                 if (between > 0)
                     lds_hog_chunk<T, K, DEPTH>(P, strip, blk.col0, U, V, R, begin + front, between, mu, mv, mr,
-                                               first_rows, lr, shrink, lane, active);
+                                               first_rows, lr, shrink, lane, active, watch);
             } else if (raw_len < 0)
-                lds_shared_row_chunk<T, K>(P, strip, blk.col0, U, V, R, begin, len, lr, shrink, lane, active);
+                lds_shared_row_chunk<T, K>(P, strip, blk.col0, U, V, R, begin, len, lr, shrink, lane, active, watch);
             else
                 lds_hog_chunk<T, K, DEPTH>(P, strip, blk.col0, U, V, R, begin, len, mu, mv, mr,
-                                                       first_rows, lr, shrink, lane, active);
+                                                       first_rows, lr, shrink, lane, active, watch);
         }
     }
     __syncthreads();
@@ -1001,7 +1054,7 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
             Row<VEC> p;
 #pragma unroll
             for (int j = 0; j < VEC; ++j)
-                p.x[j] = active ? quantise<T>(from_fixed(hot_rows[slot * K + strip_elem<T>(lane, j)])) : 0.f;
+                p.x[j] = active ? quantise<T>(from_strip(hot_rows[slot * K + strip_elem<T>(lane, j)])) : 0.f;
             store_row<VEC>(P + (int64_t)uniform_lane(hot_u, slot) * K, lane, active, p);
         }
     }
@@ -1060,6 +1113,9 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
             }
         }
     }
+    if constexpr (!EXACT) {
+        if (__any(watch.hit()) && lane == 0) *range_flag = 1;
+    }
     return true;
 }
 
@@ -1069,11 +1125,11 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_block_lds(
     T* __restrict__ P, T* __restrict__ Qt, const int32_t* __restrict__ U,
     const int32_t* __restrict__ V, const float* __restrict__ R,
     const int64_t* __restrict__ entry_begin, const int32_t* __restrict__ entry_len, const int64_t* __restrict__ hot_pos,
-    const LdsBlock* __restrict__ blocks, float lr, float lambda)
+    const LdsBlock* __restrict__ blocks, float lr, float lambda, int* range_flag)
 {
     extern __shared__ int strip[];            // ncols * K values (fixed point, or fp32 bits if EXACT)
     lds_block_body<T, K, EXACT, false, DEPTH>(strip, P, Qt, U, V, R, entry_begin, entry_len, hot_pos, blocks[blockIdx.x], lr,
-                                       lambda, [] { return true; });
+                                       lambda, range_flag, [] { return true; });
 }
 
 // One launch per EPOCH: workgroup a keeps block row a for the whole epoch (its rows of P are
@@ -1093,6 +1149,7 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_block_lds(
 // All grid_r workgroups must be resident at once (checked by the host before launching).
 // Every wait is bounded: after spin_limit polls a workgroup raises *abort_flag and leaves, and
 // every waiting workgroup leaves as soon as it sees the flag, so the grid always drains.
+// abort_flag[1] is the range flag of the fixed-point strip (see RangeWatch).
 template <typename T, int K, bool EXACT, int DEPTH>
 __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_ring_lds(
     T* __restrict__ P, T* __restrict__ Qt, const int32_t* __restrict__ U,
@@ -1165,7 +1222,7 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_ring_lds(
         bool ok;
         if (blk.n_entries > 0)
             ok = lds_block_body<T, K, EXACT, true, DEPTH>(strip, P, Qt, U, V, R, entry_begin, entry_len, hot_pos, blk, lr, lambda,
-                                                   wait_for_strip);
+                                                   abort_flag + 1, wait_for_strip);
         else
             ok = wait_for_strip();   // an empty block still waits: it passes the guarantee on
         if (!ok) return;
@@ -1266,6 +1323,12 @@ __global__ __launch_bounds__(kGroupThreads) void init_fill(T* __restrict__ X, in
     }
 }
 
+__global__ void fill_i32(int32_t* out, int64_t count, int32_t value)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) out[i] = value;
+}
+
 __global__ void xcc_probe(int32_t* out)
 {
     // hardware register XCC_ID (id 20), bits [3:0] = index of the accelerator die
@@ -1292,7 +1355,7 @@ template <typename T, int K, bool EXACT, int DEPTH>
 hipError_t launch_sgd_lds_impl(int waves, void* P, void* Qt, const int32_t* U, const int32_t* V,
                             const float* R, const int64_t* eb, const int32_t* el, const int64_t* hot,
                             const LdsBlock* blocks, int64_t n_blocks, size_t lds_bytes, float lr,
-                            float lambda, hipStream_t stream)
+                            float lambda, int* range_flag, hipStream_t stream)
 {
     // more than 64 KiB of dynamic LDS has to be allowed once per kernel and device
     static bool raised[64] = {};
@@ -1306,7 +1369,7 @@ hipError_t launch_sgd_lds_impl(int waves, void* P, void* Qt, const int32_t* U, c
         raised[dev] = true;
     }
     hipLaunchKernelGGL((sgd_block_lds<T, K, EXACT, DEPTH>), dim3((unsigned)n_blocks), dim3(waves * kWave), lds_bytes,
-                       stream, (T*)P, (T*)Qt, U, V, R, eb, el, hot, blocks, lr, lambda);
+                       stream, (T*)P, (T*)Qt, U, V, R, eb, el, hot, blocks, lr, lambda, range_flag);
     return hipGetLastError();
 }
 
@@ -1370,16 +1433,16 @@ template <typename T, int K>
 hipError_t launch_sgd_lds_t(bool exact, bool short_prefetch, int waves, void* P, void* Qt, const int32_t* U, const int32_t* V,
                             const float* R, const int64_t* eb, const int32_t* el, const int64_t* hot,
                             const LdsBlock* blocks, int64_t n_blocks, size_t lds_bytes, float lr,
-                            float lambda, hipStream_t stream)
+                            float lambda, int* range_flag, hipStream_t stream)
 {
     if (exact)
         return launch_sgd_lds_impl<T, K, true, kLdsPrefetchDepth>(1, P, Qt, U, V, R, eb, el, hot, blocks, n_blocks, lds_bytes,
-                                                                  lr, lambda, stream);
+                                                                  lr, lambda, range_flag, stream);
     if (short_prefetch)
         return launch_sgd_lds_impl<T, K, false, kShortPrefetchDepth>(waves, P, Qt, U, V, R, eb, el, hot, blocks, n_blocks,
-                                                                     lds_bytes, lr, lambda, stream);
+                                                                     lds_bytes, lr, lambda, range_flag, stream);
     return launch_sgd_lds_impl<T, K, false, kLdsPrefetchDepth>(waves, P, Qt, U, V, R, eb, el, hot, blocks, n_blocks, lds_bytes,
-                                                               lr, lambda, stream);
+                                                               lr, lambda, range_flag, stream);
 }
 
 template <typename T, int K>
@@ -1434,12 +1497,12 @@ size_t lds_strip_bytes(int k, int32_t max_cols) { return (size_t)max_cols * k * 
 hipError_t launch_sgd_lds(int dtype, int k, bool exact, bool short_prefetch, int waves, void* P, void* Qt, const int32_t* U,
                           const int32_t* V, const float* R, const int64_t* entry_begin,
                           const int32_t* entry_len, const int64_t* hot_pos, const LdsBlock* blocks, int64_t n_blocks,
-                          size_t lds_bytes, float lr, float lambda, hipStream_t stream)
+                          size_t lds_bytes, float lr, float lambda, int* range_flag, hipStream_t stream)
 {
     if (n_blocks <= 0) return hipSuccess;
-    if (waves < 1 || waves > 16 || lds_bytes > kLdsBudget) return hipErrorInvalidValue;
+    if (waves < 1 || waves > 16 || lds_bytes > kLdsBudget || !range_flag) return hipErrorInvalidValue;
     MF_DISPATCH(launch_sgd_lds_t, exact, short_prefetch, waves, P, Qt, U, V, R, entry_begin, entry_len, hot_pos, blocks, n_blocks,
-                lds_bytes, lr, lambda, stream);
+                lds_bytes, lr, lambda, range_flag, stream);
 }
 
 hipError_t launch_sgd_ring(int dtype, int k, bool exact, bool short_prefetch, int waves, bool query_only, int* max_resident,
@@ -1480,6 +1543,14 @@ hipError_t launch_init(int dtype, void* X, int64_t count, uint64_t seed, uint64_
         hipLaunchKernelGGL(init_fill<__half>, dim3(groups), dim3(kGroupThreads), 0, stream, (__half*)X, count, key, scale);
     else
         return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_i32(int32_t* d_out, int64_t count, int32_t value, hipStream_t stream)
+{
+    if (count <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_i32, dim3((unsigned)((count + kGroupThreads - 1) / kGroupThreads)), dim3(kGroupThreads), 0, stream,
+                       d_out, count, value);
     return hipGetLastError();
 }
 

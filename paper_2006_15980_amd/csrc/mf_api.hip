@@ -46,9 +46,11 @@ struct mf_ctx {
     int64_t spin_limit = (int64_t)1 << 22;
     int32_t ring_resident[2] = {-1, -1};  // workgroups of the ring kernel the device holds at once, per mode
     int32_t ring_epochs = 0;              // epochs run by the ring kernel since mf_load_blocks
+    bool ring_gave_up = false;            // a bounded wait expired on this load: per-stratum launches from now on
+    bool epochs_since_check = false;      // SGD kernels were enqueued since the device flags were last read
     uint32_t* d_perm = nullptr;           // packed -> original position when the partition was made on the device
     int32_t* d_order = nullptr;           // 2 * grid_c numbers inside the workspace: order, inverse
-    int32_t* d_ring_done = nullptr;       // grid_r counters + 1 abort flag, inside the workspace
+    int32_t* d_ring_done = nullptr;       // grid_r counters + the abort flag + the range flag, inside the workspace
     int32_t lds_chunk = 0;   // 0 = one chunk per wavefront
     int32_t lds_waves = 16;    // option value (upper bound of the workspace estimates)
     bool lds_waves_set = false;  // the caller chose it
@@ -146,7 +148,7 @@ Layout make_layout(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t l
     for (int which = 0; which < 2; ++which) {
         l.off_ring[which] = off; off += align_up((size_t)l.lds_blocks_cap * sizeof(mf::LdsBlock));
     }
-    l.off_ring_done = off; off += align_up(((size_t)gr + 1) * 4);
+    l.off_ring_done = off; off += align_up(((size_t)gr + 2) * 4);
     l.off_order = off; off += align_up((size_t)gc * 2 * 4);   // stratum order of an epoch and its inverse
     l.off_hot = off; off += align_up((size_t)l.hot_cap * 8);   // cut rows of the Hogwild LDS work list
     l.total = off;
@@ -172,17 +174,33 @@ hipError_t begin_launch_timing(mf_ctx* ctx, hipEvent_t* after)
     return hipEventRecord(before, ctx->stream);
 }
 
-// After a synchronisation: did a workgroup of the ring kernel give up waiting?
-int check_ring_abort(mf_ctx* ctx)
+// After a synchronisation: read the two device flags the SGD kernels may raise.
+//   abort flag: a workgroup of the one-launch-per-epoch kernel gave up waiting for its neighbour
+//               (the device was shared, or the wait limit was set too low); the epoch was abandoned
+//               half-applied.  The context falls back to one launch per stratum for this load.
+//   range flag: the fixed-point strip of the Hogwild LDS kernel met a value of Qt (or of a row of P
+//               kept beside it) of magnitude >= 64, or a single change of magnitude >= 4: the
+//               training has diverged and values may have wrapped round.
+// Both are cleared once reported.
+int check_device_flags(mf_ctx* ctx)
 {
-    if (!ctx->loaded || !ctx->d_ring_done || ctx->ring_epochs == 0) return MF_OK;
-    int32_t flag = 0;
-    hipError_t e = hipMemcpy(&flag, ctx->d_ring_done + ctx->part.gr, 4, hipMemcpyDeviceToHost);
-    if (e != hipSuccess) return fail_hip(ctx, "reading the ring kernel's abort flag", e);
-    if (flag != 0)
-        return fail(ctx, MF_EDEVICE, "a workgroup of the one-launch-per-epoch kernel exceeded its wait limit; "
-                                     "the factors are in an undefined state (MF_OPT_RING = 0 avoids this kernel)");
-    return MF_OK;
+    if (!ctx->loaded || !ctx->d_ring_done || !ctx->epochs_since_check) return MF_OK;
+    int32_t flags[2] = {0, 0};
+    hipError_t e = hipMemcpy(flags, ctx->d_ring_done + ctx->part.gr, 8, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail_hip(ctx, "reading the kernels' status flags", e);
+    ctx->epochs_since_check = false;
+    if (flags[0] == 0 && flags[1] == 0) return MF_OK;
+    e = hipMemset(ctx->d_ring_done, 0, ((size_t)ctx->part.gr + 2) * 4);
+    if (e != hipSuccess) return fail_hip(ctx, "clearing the kernels' status flags", e);
+    ctx->ring_epochs = 0;
+    if (flags[0] != 0) {
+        ctx->ring_gave_up = true;
+        return fail(ctx, MF_EDEVICE, "a workgroup of the one-launch-per-epoch kernel exceeded its wait limit (is the "
+                                     "device shared?); that epoch was abandoned and the factors are in an undefined "
+                                     "state; later epochs on this load use one launch per stratum");
+    }
+    return fail(ctx, MF_ERANGE, "the Hogwild LDS kernel met a value of magnitude >= 64 or a single change >= 4 in its "
+                                "fixed-point strip: the training has diverged (lower lr or the initial scale)");
 }
 
 int check_grid(mf_ctx* ctx, int64_t nnz, int32_t gr, int32_t gc)
@@ -406,8 +424,10 @@ int finish_load(mf_ctx* ctx, const Layout& lay, char* base, const mf::RowStarts&
     }
     ctx->d_ring_done = (int32_t*)(base + lay.off_ring_done);
     ctx->d_order = (int32_t*)(base + lay.off_order);
-    MF_HIP(ctx, hipMemset(ctx->d_ring_done, 0, ((size_t)ctx->part.gr + 1) * 4));
+    MF_HIP(ctx, hipMemset(ctx->d_ring_done, 0, ((size_t)ctx->part.gr + 2) * 4));
     ctx->ring_epochs = 0;
+    ctx->ring_gave_up = false;
+    ctx->epochs_since_check = false;
     ctx->ring_resident[0] = ctx->ring_resident[1] = -1;
     ctx->loaded = true;
     return MF_OK;
@@ -588,6 +608,97 @@ int mf_stratum_order(uint64_t seed, uint64_t epoch, int32_t grid_c, int32_t* ord
     return MF_OK;
 }
 
+namespace {
+
+// What one epoch of `mode` launches for the loaded grid.
+struct EpochPlan {
+    bool hog = false;
+    bool use_lds = false;          // the kernels that keep the block's strip of Qt in LDS
+    bool ring = false;             // one launch per epoch
+    bool short_prefetch = false;
+    size_t lds_bytes = 0;
+    int32_t waves = 1;             // wavefronts per workgroup
+    int32_t kernel = 0;            // MF_KERNEL_ID_*
+    int64_t launches = 0;          // per epoch
+    std::string note;
+};
+
+int plan_epoch(mf_ctx* ctx, int32_t mode, EpochPlan& p)
+{
+    // both modes take the kernel that keeps the block's strip of Qt in LDS whenever the widest
+    // strip fits (the deterministic mode additionally wants several workgroups per compute unit
+    // to be possible, since each of its workgroups is a single wavefront)
+    p.hog = mode == MF_MODE_HOGWILD;
+    // rows of P are requested 8 ratings ahead when they come from HBM, 4 when P is small enough to
+    // be served from the L2s and the memory-side cache (fewer padded positions per batch)
+    const size_t p_bytes = (size_t)ctx->m * ctx->k * (ctx->dtype == MF_F16 ? 2 : 4);
+    p.short_prefetch = ctx->lds_prefetch == 4 || (ctx->lds_prefetch == 0 && p_bytes <= ((size_t)64 << 20));
+    const mf::LdsSchedule& lsched = p.hog ? ctx->lds : ctx->det_lds;
+    p.lds_bytes = mf::lds_strip_bytes(ctx->k, lsched.max_cols) + (size_t)lsched.max_hot * ctx->k * 4;
+    const int32_t choice = p.hog ? ctx->hogwild_kernel : ctx->det_kernel;
+    const size_t budget = p.hog || choice == MF_KERNEL_LDS ? mf::kLdsBudget : mf::kLdsBudget / 4;
+    p.use_lds = choice != MF_KERNEL_GLOBAL && p.lds_bytes <= budget;
+    if (!p.use_lds && choice == MF_KERNEL_LDS)
+        return fail(ctx, MF_EINVAL, "the widest column strip of this grid does not fit the LDS");
+    p.waves = p.use_lds ? (p.hog ? ctx->lds_waves_used : 1) : mf::kWavesPerGroup;
+    std::string why;
+    if (!p.use_lds && choice != MF_KERNEL_GLOBAL)
+        why = "the widest column strip (" + std::to_string(lsched.max_cols) + " columns, " + std::to_string(p.lds_bytes) +
+              " bytes) exceeds the " + std::to_string(budget) + " bytes of LDS this mode uses per workgroup; ";
+    if (p.use_lds && ctx->use_ring && !ctx->ring_gave_up && ctx->part.nnz > 0 && !ctx->streamed) {
+        // one launch for the whole epoch if every block row's workgroup can be resident at once
+        const int m_idx = p.hog ? 1 : 0;
+        if (ctx->ring_resident[m_idx] < 0) {
+            int resident = 0;
+            MF_HIP(ctx, mf::launch_sgd_ring(ctx->dtype, ctx->k, !p.hog, p.short_prefetch, ctx->lds_waves_used, true, &resident,
+                                            nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                                            ctx->part.gr, ctx->part.gc, p.lds_bytes, 0.f, 0.f, nullptr, 0, nullptr, 0,
+                                            nullptr, nullptr, ctx->stream));
+            ctx->ring_resident[m_idx] = resident;
+        }
+        p.ring = ctx->part.gr <= ctx->ring_resident[m_idx];
+        if (!p.ring)
+            why += "the device holds " + std::to_string(ctx->ring_resident[m_idx]) + " workgroups of this shape at once, fewer than grid_r; ";
+    } else if (p.use_lds && ctx->ring_gave_up) {
+        why += "an earlier epoch of the one-launch kernel exceeded its wait limit; ";
+    }
+    if (p.ring) {
+        p.kernel = MF_KERNEL_ID_RING_LDS;
+        p.launches = 1;
+    } else {
+        p.kernel = p.use_lds ? MF_KERNEL_ID_BLOCK_LDS : MF_KERNEL_ID_CHUNKS;
+        const std::vector<int64_t>& first = p.use_lds ? lsched.stratum_block : ctx->sched[mode].stratum_entry;
+        p.launches = 0;
+        for (int32_t st = 0; st < ctx->part.gc; ++st) p.launches += first[(size_t)st + 1] > first[(size_t)st];
+    }
+    static const char* const names[] = {"", "sgd_chunks", "sgd_block_lds", "sgd_ring_lds"};
+    p.note = std::string(p.hog ? "MF_MODE_HOGWILD" : "MF_MODE_DET") + ": " + names[p.kernel] + ", " +
+             std::to_string(p.launches) + " launch(es) per epoch, " + std::to_string(p.waves) +
+             " wavefront(s) per workgroup" + (why.empty() ? "" : " (" + why.substr(0, why.size() - 2) + ")");
+    if (!p.hog && p.kernel == MF_KERNEL_ID_CHUNKS && choice != MF_KERNEL_GLOBAL)
+        p.note += "; this grid was not made for the deterministic mode: one wavefront per block and one launch per "
+                  "stratum (mf_suggest_grid gives a grid whose strips fit)";
+    return MF_OK;
+}
+
+}  // namespace
+
+int mf_epoch_plan(mf_ctx* ctx, int32_t mode, int32_t* kernel_out, int64_t* launches_out, int32_t* waves_out)
+{
+    if (!ctx) return MF_EINVAL;
+    if (!ctx->loaded) return fail(ctx, MF_ESTATE, "mf_epoch_plan before mf_load_blocks");
+    if (mode != MF_MODE_DET && mode != MF_MODE_HOGWILD) return fail(ctx, MF_EINVAL, "unknown mode");
+    MF_HIP(ctx, hipSetDevice(ctx->device));
+    EpochPlan plan;
+    int rc = plan_epoch(ctx, mode, plan);
+    if (rc) return rc;
+    if (kernel_out) *kernel_out = plan.kernel;
+    if (launches_out) *launches_out = plan.launches;
+    if (waves_out) *waves_out = plan.waves;
+    ctx->err = plan.note;
+    return MF_OK;
+}
+
 int mf_sgd_epoch(mf_ctx* ctx, float lr, float lambda, int32_t mode)
 {
     return mf_sgd_epoch_ordered(ctx, lr, lambda, mode, nullptr);
@@ -611,61 +722,40 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
         }
     }
     MF_HIP(ctx, hipSetDevice(ctx->device));
+    EpochPlan plan;
+    int rc = plan_epoch(ctx, mode, plan);
+    if (rc) return rc;
     const mf::Schedule& s = ctx->sched[mode];
-    // both modes take the kernel that keeps the block's strip of Qt in LDS whenever the widest
-    // strip fits (the deterministic mode additionally wants several workgroups per compute unit
-    // to be possible, since each of its workgroups is a single wavefront)
-    const bool hog = mode == MF_MODE_HOGWILD;
-    // rows of P are requested 8 ratings ahead when they come from HBM, 4 when P is small enough to
-    // be served from the L2s and the memory-side cache (fewer padded positions per batch)
-    const size_t p_bytes = (size_t)ctx->m * ctx->k * (ctx->dtype == MF_F16 ? 2 : 4);
-    const bool short_prefetch = ctx->lds_prefetch == 4 || (ctx->lds_prefetch == 0 && p_bytes <= ((size_t)64 << 20));
+    const bool hog = plan.hog, use_lds = plan.use_lds, short_prefetch = plan.short_prefetch;
+    const size_t lds_bytes = plan.lds_bytes;
     const mf::LdsSchedule& lsched = hog ? ctx->lds : ctx->det_lds;
-    const size_t lds_bytes = mf::lds_strip_bytes(ctx->k, lsched.max_cols) + (size_t)lsched.max_hot * ctx->k * 4;
-    const int32_t choice = hog ? ctx->hogwild_kernel : ctx->det_kernel;
-    bool use_lds = false;
-    if (choice != MF_KERNEL_GLOBAL) {
-        use_lds = hog ? lds_bytes <= mf::kLdsBudget
-                      : (choice == MF_KERNEL_LDS ? lds_bytes <= mf::kLdsBudget : lds_bytes <= mf::kLdsBudget / 4);
-        if (!use_lds && choice == MF_KERNEL_LDS)
-            return fail(ctx, MF_EINVAL, "the widest column strip of this grid does not fit the LDS");
-    }
-    if (use_lds && ctx->use_ring && ctx->part.nnz > 0 && !ctx->streamed) {
-        // one launch for the whole epoch if every block row's workgroup can be resident at once
-        const int m_idx = hog ? 1 : 0;
-        if (ctx->ring_resident[m_idx] < 0) {
-            int resident = 0;
-            MF_HIP(ctx, mf::launch_sgd_ring(ctx->dtype, ctx->k, !hog, short_prefetch, ctx->lds_waves_used, true, &resident, nullptr, nullptr,
-                                            nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, ctx->part.gr,
-                                            ctx->part.gc, lds_bytes, 0.f, 0.f, nullptr, 0, nullptr, 0, nullptr, nullptr,
-                                            ctx->stream));
-            ctx->ring_resident[m_idx] = resident;
+    int32_t* const d_flags = ctx->d_ring_done + ctx->part.gr;   // abort flag, range flag
+    ctx->epochs_since_check = true;
+    if (plan.ring) {
+        if ((int64_t)(ctx->ring_epochs + 1) * ctx->part.gc > ((int64_t)1 << 30)) {
+            // the strata counters are about to run out of range: start them again from zero (a
+            // kernel, not a memset node, so that the call may be captured into a graph)
+            MF_HIP(ctx, mf::launch_fill_i32(ctx->d_ring_done, ctx->part.gr, 0, ctx->stream));
+            ctx->ring_epochs = 0;
         }
-        if (ctx->part.gr <= ctx->ring_resident[m_idx]) {
-            if ((int64_t)(ctx->ring_epochs + 1) * ctx->part.gc > ((int64_t)1 << 30)) {
-                // the strata counters are about to run out of range: start them again from zero
-                MF_HIP(ctx, hipMemsetAsync(ctx->d_ring_done, 0, (size_t)ctx->part.gr * 4, ctx->stream));
-                ctx->ring_epochs = 0;
-            }
-            if (stratum_order) {
-                // the order and its inverse go to the workspace; an epoch that may still be reading
-                // the previous order has to finish first
-                MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
-                MF_HIP(ctx, hipMemcpy(ctx->d_order, stratum_order, (size_t)gc * 4, hipMemcpyHostToDevice));
-                MF_HIP(ctx, hipMemcpy(ctx->d_order + gc, inverse.data(), (size_t)gc * 4, hipMemcpyHostToDevice));
-            }
-            hipEvent_t ev1 = nullptr;
-            MF_HIP(ctx, begin_launch_timing(ctx, &ev1));
-            MF_HIP(ctx, mf::launch_sgd_ring(ctx->dtype, ctx->k, !hog, short_prefetch, ctx->lds_waves_used, false, nullptr, ctx->dP, ctx->dQt,
-                                            ctx->dU, ctx->dV, ctx->dR, lsched.d_begin, lsched.d_len, lsched.d_hot, lsched.d_ring,
-                                            ctx->part.gr, ctx->part.gc, lds_bytes, lr, lambda, ctx->d_ring_done,
-                                            ctx->ring_epochs * ctx->part.gc, ctx->d_ring_done + ctx->part.gr,
-                                            (long long)ctx->spin_limit, stratum_order ? ctx->d_order : nullptr,
-                                            stratum_order ? ctx->d_order + gc : nullptr, ctx->stream));
-            if (ev1) MF_HIP(ctx, hipEventRecord(ev1, ctx->stream));
-            ctx->ring_epochs += 1;
-            return MF_OK;
+        if (stratum_order) {
+            // the order and its inverse go to the workspace; an epoch that may still be reading
+            // the previous order has to finish first
+            MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
+            MF_HIP(ctx, hipMemcpy(ctx->d_order, stratum_order, (size_t)gc * 4, hipMemcpyHostToDevice));
+            MF_HIP(ctx, hipMemcpy(ctx->d_order + gc, inverse.data(), (size_t)gc * 4, hipMemcpyHostToDevice));
         }
+        hipEvent_t ev1 = nullptr;
+        MF_HIP(ctx, begin_launch_timing(ctx, &ev1));
+        MF_HIP(ctx, mf::launch_sgd_ring(ctx->dtype, ctx->k, !hog, short_prefetch, ctx->lds_waves_used, false, nullptr, ctx->dP, ctx->dQt,
+                                        ctx->dU, ctx->dV, ctx->dR, lsched.d_begin, lsched.d_len, lsched.d_hot, lsched.d_ring,
+                                        ctx->part.gr, ctx->part.gc, lds_bytes, lr, lambda, ctx->d_ring_done,
+                                        ctx->ring_epochs * ctx->part.gc, d_flags,
+                                        (long long)ctx->spin_limit, stratum_order ? ctx->d_order : nullptr,
+                                        stratum_order ? ctx->d_order + gc : nullptr, ctx->stream));
+        if (ev1) MF_HIP(ctx, hipEventRecord(ev1, ctx->stream));
+        ctx->ring_epochs += 1;
+        return MF_OK;
     }
     // Streamed mode: the ratings of a stratum are one contiguous piece of the packed arrays.  The
     // strata of `group` consecutive steps are copied from pinned host memory into one of two device
@@ -744,7 +834,7 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
         if (count > 0 && use_lds)
             MF_HIP(ctx, mf::launch_sgd_lds(ctx->dtype, ctx->k, !hog, short_prefetch, ctx->lds_waves_used, ctx->dP, ctx->dQt, U, V,
                                            R, lsched.d_begin, lsched.d_len, lsched.d_hot, lsched.d_blocks + first, count, lds_bytes,
-                                           lr, lambda, ctx->stream));
+                                           lr, lambda, d_flags + 1, ctx->stream));
         else if (count > 0)
             MF_HIP(ctx, mf::launch_sgd(ctx->dtype, ctx->k, mode == MF_MODE_HOGWILD, ctx->dP, ctx->dQt, U, V, R,
                                        s.d_begin, s.d_len, first, count, lr, lambda, ctx->stream));
@@ -781,7 +871,7 @@ int mf_rmse(mf_ctx* ctx, const int32_t* d_rows, const int32_t* d_cols, const flo
     MF_HIP(ctx, hipMemcpyAsync(&sum, d_sum, sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
     MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
     *rmse_out = std::sqrt(sum / (double)count);
-    return check_ring_abort(ctx);
+    return check_device_flags(ctx);
 }
 
 int mf_sync(mf_ctx* ctx)
@@ -789,7 +879,7 @@ int mf_sync(mf_ctx* ctx)
     if (!ctx) return MF_EINVAL;
     MF_HIP(ctx, hipSetDevice(ctx->device));
     MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    return check_ring_abort(ctx);
+    return check_device_flags(ctx);
 }
 
 int mf_profile_read(mf_ctx* ctx, double* kernel_ms_out, int64_t* launches_out)

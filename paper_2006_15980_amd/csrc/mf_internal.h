@@ -148,14 +148,16 @@ hipError_t launch_sgd(int dtype, int k, bool hogwild, void* P, void* Qt, const i
 // wavefront per workgroup, fp32 strip), else Hogwild (`waves` wavefronts, fixed-point strip;
 // short_prefetch: rows of P are requested 4 instead of 8 ratings ahead, which pays when P is
 // served from the caches).  hot_pos: the schedule's list of cut rows (see LdsBlock); lds_bytes
-// covers the widest strip plus the most cut rows of any block.
+// covers the widest strip plus the most cut rows of any block.  range_flag (device): set to 1 by
+// the Hogwild kernel when a value leaves the safe range of its fixed-point strip.
 hipError_t launch_sgd_lds(int dtype, int k, bool exact, bool short_prefetch, int waves, void* P, void* Qt, const int32_t* U,
                           const int32_t* V, const float* R, const int64_t* entry_begin,
                           const int32_t* entry_len, const int64_t* hot_pos, const LdsBlock* blocks, int64_t n_blocks,
-                          size_t lds_bytes, float lr, float lambda, hipStream_t stream);
+                          size_t lds_bytes, float lr, float lambda, int* range_flag, hipStream_t stream);
 // One launch per epoch (ring of workgroups, see kernels.hip).  ring_blocks: grid_c * grid_r
 // descriptors indexed [stratum][block row], empty blocks included.  order / pos (device, grid_c
-// entries each, both or neither): the stratum of every step and its inverse.  query_only: do not launch,
+// entries each, both or neither): the stratum of every step and its inverse.  abort_flag: two
+// device ints, [0] raised when a bounded wait expires, [1] the range flag.  query_only: do not launch,
 // return in *max_resident how many workgroups of this shape the device can hold at once.
 hipError_t launch_sgd_ring(int dtype, int k, bool exact, bool short_prefetch, int waves, bool query_only, int* max_resident,
                            void* P, void* Qt, const int32_t* U, const int32_t* V, const float* R,
@@ -171,5 +173,6 @@ hipError_t launch_rmse(int dtype, int k, const void* P, const void* Qt, const in
                        const int32_t* V, const float* R, int64_t count, double* partials,
                        double* sum_out, hipStream_t stream);
 hipError_t launch_xcc_probe(int32_t n_groups, int32_t* d_out, hipStream_t stream);
+hipError_t launch_fill_i32(int32_t* d_out, int64_t count, int32_t value, hipStream_t stream);
 
 }  // namespace mf

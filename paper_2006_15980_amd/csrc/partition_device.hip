@@ -13,8 +13,6 @@
 #include "mf_internal.h"
 
 #include <algorithm>
-#include <chrono>
-#include <cstdio>
 #include <cstdlib>
 
 #include "../../include/mf_sgd.h"
@@ -341,21 +339,6 @@ __global__ __launch_bounds__(kSortThreads) void row_start_words(const int32_t* _
     }
 }
 
-// MF_LOAD_TIMING=1 in the environment: stage times of the device partitioner on stderr.
-struct StageTimer {
-    bool on = std::getenv("MF_LOAD_TIMING") != nullptr;
-    std::chrono::steady_clock::time_point t0 = std::chrono::steady_clock::now();
-    void mark(const char* what, hipStream_t stream)
-    {
-        if (!on) return;
-        (void)hipStreamSynchronize(stream);
-        auto t1 = std::chrono::steady_clock::now();
-        std::fprintf(stderr, "[mf_load_blocks_device] %-28s %8.3f ms\n", what,
-                     std::chrono::duration<double, std::milli>(t1 - t0).count());
-        t0 = t1;
-    }
-};
-
 int bits_for(int64_t values)   // bits needed to tell `values` different numbers apart
 {
     int b = 0;
@@ -383,7 +366,6 @@ int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const f
 {
     const int64_t nblocks = (int64_t)gr * gc;
     const bool balanced = split != MF_SPLIT_EQUAL_WIDTH;
-    StageTimer timer;
     out.nnz = nnz;
     out.gr = gr;
     out.gc = gc;
@@ -445,7 +427,6 @@ int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const f
         equal_width_bounds(m, gr, out.row_bounds);
         equal_width_bounds(n, gc, out.col_bounds);
     }
-    timer.mark("degrees and bounds", stream);
     out.block_ptr.assign((size_t)nblocks + 1, 0);
     out.perm.clear();
     rs.bits.clear();
@@ -498,7 +479,6 @@ int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const f
         PD_HIP(hipMemcpy(d_row_inverse.p, inverse.data(), (size_t)gr * 4, hipMemcpyHostToDevice));
     }
 
-    timer.mark("strip tables", stream);
     // ---- keys, payload, block sizes
     const int64_t ntiles = (nnz + kSortTile - 1) / kSortTile;
     const int64_t hist_len = (int64_t)kRadix * ntiles;
@@ -515,7 +495,6 @@ int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const f
                        d_col_bounds.as<int32_t>(), gr, gc, ubits, vbits, row_seed ? d_row_shift.as<uint32_t>() : nullptr,
                        keys[0].as<uint64_t>(), payload[0].as<uint32_t>());
     PD_HIP(hipGetLastError());
-    timer.mark("allocations and keys", stream);
 
     // ---- stable radix passes over the used bits
     int cur = 0;
@@ -534,7 +513,6 @@ int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const f
         cur ^= 1;
     }
 
-    timer.mark("radix passes", stream);
     // ---- packed arrays
     hipLaunchKernelGGL(unpack_keys, dim3(streaming_groups(nnz)), dim3(kSortThreads), 0, stream,
                        keys[cur].as<uint64_t>(), payload[cur].as<uint32_t>(), nnz, d_row_bounds.as<int32_t>(),
@@ -553,7 +531,6 @@ int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const f
     PD_HIP(hipGetLastError());
     PD_HIP(hipStreamSynchronize(stream));
 
-    timer.mark("unpack", stream);
     // ---- what the host needs for the work lists: block boundaries and where the row runs begin
     {
         std::vector<uint32_t> starts((size_t)nblocks + 1);
@@ -562,7 +539,6 @@ int build_partition_device(const int32_t* d_rows, const int32_t* d_cols, const f
     }
     rs.bits.resize((size_t)nwords);
     PD_HIP(hipMemcpy(rs.bits.data(), words.p, (size_t)nwords * 8, hipMemcpyDeviceToHost));
-    timer.mark("block sizes and row starts", stream);
     return MF_OK;
 }
 

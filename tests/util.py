@@ -8,32 +8,11 @@ import oracle
 import workloads
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-CACHE = os.environ.get("MF_DATA_CACHE", os.path.join(ROOT, ".cache"))
-_mem = {}
 
 
 def dataset(name: str, factor: float = 1.0, k=None) -> workloads.Dataset:
-    """Generate (or re-load from an .npz cache) one synthetic configuration."""
-    cfg = workloads.scaled(workloads.CONFIGS[name], factor, k)
-    key = f"{name}_{factor:g}"
-    if key in _mem:
-        ds = _mem[key]
-        return workloads.Dataset(cfg, *[getattr(ds, f) for f in _FIELDS])
-    path = os.path.join(CACHE, f"{key}_seed{cfg.seed}.npz")
-    if cfg.nnz_train >= 1_000_000 and os.path.exists(path):
-        z = np.load(path)
-        ds = workloads.Dataset(cfg, *[z[f] if z[f].ndim else z[f].item() for f in _FIELDS])
-    else:
-        ds = workloads.generate(cfg)
-        if cfg.nnz_train >= 1_000_000:
-            os.makedirs(CACHE, exist_ok=True)
-            np.savez(path, **{f: getattr(ds, f) for f in _FIELDS})
-    _mem[key] = ds
-    return ds
-
-
-_FIELDS = ["rows", "cols", "vals", "test_rows", "test_cols", "test_vals", "max_row_degree",
-           "max_col_degree", "median_row_degree", "median_col_degree"]
+    """Generate (or take from the cache) one synthetic configuration."""
+    return workloads.load(name, factor, k)
 
 
 def oracle_init(m, n, k, seed, scale, arith=oracle.ARITH_F64):
