@@ -260,6 +260,23 @@ int mf_stratum_order(uint64_t seed, uint64_t epoch, int32_t grid_c, int32_t* ord
 int mf_rmse(mf_ctx* ctx, const int32_t* d_rows, const int32_t* d_cols, const float* d_vals,
             int64_t count, double* rmse_out);
 
+/* mf_rmse for callers that cannot allocate device memory or wait (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the same kernels and the same fixed-order
+ * reduction, but the partial sums go to a static device array of the library (64 KiB per GPU, held
+ * until the process ends) instead of the buffer mf_create allocates, the result
+ * sqrt(mean (r - p_u.q_v)^2) is written to DEVICE memory of the caller, and the call neither
+ * allocates, frees, copies to the host nor synchronises: it only enqueues two kernels on the
+ * context's stream.
+ *   d_rows, d_cols, d_vals : DEVICE arrays of `count` entries, caller-owned, all required;
+ *   count                  : 1 .. MF_RMSE_NOALLOC_MAX_COUNT, else MF_EINVAL;
+ *   d_rmse_out             : DEVICE, one double, valid once the stream has reached the call.
+ * All calls on one GPU share that GPU's array (every call overwrites all of it, nothing has to be
+ * cleared): calls that overlap in time on one GPU -- from two contexts, or from two streams -- race
+ * and must be ordered by the caller.  Only devices 0..63 have the array (MF_EDEVICE above). */
+#define MF_RMSE_NOALLOC_MAX_COUNT ((int64_t)1 << 32)
+int mf_rmse_noalloc(mf_ctx* ctx, const int32_t* d_rows, const int32_t* d_cols, const float* d_vals,
+                    int64_t count, double* d_rmse_out);
+
 /* Wait for all work enqueued by this context. */
 int mf_sync(mf_ctx* ctx);
 

@@ -35,7 +35,7 @@ EXPORTS = ["mf_create", "mf_destroy", "mf_last_error", "mf_set_option", "mf_init
            "mf_load_blocks_workspace", "mf_load_blocks", "mf_load_blocks_device",
            "mf_load_blocks_streamed_workspace", "mf_load_blocks_streamed", "mf_get_partition", "mf_sgd_epoch",
            "mf_sgd_epoch_ordered", "mf_stratum_order", "mf_epoch_plan",
-           "mf_rmse", "mf_sync", "mf_profile_read", "mf_debug_xcc_ids", "mf_plan_host", "mf_suggest_grid"]
+           "mf_rmse", "mf_rmse_noalloc", "mf_sync", "mf_profile_read", "mf_debug_xcc_ids", "mf_plan_host", "mf_suggest_grid"]
 
 
 class MFError(RuntimeError):
@@ -72,6 +72,7 @@ def lib() -> C.CDLL:
         l.mf_epoch_plan.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i64), C.POINTER(i32)]
         l.mf_stratum_order.argtypes = [C.c_uint64, C.c_uint64, i32, vp]
         l.mf_rmse.argtypes = [vp, vp, vp, vp, i64, C.POINTER(C.c_double)]
+        l.mf_rmse_noalloc.argtypes = [vp, vp, vp, vp, i64, vp]
         l.mf_sync.argtypes = [vp]
         l.mf_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
         l.mf_debug_xcc_ids.argtypes = [vp, i32, vp]
@@ -198,6 +199,11 @@ def mf_rmse(ctx: int, d_rows: Optional[int], d_cols: Optional[int], d_vals: Opti
     out = C.c_double()
     _check(ctx, lib().mf_rmse(ctx, d_rows, d_cols, d_vals, count, C.byref(out)))
     return out.value
+
+
+def mf_rmse_noalloc(ctx: int, d_rows: int, d_cols: int, d_vals: int, count: int, d_rmse_out: int) -> None:
+    """Enqueue only: the result lands in the device double at d_rmse_out."""
+    _check(ctx, lib().mf_rmse_noalloc(ctx, d_rows, d_cols, d_vals, count, d_rmse_out))
 
 
 def mf_sync(ctx: int) -> None:

@@ -1283,9 +1283,10 @@ __global__ __launch_bounds__(kGroupThreads) void rmse_partial(
     if (lane == 0) partials[wave_id] = acc;
 }
 
-// Fixed-order sum of the partials by one workgroup.
+// Fixed-order sum of the partials by one workgroup.  count > 0: the result is the root of the mean,
+// sqrt(sum / count); count == 0: the sum itself.
 __global__ __launch_bounds__(kGroupThreads) void rmse_final(const double* __restrict__ partials,
-                                                            int n, double* __restrict__ out)
+                                                            int n, int64_t count, double* __restrict__ out)
 {
     __shared__ double buf[kGroupThreads];
     double acc = 0.0;
@@ -1296,7 +1297,7 @@ __global__ __launch_bounds__(kGroupThreads) void rmse_final(const double* __rest
         if ((int)threadIdx.x < s) buf[threadIdx.x] += buf[threadIdx.x + s];
         __syncthreads();
     }
-    if (threadIdx.x == 0) out[0] = buf[0];
+    if (threadIdx.x == 0) out[0] = count > 0 ? sqrt(buf[0] / (double)count) : buf[0];
 }
 
 // ------------------------------------------------------------------------------------- init
@@ -1447,7 +1448,7 @@ hipError_t launch_sgd_lds_t(bool exact, bool short_prefetch, int waves, void* P,
 
 template <typename T, int K>
 hipError_t launch_rmse_t(const void* P, const void* Qt, const int32_t* U, const int32_t* V,
-                         const float* R, int64_t count, double* partials, double* sum_out,
+                         const float* R, int64_t count, double* partials, double* sum_out, bool root,
                          hipStream_t stream)
 {
     hipLaunchKernelGGL((rmse_partial<T, K>), dim3(kRmseGroups), dim3(kGroupThreads), 0, stream,
@@ -1455,7 +1456,7 @@ hipError_t launch_rmse_t(const void* P, const void* Qt, const int32_t* U, const 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(rmse_final, dim3(1), dim3(kGroupThreads), 0, stream, partials, kRmsePartials,
-                       sum_out);
+                       root ? count : (int64_t)0, sum_out);
     return hipGetLastError();
 }
 
@@ -1521,9 +1522,9 @@ hipError_t launch_sgd_ring(int dtype, int k, bool exact, bool short_prefetch, in
 
 hipError_t launch_rmse(int dtype, int k, const void* P, const void* Qt, const int32_t* U,
                        const int32_t* V, const float* R, int64_t count, double* partials,
-                       double* sum_out, hipStream_t stream)
+                       double* sum_out, bool root, hipStream_t stream)
 {
-    MF_DISPATCH(launch_rmse_t, P, Qt, U, V, R, count, partials, sum_out, stream);
+    MF_DISPATCH(launch_rmse_t, P, Qt, U, V, R, count, partials, sum_out, root, stream);
 }
 
 hipError_t launch_init(int dtype, void* X, int64_t count, uint64_t seed, uint64_t stream_id,

@@ -78,6 +78,14 @@ struct mf_ctx {
     size_t events_used = 0;
 };
 
+// Scratch of mf_rmse_noalloc: one partial sum per wavefront of the RMSE kernel's fixed launch shape.
+// Every GPU the library runs on holds its own copy (64 KiB) at its own address until the process
+// ends; the array's name is only a host-side handle, kernels and copies take the address that
+// hipGetSymbolAddress returned with that GPU current (kept in g_scratch_addr, resolved in mf_create).
+static __device__ __align__(256) double scratch[mf::kRmsePartials];
+constexpr int kMaxDevices = 64;
+static double* g_scratch_addr[kMaxDevices] = {};
+
 namespace {
 
 int fail(mf_ctx* ctx, int code, const std::string& msg)
@@ -229,6 +237,16 @@ int mf_create(mf_ctx** out, int device, void* hip_stream)
         hipMalloc((void**)&ctx->d_partials, (mf::kRmsePartials + 1) * sizeof(double)) != hipSuccess) {
         delete ctx;
         return MF_EDEVICE;
+    }
+    if (device < kMaxDevices && !g_scratch_addr[device]) {
+        // with this device current: where its copy of the static scratch array lives
+        double* addr = nullptr;
+        if (hipGetSymbolAddress((void**)&addr, HIP_SYMBOL(scratch)) != hipSuccess || !addr) {
+            (void)hipFree(ctx->d_partials);
+            delete ctx;
+            return MF_EDEVICE;
+        }
+        g_scratch_addr[device] = addr;
     }
     *out = ctx;
     return MF_OK;
@@ -866,12 +884,31 @@ int mf_rmse(mf_ctx* ctx, const int32_t* d_rows, const int32_t* d_cols, const flo
     MF_HIP(ctx, hipSetDevice(ctx->device));
     double* d_sum = ctx->d_partials + mf::kRmsePartials;
     MF_HIP(ctx, mf::launch_rmse(ctx->dtype, ctx->k, ctx->dP, ctx->dQt, d_rows, d_cols, d_vals, count,
-                                ctx->d_partials, d_sum, ctx->stream));
+                                ctx->d_partials, d_sum, false, ctx->stream));
     double sum = 0.0;
     MF_HIP(ctx, hipMemcpyAsync(&sum, d_sum, sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
     MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
     *rmse_out = std::sqrt(sum / (double)count);
     return check_device_flags(ctx);
+}
+
+int mf_rmse_noalloc(mf_ctx* ctx, const int32_t* d_rows, const int32_t* d_cols, const float* d_vals,
+                    int64_t count, double* d_rmse_out)
+{
+    if (!ctx || !d_rmse_out) return MF_EINVAL;
+    if (!ctx->inited) return fail(ctx, MF_ESTATE, "mf_rmse_noalloc before mf_init");
+    if (!d_rows || !d_cols || !d_vals) return fail(ctx, MF_EINVAL, "null rating array");
+    if (count <= 0) return fail(ctx, MF_EINVAL, "RMSE over an empty set");
+    if (count > MF_RMSE_NOALLOC_MAX_COUNT)
+        return fail(ctx, MF_EINVAL, "count exceeds MF_RMSE_NOALLOC_MAX_COUNT (2^32 entries)");
+    if (ctx->device >= kMaxDevices || !g_scratch_addr[ctx->device])
+        return fail(ctx, MF_EDEVICE, "no static scratch on this device (device index above 63)");
+    MF_HIP(ctx, hipSetDevice(ctx->device));
+    // every wavefront of the fixed launch shape writes its partial, so the scratch needs no
+    // clearing although it still holds the previous call's values
+    MF_HIP(ctx, mf::launch_rmse(ctx->dtype, ctx->k, ctx->dP, ctx->dQt, d_rows, d_cols, d_vals, count,
+                                g_scratch_addr[ctx->device], d_rmse_out, true, ctx->stream));
+    return MF_OK;
 }
 
 int mf_sync(mf_ctx* ctx)

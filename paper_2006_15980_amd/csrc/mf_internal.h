@@ -169,9 +169,11 @@ size_t lds_strip_bytes(int k, int32_t max_cols);   // dynamic LDS the kernel nee
 constexpr size_t kLdsBudget = 160 * 1024 - 1024;   // LDS of one gfx950 compute unit, minus static use
 hipError_t launch_init(int dtype, void* X, int64_t count, uint64_t seed, uint64_t stream_id,
                        float scale, hipStream_t stream);
+// partials: kRmsePartials doubles of device scratch (every one is overwritten).  root = false:
+// *sum_out = the sum of squared errors; true: the root of their mean.
 hipError_t launch_rmse(int dtype, int k, const void* P, const void* Qt, const int32_t* U,
                        const int32_t* V, const float* R, int64_t count, double* partials,
-                       double* sum_out, hipStream_t stream);
+                       double* sum_out, bool root, hipStream_t stream);
 hipError_t launch_xcc_probe(int32_t n_groups, int32_t* d_out, hipStream_t stream);
 hipError_t launch_fill_i32(int32_t* d_out, int64_t count, int32_t value, hipStream_t stream);
 
