@@ -10,7 +10,6 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
-    config.addinivalue_line("markers", "slow: full-size case, opt-in through MF_FULL=1")
 
 
 @pytest.fixture(scope="session")
