@@ -202,8 +202,8 @@ int mf_get_partition(const mf_ctx* ctx, int64_t* perm, int64_t* block_ptr,
  *                                                 wavefronts has its p_u kept in LDS in the same
  *                                                 format while that block runs (up to 8 such
  *                                                 rows per block, as room beside the strip
- *                                                 allows; else p_u is changed with atomics in the
- *                                                 L2);
+ *                                                 allows; a block is never cut into more pieces
+ *                                                 than that permits);
  *                       MF_HOGWILD_GLOBAL_ATOMICS wavefronts of a whole die share a block and use
  *                                                 floating-point atomics in that die's L2 (any
  *                                                 grid, slower).
@@ -317,8 +317,9 @@ int mf_suggest_grid(int64_t m, int64_t n, int64_t nnz, int32_t k, int32_t mode,
  * without padding (chunk = MF_OPT_LDS_CHUNK's meaning); every block's entries are taken by the
  * wavefronts of one workgroup.
  * mode = MF_PLAN_LDS_CUT_ROWS lists, for the same work list, the matrix rows that a boundary
- * between two entries of a block cuts (the LDS kernel keeps their p_u in LDS while the block runs,
- * at most 8 per block; a block with more keeps none and is absent here): entry_begin[i] = packed
+ * between two entries of a block cuts (the LDS kernel keeps their p_u in LDS while the block runs;
+ * a block whose even division would cut more than 8 rows is divided into fewer, longer chunks
+ * until it cuts at most 8): entry_begin[i] = packed
  * position of one rating of the row, entry_len[i] = stratum * grid_r + block row of the block;
  * stratum_entry is zero-filled.
  * MF_ENOMEM if entry_cap is too small. */

@@ -411,8 +411,10 @@ constexpr float kWatchChange = 67108864.f;    // 2^26 =  4.0
 constexpr float kWatchPlain = 64.f;           // the same value limit for numbers not yet scaled
 
 struct RangeWatch {
-    float value = 0.f, change = 0.f;           // per lane: largest magnitudes seen
-    bool out = false;                          // per lane: a value met outside the strip's range
+    // per lane: the largest magnitudes seen (plain floats, kept in registers; compared once at
+    // the end of the kernel)
+    float value = 0.f, change = 0.f;           // in the strip's scale
+    float plain = 0.f;                         // not scaled: values on their way into or out of the strip
     template <int VEC>
     __device__ __forceinline__ void see(const Row<VEC>& scaled_q, const Row<VEC>& scaled_dq)
     {
@@ -422,10 +424,10 @@ struct RangeWatch {
             change = fmaxf(change, fabsf(scaled_dq.x[j]));
         }
     }
-    __device__ __forceinline__ void see_plain(float x) { out |= !(fabsf(x) < kWatchPlain); }
+    __device__ __forceinline__ void see_plain(float worst) { plain = fmaxf(plain, worst); }
     __device__ __forceinline__ bool hit() const
     {
-        return out || !(value < kWatchValue) || !(change < kWatchChange);
+        return !(plain < kWatchPlain) || !(value < kWatchValue) || !(change < kWatchChange);
     }
 };
 
@@ -689,61 +691,6 @@ __device__ __forceinline__ void lds_hog_chunk(T* __restrict__ P, int* strip, int
     if constexpr (DEPTH >= kLdsPrefetchDepth) __builtin_amdgcn_s_setprio(0);
 }
 
-// A chunk that is a piece of a very long row cut into pieces which run concurrently: p_u is
-// treated like q_v -- re-read for every rating and changed with atomic adds (in the L2).
-template <typename T, int K>
-__device__ __forceinline__ void lds_shared_row_chunk(T* __restrict__ P, int* strip, int col0,
-                                                     const int32_t* __restrict__ U,
-                                                     const int32_t* __restrict__ V,
-                                                     const float* __restrict__ R, int64_t begin,
-                                                     int32_t len, float lr, float shrink, int lane,
-                                                     bool active, RangeWatch& watch)
-{
-    constexpr int VEC = RowShape<T, K>::VEC;
-    for (int32_t off = 0; off < len; off += kWave) {
-        const int cnt = min(kWave, len - off);
-        int mu = 0, mv = 0;
-        float mr = 0.f;
-        if (lane < cnt) {
-            mu = U[begin + off + lane];
-            mv = V[begin + off + lane];
-            mr = R[begin + off + lane];
-        }
-        Row<VEC> pn = load_row<VEC, true>(P + (int64_t)uniform_lane(mu, 0) * K, lane, active);
-        for (int i = 0; i < cnt; ++i) {
-            const int u = uniform_lane(mu, i);
-            const int v = uniform_lane(mv, i);
-            const float r = __int_as_float(uniform_lane(__float_as_int(mr), i));
-            const Row<VEC> p = pn;
-            pn = load_row<VEC, true>(P + (int64_t)uniform_lane(mu, min(i + 1, cnt - 1)) * K, lane, active);
-            int* const qrow = strip + (v - col0) * K;
-            const Row<VEC> q = strip_read<T, VEC>(qrow, lane, active);
-            float part = 0.f;
-#pragma unroll
-            for (int j = 0; j < VEC; ++j) part = fmaf(p.x[j], q.x[j], part);
-            const float e = r - wave_sum(part);
-            const float step = lr * e;
-            Row<VEC> dp;
-#pragma unroll
-            for (int j = 0; j < VEC; ++j) {
-                dp.x[j] = fmaf(step, q.x[j], -shrink * p.x[j]);
-                const float change = fmaf(step, p.x[j], -shrink * q.x[j]);
-                watch.see_plain(q.x[j]);
-                watch.see_plain(16.f * change);
-                const int dq = to_fixed(change);
-                if (active) atomicAdd(&qrow[strip_elem<T>(lane, j)], dq);
-            }
-            atomic_add_row<VEC>(P + (int64_t)u * K, lane, active, dp);
-            // the re-read of p_u was requested before this change was added
-            if (i + 1 < cnt && uniform_lane(mu, i + 1) == u) {
-#pragma unroll
-                for (int j = 0; j < VEC; ++j) pn.x[j] += dp.x[j];
-            }
-        }
-    }
-}
-
-
 // ---- rows of P cut by entry boundaries, held in LDS while their block runs ----------------------
 // A very long row is shared out over several wavefronts of the workgroup.  Its p_u then lives in
 // LDS beside the strip, in the strip's fixed-point format, for as long as the block runs, and is
@@ -756,6 +703,7 @@ __device__ __forceinline__ void lds_hot_row_piece(int* prow, int* strip, int col
                                                   float lr, float shrink, int lane, bool active, RangeWatch& watch)
 {
     constexpr int VEC = RowShape<T, K>::VEC;
+    float worst = 0.f;      // values, and 16 x changes, so that one limit (kWatchPlain) serves both
     int mv = 0, nv = 0;
     float mr = 0.f, nr = 0.f;
     if (lane < min(kWave, len)) {
@@ -782,10 +730,8 @@ __device__ __forceinline__ void lds_hot_row_piece(int* prow, int* strip, int col
             for (int j = 0; j < VEC; ++j) {
                 const float change_q = fmaf(step, p.x[j], -shrink * q.x[j]);
                 const float change_p = fmaf(step, q.x[j], -shrink * p.x[j]);
-                watch.see_plain(q.x[j]);
-                watch.see_plain(p.x[j]);
-                watch.see_plain(16.f * change_q);
-                watch.see_plain(16.f * change_p);
+                worst = fmaxf(fmaxf(worst, fabsf(q.x[j])), fabsf(p.x[j]));
+                worst = fmaxf(fmaxf(worst, 16.f * fabsf(change_q)), 16.f * fabsf(change_p));
                 const int dq = to_fixed(change_q);
                 const int dp = to_fixed(change_p);
                 if (active) {
@@ -797,6 +743,7 @@ __device__ __forceinline__ void lds_hot_row_piece(int* prow, int* strip, int col
         mv = nv;
         mr = nr;
     }
+    watch.see_plain(worst);
 }
 
 // Number of ratings at the front (FROM_END: at the back) of the packed range [begin, begin+len)
@@ -822,14 +769,206 @@ typedef unsigned int uint4_t __attribute__((ext_vector_type(4)));
 constexpr int kRawBufferFlags = 0x00020000;   // word 3 of a raw (untyped, unswizzled) buffer descriptor on gfx9
 constexpr int kCachePolicySc1 = 16;           // auxiliary operand of the buffer intrinsics: bit 4 = sc1
 
-// Work of one workgroup on one block: copy the strip in, run the block's entries, copy it back.
+// ---- the strip of Qt in LDS -------------------------------------------------------------------
 // COHERENT: the strip is handed from workgroup to workgroup INSIDE one launch (ring kernel
 // below), possibly across dies whose L2s do not see each other's plain stores; it is then read
 // and written with agent-scope accesses (sc1: past the L2s' non-coherent lines).
+// Values entering and leaving the fixed-point strip are watched (a value of magnitude >= 128
+// saturates on entry): each copy keeps a running maximum of the magnitudes that passed.
+// `worst`: the caller's running maximum of the magnitudes that passed (see RangeWatch).
+template <bool EXACT>
+__device__ __forceinline__ int to_strip(float x, float& worst)
+{
+    if constexpr (EXACT) return __float_as_int(x);
+    worst = fmaxf(worst, fabsf(x));
+    return to_fixed(x);
+}
+
+template <bool EXACT>
+__device__ __forceinline__ float from_strip(int x, float& worst)
+{
+    if constexpr (EXACT) return __int_as_float(x);
+    const float f = from_fixed(x);
+    worst = fmaxf(worst, fabsf(f));
+    return f;
+}
+
+// Columns col0 .. col0+ncols of Qt into LDS, by all threads of the workgroup (no barrier inside).
+template <typename T, int K, bool EXACT, bool COHERENT>
+__device__ __forceinline__ void strip_copy_in(int* strip, const T* __restrict__ Qt, int col0, int ncols,
+                                              RangeWatch& watch)
+{
+    float worst = 0.f;
+    const int total = ncols * K;          // multiple of 32
+    const T* const strip_src = Qt + (int64_t)col0 * K;
+    const int stride = 4 * (int)blockDim.x;
+    if constexpr (COHERENT && !EXACT) {
+        // 1024 threads: one 32-bit word each (one fp32 value or one pair of binary16 values); wider
+        // pieces were measured slower here, and faster for the 64-thread workgroups of the
+        // deterministic mode below
+        constexpr int kPerWord = sizeof(T) == 2 ? 2 : 1;
+        const unsigned* src = reinterpret_cast<const unsigned*>(strip_src);
+        const int words = total / kPerWord;
+        constexpr int kInFlight = 16;
+        for (int w0 = (int)threadIdx.x; w0 < words; w0 += kInFlight * (int)blockDim.x) {
+            unsigned raw[kInFlight];
+#pragma unroll
+            for (int t = 0; t < kInFlight; ++t) {
+                const int w = w0 + t * (int)blockDim.x;
+                if (w < words) raw[t] = load_word<true>(src + w);
+            }
+#pragma unroll
+            for (int t = 0; t < kInFlight; ++t) {
+                const int w = w0 + t * (int)blockDim.x;
+                if (w < words) {
+                    if constexpr (sizeof(T) == 2) {
+                        const float2 f = unpack_half2(raw[t]);
+                        strip[2 * w] = to_strip<EXACT>(f.x, worst);
+                        strip[2 * w + 1] = to_strip<EXACT>(f.y, worst);
+                    } else {
+                        strip[w] = to_strip<EXACT>(__uint_as_float(raw[t]), worst);
+                    }
+                }
+            }
+        }
+    } else if constexpr (COHERENT) {
+        // 16-byte pieces (4 fp32 values or 8 binary16 values) through a raw buffer descriptor of
+        // the strip with the agent-scope cache policy (sc1)
+        constexpr int kPerPiece = 16 / (int)sizeof(T);
+        const int pieces = total / kPerPiece;
+        const __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc((void*)strip_src, 0, total * (int)sizeof(T), kRawBufferFlags);
+        constexpr int kInFlight = 16;
+        for (int p0 = (int)threadIdx.x; p0 < pieces; p0 += kInFlight * (int)blockDim.x) {
+            uint4_t raw[kInFlight];
+#pragma unroll
+            for (int t = 0; t < kInFlight; ++t) {
+                const int pc = p0 + t * (int)blockDim.x;
+                if (pc < pieces) raw[t] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, pc * 16, 0, kCachePolicySc1);
+            }
+#pragma unroll
+            for (int t = 0; t < kInFlight; ++t) {
+                const int pc = p0 + t * (int)blockDim.x;
+                if (pc < pieces) {
+                    if constexpr (sizeof(T) == 2) {
+#pragma unroll
+                        for (int h = 0; h < 4; ++h) {
+                            const float2 f = unpack_half2(raw[t][h]);
+                            strip[pc * 8 + 2 * h] = to_strip<EXACT>(f.x, worst);
+                            strip[pc * 8 + 2 * h + 1] = to_strip<EXACT>(f.y, worst);
+                        }
+                    } else {
+                        *reinterpret_cast<int4*>(strip + pc * 4) =
+                            make_int4(to_strip<EXACT>(__uint_as_float(raw[t][0]), worst),
+                                      to_strip<EXACT>(__uint_as_float(raw[t][1]), worst),
+                                      to_strip<EXACT>(__uint_as_float(raw[t][2]), worst),
+                                      to_strip<EXACT>(__uint_as_float(raw[t][3]), worst));
+                    }
+                }
+            }
+        }
+    } else {
+        constexpr int kInFlight = 8;   // loads of the strip copy each thread keeps in flight
+        for (int i0 = 4 * (int)threadIdx.x; i0 < total; i0 += kInFlight * stride) {
+            float4 val[kInFlight];
+#pragma unroll
+            for (int t = 0; t < kInFlight; ++t) {
+                const int i = i0 + t * stride;
+                if (i < total) {
+                    if constexpr (sizeof(T) == 2) {
+                        uint2 raw = *reinterpret_cast<const uint2*>(strip_src + i);
+                        float2 a = unpack_half2(raw.x), b = unpack_half2(raw.y);
+                        val[t] = make_float4(a.x, a.y, b.x, b.y);
+                    } else {
+                        val[t] = *reinterpret_cast<const float4*>(strip_src + i);
+                    }
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < kInFlight; ++t) {
+                const int i = i0 + t * stride;
+                if (i < total)
+                    *reinterpret_cast<int4*>(strip + i) =
+                        make_int4(to_strip<EXACT>(val[t].x, worst), to_strip<EXACT>(val[t].y, worst),
+                                  to_strip<EXACT>(val[t].z, worst), to_strip<EXACT>(val[t].w, worst));
+            }
+        }
+    }
+    if constexpr (!EXACT) watch.see_plain(worst);
+}
+
+// The strip in LDS back to columns col0 .. col0+ncols of Qt, by all threads of the workgroup.
+template <typename T, int K, bool EXACT, bool COHERENT>
+__device__ __forceinline__ void strip_copy_out(const int* strip, T* __restrict__ Qt, int col0, int ncols,
+                                               RangeWatch& watch)
+{
+    float worst = 0.f;
+    const int total = ncols * K;
+    T* const strip_dst = Qt + (int64_t)col0 * K;
+    const int stride = 4 * (int)blockDim.x;
+    if constexpr (COHERENT && !EXACT) {
+        constexpr int kPerWord = sizeof(T) == 2 ? 2 : 1;
+        unsigned* dst = reinterpret_cast<unsigned*>(strip_dst);
+        const int words = total / kPerWord;
+        for (int w = (int)threadIdx.x; w < words; w += (int)blockDim.x) {
+            unsigned raw;
+            if constexpr (sizeof(T) == 2) {
+                __half2 h = __halves2half2(round_to_half(from_strip<EXACT>(strip[2 * w], worst)),
+                                           round_to_half(from_strip<EXACT>(strip[2 * w + 1], worst)));
+                raw = *reinterpret_cast<unsigned*>(&h);
+            } else {
+                raw = __float_as_uint(from_strip<EXACT>(strip[w], worst));
+            }
+            __hip_atomic_store(dst + w, raw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    } else if constexpr (COHERENT) {
+        constexpr int kPerPiece = 16 / (int)sizeof(T);
+        const int pieces = total / kPerPiece;
+        const __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc((void*)strip_dst, 0, total * (int)sizeof(T), kRawBufferFlags);
+        for (int pc = (int)threadIdx.x; pc < pieces; pc += (int)blockDim.x) {
+            uint4_t raw;
+            if constexpr (sizeof(T) == 2) {
+#pragma unroll
+                for (int h = 0; h < 4; ++h) {
+                    __half2 hh = __halves2half2(round_to_half(from_strip<EXACT>(strip[pc * 8 + 2 * h], worst)),
+                                                round_to_half(from_strip<EXACT>(strip[pc * 8 + 2 * h + 1], worst)));
+                    raw[h] = *reinterpret_cast<unsigned*>(&hh);
+                }
+            } else {
+                const int4 v = *reinterpret_cast<const int4*>(strip + pc * 4);
+                raw[0] = __float_as_uint(from_strip<EXACT>(v.x, worst));
+                raw[1] = __float_as_uint(from_strip<EXACT>(v.y, worst));
+                raw[2] = __float_as_uint(from_strip<EXACT>(v.z, worst));
+                raw[3] = __float_as_uint(from_strip<EXACT>(v.w, worst));
+            }
+            __builtin_amdgcn_raw_buffer_store_b128(raw, rsrc, pc * 16, 0, kCachePolicySc1);
+        }
+    } else {
+        for (int i = 4 * (int)threadIdx.x; i < total; i += stride) {
+            const int4 raw4 = *reinterpret_cast<const int4*>(strip + i);
+            const float4 val = make_float4(from_strip<EXACT>(raw4.x, worst), from_strip<EXACT>(raw4.y, worst),
+                                           from_strip<EXACT>(raw4.z, worst), from_strip<EXACT>(raw4.w, worst));
+            if constexpr (sizeof(T) == 2) {
+                __half2 a = __halves2half2(round_to_half(val.x), round_to_half(val.y));
+                __half2 b = __halves2half2(round_to_half(val.z), round_to_half(val.w));
+                uint2 raw;
+                raw.x = *reinterpret_cast<unsigned*>(&a);
+                raw.y = *reinterpret_cast<unsigned*>(&b);
+                *reinterpret_cast<uint2*>(strip_dst + i) = raw;
+            } else {
+                *reinterpret_cast<float4*>(strip_dst + i) = val;
+            }
+        }
+    }
+    if constexpr (!EXACT) watch.see_plain(worst);
+}
+
+// Work of one workgroup on one block: copy the strip in, run the block's entries, copy it back.
 // `before_strip()` is called after the block's first ratings and rows of P have been requested
 // and before the strip is read: the ring kernel waits there for the strip's previous user
 // (returning false means "give up": the workgroup leaves); everything requested before it is
-// independent of the strip.
+// independent of the strip.  copy_in / copy_out = false: the caller moves the strip itself.
 template <typename T, int K, bool EXACT, bool COHERENT, int DEPTH, class BeforeStrip>
 __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T* __restrict__ Qt,
                                                const int32_t* __restrict__ U, const int32_t* __restrict__ V,
@@ -837,14 +976,12 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
                                                const int64_t* __restrict__ entry_begin,
                                                const int32_t* __restrict__ entry_len,
                                                const int64_t* __restrict__ hot_pos, const LdsBlock blk,
-                                               float lr, float lambda, int* range_flag, BeforeStrip before_strip)
+                                               float lr, float lambda, bool copy_in, bool copy_out, RangeWatch& watch,
+                                               BeforeStrip before_strip)
 {
-    RangeWatch watch;   // Hogwild only: see RangeWatch
     const int lane = threadIdx.x & (kWave - 1);
     const bool active = RowShape<T, K>::ACTIVE == kWave ? true : lane < RowShape<T, K>::ACTIVE;
     const int total = blk.ncols * K;          // multiple of 32
-    T* const strip_src = Qt + (int64_t)blk.col0 * K;
-    const int stride = 4 * (int)blockDim.x;
 
     // Entries are dealt to the wavefronts round-robin.  The first entry's ratings are requested
     // before the strip is copied so that the two latencies overlap.
@@ -883,117 +1020,17 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
     }
     if (!before_strip()) return false;
 
-    // values entering and leaving the fixed-point strip are watched (a value of magnitude >= 128
-    // saturates on entry)
-    auto to_strip = [&](float x) {
-        if constexpr (EXACT) return __float_as_int(x);
-        watch.see_plain(x);
-        return to_fixed(x);
-    };
-    auto from_strip = [&](int x) {
-        if constexpr (EXACT) return __int_as_float(x);
-        const float f = from_fixed(x);
-        watch.see_plain(f);
-        return f;
-    };
+    float worst = 0.f;   // magnitudes of the cut rows on their way into and out of LDS
     if constexpr (!EXACT) {
-        // read past the L1: another block may have changed the row with atomics executed in the L2
+        // read past the L1 (the row was last written by another compute unit's plain stores)
         for (int slot = wave; slot < n_hot; slot += n_waves) {
             const Row<VEC> p = load_row<VEC, true>(P + (int64_t)uniform_lane(hot_u, slot) * K, lane, active);
 #pragma unroll
             for (int j = 0; j < VEC; ++j)
-                if (active) hot_rows[slot * K + strip_elem<T>(lane, j)] = to_strip(p.x[j]);
+                if (active) hot_rows[slot * K + strip_elem<T>(lane, j)] = to_strip<EXACT>(p.x[j], worst);
         }
     }
-    if constexpr (COHERENT && !EXACT) {
-        // 1024 threads: one 32-bit word each (one fp32 value or one pair of binary16 values); wider
-        // pieces were measured 5 % slower per epoch here, and faster for the 64-thread workgroups
-        // of the deterministic mode below
-        constexpr int kPerWord = sizeof(T) == 2 ? 2 : 1;
-        const unsigned* src = reinterpret_cast<const unsigned*>(strip_src);
-        const int words = total / kPerWord;
-        constexpr int kInFlight = 16;
-        for (int w0 = (int)threadIdx.x; w0 < words; w0 += kInFlight * (int)blockDim.x) {
-            unsigned raw[kInFlight];
-#pragma unroll
-            for (int t = 0; t < kInFlight; ++t) {
-                const int w = w0 + t * (int)blockDim.x;
-                if (w < words) raw[t] = load_word<true>(src + w);
-            }
-#pragma unroll
-            for (int t = 0; t < kInFlight; ++t) {
-                const int w = w0 + t * (int)blockDim.x;
-                if (w < words) {
-                    if constexpr (sizeof(T) == 2) {
-                        const float2 f = unpack_half2(raw[t]);
-                        strip[2 * w] = to_strip(f.x);
-                        strip[2 * w + 1] = to_strip(f.y);
-                    } else {
-                        strip[w] = to_strip(__uint_as_float(raw[t]));
-                    }
-                }
-            }
-        }
-    } else if constexpr (COHERENT) {
-        // 16-byte pieces (4 fp32 values or 8 binary16 values) through a raw buffer descriptor of
-        // the strip with the agent-scope cache policy (sc1)
-        constexpr int kPerPiece = 16 / (int)sizeof(T);
-        const int pieces = total / kPerPiece;
-        const __amdgpu_buffer_rsrc_t rsrc =
-            __builtin_amdgcn_make_buffer_rsrc((void*)strip_src, 0, total * (int)sizeof(T), kRawBufferFlags);
-        constexpr int kInFlight = 16;
-        for (int p0 = (int)threadIdx.x; p0 < pieces; p0 += kInFlight * (int)blockDim.x) {
-            uint4_t raw[kInFlight];
-#pragma unroll
-            for (int t = 0; t < kInFlight; ++t) {
-                const int pc = p0 + t * (int)blockDim.x;
-                if (pc < pieces) raw[t] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, pc * 16, 0, kCachePolicySc1);
-            }
-#pragma unroll
-            for (int t = 0; t < kInFlight; ++t) {
-                const int pc = p0 + t * (int)blockDim.x;
-                if (pc < pieces) {
-                    if constexpr (sizeof(T) == 2) {
-#pragma unroll
-                        for (int h = 0; h < 4; ++h) {
-                            const float2 f = unpack_half2(raw[t][h]);
-                            strip[pc * 8 + 2 * h] = to_strip(f.x);
-                            strip[pc * 8 + 2 * h + 1] = to_strip(f.y);
-                        }
-                    } else {
-                        *reinterpret_cast<int4*>(strip + pc * 4) =
-                            make_int4(to_strip(__uint_as_float(raw[t][0])), to_strip(__uint_as_float(raw[t][1])),
-                                      to_strip(__uint_as_float(raw[t][2])), to_strip(__uint_as_float(raw[t][3])));
-                    }
-                }
-            }
-        }
-    } else {
-        constexpr int kInFlight = 8;   // loads of the strip copy each thread keeps in flight
-        for (int i0 = 4 * (int)threadIdx.x; i0 < total; i0 += kInFlight * stride) {
-            float4 val[kInFlight];
-#pragma unroll
-            for (int t = 0; t < kInFlight; ++t) {
-                const int i = i0 + t * stride;
-                if (i < total) {
-                    if constexpr (sizeof(T) == 2) {
-                        uint2 raw = *reinterpret_cast<const uint2*>(strip_src + i);
-                        float2 a = unpack_half2(raw.x), b = unpack_half2(raw.y);
-                        val[t] = make_float4(a.x, a.y, b.x, b.y);
-                    } else {
-                        val[t] = *reinterpret_cast<const float4*>(strip_src + i);
-                    }
-                }
-            }
-#pragma unroll
-            for (int t = 0; t < kInFlight; ++t) {
-                const int i = i0 + t * stride;
-                if (i < total)
-                    *reinterpret_cast<int4*>(strip + i) =
-                        make_int4(to_strip(val[t].x), to_strip(val[t].y), to_strip(val[t].z), to_strip(val[t].w));
-            }
-        }
-    }
+    if (copy_in) strip_copy_in<T, K, EXACT, COHERENT>(strip, Qt, blk.col0, blk.ncols, watch);
     __syncthreads();
 
     const float shrink = lr * lambda;
@@ -1009,8 +1046,9 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
             lds_owned_chunk<T, K, DEPTH, true>(P, strip, blk.col0, U, V, R, begin, len, mu, mv, mr,
                                                            first_rows, lr, shrink, lane, active);
         } else {
-            if (raw_len < 0 && n_hot > 0) {
+            if (raw_len < 0) {
                 // a piece of a cut row at the front and / or at the back, whole rows between them
+                // (the work lists never cut more rows of a block than it has slots in LDS)
                 auto slot_of = [&](int u) {
                     const unsigned long long hit = __ballot(hot_u == u);
                     return hit ? (int)__builtin_ctzll(hit) : -1;
@@ -1040,11 +1078,10 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
                 if (between > 0)
                     lds_hog_chunk<T, K, DEPTH>(P, strip, blk.col0, U, V, R, begin + front, between, mu, mv, mr,
                                                first_rows, lr, shrink, lane, active, watch);
-            } else if (raw_len < 0)
-                lds_shared_row_chunk<T, K>(P, strip, blk.col0, U, V, R, begin, len, lr, shrink, lane, active, watch);
-            else
+            } else {
                 lds_hog_chunk<T, K, DEPTH>(P, strip, blk.col0, U, V, R, begin, len, mu, mv, mr,
                                                        first_rows, lr, shrink, lane, active, watch);
+            }
         }
     }
     __syncthreads();
@@ -1054,68 +1091,12 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
             Row<VEC> p;
 #pragma unroll
             for (int j = 0; j < VEC; ++j)
-                p.x[j] = active ? quantise<T>(from_strip(hot_rows[slot * K + strip_elem<T>(lane, j)])) : 0.f;
+                p.x[j] = active ? quantise<T>(from_strip<EXACT>(hot_rows[slot * K + strip_elem<T>(lane, j)], worst)) : 0.f;
             store_row<VEC>(P + (int64_t)uniform_lane(hot_u, slot) * K, lane, active, p);
         }
+        watch.see_plain(worst);
     }
-    if constexpr (COHERENT && !EXACT) {
-        constexpr int kPerWord = sizeof(T) == 2 ? 2 : 1;
-        unsigned* dst = reinterpret_cast<unsigned*>(strip_src);
-        const int words = total / kPerWord;
-        for (int w = (int)threadIdx.x; w < words; w += (int)blockDim.x) {
-            unsigned raw;
-            if constexpr (sizeof(T) == 2) {
-                __half2 h = __halves2half2(round_to_half(from_strip(strip[2 * w])),
-                                           round_to_half(from_strip(strip[2 * w + 1])));
-                raw = *reinterpret_cast<unsigned*>(&h);
-            } else {
-                raw = __float_as_uint(from_strip(strip[w]));
-            }
-            __hip_atomic_store(dst + w, raw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    } else if constexpr (COHERENT) {
-        constexpr int kPerPiece = 16 / (int)sizeof(T);
-        const int pieces = total / kPerPiece;
-        const __amdgpu_buffer_rsrc_t rsrc =
-            __builtin_amdgcn_make_buffer_rsrc((void*)strip_src, 0, total * (int)sizeof(T), kRawBufferFlags);
-        for (int pc = (int)threadIdx.x; pc < pieces; pc += (int)blockDim.x) {
-            uint4_t raw;
-            if constexpr (sizeof(T) == 2) {
-#pragma unroll
-                for (int h = 0; h < 4; ++h) {
-                    __half2 hh = __halves2half2(round_to_half(from_strip(strip[pc * 8 + 2 * h])),
-                                                round_to_half(from_strip(strip[pc * 8 + 2 * h + 1])));
-                    raw[h] = *reinterpret_cast<unsigned*>(&hh);
-                }
-            } else {
-                const int4 v = *reinterpret_cast<const int4*>(strip + pc * 4);
-                raw[0] = __float_as_uint(from_strip(v.x));
-                raw[1] = __float_as_uint(from_strip(v.y));
-                raw[2] = __float_as_uint(from_strip(v.z));
-                raw[3] = __float_as_uint(from_strip(v.w));
-            }
-            __builtin_amdgcn_raw_buffer_store_b128(raw, rsrc, pc * 16, 0, kCachePolicySc1);
-        }
-    } else {
-        for (int i = 4 * (int)threadIdx.x; i < total; i += stride) {
-            const int4 raw4 = *reinterpret_cast<const int4*>(strip + i);
-            const float4 val = make_float4(from_strip(raw4.x), from_strip(raw4.y), from_strip(raw4.z),
-                                           from_strip(raw4.w));
-            if constexpr (sizeof(T) == 2) {
-                __half2 a = __halves2half2(round_to_half(val.x), round_to_half(val.y));
-                __half2 b = __halves2half2(round_to_half(val.z), round_to_half(val.w));
-                uint2 raw;
-                raw.x = *reinterpret_cast<unsigned*>(&a);
-                raw.y = *reinterpret_cast<unsigned*>(&b);
-                *reinterpret_cast<uint2*>(strip_src + i) = raw;
-            } else {
-                *reinterpret_cast<float4*>(strip_src + i) = val;
-            }
-        }
-    }
-    if constexpr (!EXACT) {
-        if (__any(watch.hit()) && lane == 0) *range_flag = 1;
-    }
+    if (copy_out) strip_copy_out<T, K, EXACT, COHERENT>(strip, Qt, blk.col0, blk.ncols, watch);
     return true;
 }
 
@@ -1128,17 +1109,22 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_block_lds(
     const LdsBlock* __restrict__ blocks, float lr, float lambda, int* range_flag)
 {
     extern __shared__ int strip[];            // ncols * K values (fixed point, or fp32 bits if EXACT)
+    RangeWatch watch;
     lds_block_body<T, K, EXACT, false, DEPTH>(strip, P, Qt, U, V, R, entry_begin, entry_len, hot_pos, blocks[blockIdx.x], lr,
-                                       lambda, range_flag, [] { return true; });
+                                              lambda, true, true, watch, [] { return true; });
+    if constexpr (!EXACT) {
+        if (__any(watch.hit()) && (threadIdx.x & (kWave - 1)) == 0) *range_flag = 1;
+    }
 }
 
 // One launch per EPOCH: workgroup a keeps block row a for the whole epoch (its rows of P are
 // never touched by anyone else) and walks the strata on blocks (a, (a+s) mod grid_c); the column
 // strips of Qt rotate through the workgroups (the rotation of distributed SGD, here between
 // compute units instead of machines).  `done[a]` counts the steps block row a has finished since
-// mf_load_blocks (`first` = its value before this epoch).  Before step t a workgroup waits for
-// the most recent earlier user of its column strip; that one waited for its own predecessor
-// (every workgroup waits also when its block is empty), so the chain of guarantees is unbroken.
+// mf_load_blocks (`first` = its value before this epoch).  Before it reads the strip of step t a
+// workgroup makes sure that the most recent earlier user of that strip has reported its step; that
+// one waited for its own predecessor (every workgroup waits also when its block is empty), so the
+// chain of guarantees is unbroken.
 //   Strata in natural order (order == nullptr): the only other user of strip (a+s) mod grid_c
 //   is the next block row one stratum earlier, so workgroup a waits for done[a+1] >= first + s
 //   (the last block row waits for block row 0 having finished stratum s - (grid_c - grid_r) - 1).
@@ -1147,16 +1133,19 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_block_lds(
 //   t; the first wavefront takes the latest of them (one look-up per block row, a wave-wide
 //   maximum) and waits for that block row to have finished that step.
 // All grid_r workgroups must be resident at once (checked by the host before launching).
-// Every wait is bounded: after spin_limit polls a workgroup raises *abort_flag and leaves, and
-// every waiting workgroup leaves as soon as it sees the flag, so the grid always drains.
-// abort_flag[1] is the range flag of the fixed-point strip (see RangeWatch).
+// Every wait is bounded: after spin_limit polls a workgroup raises flags[0] and leaves, and every
+// waiting workgroup leaves as soon as it sees the flag, so the grid always drains.  flags[1] is
+// the range flag of the fixed-point strip (see RangeWatch).
+//
+// A step is: request the block's first ratings and rows of P, wait for the strip, strip in, block,
+// strip out, wait for the stores' acknowledgement, report.
 template <typename T, int K, bool EXACT, int DEPTH>
 __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_ring_lds(
     T* __restrict__ P, T* __restrict__ Qt, const int32_t* __restrict__ U,
     const int32_t* __restrict__ V, const float* __restrict__ R,
     const int64_t* __restrict__ entry_begin, const int32_t* __restrict__ entry_len, const int64_t* __restrict__ hot_pos,
     const LdsBlock* __restrict__ ring_blocks, int grid_r, int grid_c, float lr, float lambda,
-    int* done, int first, int* abort_flag, long long spin_limit, const int32_t* __restrict__ order,
+    int* done, int first, int* flags, long long spin_limit, const int32_t* __restrict__ order,
     const int32_t* __restrict__ pos)
 {
     extern __shared__ int strip[];
@@ -1164,6 +1153,7 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_ring_lds(
     const int a = (int)blockIdx.x;
     const int next_row = a + 1 < grid_r ? a + 1 : 0;
     const int lag = a + 1 < grid_r ? 0 : grid_c - grid_r;
+    RangeWatch watch;
     for (int t = 0; t < grid_c; ++t) {
         const int s = order ? order[t] : t;
         // wait (bounded) until the previous user of this step's column strip has reported it
@@ -1200,12 +1190,12 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_ring_lds(
                             // every poll is a round trip to memory: the abort flag is looked at on
                             // every 16th only, so that the counter is read twice as often
                             if ((polls & 15) == 15 &&
-                                __hip_atomic_load(abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                                __hip_atomic_load(flags, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
                                 ok = 0;
                                 break;
                             }
                             if (++polls > spin_limit) {
-                                __hip_atomic_store(abort_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                __hip_atomic_store(flags, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                                 ok = 0;
                                 break;
                             }
@@ -1221,8 +1211,8 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_ring_lds(
         const LdsBlock blk = ring_blocks[(int64_t)s * grid_r + a];
         bool ok;
         if (blk.n_entries > 0)
-            ok = lds_block_body<T, K, EXACT, true, DEPTH>(strip, P, Qt, U, V, R, entry_begin, entry_len, hot_pos, blk, lr, lambda,
-                                                   abort_flag + 1, wait_for_strip);
+            ok = lds_block_body<T, K, EXACT, true, DEPTH>(strip, P, Qt, U, V, R, entry_begin, entry_len, hot_pos, blk, lr,
+                                                          lambda, true, true, watch, wait_for_strip);
         else
             ok = wait_for_strip();   // an empty block still waits: it passes the guarantee on
         if (!ok) return;
@@ -1232,6 +1222,9 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_ring_lds(
         __syncthreads();
         if (threadIdx.x == 0)
             __hip_atomic_store(done + a, first + t + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if constexpr (!EXACT) {
+        if (__any(watch.hit()) && (threadIdx.x & (kWave - 1)) == 0) flags[1] = 1;
     }
 }
 

@@ -1023,7 +1023,7 @@ int mf_plan_host(const int32_t* rows, const int32_t* cols, int64_t nnz, int64_t 
             bound = mf::hogwild_entries_bound(nnz, grid_r, grid_c, chunk, 16);
         } else {
             mf::LdsSchedule l;
-            mf::build_lds_schedule(part, rs, chunk, 16, mode == MF_PLAN_LDS_CUT_ROWS ? mf::kMaxHotRows : 0, l);
+            mf::build_lds_schedule(part, rs, chunk, 16, mf::kMaxHotRows, l);
             if (mode == MF_PLAN_LDS_CUT_ROWS) {
                 bound = mf::lds_hot_bound(nnz, grid_r, grid_c);
                 s.begin = l.hot_pos;

@@ -424,35 +424,44 @@ void build_lds_schedule(const Partition& part, const RowStarts& rs, int32_t chun
                 out.begin.push_back(pos);
                 out.len.push_back(len);
             };
-            if (chunk > 0) chunk_block(rs, part.block_ptr[L], part.block_ptr[L + 1], chunk, push);
-            else chunk_block_even(rs, part.block_ptr[L], part.block_ptr[L + 1], waves, push);
-            blk.n_entries = (int32_t)((int64_t)out.begin.size() - blk.first_entry);
             // The rows of this block that an entry boundary cuts (each is named by the position of
-            // one of its ratings): a boundary lies inside a row when the entry after it does not
-            // begin a row; it continues the row of the boundary before it when that one lay inside
-            // a row too and no row begins between the two.
+            // one of its ratings) are kept in LDS while the block runs.  A boundary lies inside a
+            // row when the entry after it does not begin a row; it continues the row of the
+            // boundary before it when that one lay inside a row too and no row begins between the
+            // two.  A block may cut at most hot_slots rows: if the even division cuts more, the
+            // block is divided again into half as many (twice as long) chunks, down to a single
+            // chunk, which cuts none.
             const int64_t hot_first = (int64_t)out.hot_pos.size();
             int32_t n_hot = 0;
-            bool previous_cut_inside_row = false;
-            for (int64_t e = blk.first_entry + 1; e < (int64_t)out.begin.size() && hot_slots > 0; ++e) {
-                const int64_t at = out.begin[(size_t)e];
-                const bool inside_row = !rs.starts(at);
-                bool same_row = false;
-                if (inside_row && previous_cut_inside_row) {
-                    same_row = true;
-                    for (int64_t i = out.begin[(size_t)e - 1] + 1; i < at && same_row; ++i) same_row = !rs.starts(i);
-                }
-                if (inside_row && !same_row) {
-                    n_hot += 1;
-                    if (n_hot <= hot_slots) out.hot_pos.push_back(at);
-                }
-                previous_cut_inside_row = inside_row;
-            }
-            if (n_hot > hot_slots || hot_first + n_hot >= ((int64_t)1 << 27)) {
-                // more cut rows than slots (or than `hot` can index): this block keeps none in LDS
+            int32_t try_waves = waves, try_chunk = chunk;
+            for (;;) {
+                out.begin.resize((size_t)blk.first_entry);
+                out.len.resize((size_t)blk.first_entry);
                 out.hot_pos.resize((size_t)hot_first);
+                if (try_chunk > 0) chunk_block(rs, part.block_ptr[L], part.block_ptr[L + 1], try_chunk, push);
+                else chunk_block_even(rs, part.block_ptr[L], part.block_ptr[L + 1], try_waves, push);
                 n_hot = 0;
+                bool previous_cut_inside_row = false;
+                for (int64_t e = blk.first_entry + 1; e < (int64_t)out.begin.size(); ++e) {
+                    const int64_t at = out.begin[(size_t)e];
+                    const bool inside_row = !rs.starts(at);
+                    bool same_row = false;
+                    if (inside_row && previous_cut_inside_row) {
+                        same_row = true;
+                        for (int64_t i = out.begin[(size_t)e - 1] + 1; i < at && same_row; ++i) same_row = !rs.starts(i);
+                    }
+                    if (inside_row && !same_row) {
+                        n_hot += 1;
+                        if (n_hot <= hot_slots) out.hot_pos.push_back(at);
+                    }
+                    previous_cut_inside_row = inside_row;
+                }
+                const bool indexable = hot_first + n_hot < ((int64_t)1 << 27);   // what `hot` can index
+                if ((n_hot <= hot_slots && indexable) || (int64_t)out.begin.size() - blk.first_entry <= 1) break;
+                if (try_chunk > 0) try_chunk = try_chunk > (1 << 29) ? (1 << 30) : 2 * try_chunk;
+                else try_waves = std::max(1, try_waves / 2);
             }
+            blk.n_entries = (int32_t)((int64_t)out.begin.size() - blk.first_entry);
             blk.hot = (int32_t)((hot_first << 4) | n_hot);
             out.max_hot = std::max(out.max_hot, n_hot);
             out.blocks.push_back(blk);

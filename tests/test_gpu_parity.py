@@ -271,10 +271,60 @@ def test_ring_kernel_gives_up_cleanly_when_its_wait_limit_is_tiny(mfmod):
     opts = {mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS, mfmod.MF_OPT_RING: 1,
             mfmod.MF_OPT_RING_SPIN_LIMIT: 1}
     model = _make(mfmod, ds, 128, "f32", 64, 64, 1, options=opts)
+    assert model.epoch_plan(mfmod.MF_MODE_HOGWILD)["kernel"] == "sgd_ring_lds"
     model.sgd_epoch(ds.cfg.lr, ds.cfg.lam, mfmod.MF_MODE_HOGWILD)
     with pytest.raises(mfmod.MFError) as e:
         model.sync()
     assert e.value.code == mfmod.binding.MF_EDEVICE
+    # reported once; the context then runs one launch per stratum, which needs no neighbour, and
+    # trains on (from fresh factors: the abandoned epoch left them half-updated)
+    model.sync()
+    plan = model.epoch_plan(mfmod.MF_MODE_HOGWILD)
+    assert plan["kernel"] == "sgd_block_lds" and "wait limit" in plan["note"], plan
+    B = mfmod.binding
+    B.mf_init(model.ctx, ds.cfg.m, ds.cfg.n, 128, B.MF_F32, model.P.data_ptr(), model.Qt.data_ptr(), 1, 0.1)
+    model.load_blocks(ds.rows, ds.cols, ds.vals, 64, 64, 1)          # a new load may use the one-launch kernel again
+    B.mf_set_option(model.ctx, mfmod.MF_OPT_RING_SPIN_LIMIT, 1 << 22)
+    tr, tc, tv = model.to_device(ds.test_rows, ds.test_cols, ds.test_vals)
+    before = model.rmse(tr, tc, tv)
+    for _ in range(3):
+        model.sgd_epoch(ds.cfg.lr, ds.cfg.lam, mfmod.MF_MODE_HOGWILD)
+    assert model.rmse(tr, tc, tv) < before
+    model.close()
+
+
+# ------------------------------------------------------------------------------- divergence is reported, not wrapped round
+@pytest.mark.parametrize("ring", [1, 0])
+@pytest.mark.parametrize("case", ["value", "change", "sane"])
+def test_hogwild_lds_kernel_reports_values_outside_its_fixed_point_range(mfmod, ring, case):
+    """The Hogwild LDS kernel keeps Qt as 32-bit fixed point in [-128, 128).  Forced from the host:
+    factors preset to 70 (value watch, limit 64), or ratings so large that one step changes an
+    element by more than 4 (change watch).  Every kernel ends normally; the next synchronising
+    call returns MF_ERANGE once.  Sane inputs raise nothing."""
+    ds = dataset("tiny")
+    cfg = ds.cfg
+    B = mfmod.binding
+    opts = {mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS, mfmod.MF_OPT_RING: ring}
+    model = mfmod.MatrixFactorization(cfg.m, cfg.n, 32, "f32", seed=1, scale=0.1, options=opts)
+    vals = ds.vals
+    lr = 0.0
+    if case == "value":
+        model.Qt.fill_(70.0)
+    elif case == "change":
+        vals = np.full_like(ds.vals, 3.0e4)      # e ~ 3e4, lr*e*p ~ 0.01 * 3e4 * 0.05 = 15 > 4
+        lr = 0.01
+    model.load_blocks(ds.rows, ds.cols, vals, 16, 16, 1)
+    model.sgd_epoch(lr, 0.0, mfmod.MF_MODE_HOGWILD)
+    if case == "sane":
+        model.sync()
+    else:
+        with pytest.raises(mfmod.MFError) as e:
+            model.sync()
+        assert e.value.code == B.MF_ERANGE, e.value
+        model.sync()                               # reported once
+        if case == "value":
+            # the values themselves were inside +-128 and came back unchanged (lr = 0)
+            assert float(model.Qt.min()) == 70.0 and float(model.Qt.max()) == 70.0
     model.close()
 
 
