@@ -102,6 +102,71 @@ def cpu_baseline(ds, gr, gc, k, split, scale):
             "host_cores": len(os.sched_getaffinity(0))}
 
 
+def block_size_curve(args, mf, ds):
+    """--curve: kernel time per launch against ratings per launch, on random subsets of the
+    workload at a fixed grid, for one launch per stratum and for one launch per epoch (the
+    analogue of the paper's Fig. 3a / Fig. 7), with least-squares fits of the two forms of the
+    paper's kernel cost model (Section 5.3): T = a|R| + b, and T = |R| / (a log|R| + b).
+    Prints the markdown tables of profiles/block_size_curve_<workload>.md."""
+    import numpy as np
+
+    cfg = ds.cfg
+    rng = np.random.Generator(np.random.Philox(7))
+    fractions = (0.01, 0.02, 0.05, 0.1, 0.2, 0.35, 0.5, 0.75, 1.0)
+    print(f"# Kernel time against ratings per launch: {cfg.name}, k={cfg.k} {cfg.storage}, Hogwild, LDS kernels")
+    print(f"\nCommand: `python bench.py --curve --workload {args.workload} --steps {args.steps}`"
+          " (times: HIP events around every launch, MF_OPT_PROFILE).\n")
+    for grid, ring in ((128, 0), (224, 1)):
+        pts = []
+        for frac in fractions:
+            keep = rng.random(ds.rows.size) < frac
+            rows, cols, vals = (np.ascontiguousarray(x[keep]) for x in (ds.rows, ds.cols, ds.vals))
+            model = mf.MatrixFactorization(cfg.m, cfg.n, cfg.k, cfg.storage, scale=args.init_scale,
+                                           options={mf.MF_OPT_PROFILE: 1, mf.MF_OPT_RING: ring,
+                                                    mf.MF_OPT_HOGWILD_KERNEL: mf.MF_HOGWILD_LDS})
+            model.load_blocks(rows, cols, vals, grid, grid, mf.MF_SPLIT_NNZ_BALANCED)
+            model.sgd_epoch(cfg.lr, cfg.lam, mf.MF_MODE_HOGWILD)
+            mf.binding.mf_profile_read(model.ctx)
+            for _ in range(args.steps):
+                model.sgd_epoch(cfg.lr, cfg.lam, mf.MF_MODE_HOGWILD)
+            ms, launches = mf.binding.mf_profile_read(model.ctx)
+            model.close()
+            pts.append((rows.size * args.steps / launches, ms / launches * 1e3))
+        size = np.array([p[0] for p in pts])
+        us = np.array([p[1] for p in pts])
+        a1, b1 = np.polyfit(size, us, 1)
+        rate = size / us                                     # ratings per microsecond = a log|R| + b
+        a2, b2 = np.polyfit(np.log(size), rate, 1)
+        fit1, fit2 = a1 * size + b1, size / (a2 * np.log(size) + b2)
+        what = "one launch per epoch" if ring else "one launch per stratum"
+        print(f"## {what}, {grid} x {grid} grid: |R| = ratings per launch\n")
+        print("| ratings |R| | kernel us | G updates/s | affine fit us | log-model fit us |\n|---|---|---|---|---|")
+        for i in range(size.size):
+            print(f"| {size[i]:.0f} | {us[i]:.2f} | {size[i] / us[i] / 1e3:.3f} | {fit1[i]:.2f} | {fit2[i]:.2f} |")
+        e1, e2 = np.abs(fit1 - us) / us, np.abs(fit2 - us) / us
+        print(f"\nT = a|R| + b: a = {a1 * 1e3:.4f} ns per rating, b = {b1:.2f} us; mean relative error {e1.mean() * 100:.1f} %, "
+              f"max {e1.max() * 100:.1f} %; asymptotic rate {1e-3 / a1:.2f} G updates/s.")
+        print(f"T = |R| / (a log|R| + b): a = {a2:.2f}, b = {b2:.2f} (ratings per us); mean relative error "
+              f"{e2.mean() * 100:.1f} %, max {e2.max() * 100:.1f} %.\n")
+
+
+def rmse_kernel_bench(args, mf, model, nnz, k, elt):
+    """--rmse-bench: the RMSE kernel alone over the loaded training ratings (packed order)."""
+    import torch
+
+    model.rmse()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        value = model.rmse()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    per_entry = 12 + 2 * k * elt                 # rating record + read of p_u and q_v
+    print(json.dumps({"rmse_kernel": True, "entries": nnz, "ms_per_call": dt * 1e3, "entries_per_s": nnz / dt,
+                      "bytes_per_entry": per_entry, "algorithmic_gbs": nnz * per_entry / dt / 1e9,
+                      "frac_of_hbm_peak": nnz * per_entry / dt / 1e9 / HBM_PEAK_GBS, "train_rmse": value}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -125,6 +190,10 @@ def main():
                     help="partition on the host (mf_load_blocks) or on the GPU (mf_load_blocks_device); outside the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
+    ap.add_argument("--curve", action="store_true",
+                    help="print the block-size curve of the workload (subsampled, both launch schemes) and exit")
+    ap.add_argument("--rmse-bench", action="store_true",
+                    help="time mf_rmse over the loaded training ratings --steps times and exit")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="only run a plain device copy of this many MiB five times (a kernel of known "
                          "traffic, used to scale the profiler's FETCH_SIZE / WRITE_SIZE readings) and exit")
@@ -160,6 +229,9 @@ def main():
     ds = load_dataset(args.workload, args.scale)
     t_generate = time.perf_counter() - t0
     cfg = ds.cfg
+    if args.curve:
+        block_size_curve(args, mf, ds)
+        return
     gr, gc = (int(x) for x in args.grid.split("x"))
     mode = mf.MF_MODE_HOGWILD if args.mode == "hogwild" else mf.MF_MODE_DET
     k = cfg.k
@@ -190,6 +262,10 @@ def main():
         t_load = time.perf_counter() - t0
     tr, tc, tv = model.to_device(ds.test_rows, ds.test_cols, ds.test_vals)
     nnz = ds.rows.size
+    if args.rmse_bench:
+        rmse_kernel_bench(args, mf, model, nnz, k, elt)
+        model.close()
+        return
     plan = model.epoch_plan(mode)     # the kernel the library launches for this mode and grid
     print(f"bench: {cfg.name} generated in {t_generate:.1f} s, loaded in {t_load:.2f} s; {plan['note']}",
           file=sys.stderr, flush=True)

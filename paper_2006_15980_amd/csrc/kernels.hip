@@ -696,6 +696,10 @@ __device__ __forceinline__ void lds_hog_chunk(T* __restrict__ P, int* strip, int
 // LDS beside the strip, in the strip's fixed-point format, for as long as the block runs, and is
 // read and changed exactly like q_v (LDS atomic adds: no change is lost, every wavefront sees the
 // others' changes at once).  `prow`: the row's LDS slot.  All ratings of the piece have this row.
+// Both operands stay in the strip's scale (see lds_hog_chunk), and the operands of the NEXT rating
+// are read from LDS before this rating's sum is reduced: LDS executes a wavefront's operations in
+// order, so those reads see the state before this rating's own adds, which are then applied to
+// the copies in registers (changes other wavefronts make meanwhile arrive one rating later).
 template <typename T, int K>
 __device__ __forceinline__ void lds_hot_row_piece(int* prow, int* strip, int col0,
                                                   const int32_t* __restrict__ V,
@@ -703,15 +707,24 @@ __device__ __forceinline__ void lds_hot_row_piece(int* prow, int* strip, int col
                                                   float lr, float shrink, int lane, bool active, RangeWatch& watch)
 {
     constexpr int VEC = RowShape<T, K>::VEC;
-    float worst = 0.f;      // values, and 16 x changes, so that one limit (kWatchPlain) serves both
+    constexpr float kFromFixedSquared = kFromFixed * kFromFixed;
+    auto read_scaled = [&](const int* row) {
+        Row<VEC> x;
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) x.x[j] = active ? (float)row[strip_elem<T>(lane, j)] : 0.f;
+        return x;
+    };
     int mv = 0, nv = 0;
     float mr = 0.f, nr = 0.f;
     if (lane < min(kWave, len)) {
         mv = V[begin + lane];
         mr = R[begin + lane];
     }
+    Row<VEC> qs = read_scaled(strip + (uniform_lane(mv, 0) - col0) * K);
+    Row<VEC> ps = read_scaled(prow);
     for (int32_t off = 0; off < len; off += kWave) {
         const int cnt = min(kWave, len - off);
+        const bool more = len - off > kWave;
         if (lane < len - off - kWave) {
             nv = V[begin + off + kWave + lane];
             nr = R[begin + off + kWave + lane];
@@ -720,30 +733,36 @@ __device__ __forceinline__ void lds_hot_row_piece(int* prow, int* strip, int col
             const int v = uniform_lane(mv, i);
             const float r = __int_as_float(uniform_lane(__float_as_int(mr), i));
             int* const qrow = strip + (v - col0) * K;
-            const Row<VEC> q = strip_read<T, VEC>(qrow, lane, active);
-            const Row<VEC> p = strip_read<T, VEC>(prow, lane, active);
+            // the column of the rating after this one (at the end of the piece: this one again)
+            const int v_next = i + 1 < cnt ? uniform_lane(mv, i + 1) : (more ? uniform_lane(nv, 0) : v);
+            Row<VEC> qn = read_scaled(strip + (v_next - col0) * K);
+            Row<VEC> pn = read_scaled(prow);
             float part = 0.f;
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) part = fmaf(p.x[j], q.x[j], part);
-            const float step = lr * (r - wave_sum(part));
+            for (int j = 0; j < VEC; ++j) part = fmaf(ps.x[j], qs.x[j], part);
+            const float step = lr * fmaf(-kFromFixedSquared, wave_sum_fused(part), r);
+            Row<VEC> dqs, dps;
 #pragma unroll
             for (int j = 0; j < VEC; ++j) {
-                const float change_q = fmaf(step, p.x[j], -shrink * q.x[j]);
-                const float change_p = fmaf(step, q.x[j], -shrink * p.x[j]);
-                worst = fmaxf(fmaxf(worst, fabsf(q.x[j])), fabsf(p.x[j]));
-                worst = fmaxf(fmaxf(worst, 16.f * fabsf(change_q)), 16.f * fabsf(change_p));
-                const int dq = to_fixed(change_q);
-                const int dp = to_fixed(change_p);
+                dqs.x[j] = fmaf(step, ps.x[j], -shrink * qs.x[j]);
+                dps.x[j] = fmaf(step, qs.x[j], -shrink * ps.x[j]);
+                const int dq = __float2int_rn(dqs.x[j]);
+                const int dp = __float2int_rn(dps.x[j]);
                 if (active) {
                     atomicAdd(&qrow[strip_elem<T>(lane, j)], dq);
                     atomicAdd(&prow[strip_elem<T>(lane, j)], dp);
                 }
+                pn.x[j] += (float)dp;
+                if (v_next == v) qn.x[j] += (float)dq;
             }
+            watch.see<VEC>(qs, dqs);
+            watch.see<VEC>(ps, dps);
+            qs = qn;
+            ps = pn;
         }
         mv = nv;
         mr = nr;
     }
-    watch.see_plain(worst);
 }
 
 // Number of ratings at the front (FROM_END: at the back) of the packed range [begin, begin+len)

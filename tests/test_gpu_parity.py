@@ -901,6 +901,89 @@ def test_other_configs_scaled(mfmod, name):
     _config_case(mfmod, name, scale, det_grid, hog_grid, epochs)
 
 
+# ------------------------------------------------------------------------------- binary16 storage against the DEFINITION
+# The element-wise binary16 comparisons above are against the oracle's F16 arithmetic, whose fp32
+# operation sequence is the kernel's.  These two tie the binary16 path to Algorithm 1 itself, i.e.
+# to the oracle's F64 arithmetic: one step at a time (where the only freedom is the rounding), and
+# over the epochs of the configuration that names binary16 storage.
+def test_binary16_single_steps_round_the_fp64_definition(mfmod):
+    """n independent ratings (rating i sits alone in row i and column i), one deterministic epoch on
+    binary16 storage: every element of the result must be the binary16 neighbour of the exact
+    (fp64) step of Algorithm 1 -- the nearest one, or, where the exact value lies within fp32
+    rounding of a tie between two binary16 values, either of the two."""
+    n, k = 4096, 128
+    rng = np.random.Generator(np.random.Philox(77))
+    rows = np.arange(n, dtype=np.int32)
+    cols = rng.permutation(n).astype(np.int32)
+    vals = rng.uniform(1.0, 5.0, n).astype(np.float32)
+    P0 = rng.uniform(0.0, 0.5, (n, k)).astype(np.float16).astype(np.float64)
+    Q0 = rng.uniform(0.0, 0.5, (n, k)).astype(np.float16).astype(np.float64)
+    lr, lam = 0.01, 0.05
+    for kernel in ("global", "lds"):
+        model = mfmod.MatrixFactorization(n, n, k, "f16", seed=1, scale=-1.0, options=_det_options(mfmod, kernel))
+        model.set_factors(P0, Q0)
+        model.load_blocks(rows, cols, vals, 64, 64, 1)
+        model.sgd_epoch(lr, lam, mfmod.MF_MODE_DET)
+        P, Q = model.get_factors()
+        model.close()
+        Po, Qo = P0.copy(), Q0.copy()
+        perm, bp, _, _ = oracle.partition(rows, cols, n, n, 64, 64, 1)
+        oracle.sgd_epoch(Po, Qo, rows, cols, vals, perm, bp, 64, 64, lr, lam, oracle.ARITH_F64)
+        for X, Xo in ((P, Po), (Q, Qo)):
+            nearest = Xo.astype(np.float16).astype(np.float64)
+            off = X != nearest
+            ulp = np.spacing(np.abs(nearest).astype(np.float16)).astype(np.float64)
+            # always within half a binary16 spacing of the exact value, up to the fp32 rounding of the
+            # step's operands (all of magnitude below 1: two roundings of 2^-24 each) ...
+            assert (np.abs(X - Xo) <= 0.5 * ulp + 2.0 ** -23).all()
+            # ... and off the nearest value only at near-ties, which are rare
+            print("binary16 single steps (%s): %d of %d elements are not the nearest binary16 value of the fp64 step"
+                  % (kernel, int(off.sum()), off.size), flush=True)
+            assert off.mean() <= 1e-3
+
+
+def test_binary16_config_final_rmse_against_the_fp64_definition(mfmod):
+    """Configuration 5 (binary16 storage) at the tested scale, all its epochs: the held-out RMSE
+    of the deterministic GPU run against the oracle's F64 arithmetic (Algorithm 1 in double,
+    nothing rounded to binary16), and against its F16 arithmetic for reference."""
+    scale, det_grid, _, _ = OTHER["stress"]
+    ds = dataset("stress", scale)
+    cfg = ds.cfg
+    epochs = cfg.epochs
+    got = _train_gpu(mfmod, ds, cfg.k, "f16", det_grid[0], det_grid[1], 1, mfmod.MF_MODE_DET, epochs)
+    P64, Q64, _ = oracle_train(ds, det_grid[0], det_grid[1], 1, epochs, arith=oracle.ARITH_F64)
+    want64 = oracle.rmse(P64, Q64, ds.test_rows, ds.test_cols, ds.test_vals)
+    P16, Q16, _ = oracle_train(ds, det_grid[0], det_grid[1], 1, epochs, arith=oracle.ARITH_F16)
+    want16 = oracle.rmse(P16, Q16, ds.test_rows, ds.test_cols, ds.test_vals)
+    print("stress@%g DET binary16, %d epochs: rmse gpu %.6f, oracle F64 %.6f, oracle F16 %.6f"
+          % (scale, epochs, got, want64, want16), flush=True)
+    assert abs(got - want16) <= 1e-3
+    assert abs(got - want64) <= 1e-3
+
+
+def test_binary16_hogwild_on_the_l2_atomics_kernel(mfmod):
+    """The Hogwild fallback for grids whose strips do not fit the LDS adds binary16-rounded
+    changes with packed atomics in the L2; configuration 5 at the tested scale, on a grid that
+    forces it, has to stay inside the 0.5 % band as well."""
+    scale, _, _, epochs = OTHER["stress"]
+    ds = dataset("stress", scale)
+    cfg = ds.cfg
+    Po, Qo, _ = oracle_train(ds, 8, 8, 1, epochs, arith=oracle.ARITH_F16)
+    want = oracle.rmse(Po, Qo, ds.test_rows, ds.test_cols, ds.test_vals)
+    model = _make(mfmod, ds, cfg.k, "f16", 8, 8, 1)
+    plan = model.epoch_plan(mfmod.MF_MODE_HOGWILD)
+    assert plan["kernel"] == "sgd_chunks", plan          # MF_HOGWILD_AUTO says which kernel it took, and why
+    assert "exceeds" in plan["note"]
+    tr, tc, tv = model.to_device(ds.test_rows, ds.test_cols, ds.test_vals)
+    for _ in range(epochs):
+        model.sgd_epoch(cfg.lr, cfg.lam, mfmod.MF_MODE_HOGWILD)
+    got = model.rmse(tr, tc, tv)
+    model.close()
+    print("stress@%g HOGWILD on the L2-atomics kernel, %d epochs: rmse gpu %.6f oracle %.6f" % (scale, epochs, got, want),
+          flush=True)
+    assert abs(got - want) <= 0.005 * want
+
+
 @pytest.mark.parametrize("name", ["large", "xlarge"])
 def test_binary16_storage_on_the_fp32_configs(mfmod, name):
     """Half-precision storage is an option for every configuration, not only the one that names it."""
