@@ -812,10 +812,38 @@ __device__ __forceinline__ float from_strip(int x, float& worst)
     return f;
 }
 
+// SPARSE: only the columns whose bit is set in the block's table of touched columns are copied
+// (lane l of every wavefront holds bit word l in `mask_word`); the other columns of the strip
+// keep whatever the LDS held, which no rating of the block reads.  Taken in the one-launch
+// Hogwild form, where a wavefront's 64 consecutive words lie in one column; ignored elsewhere.
+template <typename T, int K>
+struct SparseStrip {
+    static constexpr int kWordsPerColumn = K * (int)sizeof(T) / 4;
+    static constexpr bool kPossible = kWordsPerColumn % kWave == 0;
+};
+
+// Which of its pieces of the strip a wavefront copies: the strip is copied in pieces of 64
+// consecutive 32-bit words, piece j of a wavefront beginning at word (its first thread) + j *
+// blockDim.x; bit j of the result is set when that piece lies inside the strip and -- if `sparse`
+// -- in a touched column.  Worked out once per block by the 64 lanes together (lane j looks at
+// piece j) and used by the copy in and the copy out, so that neither loop has to wait for
+// anything but its own memory operations.  Needs words <= 64 * blockDim.x; all lanes active.
+template <typename T, int K>
+__device__ __forceinline__ unsigned long long strip_pieces(int words, unsigned mask_word, bool sparse)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int w = (int)(threadIdx.x & ~(unsigned)(kWave - 1)) + lane * (int)blockDim.x;
+    const int column = min(w, words - 1) / SparseStrip<T, K>::kWordsPerColumn;
+    const unsigned bits = (unsigned)__shfl((int)mask_word, column >> 5, kWave);
+    bool take = w < words;
+    if (sparse) take = take && ((bits >> (column & 31)) & 1u);
+    return __ballot(take);
+}
+
 // Columns col0 .. col0+ncols of Qt into LDS, by all threads of the workgroup (no barrier inside).
-template <typename T, int K, bool EXACT, bool COHERENT>
+template <typename T, int K, bool EXACT, bool COHERENT, bool SPARSE>
 __device__ __forceinline__ void strip_copy_in(int* strip, const T* __restrict__ Qt, int col0, int ncols,
-                                              RangeWatch& watch)
+                                              RangeWatch& watch, unsigned mask_word)
 {
     float worst = 0.f;
     const int total = ncols * K;          // multiple of 32
@@ -829,17 +857,22 @@ __device__ __forceinline__ void strip_copy_in(int* strip, const T* __restrict__ 
         const unsigned* src = reinterpret_cast<const unsigned*>(strip_src);
         const int words = total / kPerWord;
         constexpr int kInFlight = 16;
-        for (int w0 = (int)threadIdx.x; w0 < words; w0 += kInFlight * (int)blockDim.x) {
+        unsigned long long pieces = ~0ull;
+        const bool by_pieces = SPARSE && SparseStrip<T, K>::kPossible && words <= kWave * (int)blockDim.x;
+        if (by_pieces) pieces = strip_pieces<T, K>(words, mask_word, true);
+        for (int w0 = (int)threadIdx.x, j0 = 0; w0 < words; w0 += kInFlight * (int)blockDim.x, j0 += kInFlight) {
             unsigned raw[kInFlight];
+            const unsigned now = by_pieces ? (unsigned)(pieces >> j0) & ((1u << kInFlight) - 1u) : ~0u;
+            if (now == 0u) continue;
 #pragma unroll
             for (int t = 0; t < kInFlight; ++t) {
                 const int w = w0 + t * (int)blockDim.x;
-                if (w < words) raw[t] = load_word<true>(src + w);
+                if (w < words && ((now >> t) & 1u)) raw[t] = load_word<true>(src + w);
             }
 #pragma unroll
             for (int t = 0; t < kInFlight; ++t) {
                 const int w = w0 + t * (int)blockDim.x;
-                if (w < words) {
+                if (w < words && ((now >> t) & 1u)) {
                     if constexpr (sizeof(T) == 2) {
                         const float2 f = unpack_half2(raw[t]);
                         strip[2 * w] = to_strip<EXACT>(f.x, worst);
@@ -917,9 +950,9 @@ __device__ __forceinline__ void strip_copy_in(int* strip, const T* __restrict__ 
 }
 
 // The strip in LDS back to columns col0 .. col0+ncols of Qt, by all threads of the workgroup.
-template <typename T, int K, bool EXACT, bool COHERENT>
+template <typename T, int K, bool EXACT, bool COHERENT, bool SPARSE>
 __device__ __forceinline__ void strip_copy_out(const int* strip, T* __restrict__ Qt, int col0, int ncols,
-                                               RangeWatch& watch)
+                                               RangeWatch& watch, unsigned mask_word)
 {
     float worst = 0.f;
     const int total = ncols * K;
@@ -929,7 +962,11 @@ __device__ __forceinline__ void strip_copy_out(const int* strip, T* __restrict__
         constexpr int kPerWord = sizeof(T) == 2 ? 2 : 1;
         unsigned* dst = reinterpret_cast<unsigned*>(strip_dst);
         const int words = total / kPerWord;
-        for (int w = (int)threadIdx.x; w < words; w += (int)blockDim.x) {
+        unsigned long long pieces = ~0ull;
+        const bool by_pieces = SPARSE && SparseStrip<T, K>::kPossible && words <= kWave * (int)blockDim.x;
+        if (by_pieces) pieces = strip_pieces<T, K>(words, mask_word, true);
+        for (int w = (int)threadIdx.x; w < words; w += (int)blockDim.x, pieces >>= 1) {
+            if (by_pieces && !(pieces & 1ull)) continue;
             unsigned raw;
             if constexpr (sizeof(T) == 2) {
                 __half2 h = __halves2half2(round_to_half(from_strip<EXACT>(strip[2 * w], worst)),
@@ -988,15 +1025,15 @@ __device__ __forceinline__ void strip_copy_out(const int* strip, T* __restrict__
 // and before the strip is read: the ring kernel waits there for the strip's previous user
 // (returning false means "give up": the workgroup leaves); everything requested before it is
 // independent of the strip.  copy_in / copy_out = false: the caller moves the strip itself.
-template <typename T, int K, bool EXACT, bool COHERENT, int DEPTH, class BeforeStrip>
+template <typename T, int K, bool EXACT, bool COHERENT, int DEPTH, bool SPARSE, class BeforeStrip>
 __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T* __restrict__ Qt,
                                                const int32_t* __restrict__ U, const int32_t* __restrict__ V,
                                                const float* __restrict__ R,
                                                const int64_t* __restrict__ entry_begin,
                                                const int32_t* __restrict__ entry_len,
                                                const int64_t* __restrict__ hot_pos, const LdsBlock blk,
-                                               float lr, float lambda, bool copy_in, bool copy_out, RangeWatch& watch,
-                                               BeforeStrip before_strip)
+                                               float lr, float lambda, bool copy_in, bool copy_out, unsigned mask_word,
+                                               RangeWatch& watch, BeforeStrip before_strip)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const bool active = RowShape<T, K>::ACTIVE == kWave ? true : lane < RowShape<T, K>::ACTIVE;
@@ -1049,7 +1086,7 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
                 if (active) hot_rows[slot * K + strip_elem<T>(lane, j)] = to_strip<EXACT>(p.x[j], worst);
         }
     }
-    if (copy_in) strip_copy_in<T, K, EXACT, COHERENT>(strip, Qt, blk.col0, blk.ncols, watch);
+    if (copy_in) strip_copy_in<T, K, EXACT, COHERENT, SPARSE>(strip, Qt, blk.col0, blk.ncols, watch, mask_word);
     __syncthreads();
 
     const float shrink = lr * lambda;
@@ -1115,7 +1152,7 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
         }
         watch.see_plain(worst);
     }
-    if (copy_out) strip_copy_out<T, K, EXACT, COHERENT>(strip, Qt, blk.col0, blk.ncols, watch);
+    if (copy_out) strip_copy_out<T, K, EXACT, COHERENT, SPARSE>(strip, Qt, blk.col0, blk.ncols, watch, mask_word);
     return true;
 }
 
@@ -1129,8 +1166,9 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_block_lds(
 {
     extern __shared__ int strip[];            // ncols * K values (fixed point, or fp32 bits if EXACT)
     RangeWatch watch;
-    lds_block_body<T, K, EXACT, false, DEPTH>(strip, P, Qt, U, V, R, entry_begin, entry_len, hot_pos, blocks[blockIdx.x], lr,
-                                              lambda, true, true, watch, [] { return true; });
+    lds_block_body<T, K, EXACT, false, DEPTH, false>(strip, P, Qt, U, V, R, entry_begin, entry_len, hot_pos,
+                                                     blocks[blockIdx.x], lr, lambda, true, true, 0xffffffffu, watch,
+                                                     [] { return true; });
     if constexpr (!EXACT) {
         if (__any(watch.hit()) && (threadIdx.x & (kWave - 1)) == 0) *range_flag = 1;
     }
@@ -1158,14 +1196,14 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_block_lds(
 //
 // A step is: request the block's first ratings and rows of P, wait for the strip, strip in, block,
 // strip out, wait for the stores' acknowledgement, report.
-template <typename T, int K, bool EXACT, int DEPTH>
+template <typename T, int K, bool EXACT, int DEPTH, bool SPARSE>
 __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_ring_lds(
     T* __restrict__ P, T* __restrict__ Qt, const int32_t* __restrict__ U,
     const int32_t* __restrict__ V, const float* __restrict__ R,
     const int64_t* __restrict__ entry_begin, const int32_t* __restrict__ entry_len, const int64_t* __restrict__ hot_pos,
     const LdsBlock* __restrict__ ring_blocks, int grid_r, int grid_c, float lr, float lambda,
     int* done, int first, int* flags, long long spin_limit, const int32_t* __restrict__ order,
-    const int32_t* __restrict__ pos)
+    const int32_t* __restrict__ pos, const unsigned* __restrict__ touched, int touched_words)
 {
     extern __shared__ int strip[];
     __shared__ int go;
@@ -1228,10 +1266,17 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_ring_lds(
             return go != 0;                        // the same answer in every thread of the workgroup
         };
         const LdsBlock blk = ring_blocks[(int64_t)s * grid_r + a];
+        // the block's table of touched columns, one bit word per lane (requested before the wait)
+        unsigned mask_word = 0xffffffffu;
+        if constexpr (SPARSE) {
+            const int lane = threadIdx.x & (kWave - 1);
+            mask_word = lane < touched_words ? touched[(int64_t)blk.id * touched_words + lane] : 0u;
+        }
         bool ok;
         if (blk.n_entries > 0)
-            ok = lds_block_body<T, K, EXACT, true, DEPTH>(strip, P, Qt, U, V, R, entry_begin, entry_len, hot_pos, blk, lr,
-                                                          lambda, true, true, watch, wait_for_strip);
+            ok = lds_block_body<T, K, EXACT, true, DEPTH, SPARSE>(strip, P, Qt, U, V, R, entry_begin, entry_len, hot_pos,
+                                                                  blk, lr, lambda, true, true, mask_word, watch,
+                                                                  wait_for_strip);
         else
             ok = wait_for_strip();   // an empty block still waits: it passes the guarantee on
         if (!ok) return;
@@ -1336,6 +1381,42 @@ __global__ __launch_bounds__(kGroupThreads) void init_fill(T* __restrict__ X, in
     }
 }
 
+// Table of touched columns: for every block of the list, bit c of its `words` bit words is set
+// when the block has a rating in column col0 + c of its strip.  One workgroup per block; the
+// block's ratings are the packed range its entries cover (they follow each other).
+// totals[0] += touched columns of the block, totals[1] += columns of its strip.
+__global__ __launch_bounds__(kGroupThreads) void mark_touched(const LdsBlock* __restrict__ blocks,
+                                                              const int64_t* __restrict__ entry_begin,
+                                                              const int32_t* __restrict__ entry_len,
+                                                              const int32_t* __restrict__ V, uint32_t* __restrict__ touched,
+                                                              int words, unsigned long long* totals)
+{
+    __shared__ unsigned bits[kMaxTouchedWords];
+    const LdsBlock blk = blocks[blockIdx.x];
+    if ((int)threadIdx.x < kMaxTouchedWords) bits[threadIdx.x] = 0u;
+    __syncthreads();
+    if (blk.n_entries > 0) {
+        const int64_t last = blk.first_entry + blk.n_entries - 1;
+        const int64_t begin = entry_begin[blk.first_entry];
+        const int64_t end = entry_begin[last] + (entry_len[last] & ~kSharedRowFlag);
+        for (int64_t i = begin + (int64_t)threadIdx.x; i < end; i += (int64_t)blockDim.x) {
+            const int c = V[i] - blk.col0;
+            if (c >= 0 && c < 32 * words) atomicOr(&bits[c >> 5], 1u << (c & 31));
+        }
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < words) touched[(int64_t)blk.id * words + threadIdx.x] = bits[threadIdx.x];
+    if (threadIdx.x < kWave) {
+        int set = (int)threadIdx.x < words ? __popc(bits[threadIdx.x]) : 0;   // words <= 64 = one wavefront
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) set += __shfl_xor(set, d, kWave);
+        if (threadIdx.x == 0) {
+            atomicAdd(&totals[0], (unsigned long long)set);
+            atomicAdd(&totals[1], (unsigned long long)blk.ncols);
+        }
+    }
+}
+
 __global__ void fill_i32(int32_t* out, int64_t count, int32_t value)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -1386,27 +1467,27 @@ hipError_t launch_sgd_lds_impl(int waves, void* P, void* Qt, const int32_t* U, c
     return hipGetLastError();
 }
 
-template <typename T, int K, bool EXACT, int DEPTH>
+template <typename T, int K, bool EXACT, int DEPTH, bool SPARSE>
 hipError_t launch_sgd_ring_impl(int waves, bool query_only, int* max_resident, void* P, void* Qt,
                                 const int32_t* U, const int32_t* V, const float* R, const int64_t* eb,
                                 const int32_t* el, const int64_t* hot, const LdsBlock* ring_blocks, int grid_r, int grid_c,
                                 size_t lds_bytes, float lr, float lambda, int* done, int first,
                                 int* abort_flag, long long spin_limit, const int32_t* order, const int32_t* pos,
-                                hipStream_t stream)
+                                const uint32_t* touched, int touched_words, hipStream_t stream)
 {
     static bool raised[64] = {};
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev >= 0 && dev < 64 && !raised[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sgd_ring_lds<T, K, EXACT, DEPTH>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sgd_ring_lds<T, K, EXACT, DEPTH, SPARSE>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
         if (e != hipSuccess) return e;
         raised[dev] = true;
     }
     if (query_only) {
         int per_cu = 0, cus = 0;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, sgd_ring_lds<T, K, EXACT, DEPTH>, waves * kWave,
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, sgd_ring_lds<T, K, EXACT, DEPTH, SPARSE>, waves * kWave,
                                                          lds_bytes);
         if (e != hipSuccess) return e;
         e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
@@ -1414,9 +1495,9 @@ hipError_t launch_sgd_ring_impl(int waves, bool query_only, int* max_resident, v
         *max_resident = per_cu * cus;
         return hipSuccess;
     }
-    hipLaunchKernelGGL((sgd_ring_lds<T, K, EXACT, DEPTH>), dim3((unsigned)grid_r), dim3(waves * kWave), lds_bytes,
+    hipLaunchKernelGGL((sgd_ring_lds<T, K, EXACT, DEPTH, SPARSE>), dim3((unsigned)grid_r), dim3(waves * kWave), lds_bytes,
                        stream, (T*)P, (T*)Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lr, lambda, done,
-                       first, abort_flag, spin_limit, order, pos);
+                       first, abort_flag, spin_limit, order, pos, touched, touched_words);
     return hipGetLastError();
 }
 
@@ -1425,21 +1506,32 @@ hipError_t launch_sgd_ring_t(bool exact, bool short_prefetch, int waves, bool qu
                              const int32_t* U, const int32_t* V, const float* R, const int64_t* eb,
                              const int32_t* el, const int64_t* hot, const LdsBlock* ring_blocks, int grid_r, int grid_c,
                              size_t lds_bytes, float lr, float lambda, int* done, int first, int* abort_flag,
-                             long long spin_limit, const int32_t* order, const int32_t* pos, hipStream_t stream)
+                             long long spin_limit, const int32_t* order, const int32_t* pos, const uint32_t* touched,
+                             int touched_words, hipStream_t stream)
 {
     if (exact)
-        return launch_sgd_ring_impl<T, K, true, kLdsPrefetchDepth>(1, query_only, max_resident, P, Qt, U, V, R, eb, el, hot,
-                                                                   ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda,
-                                                                   done, first, abort_flag, spin_limit, order, pos,
-                                                                   stream);
+        return launch_sgd_ring_impl<T, K, true, kLdsPrefetchDepth, false>(
+            1, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done,
+            first, abort_flag, spin_limit, order, pos, nullptr, 0, stream);
+    // the form that copies only the touched columns of a strip exists where a wavefront's piece of
+    // the strip lies in one column
+    if constexpr (SparseStrip<T, K>::kPossible) {
+        if (touched && short_prefetch)
+            return launch_sgd_ring_impl<T, K, false, kShortPrefetchDepth, true>(
+                waves, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda,
+                done, first, abort_flag, spin_limit, order, pos, touched, touched_words, stream);
+        if (touched)
+            return launch_sgd_ring_impl<T, K, false, kLdsPrefetchDepth, true>(
+                waves, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda,
+                done, first, abort_flag, spin_limit, order, pos, touched, touched_words, stream);
+    }
     if (short_prefetch)
-        return launch_sgd_ring_impl<T, K, false, kShortPrefetchDepth>(waves, query_only, max_resident, P, Qt, U, V, R, eb,
-                                                                      el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr,
-                                                                      lambda, done, first, abort_flag, spin_limit, order,
-                                                                      pos, stream);
-    return launch_sgd_ring_impl<T, K, false, kLdsPrefetchDepth>(waves, query_only, max_resident, P, Qt, U, V, R, eb, el, hot,
-                                                                ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done,
-                                                                first, abort_flag, spin_limit, order, pos, stream);
+        return launch_sgd_ring_impl<T, K, false, kShortPrefetchDepth, false>(
+            waves, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done,
+            first, abort_flag, spin_limit, order, pos, nullptr, 0, stream);
+    return launch_sgd_ring_impl<T, K, false, kLdsPrefetchDepth, false>(
+        waves, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done,
+        first, abort_flag, spin_limit, order, pos, nullptr, 0, stream);
 }
 
 template <typename T, int K>
@@ -1523,13 +1615,25 @@ hipError_t launch_sgd_ring(int dtype, int k, bool exact, bool short_prefetch, in
                            const int64_t* entry_begin, const int32_t* entry_len, const int64_t* hot_pos, const LdsBlock* ring_blocks,
                            int grid_r, int grid_c, size_t lds_bytes, float lr, float lambda, int* done,
                            int first, int* abort_flag, long long spin_limit, const int32_t* order,
-                           const int32_t* pos, hipStream_t stream)
+                           const int32_t* pos, const uint32_t* touched, int touched_words, hipStream_t stream)
 {
     if (waves < 1 || waves > 16 || lds_bytes > kLdsBudget || grid_r < 1) return hipErrorInvalidValue;
     if ((order == nullptr) != (pos == nullptr)) return hipErrorInvalidValue;
+    if (touched && (touched_words < 1 || touched_words > kMaxTouchedWords)) return hipErrorInvalidValue;
     MF_DISPATCH(launch_sgd_ring_t, exact, short_prefetch, waves, query_only, max_resident, P, Qt, U, V, R, entry_begin,
                 entry_len, hot_pos, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done, first, abort_flag,
-                spin_limit, order, pos, stream);
+                spin_limit, order, pos, touched, touched_words, stream);
+}
+
+hipError_t launch_mark_touched(const LdsBlock* blocks, int64_t n_blocks, const int64_t* entry_begin,
+                               const int32_t* entry_len, const int32_t* V, uint32_t* touched, int words,
+                               unsigned long long* totals, hipStream_t stream)
+{
+    if (n_blocks <= 0) return hipSuccess;
+    if (words < 1 || words > kMaxTouchedWords) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(mark_touched, dim3((unsigned)n_blocks), dim3(kGroupThreads), 0, stream, blocks, entry_begin,
+                       entry_len, V, touched, words, totals);
+    return hipGetLastError();
 }
 
 hipError_t launch_rmse(int dtype, int k, const void* P, const void* Qt, const int32_t* U,

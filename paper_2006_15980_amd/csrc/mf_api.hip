@@ -14,6 +14,10 @@
 #include "../../include/mf_sgd.h"
 #include "mf_internal.h"
 
+// The one-launch Hogwild kernel copies only the touched columns of a strip when at most this
+// share of all strip columns is touched.
+constexpr double kSparseStripShare = 0.75;
+
 struct mf_ctx {
     int device = 0;
     hipStream_t stream = nullptr;
@@ -26,6 +30,7 @@ struct mf_ctx {
     void* dP = nullptr;
     void* dQt = nullptr;
 
+    double touched_share = 1.0;   // touched columns / strip columns over the blocks of the last load
     // partition and schedules
     bool loaded = false;
     mf::Partition part;
@@ -124,13 +129,24 @@ bool valid_k(int32_t k) { return k == 32 || k == 64 || k == 128 || k == 256; }
 
 struct Layout {
     size_t off_u, off_v, off_r, off_perm, off_begin[2], off_len[2], off_lds_begin, off_lds_len, off_lds_blocks,
-        off_dlds_begin, off_dlds_len, off_dlds_blocks, off_ring[2], off_ring_done, off_order, off_hot, total;
+        off_dlds_begin, off_dlds_len, off_dlds_blocks, off_ring[2], off_ring_done, off_order, off_hot, off_touched, total;
     int64_t cap[2], lds_cap, lds_blocks_cap, hot_cap;
+    int32_t touched_words;
 };
 
-Layout make_layout(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t lds_chunk, int32_t lds_waves,
-                   bool resident = true)
+// Bit words per block of the table of touched columns: room for the widest strip that fits the
+// LDS with this k (before mf_init: the most the table can have).  0 in streamed mode, where the
+// table is not built.
+int32_t touched_words_bound(const mf_ctx* ctx)
 {
+    if (!ctx->inited) return mf::kMaxTouchedWords;
+    const int64_t cols = std::min<int64_t>(ctx->n, (int64_t)mf::kLdsBudget / ((int64_t)ctx->k * 4));
+    return (int32_t)std::min<int64_t>(mf::kMaxTouchedWords, (cols + 31) / 32);
+}
+
+Layout make_layout(const mf_ctx* ctx, int64_t nnz, int32_t gr, int32_t gc, bool resident = true)
+{
+    const int32_t chunk = ctx->hogwild_chunk, lds_chunk = ctx->lds_chunk, lds_waves = ctx->lds_waves;
     const size_t packed = resident ? (size_t)nnz * 4 : 0;   // streamed mode keeps the ratings on the host
     Layout l;
     l.cap[MF_MODE_DET] = mf::det_entries_bound(gr, gc);
@@ -159,6 +175,8 @@ Layout make_layout(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, int32_t l
     l.off_ring_done = off; off += align_up(((size_t)gr + 2) * 4);
     l.off_order = off; off += align_up((size_t)gc * 2 * 4);   // stratum order of an epoch and its inverse
     l.off_hot = off; off += align_up((size_t)l.hot_cap * 8);   // cut rows of the Hogwild LDS work list
+    l.touched_words = resident ? touched_words_bound(ctx) : 0;
+    l.off_touched = off; off += align_up((size_t)l.lds_blocks_cap * l.touched_words * 4) + 256;   // + two counters
     l.total = off;
     return l;
 }
@@ -358,7 +376,7 @@ int mf_load_blocks_workspace(const mf_ctx* ctx, int64_t nnz, int32_t grid_r, int
     if (!ctx || !bytes_out) return MF_EINVAL;
     int rc = check_grid(const_cast<mf_ctx*>(ctx), nnz, grid_r, grid_c);
     if (rc) return rc;
-    *bytes_out = make_layout(nnz, grid_r, grid_c, ctx->hogwild_chunk, ctx->lds_chunk, ctx->lds_waves).total;
+    *bytes_out = make_layout(ctx, nnz, grid_r, grid_c).total;
     return MF_OK;
 }
 
@@ -376,7 +394,7 @@ int check_load(mf_ctx* ctx, const void* rows, const void* cols, const void* vals
     if (nnz > 0 && (!rows || !cols || !vals)) return fail(ctx, MF_EINVAL, "null rating array");
     if (!d_workspace) return fail(ctx, MF_EINVAL, "null workspace");
     if ((uintptr_t)d_workspace & 255) return fail(ctx, MF_EINVAL, "workspace must be 256-byte aligned");
-    lay = make_layout(nnz, grid_r, grid_c, ctx->hogwild_chunk, ctx->lds_chunk, ctx->lds_waves, resident);
+    lay = make_layout(ctx, nnz, grid_r, grid_c, resident);
     if (workspace_bytes < lay.total) return fail(ctx, MF_ENOMEM, "workspace too small");
     return MF_OK;
 }
@@ -438,6 +456,33 @@ int finish_load(mf_ctx* ctx, const Layout& lay, char* base, const mf::RowStarts&
             MF_HIP(ctx, hipMemcpy(l.d_len, l.len.data(), l.len.size() * 4, hipMemcpyHostToDevice));
             MF_HIP(ctx, hipMemcpy(l.d_blocks, l.blocks.data(), l.blocks.size() * sizeof(mf::LdsBlock),
                                   hipMemcpyHostToDevice));
+        }
+    }
+    // which columns of its strip every block of the Hogwild list touches (resident ratings only)
+    ctx->lds.d_touched = nullptr;
+    ctx->lds.touched_words = 0;
+    ctx->det_lds.d_touched = nullptr;
+    ctx->det_lds.touched_words = 0;
+    // The kernel uses the table when it saves enough: looking a column up costs a little on every
+    // step, which only pays when a good part of the strips' columns can be skipped (measured: a
+    // gain of 8-10 % with 45 % of the columns touched, a loss of 7 % with nearly all touched).
+    const int32_t words = (ctx->lds.max_cols + 31) / 32;
+    ctx->touched_share = 1.0;
+    if (!ctx->streamed && ctx->dV && words >= 1 && words <= lay.touched_words && !ctx->lds.blocks.empty()) {
+        uint32_t* table = (uint32_t*)(base + lay.off_touched);
+        unsigned long long* totals =
+            (unsigned long long*)(base + lay.off_touched + align_up((size_t)lay.lds_blocks_cap * lay.touched_words * 4));
+        MF_HIP(ctx, mf::launch_fill_i32((int32_t*)table, (int64_t)lay.lds_blocks_cap * words, 0, ctx->stream));
+        MF_HIP(ctx, mf::launch_fill_i32((int32_t*)totals, 4, 0, ctx->stream));
+        MF_HIP(ctx, mf::launch_mark_touched(ctx->lds.d_blocks, (int64_t)ctx->lds.blocks.size(), ctx->lds.d_begin,
+                                            ctx->lds.d_len, ctx->dV, table, words, totals, ctx->stream));
+        MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        unsigned long long sums[2] = {0, 0};
+        MF_HIP(ctx, hipMemcpy(sums, totals, 16, hipMemcpyDeviceToHost));
+        if (sums[1] > 0) ctx->touched_share = (double)sums[0] / (double)sums[1];
+        if (ctx->touched_share <= kSparseStripShare) {
+            ctx->lds.d_touched = table;
+            ctx->lds.touched_words = words;
         }
     }
     ctx->d_ring_done = (int32_t*)(base + lay.off_ring_done);
@@ -530,7 +575,7 @@ int mf_load_blocks_streamed_workspace(const mf_ctx* ctx, int64_t nnz, int32_t gr
     if (!ctx || !bytes_out) return MF_EINVAL;
     int rc = check_grid(const_cast<mf_ctx*>(ctx), nnz, grid_r, grid_c);
     if (rc) return rc;
-    *bytes_out = make_layout(nnz, grid_r, grid_c, ctx->hogwild_chunk, ctx->lds_chunk, ctx->lds_waves, false).total;
+    *bytes_out = make_layout(ctx, nnz, grid_r, grid_c, false).total;
     return MF_OK;
 }
 
@@ -671,7 +716,7 @@ int plan_epoch(mf_ctx* ctx, int32_t mode, EpochPlan& p)
             MF_HIP(ctx, mf::launch_sgd_ring(ctx->dtype, ctx->k, !p.hog, p.short_prefetch, ctx->lds_waves_used, true, &resident,
                                             nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
                                             ctx->part.gr, ctx->part.gc, p.lds_bytes, 0.f, 0.f, nullptr, 0, nullptr, 0,
-                                            nullptr, nullptr, ctx->stream));
+                                            nullptr, nullptr, nullptr, 0, ctx->stream));
             ctx->ring_resident[m_idx] = resident;
         }
         p.ring = ctx->part.gr <= ctx->ring_resident[m_idx];
@@ -693,6 +738,9 @@ int plan_epoch(mf_ctx* ctx, int32_t mode, EpochPlan& p)
     p.note = std::string(p.hog ? "MF_MODE_HOGWILD" : "MF_MODE_DET") + ": " + names[p.kernel] + ", " +
              std::to_string(p.launches) + " launch(es) per epoch, " + std::to_string(p.waves) +
              " wavefront(s) per workgroup" + (why.empty() ? "" : " (" + why.substr(0, why.size() - 2) + ")");
+    if (p.hog && p.ring && lsched.d_touched)
+        p.note += "; copies only the touched columns of a strip (" +
+                  std::to_string((int)(ctx->touched_share * 100.0 + 0.5)) + " % of all strip columns)";
     if (!p.hog && p.kernel == MF_KERNEL_ID_CHUNKS && choice != MF_KERNEL_GLOBAL)
         p.note += "; this grid was not made for the deterministic mode: one wavefront per block and one launch per "
                   "stratum (mf_suggest_grid gives a grid whose strips fit)";
@@ -770,7 +818,8 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
                                         ctx->part.gr, ctx->part.gc, lds_bytes, lr, lambda, ctx->d_ring_done,
                                         ctx->ring_epochs * ctx->part.gc, d_flags,
                                         (long long)ctx->spin_limit, stratum_order ? ctx->d_order : nullptr,
-                                        stratum_order ? ctx->d_order + gc : nullptr, ctx->stream));
+                                        stratum_order ? ctx->d_order + gc : nullptr, lsched.d_touched,
+                                        lsched.touched_words, ctx->stream));
         if (ev1) MF_HIP(ctx, hipEventRecord(ev1, ctx->stream));
         ctx->ring_epochs += 1;
         return MF_OK;

@@ -34,13 +34,19 @@ struct Schedule {
 // several wavefronts) are held in LDS beside the strip while the block runs: `hot` = number of
 // such rows (low 4 bits, at most kMaxHotRows) and the index of the first of them in the
 // schedule's hot_pos list (the bits above).
+// `id` = the block's linear id L = stratum * G_r + block row; it indexes the table of touched
+// columns (one bit per column of the block's strip: set when the block has a rating there),
+// with which the one-launch Hogwild kernel copies only those columns in and out of LDS.
 constexpr int32_t kMaxHotRows = 8;
+constexpr int32_t kMaxTouchedWords = 64;   // bit words per block of that table (one per lane of a wavefront)
 struct LdsBlock {
     int64_t first_entry;
     int32_t n_entries;
     int32_t col0;
     int32_t ncols;
     int32_t hot;
+    int32_t id;
+    int32_t reserved;
 };
 
 struct LdsSchedule {
@@ -57,6 +63,8 @@ struct LdsSchedule {
     LdsBlock* d_blocks = nullptr;
     LdsBlock* d_ring = nullptr;
     int64_t* d_hot = nullptr;
+    uint32_t* d_touched = nullptr;       // touched-column bits, touched_words per block id; null = not built
+    int32_t touched_words = 0;
 };
 
 // Where the runs of one matrix row begin in the packed order: bit i is set when rating i has
@@ -159,12 +167,20 @@ hipError_t launch_sgd_lds(int dtype, int k, bool exact, bool short_prefetch, int
 // entries each, both or neither): the stratum of every step and its inverse.  abort_flag: two
 // device ints, [0] raised when a bounded wait expires, [1] the range flag.  query_only: do not launch,
 // return in *max_resident how many workgroups of this shape the device can hold at once.
+// touched (device, may be null) / touched_words: the table of touched columns per block id
+// (launch_mark_touched); with it the Hogwild form copies only the touched columns of a strip.
 hipError_t launch_sgd_ring(int dtype, int k, bool exact, bool short_prefetch, int waves, bool query_only, int* max_resident,
                            void* P, void* Qt, const int32_t* U, const int32_t* V, const float* R,
                            const int64_t* entry_begin, const int32_t* entry_len, const int64_t* hot_pos, const LdsBlock* ring_blocks,
                            int grid_r, int grid_c, size_t lds_bytes, float lr, float lambda, int* done,
                            int first, int* abort_flag, long long spin_limit, const int32_t* order,
-                           const int32_t* pos, hipStream_t stream);
+                           const int32_t* pos, const uint32_t* touched, int touched_words, hipStream_t stream);
+// Fill the table of touched columns for the blocks of a list (entries of untouched / empty blocks
+// are left as they are: clear the table first).  totals (device, two 64-bit counters, cleared by
+// the caller): [0] += touched columns, [1] += strip columns, summed over the blocks.
+hipError_t launch_mark_touched(const LdsBlock* blocks, int64_t n_blocks, const int64_t* entry_begin,
+                               const int32_t* entry_len, const int32_t* V, uint32_t* touched, int words,
+                               unsigned long long* totals, hipStream_t stream);
 size_t lds_strip_bytes(int k, int32_t max_cols);   // dynamic LDS the kernel needs for a grid
 constexpr size_t kLdsBudget = 160 * 1024 - 1024;   // LDS of one gfx950 compute unit, minus static use
 hipError_t launch_init(int dtype, void* X, int64_t count, uint64_t seed, uint64_t stream_id,

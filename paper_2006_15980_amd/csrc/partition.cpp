@@ -368,6 +368,35 @@ static void chunk_block_even(const RowStarts& rs, int64_t pos, int64_t end, int3
     }
 }
 
+// Cut [pos, end) greedily into chunks of at most `cap` ratings.  A chunk ends at a row boundary
+// unless the row that straddles its cap is long (more than cap/2 ratings in this block) or began
+// the chunk already: then the cut stays inside the row, and the chunks on both sides of it are
+// flagged as sharing a row of P.  A short straddling row goes whole to the next chunk, so every
+// chunk but the last is more than half full.  The workgroup is as slow as its longest chunk: the
+// caller looks for the smallest cap whose division fits its wavefronts and its slots for cut rows.
+template <class Emit>
+static void chunk_block_capped(const RowStarts& rs, int64_t pos, int64_t end, int64_t cap, Emit emit_raw)
+{
+    int64_t cur = pos;
+    bool starts_inside_row = false;
+    while (cur < end) {
+        int64_t cut = std::min(end, cur + cap);
+        bool ends_inside_row = false;
+        if (cut < end && !rs.starts(cut)) {
+            int64_t row_begin = cut, row_end = cut;
+            while (row_begin > cur && !rs.starts(row_begin)) --row_begin;
+            while (row_end < end && !rs.starts(row_end)) ++row_end;
+            if (row_begin > cur && 2 * (row_end - row_begin) <= cap) cut = row_begin;
+            else ends_inside_row = true;
+        }
+        int32_t len = (int32_t)(cut - cur);
+        if (starts_inside_row || ends_inside_row) len |= (int32_t)0x80000000;
+        emit_raw(cur, len);
+        starts_inside_row = ends_inside_row;
+        cur = cut;
+    }
+}
+
 void build_hogwild_schedule(const Partition& part, const RowStarts& rs, int32_t chunk,
                             int32_t waves, bool xcd_affinity, Schedule& out)
 {
@@ -408,7 +437,7 @@ void build_lds_schedule(const Partition& part, const RowStarts& rs, int32_t chun
     out.max_cols = 0;
     for (int32_t b = 0; b < part.gc; ++b)
         out.max_cols = std::max(out.max_cols, part.col_bounds[b + 1] - part.col_bounds[b]);
-    out.ring.assign((size_t)part.gr * part.gc, LdsBlock{0, 0, 0, 0, 0});
+    out.ring.assign((size_t)part.gr * part.gc, LdsBlock{0, 0, 0, 0, 0, 0, 0});
     hot_slots = std::min(hot_slots, kMaxHotRows);
     for (int32_t s = 0; s < part.gc; ++s) {
         for (int32_t a = 0; a < part.gr; ++a) {
@@ -420,6 +449,8 @@ void build_lds_schedule(const Partition& part, const RowStarts& rs, int32_t chun
             blk.col0 = part.col_bounds[b];
             blk.ncols = part.col_bounds[b + 1] - part.col_bounds[b];
             blk.hot = 0;
+            blk.id = (int32_t)L;
+            blk.reserved = 0;
             auto push = [&](int64_t pos, int32_t len) {
                 out.begin.push_back(pos);
                 out.len.push_back(len);
@@ -428,18 +459,21 @@ void build_lds_schedule(const Partition& part, const RowStarts& rs, int32_t chun
             // one of its ratings) are kept in LDS while the block runs.  A boundary lies inside a
             // row when the entry after it does not begin a row; it continues the row of the
             // boundary before it when that one lay inside a row too and no row begins between the
-            // two.  A block may cut at most hot_slots rows: if the even division cuts more, the
-            // block is divided again into half as many (twice as long) chunks, down to a single
-            // chunk, which cuts none.
+            // two.  A block may have at most `waves` entries and cut at most hot_slots rows: the
+            // division starts from chunks of size/waves ratings and is repeated with longer chunks
+            // (an eighth longer each time; a given chunk length is doubled) until both hold --
+            // at the latest with a single chunk, which cuts none.
             const int64_t hot_first = (int64_t)out.hot_pos.size();
             int32_t n_hot = 0;
-            int32_t try_waves = waves, try_chunk = chunk;
+            int32_t try_chunk = chunk;
+            const int64_t size = part.block_ptr[L + 1] - part.block_ptr[L];
+            int64_t cap = std::max<int64_t>(8, (size + waves - 1) / waves);
             for (;;) {
                 out.begin.resize((size_t)blk.first_entry);
                 out.len.resize((size_t)blk.first_entry);
                 out.hot_pos.resize((size_t)hot_first);
                 if (try_chunk > 0) chunk_block(rs, part.block_ptr[L], part.block_ptr[L + 1], try_chunk, push);
-                else chunk_block_even(rs, part.block_ptr[L], part.block_ptr[L + 1], try_waves, push);
+                else chunk_block_capped(rs, part.block_ptr[L], part.block_ptr[L + 1], cap, push);
                 n_hot = 0;
                 bool previous_cut_inside_row = false;
                 for (int64_t e = blk.first_entry + 1; e < (int64_t)out.begin.size(); ++e) {
@@ -457,9 +491,11 @@ void build_lds_schedule(const Partition& part, const RowStarts& rs, int32_t chun
                     previous_cut_inside_row = inside_row;
                 }
                 const bool indexable = hot_first + n_hot < ((int64_t)1 << 27);   // what `hot` can index
-                if ((n_hot <= hot_slots && indexable) || (int64_t)out.begin.size() - blk.first_entry <= 1) break;
+                const int64_t entries = (int64_t)out.begin.size() - blk.first_entry;
+                const bool fits = n_hot <= hot_slots && indexable && (try_chunk > 0 || entries <= waves);
+                if (fits || entries <= 1) break;
                 if (try_chunk > 0) try_chunk = try_chunk > (1 << 29) ? (1 << 30) : 2 * try_chunk;
-                else try_waves = std::max(1, try_waves / 2);
+                else cap += std::max<int64_t>(1, cap / 8);
             }
             blk.n_entries = (int32_t)((int64_t)out.begin.size() - blk.first_entry);
             blk.hot = (int32_t)((hot_first << 4) | n_hot);
@@ -515,7 +551,7 @@ void build_det_lds_schedule(const Partition& part, LdsSchedule& out)
     out.max_cols = 0;
     for (int32_t b = 0; b < part.gc; ++b)
         out.max_cols = std::max(out.max_cols, part.col_bounds[b + 1] - part.col_bounds[b]);
-    out.ring.assign((size_t)part.gr * part.gc, LdsBlock{0, 0, 0, 0, 0});
+    out.ring.assign((size_t)part.gr * part.gc, LdsBlock{0, 0, 0, 0, 0, 0, 0});
     for (int32_t s = 0; s < part.gc; ++s) {
         for (int32_t a = 0; a < part.gr; ++a) {
             int64_t L = (int64_t)s * part.gr + a;
@@ -528,6 +564,8 @@ void build_det_lds_schedule(const Partition& part, LdsSchedule& out)
             blk.col0 = part.col_bounds[b];
             blk.ncols = part.col_bounds[b + 1] - part.col_bounds[b];
             blk.hot = 0;
+            blk.id = (int32_t)L;
+            blk.reserved = 0;
             out.begin.push_back(part.block_ptr[L]);
             out.len.push_back((int32_t)size);
             out.blocks.push_back(blk);
@@ -541,7 +579,8 @@ int64_t lds_entries_bound(int64_t nnz, int32_t gr, int32_t gc, int32_t chunk, in
 {
     // as above, without padding; with chunk == 0 a block is cut into at most `waves` chunks
     if (chunk > 0) return 4 * (nnz / chunk + 1) + 2 * (int64_t)gr * gc;
-    return std::min<int64_t>(nnz / 8 + 1, (int64_t)waves * gr * gc) + (int64_t)gr * gc;
+    // (chunks but the last of a block are more than half full, and a full one has at least 8 ratings)
+    return std::min<int64_t>(nnz / 4 + 1, (int64_t)waves * gr * gc) + (int64_t)gr * gc;
 }
 
 }  // namespace mf

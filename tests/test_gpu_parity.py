@@ -711,6 +711,76 @@ def test_hogwild_pieces_of_long_rows_in_one_wavefront_follow_the_sequential_orde
     assert dp <= 2e-4 and dq <= 2e-4, (dp, dq)
 
 
+@pytest.mark.parametrize("storage,k,grid", [("f32", 128, (8, 32)), ("f32", 64, (8, 20)), ("f16", 128, (8, 32)),
+                                             ("f32", 256, (8, 63))])
+def test_one_launch_hogwild_kernel_copies_only_the_touched_columns(mfmod, storage, k, grid):
+    """When the blocks have ratings in a minority of their strips' columns, the one-launch Hogwild
+    kernel copies only those in and out of LDS (a table of touched columns per block, made at load
+    time).  With ONE wavefront per workgroup the Hogwild arithmetic is sequential, so that kernel
+    must give the bits of the one-launch-per-stratum kernel, which copies whole strips -- in every
+    column that has a rating.  A column without ratings is never copied by the first and is put on
+    the 2^-24 grid of the strip by the second: there the first must return the initial value.
+    (Strips of at most 4096 words: what one wavefront's 64 piece bits cover.)"""
+    ds = dataset("tiny")
+    take = 5600                                  # about half of a block's strip columns have a rating
+    rows, cols, vals = ds.rows[:take].copy(), ds.cols[:take].copy(), ds.vals[:take].copy()
+    cols[cols >= 990] -= 500                     # columns 990..999 have no ratings at all
+    gr, gc = grid
+    outs, notes = [], []
+    for ring in (1, 0):
+        model = mfmod.MatrixFactorization(ds.cfg.m, ds.cfg.n, k, storage, seed=3, scale=0.1,
+                                          options={mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS,
+                                                   mfmod.MF_OPT_LDS_WAVES: 1, mfmod.MF_OPT_RING: ring})
+        model.load_blocks(rows, cols, vals, gr, gc, 0)
+        if ring == 1:
+            P0, Q0 = model.get_factors()
+        notes.append(model.epoch_plan(mfmod.MF_MODE_HOGWILD)["note"])
+        for _ in range(3):
+            model.sgd_epoch(0.01, 0.05, mfmod.MF_MODE_HOGWILD)
+        model.sync()
+        outs.append(model.get_factors())
+        model.close()
+    assert "touched columns" in notes[0] and "touched columns" not in notes[1], notes
+    rated = np.zeros(ds.cfg.n, bool)
+    rated[cols] = True
+    assert not rated[990:].any() and rated[:990].sum() > 900
+    assert np.array_equal(outs[0][0], outs[1][0])                       # P
+    assert np.array_equal(outs[0][1][rated], outs[1][1][rated])         # Qt where it was ever used
+    assert np.array_equal(outs[0][1][~rated], Q0[~rated])               # and never touched elsewhere
+    assert not np.array_equal(outs[0][1][rated], Q0[rated])
+
+
+def test_touched_columns_only_with_sixteen_wavefronts_visits_every_rating_once(mfmod):
+    """The first-order argument of test_hogwild_visits_every_rating_exactly_once for the form that
+    copies only touched columns, with 16 wavefronts per workgroup and k = 128: at lr = 1e-5 and
+    lambda = 0 the order of the ratings matters to second order only, while one rating that is
+    missed moves its row by up to 3e-6, and a touched column that was not copied in (stale LDS) or
+    not copied back shows at full size."""
+    ds = dataset("tiny")
+    cfg = ds.cfg
+    take = 9500                                   # 37 ratings per block on strips of 62 columns
+    rows, cols, vals = ds.rows[:take], ds.cols[:take], ds.vals[:take]
+    gr, gc, lr, lam = 16, 16, 1e-5, 0.0
+    model = mfmod.MatrixFactorization(cfg.m, cfg.n, 128, "f32", seed=1, scale=0.1,
+                                      options={mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS, mfmod.MF_OPT_RING: 1,
+                                               mfmod.MF_OPT_LDS_WAVES: 16})
+    model.load_blocks(rows, cols, vals, gr, gc, 1)
+    plan = model.epoch_plan(mfmod.MF_MODE_HOGWILD)
+    assert plan["kernel"] == "sgd_ring_lds" and plan["waves"] == 16 and "touched columns" in plan["note"], plan
+    model.sgd_epoch(lr, lam, mfmod.MF_MODE_HOGWILD)
+    P, Q = model.get_factors()
+    model.close()
+    perm, bp, _, _ = oracle.partition(rows, cols, cfg.m, cfg.n, gr, gc, 1)
+    P0, Q0 = oracle_init(cfg.m, cfg.n, 128, 1, 0.1)
+    Po, Qo = P0.copy(), Q0.copy()
+    oracle.sgd_epoch_omp(Po, Qo, rows, cols, vals, perm, bp, gr, gc, lr, lam)
+    dp, dq = float(np.abs(P - Po).max()), float(np.abs(Q - Qo).max())
+    moved = float(np.abs(Po - P0).max())
+    print("touched columns only, 16 wavefronts: max|dP| %.2e max|dQ| %.2e, the epoch moves P by up to %.2e"
+          % (dp, dq, moved), flush=True)
+    assert moved > 5e-6 and dp <= 6e-7 and dq <= 1.2e-6, (moved, dp, dq)
+
+
 def test_lds_kernel_is_refused_when_the_strip_does_not_fit(mfmod):
     ds = dataset("tiny")
     model = _make(mfmod, ds, 256, "f32", 2, 2, 0, options={mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS})

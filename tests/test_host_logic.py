@@ -179,6 +179,36 @@ def test_cut_rows_of_the_lds_work_list(grid, chunk):
     assert found_some
 
 
+@pytest.mark.parametrize("grid", [(1, 1), (3, 4), (8, 8)])
+def test_lds_work_list_divides_a_block_evenly(grid):
+    """With no chunk length given, a block is divided for the 16 wavefronts of a workgroup: at most
+    16 entries, none longer than the cap the division settled on, and every entry but the last
+    more than half as long as the longest (a short row that straddles the cap goes whole to the
+    next entry, a long one is cut), so that no wavefront works much longer than the others.  A
+    block of single-rating rows is divided into entries of ceil(size / 16) ratings exactly."""
+    gr, gc = grid
+    seen_uneven = False
+    for name, rows, cols, m, n in _cases():
+        if gr > m or gc > n:
+            continue
+        plan = B.mf_plan_host(rows, cols, m, n, gr, gc, B.MF_SPLIT_NNZ_BALANCED, B.MF_PLAN_HOGWILD_LDS, 0)
+        eb, bp, perm = plan["entry_begin"], plan["block_ptr"], plan["perm"]
+        lens = plan["entry_len"] & 0x7FFFFFFF
+        pu = rows[perm]
+        block_of = np.searchsorted(bp, eb, side="right") - 1
+        for L in np.unique(block_of):
+            mine = lens[block_of == L]
+            size = int(bp[L + 1] - bp[L])
+            assert mine.sum() == size and 1 <= mine.size <= 16, (name, grid, L)
+            longest = int(mine.max())
+            assert all(2 * int(x) >= longest for x in mine[:-1]), (name, grid, L, mine)
+            block_rows = pu[bp[L]:bp[L + 1]]
+            if np.all(block_rows[1:] != block_rows[:-1]) and size >= 128:
+                assert longest == -(-size // 16), (name, grid, L, mine)
+            seen_uneven = seen_uneven or longest > -(-size // 16)
+    assert seen_uneven          # some block has rows that could not be divided exactly
+
+
 def test_plan_rejects_bad_arguments():
     rows = np.array([0, 1, 2], np.int32)
     cols = np.array([0, 1, 5], np.int32)
