@@ -27,8 +27,8 @@ WORKLOAD_DEFAULTS = {
     "tiny": ("16x16", 1, 0.1),
     "medium": ("256x256", 1, 0.1),
     "large": ("224x224", 1, 0.1),
-    "xlarge": ("256x3072", 2, 1.25),
-    "stress": ("256x6400", 2, 0.1),
+    "xlarge": ("256x2048", 2, 1.25),
+    "stress": ("256x2560", 2, 0.1),
 }
 CPU_SAMPLE = 16_000_000     # ratings of the workload the CPU oracle is timed on
 

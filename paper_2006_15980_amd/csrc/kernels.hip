@@ -591,8 +591,19 @@ __device__ __forceinline__ float wave_sum_fused(float x)
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
 }
 
-template <typename T, int K, int DEPTH>
-__device__ __forceinline__ void lds_hog_chunk(T* __restrict__ P, int* strip, int col0,
+// Where the columns of a batch of ratings sit in the strip: lane l's column index becomes the
+// index of that column's K values in LDS.  The strip holds either all columns of its range
+// (slot = column - col0) or only the touched ones, packed (slots: one 16-bit entry per column of
+// the range, written for the touched columns when the block began).
+template <bool SPARSE>
+__device__ __forceinline__ int strip_slots(int mv, int col0, const unsigned short* slots, bool valid)
+{
+    if constexpr (SPARSE) return valid ? (int)slots[mv - col0] : 0;
+    else return mv - col0;
+}
+
+template <typename T, int K, int DEPTH, bool SPARSE>
+__device__ __forceinline__ void lds_hog_chunk(T* __restrict__ P, int* strip, int col0, const unsigned short* slots,
                                               const int32_t* __restrict__ U,
                                               const int32_t* __restrict__ V,
                                               const float* __restrict__ R, int64_t begin, int32_t len,
@@ -601,6 +612,7 @@ __device__ __forceinline__ void lds_hog_chunk(T* __restrict__ P, int* strip, int
                                               float shrink, int lane, bool active, RangeWatch& watch)
 {
     constexpr int VEC = RowShape<T, K>::VEC;
+    mv = strip_slots<SPARSE>(mv, col0, slots, lane < min(kWave, len));   // from here on: slots, not columns
     Row<VEC> p_prev;
 #pragma unroll
     for (int j = 0; j < VEC; ++j) p_prev.x[j] = 0.f;
@@ -608,8 +620,8 @@ __device__ __forceinline__ void lds_hog_chunk(T* __restrict__ P, int* strip, int
     int nu = 0, nv = 0;
     float nr = 0.f;
     auto row_of = [&](int u) { return P + (int64_t)u * K; };
-    auto read_scaled = [&](int v) {
-        const int* qrow = strip + (v - col0) * K;
+    auto read_scaled = [&](int slot) {
+        const int* qrow = strip + slot * K;
         Row<VEC> q;
 #pragma unroll
         for (int j = 0; j < VEC; ++j) q.x[j] = active ? (float)qrow[strip_elem<T>(lane, j)] : 0.f;
@@ -668,7 +680,7 @@ __device__ __forceinline__ void lds_hog_chunk(T* __restrict__ P, int* strip, int
                 const float sh = valid ? shrink : 0.f;
                 const float step_q = step * kFromFixed;   // (lr*e) * q       = step_q * qs
                 const float step_p = step * kToFixed;     // (lr*e) * p * 2^24 = step_p * p
-                int* const qrow = strip + (v - col0) * K;
+                int* const qrow = strip + v * K;
                 Row<VEC> p2, dqs;
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) {
@@ -685,7 +697,7 @@ __device__ __forceinline__ void lds_hog_chunk(T* __restrict__ P, int* strip, int
             }
         }
         mu = nu;
-        mv = nv;
+        mv = strip_slots<SPARSE>(nv, col0, slots, lane < len - off - kWave);
         mr = nr;
     }
     if constexpr (DEPTH >= kLdsPrefetchDepth) __builtin_amdgcn_s_setprio(0);
@@ -700,8 +712,8 @@ __device__ __forceinline__ void lds_hog_chunk(T* __restrict__ P, int* strip, int
 // are read from LDS before this rating's sum is reduced: LDS executes a wavefront's operations in
 // order, so those reads see the state before this rating's own adds, which are then applied to
 // the copies in registers (changes other wavefronts make meanwhile arrive one rating later).
-template <typename T, int K>
-__device__ __forceinline__ void lds_hot_row_piece(int* prow, int* strip, int col0,
+template <typename T, int K, bool SPARSE>
+__device__ __forceinline__ void lds_hot_row_piece(int* prow, int* strip, int col0, const unsigned short* slots,
                                                   const int32_t* __restrict__ V,
                                                   const float* __restrict__ R, int64_t begin, int32_t len,
                                                   float lr, float shrink, int lane, bool active, RangeWatch& watch)
@@ -720,7 +732,8 @@ __device__ __forceinline__ void lds_hot_row_piece(int* prow, int* strip, int col
         mv = V[begin + lane];
         mr = R[begin + lane];
     }
-    Row<VEC> qs = read_scaled(strip + (uniform_lane(mv, 0) - col0) * K);
+    mv = strip_slots<SPARSE>(mv, col0, slots, lane < min(kWave, len));   // slots, not columns
+    Row<VEC> qs = read_scaled(strip + uniform_lane(mv, 0) * K);
     Row<VEC> ps = read_scaled(prow);
     for (int32_t off = 0; off < len; off += kWave) {
         const int cnt = min(kWave, len - off);
@@ -732,10 +745,11 @@ __device__ __forceinline__ void lds_hot_row_piece(int* prow, int* strip, int col
         for (int i = 0; i < cnt; ++i) {
             const int v = uniform_lane(mv, i);
             const float r = __int_as_float(uniform_lane(__float_as_int(mr), i));
-            int* const qrow = strip + (v - col0) * K;
+            int* const qrow = strip + v * K;
             // the column of the rating after this one (at the end of the piece: this one again)
-            const int v_next = i + 1 < cnt ? uniform_lane(mv, i + 1) : (more ? uniform_lane(nv, 0) : v);
-            Row<VEC> qn = read_scaled(strip + (v_next - col0) * K);
+            const int v_next = i + 1 < cnt ? uniform_lane(mv, i + 1)
+                                           : (more ? strip_slots<SPARSE>(uniform_lane(nv, 0), col0, slots, true) : v);
+            Row<VEC> qn = read_scaled(strip + v_next * K);
             Row<VEC> pn = read_scaled(prow);
             float part = 0.f;
 #pragma unroll
@@ -760,7 +774,7 @@ __device__ __forceinline__ void lds_hot_row_piece(int* prow, int* strip, int col
             qs = qn;
             ps = pn;
         }
-        mv = nv;
+        mv = strip_slots<SPARSE>(nv, col0, slots, lane < len - off - kWave);
         mr = nr;
     }
 }
@@ -812,44 +826,113 @@ __device__ __forceinline__ float from_strip(int x, float& worst)
     return f;
 }
 
-// SPARSE: only the columns whose bit is set in the block's table of touched columns are copied
-// (lane l of every wavefront holds bit word l in `mask_word`); the other columns of the strip
-// keep whatever the LDS held, which no rating of the block reads.  Taken in the one-launch
-// Hogwild form, where a wavefront's 64 consecutive words lie in one column; ignored elsewhere.
+// SPARSE (the one-launch Hogwild form, where a wavefront's 64 consecutive words of a strip lie in
+// one column): the LDS holds only the columns of the strip in which the block has a rating,
+// packed in ascending order -- the s-th touched column in slot s -- so a strip may span more
+// columns than the LDS could hold.  The block's table of touched columns (one bit per column of
+// the strip's range) comes with lane l of every wavefront holding bit word l (`mask_word`).
 template <typename T, int K>
 struct SparseStrip {
     static constexpr int kWordsPerColumn = K * (int)sizeof(T) / 4;
     static constexpr bool kPossible = kWordsPerColumn % kWave == 0;
 };
 
-// Which of its pieces of the strip a wavefront copies: the strip is copied in pieces of 64
-// consecutive 32-bit words, piece j of a wavefront beginning at word (its first thread) + j *
-// blockDim.x; bit j of the result is set when that piece lies inside the strip and -- if `sparse`
-// -- in a touched column.  Worked out once per block by the 64 lanes together (lane j looks at
-// piece j) and used by the copy in and the copy out, so that neither loop has to wait for
-// anything but its own memory operations.  Needs words <= 64 * blockDim.x; all lanes active.
+// What a wavefront needs to move its share of a packed strip.  The columns' values are moved in
+// pieces of 64 consecutive 32-bit words of the strip's range in memory; piece j of a wavefront
+// begins at word (its first thread) + j * blockDim.x.  `pieces`: bit j set = piece j lies in a
+// touched column; `piece_slot`: lane j holds that column's slot.  `first_slot`: lane l holds the
+// slot of the first touched column of bit word l; `n_slots`: touched columns in all.  Worked out
+// once per block by the 64 lanes together.  Needs words <= 64 * blockDim.x and all lanes active.
+struct StripMap {
+    unsigned long long pieces;
+    int piece_slot;
+    int first_slot;
+    int n_slots;
+};
+
 template <typename T, int K>
-__device__ __forceinline__ unsigned long long strip_pieces(int words, unsigned mask_word, bool sparse)
+__device__ __forceinline__ StripMap map_strip(int ncols, unsigned mask_word)
 {
     const int lane = threadIdx.x & (kWave - 1);
+    StripMap m;
+    const int mine = __popc(mask_word);
+    int upto = mine;                         // touched columns in bit words 0 .. lane
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int below = __shfl_up(upto, d, kWave);
+        if (lane >= d) upto += below;
+    }
+    m.first_slot = upto - mine;
+    m.n_slots = uniform_lane(upto, kWave - 1);
+    const int words = ncols * SparseStrip<T, K>::kWordsPerColumn;
     const int w = (int)(threadIdx.x & ~(unsigned)(kWave - 1)) + lane * (int)blockDim.x;
     const int column = min(w, words - 1) / SparseStrip<T, K>::kWordsPerColumn;
     const unsigned bits = (unsigned)__shfl((int)mask_word, column >> 5, kWave);
-    bool take = w < words;
-    if (sparse) take = take && ((bits >> (column & 31)) & 1u);
-    return __ballot(take);
+    const int before = __shfl(m.first_slot, column >> 5, kWave);
+    m.piece_slot = before + __popc(bits & ((1u << (column & 31)) - 1u));
+    m.pieces = __ballot(w < words && ((bits >> (column & 31)) & 1u));
+    return m;
+}
+
+// The 16-bit table column -> slot that the wavefronts' chunks look their columns up in: written
+// for the touched columns of the range, each bit word by one wavefront.
+__device__ __forceinline__ void write_slot_table(unsigned short* slots, unsigned mask_word, const StripMap& m)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = (int)(threadIdx.x >> 6), n_waves = (int)(blockDim.x >> 6);
+    unsigned left = (lane % n_waves == wave) ? mask_word : 0u;
+    int slot = m.first_slot;
+    while (left) {
+        const int bit = __builtin_ctz(left);
+        left &= left - 1u;
+        slots[32 * lane + bit] = (unsigned short)slot++;
+    }
 }
 
 // Columns col0 .. col0+ncols of Qt into LDS, by all threads of the workgroup (no barrier inside).
 template <typename T, int K, bool EXACT, bool COHERENT, bool SPARSE>
 __device__ __forceinline__ void strip_copy_in(int* strip, const T* __restrict__ Qt, int col0, int ncols,
-                                              RangeWatch& watch, unsigned mask_word)
+                                              RangeWatch& watch, const StripMap& map)
 {
     float worst = 0.f;
     const int total = ncols * K;          // multiple of 32
     const T* const strip_src = Qt + (int64_t)col0 * K;
     const int stride = 4 * (int)blockDim.x;
-    if constexpr (COHERENT && !EXACT) {
+    if constexpr (COHERENT && !EXACT && SPARSE) {
+        // the touched columns only, into their slots: up to 16 pieces requested, then converted
+        constexpr int kPerWord = sizeof(T) == 2 ? 2 : 1;
+        constexpr int kInColumn = SparseStrip<T, K>::kWordsPerColumn - 1;
+        const unsigned* src = reinterpret_cast<const unsigned*>(strip_src);
+        constexpr int kInFlight = 16;
+        unsigned long long left = map.pieces;
+        while (left) {
+            const int n = min(kInFlight, (int)__popcll(left));
+            unsigned raw[kInFlight];
+            int at[kInFlight];
+#pragma unroll
+            for (int t = 0; t < kInFlight; ++t) {
+                if (t < n) {
+                    const int j = __builtin_ctzll(left);
+                    left &= left - 1ull;
+                    const int w = (int)threadIdx.x + j * (int)blockDim.x;
+                    at[t] = uniform_lane(map.piece_slot, j) * K + (w & kInColumn) * kPerWord;
+                    raw[t] = load_word<true>(src + w);
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < kInFlight; ++t) {
+                if (t < n) {
+                    if constexpr (sizeof(T) == 2) {
+                        const float2 f = unpack_half2(raw[t]);
+                        strip[at[t]] = to_strip<EXACT>(f.x, worst);
+                        strip[at[t] + 1] = to_strip<EXACT>(f.y, worst);
+                    } else {
+                        strip[at[t]] = to_strip<EXACT>(__uint_as_float(raw[t]), worst);
+                    }
+                }
+            }
+        }
+    } else if constexpr (COHERENT && !EXACT) {
         // 1024 threads: one 32-bit word each (one fp32 value or one pair of binary16 values); wider
         // pieces were measured slower here, and faster for the 64-thread workgroups of the
         // deterministic mode below
@@ -857,22 +940,17 @@ __device__ __forceinline__ void strip_copy_in(int* strip, const T* __restrict__ 
         const unsigned* src = reinterpret_cast<const unsigned*>(strip_src);
         const int words = total / kPerWord;
         constexpr int kInFlight = 16;
-        unsigned long long pieces = ~0ull;
-        const bool by_pieces = SPARSE && SparseStrip<T, K>::kPossible && words <= kWave * (int)blockDim.x;
-        if (by_pieces) pieces = strip_pieces<T, K>(words, mask_word, true);
-        for (int w0 = (int)threadIdx.x, j0 = 0; w0 < words; w0 += kInFlight * (int)blockDim.x, j0 += kInFlight) {
+        for (int w0 = (int)threadIdx.x; w0 < words; w0 += kInFlight * (int)blockDim.x) {
             unsigned raw[kInFlight];
-            const unsigned now = by_pieces ? (unsigned)(pieces >> j0) & ((1u << kInFlight) - 1u) : ~0u;
-            if (now == 0u) continue;
 #pragma unroll
             for (int t = 0; t < kInFlight; ++t) {
                 const int w = w0 + t * (int)blockDim.x;
-                if (w < words && ((now >> t) & 1u)) raw[t] = load_word<true>(src + w);
+                if (w < words) raw[t] = load_word<true>(src + w);
             }
 #pragma unroll
             for (int t = 0; t < kInFlight; ++t) {
                 const int w = w0 + t * (int)blockDim.x;
-                if (w < words && ((now >> t) & 1u)) {
+                if (w < words) {
                     if constexpr (sizeof(T) == 2) {
                         const float2 f = unpack_half2(raw[t]);
                         strip[2 * w] = to_strip<EXACT>(f.x, worst);
@@ -952,21 +1030,37 @@ __device__ __forceinline__ void strip_copy_in(int* strip, const T* __restrict__ 
 // The strip in LDS back to columns col0 .. col0+ncols of Qt, by all threads of the workgroup.
 template <typename T, int K, bool EXACT, bool COHERENT, bool SPARSE>
 __device__ __forceinline__ void strip_copy_out(const int* strip, T* __restrict__ Qt, int col0, int ncols,
-                                               RangeWatch& watch, unsigned mask_word)
+                                               RangeWatch& watch, const StripMap& map)
 {
     float worst = 0.f;
     const int total = ncols * K;
     T* const strip_dst = Qt + (int64_t)col0 * K;
     const int stride = 4 * (int)blockDim.x;
-    if constexpr (COHERENT && !EXACT) {
+    if constexpr (COHERENT && !EXACT && SPARSE) {
+        constexpr int kPerWord = sizeof(T) == 2 ? 2 : 1;
+        constexpr int kInColumn = SparseStrip<T, K>::kWordsPerColumn - 1;
+        unsigned* dst = reinterpret_cast<unsigned*>(strip_dst);
+        unsigned long long left = map.pieces;
+        while (left) {
+            const int j = __builtin_ctzll(left);
+            left &= left - 1ull;
+            const int w = (int)threadIdx.x + j * (int)blockDim.x;
+            const int at = uniform_lane(map.piece_slot, j) * K + (w & kInColumn) * kPerWord;
+            unsigned raw;
+            if constexpr (sizeof(T) == 2) {
+                __half2 h = __halves2half2(round_to_half(from_strip<EXACT>(strip[at], worst)),
+                                           round_to_half(from_strip<EXACT>(strip[at + 1], worst)));
+                raw = *reinterpret_cast<unsigned*>(&h);
+            } else {
+                raw = __float_as_uint(from_strip<EXACT>(strip[at], worst));
+            }
+            __hip_atomic_store(dst + w, raw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    } else if constexpr (COHERENT && !EXACT) {
         constexpr int kPerWord = sizeof(T) == 2 ? 2 : 1;
         unsigned* dst = reinterpret_cast<unsigned*>(strip_dst);
         const int words = total / kPerWord;
-        unsigned long long pieces = ~0ull;
-        const bool by_pieces = SPARSE && SparseStrip<T, K>::kPossible && words <= kWave * (int)blockDim.x;
-        if (by_pieces) pieces = strip_pieces<T, K>(words, mask_word, true);
-        for (int w = (int)threadIdx.x; w < words; w += (int)blockDim.x, pieces >>= 1) {
-            if (by_pieces && !(pieces & 1ull)) continue;
+        for (int w = (int)threadIdx.x; w < words; w += (int)blockDim.x) {
             unsigned raw;
             if constexpr (sizeof(T) == 2) {
                 __half2 h = __halves2half2(round_to_half(from_strip<EXACT>(strip[2 * w], worst)),
@@ -1033,11 +1127,11 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
                                                const int32_t* __restrict__ entry_len,
                                                const int64_t* __restrict__ hot_pos, const LdsBlock blk,
                                                float lr, float lambda, bool copy_in, bool copy_out, unsigned mask_word,
-                                               RangeWatch& watch, BeforeStrip before_strip)
+                                               int slot_table_at, RangeWatch& watch, BeforeStrip before_strip)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const bool active = RowShape<T, K>::ACTIVE == kWave ? true : lane < RowShape<T, K>::ACTIVE;
-    const int total = blk.ncols * K;          // multiple of 32
+    int total = blk.ncols * K;                // values of the strip in LDS (SPARSE: set below); multiple of 32
 
     // Entries are dealt to the wavefronts round-robin.  The first entry's ratings are requested
     // before the strip is copied so that the two latencies overlap.
@@ -1060,7 +1154,6 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
     // rows of P cut by the entry boundaries of this block: lane s of every wavefront knows the
     // row index of slot s; the slots follow the strip in LDS
     const int n_hot = EXACT ? 0 : (blk.hot & 15);
-    int* const hot_rows = strip + total;
     int hot_u = -1;
     if (!EXACT && lane < n_hot) hot_u = U[hot_pos[(blk.hot >> 4) + lane]];
     RowRing<VEC, DEPTH> first_rows;
@@ -1076,6 +1169,17 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
     }
     if (!before_strip()) return false;
 
+    // SPARSE: where the touched columns go in LDS, and the table the chunks look columns up in
+    // (at a fixed place behind the values; nobody reads the previous block's table any more)
+    StripMap map{};
+    unsigned short* slots = nullptr;
+    if constexpr (SPARSE) {
+        map = map_strip<T, K>(blk.ncols, mask_word);
+        total = map.n_slots * K;
+        slots = reinterpret_cast<unsigned short*>(strip + slot_table_at);
+        write_slot_table(slots, mask_word, map);
+    }
+    int* const hot_rows = strip + total;
     float worst = 0.f;   // magnitudes of the cut rows on their way into and out of LDS
     if constexpr (!EXACT) {
         // read past the L1 (the row was last written by another compute unit's plain stores)
@@ -1086,7 +1190,7 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
                 if (active) hot_rows[slot * K + strip_elem<T>(lane, j)] = to_strip<EXACT>(p.x[j], worst);
         }
     }
-    if (copy_in) strip_copy_in<T, K, EXACT, COHERENT, SPARSE>(strip, Qt, blk.col0, blk.ncols, watch, mask_word);
+    if (copy_in) strip_copy_in<T, K, EXACT, COHERENT, SPARSE>(strip, Qt, blk.col0, blk.ncols, watch, map);
     __syncthreads();
 
     const float shrink = lr * lambda;
@@ -1126,17 +1230,17 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
                     first_rows = request_first_rows<T, K, DEPTH>(P, mu, min(kWave, between), lane, active);
                 }
                 if (front > 0)
-                    lds_hot_row_piece<T, K>(hot_rows + front_slot * K, strip, blk.col0, V, R, begin, front, lr, shrink,
-                                            lane, active, watch);
+                    lds_hot_row_piece<T, K, SPARSE>(hot_rows + front_slot * K, strip, blk.col0, slots, V, R, begin, front,
+                                                    lr, shrink, lane, active, watch);
                 if (back > 0)
-                    lds_hot_row_piece<T, K>(hot_rows + back_slot * K, strip, blk.col0, V, R, begin + len - back, back,
-                                            lr, shrink, lane, active, watch);
+                    lds_hot_row_piece<T, K, SPARSE>(hot_rows + back_slot * K, strip, blk.col0, slots, V, R,
+                                                    begin + len - back, back, lr, shrink, lane, active, watch);
                 if (between > 0)
-                    lds_hog_chunk<T, K, DEPTH>(P, strip, blk.col0, U, V, R, begin + front, between, mu, mv, mr,
-                                               first_rows, lr, shrink, lane, active, watch);
+                    lds_hog_chunk<T, K, DEPTH, SPARSE>(P, strip, blk.col0, slots, U, V, R, begin + front, between, mu, mv,
+                                                       mr, first_rows, lr, shrink, lane, active, watch);
             } else {
-                lds_hog_chunk<T, K, DEPTH>(P, strip, blk.col0, U, V, R, begin, len, mu, mv, mr,
-                                                       first_rows, lr, shrink, lane, active, watch);
+                lds_hog_chunk<T, K, DEPTH, SPARSE>(P, strip, blk.col0, slots, U, V, R, begin, len, mu, mv, mr,
+                                                   first_rows, lr, shrink, lane, active, watch);
             }
         }
     }
@@ -1152,7 +1256,7 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
         }
         watch.see_plain(worst);
     }
-    if (copy_out) strip_copy_out<T, K, EXACT, COHERENT, SPARSE>(strip, Qt, blk.col0, blk.ncols, watch, mask_word);
+    if (copy_out) strip_copy_out<T, K, EXACT, COHERENT, SPARSE>(strip, Qt, blk.col0, blk.ncols, watch, map);
     return true;
 }
 
@@ -1167,7 +1271,7 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_block_lds(
     extern __shared__ int strip[];            // ncols * K values (fixed point, or fp32 bits if EXACT)
     RangeWatch watch;
     lds_block_body<T, K, EXACT, false, DEPTH, false>(strip, P, Qt, U, V, R, entry_begin, entry_len, hot_pos,
-                                                     blocks[blockIdx.x], lr, lambda, true, true, 0xffffffffu, watch,
+                                                     blocks[blockIdx.x], lr, lambda, true, true, 0xffffffffu, 0, watch,
                                                      [] { return true; });
     if constexpr (!EXACT) {
         if (__any(watch.hit()) && (threadIdx.x & (kWave - 1)) == 0) *range_flag = 1;
@@ -1203,7 +1307,7 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_ring_lds(
     const int64_t* __restrict__ entry_begin, const int32_t* __restrict__ entry_len, const int64_t* __restrict__ hot_pos,
     const LdsBlock* __restrict__ ring_blocks, int grid_r, int grid_c, float lr, float lambda,
     int* done, int first, int* flags, long long spin_limit, const int32_t* __restrict__ order,
-    const int32_t* __restrict__ pos, const unsigned* __restrict__ touched, int touched_words)
+    const int32_t* __restrict__ pos, const unsigned* __restrict__ touched, int touched_words, int slot_table_at)
 {
     extern __shared__ int strip[];
     __shared__ int go;
@@ -1275,8 +1379,8 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_ring_lds(
         bool ok;
         if (blk.n_entries > 0)
             ok = lds_block_body<T, K, EXACT, true, DEPTH, SPARSE>(strip, P, Qt, U, V, R, entry_begin, entry_len, hot_pos,
-                                                                  blk, lr, lambda, true, true, mask_word, watch,
-                                                                  wait_for_strip);
+                                                                  blk, lr, lambda, true, true, mask_word, slot_table_at,
+                                                                  watch, wait_for_strip);
         else
             ok = wait_for_strip();   // an empty block still waits: it passes the guarantee on
         if (!ok) return;
@@ -1382,12 +1486,11 @@ __global__ __launch_bounds__(kGroupThreads) void init_fill(T* __restrict__ X, in
 }
 
 // Table of touched columns: for every block of the list, bit c of its `words` bit words is set
-// when the block has a rating in column col0 + c of its strip.  One workgroup per block; the
-// block's ratings are the packed range its entries cover (they follow each other).
-// totals[0] += touched columns of the block, totals[1] += columns of its strip.
+// when the block has a rating in column col0 + c of its strip.  One workgroup per block.  The list
+// is made for this kernel: first_entry = the block's first packed position, n_entries = its number
+// of ratings (not work-list entries).  totals[0] += touched columns of the block, totals[1] +=
+// columns of its strip, totals[2] = the most touched columns of any block.
 __global__ __launch_bounds__(kGroupThreads) void mark_touched(const LdsBlock* __restrict__ blocks,
-                                                              const int64_t* __restrict__ entry_begin,
-                                                              const int32_t* __restrict__ entry_len,
                                                               const int32_t* __restrict__ V, uint32_t* __restrict__ touched,
                                                               int words, unsigned long long* totals)
 {
@@ -1395,14 +1498,10 @@ __global__ __launch_bounds__(kGroupThreads) void mark_touched(const LdsBlock* __
     const LdsBlock blk = blocks[blockIdx.x];
     if ((int)threadIdx.x < kMaxTouchedWords) bits[threadIdx.x] = 0u;
     __syncthreads();
-    if (blk.n_entries > 0) {
-        const int64_t last = blk.first_entry + blk.n_entries - 1;
-        const int64_t begin = entry_begin[blk.first_entry];
-        const int64_t end = entry_begin[last] + (entry_len[last] & ~kSharedRowFlag);
-        for (int64_t i = begin + (int64_t)threadIdx.x; i < end; i += (int64_t)blockDim.x) {
-            const int c = V[i] - blk.col0;
-            if (c >= 0 && c < 32 * words) atomicOr(&bits[c >> 5], 1u << (c & 31));
-        }
+    const int64_t begin = blk.first_entry, end = begin + blk.n_entries;
+    for (int64_t i = begin + (int64_t)threadIdx.x; i < end; i += (int64_t)blockDim.x) {
+        const int c = V[i] - blk.col0;
+        if (c >= 0 && c < 32 * words) atomicOr(&bits[c >> 5], 1u << (c & 31));
     }
     __syncthreads();
     if ((int)threadIdx.x < words) touched[(int64_t)blk.id * words + threadIdx.x] = bits[threadIdx.x];
@@ -1413,6 +1512,7 @@ __global__ __launch_bounds__(kGroupThreads) void mark_touched(const LdsBlock* __
         if (threadIdx.x == 0) {
             atomicAdd(&totals[0], (unsigned long long)set);
             atomicAdd(&totals[1], (unsigned long long)blk.ncols);
+            atomicMax(&totals[2], (unsigned long long)set);
         }
     }
 }
@@ -1473,7 +1573,7 @@ hipError_t launch_sgd_ring_impl(int waves, bool query_only, int* max_resident, v
                                 const int32_t* el, const int64_t* hot, const LdsBlock* ring_blocks, int grid_r, int grid_c,
                                 size_t lds_bytes, float lr, float lambda, int* done, int first,
                                 int* abort_flag, long long spin_limit, const int32_t* order, const int32_t* pos,
-                                const uint32_t* touched, int touched_words, hipStream_t stream)
+                                const uint32_t* touched, int touched_words, int slot_table_at, hipStream_t stream)
 {
     static bool raised[64] = {};
     int dev = 0;
@@ -1497,7 +1597,7 @@ hipError_t launch_sgd_ring_impl(int waves, bool query_only, int* max_resident, v
     }
     hipLaunchKernelGGL((sgd_ring_lds<T, K, EXACT, DEPTH, SPARSE>), dim3((unsigned)grid_r), dim3(waves * kWave), lds_bytes,
                        stream, (T*)P, (T*)Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lr, lambda, done,
-                       first, abort_flag, spin_limit, order, pos, touched, touched_words);
+                       first, abort_flag, spin_limit, order, pos, touched, touched_words, slot_table_at);
     return hipGetLastError();
 }
 
@@ -1507,31 +1607,31 @@ hipError_t launch_sgd_ring_t(bool exact, bool short_prefetch, int waves, bool qu
                              const int32_t* el, const int64_t* hot, const LdsBlock* ring_blocks, int grid_r, int grid_c,
                              size_t lds_bytes, float lr, float lambda, int* done, int first, int* abort_flag,
                              long long spin_limit, const int32_t* order, const int32_t* pos, const uint32_t* touched,
-                             int touched_words, hipStream_t stream)
+                             int touched_words, int slot_table_at, hipStream_t stream)
 {
     if (exact)
         return launch_sgd_ring_impl<T, K, true, kLdsPrefetchDepth, false>(
             1, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done,
-            first, abort_flag, spin_limit, order, pos, nullptr, 0, stream);
+            first, abort_flag, spin_limit, order, pos, nullptr, 0, 0, stream);
     // the form that copies only the touched columns of a strip exists where a wavefront's piece of
     // the strip lies in one column
     if constexpr (SparseStrip<T, K>::kPossible) {
         if (touched && short_prefetch)
             return launch_sgd_ring_impl<T, K, false, kShortPrefetchDepth, true>(
                 waves, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda,
-                done, first, abort_flag, spin_limit, order, pos, touched, touched_words, stream);
+                done, first, abort_flag, spin_limit, order, pos, touched, touched_words, slot_table_at, stream);
         if (touched)
             return launch_sgd_ring_impl<T, K, false, kLdsPrefetchDepth, true>(
                 waves, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda,
-                done, first, abort_flag, spin_limit, order, pos, touched, touched_words, stream);
+                done, first, abort_flag, spin_limit, order, pos, touched, touched_words, slot_table_at, stream);
     }
     if (short_prefetch)
         return launch_sgd_ring_impl<T, K, false, kShortPrefetchDepth, false>(
             waves, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done,
-            first, abort_flag, spin_limit, order, pos, nullptr, 0, stream);
+            first, abort_flag, spin_limit, order, pos, nullptr, 0, 0, stream);
     return launch_sgd_ring_impl<T, K, false, kLdsPrefetchDepth, false>(
         waves, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done,
-        first, abort_flag, spin_limit, order, pos, nullptr, 0, stream);
+        first, abort_flag, spin_limit, order, pos, nullptr, 0, 0, stream);
 }
 
 template <typename T, int K>
@@ -1615,24 +1715,26 @@ hipError_t launch_sgd_ring(int dtype, int k, bool exact, bool short_prefetch, in
                            const int64_t* entry_begin, const int32_t* entry_len, const int64_t* hot_pos, const LdsBlock* ring_blocks,
                            int grid_r, int grid_c, size_t lds_bytes, float lr, float lambda, int* done,
                            int first, int* abort_flag, long long spin_limit, const int32_t* order,
-                           const int32_t* pos, const uint32_t* touched, int touched_words, hipStream_t stream)
+                           const int32_t* pos, const uint32_t* touched, int touched_words, int slot_table_at,
+                           hipStream_t stream)
 {
     if (waves < 1 || waves > 16 || lds_bytes > kLdsBudget || grid_r < 1) return hipErrorInvalidValue;
     if ((order == nullptr) != (pos == nullptr)) return hipErrorInvalidValue;
-    if (touched && (touched_words < 1 || touched_words > kMaxTouchedWords)) return hipErrorInvalidValue;
+    if (touched && (touched_words < 1 || touched_words > kMaxTouchedWords || slot_table_at < 0 ||
+                    (size_t)slot_table_at * 4 + (size_t)touched_words * 64 > lds_bytes))
+        return hipErrorInvalidValue;
     MF_DISPATCH(launch_sgd_ring_t, exact, short_prefetch, waves, query_only, max_resident, P, Qt, U, V, R, entry_begin,
                 entry_len, hot_pos, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done, first, abort_flag,
-                spin_limit, order, pos, touched, touched_words, stream);
+                spin_limit, order, pos, touched, touched_words, slot_table_at, stream);
 }
 
-hipError_t launch_mark_touched(const LdsBlock* blocks, int64_t n_blocks, const int64_t* entry_begin,
-                               const int32_t* entry_len, const int32_t* V, uint32_t* touched, int words,
+hipError_t launch_mark_touched(const LdsBlock* blocks, int64_t n_blocks, const int32_t* V, uint32_t* touched, int words,
                                unsigned long long* totals, hipStream_t stream)
 {
     if (n_blocks <= 0) return hipSuccess;
     if (words < 1 || words > kMaxTouchedWords) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(mark_touched, dim3((unsigned)n_blocks), dim3(kGroupThreads), 0, stream, blocks, entry_begin,
-                       entry_len, V, touched, words, totals);
+    hipLaunchKernelGGL(mark_touched, dim3((unsigned)n_blocks), dim3(kGroupThreads), 0, stream, blocks, V, touched, words,
+                       totals);
     return hipGetLastError();
 }
 

@@ -14,8 +14,8 @@
 #include "../../include/mf_sgd.h"
 #include "mf_internal.h"
 
-// The one-launch Hogwild kernel copies only the touched columns of a strip when at most this
-// share of all strip columns is touched.
+// The one-launch Hogwild kernel keeps only the touched columns of a strip in LDS when at most this
+// share of all strip columns is touched (or when whole strips do not fit).
 constexpr double kSparseStripShare = 0.75;
 
 struct mf_ctx {
@@ -31,6 +31,7 @@ struct mf_ctx {
     void* dQt = nullptr;
 
     double touched_share = 1.0;   // touched columns / strip columns over the blocks of the last load
+    int32_t max_slots = 0;        // most touched columns of any block (when the strips are packed)
     // partition and schedules
     bool loaded = false;
     mf::Partition part;
@@ -134,13 +135,15 @@ struct Layout {
     int32_t touched_words;
 };
 
-// Bit words per block of the table of touched columns: room for the widest strip that fits the
-// LDS with this k (before mf_init: the most the table can have).  0 in streamed mode, where the
+// Bit words per block of the table of touched columns: room for the widest strip the one-launch
+// Hogwild kernel can pack (64 pieces of 64 words per wavefront, 16 wavefronts) with this k and
+// storage type (before mf_init: the most the table can have).  0 in streamed mode, where the
 // table is not built.
 int32_t touched_words_bound(const mf_ctx* ctx)
 {
     if (!ctx->inited) return mf::kMaxTouchedWords;
-    const int64_t cols = std::min<int64_t>(ctx->n, (int64_t)mf::kLdsBudget / ((int64_t)ctx->k * 4));
+    const int64_t words_per_column = (int64_t)ctx->k * (ctx->dtype == MF_F16 ? 2 : 4) / 4;
+    const int64_t cols = std::min<int64_t>(ctx->n, (int64_t)64 * 64 * 16 / words_per_column);
     return (int32_t)std::min<int64_t>(mf::kMaxTouchedWords, (cols + 31) / 32);
 }
 
@@ -401,24 +404,87 @@ int check_load(mf_ctx* ctx, const void* rows, const void* cols, const void* vals
 
 // The partition and the packed arrays exist (ctx->part; `rs` = where the row runs begin):
 // derive the work lists and put them into the workspace.
+// Which columns of its strip every block touches (resident ratings only): the table the
+// one-launch Hogwild kernel packs its strips with, made before the work lists because the room
+// the packed strips leave in LDS decides how many rows a block may cut.  Sets ctx->lds.d_touched
+// when packing is possible and pays.
+int make_touched_table(mf_ctx* ctx, const Layout& lay, char* base)
+{
+    ctx->lds.d_touched = nullptr;
+    ctx->lds.touched_words = 0;
+    ctx->det_lds.d_touched = nullptr;
+    ctx->det_lds.touched_words = 0;
+    ctx->touched_share = 1.0;
+    ctx->max_slots = 0;
+    const mf::Partition& part = ctx->part;
+    const int32_t widest = mf::widest_strip(part);
+    const int32_t words = (widest + 31) / 32;
+    // a wavefront's 64 consecutive words of a strip have to lie in one column, and its 64 piece
+    // bits have to cover the widest strip
+    const int64_t words_per_column = (int64_t)ctx->k * (ctx->dtype == MF_F16 ? 2 : 4) / 4;
+    const bool shape_ok = words_per_column % 64 == 0 &&
+                          (int64_t)widest * words_per_column <= (int64_t)64 * 64 * ctx->lds_waves_used;
+    if (ctx->streamed || !ctx->dV || part.nnz == 0 || words < 1 || words > lay.touched_words || !shape_ok) return MF_OK;
+    std::vector<mf::LdsBlock> ranges;
+    for (int32_t st = 0; st < part.gc; ++st)
+        for (int32_t a = 0; a < part.gr; ++a) {
+            const int64_t L = (int64_t)st * part.gr + a;
+            const int64_t size = part.block_ptr[(size_t)L + 1] - part.block_ptr[(size_t)L];
+            if (size == 0) continue;
+            const int32_t b = (a + st) % part.gc;
+            ranges.push_back(mf::LdsBlock{part.block_ptr[(size_t)L], (int32_t)size, part.col_bounds[(size_t)b],
+                                          part.col_bounds[(size_t)b + 1] - part.col_bounds[(size_t)b], 0, (int32_t)L, 0});
+        }
+    // the list travels through the place of the work list's block descriptors, which are written later
+    mf::LdsBlock* d_ranges = (mf::LdsBlock*)(base + lay.off_lds_blocks);
+    uint32_t* table = (uint32_t*)(base + lay.off_touched);
+    unsigned long long* totals =
+        (unsigned long long*)(base + lay.off_touched + align_up((size_t)lay.lds_blocks_cap * lay.touched_words * 4));
+    MF_HIP(ctx, hipMemcpy(d_ranges, ranges.data(), ranges.size() * sizeof(mf::LdsBlock), hipMemcpyHostToDevice));
+    MF_HIP(ctx, mf::launch_fill_i32((int32_t*)table, (int64_t)lay.lds_blocks_cap * words, 0, ctx->stream));
+    MF_HIP(ctx, mf::launch_fill_i32((int32_t*)totals, 8, 0, ctx->stream));
+    MF_HIP(ctx, mf::launch_mark_touched(d_ranges, (int64_t)ranges.size(), ctx->dV, table, words, totals, ctx->stream));
+    MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    unsigned long long sums[3] = {0, 0, 0};
+    MF_HIP(ctx, hipMemcpy(sums, totals, sizeof(sums), hipMemcpyDeviceToHost));
+    if (sums[1] > 0) ctx->touched_share = (double)sums[0] / (double)sums[1];
+    // Packing costs a little on every step (the map of a strip, a table look-up per 64 ratings),
+    // which pays when a good part of the columns can be left out (measured: a gain of 8-10 % with
+    // 45 % of the columns touched, a loss of 7 % with nearly all touched) -- and is the only way
+    // when the whole strip does not fit.
+    const size_t dense = mf::lds_strip_bytes(ctx->k, widest);
+    const size_t packed = mf::lds_strip_bytes(ctx->k, (int32_t)sums[2]) + (size_t)words * 64;
+    if (packed <= mf::kLdsBudget && (ctx->touched_share <= kSparseStripShare || dense > mf::kLdsBudget)) {
+        ctx->lds.d_touched = table;
+        ctx->lds.touched_words = words;
+        ctx->max_slots = (int32_t)sums[2];
+    }
+    return MF_OK;
+}
+
 int finish_load(mf_ctx* ctx, const Layout& lay, char* base, const mf::RowStarts& rs)
 {
+    ctx->lds_waves_used = ctx->lds_waves;
+    if (!ctx->lds_waves_set && ctx->lds_chunk == 0 && ctx->part.nnz > 0) {
+        // eight ratings per wavefront and block at least (measured on the MovieLens-shaped
+        // configuration: 16 wavefronts are best for blocks of 197 and of 151 ratings)
+        int64_t blocks = 0;
+        for (size_t L = 0; L + 1 < ctx->part.block_ptr.size(); ++L)
+            blocks += ctx->part.block_ptr[L + 1] > ctx->part.block_ptr[L];
+        const int64_t per_block = ctx->part.nnz / std::max<int64_t>(1, blocks);
+        ctx->lds_waves_used = (int32_t)std::min<int64_t>(ctx->lds_waves, std::max<int64_t>(4, (per_block + 4) / 8));
+    }
+    int rc = make_touched_table(ctx, lay, base);
+    if (rc) return rc;
     try {
         mf::build_det_schedule(ctx->part, ctx->xcd_affinity != 0, ctx->sched[MF_MODE_DET]);
         mf::build_hogwild_schedule(ctx->part, rs, ctx->hogwild_chunk, ctx->lds_waves, ctx->xcd_affinity != 0,
                                    ctx->sched[MF_MODE_HOGWILD]);
-        ctx->lds_waves_used = ctx->lds_waves;
-        if (!ctx->lds_waves_set && ctx->lds_chunk == 0 && ctx->part.nnz > 0) {
-            // eight ratings per wavefront and block at least (measured on the MovieLens-shaped
-            // configuration: 16 wavefronts are best for blocks of 197 and of 151 ratings)
-            int64_t blocks = 0;
-            for (size_t L = 0; L + 1 < ctx->part.block_ptr.size(); ++L)
-                blocks += ctx->part.block_ptr[L + 1] > ctx->part.block_ptr[L];
-            const int64_t per_block = ctx->part.nnz / std::max<int64_t>(1, blocks);
-            ctx->lds_waves_used = (int32_t)std::min<int64_t>(ctx->lds_waves, std::max<int64_t>(4, (per_block + 4) / 8));
-        }
-        // cut rows stay in LDS beside the strip, as many per block as the widest strip leaves room for
-        const int64_t widest = (int64_t)mf::lds_strip_bytes(ctx->k, mf::widest_strip(ctx->part));
+        // cut rows stay in LDS beside the strip, as many per block as the widest strip (packed: the
+        // most touched columns of a block, and the column table) leaves room for
+        const int64_t widest = ctx->lds.d_touched
+                                   ? (int64_t)mf::lds_strip_bytes(ctx->k, ctx->max_slots) + (int64_t)ctx->lds.touched_words * 64
+                                   : (int64_t)mf::lds_strip_bytes(ctx->k, mf::widest_strip(ctx->part));
         const int32_t hot_slots = (int32_t)std::max<int64_t>(
             0, std::min<int64_t>(mf::kMaxHotRows, ((int64_t)mf::kLdsBudget - widest) / ((int64_t)ctx->k * 4)));
         mf::build_lds_schedule(ctx->part, rs, ctx->lds_chunk, ctx->lds_waves_used, hot_slots, ctx->lds);
@@ -456,33 +522,6 @@ int finish_load(mf_ctx* ctx, const Layout& lay, char* base, const mf::RowStarts&
             MF_HIP(ctx, hipMemcpy(l.d_len, l.len.data(), l.len.size() * 4, hipMemcpyHostToDevice));
             MF_HIP(ctx, hipMemcpy(l.d_blocks, l.blocks.data(), l.blocks.size() * sizeof(mf::LdsBlock),
                                   hipMemcpyHostToDevice));
-        }
-    }
-    // which columns of its strip every block of the Hogwild list touches (resident ratings only)
-    ctx->lds.d_touched = nullptr;
-    ctx->lds.touched_words = 0;
-    ctx->det_lds.d_touched = nullptr;
-    ctx->det_lds.touched_words = 0;
-    // The kernel uses the table when it saves enough: looking a column up costs a little on every
-    // step, which only pays when a good part of the strips' columns can be skipped (measured: a
-    // gain of 8-10 % with 45 % of the columns touched, a loss of 7 % with nearly all touched).
-    const int32_t words = (ctx->lds.max_cols + 31) / 32;
-    ctx->touched_share = 1.0;
-    if (!ctx->streamed && ctx->dV && words >= 1 && words <= lay.touched_words && !ctx->lds.blocks.empty()) {
-        uint32_t* table = (uint32_t*)(base + lay.off_touched);
-        unsigned long long* totals =
-            (unsigned long long*)(base + lay.off_touched + align_up((size_t)lay.lds_blocks_cap * lay.touched_words * 4));
-        MF_HIP(ctx, mf::launch_fill_i32((int32_t*)table, (int64_t)lay.lds_blocks_cap * words, 0, ctx->stream));
-        MF_HIP(ctx, mf::launch_fill_i32((int32_t*)totals, 4, 0, ctx->stream));
-        MF_HIP(ctx, mf::launch_mark_touched(ctx->lds.d_blocks, (int64_t)ctx->lds.blocks.size(), ctx->lds.d_begin,
-                                            ctx->lds.d_len, ctx->dV, table, words, totals, ctx->stream));
-        MF_HIP(ctx, hipStreamSynchronize(ctx->stream));
-        unsigned long long sums[2] = {0, 0};
-        MF_HIP(ctx, hipMemcpy(sums, totals, 16, hipMemcpyDeviceToHost));
-        if (sums[1] > 0) ctx->touched_share = (double)sums[0] / (double)sums[1];
-        if (ctx->touched_share <= kSparseStripShare) {
-            ctx->lds.d_touched = table;
-            ctx->lds.touched_words = words;
         }
     }
     ctx->d_ring_done = (int32_t*)(base + lay.off_ring_done);
@@ -683,6 +722,8 @@ struct EpochPlan {
     int32_t waves = 1;             // wavefronts per workgroup
     int32_t kernel = 0;            // MF_KERNEL_ID_*
     int64_t launches = 0;          // per epoch
+    bool packed = false;           // one-launch Hogwild kernel with only the touched columns of a strip in LDS
+    int32_t slot_table_at = 0;     // packed: where the kernel's column table begins in LDS (32-bit words)
     std::string note;
 };
 
@@ -697,9 +738,15 @@ int plan_epoch(mf_ctx* ctx, int32_t mode, EpochPlan& p)
     const size_t p_bytes = (size_t)ctx->m * ctx->k * (ctx->dtype == MF_F16 ? 2 : 4);
     p.short_prefetch = ctx->lds_prefetch == 4 || (ctx->lds_prefetch == 0 && p_bytes <= ((size_t)64 << 20));
     const mf::LdsSchedule& lsched = p.hog ? ctx->lds : ctx->det_lds;
-    p.lds_bytes = mf::lds_strip_bytes(ctx->k, lsched.max_cols) + (size_t)lsched.max_hot * ctx->k * 4;
+    const size_t dense_bytes = mf::lds_strip_bytes(ctx->k, lsched.max_cols) + (size_t)lsched.max_hot * ctx->k * 4;
     const int32_t choice = p.hog ? ctx->hogwild_kernel : ctx->det_kernel;
     const size_t budget = p.hog || choice == MF_KERNEL_LDS ? mf::kLdsBudget : mf::kLdsBudget / 4;
+    const bool ring_allowed = ctx->use_ring && !ctx->ring_gave_up && ctx->part.nnz > 0 && !ctx->streamed;
+    // packed strips exist in the one-launch Hogwild kernel only
+    p.slot_table_at = (ctx->max_slots + lsched.max_hot) * ctx->k;
+    const size_t packed_bytes = (size_t)p.slot_table_at * 4 + (size_t)lsched.touched_words * 64;
+    p.packed = p.hog && lsched.d_touched && ring_allowed && choice != MF_KERNEL_GLOBAL && packed_bytes <= budget;
+    p.lds_bytes = p.packed ? packed_bytes : dense_bytes;
     p.use_lds = choice != MF_KERNEL_GLOBAL && p.lds_bytes <= budget;
     if (!p.use_lds && choice == MF_KERNEL_LDS)
         return fail(ctx, MF_EINVAL, "the widest column strip of this grid does not fit the LDS");
@@ -708,7 +755,7 @@ int plan_epoch(mf_ctx* ctx, int32_t mode, EpochPlan& p)
     if (!p.use_lds && choice != MF_KERNEL_GLOBAL)
         why = "the widest column strip (" + std::to_string(lsched.max_cols) + " columns, " + std::to_string(p.lds_bytes) +
               " bytes) exceeds the " + std::to_string(budget) + " bytes of LDS this mode uses per workgroup; ";
-    if (p.use_lds && ctx->use_ring && !ctx->ring_gave_up && ctx->part.nnz > 0 && !ctx->streamed) {
+    if (p.use_lds && ring_allowed) {
         // one launch for the whole epoch if every block row's workgroup can be resident at once
         const int m_idx = p.hog ? 1 : 0;
         if (ctx->ring_resident[m_idx] < 0) {
@@ -716,12 +763,20 @@ int plan_epoch(mf_ctx* ctx, int32_t mode, EpochPlan& p)
             MF_HIP(ctx, mf::launch_sgd_ring(ctx->dtype, ctx->k, !p.hog, p.short_prefetch, ctx->lds_waves_used, true, &resident,
                                             nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
                                             ctx->part.gr, ctx->part.gc, p.lds_bytes, 0.f, 0.f, nullptr, 0, nullptr, 0,
-                                            nullptr, nullptr, nullptr, 0, ctx->stream));
+                                            nullptr, nullptr, nullptr, 0, 0, ctx->stream));
             ctx->ring_resident[m_idx] = resident;
         }
         p.ring = ctx->part.gr <= ctx->ring_resident[m_idx];
         if (!p.ring)
             why += "the device holds " + std::to_string(ctx->ring_resident[m_idx]) + " workgroups of this shape at once, fewer than grid_r; ";
+        if (!p.ring && p.packed) {
+            // one launch per stratum keeps whole strips
+            p.packed = false;
+            p.lds_bytes = dense_bytes;
+            p.use_lds = dense_bytes <= budget;
+            p.waves = p.use_lds ? ctx->lds_waves_used : mf::kWavesPerGroup;
+            if (!p.use_lds) why += "whole column strips do not fit the LDS; ";
+        }
     } else if (p.use_lds && ctx->ring_gave_up) {
         why += "an earlier epoch of the one-launch kernel exceeded its wait limit; ";
     }
@@ -738,8 +793,8 @@ int plan_epoch(mf_ctx* ctx, int32_t mode, EpochPlan& p)
     p.note = std::string(p.hog ? "MF_MODE_HOGWILD" : "MF_MODE_DET") + ": " + names[p.kernel] + ", " +
              std::to_string(p.launches) + " launch(es) per epoch, " + std::to_string(p.waves) +
              " wavefront(s) per workgroup" + (why.empty() ? "" : " (" + why.substr(0, why.size() - 2) + ")");
-    if (p.hog && p.ring && lsched.d_touched)
-        p.note += "; copies only the touched columns of a strip (" +
+    if (p.packed)
+        p.note += "; keeps only the touched columns of a strip in LDS (" +
                   std::to_string((int)(ctx->touched_share * 100.0 + 0.5)) + " % of all strip columns)";
     if (!p.hog && p.kernel == MF_KERNEL_ID_CHUNKS && choice != MF_KERNEL_GLOBAL)
         p.note += "; this grid was not made for the deterministic mode: one wavefront per block and one launch per "
@@ -818,8 +873,8 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
                                         ctx->part.gr, ctx->part.gc, lds_bytes, lr, lambda, ctx->d_ring_done,
                                         ctx->ring_epochs * ctx->part.gc, d_flags,
                                         (long long)ctx->spin_limit, stratum_order ? ctx->d_order : nullptr,
-                                        stratum_order ? ctx->d_order + gc : nullptr, lsched.d_touched,
-                                        lsched.touched_words, ctx->stream));
+                                        stratum_order ? ctx->d_order + gc : nullptr, plan.packed ? lsched.d_touched : nullptr,
+                                        lsched.touched_words, plan.slot_table_at, ctx->stream));
         if (ev1) MF_HIP(ctx, hipEventRecord(ev1, ctx->stream));
         ctx->ring_epochs += 1;
         return MF_OK;

@@ -168,18 +168,23 @@ hipError_t launch_sgd_lds(int dtype, int k, bool exact, bool short_prefetch, int
 // device ints, [0] raised when a bounded wait expires, [1] the range flag.  query_only: do not launch,
 // return in *max_resident how many workgroups of this shape the device can hold at once.
 // touched (device, may be null) / touched_words: the table of touched columns per block id
-// (launch_mark_touched); with it the Hogwild form copies only the touched columns of a strip.
+// (launch_mark_touched); with it the Hogwild form keeps only the touched columns of a strip in
+// LDS, packed; lds_bytes then covers the most touched columns of any block plus its cut rows,
+// followed -- from the 32-bit word slot_table_at on -- by 64 bytes per bit word for the kernel's
+// column -> slot table.
 hipError_t launch_sgd_ring(int dtype, int k, bool exact, bool short_prefetch, int waves, bool query_only, int* max_resident,
                            void* P, void* Qt, const int32_t* U, const int32_t* V, const float* R,
                            const int64_t* entry_begin, const int32_t* entry_len, const int64_t* hot_pos, const LdsBlock* ring_blocks,
                            int grid_r, int grid_c, size_t lds_bytes, float lr, float lambda, int* done,
                            int first, int* abort_flag, long long spin_limit, const int32_t* order,
-                           const int32_t* pos, const uint32_t* touched, int touched_words, hipStream_t stream);
-// Fill the table of touched columns for the blocks of a list (entries of untouched / empty blocks
-// are left as they are: clear the table first).  totals (device, two 64-bit counters, cleared by
-// the caller): [0] += touched columns, [1] += strip columns, summed over the blocks.
-hipError_t launch_mark_touched(const LdsBlock* blocks, int64_t n_blocks, const int64_t* entry_begin,
-                               const int32_t* entry_len, const int32_t* V, uint32_t* touched, int words,
+                           const int32_t* pos, const uint32_t* touched, int touched_words, int slot_table_at,
+                           hipStream_t stream);
+// Fill the table of touched columns for a list of blocks made for this call: first_entry = the
+// block's first packed position, n_entries = its number of ratings, col0 / ncols / id as usual
+// (rows of the table of blocks not in the list are left as they are: clear the table first).
+// totals (device, three 64-bit counters, cleared by the caller): [0] += touched columns, [1] +=
+// strip columns, summed over the blocks; [2] = the most touched columns of any block.
+hipError_t launch_mark_touched(const LdsBlock* blocks, int64_t n_blocks, const int32_t* V, uint32_t* touched, int words,
                                unsigned long long* totals, hipStream_t stream);
 size_t lds_strip_bytes(int k, int32_t max_cols);   // dynamic LDS the kernel needs for a grid
 constexpr size_t kLdsBudget = 160 * 1024 - 1024;   // LDS of one gfx950 compute unit, minus static use

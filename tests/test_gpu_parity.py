@@ -750,34 +750,39 @@ def test_one_launch_hogwild_kernel_copies_only_the_touched_columns(mfmod, storag
     assert not np.array_equal(outs[0][1][rated], Q0[rated])
 
 
-def test_touched_columns_only_with_sixteen_wavefronts_visits_every_rating_once(mfmod):
+@pytest.mark.parametrize("k,grid,take,whole_strip_fits", [(128, (16, 16), 9500, True), (256, (4, 4), 3000, False)])
+def test_packed_strips_with_sixteen_wavefronts_visit_every_rating_once(mfmod, k, grid, take, whole_strip_fits):
     """The first-order argument of test_hogwild_visits_every_rating_exactly_once for the form that
-    copies only touched columns, with 16 wavefronts per workgroup and k = 128: at lr = 1e-5 and
-    lambda = 0 the order of the ratings matters to second order only, while one rating that is
-    missed moves its row by up to 3e-6, and a touched column that was not copied in (stale LDS) or
-    not copied back shows at full size."""
+    keeps only the touched columns of a strip in LDS, with 16 wavefronts per workgroup: at
+    lr = 1e-5 and lambda = 0 the order of the ratings matters to second order only, while one
+    rating that is missed moves its row by up to 3e-6, and a touched column that went to the wrong
+    slot, was not copied in (stale LDS) or not copied back shows at full size.  Second case: strips
+    of 250 columns of k = 256, which do not fit the LDS whole (256 KB) -- only the packed form can
+    run them there, and without the one-launch kernel the L2-atomics kernel takes over."""
     ds = dataset("tiny")
     cfg = ds.cfg
-    take = 9500                                   # 37 ratings per block on strips of 62 columns
     rows, cols, vals = ds.rows[:take], ds.cols[:take], ds.vals[:take]
-    gr, gc, lr, lam = 16, 16, 1e-5, 0.0
-    model = mfmod.MatrixFactorization(cfg.m, cfg.n, 128, "f32", seed=1, scale=0.1,
-                                      options={mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS, mfmod.MF_OPT_RING: 1,
-                                               mfmod.MF_OPT_LDS_WAVES: 16})
+    gr, gc = grid
+    lr, lam = 1e-5, 0.0
+    model = mfmod.MatrixFactorization(cfg.m, cfg.n, k, "f32", seed=1, scale=0.1,
+                                      options={mfmod.MF_OPT_RING: 1, mfmod.MF_OPT_LDS_WAVES: 16})
     model.load_blocks(rows, cols, vals, gr, gc, 1)
     plan = model.epoch_plan(mfmod.MF_MODE_HOGWILD)
     assert plan["kernel"] == "sgd_ring_lds" and plan["waves"] == 16 and "touched columns" in plan["note"], plan
     model.sgd_epoch(lr, lam, mfmod.MF_MODE_HOGWILD)
     P, Q = model.get_factors()
+    mfmod.binding.mf_set_option(model.ctx, mfmod.MF_OPT_RING, 0)
+    other = model.epoch_plan(mfmod.MF_MODE_HOGWILD)
+    assert other["kernel"] == ("sgd_block_lds" if whole_strip_fits else "sgd_chunks"), other
     model.close()
     perm, bp, _, _ = oracle.partition(rows, cols, cfg.m, cfg.n, gr, gc, 1)
-    P0, Q0 = oracle_init(cfg.m, cfg.n, 128, 1, 0.1)
+    P0, Q0 = oracle_init(cfg.m, cfg.n, k, 1, 0.1)
     Po, Qo = P0.copy(), Q0.copy()
     oracle.sgd_epoch_omp(Po, Qo, rows, cols, vals, perm, bp, gr, gc, lr, lam)
     dp, dq = float(np.abs(P - Po).max()), float(np.abs(Q - Qo).max())
     moved = float(np.abs(Po - P0).max())
-    print("touched columns only, 16 wavefronts: max|dP| %.2e max|dQ| %.2e, the epoch moves P by up to %.2e"
-          % (dp, dq, moved), flush=True)
+    print("packed strips, 16 wavefronts, k=%d: max|dP| %.2e max|dQ| %.2e, the epoch moves P by up to %.2e"
+          % (k, dp, dq, moved), flush=True)
     assert moved > 5e-6 and dp <= 6e-7 and dq <= 1.2e-6, (moved, dp, dq)
 
 
