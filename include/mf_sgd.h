@@ -60,7 +60,8 @@ enum {
     MF_OPT_HOGWILD_KERNEL = 4,    /* MF_HOGWILD_AUTO (default), _GLOBAL_ATOMICS or _LDS, see          */
                                   /* mf_sgd_epoch                                                     */
     MF_OPT_LDS_CHUNK = 5,         /* target ratings per work-list entry of the LDS kernel; 0 (default)*/
-                                  /* = the block's ratings divided by MF_OPT_LDS_WAVES               */
+                                  /* = the smallest cap on an entry's ratings with which a block      */
+                                  /* gives at most MF_OPT_LDS_WAVES entries                           */
     MF_OPT_LDS_WAVES = 6,         /* wavefronts per workgroup of the LDS kernel, 1..16.  Default:     */
                                   /* chosen by mf_load_blocks -- one per eight ratings of an average  */
                                   /* block, between 4 and 16                                          */
@@ -197,13 +198,24 @@ int mf_get_partition(const mf_ctx* ctx, int64_t* perm, int64_t* block_ptr,
  *                                                 is used the values of Qt are multiples of 2^-24
  *                                                 (the fp32 spacing in [0.5, 1)) and saturate at
  *                                                 +-128.  Needs (widest column strip) * k * 4
- *                                                 bytes <= 159 KiB of LDS.  A matrix row so long
- *                                                 that a block's share of it is dealt to several
- *                                                 wavefronts has its p_u kept in LDS in the same
- *                                                 format while that block runs (up to 8 such
- *                                                 rows per block, as room beside the strip
- *                                                 allows; a block is never cut into more pieces
- *                                                 than that permits);
+ *                                                 bytes <= 159 KiB of LDS -- or, in the
+ *                                                 one-launch form below and with resident
+ *                                                 ratings, only (most columns of a strip in
+ *                                                 which one block has a rating) * k * 4 bytes:
+ *                                                 when the blocks touch at most three quarters
+ *                                                 of their strips' columns, or whole strips do
+ *                                                 not fit, that form keeps just the touched
+ *                                                 columns in LDS (a table made by the load call
+ *                                                 says which; strips of up to 65536 / (k *
+ *                                                 sizeof(element) / 4) columns).  A block's
+ *                                                 ratings are divided over the wavefronts as
+ *                                                 evenly as whole matrix rows allow; a row so
+ *                                                 long that its share of a block is dealt to
+ *                                                 several wavefronts has its p_u kept in LDS
+ *                                                 in the same format while that block runs (up
+ *                                                 to 8 such rows per block, as room beside
+ *                                                 the strip allows; a block is never cut into
+ *                                                 more pieces than that permits);
  *                       MF_HOGWILD_GLOBAL_ATOMICS wavefronts of a whole die share a block and use
  *                                                 floating-point atomics in that die's L2 (any
  *                                                 grid, slower).
