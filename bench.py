@@ -102,6 +102,39 @@ def cpu_baseline(ds, gr, gc, k, split, scale):
             "host_cores": len(os.sched_getaffinity(0))}
 
 
+def quick_rate(mf, torch, name, steps=5, warmup=2):
+    """Hogwild throughput of another configuration at full size on its grid of WORKLOAD_DEFAULTS (a
+    few steps of epoch + held-out RMSE by the wall clock; these are side figures, the line's
+    `value` is timed separately)."""
+    grid, split, scale = WORKLOAD_DEFAULTS[name]
+    gr, gc = (int(x) for x in grid.split("x"))
+    ds = load_dataset(name, 1.0)
+    cfg = ds.cfg
+    model = mf.MatrixFactorization(cfg.m, cfg.n, cfg.k, cfg.storage, seed=1, scale=scale)
+    coo = [torch.from_numpy(x).to(model.P.device) for x in (ds.rows, ds.cols, ds.vals)]
+    model.load_blocks_device(coo[0], coo[1], coo[2], gr, gc, split)
+    del coo
+    test = model.to_device(ds.test_rows, ds.test_cols, ds.test_vals)
+    plan = model.epoch_plan(mf.MF_MODE_HOGWILD)
+    rmse = float("nan")
+    for i in range(warmup + steps):
+        if i == warmup:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+        model.sgd_epoch(cfg.lr, cfg.lam, mf.MF_MODE_HOGWILD)
+        rmse = model.rmse(*test)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    model.close()
+    nnz = ds.rows.size
+    bytes_per_update = 12 + 4 * cfg.k * (4 if cfg.storage == "f32" else 2)
+    value = nnz * steps / elapsed
+    return {"workload": f"{cfg.name}: m={cfg.m} n={cfg.n} nnz_train={nnz} k={cfg.k} {cfg.storage}", "grid": grid,
+            "split": split, "steps": steps, "value": value, "unit": "updates/s", "ms_per_step": elapsed * 1e3 / steps,
+            "bytes_per_update": bytes_per_update, "algorithmic_frac_of_hbm_peak": value * bytes_per_update / 1e9 / HBM_PEAK_GBS,
+            "kernel": plan["kernel"], "waves_per_workgroup": plan["waves"], "held_out_rmse": rmse}
+
+
 def block_size_curve(args, mf, ds):
     """--curve: kernel time per launch against ratings per launch, on random subsets of the
     workload at a fixed grid, for one launch per stratum and for one launch per epoch (the
@@ -189,6 +222,8 @@ def main():
     ap.add_argument("--load", default="device", choices=["host", "device"],
                     help="partition on the host (mf_load_blocks) or on the GPU (mf_load_blocks_device); outside the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="skip the side figures for the other full-size configurations (default run only)")
     ap.add_argument("--no-kernel-events", action="store_true")
     ap.add_argument("--curve", action="store_true",
                     help="print the block-size curve of the workload (subsampled, both launch schemes) and exit")
@@ -345,6 +380,14 @@ def main():
            "roofline": roofline}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(ds, gr, gc, k, args.split, args.init_scale)
+    default_run = (args.workload == "xlarge" and args.scale == 1.0 and args.mode == "hogwild" and args.grid == d_grid
+                   and args.split == d_split and not args.no_cpu_baseline)
+    if default_run and not args.no_per_config:
+        # side figures: the other configurations at full size on their grids, same mode
+        del ds
+        import workloads
+        workloads.forget()
+        out["per_config"] = [quick_rate(mf, torch, name) for name in ("medium", "large", "stress")]
     print(json.dumps(out))
 
 
