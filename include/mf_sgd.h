@@ -73,6 +73,9 @@ enum {
     MF_OPT_RING_SPIN_LIMIT = 9,   /* polls after which a waiting workgroup gives up (default 2^22)    */
     MF_OPT_LDS_PREFETCH = 10,     /* MF_MODE_HOGWILD, LDS kernels: rows of P requested 4 or 8 ratings */
                                   /* ahead; 0 (default): 4 if P takes at most 64 MiB, else 8          */
+    MF_OPT_PACK_STRIPS = 12,      /* read by mf_load_blocks(_device): 1 (default) = the Hogwild LDS    */
+                                  /* kernels may keep only the touched columns of a strip in LDS     */
+                                  /* (see mf_sgd_epoch); 0 = always whole strips                     */
     MF_OPT_ROW_ORDER_SEED = 11    /* read by mf_load_blocks(_device): 0 (default) = the rows of a     */
                                   /* block in ascending order; else they are visited in a seeded      */
                                   /* order (the paper's scheduler visits "randomly", Section 3.1):    */
@@ -198,13 +201,12 @@ int mf_get_partition(const mf_ctx* ctx, int64_t* perm, int64_t* block_ptr,
  *                                                 is used the values of Qt are multiples of 2^-24
  *                                                 (the fp32 spacing in [0.5, 1)) and saturate at
  *                                                 +-128.  Needs (widest column strip) * k * 4
- *                                                 bytes <= 159 KiB of LDS -- or, in the
- *                                                 one-launch form below and with resident
+ *                                                 bytes <= 159 KiB of LDS -- or, with resident
  *                                                 ratings, only (most columns of a strip in
  *                                                 which one block has a rating) * k * 4 bytes:
  *                                                 when the blocks touch at most three quarters
  *                                                 of their strips' columns, or whole strips do
- *                                                 not fit, that form keeps just the touched
+ *                                                 not fit, the kernel keeps just the touched
  *                                                 columns in LDS (a table made by the load call
  *                                                 says which; strips of up to 65536 / (k *
  *                                                 sizeof(element) / 4) columns).  A block's

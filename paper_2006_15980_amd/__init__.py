@@ -10,7 +10,7 @@ import numpy as np
 
 from . import binding
 from .binding import *  # noqa: F401,F403
-from .binding import (MF_F16, MF_F32, MF_KERNEL_AUTO, MF_KERNEL_GLOBAL, MF_KERNEL_LDS, MF_OPT_DET_KERNEL, MF_OPT_RING, MF_OPT_RING_SPIN_LIMIT, MF_OPT_LDS_PREFETCH, MF_OPT_ROW_ORDER_SEED, MF_HOGWILD_AUTO, MF_HOGWILD_GLOBAL_ATOMICS, MF_HOGWILD_LDS, MF_MODE_DET,
+from .binding import (MF_F16, MF_F32, MF_KERNEL_AUTO, MF_KERNEL_GLOBAL, MF_KERNEL_LDS, MF_OPT_DET_KERNEL, MF_OPT_RING, MF_OPT_RING_SPIN_LIMIT, MF_OPT_LDS_PREFETCH, MF_OPT_ROW_ORDER_SEED, MF_OPT_PACK_STRIPS, MF_HOGWILD_AUTO, MF_HOGWILD_GLOBAL_ATOMICS, MF_HOGWILD_LDS, MF_MODE_DET,
                       MF_MODE_HOGWILD, MF_OPT_HOGWILD_CHUNK, MF_OPT_HOGWILD_KERNEL, MF_OPT_LDS_CHUNK,
                       MF_OPT_LDS_WAVES, MF_OPT_PROFILE, MF_OPT_XCD_AFFINITY, MF_PLAN_HOGWILD_LDS, MF_PLAN_LDS_CUT_ROWS,
                       MF_SPLIT_EQUAL_WIDTH, MF_SPLIT_NNZ_BALANCED, MF_SPLIT_NNZ_WIDTH_BALANCED, MFError)

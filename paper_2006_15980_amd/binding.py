@@ -21,6 +21,7 @@ MF_OPT_HOGWILD_CHUNK, MF_OPT_XCD_AFFINITY, MF_OPT_PROFILE = 1, 2, 3
 MF_OPT_HOGWILD_KERNEL, MF_OPT_LDS_CHUNK, MF_OPT_LDS_WAVES = 4, 5, 6
 MF_OPT_DET_KERNEL = 7
 MF_OPT_RING, MF_OPT_RING_SPIN_LIMIT, MF_OPT_LDS_PREFETCH, MF_OPT_ROW_ORDER_SEED = 8, 9, 10, 11
+MF_OPT_PACK_STRIPS = 12
 MF_KERNEL_AUTO, MF_KERNEL_GLOBAL, MF_KERNEL_LDS = 0, 1, 2
 MF_HOGWILD_AUTO, MF_HOGWILD_GLOBAL_ATOMICS, MF_HOGWILD_LDS = 0, 1, 2
 MF_PLAN_HOGWILD_LDS = 2

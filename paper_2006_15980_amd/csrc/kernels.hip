@@ -898,7 +898,7 @@ __device__ __forceinline__ void strip_copy_in(int* strip, const T* __restrict__ 
     const int total = ncols * K;          // multiple of 32
     const T* const strip_src = Qt + (int64_t)col0 * K;
     const int stride = 4 * (int)blockDim.x;
-    if constexpr (COHERENT && !EXACT && SPARSE) {
+    if constexpr (!EXACT && SPARSE) {
         // the touched columns only, into their slots: up to 16 pieces requested, then converted
         constexpr int kPerWord = sizeof(T) == 2 ? 2 : 1;
         constexpr int kInColumn = SparseStrip<T, K>::kWordsPerColumn - 1;
@@ -916,7 +916,7 @@ __device__ __forceinline__ void strip_copy_in(int* strip, const T* __restrict__ 
                     left &= left - 1ull;
                     const int w = (int)threadIdx.x + j * (int)blockDim.x;
                     at[t] = uniform_lane(map.piece_slot, j) * K + (w & kInColumn) * kPerWord;
-                    raw[t] = load_word<true>(src + w);
+                    raw[t] = load_word<COHERENT>(src + w);
                 }
             }
 #pragma unroll
@@ -1036,7 +1036,7 @@ __device__ __forceinline__ void strip_copy_out(const int* strip, T* __restrict__
     const int total = ncols * K;
     T* const strip_dst = Qt + (int64_t)col0 * K;
     const int stride = 4 * (int)blockDim.x;
-    if constexpr (COHERENT && !EXACT && SPARSE) {
+    if constexpr (!EXACT && SPARSE) {
         constexpr int kPerWord = sizeof(T) == 2 ? 2 : 1;
         constexpr int kInColumn = SparseStrip<T, K>::kWordsPerColumn - 1;
         unsigned* dst = reinterpret_cast<unsigned*>(strip_dst);
@@ -1054,7 +1054,8 @@ __device__ __forceinline__ void strip_copy_out(const int* strip, T* __restrict__
             } else {
                 raw = __float_as_uint(from_strip<EXACT>(strip[at], worst));
             }
-            __hip_atomic_store(dst + w, raw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if constexpr (COHERENT) __hip_atomic_store(dst + w, raw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            else dst[w] = raw;
         }
     } else if constexpr (COHERENT && !EXACT) {
         constexpr int kPerWord = sizeof(T) == 2 ? 2 : 1;
@@ -1261,18 +1262,25 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
 }
 
 // One launch per stratum: workgroup i works on the i-th non-empty block of the stratum.
-template <typename T, int K, bool EXACT, int DEPTH>
+template <typename T, int K, bool EXACT, int DEPTH, bool SPARSE>
 __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_block_lds(
     T* __restrict__ P, T* __restrict__ Qt, const int32_t* __restrict__ U,
     const int32_t* __restrict__ V, const float* __restrict__ R,
     const int64_t* __restrict__ entry_begin, const int32_t* __restrict__ entry_len, const int64_t* __restrict__ hot_pos,
-    const LdsBlock* __restrict__ blocks, float lr, float lambda, int* range_flag)
+    const LdsBlock* __restrict__ blocks, float lr, float lambda, int* range_flag, const unsigned* __restrict__ touched,
+    int touched_words, int slot_table_at)
 {
     extern __shared__ int strip[];            // ncols * K values (fixed point, or fp32 bits if EXACT)
     RangeWatch watch;
-    lds_block_body<T, K, EXACT, false, DEPTH, false>(strip, P, Qt, U, V, R, entry_begin, entry_len, hot_pos,
-                                                     blocks[blockIdx.x], lr, lambda, true, true, 0xffffffffu, 0, watch,
-                                                     [] { return true; });
+    const LdsBlock blk = blocks[blockIdx.x];
+    unsigned mask_word = 0xffffffffu;
+    if constexpr (SPARSE) {
+        const int lane = threadIdx.x & (kWave - 1);
+        mask_word = lane < touched_words ? touched[(int64_t)blk.id * touched_words + lane] : 0u;
+    }
+    lds_block_body<T, K, EXACT, false, DEPTH, SPARSE>(strip, P, Qt, U, V, R, entry_begin, entry_len, hot_pos, blk, lr,
+                                                      lambda, true, true, mask_word, slot_table_at, watch,
+                                                      [] { return true; });
     if constexpr (!EXACT) {
         if (__any(watch.hit()) && (threadIdx.x & (kWave - 1)) == 0) *range_flag = 1;
     }
@@ -1545,11 +1553,12 @@ hipError_t launch_sgd_t(bool hogwild, void* P, void* Qt, const int32_t* U, const
     return hipGetLastError();
 }
 
-template <typename T, int K, bool EXACT, int DEPTH>
+template <typename T, int K, bool EXACT, int DEPTH, bool SPARSE>
 hipError_t launch_sgd_lds_impl(int waves, void* P, void* Qt, const int32_t* U, const int32_t* V,
                             const float* R, const int64_t* eb, const int32_t* el, const int64_t* hot,
                             const LdsBlock* blocks, int64_t n_blocks, size_t lds_bytes, float lr,
-                            float lambda, int* range_flag, hipStream_t stream)
+                            float lambda, int* range_flag, const uint32_t* touched, int touched_words,
+                            int slot_table_at, hipStream_t stream)
 {
     // more than 64 KiB of dynamic LDS has to be allowed once per kernel and device
     static bool raised[64] = {};
@@ -1557,13 +1566,14 @@ hipError_t launch_sgd_lds_impl(int waves, void* P, void* Qt, const int32_t* U, c
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev >= 0 && dev < 64 && !raised[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sgd_block_lds<T, K, EXACT, DEPTH>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sgd_block_lds<T, K, EXACT, DEPTH, SPARSE>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
         if (e != hipSuccess) return e;
         raised[dev] = true;
     }
-    hipLaunchKernelGGL((sgd_block_lds<T, K, EXACT, DEPTH>), dim3((unsigned)n_blocks), dim3(waves * kWave), lds_bytes,
-                       stream, (T*)P, (T*)Qt, U, V, R, eb, el, hot, blocks, lr, lambda, range_flag);
+    hipLaunchKernelGGL((sgd_block_lds<T, K, EXACT, DEPTH, SPARSE>), dim3((unsigned)n_blocks), dim3(waves * kWave), lds_bytes,
+                       stream, (T*)P, (T*)Qt, U, V, R, eb, el, hot, blocks, lr, lambda, range_flag, touched, touched_words,
+                       slot_table_at);
     return hipGetLastError();
 }
 
@@ -1638,16 +1648,30 @@ template <typename T, int K>
 hipError_t launch_sgd_lds_t(bool exact, bool short_prefetch, int waves, void* P, void* Qt, const int32_t* U, const int32_t* V,
                             const float* R, const int64_t* eb, const int32_t* el, const int64_t* hot,
                             const LdsBlock* blocks, int64_t n_blocks, size_t lds_bytes, float lr,
-                            float lambda, int* range_flag, hipStream_t stream)
+                            float lambda, int* range_flag, const uint32_t* touched, int touched_words, int slot_table_at,
+                            hipStream_t stream)
 {
     if (exact)
-        return launch_sgd_lds_impl<T, K, true, kLdsPrefetchDepth>(1, P, Qt, U, V, R, eb, el, hot, blocks, n_blocks, lds_bytes,
-                                                                  lr, lambda, range_flag, stream);
+        return launch_sgd_lds_impl<T, K, true, kLdsPrefetchDepth, false>(1, P, Qt, U, V, R, eb, el, hot, blocks, n_blocks,
+                                                                         lds_bytes, lr, lambda, range_flag, nullptr, 0, 0,
+                                                                         stream);
+    if constexpr (SparseStrip<T, K>::kPossible) {
+        if (touched && short_prefetch)
+            return launch_sgd_lds_impl<T, K, false, kShortPrefetchDepth, true>(
+                waves, P, Qt, U, V, R, eb, el, hot, blocks, n_blocks, lds_bytes, lr, lambda, range_flag, touched,
+                touched_words, slot_table_at, stream);
+        if (touched)
+            return launch_sgd_lds_impl<T, K, false, kLdsPrefetchDepth, true>(
+                waves, P, Qt, U, V, R, eb, el, hot, blocks, n_blocks, lds_bytes, lr, lambda, range_flag, touched,
+                touched_words, slot_table_at, stream);
+    }
     if (short_prefetch)
-        return launch_sgd_lds_impl<T, K, false, kShortPrefetchDepth>(waves, P, Qt, U, V, R, eb, el, hot, blocks, n_blocks,
-                                                                     lds_bytes, lr, lambda, range_flag, stream);
-    return launch_sgd_lds_impl<T, K, false, kLdsPrefetchDepth>(waves, P, Qt, U, V, R, eb, el, hot, blocks, n_blocks, lds_bytes,
-                                                               lr, lambda, range_flag, stream);
+        return launch_sgd_lds_impl<T, K, false, kShortPrefetchDepth, false>(waves, P, Qt, U, V, R, eb, el, hot, blocks,
+                                                                            n_blocks, lds_bytes, lr, lambda, range_flag,
+                                                                            nullptr, 0, 0, stream);
+    return launch_sgd_lds_impl<T, K, false, kLdsPrefetchDepth, false>(waves, P, Qt, U, V, R, eb, el, hot, blocks, n_blocks,
+                                                                      lds_bytes, lr, lambda, range_flag, nullptr, 0, 0,
+                                                                      stream);
 }
 
 template <typename T, int K>
@@ -1702,12 +1726,16 @@ size_t lds_strip_bytes(int k, int32_t max_cols) { return (size_t)max_cols * k * 
 hipError_t launch_sgd_lds(int dtype, int k, bool exact, bool short_prefetch, int waves, void* P, void* Qt, const int32_t* U,
                           const int32_t* V, const float* R, const int64_t* entry_begin,
                           const int32_t* entry_len, const int64_t* hot_pos, const LdsBlock* blocks, int64_t n_blocks,
-                          size_t lds_bytes, float lr, float lambda, int* range_flag, hipStream_t stream)
+                          size_t lds_bytes, float lr, float lambda, int* range_flag, const uint32_t* touched,
+                          int touched_words, int slot_table_at, hipStream_t stream)
 {
     if (n_blocks <= 0) return hipSuccess;
     if (waves < 1 || waves > 16 || lds_bytes > kLdsBudget || !range_flag) return hipErrorInvalidValue;
+    if (touched && (touched_words < 1 || touched_words > kMaxTouchedWords || slot_table_at < 0 ||
+                    (size_t)slot_table_at * 4 + (size_t)touched_words * 64 > lds_bytes))
+        return hipErrorInvalidValue;
     MF_DISPATCH(launch_sgd_lds_t, exact, short_prefetch, waves, P, Qt, U, V, R, entry_begin, entry_len, hot_pos, blocks, n_blocks,
-                lds_bytes, lr, lambda, range_flag, stream);
+                lds_bytes, lr, lambda, range_flag, touched, touched_words, slot_table_at, stream);
 }
 
 hipError_t launch_sgd_ring(int dtype, int k, bool exact, bool short_prefetch, int waves, bool query_only, int* max_resident,

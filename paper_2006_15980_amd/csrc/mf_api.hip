@@ -62,6 +62,7 @@ struct mf_ctx {
     bool lds_waves_set = false;  // the caller chose it
     int32_t lds_waves_used = 16; // what the loaded LDS work list was built for
     int32_t lds_prefetch = 0;  // 0 = by the size of P, else 4 or 8
+    bool pack_strips = true;   // MF_OPT_PACK_STRIPS
     uint64_t row_seed = 0;     // 0 = rows of a block in ascending order
 
     // library-owned device buffer: RMSE partials followed by the final sum
@@ -341,6 +342,10 @@ int mf_set_option(mf_ctx* ctx, int32_t option, int64_t value)
             if (value != 0 && value != 4 && value != 8) return fail(ctx, MF_EINVAL, "MF_OPT_LDS_PREFETCH is 0, 4 or 8");
             ctx->lds_prefetch = (int32_t)value;
             return MF_OK;
+        case MF_OPT_PACK_STRIPS:
+            if (value != 0 && value != 1) return fail(ctx, MF_EINVAL, "MF_OPT_PACK_STRIPS is 0 or 1");
+            ctx->pack_strips = value != 0;
+            return MF_OK;
     }
     return fail(ctx, MF_EINVAL, "unknown option");
 }
@@ -424,7 +429,9 @@ int make_touched_table(mf_ctx* ctx, const Layout& lay, char* base)
     const int64_t words_per_column = (int64_t)ctx->k * (ctx->dtype == MF_F16 ? 2 : 4) / 4;
     const bool shape_ok = words_per_column % 64 == 0 &&
                           (int64_t)widest * words_per_column <= (int64_t)64 * 64 * ctx->lds_waves_used;
-    if (ctx->streamed || !ctx->dV || part.nnz == 0 || words < 1 || words > lay.touched_words || !shape_ok) return MF_OK;
+    if (!ctx->pack_strips || ctx->streamed || !ctx->dV || part.nnz == 0 || words < 1 || words > lay.touched_words ||
+        !shape_ok)
+        return MF_OK;
     std::vector<mf::LdsBlock> ranges;
     for (int32_t st = 0; st < part.gc; ++st)
         for (int32_t a = 0; a < part.gr; ++a) {
@@ -742,10 +749,10 @@ int plan_epoch(mf_ctx* ctx, int32_t mode, EpochPlan& p)
     const int32_t choice = p.hog ? ctx->hogwild_kernel : ctx->det_kernel;
     const size_t budget = p.hog || choice == MF_KERNEL_LDS ? mf::kLdsBudget : mf::kLdsBudget / 4;
     const bool ring_allowed = ctx->use_ring && !ctx->ring_gave_up && ctx->part.nnz > 0 && !ctx->streamed;
-    // packed strips exist in the one-launch Hogwild kernel only
+    // packed strips: Hogwild LDS kernels, when the load made the table of touched columns
     p.slot_table_at = (ctx->max_slots + lsched.max_hot) * ctx->k;
     const size_t packed_bytes = (size_t)p.slot_table_at * 4 + (size_t)lsched.touched_words * 64;
-    p.packed = p.hog && lsched.d_touched && ring_allowed && choice != MF_KERNEL_GLOBAL && packed_bytes <= budget;
+    p.packed = p.hog && lsched.d_touched && choice != MF_KERNEL_GLOBAL && packed_bytes <= budget;
     p.lds_bytes = p.packed ? packed_bytes : dense_bytes;
     p.use_lds = choice != MF_KERNEL_GLOBAL && p.lds_bytes <= budget;
     if (!p.use_lds && choice == MF_KERNEL_LDS)
@@ -769,14 +776,7 @@ int plan_epoch(mf_ctx* ctx, int32_t mode, EpochPlan& p)
         p.ring = ctx->part.gr <= ctx->ring_resident[m_idx];
         if (!p.ring)
             why += "the device holds " + std::to_string(ctx->ring_resident[m_idx]) + " workgroups of this shape at once, fewer than grid_r; ";
-        if (!p.ring && p.packed) {
-            // one launch per stratum keeps whole strips
-            p.packed = false;
-            p.lds_bytes = dense_bytes;
-            p.use_lds = dense_bytes <= budget;
-            p.waves = p.use_lds ? ctx->lds_waves_used : mf::kWavesPerGroup;
-            if (!p.use_lds) why += "whole column strips do not fit the LDS; ";
-        }
+
     } else if (p.use_lds && ctx->ring_gave_up) {
         why += "an earlier epoch of the one-launch kernel exceeded its wait limit; ";
     }
@@ -793,7 +793,7 @@ int plan_epoch(mf_ctx* ctx, int32_t mode, EpochPlan& p)
     p.note = std::string(p.hog ? "MF_MODE_HOGWILD" : "MF_MODE_DET") + ": " + names[p.kernel] + ", " +
              std::to_string(p.launches) + " launch(es) per epoch, " + std::to_string(p.waves) +
              " wavefront(s) per workgroup" + (why.empty() ? "" : " (" + why.substr(0, why.size() - 2) + ")");
-    if (p.packed)
+    if (p.packed && p.use_lds)
         p.note += "; keeps only the touched columns of a strip in LDS (" +
                   std::to_string((int)(ctx->touched_share * 100.0 + 0.5)) + " % of all strip columns)";
     if (!p.hog && p.kernel == MF_KERNEL_ID_CHUNKS && choice != MF_KERNEL_GLOBAL)
@@ -956,7 +956,8 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
         if (count > 0 && use_lds)
             MF_HIP(ctx, mf::launch_sgd_lds(ctx->dtype, ctx->k, !hog, short_prefetch, ctx->lds_waves_used, ctx->dP, ctx->dQt, U, V,
                                            R, lsched.d_begin, lsched.d_len, lsched.d_hot, lsched.d_blocks + first, count, lds_bytes,
-                                           lr, lambda, d_flags + 1, ctx->stream));
+                                           lr, lambda, d_flags + 1, plan.packed ? lsched.d_touched : nullptr,
+                                           lsched.touched_words, plan.slot_table_at, ctx->stream));
         else if (count > 0)
             MF_HIP(ctx, mf::launch_sgd(ctx->dtype, ctx->k, mode == MF_MODE_HOGWILD, ctx->dP, ctx->dQt, U, V, R,
                                        s.d_begin, s.d_len, first, count, lr, lambda, ctx->stream));

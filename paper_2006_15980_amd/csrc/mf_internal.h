@@ -158,20 +158,22 @@ hipError_t launch_sgd(int dtype, int k, bool hogwild, void* P, void* Qt, const i
 // served from the caches).  hot_pos: the schedule's list of cut rows (see LdsBlock); lds_bytes
 // covers the widest strip plus the most cut rows of any block.  range_flag (device): set to 1 by
 // the Hogwild kernel when a value leaves the safe range of its fixed-point strip.
+// touched (device, may be null) / touched_words / slot_table_at: the table of touched columns per
+// block id (launch_mark_touched).  With it the Hogwild form keeps only the touched columns of a
+// strip in LDS, packed; lds_bytes then covers the most touched columns of any block plus its cut
+// rows, followed -- from the 32-bit word slot_table_at on -- by 64 bytes per bit word for the
+// kernel's column -> slot table.
 hipError_t launch_sgd_lds(int dtype, int k, bool exact, bool short_prefetch, int waves, void* P, void* Qt, const int32_t* U,
                           const int32_t* V, const float* R, const int64_t* entry_begin,
                           const int32_t* entry_len, const int64_t* hot_pos, const LdsBlock* blocks, int64_t n_blocks,
-                          size_t lds_bytes, float lr, float lambda, int* range_flag, hipStream_t stream);
+                          size_t lds_bytes, float lr, float lambda, int* range_flag, const uint32_t* touched,
+                          int touched_words, int slot_table_at, hipStream_t stream);
 // One launch per epoch (ring of workgroups, see kernels.hip).  ring_blocks: grid_c * grid_r
 // descriptors indexed [stratum][block row], empty blocks included.  order / pos (device, grid_c
 // entries each, both or neither): the stratum of every step and its inverse.  abort_flag: two
 // device ints, [0] raised when a bounded wait expires, [1] the range flag.  query_only: do not launch,
 // return in *max_resident how many workgroups of this shape the device can hold at once.
-// touched (device, may be null) / touched_words: the table of touched columns per block id
-// (launch_mark_touched); with it the Hogwild form keeps only the touched columns of a strip in
-// LDS, packed; lds_bytes then covers the most touched columns of any block plus its cut rows,
-// followed -- from the 32-bit word slot_table_at on -- by 64 bytes per bit word for the kernel's
-// column -> slot table.
+// touched / touched_words / slot_table_at: as for launch_sgd_lds.
 hipError_t launch_sgd_ring(int dtype, int k, bool exact, bool short_prefetch, int waves, bool query_only, int* max_resident,
                            void* P, void* Qt, const int32_t* U, const int32_t* V, const float* R,
                            const int64_t* entry_begin, const int32_t* entry_len, const int64_t* hot_pos, const LdsBlock* ring_blocks,

@@ -713,13 +713,14 @@ def test_hogwild_pieces_of_long_rows_in_one_wavefront_follow_the_sequential_orde
 
 @pytest.mark.parametrize("storage,k,grid", [("f32", 128, (8, 32)), ("f32", 64, (8, 20)), ("f16", 128, (8, 32)),
                                              ("f32", 256, (8, 63))])
-def test_one_launch_hogwild_kernel_copies_only_the_touched_columns(mfmod, storage, k, grid):
-    """When the blocks have ratings in a minority of their strips' columns, the one-launch Hogwild
-    kernel copies only those in and out of LDS (a table of touched columns per block, made at load
-    time).  With ONE wavefront per workgroup the Hogwild arithmetic is sequential, so that kernel
-    must give the bits of the one-launch-per-stratum kernel, which copies whole strips -- in every
-    column that has a rating.  A column without ratings is never copied by the first and is put on
-    the 2^-24 grid of the strip by the second: there the first must return the initial value.
+def test_packed_strips_give_the_bits_of_whole_strips(mfmod, storage, k, grid):
+    """When the blocks have ratings in a minority of their strips' columns, the Hogwild LDS kernels
+    keep only those columns in LDS, packed (a table of touched columns per block, made at load
+    time).  With ONE wavefront per workgroup the Hogwild arithmetic is sequential, so the packed
+    form -- one launch per epoch and one launch per stratum -- must give the bits of the form that
+    keeps whole strips (MF_OPT_PACK_STRIPS = 0), in every column that has a rating.  A column
+    without ratings is never copied by the packed form and is put on the 2^-24 grid of the strip
+    by the other: there the packed form must return the initial value.
     (Strips of at most 4096 words: what one wavefront's 64 piece bits cover.)"""
     ds = dataset("tiny")
     take = 5600                                  # about half of a block's strip columns have a rating
@@ -727,53 +728,60 @@ def test_one_launch_hogwild_kernel_copies_only_the_touched_columns(mfmod, storag
     cols[cols >= 990] -= 500                     # columns 990..999 have no ratings at all
     gr, gc = grid
     outs, notes = [], []
-    for ring in (1, 0):
+    for ring, pack in ((1, 1), (0, 1), (0, 0)):
         model = mfmod.MatrixFactorization(ds.cfg.m, ds.cfg.n, k, storage, seed=3, scale=0.1,
                                           options={mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS,
-                                                   mfmod.MF_OPT_LDS_WAVES: 1, mfmod.MF_OPT_RING: ring})
+                                                   mfmod.MF_OPT_LDS_WAVES: 1, mfmod.MF_OPT_RING: ring,
+                                                   mfmod.MF_OPT_PACK_STRIPS: pack})
         model.load_blocks(rows, cols, vals, gr, gc, 0)
-        if ring == 1:
+        if not outs:
             P0, Q0 = model.get_factors()
-        notes.append(model.epoch_plan(mfmod.MF_MODE_HOGWILD)["note"])
+        plan = model.epoch_plan(mfmod.MF_MODE_HOGWILD)
+        assert plan["kernel"] == ("sgd_ring_lds" if ring else "sgd_block_lds"), plan
+        notes.append(plan["note"])
         for _ in range(3):
             model.sgd_epoch(0.01, 0.05, mfmod.MF_MODE_HOGWILD)
         model.sync()
         outs.append(model.get_factors())
         model.close()
-    assert "touched columns" in notes[0] and "touched columns" not in notes[1], notes
+    assert "touched columns" in notes[0] and "touched columns" in notes[1] and "touched columns" not in notes[2], notes
     rated = np.zeros(ds.cfg.n, bool)
     rated[cols] = True
     assert not rated[990:].any() and rated[:990].sum() > 900
-    assert np.array_equal(outs[0][0], outs[1][0])                       # P
-    assert np.array_equal(outs[0][1][rated], outs[1][1][rated])         # Qt where it was ever used
-    assert np.array_equal(outs[0][1][~rated], Q0[~rated])               # and never touched elsewhere
+    for packed in outs[:2]:
+        assert np.array_equal(packed[0], outs[2][0])                        # P
+        assert np.array_equal(packed[1][rated], outs[2][1][rated])          # Qt where it was ever used
+        assert np.array_equal(packed[1][~rated], Q0[~rated])                # and never touched elsewhere
     assert not np.array_equal(outs[0][1][rated], Q0[rated])
 
 
 @pytest.mark.parametrize("k,grid,take,whole_strip_fits", [(128, (16, 16), 9500, True), (256, (4, 4), 3000, False)])
-def test_packed_strips_with_sixteen_wavefronts_visit_every_rating_once(mfmod, k, grid, take, whole_strip_fits):
+@pytest.mark.parametrize("ring", [1, 0])
+def test_packed_strips_with_sixteen_wavefronts_visit_every_rating_once(mfmod, ring, k, grid, take, whole_strip_fits):
     """The first-order argument of test_hogwild_visits_every_rating_exactly_once for the form that
     keeps only the touched columns of a strip in LDS, with 16 wavefronts per workgroup: at
     lr = 1e-5 and lambda = 0 the order of the ratings matters to second order only, while one
     rating that is missed moves its row by up to 3e-6, and a touched column that went to the wrong
     slot, was not copied in (stale LDS) or not copied back shows at full size.  Second case: strips
     of 250 columns of k = 256, which do not fit the LDS whole (256 KB) -- only the packed form can
-    run them there, and without the one-launch kernel the L2-atomics kernel takes over."""
+    run them there; with packing switched off the L2-atomics kernel takes over."""
     ds = dataset("tiny")
     cfg = ds.cfg
     rows, cols, vals = ds.rows[:take], ds.cols[:take], ds.vals[:take]
     gr, gc = grid
     lr, lam = 1e-5, 0.0
     model = mfmod.MatrixFactorization(cfg.m, cfg.n, k, "f32", seed=1, scale=0.1,
-                                      options={mfmod.MF_OPT_RING: 1, mfmod.MF_OPT_LDS_WAVES: 16})
+                                      options={mfmod.MF_OPT_RING: ring, mfmod.MF_OPT_LDS_WAVES: 16})
     model.load_blocks(rows, cols, vals, gr, gc, 1)
     plan = model.epoch_plan(mfmod.MF_MODE_HOGWILD)
-    assert plan["kernel"] == "sgd_ring_lds" and plan["waves"] == 16 and "touched columns" in plan["note"], plan
+    assert plan["kernel"] == ("sgd_ring_lds" if ring else "sgd_block_lds") and plan["waves"] == 16, plan
+    assert "touched columns" in plan["note"], plan
     model.sgd_epoch(lr, lam, mfmod.MF_MODE_HOGWILD)
     P, Q = model.get_factors()
-    mfmod.binding.mf_set_option(model.ctx, mfmod.MF_OPT_RING, 0)
+    mfmod.binding.mf_set_option(model.ctx, mfmod.MF_OPT_PACK_STRIPS, 0)
+    model.load_blocks(rows, cols, vals, gr, gc, 1)
     other = model.epoch_plan(mfmod.MF_MODE_HOGWILD)
-    assert other["kernel"] == ("sgd_block_lds" if whole_strip_fits else "sgd_chunks"), other
+    assert "touched columns" not in other["note"] and (other["kernel"] == "sgd_chunks") == (not whole_strip_fits), other
     model.close()
     perm, bp, _, _ = oracle.partition(rows, cols, cfg.m, cfg.n, gr, gc, 1)
     P0, Q0 = oracle_init(cfg.m, cfg.n, k, 1, 0.1)
@@ -781,8 +789,8 @@ def test_packed_strips_with_sixteen_wavefronts_visit_every_rating_once(mfmod, k,
     oracle.sgd_epoch_omp(Po, Qo, rows, cols, vals, perm, bp, gr, gc, lr, lam)
     dp, dq = float(np.abs(P - Po).max()), float(np.abs(Q - Qo).max())
     moved = float(np.abs(Po - P0).max())
-    print("packed strips, 16 wavefronts, k=%d: max|dP| %.2e max|dQ| %.2e, the epoch moves P by up to %.2e"
-          % (k, dp, dq, moved), flush=True)
+    print("packed strips, 16 wavefronts, k=%d ring=%d: max|dP| %.2e max|dQ| %.2e, the epoch moves P by up to %.2e"
+          % (k, ring, dp, dq, moved), flush=True)
     assert moved > 5e-6 and dp <= 6e-7 and dq <= 1.2e-6, (moved, dp, dq)
 
 
