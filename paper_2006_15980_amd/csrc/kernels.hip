@@ -9,12 +9,14 @@
 //   sgd_block_lds : one workgroup per block of a stratum; the block's strip of Qt lives in LDS
 //                   (fp32 for the deterministic mode, 32-bit fixed point + integer atomics for
 //                   Hogwild), rows of P stream through registers; in Hogwild mode the few rows
-//                   of P that are shared out over several wavefronts sit in LDS beside the strip.
+//                   of P that are shared out over several wavefronts sit in LDS beside the strip,
+//                   and the strip may be packed: only the columns in which the block has a rating.
 //   sgd_ring_lds  : the same block body, one launch per epoch: workgroup a keeps block row a and
 //                   the column strips are handed from workgroup to workgroup with bounded waits.
 //   rmse_partial / rmse_final : sum of squared prediction errors (Eq. 1 against the rating),
 //                   double precision, fixed reduction order.
 //   init_fill     : counter-based uniform initial factors.
+//   mark_touched  : per block, the columns of its strip in which it has a rating (for packing).
 //
 // This is a gather / dot / scatter over rows of 128..1024 bytes with about half a flop per byte:
 // there is no MFMA here; the lanes hold rows in registers, consecutive ratings of one matrix row
@@ -1623,7 +1625,7 @@ hipError_t launch_sgd_ring_t(bool exact, bool short_prefetch, int waves, bool qu
         return launch_sgd_ring_impl<T, K, true, kLdsPrefetchDepth, false>(
             1, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done,
             first, abort_flag, spin_limit, order, pos, nullptr, 0, 0, stream);
-    // the form that copies only the touched columns of a strip exists where a wavefront's piece of
+    // the form that keeps only the touched columns of a strip in LDS exists where a wavefront's piece of
     // the strip lies in one column
     if constexpr (SparseStrip<T, K>::kPossible) {
         if (touched && short_prefetch)

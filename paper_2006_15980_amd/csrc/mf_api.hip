@@ -14,7 +14,7 @@
 #include "../../include/mf_sgd.h"
 #include "mf_internal.h"
 
-// The one-launch Hogwild kernel keeps only the touched columns of a strip in LDS when at most this
+// The Hogwild LDS kernels keep only the touched columns of a strip in LDS when at most this
 // share of all strip columns is touched (or when whole strips do not fit).
 constexpr double kSparseStripShare = 0.75;
 
@@ -410,7 +410,7 @@ int check_load(mf_ctx* ctx, const void* rows, const void* cols, const void* vals
 // The partition and the packed arrays exist (ctx->part; `rs` = where the row runs begin):
 // derive the work lists and put them into the workspace.
 // Which columns of its strip every block touches (resident ratings only): the table the
-// one-launch Hogwild kernel packs its strips with, made before the work lists because the room
+// Hogwild LDS kernels pack their strips with, made before the work lists because the room
 // the packed strips leave in LDS decides how many rows a block may cut.  Sets ctx->lds.d_touched
 // when packing is possible and pays.
 int make_touched_table(mf_ctx* ctx, const Layout& lay, char* base)
@@ -729,7 +729,7 @@ struct EpochPlan {
     int32_t waves = 1;             // wavefronts per workgroup
     int32_t kernel = 0;            // MF_KERNEL_ID_*
     int64_t launches = 0;          // per epoch
-    bool packed = false;           // one-launch Hogwild kernel with only the touched columns of a strip in LDS
+    bool packed = false;           // Hogwild LDS kernels with only the touched columns of a strip in LDS
     int32_t slot_table_at = 0;     // packed: where the kernel's column table begins in LDS (32-bit words)
     std::string note;
 };

@@ -36,7 +36,7 @@ struct Schedule {
 // schedule's hot_pos list (the bits above).
 // `id` = the block's linear id L = stratum * G_r + block row; it indexes the table of touched
 // columns (one bit per column of the block's strip: set when the block has a rating there),
-// with which the one-launch Hogwild kernel copies only those columns in and out of LDS.
+// with which the Hogwild LDS kernels keep only those columns in LDS, packed.
 constexpr int32_t kMaxHotRows = 8;
 constexpr int32_t kMaxTouchedWords = 64;   // bit words per block of that table (one per lane of a wavefront)
 struct LdsBlock {
