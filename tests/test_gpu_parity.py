@@ -1169,13 +1169,22 @@ def test_full_size_against_the_stored_oracle_results(mfmod, name):
     got = model.rmse(*test)
     print(f"{name} DET epoch 1: rmse gpu {got:.6f} oracle {want_rmse[0]:.6f}", flush=True)
     assert abs(got - want_rmse[0]) <= 1e-3
+    # further deterministic epochs, as many as a minute allows (the grid was made for the Hogwild
+    # mode: the deterministic one runs on its fallback kernel here); the oracle's held-out RMSE is
+    # stored after every epoch
     t0 = time.perf_counter()
-    for e in range(1, len(want_rmse)):
+    done = 1
+    while done < len(want_rmse):
         model.sgd_epoch(cfg.lr, cfg.lam, mfmod.MF_MODE_DET)
+        model.sync()
+        done += 1
+        spent = time.perf_counter() - t0
+        if spent + spent / (done - 1) > 60.0:
+            break
     got = model.rmse(*test)
-    print(f"{name} DET {len(want_rmse)} epochs: rmse gpu {got:.6f} oracle {want_rmse[-1]:.6f} "
+    print(f"{name} DET {done} of {len(want_rmse)} epochs: rmse gpu {got:.6f} oracle {want_rmse[done - 1]:.6f} "
           f"({time.perf_counter() - t0:.1f} s)", flush=True)
-    assert abs(got - want_rmse[-1]) <= 1e-3
+    assert abs(got - want_rmse[done - 1]) <= 1e-3
     model.close()
 
     # Hogwild mode as bench.py runs it (kernel and wavefronts per workgroup: the library's choice)
