@@ -185,8 +185,10 @@ int mf_get_partition(const mf_ctx* ctx, int64_t* perm, int64_t* block_ptr,
  *                     on every run and equals the sequential order (strata ascending, blocks
  *                     ascending, stored order) up to fp32 rounding.  Two kernels with identical
  *                     results: MF_KERNEL_LDS keeps the block's strip of Qt in LDS (fp32; taken by
- *                     MF_KERNEL_AUTO when a strip needs at most 39 KiB, so that several blocks
- *                     fit one compute unit), MF_KERNEL_GLOBAL works on Qt in memory (any grid).
+ *                     MF_KERNEL_AUTO when a strip needs no more than the share of a compute
+ *                     unit's 159 KiB of LDS that lets all grid_r single-wavefront workgroups be
+ *                     resident: all of it up to 256 block rows, half up to 512, else a quarter),
+ *                     MF_KERNEL_GLOBAL works on Qt in memory (any grid).
  *   MF_MODE_HOGWILD : every block is cut into chunks of whole rows that many wavefronts process
  *                     concurrently without locks (lock-free updates in the sense of Hogwild,
  *                     Section 3.1).  A wavefront owns the rows of P of its chunk; rows of Qt are

@@ -386,8 +386,11 @@ __device__ __forceinline__ int strip_elem(int lane, int j)
     return lane + kWave * j;
 }
 
-constexpr int kLdsPrefetchDepth = 8;   // rows of P requested ahead (deterministic mode; Hogwild: 8 or kShortPrefetchDepth)
+constexpr int kLdsPrefetchDepth = 8;   // rows of P requested ahead in the Hogwild form (or kShortPrefetchDepth)
 constexpr int kShortPrefetchDepth = 4;
+// The deterministic form has a compute unit nearly to itself (one wavefront per workgroup) and
+// registers to spare: 16 rows ahead measured 5 % faster than 8 on 250 M ratings, 32 slower.
+constexpr int kDetPrefetchDepth = 16;
 
 constexpr int kFixedBits = 24;
 constexpr float kToFixed = (float)(1 << kFixedBits);
@@ -1622,7 +1625,7 @@ hipError_t launch_sgd_ring_t(bool exact, bool short_prefetch, int waves, bool qu
                              int touched_words, int slot_table_at, hipStream_t stream)
 {
     if (exact)
-        return launch_sgd_ring_impl<T, K, true, kLdsPrefetchDepth, false>(
+        return launch_sgd_ring_impl<T, K, true, kDetPrefetchDepth, false>(
             1, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done,
             first, abort_flag, spin_limit, order, pos, nullptr, 0, 0, stream);
     // the form that keeps only the touched columns of a strip in LDS exists where a wavefront's piece of
@@ -1654,7 +1657,7 @@ hipError_t launch_sgd_lds_t(bool exact, bool short_prefetch, int waves, void* P,
                             hipStream_t stream)
 {
     if (exact)
-        return launch_sgd_lds_impl<T, K, true, kLdsPrefetchDepth, false>(1, P, Qt, U, V, R, eb, el, hot, blocks, n_blocks,
+        return launch_sgd_lds_impl<T, K, true, kDetPrefetchDepth, false>(1, P, Qt, U, V, R, eb, el, hot, blocks, n_blocks,
                                                                          lds_bytes, lr, lambda, range_flag, nullptr, 0, 0,
                                                                          stream);
     if constexpr (SparseStrip<T, K>::kPossible) {

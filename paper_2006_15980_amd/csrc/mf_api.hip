@@ -20,6 +20,7 @@ constexpr double kSparseStripShare = 0.75;
 
 struct mf_ctx {
     int device = 0;
+    int compute_units = 256;
     hipStream_t stream = nullptr;
     std::string err;
 
@@ -270,6 +271,9 @@ int mf_create(mf_ctx** out, int device, void* hip_stream)
         }
         g_scratch_addr[device] = addr;
     }
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cus > 0)
+        ctx->compute_units = cus;
     *out = ctx;
     return MF_OK;
 }
@@ -747,7 +751,11 @@ int plan_epoch(mf_ctx* ctx, int32_t mode, EpochPlan& p)
     const mf::LdsSchedule& lsched = p.hog ? ctx->lds : ctx->det_lds;
     const size_t dense_bytes = mf::lds_strip_bytes(ctx->k, lsched.max_cols) + (size_t)lsched.max_hot * ctx->k * 4;
     const int32_t choice = p.hog ? ctx->hogwild_kernel : ctx->det_kernel;
-    const size_t budget = p.hog || choice == MF_KERNEL_LDS ? mf::kLdsBudget : mf::kLdsBudget / 4;
+    // the deterministic form runs one wavefront per workgroup: its strips may take the share of a
+    // compute unit's LDS that lets all grid_r workgroups be resident (at most four per unit)
+    const int64_t per_unit =
+        std::min<int64_t>(4, std::max<int64_t>(1, (ctx->part.gr + ctx->compute_units - 1) / ctx->compute_units));
+    const size_t budget = p.hog || choice == MF_KERNEL_LDS ? mf::kLdsBudget : mf::kLdsBudget / (size_t)per_unit;
     const bool ring_allowed = ctx->use_ring && !ctx->ring_gave_up && ctx->part.nnz > 0 && !ctx->streamed;
     // packed strips: Hogwild LDS kernels, when the load made the table of touched columns
     p.slot_table_at = (ctx->max_slots + lsched.max_hot) * ctx->k;
