@@ -739,8 +739,9 @@ def test_packed_strips_give_the_bits_of_whole_strips(mfmod, storage, k, grid):
         plan = model.epoch_plan(mfmod.MF_MODE_HOGWILD)
         assert plan["kernel"] == ("sgd_ring_lds" if ring else "sgd_block_lds"), plan
         notes.append(plan["note"])
-        for _ in range(3):
-            model.sgd_epoch(0.01, 0.05, mfmod.MF_MODE_HOGWILD)
+        for epoch in range(3):      # the first in natural order of the strata, then two shuffled ones
+            order = oracle.stratum_order(11, epoch, gc) if epoch else None
+            model.sgd_epoch(0.01, 0.05, mfmod.MF_MODE_HOGWILD, stratum_order=order)
         model.sync()
         outs.append(model.get_factors())
         model.close()
