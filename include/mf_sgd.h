@@ -314,8 +314,12 @@ int mf_debug_xcc_ids(mf_ctx* ctx, int32_t n_groups, int32_t* xcc_out);
  * that are too small leave the GPU idle).  Rules: MF_MODE_HOGWILD wants about 224 x 224 blocks (all
  * block rows resident for the one-launch ring kernel), at least ~64 ratings per block, and column
  * strips that fit the LDS under MF_SPLIT_NNZ_WIDTH_BALANCED (at most 2*n/grid_c columns of k fp32
- * values in 159 KiB), which raises grid_c for wide matrices; MF_MODE_DET wants strips of at most a
- * quarter of that and about 40 ratings per block, capped at 512.  All outputs are HOST pointers. */
+ * values in 159 KiB), which raises grid_c for wide matrices; MF_MODE_DET wants about 40 ratings per
+ * block, up to 1024 block rows, and strips of the LDS share that keeps all of them resident (all of
+ * it up to 256 block rows, half up to 512, else a quarter).  The grids are safe for any data of
+ * that shape; where blocks touch few of their strips' columns, coarser grid_c may run faster (see
+ * mf_sgd_epoch on packed strips; mf_epoch_plan tells what a grid gets).  All outputs are HOST
+ * pointers. */
 int mf_suggest_grid(int64_t m, int64_t n, int64_t nnz, int32_t k, int32_t mode,
                     int32_t* grid_r_out, int32_t* grid_c_out, int32_t* split_out);
 

@@ -467,6 +467,17 @@ __device__ __forceinline__ RowRing<RowShape<T, K>::VEC, DEPTH> request_first_row
     return ring;
 }
 
+// Where the columns of a batch of ratings sit in the strip: lane l's column index becomes the
+// index of that column's K values in LDS.  The strip holds either all columns of its range
+// (slot = column - col0) or only the touched ones, packed (slots: one 16-bit entry per column of
+// the range, written for the touched columns when the block began).
+template <bool SPARSE>
+__device__ __forceinline__ int strip_slots(int mv, int col0, const unsigned short* slots, bool valid)
+{
+    if constexpr (SPARSE) return valid ? (int)slots[mv - col0] : 0;
+    else return mv - col0;
+}
+
 // A chunk whose rows of P belong to this wavefront alone.  Rows of P are cold (each is visited by
 // one wavefront per launch), so their latency is hidden by requesting the row of the rating DEPTH
 // positions ahead; every rating issues the same memory operations (one row request, one row
@@ -476,8 +487,8 @@ __device__ __forceinline__ RowRing<RowShape<T, K>::VEC, DEPTH> request_first_row
 // last rating with a zero step, which changes nothing.
 // EXACT (deterministic mode, the wavefront is alone in its workgroup): the strip holds fp32, q_v
 // is read and written in program order, every operation is the sequential order's.
-template <typename T, int K, int DEPTH, bool EXACT>
-__device__ __forceinline__ void lds_owned_chunk(T* __restrict__ P, int* strip, int col0,
+template <typename T, int K, int DEPTH, bool EXACT, bool SPARSE>
+__device__ __forceinline__ void lds_owned_chunk(T* __restrict__ P, int* strip, int col0, const unsigned short* slots,
                                                 const int32_t* __restrict__ U,
                                                 const int32_t* __restrict__ V,
                                                 const float* __restrict__ R, int64_t begin,
@@ -488,6 +499,7 @@ __device__ __forceinline__ void lds_owned_chunk(T* __restrict__ P, int* strip, i
     // mu, mv, mr: the first batch of the chunk (rating `lane` of it), already loaded by the caller;
     // first_rows: the rows of P of its first DEPTH ratings, already requested by the caller
     constexpr int VEC = RowShape<T, K>::VEC;
+    mv = strip_slots<SPARSE>(mv, col0, slots, lane < min(kWave, len));   // from here on: slots, not columns
     Row<VEC> p_prev;
 #pragma unroll
     for (int j = 0; j < VEC; ++j) p_prev.x[j] = 0.f;
@@ -513,7 +525,7 @@ __device__ __forceinline__ void lds_owned_chunk(T* __restrict__ P, int* strip, i
                 ring[d] = load_row<VEC, false>(P + (int64_t)uniform_lane(mu, min(d, last)) * K, lane, active);
         }
         int v_next = uniform_lane(mv, 0);
-        Row<VEC> q_next = strip_read<T, VEC, EXACT>(strip + (v_next - col0) * K, lane, active);
+        Row<VEC> q_next = strip_read<T, VEC, EXACT>(strip + v_next * K, lane, active);
         for (int base = 0; base < cnt; base += DEPTH) {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
@@ -528,9 +540,9 @@ __device__ __forceinline__ void lds_owned_chunk(T* __restrict__ P, int* strip, i
                 for (int j = 0; j < VEC; ++j) p.x[j] = (u == u_prev) ? p_prev.x[j] : ring[d].x[j];
                 ring[d] = load_row<VEC, false>(P + (int64_t)uniform_lane(mu, min(i + DEPTH, last)) * K, lane, active);
                 const Row<VEC> q = q_next;
-                int* const qrow = strip + (v - col0) * K;
+                int* const qrow = strip + v * K;
                 v_next = uniform_lane(mv, min(i + 1, last));
-                const Row<VEC> q_ahead = strip_read<T, VEC, EXACT>(strip + (v_next - col0) * K, lane, active);
+                const Row<VEC> q_ahead = strip_read<T, VEC, EXACT>(strip + v_next * K, lane, active);
                 float e;
                 if constexpr (EXACT && sizeof(T) == 2) {
                     double part = 0.0;   // see sgd_chunks: the binary16 result must not depend on summation order
@@ -566,7 +578,7 @@ __device__ __forceinline__ void lds_owned_chunk(T* __restrict__ P, int* strip, i
             }
         }
         mu = nu;
-        mv = nv;
+        mv = strip_slots<SPARSE>(nv, col0, slots, lane < len - off - kWave);
         mr = nr;
     }
 }
@@ -594,17 +606,6 @@ __device__ __forceinline__ float wave_sum_fused(float x)
     asm("s_nop 1\n\tv_add_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf" : "+v"(x));
     asm("s_nop 1\n\tv_add_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf" : "+v"(x));
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
-}
-
-// Where the columns of a batch of ratings sit in the strip: lane l's column index becomes the
-// index of that column's K values in LDS.  The strip holds either all columns of its range
-// (slot = column - col0) or only the touched ones, packed (slots: one 16-bit entry per column of
-// the range, written for the touched columns when the block began).
-template <bool SPARSE>
-__device__ __forceinline__ int strip_slots(int mv, int col0, const unsigned short* slots, bool valid)
-{
-    if constexpr (SPARSE) return valid ? (int)slots[mv - col0] : 0;
-    else return mv - col0;
 }
 
 template <typename T, int K, int DEPTH, bool SPARSE>
@@ -853,6 +854,41 @@ struct StripMap {
     int piece_slot;
     int first_slot;
     int n_slots;
+    unsigned mask;    // lane l: bit word l of the block's table
+};
+
+// The touched columns of a strip one after the other, in ascending order (wave-uniform; for the
+// one-wavefront workgroups of the deterministic form, which move a strip column by column).
+struct TouchedColumns {
+    unsigned mask;    // lane l: bit word l
+    int n_words;
+    int word;
+    unsigned bits;
+    __device__ __forceinline__ TouchedColumns(unsigned mask_, int ncols) : mask(mask_), n_words((ncols + 31) >> 5), word(0)
+    {
+        bits = n_words > 0 ? (unsigned)uniform_lane((int)mask, 0) : 0u;
+    }
+    __device__ __forceinline__ int next()   // the next touched column (offset in the strip's range), or -1
+    {
+        while (bits == 0u && word + 1 < n_words) {
+            word += 1;
+            bits = (unsigned)uniform_lane((int)mask, word);
+        }
+        if (bits == 0u) return -1;
+        const int bit = __builtin_ctz(bits);
+        bits &= bits - 1u;
+        return 32 * word + bit;
+    }
+};
+
+// How the one wavefront of a deterministic workgroup holds a column of K values in memory: lane l
+// has kWords consecutive 32-bit words from word l * kWords on; lanes >= kLanes are idle.
+template <typename T, int K>
+struct ColumnShape {
+    static constexpr int kColumnWords = K * (int)sizeof(T) / 4;
+    static constexpr int kWords = kColumnWords >= kWave ? kColumnWords / kWave : 1;
+    static constexpr int kLanes = kColumnWords / kWords;
+    static constexpr int kPerWord = sizeof(T) == 2 ? 2 : 1;    // values per word
 };
 
 template <typename T, int K>
@@ -867,6 +903,7 @@ __device__ __forceinline__ StripMap map_strip(int ncols, unsigned mask_word)
         const int below = __shfl_up(upto, d, kWave);
         if (lane >= d) upto += below;
     }
+    m.mask = mask_word;
     m.first_slot = upto - mine;
     m.n_slots = uniform_lane(upto, kWave - 1);
     const int words = ncols * SparseStrip<T, K>::kWordsPerColumn;
@@ -903,7 +940,50 @@ __device__ __forceinline__ void strip_copy_in(int* strip, const T* __restrict__ 
     const int total = ncols * K;          // multiple of 32
     const T* const strip_src = Qt + (int64_t)col0 * K;
     const int stride = 4 * (int)blockDim.x;
-    if constexpr (!EXACT && SPARSE) {
+    if constexpr (EXACT && SPARSE) {
+        // one wavefront: the touched columns one after the other into consecutive slots, eight
+        // columns requested, then stored
+        using Shape = ColumnShape<T, K>;
+        const int lane = threadIdx.x & (kWave - 1);
+        const unsigned* src = reinterpret_cast<const unsigned*>(strip_src);
+        constexpr int kInFlight = 8;
+        TouchedColumns columns(map.mask, ncols);
+        int slot = 0;
+        for (;;) {
+            int col[kInFlight];
+            int n = 0;
+#pragma unroll
+            for (int t = 0; t < kInFlight; ++t) {
+                col[t] = columns.next();
+                if (col[t] >= 0) n = t + 1;
+            }
+            if (n == 0) break;
+            unsigned raw[kInFlight][Shape::kWords];
+#pragma unroll
+            for (int t = 0; t < kInFlight; ++t)
+                if (t < n && lane < Shape::kLanes) {
+#pragma unroll
+                    for (int j = 0; j < Shape::kWords; ++j)
+                        raw[t][j] = load_word<COHERENT>(src + col[t] * Shape::kColumnWords + lane * Shape::kWords + j);
+                }
+#pragma unroll
+            for (int t = 0; t < kInFlight; ++t)
+                if (t < n && lane < Shape::kLanes) {
+#pragma unroll
+                    for (int j = 0; j < Shape::kWords; ++j) {
+                        int* at = strip + (slot + t) * K + (lane * Shape::kWords + j) * Shape::kPerWord;
+                        if constexpr (sizeof(T) == 2) {
+                            const float2 f = unpack_half2(raw[t][j]);
+                            at[0] = to_strip<EXACT>(f.x, worst);
+                            at[1] = to_strip<EXACT>(f.y, worst);
+                        } else {
+                            at[0] = to_strip<EXACT>(__uint_as_float(raw[t][j]), worst);
+                        }
+                    }
+                }
+            slot += n;
+        }
+    } else if constexpr (!EXACT && SPARSE) {
         // the touched columns only, into their slots: up to 16 pieces requested, then converted
         constexpr int kPerWord = sizeof(T) == 2 ? 2 : 1;
         constexpr int kInColumn = SparseStrip<T, K>::kWordsPerColumn - 1;
@@ -1041,7 +1121,32 @@ __device__ __forceinline__ void strip_copy_out(const int* strip, T* __restrict__
     const int total = ncols * K;
     T* const strip_dst = Qt + (int64_t)col0 * K;
     const int stride = 4 * (int)blockDim.x;
-    if constexpr (!EXACT && SPARSE) {
+    if constexpr (EXACT && SPARSE) {
+        using Shape = ColumnShape<T, K>;
+        const int lane = threadIdx.x & (kWave - 1);
+        unsigned* dst = reinterpret_cast<unsigned*>(strip_dst);
+        TouchedColumns columns(map.mask, ncols);
+        int slot = 0;
+        for (int col = columns.next(); col >= 0; col = columns.next(), ++slot) {
+            if (lane < Shape::kLanes) {
+#pragma unroll
+                for (int j = 0; j < Shape::kWords; ++j) {
+                    const int* at = strip + slot * K + (lane * Shape::kWords + j) * Shape::kPerWord;
+                    unsigned raw;
+                    if constexpr (sizeof(T) == 2) {
+                        __half2 h = __halves2half2(round_to_half(from_strip<EXACT>(at[0], worst)),
+                                                   round_to_half(from_strip<EXACT>(at[1], worst)));
+                        raw = *reinterpret_cast<unsigned*>(&h);
+                    } else {
+                        raw = __float_as_uint(from_strip<EXACT>(at[0], worst));
+                    }
+                    unsigned* to = dst + col * Shape::kColumnWords + lane * Shape::kWords + j;
+                    if constexpr (COHERENT) __hip_atomic_store(to, raw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    else *to = raw;
+                }
+            }
+        }
+    } else if constexpr (!EXACT && SPARSE) {
         constexpr int kPerWord = sizeof(T) == 2 ? 2 : 1;
         constexpr int kInColumn = SparseStrip<T, K>::kWordsPerColumn - 1;
         unsigned* dst = reinterpret_cast<unsigned*>(strip_dst);
@@ -1209,8 +1314,8 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
         }
         const int32_t len = raw_len & ~kSharedRowFlag;
         if constexpr (EXACT) {
-            lds_owned_chunk<T, K, DEPTH, true>(P, strip, blk.col0, U, V, R, begin, len, mu, mv, mr,
-                                                           first_rows, lr, shrink, lane, active);
+            lds_owned_chunk<T, K, DEPTH, true, SPARSE>(P, strip, blk.col0, slots, U, V, R, begin, len, mu, mv, mr,
+                                                       first_rows, lr, shrink, lane, active);
         } else {
             if (raw_len < 0) {
                 // a piece of a cut row at the front and / or at the back, whole rows between them
@@ -1624,6 +1729,10 @@ hipError_t launch_sgd_ring_t(bool exact, bool short_prefetch, int waves, bool qu
                              long long spin_limit, const int32_t* order, const int32_t* pos, const uint32_t* touched,
                              int touched_words, int slot_table_at, hipStream_t stream)
 {
+    if (exact && touched)
+        return launch_sgd_ring_impl<T, K, true, kDetPrefetchDepth, true>(
+            1, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done,
+            first, abort_flag, spin_limit, order, pos, touched, touched_words, slot_table_at, stream);
     if (exact)
         return launch_sgd_ring_impl<T, K, true, kDetPrefetchDepth, false>(
             1, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done,
@@ -1656,6 +1765,10 @@ hipError_t launch_sgd_lds_t(bool exact, bool short_prefetch, int waves, void* P,
                             float lambda, int* range_flag, const uint32_t* touched, int touched_words, int slot_table_at,
                             hipStream_t stream)
 {
+    if (exact && touched)
+        return launch_sgd_lds_impl<T, K, true, kDetPrefetchDepth, true>(1, P, Qt, U, V, R, eb, el, hot, blocks, n_blocks,
+                                                                        lds_bytes, lr, lambda, range_flag, touched,
+                                                                        touched_words, slot_table_at, stream);
     if (exact)
         return launch_sgd_lds_impl<T, K, true, kDetPrefetchDepth, false>(1, P, Qt, U, V, R, eb, el, hot, blocks, n_blocks,
                                                                          lds_bytes, lr, lambda, range_flag, nullptr, 0, 0,

@@ -32,7 +32,9 @@ struct mf_ctx {
     void* dQt = nullptr;
 
     double touched_share = 1.0;   // touched columns / strip columns over the blocks of the last load
-    int32_t max_slots = 0;        // most touched columns of any block (when the strips are packed)
+    int32_t max_slots = 0;        // most touched columns of any block (when the table was made)
+    uint32_t* touched = nullptr;  // the table of touched columns of the last load (null: not made)
+    int32_t touched_words = 0;
     // partition and schedules
     bool loaded = false;
     mf::Partition part;
@@ -425,17 +427,19 @@ int make_touched_table(mf_ctx* ctx, const Layout& lay, char* base)
     ctx->det_lds.touched_words = 0;
     ctx->touched_share = 1.0;
     ctx->max_slots = 0;
+    ctx->touched = nullptr;
+    ctx->touched_words = 0;
     const mf::Partition& part = ctx->part;
     const int32_t widest = mf::widest_strip(part);
     const int32_t words = (widest + 31) / 32;
-    // a wavefront's 64 consecutive words of a strip have to lie in one column, and its 64 piece
-    // bits have to cover the widest strip
+    if (!ctx->pack_strips || ctx->streamed || !ctx->dV || part.nnz == 0 || words < 1 || words > lay.touched_words)
+        return MF_OK;
+    // Hogwild form: a wavefront's 64 consecutive words of a strip have to lie in one column, and
+    // its 64 piece bits have to cover the widest strip (the deterministic form moves a strip
+    // column by column and has no such limits)
     const int64_t words_per_column = (int64_t)ctx->k * (ctx->dtype == MF_F16 ? 2 : 4) / 4;
     const bool shape_ok = words_per_column % 64 == 0 &&
                           (int64_t)widest * words_per_column <= (int64_t)64 * 64 * ctx->lds_waves_used;
-    if (!ctx->pack_strips || ctx->streamed || !ctx->dV || part.nnz == 0 || words < 1 || words > lay.touched_words ||
-        !shape_ok)
-        return MF_OK;
     std::vector<mf::LdsBlock> ranges;
     for (int32_t st = 0; st < part.gc; ++st)
         for (int32_t a = 0; a < part.gr; ++a) {
@@ -459,16 +463,18 @@ int make_touched_table(mf_ctx* ctx, const Layout& lay, char* base)
     unsigned long long sums[3] = {0, 0, 0};
     MF_HIP(ctx, hipMemcpy(sums, totals, sizeof(sums), hipMemcpyDeviceToHost));
     if (sums[1] > 0) ctx->touched_share = (double)sums[0] / (double)sums[1];
+    ctx->touched = table;
+    ctx->touched_words = words;
+    ctx->max_slots = (int32_t)sums[2];
     // Packing costs a little on every step (the map of a strip, a table look-up per 64 ratings),
     // which pays when a good part of the columns can be left out (measured: a gain of 8-10 % with
     // 45 % of the columns touched, a loss of 7 % with nearly all touched) -- and is the only way
     // when the whole strip does not fit.
     const size_t dense = mf::lds_strip_bytes(ctx->k, widest);
     const size_t packed = mf::lds_strip_bytes(ctx->k, (int32_t)sums[2]) + (size_t)words * 64;
-    if (packed <= mf::kLdsBudget && (ctx->touched_share <= kSparseStripShare || dense > mf::kLdsBudget)) {
+    if (shape_ok && packed <= mf::kLdsBudget && (ctx->touched_share <= kSparseStripShare || dense > mf::kLdsBudget)) {
         ctx->lds.d_touched = table;
         ctx->lds.touched_words = words;
-        ctx->max_slots = (int32_t)sums[2];
     }
     return MF_OK;
 }
@@ -733,8 +739,10 @@ struct EpochPlan {
     int32_t waves = 1;             // wavefronts per workgroup
     int32_t kernel = 0;            // MF_KERNEL_ID_*
     int64_t launches = 0;          // per epoch
-    bool packed = false;           // Hogwild LDS kernels with only the touched columns of a strip in LDS
+    bool packed = false;           // LDS kernels with only the touched columns of a strip in LDS
     int32_t slot_table_at = 0;     // packed: where the kernel's column table begins in LDS (32-bit words)
+    const uint32_t* touched = nullptr;   // packed: the table of touched columns
+    int32_t touched_words = 0;
     std::string note;
 };
 
@@ -752,24 +760,37 @@ int plan_epoch(mf_ctx* ctx, int32_t mode, EpochPlan& p)
     const size_t dense_bytes = mf::lds_strip_bytes(ctx->k, lsched.max_cols) + (size_t)lsched.max_hot * ctx->k * 4;
     const int32_t choice = p.hog ? ctx->hogwild_kernel : ctx->det_kernel;
     // the deterministic form runs one wavefront per workgroup: its strips may take the share of a
-    // compute unit's LDS that lets all grid_r workgroups be resident (at most four per unit)
-    const int64_t per_unit =
-        std::min<int64_t>(4, std::max<int64_t>(1, (ctx->part.gr + ctx->compute_units - 1) / ctx->compute_units));
-    const size_t budget = p.hog || choice == MF_KERNEL_LDS ? mf::kLdsBudget : mf::kLdsBudget / (size_t)per_unit;
+    // compute unit's LDS that lets all grid_r workgroups be resident -- 1, 2, 4, 8 or 16 per unit
+    // (shares that divide the LDS evenly; allocations are rounded up to 2 KiB, and a one-launch
+    // epoch whose workgroups do not all fit can only give up)
+    int64_t per_unit = 1;
+    while (per_unit < 16 && per_unit * ctx->compute_units < ctx->part.gr) per_unit *= 2;
+    const size_t det_budget = (((size_t)160 * 1024 / (size_t)per_unit) & ~(size_t)2047) - 1024;
+    const size_t budget = p.hog || choice == MF_KERNEL_LDS ? mf::kLdsBudget : std::min(mf::kLdsBudget, det_budget);
     const bool ring_allowed = ctx->use_ring && !ctx->ring_gave_up && ctx->part.nnz > 0 && !ctx->streamed;
-    // packed strips: Hogwild LDS kernels, when the load made the table of touched columns
+    // packed strips, when the load made the table of touched columns: the Hogwild form as the load
+    // decided (its work list was made for that room); the deterministic form when packing pays
+    // or whole strips do not fit
+    p.touched = p.hog ? lsched.d_touched : ctx->touched;
+    p.touched_words = p.hog ? lsched.touched_words : ctx->touched_words;
     p.slot_table_at = (ctx->max_slots + lsched.max_hot) * ctx->k;
-    const size_t packed_bytes = (size_t)p.slot_table_at * 4 + (size_t)lsched.touched_words * 64;
-    p.packed = p.hog && lsched.d_touched && choice != MF_KERNEL_GLOBAL && packed_bytes <= budget;
+    const size_t packed_bytes = (size_t)p.slot_table_at * 4 + (size_t)p.touched_words * 64;
+    p.packed = p.touched && choice != MF_KERNEL_GLOBAL && packed_bytes <= budget &&
+               (p.hog || ctx->touched_share <= kSparseStripShare || dense_bytes > budget);
     p.lds_bytes = p.packed ? packed_bytes : dense_bytes;
     p.use_lds = choice != MF_KERNEL_GLOBAL && p.lds_bytes <= budget;
     if (!p.use_lds && choice == MF_KERNEL_LDS)
         return fail(ctx, MF_EINVAL, "the widest column strip of this grid does not fit the LDS");
     p.waves = p.use_lds ? (p.hog ? ctx->lds_waves_used : 1) : mf::kWavesPerGroup;
     std::string why;
-    if (!p.use_lds && choice != MF_KERNEL_GLOBAL)
-        why = "the widest column strip (" + std::to_string(lsched.max_cols) + " columns, " + std::to_string(p.lds_bytes) +
-              " bytes) exceeds the " + std::to_string(budget) + " bytes of LDS this mode uses per workgroup; ";
+    if (!p.use_lds && choice != MF_KERNEL_GLOBAL) {
+        why = "the widest column strip (" + std::to_string(lsched.max_cols) + " columns, " + std::to_string(dense_bytes) +
+              " bytes) exceeds the " + std::to_string(budget) + " bytes of LDS this mode uses per workgroup";
+        if (p.touched)
+            why += ", and so do the " + std::to_string(ctx->max_slots) + " columns (" + std::to_string(packed_bytes) +
+                   " bytes) that the block with the most touched columns would keep";
+        why += "; ";
+    }
     if (p.use_lds && ring_allowed) {
         // one launch for the whole epoch if every block row's workgroup can be resident at once
         const int m_idx = p.hog ? 1 : 0;
@@ -881,8 +902,8 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
                                         ctx->part.gr, ctx->part.gc, lds_bytes, lr, lambda, ctx->d_ring_done,
                                         ctx->ring_epochs * ctx->part.gc, d_flags,
                                         (long long)ctx->spin_limit, stratum_order ? ctx->d_order : nullptr,
-                                        stratum_order ? ctx->d_order + gc : nullptr, plan.packed ? lsched.d_touched : nullptr,
-                                        lsched.touched_words, plan.slot_table_at, ctx->stream));
+                                        stratum_order ? ctx->d_order + gc : nullptr, plan.packed ? plan.touched : nullptr,
+                                        plan.touched_words, plan.slot_table_at, ctx->stream));
         if (ev1) MF_HIP(ctx, hipEventRecord(ev1, ctx->stream));
         ctx->ring_epochs += 1;
         return MF_OK;
@@ -964,8 +985,8 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
         if (count > 0 && use_lds)
             MF_HIP(ctx, mf::launch_sgd_lds(ctx->dtype, ctx->k, !hog, short_prefetch, ctx->lds_waves_used, ctx->dP, ctx->dQt, U, V,
                                            R, lsched.d_begin, lsched.d_len, lsched.d_hot, lsched.d_blocks + first, count, lds_bytes,
-                                           lr, lambda, d_flags + 1, plan.packed ? lsched.d_touched : nullptr,
-                                           lsched.touched_words, plan.slot_table_at, ctx->stream));
+                                           lr, lambda, d_flags + 1, plan.packed ? plan.touched : nullptr,
+                                           plan.touched_words, plan.slot_table_at, ctx->stream));
         else if (count > 0)
             MF_HIP(ctx, mf::launch_sgd(ctx->dtype, ctx->k, mode == MF_MODE_HOGWILD, ctx->dP, ctx->dQt, U, V, R,
                                        s.d_begin, s.d_len, first, count, lr, lambda, ctx->stream));
@@ -1087,15 +1108,19 @@ int mf_suggest_grid(int64_t m, int64_t n, int64_t nnz, int32_t k, int32_t mode, 
     if (m < 1 || n < 1 || nnz < 0 || !valid_k(k) || !grid_r_out || !grid_c_out || !split_out) return MF_EINVAL;
     if (mode != MF_MODE_DET && mode != MF_MODE_HOGWILD) return MF_EINVAL;
     const bool hog = mode == MF_MODE_HOGWILD;
-    const int64_t lds = hog ? (int64_t)mf::kLdsBudget : (int64_t)mf::kLdsBudget / 4;
+    // few enough blocks for ~64 (Hogwild) / ~40 (deterministic) ratings in each; the deterministic
+    // form, one wavefront per workgroup, wants many block rows (measured on 99 M ratings: 1.65 G
+    // updates/s with 512, 2.10 G with 1024, no more with 2048)
+    const double per_block = hog ? 64.0 : 40.0;
+    int64_t g = (int64_t)std::floor(std::sqrt((double)std::max<int64_t>(nnz, 1) / per_block));
+    g = std::min<int64_t>(g, hog ? 224 : 1024);
+    g = std::max<int64_t>(g, 1);
+    // LDS of a strip: all of a compute unit's for Hogwild; for the deterministic form the share that
+    // lets g workgroups be resident on 256 compute units (half above 256 block rows, a quarter above 512)
+    const int64_t lds = hog || g <= 256 ? (int64_t)mf::kLdsBudget : (g <= 512 ? 80 * 1024 - 1024 : 40 * 1024 - 1024);
     const int64_t strip_cols = std::max<int64_t>(1, lds / ((int64_t)k * 4));   // columns one strip may hold
     // enough column strips for the widest one (at most about 2*n/grid_c columns) to fit
     const int64_t gc_for_lds = (2 * n + strip_cols - 1) / strip_cols;
-    // few enough blocks for ~64 (Hogwild) / ~40 (deterministic) ratings in each
-    const double per_block = hog ? 64.0 : 40.0;
-    int64_t g = (int64_t)std::floor(std::sqrt((double)std::max<int64_t>(nnz, 1) / per_block));
-    g = std::min<int64_t>(g, hog ? 224 : 512);
-    g = std::max<int64_t>(g, 1);
     int64_t gr = std::min<int64_t>(g, m);
     int64_t gc = std::min<int64_t>(std::max<int64_t>(g, gc_for_lds), n);
     gr = std::min(gr, gc);

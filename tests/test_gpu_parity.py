@@ -795,6 +795,55 @@ def test_packed_strips_with_sixteen_wavefronts_visit_every_rating_once(mfmod, ri
     assert moved > 5e-6 and dp <= 6e-7 and dq <= 1.2e-6, (moved, dp, dq)
 
 
+@pytest.mark.parametrize("storage,k,grid", [("f32", 128, (8, 32)), ("f32", 32, (8, 16)), ("f32", 64, (16, 20)),
+                                             ("f16", 128, (8, 32)), ("f16", 64, (8, 13)), ("f32", 256, (8, 63))])
+def test_deterministic_mode_with_packed_strips_gives_the_same_bits(mfmod, storage, k, grid):
+    """The deterministic LDS kernels keep only the touched columns of a strip in LDS too when few
+    are touched (they move a strip column by column).  Packing changes where a column sits in LDS
+    and nothing else: one launch per epoch and one launch per stratum with packed strips, the
+    same with whole strips (MF_OPT_PACK_STRIPS = 0) and the kernel on Qt in memory must agree bit
+    for bit, over three epochs (two of them with shuffled strata), and match the oracle."""
+    ds = dataset("tiny")
+    take = 5600
+    rows, cols, vals = ds.rows[:take].copy(), ds.cols[:take].copy(), ds.vals[:take].copy()
+    gr, gc = grid
+    outs = []
+    for kernel, ring, pack in (("lds", 1, 1), ("lds", 0, 1), ("lds", 1, 0), ("global", 0, 1)):
+        which = mfmod.MF_KERNEL_LDS if kernel == "lds" else mfmod.MF_KERNEL_GLOBAL
+        model = mfmod.MatrixFactorization(ds.cfg.m, ds.cfg.n, k, storage, seed=3, scale=0.1,
+                                          options={mfmod.MF_OPT_DET_KERNEL: which, mfmod.MF_OPT_RING: ring,
+                                                   mfmod.MF_OPT_PACK_STRIPS: pack})
+        model.load_blocks(rows, cols, vals, gr, gc, 0)
+        plan = model.epoch_plan(mfmod.MF_MODE_DET)
+        if kernel == "lds":
+            assert plan["kernel"] == ("sgd_ring_lds" if ring else "sgd_block_lds"), plan
+            assert ("touched columns" in plan["note"]) == bool(pack), plan
+        else:
+            assert plan["kernel"] == "sgd_chunks", plan
+        for epoch in range(3):
+            order = oracle.stratum_order(5, epoch, gc) if epoch else None
+            model.sgd_epoch(0.01, 0.05, mfmod.MF_MODE_DET, stratum_order=order)
+        model.sync()
+        outs.append(model.get_factors())
+        model.close()
+    for other in outs[1:]:
+        assert np.array_equal(outs[0][0], other[0]) and np.array_equal(outs[0][1], other[1])
+    arith = oracle.ARITH_F64 if storage == "f32" else oracle.ARITH_F16
+    perm, bp, _, _ = oracle.partition(rows, cols, ds.cfg.m, ds.cfg.n, gr, gc, 0)
+    Po, Qo = oracle_init(ds.cfg.m, ds.cfg.n, k, 3, 0.1, arith)
+    for epoch in range(3):
+        if epoch:
+            oracle.sgd_epoch_ordered(Po, Qo, rows, cols, vals, perm, bp, gr, gc, 0.01, 0.05,
+                                     oracle.stratum_order(5, epoch, gc), arith)
+        else:
+            oracle.sgd_epoch(Po, Qo, rows, cols, vals, perm, bp, gr, gc, 0.01, 0.05, arith)
+    if storage == "f32":
+        assert np.abs(outs[0][0] - Po).max() <= 1e-4 and np.abs(outs[0][1] - Qo).max() <= 1e-4
+    else:
+        differing = int((outs[0][0] != Po).sum() + (outs[0][1] != Qo).sum())
+        assert differing <= max(1, int(1e-5 * (Po.size + Qo.size))), differing
+
+
 def test_lds_kernel_is_refused_when_the_strip_does_not_fit(mfmod):
     ds = dataset("tiny")
     model = _make(mfmod, ds, 256, "f32", 2, 2, 0, options={mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS})
