@@ -219,6 +219,7 @@ def main():
     ap.add_argument("--split", type=int, default=None,
                     help="0 equal width, 1 ratings balanced, 2 ratings and width balanced; default: the workload's")
     ap.add_argument("--ring", type=int, default=1, help="1: one launch per epoch (workgroups hand the strips round)")
+    ap.add_argument("--pack-strips", type=int, default=1, help="0: the LDS kernels always keep whole strips; 2: packed strips wherever possible")
     ap.add_argument("--load", default="device", choices=["host", "device"],
                     help="partition on the host (mf_load_blocks) or on the GPU (mf_load_blocks_device); outside the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -277,7 +278,7 @@ def main():
              "lds": mf.MF_HOGWILD_LDS}[args.hogwild_kernel]
     opts = {mf.MF_OPT_HOGWILD_CHUNK: args.chunk, mf.MF_OPT_XCD_AFFINITY: args.affinity,
             mf.MF_OPT_HOGWILD_KERNEL: which,
-            mf.MF_OPT_LDS_CHUNK: args.lds_chunk, mf.MF_OPT_RING: args.ring}
+            mf.MF_OPT_LDS_CHUNK: args.lds_chunk, mf.MF_OPT_RING: args.ring, mf.MF_OPT_PACK_STRIPS: args.pack_strips}
     if args.lds_waves:
         opts[mf.MF_OPT_LDS_WAVES] = args.lds_waves
     model = mf.MatrixFactorization(cfg.m, cfg.n, k, cfg.storage, seed=1, scale=args.init_scale, options=opts)
@@ -347,7 +348,7 @@ def main():
         key = (f"workload={args.workload} scale={args.scale:g} mode={args.mode} grid={args.grid} split={args.split} "
                f"kernel={plan['kernel']} waves={plan['waves']}")
         traffic, source = profiled_traffic(key)
-        if args.lds_chunk != 0 or args.chunk != 0 or not args.affinity:
+        if args.lds_chunk != 0 or args.chunk != 0 or not args.affinity or args.pack_strips != 1:
             traffic, source = None, None
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
@@ -371,6 +372,7 @@ def main():
                       "mode": args.mode, "grid": args.grid, "split": args.split, "init_scale": args.init_scale,
                       "hogwild_kernel": args.hogwild_kernel,
                       "lds_chunk": args.lds_chunk, "lds_waves": args.lds_waves, "ring": args.ring,
+                      "pack_strips": args.pack_strips,
                       "chunk": args.chunk,
                       "xcd_affinity": args.affinity,
                       "lr": cfg.lr, "lambda": cfg.lam},

@@ -73,9 +73,10 @@ enum {
     MF_OPT_RING_SPIN_LIMIT = 9,   /* polls after which a waiting workgroup gives up (default 2^22)    */
     MF_OPT_LDS_PREFETCH = 10,     /* MF_MODE_HOGWILD, LDS kernels: rows of P requested 4 or 8 ratings */
                                   /* ahead; 0 (default): 4 if P takes at most 64 MiB, else 8          */
-    MF_OPT_PACK_STRIPS = 12,      /* read by mf_load_blocks(_device): 1 (default) = the Hogwild LDS    */
-                                  /* kernels may keep only the touched columns of a strip in LDS     */
-                                  /* (see mf_sgd_epoch); 0 = always whole strips                     */
+    MF_OPT_PACK_STRIPS = 12,      /* read by mf_load_blocks(_device): 1 (default) = the LDS kernels   */
+                                  /* keep only the touched columns of a strip in LDS where that pays  */
+                                  /* or whole strips do not fit (see mf_sgd_epoch); 2 = wherever the  */
+                                  /* packed form is possible; 0 = always whole strips                 */
     MF_OPT_ROW_ORDER_SEED = 11    /* read by mf_load_blocks(_device): 0 (default) = the rows of a     */
                                   /* block in ascending order; else they are visited in a seeded      */
                                   /* order (the paper's scheduler visits "randomly", Section 3.1):    */

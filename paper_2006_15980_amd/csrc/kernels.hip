@@ -21,6 +21,8 @@
 // This is a gather / dot / scatter over rows of 128..1024 bytes with about half a flop per byte:
 // there is no MFMA here; the lanes hold rows in registers, consecutive ratings of one matrix row
 // reuse p_u from registers, and the rows of later ratings are requested ahead of their use.
+#include <algorithm>
+
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
@@ -1608,37 +1610,41 @@ __global__ __launch_bounds__(kGroupThreads) void init_fill(T* __restrict__ X, in
 // is made for this kernel: first_entry = the block's first packed position, n_entries = its number
 // of ratings (not work-list entries).  totals[0] += touched columns of the block, totals[1] +=
 // columns of its strip, totals[2] = the most touched columns of any block.
-__global__ __launch_bounds__(kGroupThreads) void mark_touched(const LdsBlock* __restrict__ blocks,
+__global__ __launch_bounds__(kGroupThreads) void mark_touched(const LdsBlock* __restrict__ blocks, int64_t n_blocks,
                                                               const int32_t* __restrict__ V, uint32_t* __restrict__ touched,
                                                               int words, unsigned long long* totals)
 {
     __shared__ unsigned bits[kMaxTouchedWords];
-    const LdsBlock blk = blocks[blockIdx.x];
-    if ((int)threadIdx.x < kMaxTouchedWords) bits[threadIdx.x] = 0u;
-    __syncthreads();
-    const int64_t begin = blk.first_entry, end = begin + blk.n_entries;
-    for (int64_t i = begin + (int64_t)threadIdx.x; i < end; i += (int64_t)blockDim.x) {
-        const int c = V[i] - blk.col0;
-        if (c >= 0 && c < 32 * words) atomicOr(&bits[c >> 5], 1u << (c & 31));
-    }
-    __syncthreads();
-    if ((int)threadIdx.x < words) touched[(int64_t)blk.id * words + threadIdx.x] = bits[threadIdx.x];
-    if (threadIdx.x < kWave) {
-        int set = (int)threadIdx.x < words ? __popc(bits[threadIdx.x]) : 0;   // words <= 64 = one wavefront
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) set += __shfl_xor(set, d, kWave);
-        if (threadIdx.x == 0) {
-            atomicAdd(&totals[0], (unsigned long long)set);
-            atomicAdd(&totals[1], (unsigned long long)blk.ncols);
-            atomicMax(&totals[2], (unsigned long long)set);
+    // a workgroup takes every gridDim.x-th block of the list (a grid may have billions of blocks)
+    for (int64_t at = blockIdx.x; at < n_blocks; at += gridDim.x) {
+        const LdsBlock blk = blocks[at];
+        if ((int)threadIdx.x < kMaxTouchedWords) bits[threadIdx.x] = 0u;
+        __syncthreads();
+        const int64_t begin = blk.first_entry, end = begin + blk.n_entries;
+        for (int64_t i = begin + (int64_t)threadIdx.x; i < end; i += (int64_t)blockDim.x) {
+            const int c = V[i] - blk.col0;
+            if (c >= 0 && c < 32 * words) atomicOr(&bits[c >> 5], 1u << (c & 31));
         }
+        __syncthreads();
+        if ((int)threadIdx.x < words) touched[(int64_t)blk.id * words + threadIdx.x] = bits[threadIdx.x];
+        if (threadIdx.x < kWave) {
+            int set = (int)threadIdx.x < words ? __popc(bits[threadIdx.x]) : 0;   // words <= 64 = one wavefront
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) set += __shfl_xor(set, d, kWave);
+            if (threadIdx.x == 0) {
+                atomicAdd(&totals[0], (unsigned long long)set);
+                atomicAdd(&totals[1], (unsigned long long)blk.ncols);
+                atomicMax(&totals[2], (unsigned long long)set);
+            }
+        }
+        __syncthreads();   // before the bits are cleared for the next block
     }
 }
 
 __global__ void fill_i32(int32_t* out, int64_t count, int32_t value)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < count) out[i] = value;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) out[i] = value;
 }
 
 __global__ void xcc_probe(int32_t* out)
@@ -1879,7 +1885,9 @@ hipError_t launch_mark_touched(const LdsBlock* blocks, int64_t n_blocks, const i
 {
     if (n_blocks <= 0) return hipSuccess;
     if (words < 1 || words > kMaxTouchedWords) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(mark_touched, dim3((unsigned)n_blocks), dim3(kGroupThreads), 0, stream, blocks, V, touched, words,
+    // a launch holds fewer than 2^32 threads in a dimension: workgroups loop over the list
+    const unsigned groups = (unsigned)std::min<int64_t>(n_blocks, (int64_t)1 << 20);
+    hipLaunchKernelGGL(mark_touched, dim3(groups), dim3(kGroupThreads), 0, stream, blocks, n_blocks, V, touched, words,
                        totals);
     return hipGetLastError();
 }
@@ -1914,8 +1922,8 @@ hipError_t launch_init(int dtype, void* X, int64_t count, uint64_t seed, uint64_
 hipError_t launch_fill_i32(int32_t* d_out, int64_t count, int32_t value, hipStream_t stream)
 {
     if (count <= 0) return hipSuccess;
-    hipLaunchKernelGGL(fill_i32, dim3((unsigned)((count + kGroupThreads - 1) / kGroupThreads)), dim3(kGroupThreads), 0, stream,
-                       d_out, count, value);
+    const int64_t groups = std::min<int64_t>((count + kGroupThreads - 1) / kGroupThreads, (int64_t)1 << 20);
+    hipLaunchKernelGGL(fill_i32, dim3((unsigned)groups), dim3(kGroupThreads), 0, stream, d_out, count, value);
     return hipGetLastError();
 }
 

@@ -799,7 +799,8 @@ def test_packed_strips_with_sixteen_wavefronts_visit_every_rating_once(mfmod, ri
                                              ("f16", 128, (8, 32)), ("f16", 64, (8, 13)), ("f32", 256, (8, 63))])
 def test_deterministic_mode_with_packed_strips_gives_the_same_bits(mfmod, storage, k, grid):
     """The deterministic LDS kernels keep only the touched columns of a strip in LDS too when few
-    are touched (they move a strip column by column).  Packing changes where a column sits in LDS
+    are touched (they move a strip column by column; MF_OPT_PACK_STRIPS = 2 asks for it wherever it
+    is possible).  Packing changes where a column sits in LDS
     and nothing else: one launch per epoch and one launch per stratum with packed strips, the
     same with whole strips (MF_OPT_PACK_STRIPS = 0) and the kernel on Qt in memory must agree bit
     for bit, over three epochs (two of them with shuffled strata), and match the oracle."""
@@ -808,7 +809,7 @@ def test_deterministic_mode_with_packed_strips_gives_the_same_bits(mfmod, storag
     rows, cols, vals = ds.rows[:take].copy(), ds.cols[:take].copy(), ds.vals[:take].copy()
     gr, gc = grid
     outs = []
-    for kernel, ring, pack in (("lds", 1, 1), ("lds", 0, 1), ("lds", 1, 0), ("global", 0, 1)):
+    for kernel, ring, pack in (("lds", 1, 2), ("lds", 0, 2), ("lds", 1, 0), ("global", 0, 1)):
         which = mfmod.MF_KERNEL_LDS if kernel == "lds" else mfmod.MF_KERNEL_GLOBAL
         model = mfmod.MatrixFactorization(ds.cfg.m, ds.cfg.n, k, storage, seed=3, scale=0.1,
                                           options={mfmod.MF_OPT_DET_KERNEL: which, mfmod.MF_OPT_RING: ring,
@@ -842,6 +843,32 @@ def test_deterministic_mode_with_packed_strips_gives_the_same_bits(mfmod, storag
     else:
         differing = int((outs[0][0] != Po).sum() + (outs[0][1] != Qo).sum())
         assert differing <= max(1, int(1e-5 * (Po.size + Qo.size))), differing
+
+
+def test_table_of_touched_columns_on_a_grid_of_millions_of_blocks(mfmod):
+    """17.2 million blocks, 2.7 million of them with ratings: the kernel that makes the table of
+    touched columns takes one workgroup per non-empty block and has to loop over the list (a
+    launch dimension holds fewer than 2^32 threads: launched with one workgroup per block it
+    left most of the table empty on 25 million blocks, and the packed kernels then skipped columns
+    that have ratings).  The packed deterministic kernel must give the bits of the kernel that
+    works on Qt in memory."""
+    rng = np.random.default_rng(5)
+    m, n, nnz, k = 4100, 42_000, 3_000_000, 32      # strips of 10 columns, one or two of them touched by a block
+    rows = rng.integers(0, m, nnz).astype(np.int32)
+    cols = rng.integers(0, n, nnz).astype(np.int32)
+    vals = rng.uniform(1.0, 5.0, nnz).astype(np.float32)
+    outs = []
+    for which in (mfmod.MF_KERNEL_LDS, mfmod.MF_KERNEL_GLOBAL):
+        model = mfmod.MatrixFactorization(m, n, k, "f32", seed=2, scale=0.1, options={mfmod.MF_OPT_DET_KERNEL: which})
+        model.load_blocks(rows, cols, vals, 4100, 4200, 0)
+        plan = model.epoch_plan(mfmod.MF_MODE_DET)
+        if which == mfmod.MF_KERNEL_LDS:
+            assert plan["kernel"] in ("sgd_ring_lds", "sgd_block_lds") and "touched columns" in plan["note"], plan
+        model.sgd_epoch(0.01, 0.05, mfmod.MF_MODE_DET)
+        model.sync()
+        outs.append(model.get_factors())
+        model.close()
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
 
 
 def test_lds_kernel_is_refused_when_the_strip_does_not_fit(mfmod):
