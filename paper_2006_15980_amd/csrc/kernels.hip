@@ -22,6 +22,7 @@
 // there is no MFMA here; the lanes hold rows in registers, consecutive ratings of one matrix row
 // reuse p_u from registers, and the rows of later ratings are requested ahead of their use.
 #include <algorithm>
+#include <utility>
 
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
@@ -126,6 +127,43 @@ __device__ __forceinline__ void store_row(__half* row_ptr, int lane, bool active
 #pragma unroll
     for (int j = 0; j < VEC / 2; ++j)
         reinterpret_cast<unsigned*>(row_ptr)[lane + kWave * j] = pack_half2(r.x[2 * j], r.x[2 * j + 1]);
+}
+
+// A row as it lies in memory, requested now and turned into values only where it is used: the
+// registers of a row on its way hold the loaded words (binary16: half as many as values), and
+// the conversion cannot drift up to the load, where it would wait for the data at once.
+template <typename T, int K>
+struct StoredRow {
+    static constexpr int WORDS = RowShape<T, K>::VEC * (int)sizeof(T) / 4;
+    unsigned w[WORDS];
+};
+
+template <typename T, int K, bool FRESH>
+__device__ __forceinline__ StoredRow<T, K> request_row(const T* row_ptr, int lane, bool active)
+{
+    StoredRow<T, K> r;
+#pragma unroll
+    for (int j = 0; j < StoredRow<T, K>::WORDS; ++j)
+        r.w[j] = active ? load_word<FRESH>(reinterpret_cast<const unsigned*>(row_ptr) + lane + kWave * j) : 0u;
+    return r;
+}
+
+template <typename T, int K>
+__device__ __forceinline__ Row<RowShape<T, K>::VEC> row_values(const StoredRow<T, K>& r)
+{
+    Row<RowShape<T, K>::VEC> out;
+    if constexpr (sizeof(T) == 2) {
+#pragma unroll
+        for (int j = 0; j < StoredRow<T, K>::WORDS; ++j) {
+            const float2 t = unpack_half2(r.w[j]);
+            out.x[2 * j] = t.x;
+            out.x[2 * j + 1] = t.y;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < StoredRow<T, K>::WORDS; ++j) out.x[j] = __uint_as_float(r.w[j]);
+    }
+    return out;
 }
 
 // row += d with hardware floating-point atomic adds executed in the L2 (no value returned).
@@ -388,8 +426,13 @@ __device__ __forceinline__ int strip_elem(int lane, int j)
     return lane + kWave * j;
 }
 
-constexpr int kLdsPrefetchDepth = 8;   // rows of P requested ahead in the Hogwild form (or kShortPrefetchDepth)
+// rows of P requested ahead in the Hogwild form: kShortPrefetchDepth, or the long depth of the
+// storage type (a requested binary16 row takes one register per lane, an fp32 row two)
+constexpr int kLdsPrefetchDepth = 8;
+constexpr int kLdsPrefetchDepthHalf = 12;
 constexpr int kShortPrefetchDepth = 4;
+template <typename T>
+constexpr int kLongPrefetchDepth = sizeof(T) == 2 ? kLdsPrefetchDepthHalf : kLdsPrefetchDepth;
 // The deterministic form has a compute unit nearly to itself (one wavefront per workgroup) and
 // registers to spare: 16 rows ahead measured 5 % faster than 8 on 250 M ratings, 32 slower.
 constexpr int kDetPrefetchDepth = 16;
@@ -451,21 +494,33 @@ __device__ __forceinline__ Row<VEC> strip_read(const int* qrow, int lane, bool a
     return q;
 }
 
+// Calls f(0), f(1), ... f(N-1) with compile-time arguments until one returns false: a fully
+// unrolled loop with an early exit whose register arrays keep constant indices.
+template <class F, int... I>
+__device__ __forceinline__ void unrolled_while(F&& f, std::integer_sequence<int, I...>)
+{
+    (void)(f(std::integral_constant<int, I>{}) && ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void unrolled_while(F&& f)
+{
+    unrolled_while(f, std::make_integer_sequence<int, N>{});
+}
+
 // The rows of P of the first DEPTH ratings of a batch, requested ahead of their use.
-template <int VEC, int DEPTH>
+template <typename T, int K, int DEPTH>
 struct RowRing {
-    Row<VEC> r[DEPTH];
+    StoredRow<T, K> r[DEPTH];
 };
 
 template <typename T, int K, int DEPTH>
-__device__ __forceinline__ RowRing<RowShape<T, K>::VEC, DEPTH> request_first_rows(const T* __restrict__ P, int mu,
-                                                                                  int cnt, int lane, bool active)
+__device__ __forceinline__ RowRing<T, K, DEPTH> request_first_rows(const T* __restrict__ P, int mu, int cnt, int lane,
+                                                                    bool active)
 {
-    constexpr int VEC = RowShape<T, K>::VEC;
-    RowRing<VEC, DEPTH> ring;
+    RowRing<T, K, DEPTH> ring;
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d)
-        ring.r[d] = load_row<VEC, false>(P + (int64_t)uniform_lane(mu, min(d, cnt - 1)) * K, lane, active);
+        ring.r[d] = request_row<T, K, false>(P + (int64_t)uniform_lane(mu, min(d, cnt - 1)) * K, lane, active);
     return ring;
 }
 
@@ -485,8 +540,8 @@ __device__ __forceinline__ int strip_slots(int mv, int col0, const unsigned shor
 // positions ahead; every rating issues the same memory operations (one row request, one row
 // store, whether or not the row changes) so that the wait counters are exact.  A rating whose row
 // equals the previous rating's takes the row from registers: the request for it was issued before
-// the previous ratings of that run were applied.  Positions past the end of the batch repeat the
-// last rating with a zero step, which changes nothing.
+// the previous ratings of that run were applied.  Requests past the end of the batch ask for its
+// last row again; the unrolled group of DEPTH ratings in which the batch ends is left early.
 // EXACT (deterministic mode, the wavefront is alone in its workgroup): the strip holds fp32, q_v
 // is read and written in program order, every operation is the sequential order's.
 template <typename T, int K, int DEPTH, bool EXACT, bool SPARSE>
@@ -495,7 +550,7 @@ __device__ __forceinline__ void lds_owned_chunk(T* __restrict__ P, int* strip, i
                                                 const int32_t* __restrict__ V,
                                                 const float* __restrict__ R, int64_t begin,
                                                 int32_t len, int mu, int mv, float mr,
-                                                RowRing<RowShape<T, K>::VEC, DEPTH> first_rows, float lr,
+                                                RowRing<T, K, DEPTH> first_rows, float lr,
                                                 float shrink, int lane, bool active)
 {
     // mu, mv, mr: the first batch of the chunk (rating `lane` of it), already loaded by the caller;
@@ -517,30 +572,31 @@ __device__ __forceinline__ void lds_owned_chunk(T* __restrict__ P, int* strip, i
             nr = R[begin + off + kWave + lane];
         }
         const int last = cnt - 1;
-        Row<VEC> ring[DEPTH];
+        StoredRow<T, K> ring[DEPTH];
         if (off == 0) {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) ring[d] = first_rows.r[d];
         } else {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d)
-                ring[d] = load_row<VEC, false>(P + (int64_t)uniform_lane(mu, min(d, last)) * K, lane, active);
+                ring[d] = request_row<T, K, false>(P + (int64_t)uniform_lane(mu, min(d, last)) * K, lane, active);
         }
         int v_next = uniform_lane(mv, 0);
         Row<VEC> q_next = strip_read<T, VEC, EXACT>(strip + v_next * K, lane, active);
-        for (int base = 0; base < cnt; base += DEPTH) {
-#pragma unroll
-            for (int d = 0; d < DEPTH; ++d) {
-                const int i = base + d;
-                const bool valid = i < cnt;
-                const int ic = min(i, last);
-                const int u = uniform_lane(mu, ic);
+        // one rating: position d of its group of DEPTH, rating i of the batch; AHEAD: the row of
+        // the rating DEPTH positions on is requested (not in the last, partial group of a batch)
+        auto rating = [&](auto position, auto ahead, int i) {
+                constexpr int d = decltype(position)::value;
+                constexpr bool AHEAD = decltype(ahead)::value;
+                const int u = uniform_lane(mu, i);
                 const int v = v_next;
-                const float r = __int_as_float(uniform_lane(__float_as_int(mr), ic));
+                const float r = __int_as_float(uniform_lane(__float_as_int(mr), i));
+                const Row<VEC> arrived = row_values<T, K>(ring[d]);
                 Row<VEC> p;
 #pragma unroll
-                for (int j = 0; j < VEC; ++j) p.x[j] = (u == u_prev) ? p_prev.x[j] : ring[d].x[j];
-                ring[d] = load_row<VEC, false>(P + (int64_t)uniform_lane(mu, min(i + DEPTH, last)) * K, lane, active);
+                for (int j = 0; j < VEC; ++j) p.x[j] = (u == u_prev) ? p_prev.x[j] : arrived.x[j];
+                if constexpr (AHEAD)
+                    ring[d] = request_row<T, K, false>(P + (int64_t)uniform_lane(mu, min(i + DEPTH, last)) * K, lane, active);
                 const Row<VEC> q = q_next;
                 int* const qrow = strip + v * K;
                 v_next = uniform_lane(mv, min(i + 1, last));
@@ -557,8 +613,8 @@ __device__ __forceinline__ void lds_owned_chunk(T* __restrict__ P, int* strip, i
                     for (int j = 0; j < VEC; ++j) part = fmaf(p.x[j], q.x[j], part);
                     e = r - wave_sum(part);
                 }
-                const float step = valid ? lr * e : 0.f;
-                const float sh = valid ? shrink : 0.f;
+                const float step = lr * e;
+                const float sh = shrink;
                 Row<VEC> p2;
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) {
@@ -577,8 +633,21 @@ __device__ __forceinline__ void lds_owned_chunk(T* __restrict__ P, int* strip, i
                 store_row<VEC>(P + (int64_t)u * K, lane, active, p2);
                 p_prev = p2;
                 u_prev = u;
-            }
-        }
+        };
+        // whole groups of DEPTH ratings: the same memory operations at every position, so the wait
+        // counts are static; then what is left of the batch, with an exit after every rating
+        int base = 0;
+        for (; base + DEPTH <= cnt; base += DEPTH)
+            unrolled_while<DEPTH>([&](auto position) {
+                rating(position, std::true_type{}, base + decltype(position)::value);
+                return true;
+            });
+        unrolled_while<DEPTH - 1>([&](auto position) {
+            const int i = base + decltype(position)::value;
+            if (i >= cnt) return false;
+            rating(position, std::false_type{}, i);
+            return true;
+        });
         mu = nu;
         mv = strip_slots<SPARSE>(nv, col0, slots, lane < len - off - kWave);
         mr = nr;
@@ -616,7 +685,7 @@ __device__ __forceinline__ void lds_hog_chunk(T* __restrict__ P, int* strip, int
                                               const int32_t* __restrict__ V,
                                               const float* __restrict__ R, int64_t begin, int32_t len,
                                               int mu, int mv, float mr,
-                                              RowRing<RowShape<T, K>::VEC, DEPTH> first_rows, float lr,
+                                              RowRing<T, K, DEPTH> first_rows, float lr,
                                               float shrink, int lane, bool active, RangeWatch& watch)
 {
     constexpr int VEC = RowShape<T, K>::VEC;
@@ -644,71 +713,88 @@ __device__ __forceinline__ void lds_hog_chunk(T* __restrict__ P, int* strip, int
             nr = R[begin + off + kWave + lane];
         }
         const int last = cnt - 1;
-        Row<VEC> ring[DEPTH];
+        StoredRow<T, K> ring[DEPTH];
         if (off == 0) {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) ring[d] = first_rows.r[d];
         } else {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d)
-                ring[d] = load_row<VEC, false>(row_of(uniform_lane(mu, min(d, last))), lane, active);
+                ring[d] = request_row<T, K, false>(row_of(uniform_lane(mu, min(d, last))), lane, active);
         }
         Row<VEC> qs = read_scaled(uniform_lane(mv, 0));
-        for (int base = 0; base < cnt; base += DEPTH) {
+        // one rating: position d of its group of DEPTH, rating i of the batch; AHEAD: the row of
+        // the rating DEPTH positions on is requested (not in the last, partial group of a batch)
+        auto rating = [&](auto position, auto ahead, int i) {
+            constexpr int d = decltype(position)::value;
+            constexpr bool AHEAD = decltype(ahead)::value;
+            const int u = uniform_lane(mu, i);
+            const int v = uniform_lane(mv, i);
+            const float r = __int_as_float(uniform_lane(__float_as_int(mr), i));
+            const Row<VEC> arrived = row_values<T, K>(ring[d]);
+            Row<VEC> p;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) p.x[j] = (u == u_prev) ? p_prev.x[j] : arrived.x[j];
+            if constexpr (AHEAD)
+                ring[d] = request_row<T, K, false>(row_of(uniform_lane(mu, min(i + DEPTH, last))), lane, active);
+            float part = 0.f;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) part = fmaf(p.x[j], qs.x[j], part);
+            const float e = fmaf(-kFromFixed, wave_sum_fused(part), r);
+            const float step = lr * e;
+            const float step_q = step * kFromFixed;   // (lr*e) * q       = step_q * qs
+            const float step_p = step * kToFixed;     // (lr*e) * p * 2^24 = step_p * p
+            int* const qrow = strip + v * K;
+            Row<VEC> p2, dqs;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                p2.x[j] = quantise<T>(fmaf(step_q, qs.x[j], fmaf(-shrink, p.x[j], p.x[j])));
+                dqs.x[j] = fmaf(step_p, p.x[j], -shrink * qs.x[j]);
+                const int dq = __float2int_rn(dqs.x[j]);
+                if (active) atomicAdd(&qrow[strip_elem<T>(lane, j)], dq);
+            }
+            watch.see<VEC>(qs, dqs);
+            store_row<VEC>(row_of(u), lane, active, p2);
+            qs = read_scaled(uniform_lane(mv, min(i + 1, last)));   // after the add above
+            p_prev = p2;
+            u_prev = u;
+        };
+        // whole groups of DEPTH ratings: the same memory operations at every position, so the wait
+        // counts are static; then what is left of the batch, with an exit after every rating
+        int base = 0;
+        for (; base + DEPTH <= cnt; base += DEPTH) {
             // The wavefronts of a workgroup get equal shares of the block, but the instruction
             // arbiter favours the oldest wavefront of a SIMD: left alone they finish one after
             // the other and the last ones run alone, far below the issue rate.  A wavefront with
             // more of its chunk left asks for a higher priority, which keeps them level.
             // Only in the build with the long prefetch depth, which is the one taken for large
             // inputs: on short chunks the priority changes were measured to cost 2 %.
-            if constexpr (DEPTH >= kLdsPrefetchDepth) {
+            if constexpr (DEPTH > kShortPrefetchDepth) {
                 const int left = len - off - base;
                 if (left > three_quarters) __builtin_amdgcn_s_setprio(3);
                 else if (left > half) __builtin_amdgcn_s_setprio(2);
                 else if (left > quarter) __builtin_amdgcn_s_setprio(1);
                 else __builtin_amdgcn_s_setprio(0);
             }
-#pragma unroll
-            for (int d = 0; d < DEPTH; ++d) {
-                const int i = base + d;
-                const bool valid = i < cnt;
-                const int ic = min(i, last);
-                const int u = uniform_lane(mu, ic);
-                const int v = uniform_lane(mv, ic);
-                const float r = __int_as_float(uniform_lane(__float_as_int(mr), ic));
-                Row<VEC> p;
-#pragma unroll
-                for (int j = 0; j < VEC; ++j) p.x[j] = (u == u_prev) ? p_prev.x[j] : ring[d].x[j];
-                ring[d] = load_row<VEC, false>(row_of(uniform_lane(mu, min(i + DEPTH, last))), lane, active);
-                float part = 0.f;
-#pragma unroll
-                for (int j = 0; j < VEC; ++j) part = fmaf(p.x[j], qs.x[j], part);
-                const float e = fmaf(-kFromFixed, wave_sum_fused(part), r);
-                const float step = valid ? lr * e : 0.f;
-                const float sh = valid ? shrink : 0.f;
-                const float step_q = step * kFromFixed;   // (lr*e) * q       = step_q * qs
-                const float step_p = step * kToFixed;     // (lr*e) * p * 2^24 = step_p * p
-                int* const qrow = strip + v * K;
-                Row<VEC> p2, dqs;
-#pragma unroll
-                for (int j = 0; j < VEC; ++j) {
-                    p2.x[j] = quantise<T>(fmaf(step_q, qs.x[j], fmaf(-sh, p.x[j], p.x[j])));
-                    dqs.x[j] = fmaf(step_p, p.x[j], -sh * qs.x[j]);
-                    const int dq = __float2int_rn(dqs.x[j]);
-                    if (active) atomicAdd(&qrow[strip_elem<T>(lane, j)], dq);
-                }
-                watch.see<VEC>(qs, dqs);
-                store_row<VEC>(row_of(u), lane, active, p2);
-                qs = read_scaled(uniform_lane(mv, min(i + 1, last)));   // after the add above
-                p_prev = p2;
-                u_prev = u;
-            }
+            unrolled_while<DEPTH>([&](auto position) {
+                rating(position, std::true_type{}, base + decltype(position)::value);
+                return true;
+            });
         }
+        if constexpr (DEPTH > kShortPrefetchDepth) {
+            if (base < cnt) __builtin_amdgcn_s_setprio(0);
+        }
+        unrolled_while<DEPTH - 1>([&](auto position) {
+            const int i = base + decltype(position)::value;
+            if (i >= cnt) return false;
+            rating(position, std::false_type{}, i);
+            return true;
+        });
         mu = nu;
         mv = strip_slots<SPARSE>(nv, col0, slots, lane < len - off - kWave);
         mr = nr;
     }
-    if constexpr (DEPTH >= kLdsPrefetchDepth) __builtin_amdgcn_s_setprio(0);
+    if constexpr (DEPTH > kShortPrefetchDepth) __builtin_amdgcn_s_setprio(0);
 }
 
 // ---- rows of P cut by entry boundaries, held in LDS while their block runs ----------------------
@@ -1269,11 +1355,11 @@ __device__ __forceinline__ bool lds_block_body(int* strip, T* __restrict__ P, T*
     const int n_hot = EXACT ? 0 : (blk.hot & 15);
     int hot_u = -1;
     if (!EXACT && lane < n_hot) hot_u = U[hot_pos[(blk.hot >> 4) + lane]];
-    RowRing<VEC, DEPTH> first_rows;
+    RowRing<T, K, DEPTH> first_rows;
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d)
 #pragma unroll
-        for (int j = 0; j < VEC; ++j) first_rows.r[d].x[j] = 0.f;
+        for (int j = 0; j < StoredRow<T, K>::WORDS; ++j) first_rows.r[d].w[j] = 0u;
     if (wave < blk.n_entries) {
         fetch_entry(wave);
         if (EXACT || raw_len > 0)
@@ -1659,13 +1745,17 @@ hipError_t launch_sgd_t(bool hogwild, void* P, void* Qt, const int32_t* U, const
                         const float* R, const int64_t* eb, const int32_t* el, int64_t first,
                         int64_t n_entries, float lr, float lambda, hipStream_t stream)
 {
-    const unsigned groups = (unsigned)(n_entries / kWavesPerGroup);
-    if (hogwild)
-        hipLaunchKernelGGL((sgd_chunks<T, K, true>), dim3(groups), dim3(kGroupThreads), 0, stream, (T*)P,
-                           (T*)Qt, U, V, R, eb, el, first, lr, lambda);
-    else
-        hipLaunchKernelGGL((sgd_chunks<T, K, false>), dim3(groups), dim3(kGroupThreads), 0, stream, (T*)P,
-                           (T*)Qt, U, V, R, eb, el, first, lr, lambda);
+    // a launch holds fewer than 2^32 threads: a longer work list goes in slices, in order
+    constexpr int64_t kMaxGroups = (int64_t)1 << 22;
+    for (int64_t done = 0; done < n_entries; done += kMaxGroups * kWavesPerGroup) {
+        const unsigned groups = (unsigned)std::min<int64_t>((n_entries - done) / kWavesPerGroup, kMaxGroups);
+        if (hogwild)
+            hipLaunchKernelGGL((sgd_chunks<T, K, true>), dim3(groups), dim3(kGroupThreads), 0, stream, (T*)P,
+                               (T*)Qt, U, V, R, eb, el, first + done, lr, lambda);
+        else
+            hipLaunchKernelGGL((sgd_chunks<T, K, false>), dim3(groups), dim3(kGroupThreads), 0, stream, (T*)P,
+                               (T*)Qt, U, V, R, eb, el, first + done, lr, lambda);
+    }
     return hipGetLastError();
 }
 
@@ -1751,7 +1841,7 @@ hipError_t launch_sgd_ring_t(bool exact, bool short_prefetch, int waves, bool qu
                 waves, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda,
                 done, first, abort_flag, spin_limit, order, pos, touched, touched_words, slot_table_at, stream);
         if (touched)
-            return launch_sgd_ring_impl<T, K, false, kLdsPrefetchDepth, true>(
+            return launch_sgd_ring_impl<T, K, false, kLongPrefetchDepth<T>, true>(
                 waves, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda,
                 done, first, abort_flag, spin_limit, order, pos, touched, touched_words, slot_table_at, stream);
     }
@@ -1759,7 +1849,7 @@ hipError_t launch_sgd_ring_t(bool exact, bool short_prefetch, int waves, bool qu
         return launch_sgd_ring_impl<T, K, false, kShortPrefetchDepth, false>(
             waves, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done,
             first, abort_flag, spin_limit, order, pos, nullptr, 0, 0, stream);
-    return launch_sgd_ring_impl<T, K, false, kLdsPrefetchDepth, false>(
+    return launch_sgd_ring_impl<T, K, false, kLongPrefetchDepth<T>, false>(
         waves, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done,
         first, abort_flag, spin_limit, order, pos, nullptr, 0, 0, stream);
 }
@@ -1785,7 +1875,7 @@ hipError_t launch_sgd_lds_t(bool exact, bool short_prefetch, int waves, void* P,
                 waves, P, Qt, U, V, R, eb, el, hot, blocks, n_blocks, lds_bytes, lr, lambda, range_flag, touched,
                 touched_words, slot_table_at, stream);
         if (touched)
-            return launch_sgd_lds_impl<T, K, false, kLdsPrefetchDepth, true>(
+            return launch_sgd_lds_impl<T, K, false, kLongPrefetchDepth<T>, true>(
                 waves, P, Qt, U, V, R, eb, el, hot, blocks, n_blocks, lds_bytes, lr, lambda, range_flag, touched,
                 touched_words, slot_table_at, stream);
     }
@@ -1793,7 +1883,7 @@ hipError_t launch_sgd_lds_t(bool exact, bool short_prefetch, int waves, void* P,
         return launch_sgd_lds_impl<T, K, false, kShortPrefetchDepth, false>(waves, P, Qt, U, V, R, eb, el, hot, blocks,
                                                                             n_blocks, lds_bytes, lr, lambda, range_flag,
                                                                             nullptr, 0, 0, stream);
-    return launch_sgd_lds_impl<T, K, false, kLdsPrefetchDepth, false>(waves, P, Qt, U, V, R, eb, el, hot, blocks, n_blocks,
+    return launch_sgd_lds_impl<T, K, false, kLongPrefetchDepth<T>, false>(waves, P, Qt, U, V, R, eb, el, hot, blocks, n_blocks,
                                                                       lds_bytes, lr, lambda, range_flag, nullptr, 0, 0,
                                                                       stream);
 }
