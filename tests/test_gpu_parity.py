@@ -46,6 +46,22 @@ def _make(mf, ds, k, storage, gr, gc, split, seed=1, scale=0.1, options=None):
     return model
 
 
+def _one_heavy_block_row(mf, options):
+    """A model on a 64 x 64 grid of equal-width strips in which block row 5 holds a hundred times
+    the ratings of any other: the block row before it finishes each step long before block row 5
+    has released the strip it needs, whatever the timing of the launch."""
+    rng = np.random.default_rng(20061642)
+    m, n, per_strip = 64 * 16, 640, 16
+    light = rng.integers(0, m, 64 * 1000)
+    heavy = rng.integers(5 * per_strip, 6 * per_strip, 100000)
+    rows = np.concatenate([light, heavy]).astype(np.int32)
+    cols = rng.integers(0, n, rows.size).astype(np.int32)
+    vals = rng.uniform(1.0, 5.0, rows.size).astype(np.float32)
+    model = mf.MatrixFactorization(m, n, 128, "f32", seed=1, scale=0.1, options=options)
+    model.load_blocks(rows, cols, vals, 64, 64, 0)
+    return model, rows, cols, vals
+
+
 # ------------------------------------------------------------------------------- integer work
 @pytest.mark.parametrize("storage", ["f32", "f16"])
 def test_init_factors_bit_exact(mfmod, storage):
@@ -264,13 +280,14 @@ def test_one_launch_per_epoch_gives_the_same_bits_as_one_launch_per_stratum(mfmo
 
 
 def test_ring_kernel_gives_up_cleanly_when_its_wait_limit_is_tiny(mfmod):
-    """Failure handling forced from the host: with a wait limit of one poll some workgroup finds
-    its neighbour not ready, raises the abort flag, every workgroup leaves, and the next
-    synchronising call reports MF_EDEVICE (the kernel itself ends normally)."""
+    """Failure handling forced from the host: with a wait limit of one poll and one block row far
+    heavier than the others, the workgroup that needs its strips finds it not ready, raises the
+    abort flag, every workgroup leaves, and the next synchronising call reports MF_EDEVICE (the
+    kernel itself ends normally)."""
     ds = dataset("tiny")
     opts = {mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS, mfmod.MF_OPT_RING: 1,
             mfmod.MF_OPT_RING_SPIN_LIMIT: 1}
-    model = _make(mfmod, ds, 128, "f32", 64, 64, 1, options=opts)
+    model, rows, cols, vals = _one_heavy_block_row(mfmod, opts)
     assert model.epoch_plan(mfmod.MF_MODE_HOGWILD)["kernel"] == "sgd_ring_lds"
     model.sgd_epoch(ds.cfg.lr, ds.cfg.lam, mfmod.MF_MODE_HOGWILD)
     with pytest.raises(mfmod.MFError) as e:
@@ -282,13 +299,14 @@ def test_ring_kernel_gives_up_cleanly_when_its_wait_limit_is_tiny(mfmod):
     plan = model.epoch_plan(mfmod.MF_MODE_HOGWILD)
     assert plan["kernel"] == "sgd_block_lds" and "wait limit" in plan["note"], plan
     B = mfmod.binding
-    B.mf_init(model.ctx, ds.cfg.m, ds.cfg.n, 128, B.MF_F32, model.P.data_ptr(), model.Qt.data_ptr(), 1, 0.1)
-    model.load_blocks(ds.rows, ds.cols, ds.vals, 64, 64, 1)          # a new load may use the one-launch kernel again
+    B.mf_init(model.ctx, model.m, model.n, 128, B.MF_F32, model.P.data_ptr(), model.Qt.data_ptr(), 1, 0.1)
     B.mf_set_option(model.ctx, mfmod.MF_OPT_RING_SPIN_LIMIT, 1 << 22)
-    tr, tc, tv = model.to_device(ds.test_rows, ds.test_cols, ds.test_vals)
+    model.load_blocks(rows, cols, vals, 64, 64, 0)                    # a new load may use the one-launch kernel again
+    assert model.epoch_plan(mfmod.MF_MODE_HOGWILD)["kernel"] == "sgd_ring_lds"
+    tr, tc, tv = model.to_device(rows[::7], cols[::7], vals[::7])
     before = model.rmse(tr, tc, tv)
     for _ in range(3):
-        model.sgd_epoch(ds.cfg.lr, ds.cfg.lam, mfmod.MF_MODE_HOGWILD)
+        model.sgd_epoch(0.002, ds.cfg.lam, mfmod.MF_MODE_HOGWILD)
     assert model.rmse(tr, tc, tv) < before
     model.close()
 
@@ -396,7 +414,8 @@ def test_ring_kernel_with_an_order_gives_up_cleanly_when_its_wait_limit_is_tiny(
     ds = dataset("tiny")
     opts = {mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS, mfmod.MF_OPT_RING: 1,
             mfmod.MF_OPT_RING_SPIN_LIMIT: 1}
-    model = _make(mfmod, ds, 128, "f32", 64, 64, 1, options=opts)
+    model = _one_heavy_block_row(mfmod, opts)[0]
+    assert model.epoch_plan(mfmod.MF_MODE_HOGWILD)["kernel"] == "sgd_ring_lds"
     model.sgd_epoch(ds.cfg.lr, ds.cfg.lam, mfmod.MF_MODE_HOGWILD, stratum_order=oracle.stratum_order(1, 0, 64))
     with pytest.raises(mfmod.MFError) as e:
         model.sync()
