@@ -71,8 +71,9 @@ enum {
                                   /* mf_sgd_epoch) when all grid_r workgroups fit the device at once; */
                                   /* 0: always one launch per stratum                                 */
     MF_OPT_RING_SPIN_LIMIT = 9,   /* polls after which a waiting workgroup gives up (default 2^22)    */
-    MF_OPT_LDS_PREFETCH = 10,     /* MF_MODE_HOGWILD, LDS kernels: rows of P requested 4 or 8 ratings */
-                                  /* ahead; 0 (default): 4 if P takes at most 64 MiB, else 8          */
+    MF_OPT_LDS_PREFETCH = 10,     /* MF_MODE_HOGWILD, LDS kernels: rows of P requested ahead.  4 = the */
+                                  /* short depth (4 ratings), 8 = the long one (8 ratings, 12 with    */
+                                  /* binary16 storage); 0 (default): short if P takes at most 64 MiB  */
     MF_OPT_PACK_STRIPS = 12,      /* read by mf_load_blocks(_device): 1 (default) = the LDS kernels   */
                                   /* keep only the touched columns of a strip in LDS where that pays  */
                                   /* or whole strips do not fit (see mf_sgd_epoch); 2 = wherever the  */
