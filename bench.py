@@ -30,6 +30,8 @@ WORKLOAD_DEFAULTS = {
     "xlarge": ("256x2048", 2, 1.25),
     "stress": ("256x2560", 2, 0.1),
 }
+# grids of the deterministic mode's side figures (more block rows: its workgroups are single wavefronts)
+DET_GRIDS = {"medium": "512x512", "large": "1024x1024", "xlarge": "1024x6144", "stress": "2048x8192"}
 CPU_SAMPLE = 16_000_000     # ratings of the workload the CPU oracle is timed on
 
 
@@ -102,6 +104,37 @@ def cpu_baseline(ds, gr, gc, k, split, scale):
             "host_cores": len(os.sched_getaffinity(0))}
 
 
+def det_rate(mf, torch, ds, name, steps=3, warmup=1):
+    """Deterministic-mode throughput of a configuration at full size on its grid of DET_GRIDS (side
+    figure: epochs alone, by the wall clock)."""
+    _, split, scale = WORKLOAD_DEFAULTS[name]
+    grid = DET_GRIDS[name]
+    gr, gc = (int(x) for x in grid.split("x"))
+    cfg = ds.cfg
+    model = mf.MatrixFactorization(cfg.m, cfg.n, cfg.k, cfg.storage, seed=1, scale=scale)
+    coo = [torch.from_numpy(x).to(model.P.device) for x in (ds.rows, ds.cols, ds.vals)]
+    model.load_blocks_device(coo[0], coo[1], coo[2], gr, gc, split)
+    del coo
+    plan = model.epoch_plan(mf.MF_MODE_DET)
+    for i in range(warmup + steps):
+        if i == warmup:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+        model.sgd_epoch(cfg.lr, cfg.lam, mf.MF_MODE_DET)
+    model.sync()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    model.close()
+    nnz = ds.rows.size
+    bytes_per_update = 12 + 4 * cfg.k * (4 if cfg.storage == "f32" else 2)
+    value = nnz * steps / elapsed
+    return {"workload": f"{cfg.name}: m={cfg.m} n={cfg.n} nnz_train={nnz} k={cfg.k} {cfg.storage}", "mode": "det",
+            "grid": grid, "split": split, "steps": steps, "value": value, "unit": "updates/s",
+            "ms_per_step": elapsed * 1e3 / steps,
+            "algorithmic_frac_of_hbm_peak": value * bytes_per_update / 1e9 / HBM_PEAK_GBS,
+            "kernel": plan["kernel"], "waves_per_workgroup": plan["waves"], "launches_per_epoch": plan["launches"]}
+
+
 def quick_rate(mf, torch, name, steps=5, warmup=2):
     """Hogwild throughput of another configuration at full size on its grid of WORKLOAD_DEFAULTS (a
     few steps of epoch + held-out RMSE by the wall clock; these are side figures, the line's
@@ -129,10 +162,12 @@ def quick_rate(mf, torch, name, steps=5, warmup=2):
     nnz = ds.rows.size
     bytes_per_update = 12 + 4 * cfg.k * (4 if cfg.storage == "f32" else 2)
     value = nnz * steps / elapsed
-    return {"workload": f"{cfg.name}: m={cfg.m} n={cfg.n} nnz_train={nnz} k={cfg.k} {cfg.storage}", "grid": grid,
-            "split": split, "steps": steps, "value": value, "unit": "updates/s", "ms_per_step": elapsed * 1e3 / steps,
-            "bytes_per_update": bytes_per_update, "algorithmic_frac_of_hbm_peak": value * bytes_per_update / 1e9 / HBM_PEAK_GBS,
-            "kernel": plan["kernel"], "waves_per_workgroup": plan["waves"], "held_out_rmse": rmse}
+    return [{"workload": f"{cfg.name}: m={cfg.m} n={cfg.n} nnz_train={nnz} k={cfg.k} {cfg.storage}", "mode": "hogwild",
+             "grid": grid, "split": split, "steps": steps, "value": value, "unit": "updates/s",
+             "ms_per_step": elapsed * 1e3 / steps, "bytes_per_update": bytes_per_update,
+             "algorithmic_frac_of_hbm_peak": value * bytes_per_update / 1e9 / HBM_PEAK_GBS,
+             "kernel": plan["kernel"], "waves_per_workgroup": plan["waves"], "held_out_rmse": rmse},
+            det_rate(mf, torch, ds, name)]
 
 
 def block_size_curve(args, mf, ds):
@@ -385,11 +420,14 @@ def main():
     default_run = (args.workload == "xlarge" and args.scale == 1.0 and args.mode == "hogwild" and args.grid == d_grid
                    and args.split == d_split and not args.no_cpu_baseline)
     if default_run and not args.no_per_config:
-        # side figures: the other configurations at full size on their grids, same mode
+        # side figures: this configuration in deterministic mode, then the other configurations at
+        # full size on their grids in both modes
+        out["per_config"] = [det_rate(mf, torch, ds, "xlarge")]
         del ds
         import workloads
         workloads.forget()
-        out["per_config"] = [quick_rate(mf, torch, name) for name in ("medium", "large", "stress")]
+        for name in ("medium", "large", "stress"):
+            out["per_config"] += quick_rate(mf, torch, name)
     print(json.dumps(out))
 
 
