@@ -254,6 +254,8 @@ def main():
     ap.add_argument("--split", type=int, default=None,
                     help="0 equal width, 1 ratings balanced, 2 ratings and width balanced; default: the workload's")
     ap.add_argument("--ring", type=int, default=1, help="1: one launch per epoch (workgroups hand the strips round)")
+    ap.add_argument("--stratum-seed", type=int, default=0,
+                    help="nonzero: every epoch visits the strata in a seeded random order (mf_stratum_order)")
     ap.add_argument("--pack-strips", type=int, default=1, help="0: the LDS kernels always keep whole strips; 2: packed strips wherever possible")
     ap.add_argument("--load", default="device", choices=["host", "device"],
                     help="partition on the host (mf_load_blocks) or on the GPU (mf_load_blocks_device); outside the timed region")
@@ -341,10 +343,16 @@ def main():
     print(f"bench: {cfg.name} generated in {t_generate:.1f} s, loaded in {t_load:.2f} s; {plan['note']}",
           file=sys.stderr, flush=True)
 
+    epochs_run = [0]
+
     def run_steps(count):
         last = float("nan")
         for _ in range(count):
-            model.sgd_epoch(cfg.lr, cfg.lam, mode)
+            order = None
+            if args.stratum_seed:
+                order = mf.binding.mf_stratum_order(args.stratum_seed, epochs_run[0], gc)
+            model.sgd_epoch(cfg.lr, cfg.lam, mode, stratum_order=order)
+            epochs_run[0] += 1
             last = model.rmse(tr, tc, tv)
         return last
 
@@ -383,7 +391,7 @@ def main():
         key = (f"workload={args.workload} scale={args.scale:g} mode={args.mode} grid={args.grid} split={args.split} "
                f"kernel={plan['kernel']} waves={plan['waves']}")
         traffic, source = profiled_traffic(key)
-        if args.lds_chunk != 0 or args.chunk != 0 or not args.affinity or args.pack_strips != 1:
+        if args.lds_chunk != 0 or args.chunk != 0 or not args.affinity or args.pack_strips != 1 or args.stratum_seed != 0:
             traffic, source = None, None
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
@@ -407,7 +415,7 @@ def main():
                       "mode": args.mode, "grid": args.grid, "split": args.split, "init_scale": args.init_scale,
                       "hogwild_kernel": args.hogwild_kernel,
                       "lds_chunk": args.lds_chunk, "lds_waves": args.lds_waves, "ring": args.ring,
-                      "pack_strips": args.pack_strips,
+                      "pack_strips": args.pack_strips, "stratum_seed": args.stratum_seed,
                       "chunk": args.chunk,
                       "xcd_affinity": args.affinity,
                       "lr": cfg.lr, "lambda": cfg.lam},
