@@ -104,7 +104,7 @@ def cpu_baseline(ds, gr, gc, k, split, scale):
             "host_cores": len(os.sched_getaffinity(0))}
 
 
-def det_rate(mf, torch, ds, name, steps=3, warmup=1):
+def det_rate(mf, torch, ds, name, steps=3, warmup=1, together=8):
     """Deterministic-mode throughput of a configuration at full size on its grid of DET_GRIDS (side
     figure: epochs alone, by the wall clock)."""
     _, split, scale = WORKLOAD_DEFAULTS[name]
@@ -124,6 +124,12 @@ def det_rate(mf, torch, ds, name, steps=3, warmup=1):
     model.sync()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    # the same number of epochs in ONE call (mf_sgd_epochs: one launch where an epoch is one launch)
+    t0 = time.perf_counter()
+    model.sgd_epochs(cfg.lr, cfg.lam, mf.MF_MODE_DET, together)
+    model.sync()
+    torch.cuda.synchronize()
+    elapsed_together = time.perf_counter() - t0
     model.close()
     nnz = ds.rows.size
     bytes_per_update = 12 + 4 * cfg.k * (4 if cfg.storage == "f32" else 2)
@@ -132,7 +138,9 @@ def det_rate(mf, torch, ds, name, steps=3, warmup=1):
             "grid": grid, "split": split, "steps": steps, "value": value, "unit": "updates/s",
             "ms_per_step": elapsed * 1e3 / steps,
             "algorithmic_frac_of_hbm_peak": value * bytes_per_update / 1e9 / HBM_PEAK_GBS,
-            "kernel": plan["kernel"], "waves_per_workgroup": plan["waves"], "launches_per_epoch": plan["launches"]}
+            "kernel": plan["kernel"], "waves_per_workgroup": plan["waves"], "launches_per_epoch": plan["launches"],
+            "epochs_in_one_call": together, "value_in_one_call": nnz * together / elapsed_together,
+            "ms_per_epoch_in_one_call": elapsed_together * 1e3 / together}
 
 
 def quick_rate(mf, torch, name, steps=5, warmup=2):

@@ -263,6 +263,15 @@ int mf_epoch_plan(mf_ctx* ctx, int32_t mode, int32_t* kernel_out, int64_t* launc
  * uploads the order.  MF_EINVAL if stratum_order is not a permutation. */
 int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, const int32_t* stratum_order);
 
+/* n_epochs epochs of mf_sgd_epoch(ctx, lr, lambda, mode), strata in natural order (Algorithm 1, the
+ * training phase repeated).  Where an epoch is one launch (see mf_epoch_plan) the epochs run in ONE
+ * launch: a block row goes on with the next epoch as soon as the strips it needs are free, instead
+ * of waiting until every block row has finished the epoch, which in MF_MODE_DET is most of an
+ * epoch's time on matrices with very popular columns.  The result is that of n_epochs calls of
+ * mf_sgd_epoch (MF_MODE_DET: bit for bit).  n_epochs: 1 .. 4096, n_epochs * grid_c at most 2^29.
+ * Errors as mf_sgd_epoch. */
+int mf_sgd_epochs(mf_ctx* ctx, float lr, float lambda, int32_t mode, int32_t n_epochs);
+
 /* Host-only: the per-epoch stratum permutation this library proposes (a convention, the paper
  * names no generator): stratum s gets the key mix(mix(seed ^ epoch * 0xD1B54A32D192ED03) + s) with
  * mix = the SplitMix64 output function, strata in ascending (key, s).  order_out: HOST, grid_c

@@ -97,6 +97,10 @@ class MatrixFactorization:
                 raise ValueError("stratum_order needs grid_c entries")
             binding.mf_sgd_epoch_ordered(self.ctx, lr, lam, mode, np.ascontiguousarray(stratum_order, np.int32))
 
+    def sgd_epochs(self, lr: float, lam: float, mode: int, n_epochs: int):
+        """n_epochs epochs in natural order; one launch where an epoch is one launch (mf_sgd_epochs)."""
+        binding.mf_sgd_epochs(self.ctx, lr, lam, mode, n_epochs)
+
     def epoch_plan(self, mode: int) -> dict:
         """What sgd_epoch(mode) launches on the loaded grid (mf_epoch_plan)."""
         kernel, launches, waves, note = binding.mf_epoch_plan(self.ctx, mode)

@@ -35,7 +35,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmf_sgd.s
 EXPORTS = ["mf_create", "mf_destroy", "mf_last_error", "mf_set_option", "mf_init",
            "mf_load_blocks_workspace", "mf_load_blocks", "mf_load_blocks_device",
            "mf_load_blocks_streamed_workspace", "mf_load_blocks_streamed", "mf_get_partition", "mf_sgd_epoch",
-           "mf_sgd_epoch_ordered", "mf_stratum_order", "mf_epoch_plan",
+           "mf_sgd_epoch_ordered", "mf_sgd_epochs", "mf_stratum_order", "mf_epoch_plan",
            "mf_rmse", "mf_rmse_noalloc", "mf_sync", "mf_profile_read", "mf_debug_xcc_ids", "mf_plan_host", "mf_suggest_grid"]
 
 
@@ -70,6 +70,7 @@ def lib() -> C.CDLL:
         l.mf_get_partition.argtypes = [vp, vp, vp, vp, vp]
         l.mf_sgd_epoch.argtypes = [vp, f32, f32, i32]
         l.mf_sgd_epoch_ordered.argtypes = [vp, f32, f32, i32, vp]
+        l.mf_sgd_epochs.argtypes = [vp, f32, f32, i32, i32]
         l.mf_epoch_plan.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i64), C.POINTER(i32)]
         l.mf_stratum_order.argtypes = [C.c_uint64, C.c_uint64, i32, vp]
         l.mf_rmse.argtypes = [vp, vp, vp, vp, i64, C.POINTER(C.c_double)]
@@ -174,6 +175,10 @@ def mf_get_partition(ctx: int, nnz: int, grid_r: int, grid_c: int):
 
 def mf_sgd_epoch(ctx: int, lr: float, lam: float, mode: int) -> None:
     _check(ctx, lib().mf_sgd_epoch(ctx, lr, lam, mode))
+
+
+def mf_sgd_epochs(ctx: int, lr: float, lam: float, mode: int, n_epochs: int) -> None:
+    _check(ctx, lib().mf_sgd_epochs(ctx, lr, lam, mode, n_epochs))
 
 
 def mf_sgd_epoch_ordered(ctx: int, lr: float, lam: float, mode: int, stratum_order: Optional[np.ndarray]) -> None:

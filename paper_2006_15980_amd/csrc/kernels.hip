@@ -1513,7 +1513,8 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_ring_lds(
     const int64_t* __restrict__ entry_begin, const int32_t* __restrict__ entry_len, const int64_t* __restrict__ hot_pos,
     const LdsBlock* __restrict__ ring_blocks, int grid_r, int grid_c, float lr, float lambda,
     int* done, int first, int* flags, long long spin_limit, const int32_t* __restrict__ order,
-    const int32_t* __restrict__ pos, const unsigned* __restrict__ touched, int touched_words, int slot_table_at)
+    const int32_t* __restrict__ pos, const unsigned* __restrict__ touched, int touched_words, int slot_table_at,
+    int n_steps)
 {
     extern __shared__ int strip[];
     __shared__ int go;
@@ -1521,8 +1522,11 @@ __global__ __launch_bounds__(EXACT ? kWave : 1024) void sgd_ring_lds(
     const int next_row = a + 1 < grid_r ? a + 1 : 0;
     const int lag = a + 1 < grid_r ? 0 : grid_c - grid_r;
     RangeWatch watch;
-    for (int t = 0; t < grid_c; ++t) {
-        const int s = order ? order[t] : t;
+    // n_steps = grid_c for one epoch; a multiple of it (strata in natural order only) for several
+    // epochs in one launch: step t of the launch is stratum t mod grid_c, and the waits below hold
+    // across the epochs' boundaries as they do inside an epoch
+    for (int t = 0; t < n_steps; ++t) {
+        const int s = order ? order[t] : t % grid_c;
         // wait (bounded) until the previous user of this step's column strip has reported it
         // finished; returns false when the workgroup has to leave
         auto wait_for_strip = [&]() -> bool {
@@ -1789,7 +1793,8 @@ hipError_t launch_sgd_ring_impl(int waves, bool query_only, int* max_resident, v
                                 const int32_t* el, const int64_t* hot, const LdsBlock* ring_blocks, int grid_r, int grid_c,
                                 size_t lds_bytes, float lr, float lambda, int* done, int first,
                                 int* abort_flag, long long spin_limit, const int32_t* order, const int32_t* pos,
-                                const uint32_t* touched, int touched_words, int slot_table_at, hipStream_t stream)
+                                const uint32_t* touched, int touched_words, int slot_table_at, int n_steps,
+                                hipStream_t stream)
 {
     static bool raised[64] = {};
     int dev = 0;
@@ -1813,7 +1818,7 @@ hipError_t launch_sgd_ring_impl(int waves, bool query_only, int* max_resident, v
     }
     hipLaunchKernelGGL((sgd_ring_lds<T, K, EXACT, DEPTH, SPARSE>), dim3((unsigned)grid_r), dim3(waves * kWave), lds_bytes,
                        stream, (T*)P, (T*)Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lr, lambda, done,
-                       first, abort_flag, spin_limit, order, pos, touched, touched_words, slot_table_at);
+                       first, abort_flag, spin_limit, order, pos, touched, touched_words, slot_table_at, n_steps);
     return hipGetLastError();
 }
 
@@ -1823,35 +1828,35 @@ hipError_t launch_sgd_ring_t(bool exact, bool short_prefetch, int waves, bool qu
                              const int32_t* el, const int64_t* hot, const LdsBlock* ring_blocks, int grid_r, int grid_c,
                              size_t lds_bytes, float lr, float lambda, int* done, int first, int* abort_flag,
                              long long spin_limit, const int32_t* order, const int32_t* pos, const uint32_t* touched,
-                             int touched_words, int slot_table_at, hipStream_t stream)
+                             int touched_words, int slot_table_at, int n_steps, hipStream_t stream)
 {
     if (exact && touched)
         return launch_sgd_ring_impl<T, K, true, kDetPrefetchDepth, true>(
             1, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done,
-            first, abort_flag, spin_limit, order, pos, touched, touched_words, slot_table_at, stream);
+            first, abort_flag, spin_limit, order, pos, touched, touched_words, slot_table_at, n_steps, stream);
     if (exact)
         return launch_sgd_ring_impl<T, K, true, kDetPrefetchDepth, false>(
             1, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done,
-            first, abort_flag, spin_limit, order, pos, nullptr, 0, 0, stream);
+            first, abort_flag, spin_limit, order, pos, nullptr, 0, 0, n_steps, stream);
     // the form that keeps only the touched columns of a strip in LDS exists where a wavefront's piece of
     // the strip lies in one column
     if constexpr (SparseStrip<T, K>::kPossible) {
         if (touched && short_prefetch)
             return launch_sgd_ring_impl<T, K, false, kShortPrefetchDepth, true>(
                 waves, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda,
-                done, first, abort_flag, spin_limit, order, pos, touched, touched_words, slot_table_at, stream);
+                done, first, abort_flag, spin_limit, order, pos, touched, touched_words, slot_table_at, n_steps, stream);
         if (touched)
             return launch_sgd_ring_impl<T, K, false, kLongPrefetchDepth<T>, true>(
                 waves, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda,
-                done, first, abort_flag, spin_limit, order, pos, touched, touched_words, slot_table_at, stream);
+                done, first, abort_flag, spin_limit, order, pos, touched, touched_words, slot_table_at, n_steps, stream);
     }
     if (short_prefetch)
         return launch_sgd_ring_impl<T, K, false, kShortPrefetchDepth, false>(
             waves, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done,
-            first, abort_flag, spin_limit, order, pos, nullptr, 0, 0, stream);
+            first, abort_flag, spin_limit, order, pos, nullptr, 0, 0, n_steps, stream);
     return launch_sgd_ring_impl<T, K, false, kLongPrefetchDepth<T>, false>(
         waves, query_only, max_resident, P, Qt, U, V, R, eb, el, hot, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done,
-        first, abort_flag, spin_limit, order, pos, nullptr, 0, 0, stream);
+        first, abort_flag, spin_limit, order, pos, nullptr, 0, 0, n_steps, stream);
 }
 
 template <typename T, int K>
@@ -1958,16 +1963,18 @@ hipError_t launch_sgd_ring(int dtype, int k, bool exact, bool short_prefetch, in
                            int grid_r, int grid_c, size_t lds_bytes, float lr, float lambda, int* done,
                            int first, int* abort_flag, long long spin_limit, const int32_t* order,
                            const int32_t* pos, const uint32_t* touched, int touched_words, int slot_table_at,
-                           hipStream_t stream)
+                           int n_epochs, hipStream_t stream)
 {
     if (waves < 1 || waves > 16 || lds_bytes > kLdsBudget || grid_r < 1) return hipErrorInvalidValue;
+    if (n_epochs < 1 || (order && n_epochs != 1) || (int64_t)n_epochs * grid_c > ((int64_t)1 << 30)) return hipErrorInvalidValue;
+    const int n_steps = n_epochs * grid_c;
     if ((order == nullptr) != (pos == nullptr)) return hipErrorInvalidValue;
     if (touched && (touched_words < 1 || touched_words > kMaxTouchedWords || slot_table_at < 0 ||
                     (size_t)slot_table_at * 4 + (size_t)touched_words * 64 > lds_bytes))
         return hipErrorInvalidValue;
     MF_DISPATCH(launch_sgd_ring_t, exact, short_prefetch, waves, query_only, max_resident, P, Qt, U, V, R, entry_begin,
                 entry_len, hot_pos, ring_blocks, grid_r, grid_c, lds_bytes, lr, lambda, done, first, abort_flag,
-                spin_limit, order, pos, touched, touched_words, slot_table_at, stream);
+                spin_limit, order, pos, touched, touched_words, slot_table_at, n_steps, stream);
 }
 
 hipError_t launch_mark_touched(const LdsBlock* blocks, int64_t n_blocks, const int32_t* V, uint32_t* touched, int words,

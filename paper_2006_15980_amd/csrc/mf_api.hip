@@ -802,7 +802,7 @@ int plan_epoch(mf_ctx* ctx, int32_t mode, EpochPlan& p)
             MF_HIP(ctx, mf::launch_sgd_ring(ctx->dtype, ctx->k, !p.hog, p.short_prefetch, ctx->lds_waves_used, true, &resident,
                                             nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
                                             ctx->part.gr, ctx->part.gc, p.lds_bytes, 0.f, 0.f, nullptr, 0, nullptr, 0,
-                                            nullptr, nullptr, nullptr, 0, 0, ctx->stream));
+                                            nullptr, nullptr, nullptr, 0, 0, 1, ctx->stream));
             ctx->ring_resident[m_idx] = resident;
         }
         p.ring = ctx->part.gr <= ctx->ring_resident[m_idx];
@@ -852,12 +852,28 @@ int mf_epoch_plan(mf_ctx* ctx, int32_t mode, int32_t* kernel_out, int64_t* launc
     return MF_OK;
 }
 
+namespace {
+int sgd_epochs(mf_ctx* ctx, float lr, float lambda, int32_t mode, const int32_t* stratum_order, int32_t n_epochs);
+}
+
 int mf_sgd_epoch(mf_ctx* ctx, float lr, float lambda, int32_t mode)
 {
-    return mf_sgd_epoch_ordered(ctx, lr, lambda, mode, nullptr);
+    return sgd_epochs(ctx, lr, lambda, mode, nullptr, 1);
 }
 
 int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, const int32_t* stratum_order)
+{
+    return sgd_epochs(ctx, lr, lambda, mode, stratum_order, 1);
+}
+
+int mf_sgd_epochs(mf_ctx* ctx, float lr, float lambda, int32_t mode, int32_t n_epochs)
+{
+    if (ctx && (n_epochs < 1 || n_epochs > 4096)) return fail(ctx, MF_EINVAL, "n_epochs must be in 1 .. 4096");
+    return sgd_epochs(ctx, lr, lambda, mode, nullptr, n_epochs);
+}
+
+namespace {
+int sgd_epochs(mf_ctx* ctx, float lr, float lambda, int32_t mode, const int32_t* stratum_order, int32_t n_epochs)
 {
     if (!ctx) return MF_EINVAL;
     if (!ctx->loaded) return fail(ctx, MF_ESTATE, "mf_sgd_epoch before mf_load_blocks");
@@ -884,8 +900,18 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
     const mf::LdsSchedule& lsched = hog ? ctx->lds : ctx->det_lds;
     int32_t* const d_flags = ctx->d_ring_done + ctx->part.gr;   // abort flag, range flag
     ctx->epochs_since_check = true;
+    if (!plan.ring && n_epochs > 1) {
+        // only the one-launch kernel runs epochs on end: here, one after the other
+        for (int32_t e = 0; e < n_epochs; ++e) {
+            rc = sgd_epochs(ctx, lr, lambda, mode, nullptr, 1);
+            if (rc) return rc;
+        }
+        return MF_OK;
+    }
     if (plan.ring) {
-        if ((int64_t)(ctx->ring_epochs + 1) * ctx->part.gc > ((int64_t)1 << 30)) {
+        if ((int64_t)n_epochs * ctx->part.gc > ((int64_t)1 << 29))
+            return fail(ctx, MF_EINVAL, "n_epochs * grid_c exceeds the range of the step counters");
+        if ((int64_t)(ctx->ring_epochs + n_epochs) * ctx->part.gc > ((int64_t)1 << 30)) {
             // the strata counters are about to run out of range: start them again from zero (a
             // kernel, not a memset node, so that the call may be captured into a graph)
             MF_HIP(ctx, mf::launch_fill_i32(ctx->d_ring_done, ctx->part.gr, 0, ctx->stream));
@@ -906,9 +932,9 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
                                         ctx->ring_epochs * ctx->part.gc, d_flags,
                                         (long long)ctx->spin_limit, stratum_order ? ctx->d_order : nullptr,
                                         stratum_order ? ctx->d_order + gc : nullptr, plan.packed ? plan.touched : nullptr,
-                                        plan.touched_words, plan.slot_table_at, ctx->stream));
+                                        plan.touched_words, plan.slot_table_at, n_epochs, ctx->stream));
         if (ev1) MF_HIP(ctx, hipEventRecord(ev1, ctx->stream));
-        ctx->ring_epochs += 1;
+        ctx->ring_epochs += n_epochs;
         return MF_OK;
     }
     // Streamed mode: the ratings of a stratum are one contiguous piece of the packed arrays.  The
@@ -1001,6 +1027,7 @@ int mf_sgd_epoch_ordered(mf_ctx* ctx, float lr, float lambda, int32_t mode, cons
     }
     return MF_OK;
 }
+}  // namespace
 
 int mf_rmse(mf_ctx* ctx, const int32_t* d_rows, const int32_t* d_cols, const float* d_vals,
             int64_t count, double* rmse_out)

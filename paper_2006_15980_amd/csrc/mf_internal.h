@@ -173,14 +173,16 @@ hipError_t launch_sgd_lds(int dtype, int k, bool exact, bool short_prefetch, int
 // entries each, both or neither): the stratum of every step and its inverse.  abort_flag: two
 // device ints, [0] raised when a bounded wait expires, [1] the range flag.  query_only: do not launch,
 // return in *max_resident how many workgroups of this shape the device can hold at once.
-// touched / touched_words / slot_table_at: as for launch_sgd_lds.
+// touched / touched_words / slot_table_at: as for launch_sgd_lds.  n_epochs: epochs run by the one
+// launch (more than one only with the strata in natural order); the caller then adds
+// n_epochs * grid_c to `first` for the next launch.
 hipError_t launch_sgd_ring(int dtype, int k, bool exact, bool short_prefetch, int waves, bool query_only, int* max_resident,
                            void* P, void* Qt, const int32_t* U, const int32_t* V, const float* R,
                            const int64_t* entry_begin, const int32_t* entry_len, const int64_t* hot_pos, const LdsBlock* ring_blocks,
                            int grid_r, int grid_c, size_t lds_bytes, float lr, float lambda, int* done,
                            int first, int* abort_flag, long long spin_limit, const int32_t* order,
                            const int32_t* pos, const uint32_t* touched, int touched_words, int slot_table_at,
-                           hipStream_t stream);
+                           int n_epochs, hipStream_t stream);
 // Fill the table of touched columns for a list of blocks made for this call: first_entry = the
 // block's first packed position, n_entries = its number of ratings, col0 / ncols / id as usual
 // (rows of the table of blocks not in the list are left as they are: clear the table first).

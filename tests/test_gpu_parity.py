@@ -814,6 +814,57 @@ def test_packed_strips_with_sixteen_wavefronts_visit_every_rating_once(mfmod, ri
     assert moved > 5e-6 and dp <= 6e-7 and dq <= 1.2e-6, (moved, dp, dq)
 
 
+@pytest.mark.parametrize("storage,k,grid,pack", [("f32", 128, (8, 32), 1), ("f32", 32, (16, 16), 1), ("f32", 64, (5, 23), 1),
+                                                  ("f16", 128, (8, 32), 2), ("f32", 128, (33, 40), 2), ("f16", 64, (7, 7), 1)])
+def test_epochs_in_one_launch_give_the_bits_of_epochs_one_by_one(mfmod, storage, k, grid, pack):
+    """mf_sgd_epochs runs its epochs in one launch of the ring kernel: a block row starts the next
+    epoch while others are still in the one before, held back only by the strips it needs.  In
+    deterministic mode four epochs that way must give the bits of four calls of mf_sgd_epoch (square,
+    rectangular and closed grids, whole and packed strips), and of the kernel that launches every
+    stratum by itself; in Hogwild mode (lr tiny, no regularisation: an epoch is a sum over the
+    ratings to first order) every rating must have been applied four times."""
+    ds = dataset("tiny")
+    take = 7000
+    rows, cols, vals = ds.rows[:take].copy(), ds.cols[:take].copy(), ds.vals[:take].copy()
+    gr, gc = grid
+    outs = []
+    for ring, together in ((1, True), (1, False), (0, True)):
+        model = mfmod.MatrixFactorization(ds.cfg.m, ds.cfg.n, k, storage, seed=3, scale=0.1,
+                                          options={mfmod.MF_OPT_DET_KERNEL: mfmod.MF_KERNEL_LDS, mfmod.MF_OPT_RING: ring,
+                                                   mfmod.MF_OPT_PACK_STRIPS: pack})
+        model.load_blocks(rows, cols, vals, gr, gc, 0)
+        assert model.epoch_plan(mfmod.MF_MODE_DET)["kernel"] == ("sgd_ring_lds" if ring else "sgd_block_lds")
+        model.sgd_epoch(0.01, 0.05, mfmod.MF_MODE_DET)          # the counters do not start at zero
+        if together:
+            model.sgd_epochs(0.01, 0.05, mfmod.MF_MODE_DET, 4)
+        else:
+            for _ in range(4):
+                model.sgd_epoch(0.01, 0.05, mfmod.MF_MODE_DET)
+        model.sgd_epoch(0.01, 0.05, mfmod.MF_MODE_DET)
+        model.sync()
+        outs.append(model.get_factors())
+        model.close()
+    for P, Q in outs[1:]:
+        assert np.array_equal(P, outs[0][0]) and np.array_equal(Q, outs[0][1])
+    if storage == "f32":
+        lr = 1e-5
+        model = mfmod.MatrixFactorization(ds.cfg.m, ds.cfg.n, k, storage, seed=3, scale=0.1,
+                                          options={mfmod.MF_OPT_HOGWILD_KERNEL: mfmod.MF_HOGWILD_LDS, mfmod.MF_OPT_RING: 1})
+        model.load_blocks(rows, cols, vals, gr, gc, 1)
+        assert model.epoch_plan(mfmod.MF_MODE_HOGWILD)["kernel"] == "sgd_ring_lds"
+        P0, Q0 = model.get_factors()
+        model.sgd_epochs(lr, 0.0, mfmod.MF_MODE_HOGWILD, 4)
+        P4, Q4 = model.get_factors()
+        model.close()
+        perm, bp, _, _ = oracle.partition(rows, cols, ds.cfg.m, ds.cfg.n, gr, gc, 1)
+        Po, Qo = P0.astype(np.float64), Q0.astype(np.float64)
+        for _ in range(4):
+            oracle.sgd_epoch_omp(Po, Qo, rows, cols, vals, perm, bp, gr, gc, lr, 0.0)
+        dp, dq = float(np.abs(P4 - Po).max()), float(np.abs(Q4 - Qo).max())
+        print("four Hogwild epochs in one launch: max|dP| %.2e max|dQ| %.2e" % (dp, dq), flush=True)
+        assert dp <= 2.4e-6 and dq <= 4.8e-6, (dp, dq)
+
+
 @pytest.mark.parametrize("storage,k,grid", [("f32", 128, (8, 32)), ("f32", 32, (8, 16)), ("f32", 64, (16, 20)),
                                              ("f16", 128, (8, 32)), ("f16", 64, (8, 13)), ("f32", 256, (8, 63))])
 def test_deterministic_mode_with_packed_strips_gives_the_same_bits(mfmod, storage, k, grid):
