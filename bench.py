@@ -104,6 +104,22 @@ def cpu_baseline(ds, gr, gc, k, split, scale):
             "host_cores": len(os.sched_getaffinity(0))}
 
 
+def epochs_in_one_call(mf, torch, model, cfg, mode, nnz, together=8):
+    """`together` epochs in ONE call of mf_sgd_epochs (one launch where an epoch is one launch;
+    no RMSE between them), by the wall clock."""
+    model.sync()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    model.sgd_epochs(cfg.lr, cfg.lam, mode, together)
+    model.sync()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    bytes_per_update = 12 + 4 * cfg.k * (4 if cfg.storage == "f32" else 2)
+    value = nnz * together / elapsed
+    return {"epochs": together, "value": value, "unit": "updates/s", "ms_per_epoch": elapsed * 1e3 / together,
+            "algorithmic_frac_of_hbm_peak": value * bytes_per_update / 1e9 / HBM_PEAK_GBS}
+
+
 def det_rate(mf, torch, ds, name, steps=3, warmup=1, together=8):
     """Deterministic-mode throughput of a configuration at full size on its grid of DET_GRIDS (side
     figure: epochs alone, by the wall clock)."""
@@ -124,14 +140,9 @@ def det_rate(mf, torch, ds, name, steps=3, warmup=1, together=8):
     model.sync()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    # the same number of epochs in ONE call (mf_sgd_epochs: one launch where an epoch is one launch)
-    t0 = time.perf_counter()
-    model.sgd_epochs(cfg.lr, cfg.lam, mf.MF_MODE_DET, together)
-    model.sync()
-    torch.cuda.synchronize()
-    elapsed_together = time.perf_counter() - t0
-    model.close()
     nnz = ds.rows.size
+    one_call = epochs_in_one_call(mf, torch, model, cfg, mf.MF_MODE_DET, nnz, together)
+    model.close()
     bytes_per_update = 12 + 4 * cfg.k * (4 if cfg.storage == "f32" else 2)
     value = nnz * steps / elapsed
     return {"workload": f"{cfg.name}: m={cfg.m} n={cfg.n} nnz_train={nnz} k={cfg.k} {cfg.storage}", "mode": "det",
@@ -139,8 +150,7 @@ def det_rate(mf, torch, ds, name, steps=3, warmup=1, together=8):
             "ms_per_step": elapsed * 1e3 / steps,
             "algorithmic_frac_of_hbm_peak": value * bytes_per_update / 1e9 / HBM_PEAK_GBS,
             "kernel": plan["kernel"], "waves_per_workgroup": plan["waves"], "launches_per_epoch": plan["launches"],
-            "epochs_in_one_call": together, "value_in_one_call": nnz * together / elapsed_together,
-            "ms_per_epoch_in_one_call": elapsed_together * 1e3 / together}
+            "epochs_in_one_call": one_call}
 
 
 def quick_rate(mf, torch, name, steps=5, warmup=2):
@@ -166,15 +176,17 @@ def quick_rate(mf, torch, name, steps=5, warmup=2):
         rmse = model.rmse(*test)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    model.close()
     nnz = ds.rows.size
+    one_call = epochs_in_one_call(mf, torch, model, cfg, mf.MF_MODE_HOGWILD, nnz)
+    model.close()
     bytes_per_update = 12 + 4 * cfg.k * (4 if cfg.storage == "f32" else 2)
     value = nnz * steps / elapsed
     return [{"workload": f"{cfg.name}: m={cfg.m} n={cfg.n} nnz_train={nnz} k={cfg.k} {cfg.storage}", "mode": "hogwild",
              "grid": grid, "split": split, "steps": steps, "value": value, "unit": "updates/s",
              "ms_per_step": elapsed * 1e3 / steps, "bytes_per_update": bytes_per_update,
              "algorithmic_frac_of_hbm_peak": value * bytes_per_update / 1e9 / HBM_PEAK_GBS,
-             "kernel": plan["kernel"], "waves_per_workgroup": plan["waves"], "held_out_rmse": rmse},
+             "kernel": plan["kernel"], "waves_per_workgroup": plan["waves"], "held_out_rmse": rmse,
+             "epochs_in_one_call": one_call},
             det_rate(mf, torch, ds, name)]
 
 
@@ -384,6 +396,10 @@ def main():
         torch.cuda.synchronize()
         elapsed_events = time.perf_counter() - t0
         kernel_ms, launches = mf.binding.mf_profile_read(model.ctx)
+    one_call = None
+    if args.stratum_seed == 0 and not args.no_per_config:
+        mf.binding.mf_set_option(model.ctx, mf.MF_OPT_PROFILE, 0)
+        one_call = epochs_in_one_call(mf, torch, model, cfg, mode, nnz)
     model.close()
 
     value = nnz * args.steps / elapsed
@@ -431,6 +447,9 @@ def main():
            "algorithmic_gbs": value * bytes_per_update / 1e9,
            "hbm_roofline_frac": value * bytes_per_update / 1e9 / HBM_PEAK_GBS,
            "roofline": roofline}
+    if one_call:
+        # side figure: epochs without the RMSE between them, in one call (never `value`)
+        out["epochs_in_one_call"] = one_call
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(ds, gr, gc, k, args.split, args.init_scale)
     default_run = (args.workload == "xlarge" and args.scale == 1.0 and args.mode == "hogwild" and args.grid == d_grid
