@@ -396,8 +396,11 @@ def main():
         torch.cuda.synchronize()
         elapsed_events = time.perf_counter() - t0
         kernel_ms, launches = mf.binding.mf_profile_read(model.ctx)
+    # the default run adds side figures (the profiles' commands, with --no-cpu-baseline, do not)
+    default_run = (args.workload == "xlarge" and args.scale == 1.0 and args.mode == "hogwild" and args.grid == d_grid
+                   and args.split == d_split and not args.no_cpu_baseline and args.stratum_seed == 0)
     one_call = None
-    if args.stratum_seed == 0 and not args.no_per_config:
+    if default_run and not args.no_per_config:
         mf.binding.mf_set_option(model.ctx, mf.MF_OPT_PROFILE, 0)
         one_call = epochs_in_one_call(mf, torch, model, cfg, mode, nnz)
     model.close()
@@ -452,8 +455,6 @@ def main():
         out["epochs_in_one_call"] = one_call
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(ds, gr, gc, k, args.split, args.init_scale)
-    default_run = (args.workload == "xlarge" and args.scale == 1.0 and args.mode == "hogwild" and args.grid == d_grid
-                   and args.split == d_split and not args.no_cpu_baseline)
     if default_run and not args.no_per_config:
         # side figures: this configuration in deterministic mode, then the other configurations at
         # full size on their grids in both modes
