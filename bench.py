@@ -274,6 +274,8 @@ def main():
     ap.add_argument("--split", type=int, default=None,
                     help="0 equal width, 1 ratings balanced, 2 ratings and width balanced; default: the workload's")
     ap.add_argument("--ring", type=int, default=1, help="1: one launch per epoch (workgroups hand the strips round)")
+    ap.add_argument("--epochs-per-call", type=int, default=1,
+                    help="more than 1: a step is that many epochs in one call of mf_sgd_epochs, then the held-out RMSE")
     ap.add_argument("--stratum-seed", type=int, default=0,
                     help="nonzero: every epoch visits the strata in a seeded random order (mf_stratum_order)")
     ap.add_argument("--pack-strips", type=int, default=1, help="0: the LDS kernels always keep whole strips; 2: packed strips wherever possible")
@@ -354,7 +356,7 @@ def main():
         model.sync()
         t_load = time.perf_counter() - t0
     tr, tc, tv = model.to_device(ds.test_rows, ds.test_cols, ds.test_vals)
-    nnz = ds.rows.size
+    nnz = ds.rows.size * max(1, args.epochs_per_call)     # updates per step
     if args.rmse_bench:
         rmse_kernel_bench(args, mf, model, nnz, k, elt)
         model.close()
@@ -371,8 +373,11 @@ def main():
             order = None
             if args.stratum_seed:
                 order = mf.binding.mf_stratum_order(args.stratum_seed, epochs_run[0], gc)
-            model.sgd_epoch(cfg.lr, cfg.lam, mode, stratum_order=order)
-            epochs_run[0] += 1
+            if args.epochs_per_call > 1:
+                model.sgd_epochs(cfg.lr, cfg.lam, mode, args.epochs_per_call)
+            else:
+                model.sgd_epoch(cfg.lr, cfg.lam, mode, stratum_order=order)
+            epochs_run[0] += args.epochs_per_call
             last = model.rmse(tr, tc, tv)
         return last
 
@@ -398,7 +403,8 @@ def main():
         kernel_ms, launches = mf.binding.mf_profile_read(model.ctx)
     # the default run adds side figures (the profiles' commands, with --no-cpu-baseline, do not)
     default_run = (args.workload == "xlarge" and args.scale == 1.0 and args.mode == "hogwild" and args.grid == d_grid
-                   and args.split == d_split and not args.no_cpu_baseline and args.stratum_seed == 0)
+                   and args.split == d_split and not args.no_cpu_baseline and args.stratum_seed == 0
+                   and args.epochs_per_call == 1)
     one_call = None
     if default_run and not args.no_per_config:
         mf.binding.mf_set_option(model.ctx, mf.MF_OPT_PROFILE, 0)
@@ -418,7 +424,7 @@ def main():
         key = (f"workload={args.workload} scale={args.scale:g} mode={args.mode} grid={args.grid} split={args.split} "
                f"kernel={plan['kernel']} waves={plan['waves']}")
         traffic, source = profiled_traffic(key)
-        if args.lds_chunk != 0 or args.chunk != 0 or not args.affinity or args.pack_strips != 1 or args.stratum_seed != 0:
+        if args.lds_chunk != 0 or args.chunk != 0 or not args.affinity or args.pack_strips != 1 or args.stratum_seed != 0 or args.epochs_per_call != 1:
             traffic, source = None, None
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
@@ -442,7 +448,7 @@ def main():
                       "mode": args.mode, "grid": args.grid, "split": args.split, "init_scale": args.init_scale,
                       "hogwild_kernel": args.hogwild_kernel,
                       "lds_chunk": args.lds_chunk, "lds_waves": args.lds_waves, "ring": args.ring,
-                      "pack_strips": args.pack_strips, "stratum_seed": args.stratum_seed,
+                      "pack_strips": args.pack_strips, "stratum_seed": args.stratum_seed, "epochs_per_call": args.epochs_per_call,
                       "chunk": args.chunk,
                       "xcd_affinity": args.affinity,
                       "lr": cfg.lr, "lambda": cfg.lam},
