@@ -814,6 +814,18 @@ def test_packed_strips_with_sixteen_wavefronts_visit_every_rating_once(mfmod, ri
     assert moved > 5e-6 and dp <= 6e-7 and dq <= 1.2e-6, (moved, dp, dq)
 
 
+def test_epochs_in_one_call_reject_a_count_out_of_range(mfmod):
+    ds = dataset("tiny")
+    model = _make(mfmod, ds, 32, "f32", 8, 8, 1)
+    for count in (0, -3, 4097):
+        with pytest.raises(mfmod.MFError) as e:
+            model.sgd_epochs(0.01, 0.05, mfmod.MF_MODE_DET, count)
+        assert e.value.code == mfmod.binding.MF_EINVAL
+    model.sgd_epochs(0.01, 0.05, mfmod.MF_MODE_DET, 1)
+    model.sync()
+    model.close()
+
+
 @pytest.mark.parametrize("storage,k,grid,pack", [("f32", 128, (8, 32), 1), ("f32", 32, (16, 16), 1), ("f32", 64, (5, 23), 1),
                                                   ("f16", 128, (8, 32), 2), ("f32", 128, (33, 40), 2), ("f16", 64, (7, 7), 1)])
 def test_epochs_in_one_launch_give_the_bits_of_epochs_one_by_one(mfmod, storage, k, grid, pack):
